@@ -1,0 +1,329 @@
+"""Pins for the CPU decoder oracle: closed forms, invariants, library routines, brute force.
+
+Each test is chosen so that a plausible slip in oracle/decoder_oracle.c (dropped term, wrong sign
+or index, transposed operand, wrong pairing) fails at least one of them.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import decoder as D
+from synth import gen as G
+
+RNG = np.random.default_rng(1234)
+
+
+def bf(x):
+    """fp32 array -> bf16 bit patterns (RNE) via torch, an implementation independent of ours."""
+    return torch.from_numpy(np.asarray(x, np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def unbf(b):
+    return torch.from_numpy(np.asarray(b, np.uint16).view(np.int16)).view(torch.bfloat16).float().numpy()
+
+
+@pytest.fixture(scope="module", params=["f32", "f64"])
+def ops(request):
+    return D.Ops(request.param)
+
+
+# ------------------------------------------------------------------ bf16 conversions
+def test_bf16_widen_exhaustive():
+    L = D.lib("f32")
+    allb = np.arange(65536, dtype=np.uint16)
+    ref = unbf(allb)
+    got = np.array([L.orc_bf16_to_f32(int(b)) for b in allb], np.float32)
+    nan = np.isnan(ref)          # signalling NaNs are quieted on the way back through ctypes
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got.view(np.uint32)[~nan], ref.view(np.uint32)[~nan])
+
+
+def test_bf16_narrow_rne_directed_and_random():
+    L = D.lib("f32")
+    vals = [0.0, -0.0, 1.0, 1.00390625, 1.01171875, 1.001953125, 1.005859375,  # incl. ties
+            np.float32(1.0) + np.float32(2 ** -9) + np.float32(2 ** -20), 3.3895314e38,
+            1e-40, -1e-40, float("inf"), -float("inf"), 65504.0, 0.1, -0.3]
+    vals = np.array(vals, np.float32)
+    vals = np.concatenate([vals, RNG.standard_normal(5000).astype(np.float32) * 3,
+                           (RNG.integers(0, 2 ** 32, 5000, dtype=np.uint64).astype(np.uint32)
+                            ).view(np.float32)])
+    vals = vals[~np.isnan(vals)]
+    got = np.array([L.orc_f32_to_bf16(float(v)) for v in vals], np.uint16)
+    assert np.array_equal(got, bf(vals))
+    # ties-to-even spelled out: the bf16 ulp at 1.0 is 2^-7, so 1 + 2^-8 is a tie
+    assert L.orc_f32_to_bf16(1.0 + 2 ** -8) == 0x3F80          # tie -> even (1.0)
+    assert L.orc_f32_to_bf16(1.0 + 3 * 2 ** -8) == 0x3F82      # tie -> even (1 + 2*2^-7)
+    assert L.orc_f32_to_bf16(1.0 + 2 ** -8 + 2 ** -20) == 0x3F81   # just above the tie -> up
+    nan = L.orc_f32_to_bf16(float("nan"))
+    assert (nan & 0x7F80) == 0x7F80 and (nan & 0x7F) != 0
+
+
+# ------------------------------------------------------------------ RMSNorm
+def test_rmsnorm_constant_vector_gives_signed_gain(ops):
+    n, eps = 256, 1e-6
+    g = bf(1 + 0.02 * RNG.standard_normal(n))
+    for c in (3.0, -0.5):
+        y = ops.rmsnorm(np.full(n, c), g, eps)
+        expect = np.sign(c) * unbf(g)
+        assert np.allclose(y, expect, rtol=eps / (2 * c * c) + 1e-6, atol=0)
+
+
+def test_rmsnorm_scale_invariance_and_torch(ops):
+    n = 688
+    x = RNG.standard_normal(n)
+    g = bf(1 + 0.02 * RNG.standard_normal(n))
+    y1, y2 = ops.rmsnorm(x, g, 1e-12), ops.rmsnorm(7.0 * x, g, 1e-12)
+    assert np.allclose(y1, y2, rtol=1e-5)
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(x), (n,), torch.from_numpy(unbf(g)).double(), 1e-6)
+    assert np.allclose(ops.rmsnorm(x, g, 1e-6), ref.numpy(), rtol=2e-5, atol=1e-6)
+
+
+def test_rmsnorm_eps_matters(ops):
+    # with x tiny, eps dominates: y = x / sqrt(eps) * g
+    x = np.full(16, 1e-6)
+    y = ops.rmsnorm(x, bf(np.ones(16)), 1e-2)
+    assert np.allclose(y, 1e-6 / math.sqrt(1e-12 + 1e-2), rtol=1e-5)
+
+
+# ------------------------------------------------------------------ linear
+def test_linear_identity_onehot_and_doubling(ops):
+    n = 64
+    x = RNG.standard_normal(n).astype(np.float32)
+    assert np.array_equal(ops.linear(bf(np.eye(n)), x), x.astype(ops.dt))
+    perm = RNG.permutation(n)
+    P = np.zeros((n, n), np.float32)
+    P[np.arange(n), perm] = 1.0                       # y_r = x[perm[r]]  (row r picks column perm[r])
+    assert np.array_equal(ops.linear(bf(P), x), x[perm].astype(ops.dt))
+    W = bf(0.02 * RNG.standard_normal((24, n)))
+    W2 = bf(2 * unbf(W))
+    assert np.array_equal(ops.linear(W2, x), 2 * ops.linear(W, x))
+
+
+def test_linear_non_square_vs_float64(ops):
+    W = bf(0.02 * RNG.standard_normal((37, 688)))
+    x = RNG.standard_normal(688).astype(np.float32)
+    ref = unbf(W).astype(np.float64) @ x.astype(np.float64)
+    tol = 1e-5 if ops.dt == np.float32 else 1e-12
+    assert np.allclose(ops.linear(W, x), ref, rtol=tol, atol=tol)
+
+
+# ------------------------------------------------------------------ RoPE
+def test_rope_position_zero_is_identity(ops):
+    u = RNG.standard_normal(128)
+    assert np.array_equal(ops.rope(u, 0, 1e6), u.astype(ops.dt))
+
+
+def test_rope_norms_relative_position_and_pairing(ops):
+    d, theta = 64, 1e4
+    q, k = RNG.standard_normal(d), RNG.standard_normal(d)
+    rq = ops.rope(q, 17, theta)
+    h = d // 2
+    # each (i, i+d/2) pair keeps its norm (half-split pairing; an interleaved pairing fails this)
+    assert np.allclose(rq[:h] ** 2 + rq[h:] ** 2, q[:h] ** 2 + q[h:] ** 2, rtol=1e-4)
+    a = np.dot(ops.rope(q, 9, theta), ops.rope(k, 4, theta))
+    b = np.dot(ops.rope(q, 109, theta), ops.rope(k, 104, theta))
+    assert abs(a - b) < 1e-3
+    # closed form for one pair: pair i rotates by pos * theta^(-2i/d), counter-clockwise
+    i, pos = 3, 5
+    ang = pos * theta ** (-2 * i / d)
+    u = np.zeros(d); u[i] = 1.0
+    r = ops.rope(u, pos, theta)
+    assert np.allclose([r[i], r[i + h]], [math.cos(ang), math.sin(ang)], atol=1e-6)
+    # theta -> infinity: only pair 0 (frequency 1) rotates
+    r = ops.rope(q, 3, 1e300)
+    assert np.allclose(r[1:h], q[1:h]) and np.allclose(r[h + 1:], q[h + 1:])
+    assert not np.allclose(r[0], q[0])
+
+
+# ------------------------------------------------------------------ attention
+def test_attention_single_position_returns_v(ops):
+    d = 64
+    K, V = bf(RNG.standard_normal((1, d))), bf(RNG.standard_normal((1, d)))
+    o = ops.attention_head(RNG.standard_normal(d), K, V, 1)
+    assert np.array_equal(o, unbf(V)[0].astype(ops.dt))
+
+
+def test_attention_zero_query_is_mean_and_shift_invariance(ops):
+    d, T = 64, 37
+    K, V = bf(RNG.standard_normal((T, d))), bf(RNG.standard_normal((T, d)))
+    o = ops.attention_head(np.zeros(d), K, V, T)
+    assert np.allclose(o, unbf(V).mean(0), rtol=1e-5, atol=1e-6)
+    # only rows < n_pos are read
+    o2 = ops.attention_head(np.zeros(d), K, V, 10)
+    assert np.allclose(o2, unbf(V)[:10].mean(0), rtol=1e-5, atol=1e-6)
+    # adding a constant to every score changes nothing: append a constant key coordinate
+    q = RNG.standard_normal(d)
+    o_a = ops.attention_head(q, K, V, T)
+    q2 = np.concatenate([q, [5.0]]);
+    K2 = bf(np.concatenate([unbf(K), np.ones((T, 1))], 1))
+    V2 = bf(np.concatenate([unbf(V), np.zeros((T, 1))], 1))
+    # (d+1 changes the 1/sqrt(d) scale, so rescale q to compensate)
+    o_b = ops.attention_head(q2 * math.sqrt((d + 1) / d), K2, V2, T)[:d]
+    assert np.allclose(o_a, o_b, rtol=2e-4, atol=2e-5)
+
+
+def test_attention_vs_torch_sdpa(ops):
+    d, T = 128, 200
+    q = RNG.standard_normal(d).astype(np.float32)
+    K, V = bf(RNG.standard_normal((T, d))), bf(RNG.standard_normal((T, d)))
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q).double()[None, None, None], torch.from_numpy(unbf(K)).double()[None, None],
+        torch.from_numpy(unbf(V)).double()[None, None])[0, 0, 0].numpy()
+    tol = 2e-5 if ops.dt == np.float32 else 1e-10
+    assert np.allclose(ops.attention_head(q, K, V, T), ref, rtol=tol, atol=tol)
+
+
+# ------------------------------------------------------------------ SwiGLU, argmax, router
+def test_swiglu_cases(ops):
+    F = 8
+    up = RNG.standard_normal(F)
+    assert np.array_equal(ops.swiglu(np.concatenate([np.zeros(F), up])), np.zeros(F, ops.dt))
+    big = np.full(F, 30.0)
+    assert np.allclose(ops.swiglu(np.concatenate([big, up])), 30.0 * up, rtol=1e-6)
+    g = RNG.standard_normal(F)
+    ref = torch.nn.functional.silu(torch.from_numpy(g)) .numpy() * up
+    assert np.allclose(ops.swiglu(np.concatenate([g, up])), ref, rtol=1e-5, atol=1e-7)
+    # layout: first half is the gate (swapping halves changes the result)
+    assert not np.allclose(ops.swiglu(np.concatenate([up, g])), ref)
+
+
+def test_argmax_lowest_index_on_ties(ops):
+    assert ops.argmax(np.array([1.0, 5.0, 5.0, 2.0])) == 1
+    assert ops.argmax(np.array([-1.0, -1.0])) == 0
+
+
+def test_router_topk_vs_sort_and_sum(ops):
+    for E, k in ((8, 2), (16, 4), (128, 8)):
+        lg = RNG.standard_normal(E)
+        sel, w = ops.router_topk(lg, k)
+        order = np.argsort(-lg, kind="stable")[:k]
+        assert sorted(sel.tolist()) == sorted(order.tolist())
+        assert list(sel) == sorted(sel)
+        p = np.exp(lg - lg.max()); p /= p.sum()
+        assert np.allclose(w, p[sel] / p[sel].sum(), rtol=1e-5)
+        assert abs(w.sum() - 1) < 1e-5
+        # permutation equivariance
+        perm = RNG.permutation(E)
+        sel2, w2 = ops.router_topk(lg[perm], k)
+        assert sorted(perm[sel2].tolist()) == sorted(sel.tolist())
+    sel, _ = ops.router_topk(np.array([1.0, 2.0, 2.0, 2.0, 0.0]), 2)
+    assert list(sel) == [1, 2]          # ties -> lower index
+
+
+# ------------------------------------------------------------------ whole layer / model
+class DictProvider:
+    def __init__(self, s, embed, layers, final_norm, lm_head, kv):
+        self.s, self.E, self.layers, self.fn, self.lm, self.kv = s, embed, layers, final_norm, lm_head, kv
+
+    def embed_row(self, t): return self.E[t]
+    def layer(self, l): return self.layers[l]
+    def final_norm(self): return self.fn
+    def lm_head(self): return self.lm
+    def kv_layer(self, l): return self.kv[l]
+
+
+def synth_provider_as_dict(s, seed=0, zero=()):
+    sw = G.SynthWeights(s, seed)
+    E = G.fill_host(seed, G.TID_EMBED, 0, s.vocab * s.hidden, "w").reshape(s.vocab, s.hidden)
+    layers = []
+    for l in range(s.n_layers):
+        w = dict(sw.layer(l))
+        for z in zero:
+            w[z] = np.zeros_like(w[z])
+        layers.append(w)
+    kv = [sw.kv_layer(l) for l in range(s.n_layers)]
+    return DictProvider(s, E, layers, sw.final_norm(), sw.lm_head(), kv)
+
+
+def test_layer_is_identity_when_wo_and_wd_zero():
+    s = G.CONFIGS["C1"]
+    prov = synth_provider_as_dict(s, zero=(G.L_WO, G.L_WD))
+    o = D.DecoderOracle(s, prov, "f32")
+    tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
+    hid = o.step(tok, pos, return_hidden=True)
+    assert np.array_equal(hid[0], unbf(prov.E[tok[0]]))
+    # and then logits have the closed form  Wlm . RMSNorm(E[token])
+    lg = o.step(tok, pos)
+    x = unbf(prov.E[tok[0]]).astype(np.float64)
+    xn = x / np.sqrt((x * x).mean() + s.rms_eps) * unbf(prov.fn).astype(np.float64)
+    assert np.allclose(lg[0], unbf(prov.lm).astype(np.float64) @ xn, rtol=1e-4, atol=1e-5)
+
+
+def test_f32_oracle_close_to_f64_oracle():
+    s = G.CONFIGS["C1"]
+    tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
+    l32 = D.DecoderOracle(s, G.SynthWeights(s, 0), "f32").step(tok, pos)
+    l64 = D.DecoderOracle(s, G.SynthWeights(s, 0), "f64").step(tok, pos)
+    assert np.abs(l32 - l64).max() / np.abs(l64).max() < 1e-5
+    assert l32.argmax() == l64.argmax()
+
+
+def test_kv_append_rounds_and_next_step_reads_rounded_row():
+    s = G.CONFIGS["C1"]
+    o = D.DecoderOracle(s, G.SynthWeights(s, 0), "f32")
+    tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
+    k_before = o._kv(0)[0].copy()
+    o.step(tok, pos)
+    k_after = o._kv(0)[0]
+    p = int(pos[0])
+    changed = np.argwhere((k_before != k_after).any(-1))
+    assert set(map(tuple, changed)) == {(0, g, p) for g in range(s.n_kv_heads)}
+
+
+def test_whole_model_vs_transformers_llama():
+    """Library pin: a randomly initialised Llama-architecture model from the `transformers`
+    package, loaded with the same seeded tensors, fp32 on CPU, one token with a 128-row past."""
+    from transformers import LlamaConfig, LlamaForCausalLM
+    from transformers.cache_utils import DynamicCache
+    s = G.CONFIGS["C1"]
+    seed = 0
+    prov = synth_provider_as_dict(s, seed)
+    cfg = LlamaConfig(vocab_size=s.vocab, hidden_size=s.hidden, intermediate_size=s.ffn,
+                      num_hidden_layers=s.n_layers, num_attention_heads=s.n_q_heads,
+                      num_key_value_heads=s.n_kv_heads, head_dim=s.head_dim, rms_norm_eps=s.rms_eps,
+                      rope_theta=s.rope_theta, max_position_embeddings=4096,
+                      attention_bias=False, mlp_bias=False, tie_word_embeddings=False,
+                      attn_implementation="eager")
+    try:
+        cfg.rope_parameters = {"rope_type": "default", "rope_theta": s.rope_theta}
+    except Exception:
+        pass
+    m = LlamaForCausalLM(cfg).float().eval()
+    t = lambda a: torch.from_numpy(unbf(a))
+    nq, nkv, d, F = s.n_q_heads, s.n_kv_heads, s.head_dim, s.ffn
+    sd = {"model.embed_tokens.weight": t(prov.E), "model.norm.weight": t(prov.fn),
+          "lm_head.weight": t(prov.lm)}
+    for l, w in enumerate(prov.layers):
+        p = f"model.layers.{l}."
+        qkv = t(w[G.L_WQKV])
+        sd[p + "self_attn.q_proj.weight"] = qkv[:nq * d]
+        sd[p + "self_attn.k_proj.weight"] = qkv[nq * d:(nq + nkv) * d]
+        sd[p + "self_attn.v_proj.weight"] = qkv[(nq + nkv) * d:]
+        sd[p + "self_attn.o_proj.weight"] = t(w[G.L_WO])
+        gu = t(w[G.L_WGU])
+        sd[p + "mlp.gate_proj.weight"] = gu[:F]
+        sd[p + "mlp.up_proj.weight"] = gu[F:]
+        sd[p + "mlp.down_proj.weight"] = t(w[G.L_WD])
+        sd[p + "input_layernorm.weight"] = t(w[G.L_ATTN_NORM]).reshape(-1)
+        sd[p + "post_attention_layernorm.weight"] = t(w[G.L_MLP_NORM]).reshape(-1)
+    missing, unexpected = m.load_state_dict(sd, strict=False)
+    assert not [k for k in missing if "rotary" not in k] and not unexpected
+    tok, pos = G.tokens(seed, s), G.kv_lengths(seed, s)
+    T = int(pos[0])
+    cache = DynamicCache(config=cfg)
+    for l in range(s.n_layers):
+        K, V = prov.kv[l]
+        cache.update(t(K[:, :, :T]), t(V[:, :, :T]), l)
+    with torch.no_grad():
+        out = m(input_ids=torch.tensor([[int(tok[0])]]), past_key_values=cache,
+                position_ids=torch.tensor([[T]]), use_cache=True)
+    ref = out.logits[0, -1].numpy()
+    o = D.DecoderOracle(s, prov, "f32")
+    lg = o.step(tok, pos)[0]
+    # the library keeps the new K/V row in fp32 while the method rounds it to bf16 in the cache;
+    # that single row's rounding is the only modelled difference -> loose but meaningful bound
+    err = np.abs(lg - ref).max() / np.abs(ref).max()
+    assert err < 5e-3, err
+    assert lg.argmax() == ref.argmax()
