@@ -1,0 +1,278 @@
+"""Pins for the task-graph oracle (oracle/tgraph.py): the worked example of Fig. 4 as far as the
+paper's text fixes it, Defs. 4.1/4.2 as properties, the normalization post-condition, the
+guarantees stated in Algorithm 1's caption, and the runtime rules of Sections 3 and 5."""
+import random
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+from oracle import tgraph as TG
+from synth import gen as G
+
+
+# ------------------------------------------------------------------ helpers
+def direct_producers(events):
+    p = {}
+    for e in events:
+        for t in e.outs:
+            p.setdefault(t, set()).update(e.ins)
+    return p
+
+
+def closure(prod, through=lambda t: False):
+    """Transitive producer sets; tasks for which `through` holds (dummies) are looked through
+    and not reported."""
+    memo = {}
+
+    def go(t):
+        if t in memo:
+            return memo[t]
+        memo[t] = set()
+        acc = set()
+        for p in prod.get(t, ()):
+            acc |= go(p)
+            if not through(p):
+                acc.add(p)
+        memo[t] = acc
+        return acc
+    return {t: go(t) for t in list(prod)}
+
+
+def real_direct(prod_norm, t, is_dummy):
+    """Direct REAL producers of t in a normalized graph: walk back through dummy tasks."""
+    out, stack = set(), list(prod_norm.get(t, ()))
+    while stack:
+        p = stack.pop()
+        if is_dummy(p):
+            stack += list(prod_norm.get(p, ()))
+        else:
+            out.add(p)
+    return out
+
+
+is_dummy = lambda t: isinstance(t, tuple) and t[0] == "D"
+
+
+# ------------------------------------------------------------------ Fig. 4 worked example
+def fig4_pairs():
+    """Q, K, V -> attention A (2 tasks) -> output projection O (4 tasks) and RMSNorm R, which
+    also needs an independent input X, so O and R can run in parallel after A."""
+    pairs = []
+    for a in ("A1", "A2"):
+        pairs += [("Q", a), ("K", a), ("V", a)]
+        pairs += [(a, o) for o in ("O1", "O2", "O3", "O4")]
+        pairs += [(a, "R")]
+    pairs += [("X", "R")]
+    tasks = ["Q", "K", "V", "X", "A1", "A2", "O1", "O2", "O3", "O4", "R"]
+    return tasks, pairs
+
+
+def test_fig4_fusions_and_two_dummies():
+    tasks, pairs = fig4_pairs()
+    ev = TG.pair_events(pairs)
+    assert len(ev) == 17
+    s = TG.successor_set_fusion(ev)
+    # the two pair events (A1,O1), (A2,O1) became one event that O1 waits on
+    o1 = [e for e in s if e.outs == frozenset(["O1"])]
+    assert len(o1) == 1 and o1[0].ins == frozenset(["A1", "A2"])
+    assert len(s) == 7                      # one per consumer task: A1 A2 O1..O4 R
+    p = TG.predecessor_set_fusion(s)
+    # the four events that all depend on {A1, A2} became one, which launches four tasks
+    eo = [e for e in p if e.ins == frozenset(["A1", "A2"])]
+    assert len(eo) == 1 and eo[0].outs == frozenset(["O1", "O2", "O3", "O4"])
+    assert len(p) == 3                      # {QKV}->{A1,A2}, {A1,A2}->{O*}, {A1,A2,X}->{R}
+    # A1 and A2 each trigger two events (O's and R's) -> normalization adds exactly D1, D2
+    n_ev, n_tasks, dummies = TG.normalize(p, tasks)
+    assert len(dummies) == 2
+    assert len(n_ev) == 4
+    trig = {}
+    dep = {}
+    for e in n_ev:
+        for t in e.ins:
+            assert t not in trig
+            trig[t] = e
+        for t in e.outs:
+            assert t not in dep
+            dep[t] = e
+    assert trig["A1"] is trig["A2"] and trig["A1"].outs == frozenset(dummies)
+    # dependencies seen through the dummies are unchanged
+    before = direct_producers(p)
+    after = direct_producers(n_ev)
+    for t in tasks:
+        assert real_direct(after, t, is_dummy) == before.get(t, set())
+    order, ranges, ev_order = TG.linearize(n_ev, n_tasks)
+    assert sorted(map(str, order)) == sorted(map(str, n_tasks))
+    pos = {t: i for i, t in enumerate(order)}
+    # the event launching the four O tasks stores them as one contiguous range
+    o_pos = sorted(pos[o] for o in ("O1", "O2", "O3", "O4"))
+    assert o_pos == list(range(o_pos[0], o_pos[0] + 4))
+
+
+def test_fanin_rewrite_on_handmade_graph():
+    # T0 depends on two events that cannot be fused (different InTasks, and e1 has another consumer)
+    ev = [TG.Event(frozenset(["a"]), frozenset(["T0", "u"])), TG.Event(frozenset(["b"]), frozenset(["T0"]))]
+    n_ev, n_tasks, dummies = TG.normalize(ev, ["a", "b", "u", "T0"])
+    assert len(dummies) == 2
+    dep = [e for e in n_ev if "T0" in e.outs]
+    assert len(dep) == 1 and dep[0].ins == frozenset(dummies)
+    after = direct_producers(n_ev)
+    assert real_direct(after, "T0", is_dummy) == {"a", "b"}
+    assert real_direct(after, "u", is_dummy) == {"a"}
+
+
+# ------------------------------------------------------------------ properties on random DAGs
+@st.composite
+def random_dag_pairs(draw):
+    n = draw(st.integers(2, 14))
+    pairs = set()
+    for b in range(1, n):
+        for a in draw(st.lists(st.integers(0, b - 1), max_size=4)):
+            pairs.add((a, b))
+    return n, sorted(pairs)
+
+
+@settings(max_examples=150, deadline=None)
+@given(random_dag_pairs())
+def test_fusion_normalization_linearization_properties(g):
+    n, pairs = g
+    tasks = list(range(n))
+    ev0 = TG.pair_events(pairs)
+    base = direct_producers(ev0)
+    s = TG.successor_set_fusion(ev0)
+    assert direct_producers(s) == base                       # Def 4.1 keeps every dependency
+    assert len({e.outs for e in s}) == len(s)
+    p = TG.predecessor_set_fusion(s)
+    assert direct_producers(p) == base                       # Def 4.2 too
+    assert len({e.ins for e in p}) == len(p) and len({e.outs for e in p}) == len(p)
+    # fixed point: a second round changes nothing
+    again = TG.predecessor_set_fusion(TG.successor_set_fusion(p))
+    assert {(e.ins, e.outs) for e in again} == {(e.ins, e.outs) for e in p}
+    # after the two passes every task waits on at most one event
+    for t in tasks:
+        assert sum(t in e.outs for e in p) <= 1
+    n_ev, n_tasks, dummies = TG.normalize(p, tasks)
+    for t in n_tasks:
+        assert sum(t in e.ins for e in n_ev) <= 1 and sum(t in e.outs for e in n_ev) <= 1
+    forks = {t for t in tasks if sum(t in e.ins for e in p) > 1}
+    assert (len(dummies) > 0) == (len(forks) > 0)             # dummies only where a fork exists
+    after = direct_producers(n_ev)
+    for t in tasks:
+        assert real_direct(after, t, is_dummy) == base.get(t, set())
+    order, ranges, ev_order = TG.linearize(n_ev, n_tasks)
+    assert len(order) == len(n_tasks) and len(set(order)) == len(order)   # each task once
+    assert len(set(ev_order)) == len(ev_order) == len(n_ev) + 1           # each event once
+    pos = {t: i for i, t in enumerate(order)}
+    for ei, e in enumerate(n_ev):                                          # contiguity
+        ps = sorted(pos[t] for t in e.outs)
+        assert ps == list(range(ps[0], ps[0] + len(ps)))
+        assert ranges[ei] == (ps[0], ps[-1])
+    for a, b in pairs:                                                     # topological
+        assert pos[a] < pos[b]
+
+
+# ------------------------------------------------------------------ dependency brute force
+def test_split_even_rule():
+    assert TG.split_even(10, 4) == [0, 3, 6, 8, 10]
+    assert TG.split_even(3, 5) == [0, 1, 2, 3, 3, 3]
+
+
+def tiny_degrees(ops, lin=4, rope=None, merge=2, pw=1):
+    deg = []
+    for op in ops:
+        if op.kind in (TG.K_LINEAR, TG.K_GATEUP):
+            deg.append((1, lin))
+        elif op.kind == TG.K_ROPE:
+            deg.append((op.rows, rope or op.cols // op.unit))
+        elif op.kind == TG.K_ATTN_PARTIAL:
+            deg.append((op.rows, op.cols // op.unit))
+        elif op.kind == TG.K_ATTN_MERGE:
+            deg.append((op.rows, merge))
+        else:
+            deg.append((op.rows, pw))
+    return deg
+
+
+def test_producer_sets_spot_checks_unfused():
+    s = G.small_variant("C1", n_layers=1, batch=2)
+    ops = TG.build_ops(s, 0, attn_chunks=3)
+    names = [o.name for o in ops]
+    assert names == ["embed", "L0.attn_norm", "L0.qkv", "L0.rope", "L0.attn_partial",
+                     "L0.attn_merge", "L0.o_proj", "L0.resid1", "L0.mlp_norm", "L0.gate_up",
+                     "L0.swiglu", "L0.down", "L0.resid2", "final_norm", "lm_head"]
+    deg = tiny_degrees(ops)
+    ps = TG.producer_sets(ops, deg)
+    ix = {n: i for i, n in enumerate(names)}
+    # norm of batch row 1 needs only embed's row-1 task
+    assert ps[ix["L0.attn_norm"]][1] == [(ix["embed"], 1)]
+    # every linear tile needs the norm tasks of all batch rows
+    assert all(p == [(ix["L0.attn_norm"], 0), (ix["L0.attn_norm"], 1)] for p in ps[ix["L0.qkv"]])
+    # rope of head slot h (512 qkv rows in 4 tiles of 128 = 2 heads each) needs qkv tile h//2
+    nslots = s.n_q_heads + 2 * s.n_kv_heads
+    for b in range(2):
+        for h in range(nslots):
+            assert ps[ix["L0.rope"]][b * nslots + h] == [(ix["L0.qkv"], h // 2)]
+    # attention partial (b, g, c): q heads of group g; the last chunk also this step's k and v
+    C, grp = 3, s.n_q_heads // s.n_kv_heads
+    for b in range(2):
+        for g in range(s.n_kv_heads):
+            for c in range(C):
+                want = {(ix["L0.rope"], b * nslots + h) for h in range(g * grp, (g + 1) * grp)}
+                if c == C - 1:
+                    want |= {(ix["L0.rope"], b * nslots + s.n_q_heads + g),
+                             (ix["L0.rope"], b * nslots + s.n_q_heads + s.n_kv_heads + g)}
+                assert set(ps[ix["L0.attn_partial"]][(b * s.n_kv_heads + g) * C + c]) == want
+    # merge tile = 2 heads = one group -> all chunks of that (b, group)
+    for b in range(2):
+        for g in range(s.n_kv_heads):
+            want = {(ix["L0.attn_partial"], (b * s.n_kv_heads + g) * C + c) for c in range(C)}
+            assert set(ps[ix["L0.attn_merge"]][b * 2 + g]) == want
+    # residual add (one tile per batch row) needs x0's row task and every o_proj tile
+    assert set(ps[ix["L0.resid1"]][0]) == {(ix["embed"], 0)} | {(ix["L0.o_proj"], t) for t in range(4)}
+    # swiglu reads gate and up halves: with 4 gate_up tiles over 2F rows, one h tile over all F
+    assert set(ps[ix["L0.swiglu"]][0]) == {(ix["L0.gate_up"], t) for t in range(4)}
+
+
+def test_producer_sets_fused_residual_reads_only_its_tile():
+    s = G.small_variant("C1", n_layers=2)
+    fusion = TG.F_NORM | TG.F_RESID | TG.F_SWIGLU
+    ops = TG.build_ops(s, fusion, attn_chunks=2)
+    names = [o.name for o in ops]
+    assert names[:6] == ["embed", "L0.qkv", "L0.rope", "L0.attn_partial", "L0.attn_merge", "L0.o_proj"]
+    ps = TG.producer_sets(ops, tiny_degrees(ops))
+    ix = {n: i for i, n in enumerate(names)}
+    # layer-1 o_proj tile j: all merge tasks + layer-0 down tile j (its residual slice)
+    for j in range(4):
+        want = {(ix["L1.attn_merge"], t) for t in range(2)} | {(ix["L0.down"], j)}
+        assert set(ps[ix["L1.o_proj"]][j]) == want
+
+
+# ------------------------------------------------------------------ runtime simulator
+def small_linear_graph():
+    """a0,a1 -> e1 -> b0,b1,b2 -> e2 -> c0 ; start event 0 launches a*."""
+    tasks = [dict(dep=0, trig=1, jit=False), dict(dep=0, trig=1, jit=False),
+             dict(dep=1, trig=2, jit=True), dict(dep=1, trig=2, jit=True), dict(dep=1, trig=2, jit=True),
+             dict(dep=2, trig=3, jit=False)]
+    events = [dict(required=0, first=0, last=1), dict(required=2, first=2, last=4),
+              dict(required=3, first=5, last=5), dict(required=1, first=6, last=5)]
+    producers = [set(), set(), {0, 1}, {0, 1}, {0, 1}, {2, 3, 4}]
+    return tasks, events, producers
+
+
+def test_simulator_random_schedules_and_hops():
+    tasks, events, producers = small_linear_graph()
+    for seed in range(1000):
+        rng = random.Random(seed)
+        log, hops = TG.simulate(tasks, events, [[0, 5], [1]], 2, rng, producers)
+        assert len(log) == len(tasks)
+        assert all(hops[t] == (2 if tasks[t]["jit"] else 1) for t in range(len(tasks)))
+
+
+def test_simulator_detects_dropped_trigger_and_bad_aot_order():
+    tasks, events, producers = small_linear_graph()
+    with pytest.raises(TG.Deadlock):
+        TG.simulate(tasks, events, [[0, 5], [1]], 2, random.Random(0), producers, drop_trigger=1)
+    # AOT queue not a subsequence of the linearized order: worker 0 waits on c0 first while it
+    # also owns a0 -> nothing can ever run
+    with pytest.raises(TG.Deadlock):
+        TG.simulate(tasks, events, [[5, 0], [1]], 2, random.Random(0), producers)
