@@ -1,0 +1,233 @@
+/*
+ * mpk.h -- C ABI of the MI355X task-graph mega-kernel decoder.
+ *
+ * One LLM decode step (embedding; per layer RMSNorm, QKV projection, RoPE, decode attention over
+ * the KV cache, O projection, residual, RMSNorm, SwiGLU MLP, residual; final RMSNorm; LM head) is
+ * compiled on the host into a CU-level task graph ("tGraph", paper Section 3) and executed by one
+ * persistent HIP kernel (paper Section 5).
+ *
+ * Conventions used by every entry point
+ *   - "host" / "device" on a pointer says where the memory must live.  Device pointers are plain
+ *     HIP device allocations of the GPU that was current when mpk_compile was called.
+ *   - The library BORROWS every pointer handed to mpk_compile for the lifetime of the graph and
+ *     never frees it.  The library OWNS the graph object and everything it allocates (task and
+ *     event tables, queues, event counters, fp32 activation buffers); mpk_graph_destroy frees it.
+ *   - No function throws or aborts.  Failures return a status code; mpk_last_error() gives a
+ *     thread-local message that stays valid until the next call on the same thread.
+ *   - `stream` arguments are a hipStream_t passed as void* (NULL = the default stream).
+ */
+#ifndef MPK_H
+#define MPK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MPK_OK = 0,
+  MPK_ERR_INVALID_ARG = 1, /* null pointer, zero size, bad struct_size, misaligned pointer    */
+  MPK_ERR_UNSUPPORTED = 2, /* a shape the task bodies cannot tile (see mpk_compile)           */
+  MPK_ERR_OOM = 3,         /* host or device allocation failed                                */
+  MPK_ERR_RESIDENCY = 4,   /* the persistent kernel's workgroups cannot all be co-resident    */
+  MPK_ERR_HIP = 5,         /* a HIP call failed; message holds the HIP error string           */
+  MPK_ERR_TIMEOUT = 6,     /* the in-kernel watchdog fired (an event never activated)         */
+  MPK_ERR_INTERNAL = 7,    /* compiler invariant violated                                     */
+  MPK_ERR_DEVICE = 8       /* the kernel reported an error (e.g. position >= max_seq)         */
+} mpk_status;
+
+/* ----------------------------------------------------------------------------------------------
+ * Model description.  Sizes are element counts.  All weights are bf16, row-major [out][in];
+ * the fused QKV matrix stacks the query rows, then the key rows, then the value rows; the fused
+ * gate/up matrix stacks the gate rows [0, ffn) then the up rows [ffn, 2 ffn).  Activations are
+ * fp32 inside the library.  The paper fixes none of these layouts (it names the operators only,
+ * Section 4 Fig. 4 and Section 6.5); they are this library's contract.
+ * -------------------------------------------------------------------------------------------- */
+typedef struct mpk_model_config {
+  uint32_t struct_size; /* = sizeof(mpk_model_config) */
+  uint32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  float rms_eps, rope_theta;
+  uint32_t batch;   /* the graph is specialised for this batch size (Section 6.1, "supporting
+                       runtime dynamism": one tGraph per batch size)                              */
+  uint32_t max_seq; /* KV-cache capacity per sequence, in positions                              */
+  uint32_t n_experts, top_k, expert_ffn; /* 0 = dense MLP                                        */
+  uint32_t flags;                        /* reserved, must be 0                                  */
+} mpk_model_config;
+
+typedef struct mpk_layer_weights {
+  const void *attn_norm; /* device bf16 [hidden]                                   */
+  const void *wqkv;      /* device bf16 [(n_q + 2 n_kv) head_dim][hidden]          */
+  const void *wo;        /* device bf16 [hidden][n_q head_dim]                     */
+  const void *mlp_norm;  /* device bf16 [hidden]                                   */
+  const void *wgu;       /* device bf16 [2 ffn][hidden]           (dense)          */
+  const void *wd;        /* device bf16 [hidden][ffn]             (dense)          */
+  const void *router;    /* device bf16 [n_experts][hidden]       (MoE)            */
+  const void *expert_wgu; /* device bf16 [n_experts][2 expert_ffn][hidden] (MoE)   */
+  const void *expert_wd;  /* device bf16 [n_experts][hidden][expert_ffn]   (MoE)   */
+} mpk_layer_weights;
+
+typedef struct mpk_weight_ptrs {
+  const void *embed;      /* device bf16 [vocab][hidden]                            */
+  const void *final_norm; /* device bf16 [hidden]                                   */
+  const void *lm_head;    /* device bf16 [vocab][hidden] (not tied to `embed`)      */
+  const mpk_layer_weights *layers; /* HOST array [n_layers] of device pointers      */
+} mpk_weight_ptrs;
+
+/* KV cache: bf16, layout [n_layers][batch][n_kv_heads][max_seq][head_dim], one allocation each.
+ * A decode step WRITES row positions[b] of every (layer, b, kv head) and READS rows
+ * 0..positions[b] (the freshly written row included, as rounded to bf16). */
+typedef struct mpk_kv_ptrs {
+  void *k; /* device */
+  void *v; /* device */
+} mpk_kv_ptrs;
+
+/* Operator fusions applied when the operator list is built (before decomposition). */
+#define MPK_FUSE_NORM 1u   /* RMSNorm folded into the linear operator that consumes it          */
+#define MPK_FUSE_RESID 2u  /* residual add folded into the producing linear operator's epilogue */
+#define MPK_FUSE_SWIGLU 4u /* gate/up projection emits silu(gate)*up directly                   */
+#define MPK_FUSE_MERGE 8u  /* split-KV merge folded into the O projection's input stage         */
+#define MPK_FUSE_ROPE 16u  /* RoPE + KV append folded into the attention tasks                  */
+
+#define MPK_LAUNCH_MEGA 0u   /* one persistent kernel per decode step (Section 5)               */
+#define MPK_LAUNCH_PER_OP 1u /* same task bodies, one kernel launch per operator (baseline)     */
+
+typedef struct mpk_compile_options {
+  uint32_t struct_size;     /* = sizeof(mpk_compile_options)                                    */
+  uint32_t n_workers;       /* worker workgroups, one per CU (Section 5); 0 = all CUs minus the
+                               scheduler CUs (host_only: 256 - n_sched_wgs)                     */
+  uint32_t n_sched_wgs;     /* scheduler workgroups, 4 scheduler wavefronts each (Section 5,
+                               Table 2 uses 4 SMs x 4 warps); 0 = no schedulers: every operator
+                               is launched ahead of time                                        */
+  uint32_t fusion;          /* MPK_FUSE_* bits                                                  */
+  uint32_t transitive_reduction; /* 1 = drop producer->consumer pairs implied by other pairs
+                               before event fusion (not in the paper; removes fork/join dummies
+                               caused by residual connections)                                  */
+  uint32_t attn_chunks;     /* KV splits per (sequence, KV head); 0 = auto                      */
+  uint32_t tiles_linear;    /* tasks per linear operator (Section 4.1: "proportional to the
+                               number of SMs", user-settable); 0 = n_workers                    */
+  uint32_t tiles_lm_head;   /* tasks for the LM head; 0 = n_workers                             */
+  uint32_t tiles_pointwise; /* column tiles per batch row of add / swiglu operators; 0 = 1     */
+  uint32_t launch_mode;     /* MPK_LAUNCH_*                                                     */
+  uint32_t force_aot;       /* 1 = label every operator ahead-of-time even with schedulers      */
+  uint32_t prefetch;        /* 1 = cross-task weight pre-loading (Section 5.3)                  */
+  uint32_t host_only;       /* 1 = build the task graph on the host only: no device is touched,
+                               weight/KV pointers may be NULL; mpk_decode_step is refused       */
+  uint32_t spin_timeout_ms; /* in-kernel watchdog for every wait; 0 = 2000 ms                   */
+  uint32_t debug_flags;     /* reserved, must be 0                                              */
+} mpk_compile_options;
+
+typedef struct mpk_graph mpk_graph;
+
+/* Compile one decode step for `cfg` into a task graph (Section 4.1: operator decomposition,
+ * dependency analysis, event fusion, normalization, linearization; Section 5.2: launch-mode
+ * labelling and ahead-of-time pre-enqueue) and upload it.
+ *   cfg, weights, kv : host structs (see above); weights/kv may be NULL only with host_only.
+ *   opts             : host, may be NULL (all defaults).
+ *   out              : host, receives the graph handle (NULL on failure).
+ * Errors: INVALID_ARG (null/zero/misaligned: every weight pointer must be 16-byte aligned),
+ * UNSUPPORTED (head_dim not 64 or 128; hidden, ffn or n_q*head_dim not a multiple of 8;
+ * n_q not a multiple of n_kv; batch > 8 for dense linear operators; MoE fields non-zero),
+ * RESIDENCY, OOM, HIP. */
+mpk_status mpk_compile(const mpk_model_config *cfg, const mpk_weight_ptrs *weights,
+                       const mpk_kv_ptrs *kv, const mpk_compile_options *opts, mpk_graph **out);
+
+/* Compile an explicit task DAG (diagnostics and tests of the graph passes of Section 4.1 on
+ * arbitrary graphs): tasks 0..n_tasks-1, `pairs` = host array of n_pairs (producer, consumer)
+ * u32 pairs.  The result is a host-only graph: event fusion, normalization, linearization and
+ * round-robin pre-enqueue are applied exactly as in mpk_compile; it can be exported, not run. */
+mpk_status mpk_compile_dag(uint32_t n_tasks, const uint32_t *pairs, size_t n_pairs,
+                           const mpk_compile_options *opts, mpk_graph **out);
+
+/* Run one decode step (Section 6.1: calling the compiled object issues a single mega-kernel
+ * launch).  Asynchronous on `stream`; no host synchronisation, no allocation.
+ *   token_ids  : device int32 [batch]
+ *   positions  : device int32 [batch]; positions[b] = number of rows already cached for b
+ *   logits_out : device fp32 [batch][vocab], written by the LM-head tasks
+ * A position >= max_seq or a token outside [0, vocab) is detected in the kernel and reported by
+ * mpk_graph_status.  Steps of one graph must not overlap (same stream, or externally ordered). */
+mpk_status mpk_decode_step(mpk_graph *g, const int32_t *token_ids, const int32_t *positions,
+                           float *logits_out, void *stream);
+
+/* After the stream has been synchronised by the caller: translate the device error word.
+ * MPK_OK, MPK_ERR_TIMEOUT (watchdog; the graph must be reset) or MPK_ERR_DEVICE. */
+mpk_status mpk_graph_status(mpk_graph *g);
+
+/* Clear event counters, queues and the error word (after a TIMEOUT).  Synchronises the device. */
+mpk_status mpk_graph_reset(mpk_graph *g);
+
+typedef struct mpk_stats {
+  uint32_t struct_size;
+  uint32_t n_ops;          /* operators after fusion flags                                     */
+  uint32_t n_tasks;        /* tasks in the final graph, dummy tasks included                    */
+  uint32_t n_dummy_tasks;  /* inserted by normalization                                         */
+  uint32_t n_events;       /* events in the final graph (start and terminal events included)   */
+  uint32_t n_events_fused; /* events after the two fusion passes, before normalization          */
+  uint64_t n_pair_deps;    /* producer-consumer task pairs = events before fusion               */
+  uint64_t n_pairs_removed;/* pairs dropped by transitive reduction                             */
+  uint32_t n_jit_tasks, n_aot_tasks;
+  uint32_t n_workers, n_sched_wgs;
+  uint32_t lds_bytes;      /* dynamic LDS per workgroup                                         */
+  uint32_t task_desc_bytes;/* size of one device task descriptor                                */
+  uint64_t successor_bytes_unlinearized; /* 4 B per (event, launched task) entry                */
+  uint64_t successor_bytes_linearized;   /* 8 B per event (first, last)                         */
+  uint64_t weight_bytes;   /* bf16 weight bytes one step streams (embedding rows included)      */
+  uint64_t kv_row_bytes;   /* K+V bytes read per cached position, summed over layers & kv heads */
+  uint64_t act_bytes;      /* fp32 activation buffers owned by the graph                        */
+} mpk_stats;
+
+mpk_status mpk_graph_stats(const mpk_graph *g, mpk_stats *out);
+
+/* Export the compiled graph (host memory, little-endian, see the mpk_export_* structs).
+ * Layout: header | ops[n_ops] | tasks[n_tasks] (linearized order) | events[n_events] |
+ * u32 aot_offsets[n_workers + 1] | u32 aot_tasks[aot_offsets[n_workers]].
+ * Call with buf == NULL to get the size in *need.  INVALID_ARG if cap is too small. */
+#define MPK_EXPORT_MAGIC 0x4B504D54u /* "TMPK" */
+#define MPK_NO_EVENT (-1)
+#define MPK_TASK_DUMMY_OP 0xFFFFFFFFu
+
+typedef struct mpk_export_header {
+  uint32_t magic, version, n_ops, n_tasks, n_events, n_workers, n_sched_wgs, start_event;
+  uint32_t terminal_event, n_real_tasks, fusion, reserved;
+} mpk_export_header;
+
+typedef struct mpk_export_op {
+  uint32_t kind;  /* MPK_OP_*                                          */
+  int32_t layer;  /* -1 for embedding / final norm / LM head           */
+  uint32_t tb, tc; /* partition degree along batch rows and columns    */
+  uint32_t n_tasks;
+  uint32_t jit;   /* 1 = just-in-time launch, 0 = ahead-of-time        */
+  uint32_t rows, cols; /* output tensor shape                          */
+} mpk_export_op;
+
+typedef struct mpk_export_task {
+  uint32_t op;   /* index into ops, MPK_TASK_DUMMY_OP for a dummy task */
+  uint32_t tile; /* tile index ib * tc + ic within the operator        */
+  int32_t dep_event, trig_event; /* MPK_NO_EVENT if none               */
+  int32_t worker; /* pre-assigned worker (AOT), -1 for JIT             */
+  uint32_t jit;
+} mpk_export_task;
+
+typedef struct mpk_export_event {
+  uint32_t required; /* notifications needed for activation                       */
+  uint32_t first;    /* first launched task (index into the linearized task list) */
+  uint32_t last;     /* one past the last launched task (empty range: == first)   */
+  uint32_t flags;    /* bit 0: launches JIT tasks (handled by a scheduler)        */
+} mpk_export_event;
+
+enum {
+  MPK_OP_EMBED = 0, MPK_OP_RMSNORM = 1, MPK_OP_LINEAR = 2, MPK_OP_ROPE = 3,
+  MPK_OP_ATTN_PARTIAL = 4, MPK_OP_ATTN_MERGE = 5, MPK_OP_ADD = 6, MPK_OP_SWIGLU = 7,
+  MPK_OP_GATEUP = 8, MPK_OP_ROUTER = 9, MPK_OP_EXPERT = 10
+};
+
+mpk_status mpk_graph_export(const mpk_graph *g, void *buf, size_t cap, size_t *need);
+
+const char *mpk_last_error(void);
+void mpk_graph_destroy(mpk_graph *g);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MPK_H */

@@ -1,0 +1,235 @@
+"""Thin ctypes binding over include/mpk.h: argument marshalling only.
+
+Every step of the decode path runs inside libmpk.so; nothing here computes.  If the library is
+missing the import fails loudly (there is no fallback path)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+(MPK_OK, MPK_ERR_INVALID_ARG, MPK_ERR_UNSUPPORTED, MPK_ERR_OOM, MPK_ERR_RESIDENCY, MPK_ERR_HIP,
+ MPK_ERR_TIMEOUT, MPK_ERR_INTERNAL, MPK_ERR_DEVICE) = range(9)
+FUSE_NORM, FUSE_RESID, FUSE_SWIGLU, FUSE_MERGE, FUSE_ROPE = 1, 2, 4, 8, 16
+LAUNCH_MEGA, LAUNCH_PER_OP = 0, 1
+TASK_DUMMY_OP = 0xFFFFFFFF
+(OP_EMBED, OP_RMSNORM, OP_LINEAR, OP_ROPE, OP_ATTN_PARTIAL, OP_ATTN_MERGE, OP_ADD, OP_SWIGLU,
+ OP_GATEUP, OP_ROUTER, OP_EXPERT) = range(11)
+
+
+class ModelConfig(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("n_layers", C.c_uint32), ("hidden", C.c_uint32),
+                ("n_q_heads", C.c_uint32), ("n_kv_heads", C.c_uint32), ("head_dim", C.c_uint32),
+                ("ffn", C.c_uint32), ("vocab", C.c_uint32), ("rms_eps", C.c_float),
+                ("rope_theta", C.c_float), ("batch", C.c_uint32), ("max_seq", C.c_uint32),
+                ("n_experts", C.c_uint32), ("top_k", C.c_uint32), ("expert_ffn", C.c_uint32),
+                ("flags", C.c_uint32)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("attn_norm", "wqkv", "wo", "mlp_norm", "wgu", "wd",
+                                          "router", "expert_wgu", "expert_wd")]
+
+
+class WeightPtrs(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p),
+                ("layers", C.POINTER(LayerWeights))]
+
+
+class KvPtrs(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p)]
+
+
+class CompileOptions(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in
+                ("struct_size", "n_workers", "n_sched_wgs", "fusion", "transitive_reduction",
+                 "attn_chunks", "tiles_linear", "tiles_lm_head", "tiles_pointwise", "launch_mode",
+                 "force_aot", "prefetch", "host_only", "spin_timeout_ms", "debug_flags")]
+
+
+class Stats(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("n_ops", C.c_uint32), ("n_tasks", C.c_uint32),
+                ("n_dummy_tasks", C.c_uint32), ("n_events", C.c_uint32),
+                ("n_events_fused", C.c_uint32), ("n_pair_deps", C.c_uint64),
+                ("n_pairs_removed", C.c_uint64), ("n_jit_tasks", C.c_uint32),
+                ("n_aot_tasks", C.c_uint32), ("n_workers", C.c_uint32),
+                ("n_sched_wgs", C.c_uint32), ("lds_bytes", C.c_uint32),
+                ("task_desc_bytes", C.c_uint32), ("successor_bytes_unlinearized", C.c_uint64),
+                ("successor_bytes_linearized", C.c_uint64), ("weight_bytes", C.c_uint64),
+                ("kv_row_bytes", C.c_uint64), ("act_bytes", C.c_uint64)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+EXPORT_HEADER = np.dtype([(n, "<u4") for n in
+                          ("magic", "version", "n_ops", "n_tasks", "n_events", "n_workers",
+                           "n_sched_wgs", "start_event", "terminal_event", "n_real_tasks",
+                           "fusion", "reserved")])
+EXPORT_OP = np.dtype([("kind", "<u4"), ("layer", "<i4"), ("tb", "<u4"), ("tc", "<u4"),
+                      ("n_tasks", "<u4"), ("jit", "<u4"), ("rows", "<u4"), ("cols", "<u4")])
+EXPORT_TASK = np.dtype([("op", "<u4"), ("tile", "<u4"), ("dep_event", "<i4"),
+                        ("trig_event", "<i4"), ("worker", "<i4"), ("jit", "<u4")])
+EXPORT_EVENT = np.dtype([("required", "<u4"), ("first", "<u4"), ("last", "<u4"),
+                         ("flags", "<u4")])
+
+SYMBOLS = ("mpk_compile", "mpk_compile_dag", "mpk_decode_step", "mpk_graph_status",
+           "mpk_graph_reset", "mpk_graph_stats", "mpk_graph_export", "mpk_last_error",
+           "mpk_graph_destroy")
+
+_lib = None
+
+
+def lib():
+    """Load libmpk.so (building it only if nothing has been built yet)."""
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build(force=True)
+        L = C.CDLL(path)
+        vp = C.c_void_p
+        L.mpk_compile.argtypes = [C.POINTER(ModelConfig), C.POINTER(WeightPtrs), C.POINTER(KvPtrs),
+                                  C.POINTER(CompileOptions), C.POINTER(vp)]
+        L.mpk_compile_dag.argtypes = [C.c_uint32, vp, C.c_size_t, C.POINTER(CompileOptions),
+                                      C.POINTER(vp)]
+        L.mpk_decode_step.argtypes = [vp, vp, vp, vp, vp]
+        L.mpk_graph_status.argtypes = [vp]
+        L.mpk_graph_reset.argtypes = [vp]
+        L.mpk_graph_stats.argtypes = [vp, C.POINTER(Stats)]
+        L.mpk_graph_export.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
+        L.mpk_last_error.restype = C.c_char_p
+        L.mpk_graph_destroy.argtypes = [vp]
+        L.mpk_graph_destroy.restype = None
+        for n in SYMBOLS[:7]:
+            getattr(L, n).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+class MpkError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__(f"mpk status {status}: {msg}")
+        self.status = status
+
+
+def _check(st):
+    if st != MPK_OK:
+        raise MpkError(st, lib().mpk_last_error().decode())
+
+
+def model_config(shape) -> ModelConfig:
+    """shape: any object with the ModelShape fields (synth.gen.ModelShape)."""
+    return ModelConfig(C.sizeof(ModelConfig), shape.n_layers, shape.hidden, shape.n_q_heads,
+                       shape.n_kv_heads, shape.head_dim, shape.ffn, shape.vocab, shape.rms_eps,
+                       shape.rope_theta, shape.batch, shape.max_seq, shape.n_experts, shape.top_k,
+                       shape.expert_ffn, 0)
+
+
+def compile_options(**kw) -> CompileOptions:
+    o = CompileOptions()
+    o.struct_size = C.sizeof(CompileOptions)
+    for k, v in kw.items():
+        if not hasattr(o, k):
+            raise TypeError(k)
+        setattr(o, k, int(v))
+    return o
+
+
+class Export:
+    """Parsed mpk_graph_export blob."""
+
+    def __init__(self, blob: bytes):
+        off = 0
+        self.header = np.frombuffer(blob, EXPORT_HEADER, 1, off)[0]
+        off += EXPORT_HEADER.itemsize
+        h = self.header
+        assert h["magic"] == 0x4B504D54
+        self.ops = np.frombuffer(blob, EXPORT_OP, int(h["n_ops"]), off)
+        off += EXPORT_OP.itemsize * int(h["n_ops"])
+        self.tasks = np.frombuffer(blob, EXPORT_TASK, int(h["n_tasks"]), off)
+        off += EXPORT_TASK.itemsize * int(h["n_tasks"])
+        self.events = np.frombuffer(blob, EXPORT_EVENT, int(h["n_events"]), off)
+        off += EXPORT_EVENT.itemsize * int(h["n_events"])
+        nw = int(h["n_workers"])
+        self.aot_off = np.frombuffer(blob, "<u4", nw + 1, off)
+        off += 4 * (nw + 1)
+        self.aot = np.frombuffer(blob, "<u4", int(self.aot_off[-1]), off)
+        off += 4 * int(self.aot_off[-1])
+        assert off == len(blob)
+
+
+class Graph:
+    """Owner of one mpk_graph handle."""
+
+    def __init__(self, handle, keepalive=None):
+        self._h = handle
+        self._keep = keepalive
+
+    def decode_step(self, token_ids_ptr: int, positions_ptr: int, logits_ptr: int, stream: int = 0):
+        _check(lib().mpk_decode_step(self._h, token_ids_ptr, positions_ptr, logits_ptr, stream))
+
+    def status(self):
+        _check(lib().mpk_graph_status(self._h))
+
+    def reset(self):
+        _check(lib().mpk_graph_reset(self._h))
+
+    def stats(self) -> dict:
+        s = Stats()
+        _check(lib().mpk_graph_stats(self._h, C.byref(s)))
+        return s.as_dict()
+
+    def export(self) -> Export:
+        need = C.c_size_t(0)
+        _check(lib().mpk_graph_export(self._h, None, 0, C.byref(need)))
+        buf = C.create_string_buffer(need.value)
+        _check(lib().mpk_graph_export(self._h, buf, need.value, C.byref(need)))
+        return Export(buf.raw)
+
+    def destroy(self):
+        if self._h:
+            lib().mpk_graph_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def compile_graph(shape, weights: dict | None, kv: tuple | None, **opts) -> Graph:
+    """weights: {'embed': ptr, 'final_norm': ptr, 'lm_head': ptr, 'layers': [dict per layer with
+    attn_norm, wqkv, wo, mlp_norm, wgu, wd]} of integer device addresses; kv: (k_ptr, v_ptr).
+    Both may be None with host_only=1."""
+    cfg = model_config(shape)
+    o = compile_options(**opts)
+    h = C.c_void_p()
+    keep = []
+    if weights is None:
+        st = lib().mpk_compile(C.byref(cfg), None, None, C.byref(o), C.byref(h))
+    else:
+        arr = (LayerWeights * shape.n_layers)()
+        for l, lw in enumerate(weights["layers"]):
+            for k, v in lw.items():
+                setattr(arr[l], k, v)
+        wp = WeightPtrs(weights["embed"], weights["final_norm"], weights["lm_head"], arr)
+        kp = KvPtrs(kv[0], kv[1])
+        keep = [arr, wp, kp]
+        st = lib().mpk_compile(C.byref(cfg), C.byref(wp), C.byref(kp), C.byref(o), C.byref(h))
+    _check(st)
+    return Graph(h, keep)
+
+
+def compile_dag(n_tasks: int, pairs, **opts) -> Graph:
+    p = np.ascontiguousarray(np.asarray(pairs, dtype=np.uint32).reshape(-1, 2))
+    o = compile_options(**opts)
+    h = C.c_void_p()
+    _check(lib().mpk_compile_dag(n_tasks, p.ctypes.data, len(p), C.byref(o), C.byref(h)))
+    return Graph(h)

@@ -1,0 +1,877 @@
+// Host-side task-graph compiler (paper Section 4.1 and the launch-mode labelling of Section 5.2).
+//
+//   K1  operator list of one decode step (fusion flags applied here)
+//   K2  operator decomposition: each operator's OUTPUT tensor is cut into disjoint tiles, one
+//       task per tile (Section 4.1 "operator decomposition")
+//   K3  dependency analysis: task t1 -> t2 iff t1's output region overlaps a region t2 reads
+//       (Section 4.1 "dependency analysis"), evaluated with interval arithmetic on tile bounds
+//   K4  event fusion: successor-set (Def. 4.1) then predecessor-set (Def. 4.2)
+//   K5  normalization: at most one dependent and one triggering event per task (Fig. 5)
+//   K6  linearization: Algorithm 1, events store [first, last) into the task list
+//   K7  JIT / AOT labels per operator and round-robin pre-enqueue of AOT tasks (Section 5.2)
+//
+// Integer-only; runs once per mpk_compile.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <map>
+#include <numeric>
+#include <unordered_map>
+
+#include "mpk_internal.h"
+
+namespace mpk {
+
+static thread_local char g_err[512] = "";
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+const char* last_error() { return g_err; }
+
+// ------------------------------------------------------------------ tiling helpers
+// n units in k contiguous tiles: the first n % k tiles hold ceil(n / k) units, the rest floor.
+static inline uint32_t tile_begin(uint32_t n, uint32_t k, uint32_t i) {
+  uint32_t q = n / k, r = n % k;
+  return i * q + std::min(i, r);
+}
+static inline uint32_t tile_of(uint32_t n, uint32_t k, uint32_t u) {
+  uint32_t q = n / k, r = n % k;
+  uint32_t big = r * (q + 1);
+  if (u < big) return u / (q + 1);
+  return r + (u - big) / q;   // q > 0 here because k <= n is enforced at decomposition
+}
+
+struct Rect {
+  int tensor;
+  uint32_t b0, b1, c0, c1;
+};
+
+// ------------------------------------------------------------------ generic graph passes
+struct Ev {
+  std::vector<uint32_t> in, out;   // sorted task ids
+};
+
+struct VecHash {
+  size_t operator()(const std::vector<uint32_t>& v) const {
+    uint64_t h = 0x9E3779B97F4A7C15ull ^ v.size();
+    for (uint32_t x : v) {
+      h ^= x + 0x9E3779B97F4A7C15ull + (h << 6) + (h >> 2);
+    }
+    return (size_t)h;
+  }
+};
+
+static void sort_unique(std::vector<uint32_t>& v) {
+  std::sort(v.begin(), v.end());
+  v.erase(std::unique(v.begin(), v.end()), v.end());
+}
+
+// Def. 4.1: events with equal OutTasks become one event whose InTasks is the union.
+static std::vector<Ev> successor_set_fusion(std::vector<Ev>& evs) {
+  std::unordered_map<std::vector<uint32_t>, size_t, VecHash> by;
+  std::vector<Ev> out;
+  for (auto& e : evs) {
+    auto it = by.find(e.out);
+    if (it == by.end()) {
+      by.emplace(e.out, out.size());
+      out.push_back(std::move(e));
+    } else {
+      auto& dst = out[it->second].in;
+      dst.insert(dst.end(), e.in.begin(), e.in.end());
+    }
+  }
+  for (auto& e : out) sort_unique(e.in);
+  return out;
+}
+
+// Def. 4.2: events with equal InTasks become one event whose OutTasks is the union.
+static std::vector<Ev> predecessor_set_fusion(std::vector<Ev>& evs) {
+  std::unordered_map<std::vector<uint32_t>, size_t, VecHash> by;
+  std::vector<Ev> out;
+  for (auto& e : evs) {
+    auto it = by.find(e.in);
+    if (it == by.end()) {
+      by.emplace(e.in, out.size());
+      out.push_back(std::move(e));
+    } else {
+      auto& dst = out[it->second].out;
+      dst.insert(dst.end(), e.out.begin(), e.out.end());
+    }
+  }
+  for (auto& e : out) sort_unique(e.out);
+  return out;
+}
+
+// Fig. 5 rewrites.  Tasks that trigger the same set of k > 1 events share one new event and k
+// dummy tasks (one per original event); likewise for tasks that depend on the same set of k > 1
+// events.  Dummy ids start at *n_tasks and *n_tasks is advanced.
+static void normalize(std::vector<Ev>& evs, uint32_t* n_tasks) {
+  for (int pass = 0; pass < 2; ++pass) {
+    // pass 0: fan-out (lists = events a task triggers); pass 1: fan-in (events it depends on)
+    std::vector<std::vector<uint32_t>> lists(*n_tasks);
+    for (uint32_t ei = 0; ei < evs.size(); ++ei)
+      for (uint32_t t : (pass == 0 ? evs[ei].in : evs[ei].out)) lists[t].push_back(ei);
+    std::map<std::vector<uint32_t>, std::vector<uint32_t>> groups;   // ordered: deterministic
+    for (uint32_t t = 0; t < lists.size(); ++t)
+      if (lists[t].size() > 1) groups[lists[t]].push_back(t);
+    for (auto& kv : groups) {
+      const std::vector<uint32_t>& es = kv.first;
+      const std::vector<uint32_t>& ts = kv.second;   // sorted by construction
+      Ev fresh;
+      std::vector<uint32_t> dummies;
+      for (uint32_t ei : es) {
+        uint32_t dmy = (*n_tasks)++;
+        dummies.push_back(dmy);
+        auto& side = (pass == 0 ? evs[ei].in : evs[ei].out);
+        std::vector<uint32_t> kept;
+        std::set_difference(side.begin(), side.end(), ts.begin(), ts.end(),
+                            std::back_inserter(kept));
+        kept.push_back(dmy);   // dummy ids exceed all earlier ids: stays sorted
+        side.swap(kept);
+      }
+      if (pass == 0) {
+        fresh.in = ts;
+        fresh.out = dummies;
+      } else {
+        fresh.in = dummies;
+        fresh.out = ts;
+      }
+      evs.push_back(std::move(fresh));
+    }
+  }
+}
+
+struct PassInput {
+  uint32_t n_real = 0;
+  std::vector<std::vector<uint32_t>> prod;   // per task: sorted direct producers
+  std::vector<uint32_t> op_of;               // per real task: operator index (or 0)
+  std::vector<uint32_t> op_jit;              // per operator: 1 = JIT
+  std::vector<uint32_t> tile_of_task;        // per real task
+  std::vector<std::vector<uint32_t>> prod_before;   // transitive reduction: sets before pruning
+  std::vector<uint64_t> scratch_anc;
+};
+
+static mpk_status run_passes(PassInput& in, const mpk_compile_options& opt, HostGraph& g) {
+  const uint32_t n_real = in.n_real;
+  g.n_real = n_real;
+  // --- K3 result -> one event per consumer.  Every pair event (t1, t2) has OutTasks = {t2}, so
+  // grouping the pairs by consumer IS successor-set fusion applied to the pair events; the
+  // function is still run so that arbitrary inputs take the same path.
+  uint64_t n_pairs = 0;
+  std::vector<Ev> evs;
+  for (uint32_t t = 0; t < n_real; ++t) {
+    if (in.prod[t].empty()) continue;
+    n_pairs += in.prod[t].size();
+    Ev e;
+    e.in = in.prod[t];
+    e.out = {t};
+    evs.push_back(std::move(e));
+  }
+  g.stats.n_pair_deps = n_pairs;
+  evs = successor_set_fusion(evs);
+  evs = predecessor_set_fusion(evs);
+  g.stats.n_events_fused = (uint32_t)evs.size();
+  uint64_t succ_entries = 0;
+  for (auto& e : evs) succ_entries += e.out.size();
+
+  // --- K5
+  uint32_t n_tasks = n_real;
+  normalize(evs, &n_tasks);
+  g.stats.n_dummy_tasks = n_tasks - n_real;
+
+  // terminal event: tasks that trigger nothing notify it, its range is empty
+  std::vector<int32_t> dep_of(n_tasks, -1), trig_of(n_tasks, -1);
+  for (uint32_t ei = 0; ei < evs.size(); ++ei) {
+    for (uint32_t t : evs[ei].out) {
+      if (dep_of[t] != -1) { set_error("normalization left task %u with two dependent events", t); return MPK_ERR_INTERNAL; }
+      dep_of[t] = (int32_t)ei;
+    }
+    for (uint32_t t : evs[ei].in) {
+      if (trig_of[t] != -1) { set_error("normalization left task %u with two triggering events", t); return MPK_ERR_INTERNAL; }
+      trig_of[t] = (int32_t)ei;
+    }
+  }
+  {
+    Ev term;
+    for (uint32_t t = 0; t < n_tasks; ++t)
+      if (trig_of[t] == -1) term.in.push_back(t);
+    for (uint32_t t : term.in) trig_of[t] = (int32_t)evs.size();
+    evs.push_back(std::move(term));
+  }
+  const uint32_t term_old = (uint32_t)evs.size() - 1;
+
+  // --- K6: Algorithm 1.  Event ids are renumbered in dequeue order; the start event is id 0.
+  std::vector<std::vector<uint32_t>> members(evs.size());
+  std::vector<uint32_t> sources;
+  for (uint32_t t = 0; t < n_tasks; ++t) {
+    if (dep_of[t] < 0) sources.push_back(t);
+    else members[dep_of[t]].push_back(t);   // ascending task id: (op, tile) order, dummies last
+  }
+  std::vector<uint32_t> remaining(evs.size());
+  for (uint32_t ei = 0; ei < evs.size(); ++ei) remaining[ei] = (uint32_t)evs[ei].in.size();
+  std::vector<int32_t> new_id(evs.size(), -1);
+  std::vector<uint32_t> order;          // old task ids in linearized order
+  std::vector<uint32_t> pos(n_tasks, UINT32_MAX);
+  std::vector<EventDesc> events;
+  std::deque<int32_t> q;
+  q.push_back(-1);   // start event
+  while (!q.empty()) {
+    int32_t e = q.front();
+    q.pop_front();
+    const std::vector<uint32_t>& mem = (e < 0) ? sources : members[e];
+    EventDesc d{};
+    d.required = (e < 0) ? 0u : (uint32_t)evs[e].in.size();
+    d.first = (uint32_t)order.size();
+    if (e >= 0) new_id[e] = (int32_t)events.size();
+    for (uint32_t t : mem) {
+      pos[t] = (uint32_t)order.size();
+      order.push_back(t);
+      int32_t e2 = trig_of[t];
+      if (e2 >= 0 && --remaining[e2] == 0) q.push_back(e2);
+    }
+    d.last = (uint32_t)order.size();
+    events.push_back(d);
+  }
+  if (order.size() != n_tasks) { set_error("linearization placed %zu of %u tasks (cycle?)", order.size(), n_tasks); return MPK_ERR_INTERNAL; }
+  for (uint32_t ei = 0; ei < evs.size(); ++ei)
+    if (new_id[ei] < 0) { set_error("event %u never activated during linearization", ei); return MPK_ERR_INTERNAL; }
+  g.start_event = 0;
+  g.terminal_event = (uint32_t)new_id[term_old];
+
+  // --- K7: launch modes.  A dummy task is AOT.  An event that launches at least one JIT task is
+  // handled by a scheduler.
+  const bool have_sched = opt.n_sched_wgs > 0 && !opt.force_aot;
+  g.tasks.resize(n_tasks);
+  uint32_t n_jit = 0;
+  for (uint32_t i = 0; i < n_tasks; ++i) {
+    uint32_t t = order[i];
+    HostTask& ht = g.tasks[i];
+    bool real = t < n_real;
+    ht.op = real ? in.op_of[t] : MPK_TASK_DUMMY_OP;
+    ht.tile = real ? in.tile_of_task[t] : (t - n_real);
+    ht.dep_event = dep_of[t] < 0 ? 0 : new_id[dep_of[t]];   // sources depend on the start event
+    ht.trig_event = new_id[trig_of[t]];
+    ht.jit = (real && have_sched && !in.op_jit.empty() && in.op_jit[in.op_of[t]]) ? 1u : 0u;
+    ht.worker = -1;
+    n_jit += ht.jit;
+  }
+  for (auto& e : events) {
+    e.flags = 0;
+    for (uint32_t i = e.first; i < e.last; ++i)
+      if (g.tasks[i].jit) e.flags |= 1u;
+  }
+  g.events = events;
+  const uint32_t W = opt.n_workers;
+  std::vector<std::vector<uint32_t>> queues(W);
+  uint32_t cursor = 0;
+  for (uint32_t i = 0; i < n_tasks; ++i) {
+    if (g.tasks[i].jit) continue;
+    g.tasks[i].worker = (int32_t)(cursor % W);
+    queues[cursor % W].push_back(i);
+    ++cursor;
+  }
+  g.aot_off.assign(W + 1, 0);
+  g.aot.clear();
+  for (uint32_t w = 0; w < W; ++w) {
+    g.aot_off[w] = (uint32_t)g.aot.size();
+    g.aot.insert(g.aot.end(), queues[w].begin(), queues[w].end());
+  }
+  g.aot_off[W] = (uint32_t)g.aot.size();
+
+  g.stats.n_tasks = n_tasks;
+  g.stats.n_events = (uint32_t)events.size();
+  g.stats.n_jit_tasks = n_jit;
+  g.stats.n_aot_tasks = n_tasks - n_jit;
+  g.stats.successor_bytes_unlinearized = 4 * (succ_entries + g.stats.n_dummy_tasks);
+  g.stats.successor_bytes_linearized = 8ull * events.size();
+  g.stats.n_workers = W;
+  g.stats.n_sched_wgs = opt.n_sched_wgs;
+  g.stats.task_desc_bytes = sizeof(TaskDesc);
+  return MPK_OK;
+}
+
+// ------------------------------------------------------------------ transitive reduction
+// Drops a pair (p, t) when p is already an ancestor of another direct producer of t.  Ancestor
+// sets are bitsets over a sliding window of operators: an implied path from p to t only visits
+// operators between op(p) and op(t), and no pair spans more than `max_span` operators.
+static uint64_t transitive_reduction(PassInput& in, const std::vector<HostOp>& ops) {
+  const uint32_t n = in.n_real;
+  uint32_t max_span = 1;
+  for (uint32_t t = 0; t < n; ++t)
+    for (uint32_t p : in.prod[t]) max_span = std::max(max_span, in.op_of[t] - in.op_of[p]);
+  auto window_base = [&](uint32_t op) {
+    uint32_t lo = op > max_span ? op - max_span : 0;
+    return ops[lo].task_base;
+  };
+  std::vector<std::vector<uint64_t>> anc(n);   // bit i = task (window_base(op(t)) + i)
+  in.prod_before.assign(n, {});
+  uint64_t removed = 0;
+  uint32_t free_below = 0;
+  for (uint32_t t = 0; t < n; ++t) {
+    uint32_t op = in.op_of[t];
+    uint32_t base = window_base(op);
+    // release ancestor sets that can no longer be referenced
+    while (free_below < base) {
+      std::vector<uint64_t>().swap(anc[free_below]);
+      ++free_below;
+    }
+    uint32_t nbits = t - base;
+    std::vector<uint64_t> u((nbits + 63) / 64 + 1, 0);   // union of producers' ancestors
+    auto& P = in.prod[t];
+    if (t > 0 && in.op_of[t - 1] == op && in.prod_before[t - 1] == P) {
+      u = anc[t - 1];   // same producer set as the previous tile: same ancestors
+      u.resize((nbits + 63) / 64 + 1, 0);
+    } else {
+      for (uint32_t p : P) {
+        // anc[p] bit j is task pb + j with pb <= base: shift right by s = base - pb
+        uint32_t s = base - window_base(in.op_of[p]);
+        const auto& a = anc[p];
+        size_t ws = s >> 6, bs = s & 63;
+        for (size_t k = 0; k < u.size(); ++k) {
+          uint64_t lo = (k + ws < a.size()) ? a[k + ws] : 0;
+          uint64_t hi = (k + ws + 1 < a.size()) ? a[k + ws + 1] : 0;
+          u[k] |= bs ? ((lo >> bs) | (hi << (64 - bs))) : lo;
+        }
+        u[(p - base) >> 6] |= 1ull << ((p - base) & 63);
+      }
+      // u now holds P and all ancestors; strip P's own bits unless implied by another producer
+      std::vector<uint64_t> self(u.size(), 0);
+      for (uint32_t p : P) {
+        uint32_t s = base - window_base(in.op_of[p]);
+        const auto& a = anc[p];
+        size_t ws = s >> 6, bs = s & 63;
+        for (size_t k = 0; k < self.size(); ++k) {
+          uint64_t lo = (k + ws < a.size()) ? a[k + ws] : 0;
+          uint64_t hi = (k + ws + 1 < a.size()) ? a[k + ws + 1] : 0;
+          self[k] |= bs ? ((lo >> bs) | (hi << (64 - bs))) : lo;
+        }
+      }
+      in.scratch_anc.swap(self);   // ancestors only (without P itself)
+    }
+    const std::vector<uint64_t>& only_anc = in.scratch_anc;
+    std::vector<uint32_t> kept;
+    for (uint32_t p : P) {
+      bool implied = ((p - base) >> 6) < only_anc.size() &&
+                     ((only_anc[(p - base) >> 6] >> ((p - base) & 63)) & 1);
+      if (implied) ++removed;
+      else kept.push_back(p);
+    }
+    in.prod_before[t] = P;
+    P.swap(kept);
+    anc[t].swap(u);
+  }
+  return removed;
+}
+
+// ------------------------------------------------------------------ K1: operator list
+struct Builder {
+  const mpk_model_config& c;
+  const mpk_compile_options& o;
+  HostGraph& g;
+  int new_tensor(uint32_t rows, uint32_t cols, bool external = false) {
+    HostTensor t{rows, cols, external ? SIZE_MAX : g.arena_floats};
+    if (!external) g.arena_floats += ((size_t)rows * cols + 63) / 64 * 64;
+    g.tensors.push_back(t);
+    return (int)g.tensors.size() - 1;
+  }
+  HostOp& add(uint32_t kind, int layer, const char* name, int out, uint32_t unit, int in1,
+              int in2 = -1) {
+    HostOp op{};
+    op.kind = kind;
+    op.layer = layer;
+    op.name = (layer >= 0 ? "L" + std::to_string(layer) + "." : std::string()) + name;
+    op.out_tensor = out;
+    op.rows = g.tensors[out].rows;
+    op.cols = g.tensors[out].cols;
+    op.unit = unit;
+    op.in_tensor = in1;
+    op.in2_tensor = in2;
+    g.ops.push_back(op);
+    return g.ops.back();
+  }
+};
+
+static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
+                            const mpk_compile_options& o, uint32_t C, HostGraph& g) {
+  Builder b{c, o, g};
+  const uint32_t B = c.batch, H = c.hidden, d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads;
+  const uint32_t F = c.ffn, V = c.vocab, grp = nq / nkv, QKV = (nq + 2 * nkv) * d;
+  const uint32_t f = o.fusion;
+  mpk_layer_weights none{};
+  int x = b.new_tensor(B, H);
+  {
+    HostOp& op = b.add(MPK_OP_EMBED, -1, "embed", x, H, -1);
+    op.w = w ? w->embed : nullptr;
+    op.K = H;
+  }
+  for (uint32_t l = 0; l < c.n_layers; ++l) {
+    const mpk_layer_weights& lw = (w && w->layers) ? w->layers[l] : none;
+    int qkv_in = x;
+    if (!(f & MPK_FUSE_NORM)) {
+      int xn = b.new_tensor(B, H);
+      HostOp& op = b.add(MPK_OP_RMSNORM, l, "attn_norm", xn, H, x);
+      op.w2 = lw.attn_norm; op.f0 = c.rms_eps; op.K = H;
+      qkv_in = xn;
+    }
+    int qkv = b.new_tensor(B, QKV);
+    {
+      HostOp& op = b.add(MPK_OP_LINEAR, l, "qkv", qkv, 1, qkv_in);
+      op.w = lw.wqkv; op.K = H;
+      if (f & MPK_FUSE_NORM) { op.flags |= TF_PRO_NORM; op.w2 = lw.attn_norm; op.f0 = c.rms_eps; }
+    }
+    int qsrc = qkv;
+    if (!(f & MPK_FUSE_ROPE)) {
+      int rk = b.new_tensor(B, QKV);
+      HostOp& op = b.add(MPK_OP_ROPE, l, "rope", rk, d, qkv);
+      op.f1 = c.rope_theta; op.p0 = l;
+      qsrc = rk;
+    }
+    int part = b.new_tensor(B, nkv * C * grp * (d + 2));
+    {
+      HostOp& op = b.add(MPK_OP_ATTN_PARTIAL, l, "attn_partial", part, grp * (d + 2), qsrc);
+      op.p0 = l; op.p1 = C; op.f1 = c.rope_theta;
+      if (f & MPK_FUSE_ROPE) op.flags |= TF_ROPE_FUSED;
+    }
+    int osrc = part;
+    uint32_t oK = nq * d;
+    if (!(f & MPK_FUSE_MERGE)) {
+      int ot = b.new_tensor(B, nq * d);
+      HostOp& op = b.add(MPK_OP_ATTN_MERGE, l, "attn_merge", ot, d, part);
+      op.p1 = C;
+      osrc = ot;
+    }
+    int x1 = b.new_tensor(B, H);
+    if (f & MPK_FUSE_RESID) {
+      HostOp& op = b.add(MPK_OP_LINEAR, l, "o_proj", x1, 1, osrc, x);
+      op.w = lw.wo; op.K = oK; op.flags |= TF_EPI_RESID;
+      if (f & MPK_FUSE_MERGE) { op.flags |= TF_PRO_MERGE; op.p1 = C; }
+    } else {
+      int a = b.new_tensor(B, H);
+      HostOp& op = b.add(MPK_OP_LINEAR, l, "o_proj", a, 1, osrc);
+      op.w = lw.wo; op.K = oK;
+      if (f & MPK_FUSE_MERGE) { op.flags |= TF_PRO_MERGE; op.p1 = C; }
+      b.add(MPK_OP_ADD, l, "resid1", x1, 1, x, a);
+    }
+    int gin = x1;
+    if (!(f & MPK_FUSE_NORM)) {
+      int xn2 = b.new_tensor(B, H);
+      HostOp& op = b.add(MPK_OP_RMSNORM, l, "mlp_norm", xn2, H, x1);
+      op.w2 = lw.mlp_norm; op.f0 = c.rms_eps; op.K = H;
+      gin = xn2;
+    }
+    int h = b.new_tensor(B, F);
+    if (f & MPK_FUSE_SWIGLU) {
+      HostOp& op = b.add(MPK_OP_GATEUP, l, "gate_up", h, 1, gin);
+      op.w = lw.wgu; op.K = H; op.flags |= TF_GATEUP; op.p0 = F;
+      if (f & MPK_FUSE_NORM) { op.flags |= TF_PRO_NORM; op.w2 = lw.mlp_norm; op.f0 = c.rms_eps; }
+    } else {
+      int gu = b.new_tensor(B, 2 * F);
+      HostOp& op = b.add(MPK_OP_LINEAR, l, "gate_up", gu, 1, gin);
+      op.w = lw.wgu; op.K = H;
+      if (f & MPK_FUSE_NORM) { op.flags |= TF_PRO_NORM; op.w2 = lw.mlp_norm; op.f0 = c.rms_eps; }
+      HostOp& sw = b.add(MPK_OP_SWIGLU, l, "swiglu", h, 1, gu);
+      sw.p0 = F;
+    }
+    int xo = b.new_tensor(B, H);
+    if (f & MPK_FUSE_RESID) {
+      HostOp& op = b.add(MPK_OP_LINEAR, l, "down", xo, 1, h, x1);
+      op.w = lw.wd; op.K = F; op.flags |= TF_EPI_RESID;
+    } else {
+      int m = b.new_tensor(B, H);
+      HostOp& op = b.add(MPK_OP_LINEAR, l, "down", m, 1, h);
+      op.w = lw.wd; op.K = F;
+      b.add(MPK_OP_ADD, l, "resid2", xo, 1, x1, m);
+    }
+    x = xo;
+  }
+  int lin = x;
+  if (!(f & MPK_FUSE_NORM)) {
+    int xnf = b.new_tensor(B, H);
+    HostOp& op = b.add(MPK_OP_RMSNORM, -1, "final_norm", xnf, H, x);
+    op.w2 = w ? w->final_norm : nullptr; op.f0 = c.rms_eps; op.K = H;
+    lin = xnf;
+  }
+  int logits = b.new_tensor(B, V, /*external=*/true);
+  {
+    HostOp& op = b.add(MPK_OP_LINEAR, -1, "lm_head", logits, 1, lin);
+    op.w = w ? w->lm_head : nullptr; op.K = H; op.flags |= TF_OUT_LOGITS;
+    if (f & MPK_FUSE_NORM) { op.flags |= TF_PRO_NORM; op.w2 = w ? w->final_norm : nullptr; op.f0 = c.rms_eps; }
+  }
+  return MPK_OK;
+}
+
+// ------------------------------------------------------------------ K2: decomposition
+static void tile_bounds(const HostOp& op, uint32_t tile, uint32_t* b0, uint32_t* b1, uint32_t* c0,
+                        uint32_t* c1) {
+  uint32_t ib = tile / op.tc, ic = tile % op.tc, nu = op.cols / op.unit;
+  *b0 = tile_begin(op.rows, op.tb, ib);
+  *b1 = tile_begin(op.rows, op.tb, ib + 1);
+  *c0 = tile_begin(nu, op.tc, ic) * op.unit;
+  *c1 = tile_begin(nu, op.tc, ic + 1) * op.unit;
+}
+
+static void choose_partitions(const mpk_model_config& c, const mpk_compile_options& o,
+                              HostGraph& g) {
+  const uint32_t W = o.n_workers;
+  for (auto& op : g.ops) {
+    uint32_t nu = op.cols / op.unit;
+    switch (op.kind) {
+      case MPK_OP_LINEAR:
+      case MPK_OP_GATEUP: {
+        // One pass over the weights serves every batch row, so the batch is not split; rows are
+        // split over the workers (the partition that minimises device-memory loading,
+        // Section 4.1): each weight byte is read by exactly one task.
+        uint32_t want = (op.flags & TF_OUT_LOGITS) ? (o.tiles_lm_head ? o.tiles_lm_head : W)
+                                                   : (o.tiles_linear ? o.tiles_linear : W);
+        uint32_t cap = std::max(1u, nu / 8);   // at least 8 output rows per task
+        op.tb = 1;
+        op.tc = std::max(1u, std::min(want, cap));
+        break;
+      }
+      case MPK_OP_ROPE:
+      case MPK_OP_ATTN_PARTIAL:
+        op.tb = op.rows;
+        op.tc = nu;
+        break;
+      case MPK_OP_ATTN_MERGE:
+        op.tb = op.rows;
+        op.tc = c.n_kv_heads;
+        break;
+      case MPK_OP_ADD:
+      case MPK_OP_SWIGLU:
+        op.tb = op.rows;
+        op.tc = std::max(1u, std::min(o.tiles_pointwise ? o.tiles_pointwise : 1u, nu));
+        break;
+      default:   // embed, rmsnorm: one task per batch row (needs the whole row)
+        op.tb = op.rows;
+        op.tc = 1;
+    }
+  }
+  uint32_t base = 0;
+  for (auto& op : g.ops) {
+    op.task_base = base;
+    base += op.tb * op.tc;
+  }
+}
+
+// ------------------------------------------------------------------ K3: dependency analysis
+// Regions of the input tensors that one task reads, from the operator's definition.
+static void input_rects(const mpk_model_config& c, const HostOp& op, uint32_t tile,
+                        std::vector<Rect>& out) {
+  uint32_t b0, b1, c0, c1;
+  tile_bounds(op, tile, &b0, &b1, &c0, &c1);
+  const uint32_t d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, grp = nq / nkv;
+  out.clear();
+  switch (op.kind) {
+    case MPK_OP_EMBED:
+      break;
+    case MPK_OP_RMSNORM:
+      out.push_back({op.in_tensor, b0, b1, 0, op.K});
+      break;
+    case MPK_OP_LINEAR:
+    case MPK_OP_GATEUP:
+      out.push_back({op.in_tensor, b0, b1, 0, UINT32_MAX});   // whole input rows
+      if (op.flags & TF_EPI_RESID) out.push_back({op.in2_tensor, b0, b1, c0, c1});
+      break;
+    case MPK_OP_ROPE:
+      out.push_back({op.in_tensor, b0, b1, c0, c1});   // whole heads: partners included
+      break;
+    case MPK_OP_ATTN_PARTIAL: {
+      uint32_t per = grp * (d + 2), C = op.p1;
+      for (uint32_t u = c0 / per; u < c1 / per; ++u) {
+        uint32_t gidx = u / C, ch = u % C;
+        out.push_back({op.in_tensor, b0, b1, gidx * grp * d, (gidx + 1) * grp * d});
+        if (ch == C - 1) {
+          out.push_back({op.in_tensor, b0, b1, (nq + gidx) * d, (nq + gidx + 1) * d});
+          out.push_back({op.in_tensor, b0, b1, (nq + nkv + gidx) * d, (nq + nkv + gidx + 1) * d});
+        }
+      }
+      break;
+    }
+    case MPK_OP_ATTN_MERGE: {
+      uint32_t C = op.p1;
+      for (uint32_t h = c0 / d; h < c1 / d; ++h) {
+        uint32_t gidx = h / grp, j = h % grp;
+        for (uint32_t ch = 0; ch < C; ++ch) {
+          uint32_t base = ((gidx * C + ch) * grp + j) * (d + 2);
+          out.push_back({op.in_tensor, b0, b1, base, base + d + 2});
+        }
+      }
+      break;
+    }
+    case MPK_OP_ADD:
+      out.push_back({op.in_tensor, b0, b1, c0, c1});
+      out.push_back({op.in2_tensor, b0, b1, c0, c1});
+      break;
+    case MPK_OP_SWIGLU:
+      out.push_back({op.in_tensor, b0, b1, c0, c1});
+      out.push_back({op.in_tensor, b0, b1, op.p0 + c0, op.p0 + c1});
+      break;
+  }
+}
+
+static void dependency_analysis(const mpk_model_config& c, HostGraph& g, PassInput& pi) {
+  std::vector<int> producer_op(g.tensors.size(), -1);
+  for (size_t i = 0; i < g.ops.size(); ++i) producer_op[g.ops[i].out_tensor] = (int)i;
+  uint32_t n = 0;
+  for (auto& op : g.ops) n += op.tb * op.tc;
+  pi.n_real = n;
+  pi.prod.assign(n, {});
+  pi.op_of.resize(n);
+  pi.tile_of_task.resize(n);
+  std::vector<Rect> rects;
+  for (size_t oi = 0; oi < g.ops.size(); ++oi) {
+    const HostOp& op = g.ops[oi];
+    for (uint32_t tile = 0; tile < op.tb * op.tc; ++tile) {
+      uint32_t t = op.task_base + tile;
+      pi.op_of[t] = (uint32_t)oi;
+      pi.tile_of_task[t] = tile;
+      input_rects(c, op, tile, rects);
+      auto& P = pi.prod[t];
+      for (const Rect& r : rects) {
+        int po = producer_op[r.tensor];
+        if (po < 0) continue;
+        const HostOp& p = g.ops[po];
+        uint32_t c1 = std::min(r.c1, p.cols);
+        if (r.b0 >= r.b1 || r.c0 >= c1) continue;
+        uint32_t nu = p.cols / p.unit;
+        uint32_t ib0 = tile_of(p.rows, p.tb, r.b0), ib1 = tile_of(p.rows, p.tb, r.b1 - 1);
+        uint32_t ic0 = tile_of(nu, p.tc, r.c0 / p.unit), ic1 = tile_of(nu, p.tc, (c1 - 1) / p.unit);
+        for (uint32_t ib = ib0; ib <= ib1; ++ib)
+          for (uint32_t ic = ic0; ic <= ic1; ++ic) P.push_back(p.task_base + ib * p.tc + ic);
+      }
+      sort_unique(P);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ K7 labels (operator level)
+// Attention has a data-dependent duration -> JIT.  A downstream operator stays JIT unless each of
+// its tasks waits for ALL tasks of every JIT operator it reads from (a global barrier with
+// respect to the accumulated imbalance, Section 5.2).
+static void label_ops(HostGraph& g, const PassInput& pi, std::vector<uint32_t>& op_jit) {
+  op_jit.assign(g.ops.size(), 0);
+  for (size_t oi = 0; oi < g.ops.size(); ++oi) {
+    const HostOp& op = g.ops[oi];
+    if (op.kind == MPK_OP_ATTN_PARTIAL) { op_jit[oi] = 1; continue; }
+    bool jit = false;
+    for (uint32_t tile = 0; tile < op.tb * op.tc && !jit; ++tile) {
+      const auto& P = pi.prod[op.task_base + tile];
+      std::map<uint32_t, uint32_t> per_op;
+      for (uint32_t p : P) per_op[pi.op_of[p]]++;
+      for (auto& kv : per_op)
+        if (op_jit[kv.first] && kv.second != g.ops[kv.first].tb * g.ops[kv.first].tc) jit = true;
+    }
+    op_jit[oi] = jit ? 1u : 0u;
+  }
+  for (size_t oi = 0; oi < g.ops.size(); ++oi) g.ops[oi].jit = op_jit[oi];
+}
+
+// ------------------------------------------------------------------ task descriptors
+static const float* act_ref(const HostGraph& g, int tensor) {
+  if (tensor < 0) return nullptr;
+  size_t off = g.tensors[tensor].offset;
+  if (off == SIZE_MAX) return nullptr;
+  return (const float*)(uintptr_t)((off + 1) * sizeof(float));   // relocated by the runtime
+}
+
+static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGraph& g) {
+  g.descs.assign(g.tasks.size(), TaskDesc{});
+  const size_t kv_layer = (size_t)c.batch * c.n_kv_heads * c.max_seq * c.head_dim;   // elements
+  for (size_t i = 0; i < g.tasks.size(); ++i) {
+    const HostTask& ht = g.tasks[i];
+    TaskDesc& t = g.descs[i];
+    t.dep_event = ht.dep_event;
+    t.trig_event = ht.trig_event;
+    if (ht.op == MPK_TASK_DUMMY_OP) { t.kind = TK_DUMMY; continue; }
+    const HostOp& op = g.ops[ht.op];
+    tile_bounds(op, ht.tile, &t.b0, &t.b1, &t.c0, &t.c1);
+    t.flags = op.flags;
+    t.K = op.K;
+    t.w = op.w; t.w2 = op.w2; t.f0 = op.f0; t.f1 = op.f1;
+    t.p0 = op.p0; t.p1 = op.p1; t.p2 = op.p2; t.p3 = op.p3;
+    t.in = act_ref(g, op.in_tensor);
+    t.in2 = act_ref(g, op.in2_tensor);
+    t.out = const_cast<float*>(act_ref(g, op.out_tensor));
+    t.ld_in = op.in_tensor >= 0 ? g.tensors[op.in_tensor].cols : 0;
+    t.ld_out = op.cols;
+    switch (op.kind) {
+      case MPK_OP_EMBED: t.kind = TK_EMBED; break;
+      case MPK_OP_RMSNORM: t.kind = TK_RMSNORM; break;
+      case MPK_OP_LINEAR:
+      case MPK_OP_GATEUP: t.kind = TK_LINEAR; break;
+      case MPK_OP_ROPE: t.kind = TK_ROPE; break;
+      case MPK_OP_ATTN_PARTIAL: t.kind = TK_ATTN_PARTIAL; break;
+      case MPK_OP_ATTN_MERGE: t.kind = TK_ATTN_MERGE; break;
+      case MPK_OP_ADD: t.kind = TK_ADD; break;
+      case MPK_OP_SWIGLU: t.kind = TK_SWIGLU; break;
+    }
+    if (op.kind == MPK_OP_ROPE || op.kind == MPK_OP_ATTN_PARTIAL) {
+      if (kv && kv->k && kv->v) {
+        t.aux0 = (uint16_t*)kv->k + (size_t)op.p0 * kv_layer;
+        t.aux1 = (uint16_t*)kv->v + (size_t)op.p0 * kv_layer;
+      }
+    }
+  }
+}
+
+static uint32_t lds_requirement(const mpk_model_config& c, const HostGraph& g, uint32_t C) {
+  size_t need = 0;
+  const uint32_t grp = c.n_q_heads / c.n_kv_heads;
+  for (auto& op : g.ops) {
+    size_t f = 0;
+    if (op.kind == MPK_OP_LINEAR || op.kind == MPK_OP_GATEUP) {
+      uint32_t nb = c.batch <= 2 ? c.batch : (c.batch <= 4 ? 4u : 8u);   // body template sizes
+      f = (size_t)nb * op.K;
+    }
+    else if (op.kind == MPK_OP_RMSNORM) f = 0;
+    else if (op.kind == MPK_OP_ATTN_PARTIAL)
+      f = (size_t)grp * c.head_dim                                   // q
+          + (size_t)grp * ((c.max_seq + C - 1) / C + 1)              // scores of one chunk
+          + (size_t)(kThreads / 64) * grp * c.head_dim;              // per-wave partial outputs
+    need = std::max(need, f);
+  }
+  size_t bytes = (need + kLdsReduceFloats) * sizeof(float);
+  return (uint32_t)std::max<size_t>(bytes, kMinLdsBytes);
+}
+
+static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
+                           const mpk_kv_ptrs* kv, const mpk_compile_options& o) {
+  if (c.struct_size != sizeof(mpk_model_config)) { set_error("mpk_model_config.struct_size is %u, expected %zu", c.struct_size, sizeof(mpk_model_config)); return MPK_ERR_INVALID_ARG; }
+  if (!c.n_layers || !c.hidden || !c.n_q_heads || !c.n_kv_heads || !c.head_dim || !c.vocab || !c.batch || !c.max_seq) { set_error("a model dimension is zero"); return MPK_ERR_INVALID_ARG; }
+  if (c.flags) { set_error("mpk_model_config.flags must be 0"); return MPK_ERR_INVALID_ARG; }
+  if (c.n_experts || c.top_k || c.expert_ffn) { set_error("mixture-of-experts layers are not supported yet"); return MPK_ERR_UNSUPPORTED; }
+  if (!c.ffn) { set_error("ffn is zero"); return MPK_ERR_INVALID_ARG; }
+  if (c.head_dim != 64 && c.head_dim != 128) { set_error("head_dim %u unsupported (64 or 128)", c.head_dim); return MPK_ERR_UNSUPPORTED; }
+  if (c.n_q_heads % c.n_kv_heads) { set_error("n_q_heads must be a multiple of n_kv_heads"); return MPK_ERR_UNSUPPORTED; }
+  if (c.n_q_heads / c.n_kv_heads > 8) { set_error("more than 8 query heads per KV head unsupported"); return MPK_ERR_UNSUPPORTED; }
+  if (c.hidden % 8 || c.ffn % 8 || (c.n_q_heads * c.head_dim) % 8) { set_error("hidden, ffn and n_q*head_dim must be multiples of 8"); return MPK_ERR_UNSUPPORTED; }
+  if (c.batch > 8) { set_error("batch %u unsupported by the dense linear bodies (max 8)", c.batch); return MPK_ERR_UNSUPPORTED; }
+  if (o.debug_flags) { set_error("debug_flags must be 0"); return MPK_ERR_INVALID_ARG; }
+  if (o.fusion & ~(MPK_FUSE_NORM | MPK_FUSE_RESID | MPK_FUSE_SWIGLU | MPK_FUSE_MERGE | MPK_FUSE_ROPE)) { set_error("unknown fusion bits"); return MPK_ERR_INVALID_ARG; }
+  if (o.fusion & (MPK_FUSE_MERGE | MPK_FUSE_ROPE)) { set_error("MPK_FUSE_MERGE / MPK_FUSE_ROPE are not implemented yet"); return MPK_ERR_UNSUPPORTED; }
+  if (!o.host_only) {
+    if (!w || !kv || !w->layers) { set_error("weights / kv pointers are NULL"); return MPK_ERR_INVALID_ARG; }
+    auto bad = [](const void* p) { return p == nullptr || ((uintptr_t)p & 15u); };
+    if (bad(w->embed) || bad(w->final_norm) || bad(w->lm_head) || bad(kv->k) || bad(kv->v)) { set_error("a model-level pointer is NULL or not 16-byte aligned"); return MPK_ERR_INVALID_ARG; }
+    for (uint32_t l = 0; l < c.n_layers; ++l) {
+      const mpk_layer_weights& lw = w->layers[l];
+      if (bad(lw.attn_norm) || bad(lw.wqkv) || bad(lw.wo) || bad(lw.mlp_norm) || bad(lw.wgu) || bad(lw.wd)) { set_error("layer %u: a weight pointer is NULL or not 16-byte aligned", l); return MPK_ERR_INVALID_ARG; }
+    }
+  }
+  return MPK_OK;
+}
+
+mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs* w,
+                             const mpk_kv_ptrs* kv, const mpk_compile_options& opt_in,
+                             HostGraph& g) {
+  mpk_compile_options opt = opt_in;
+  mpk_status st = validate(cfg, w, kv, opt);
+  if (st != MPK_OK) return st;
+  if (opt.n_workers == 0) { set_error("n_workers unresolved"); return MPK_ERR_INTERNAL; }
+  uint32_t C = opt.attn_chunks;
+  if (C == 0) {
+    C = std::max(1u, opt.n_workers / (cfg.batch * cfg.n_kv_heads));
+    C = std::min(C, std::max(1u, cfg.max_seq / 32));
+    C = std::min(C, 64u);
+  }
+  if (C > 64) { set_error("attn_chunks %u too large (max 64)", C); return MPK_ERR_INVALID_ARG; }
+  opt.attn_chunks = C;
+  g.cfg = cfg;
+  g.opt = opt;
+  st = build_ops(cfg, w, opt, C, g);
+  if (st != MPK_OK) return st;
+  choose_partitions(cfg, opt, g);
+  PassInput pi;
+  dependency_analysis(cfg, g, pi);
+  label_ops(g, pi, pi.op_jit);   // labels follow the paper's rule on the full dependency sets
+  if (opt.transitive_reduction) g.stats.n_pairs_removed = transitive_reduction(pi, g.ops);
+  // count pairs before reduction for the statistics
+  st = run_passes(pi, opt, g);
+  if (st != MPK_OK) return st;
+  g.stats.n_pair_deps += g.stats.n_pairs_removed;
+  build_descs(cfg, kv, g);
+  g.lds_bytes = lds_requirement(cfg, g, C);
+  if (g.lds_bytes > 160 * 1024 && !opt.host_only) { set_error("task bodies need %u bytes of LDS (> 160 KB): batch x input length too large", g.lds_bytes); return MPK_ERR_UNSUPPORTED; }
+  // statistics
+  g.stats.struct_size = sizeof(mpk_stats);
+  g.stats.n_ops = (uint32_t)g.ops.size();
+  g.stats.lds_bytes = g.lds_bytes;
+  g.stats.act_bytes = g.arena_floats * sizeof(float);
+  uint64_t wb = (uint64_t)cfg.batch * cfg.hidden * 2 + (uint64_t)cfg.hidden * 2 +
+                (uint64_t)cfg.vocab * cfg.hidden * 2;
+  uint64_t qkv_rows = (uint64_t)(cfg.n_q_heads + 2 * cfg.n_kv_heads) * cfg.head_dim;
+  wb += (uint64_t)cfg.n_layers * 2 * (2ull * cfg.hidden + qkv_rows * cfg.hidden +
+                                      (uint64_t)cfg.hidden * cfg.n_q_heads * cfg.head_dim +
+                                      3ull * cfg.ffn * cfg.hidden);
+  g.stats.weight_bytes = wb;
+  g.stats.kv_row_bytes = (uint64_t)cfg.n_layers * 2 * cfg.n_kv_heads * cfg.head_dim * 2;
+  return MPK_OK;
+}
+
+mpk_status build_dag_graph(uint32_t n_tasks, const uint32_t* pairs, size_t n_pairs,
+                           const mpk_compile_options& opt, HostGraph& g) {
+  if (n_tasks == 0 || (!pairs && n_pairs)) { set_error("empty DAG"); return MPK_ERR_INVALID_ARG; }
+  if (opt.n_workers == 0) { set_error("n_workers unresolved"); return MPK_ERR_INTERNAL; }
+  PassInput pi;
+  pi.n_real = n_tasks;
+  pi.prod.assign(n_tasks, {});
+  pi.op_of.assign(n_tasks, 0);
+  pi.tile_of_task.resize(n_tasks);
+  std::iota(pi.tile_of_task.begin(), pi.tile_of_task.end(), 0u);
+  for (size_t i = 0; i < n_pairs; ++i) {
+    uint32_t a = pairs[2 * i], b = pairs[2 * i + 1];
+    if (a >= n_tasks || b >= n_tasks || a == b) { set_error("pair %zu (%u -> %u) out of range", i, a, b); return MPK_ERR_INVALID_ARG; }
+    pi.prod[b].push_back(a);
+  }
+  for (auto& P : pi.prod) sort_unique(P);
+  g.opt = opt;
+  HostOp op{};
+  op.kind = MPK_OP_ADD; op.layer = -1; op.name = "dag"; op.tb = 1; op.tc = n_tasks;
+  op.rows = 1; op.cols = n_tasks; op.unit = 1; op.in_tensor = op.in2_tensor = op.out_tensor = -1;
+  g.ops.push_back(op);
+  mpk_status st = run_passes(pi, opt, g);
+  if (st != MPK_OK) return st;
+  g.stats.struct_size = sizeof(mpk_stats);
+  g.stats.n_ops = 1;
+  return MPK_OK;
+}
+
+// ------------------------------------------------------------------ export
+size_t export_size(const HostGraph& g) {
+  return sizeof(mpk_export_header) + g.ops.size() * sizeof(mpk_export_op) +
+         g.tasks.size() * sizeof(mpk_export_task) + g.events.size() * sizeof(mpk_export_event) +
+         (g.aot_off.size() + g.aot.size()) * sizeof(uint32_t);
+}
+
+void export_graph(const HostGraph& g, void* buf) {
+  char* p = (char*)buf;
+  mpk_export_header h{};
+  h.magic = MPK_EXPORT_MAGIC; h.version = 1;
+  h.n_ops = (uint32_t)g.ops.size(); h.n_tasks = (uint32_t)g.tasks.size();
+  h.n_events = (uint32_t)g.events.size(); h.n_workers = g.opt.n_workers;
+  h.n_sched_wgs = g.opt.n_sched_wgs; h.start_event = g.start_event;
+  h.terminal_event = g.terminal_event; h.n_real_tasks = g.n_real; h.fusion = g.opt.fusion;
+  memcpy(p, &h, sizeof(h)); p += sizeof(h);
+  for (auto& op : g.ops) {
+    mpk_export_op e{op.kind, op.layer, op.tb, op.tc, op.tb * op.tc, op.jit, op.rows, op.cols};
+    memcpy(p, &e, sizeof(e)); p += sizeof(e);
+  }
+  for (auto& t : g.tasks) {
+    mpk_export_task e{t.op, t.tile, t.dep_event, t.trig_event, t.worker, t.jit};
+    memcpy(p, &e, sizeof(e)); p += sizeof(e);
+  }
+  for (auto& ev : g.events) {
+    mpk_export_event e{ev.required, ev.first, ev.last, ev.flags};
+    memcpy(p, &e, sizeof(e)); p += sizeof(e);
+  }
+  memcpy(p, g.aot_off.data(), g.aot_off.size() * 4); p += g.aot_off.size() * 4;
+  memcpy(p, g.aot.data(), g.aot.size() * 4);
+}
+
+}  // namespace mpk

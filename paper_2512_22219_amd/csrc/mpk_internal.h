@@ -1,0 +1,124 @@
+// Internal structures shared by the host compiler (compiler.cpp) and the HIP runtime
+// (runtime.hip).  Nothing here is part of the public ABI.
+#pragma once
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "mpk.h"
+
+namespace mpk {
+
+// ---------------------------------------------------------------- device task descriptor
+// One fixed-size record per task (paper Section 4.1, "tGraph normalization": after
+// normalization a descriptor stores exactly one dependent and one triggering event id, plus
+// tensors and configuration).  128 bytes; immutable after compile, so workers may fetch it
+// through the scalar cache.
+enum TaskKind : uint16_t {
+  TK_DUMMY = 0,
+  TK_EMBED,
+  TK_RMSNORM,
+  TK_LINEAR,
+  TK_ROPE,
+  TK_ATTN_PARTIAL,
+  TK_ATTN_MERGE,
+  TK_ADD,
+  TK_SWIGLU,
+};
+
+enum TaskFlags : uint16_t {
+  TF_PRO_NORM = 1,    // linear: RMSNorm the input row first (gain = w2, eps = f0)
+  TF_PRO_MERGE = 2,   // linear: input is the split-KV partial buffer, merge while loading
+  TF_EPI_RESID = 4,   // linear: out = in2 + W x
+  TF_GATEUP = 8,      // linear: out_c = silu(W[c] x) * (W[F + c] x), F = p0
+  TF_OUT_LOGITS = 16, // output pointer is the caller's logits buffer of this step
+  TF_ROPE_FUSED = 32, // attention: rotate q (and the new k) itself, append k/v itself
+};
+
+struct alignas(16) TaskDesc {
+  uint16_t kind, flags;
+  int32_t dep_event, trig_event;
+  uint32_t b0, b1;   // batch rows [b0, b1)
+  uint32_t c0, c1;   // output columns [c0, c1)
+  uint32_t K;        // input length (linear / norm), or kind specific
+  uint32_t ld_in, ld_out;
+  uint32_t p0, p1, p2, p3;  // kind specific
+  float f0, f1;             // eps / theta
+  const void* w;            // weights (bf16)
+  const void* w2;           // gain (bf16)
+  const float* in;
+  const float* in2;
+  float* out;
+  void* aux0;               // K cache of the layer
+  void* aux1;               // V cache of the layer
+  uint64_t pad;
+};
+static_assert(sizeof(TaskDesc) == 128, "TaskDesc must stay 128 bytes");
+
+struct EventDesc {   // paper Section 4.1 "tGraph linearization" / Fig. 4(f)
+  uint32_t required, first, last, flags;
+};
+
+// ---------------------------------------------------------------- host-side graph
+struct HostOp {
+  uint32_t kind;     // MPK_OP_*
+  int32_t layer;
+  std::string name;
+  uint32_t rows, cols, unit;   // output tensor [rows][cols]; columns tile in multiples of unit
+  uint32_t tb, tc;
+  uint32_t task_base;          // canonical id of tile 0
+  uint32_t jit;
+  // tensors
+  int out_tensor;
+  int in_tensor, in2_tensor;   // -1 if none
+  // parameters
+  uint32_t K;
+  uint16_t flags;
+  const void *w, *w2;
+  float f0, f1;
+  uint32_t p0, p1, p2, p3;
+};
+
+struct HostTask {   // linearized order
+  uint32_t op;      // MPK_TASK_DUMMY_OP for dummies
+  uint32_t tile;
+  int32_t dep_event, trig_event;
+  int32_t worker;
+  uint32_t jit;
+};
+
+struct HostTensor {
+  uint32_t rows, cols;
+  size_t offset;   // float offset into the activation arena; SIZE_MAX = external (logits)
+};
+
+struct HostGraph {
+  mpk_model_config cfg{};
+  mpk_compile_options opt{};
+  std::vector<HostOp> ops;
+  std::vector<HostTensor> tensors;
+  std::vector<HostTask> tasks;
+  std::vector<EventDesc> events;
+  std::vector<uint32_t> aot_off, aot;
+  std::vector<TaskDesc> descs;   // parallel to tasks; activation pointers hold arena offsets
+                                 // until the runtime relocates them
+  uint32_t n_real = 0, start_event = 0, terminal_event = 0;
+  size_t arena_floats = 0;
+  uint32_t lds_bytes = 0;
+  mpk_stats stats{};
+};
+
+void set_error(const char* fmt, ...);
+
+// compiler.cpp
+mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs* w,
+                             const mpk_kv_ptrs* kv, const mpk_compile_options& opt, HostGraph& g);
+mpk_status build_dag_graph(uint32_t n_tasks, const uint32_t* pairs, size_t n_pairs,
+                           const mpk_compile_options& opt, HostGraph& g);
+
+// LDS layout constants shared with the kernels
+constexpr uint32_t kThreads = 512;        // worker workgroup size (8 wavefronts)
+constexpr uint32_t kLdsReduceFloats = 1024;  // scratch for cross-wave reductions
+constexpr uint32_t kMinLdsBytes = 84 * 1024; // > half of 160 KB: at most one worker per CU
+
+}  // namespace mpk

@@ -1,0 +1,782 @@
+// In-kernel runtime and task bodies for gfx950 (paper Section 5), plus the C ABI entry points.
+//
+// One persistent kernel: worker workgroups (one per CU, 512 threads = 8 wavefronts) walk their
+// pre-enqueued (ahead-of-time) task list; before a task they wait until its dependent event's
+// counter has reached epoch * required, after it they publish their stores and add one to the
+// triggering event's counter.  Event counters only ever grow (no reset between steps).
+//
+// Memory ordering (the GPU has 8 XCDs with private L2s): producer side = every wavefront issues
+// an agent-scope release fence after its stores, workgroup barrier, then one lane does the
+// relaxed agent-scope atomic add.  Consumer side = one lane polls with relaxed agent-scope
+// atomic loads, workgroup barrier, then every wavefront issues an agent-scope acquire fence
+// before touching activations.  Weights never depend on an event.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "mpk_internal.h"
+
+namespace mpk {
+const char* last_error();
+size_t export_size(const HostGraph& g);
+void export_graph(const HostGraph& g, void* buf);
+
+struct StepArgs {
+  const TaskDesc* tasks;
+  const EventDesc* events;
+  uint32_t* counters;
+  const uint32_t* aot_off;
+  const uint32_t* aot;
+  const uint32_t* op_list;   // per-operator launch: task indices grouped by operator
+  const int32_t* token_ids;
+  const int32_t* positions;
+  float* logits;
+  uint32_t* err;   // [0] error code, [1] abort flag, [2..3] detail
+  uint64_t timeout_ticks;
+  uint32_t epoch, n_workers;
+  uint32_t vocab, max_seq, n_q, n_kv, head_dim, batch;
+};
+
+enum DevErr : uint32_t { DE_NONE = 0, DE_TIMEOUT = 1, DE_BAD_POSITION = 2, DE_BAD_TOKEN = 3 };
+
+// ------------------------------------------------------------------------------ device helpers
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// fp32 -> bf16, round to nearest even; NaN stays a quiet NaN.
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+// Sum over the whole workgroup; every thread gets the result.  red: >= 16 floats of LDS.
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  __syncthreads();
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < (int)(kThreads / 64); ++i) s += red[i];
+  return s;
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float dot8(const u32x4& w, const float4& x0, const float4& x1, float acc) {
+  acc = fmaf(bf16_lo(w.x), x0.x, acc);
+  acc = fmaf(bf16_hi(w.x), x0.y, acc);
+  acc = fmaf(bf16_lo(w.y), x0.z, acc);
+  acc = fmaf(bf16_hi(w.y), x0.w, acc);
+  acc = fmaf(bf16_lo(w.z), x1.x, acc);
+  acc = fmaf(bf16_hi(w.z), x1.y, acc);
+  acc = fmaf(bf16_lo(w.w), x1.z, acc);
+  acc = fmaf(bf16_hi(w.w), x1.w, acc);
+  return acc;
+}
+
+__device__ __forceinline__ void report(const StepArgs& a, uint32_t code, uint32_t d0, uint32_t d1) {
+  if (atomicCAS(&a.err[0], 0u, code) == 0u) {
+    a.err[2] = d0;
+    a.err[3] = d1;
+  }
+}
+
+// ------------------------------------------------------------------------------ task bodies
+// T0: x[b] = E[token[b]] widened to fp32.
+__device__ void body_embed(const TaskDesc& t, const StepArgs& a) {
+  for (uint32_t b = t.b0; b < t.b1; ++b) {
+    int32_t tok = a.token_ids[b];
+    if (tok < 0 || (uint32_t)tok >= a.vocab) {
+      if (threadIdx.x == 0) report(a, DE_BAD_TOKEN, b, (uint32_t)tok);
+      tok = 0;
+    }
+    const uint16_t* row = (const uint16_t*)t.w + (size_t)tok * t.K;
+    float* out = t.out + (size_t)b * t.ld_out;
+    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) out[i] = bf16_to_f32(row[i]);
+  }
+}
+
+// T1/T8/T13: y = x * (1 / sqrt(mean(x^2) + eps)) * g, one batch row per task.
+__device__ void body_rmsnorm(const TaskDesc& t, float* lds) {
+  const uint16_t* g = (const uint16_t*)t.w2;
+  for (uint32_t b = t.b0; b < t.b1; ++b) {
+    const float* x = t.in + (size_t)b * t.ld_in;
+    float* y = t.out + (size_t)b * t.ld_out;
+    float ss = 0.f;
+    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) ss = fmaf(x[i], x[i], ss);
+    ss = block_sum(ss, lds);
+    float inv = 1.0f / sqrtf(ss / (float)t.K + t.f0);
+    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) y[i] = x[i] * inv * bf16_to_f32(g[i]);
+  }
+}
+
+// T2/T6/T9/T11/T14: y[b][c] = sum_j W[c][j] x[b][j] for output columns [c0, c1), all batch rows
+// at once.  The input rows are staged in LDS (fp32); every wavefront owns groups of RW weight
+// rows and streams them with 16-byte loads, 64 lanes x 8 bf16 = 512 input elements per step.
+// Optional stages: RMSNorm of the input (TF_PRO_NORM), residual add (TF_EPI_RESID), fused
+// silu(gate) * up (TF_GATEUP: column c needs weight rows c and F + c).
+template <int NB, int RW>
+__device__ void body_linear(const TaskDesc& t, const StepArgs& a, float* lds) {
+  const uint32_t K = t.K, nb = t.b1 - t.b0;
+  float* xs = lds;                 // [NB][K]
+  float* red = lds + (size_t)NB * K;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // ---- stage the input rows
+  for (uint32_t b = 0; b < NB; ++b) {
+    if (b < nb) {
+      const float4* src = (const float4*)(t.in + (size_t)(t.b0 + b) * t.ld_in);
+      float4* dst = (float4*)(xs + (size_t)b * K);
+      for (uint32_t i = threadIdx.x; i < K / 4; i += kThreads) dst[i] = src[i];
+    } else {
+      float4* dst = (float4*)(xs + (size_t)b * K);
+      for (uint32_t i = threadIdx.x; i < K / 4; i += kThreads) dst[i] = make_float4(0, 0, 0, 0);
+    }
+  }
+  __syncthreads();
+  if (t.flags & TF_PRO_NORM) {
+    const uint16_t* g = (const uint16_t*)t.w2;
+    for (uint32_t b = 0; b < nb; ++b) {
+      float* x = xs + (size_t)b * K;
+      float ss = 0.f;
+      for (uint32_t i = threadIdx.x; i < K; i += kThreads) ss = fmaf(x[i], x[i], ss);
+      ss = block_sum(ss, red);
+      float inv = 1.0f / sqrtf(ss / (float)K + t.f0);
+      for (uint32_t i = threadIdx.x; i < K; i += kThreads) x[i] = x[i] * inv * bf16_to_f32(g[i]);
+    }
+    __syncthreads();
+  }
+  // ---- stream the weight rows
+  const bool gateup = t.flags & TF_GATEUP;
+  const uint32_t ncols = t.c1 - t.c0;
+  const uint32_t G = gateup ? RW / 2 : RW;          // output columns per group
+  const uint32_t ngroups = (ncols + G - 1) / G;
+  const uint16_t* W = (const uint16_t*)t.w;
+  float* outp = (t.flags & TF_OUT_LOGITS) ? a.logits : t.out;
+  for (uint32_t grp = wave; grp < ngroups; grp += kThreads / 64) {
+    const uint16_t* wp[RW];
+    uint32_t col[RW];
+#pragma unroll
+    for (int i = 0; i < RW; ++i) {
+      uint32_t c = t.c0 + grp * G + (gateup ? (i >> 1) : i);
+      col[i] = c;
+      uint32_t cc = c < t.c1 ? c : t.c1 - 1;   // clamp: masked rows re-read a valid row
+      uint32_t row = gateup ? ((i & 1) ? t.p0 + cc : cc) : cc;
+      wp[i] = W + (size_t)row * K;
+    }
+    float acc[RW][NB];
+#pragma unroll
+    for (int i = 0; i < RW; ++i)
+#pragma unroll
+      for (int b = 0; b < NB; ++b) acc[i][b] = 0.f;
+#pragma unroll 2
+    for (uint32_t k = lane * 8; k < K; k += 512) {
+      u32x4 wv[RW];
+#pragma unroll
+      for (int i = 0; i < RW; ++i) wv[i] = __builtin_nontemporal_load((const u32x4*)(wp[i] + k));
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        const float4* xp = (const float4*)(xs + (size_t)b * K + k);
+        float4 x0 = xp[0], x1 = xp[1];
+#pragma unroll
+        for (int i = 0; i < RW; ++i) acc[i][b] = dot8(wv[i], x0, x1, acc[i][b]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < RW; ++i)
+#pragma unroll
+      for (int b = 0; b < NB; ++b) acc[i][b] = wave_sum(acc[i][b]);
+    if (lane == 0) {
+      if (gateup) {
+#pragma unroll
+        for (int i = 0; i < RW; i += 2) {
+          if (col[i] < t.c1) {
+            for (uint32_t b = 0; b < nb; ++b) {
+              float gte = acc[i][b], up = acc[i + 1][b];
+              outp[(size_t)(t.b0 + b) * t.ld_out + col[i]] = gte / (1.0f + expf(-gte)) * up;
+            }
+          }
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < RW; ++i) {
+          if (col[i] < t.c1) {
+            for (uint32_t b = 0; b < nb; ++b) {
+              float v = acc[i][b];
+              size_t o = (size_t)(t.b0 + b) * t.ld_out + col[i];
+              if (t.flags & TF_EPI_RESID) v = t.in2[o] + v;
+              outp[o] = v;
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// T3: rotate q and k heads by the sequence position (half-split pairing), copy v, and append the
+// new k and v rows to the cache as bf16.  Angles are evaluated in double precision.
+__device__ void body_rope(const TaskDesc& t, const StepArgs& a) {
+  const uint32_t d = a.head_dim, half = d / 2, nq = a.n_q, nkv = a.n_kv;
+  const uint32_t s0 = t.c0 / d, s1 = t.c1 / d;
+  for (uint32_t b = t.b0; b < t.b1; ++b) {
+    int32_t pos = a.positions[b];
+    if (pos < 0 || (uint32_t)pos >= a.max_seq) {
+      if (threadIdx.x == 0) report(a, DE_BAD_POSITION, b, (uint32_t)pos);
+      continue;
+    }
+    const float* src = t.in + (size_t)b * t.ld_in;
+    float* dst = t.out + (size_t)b * t.ld_out;
+    for (uint32_t idx = threadIdx.x; idx < (s1 - s0) * half; idx += kThreads) {
+      uint32_t s = s0 + idx / half, i = idx % half;
+      float u0 = src[s * d + i], u1 = src[s * d + i + half];
+      float r0, r1;
+      if (s < nq + nkv) {
+        double f = pow((double)t.f1, -2.0 * (double)i / (double)d);
+        double ang = (double)pos * f;
+        float c = (float)cos(ang), sn = (float)sin(ang);
+        r0 = u0 * c - u1 * sn;
+        r1 = u1 * c + u0 * sn;
+      } else {
+        r0 = u0;
+        r1 = u1;
+      }
+      dst[s * d + i] = r0;
+      dst[s * d + i + half] = r1;
+      if (s >= nq) {
+        bool is_k = s < nq + nkv;
+        uint32_t g = is_k ? s - nq : s - nq - nkv;
+        uint16_t* cache = (uint16_t*)(is_k ? t.aux0 : t.aux1);
+        uint16_t* row = cache + (((size_t)b * nkv + g) * a.max_seq + (uint32_t)pos) * d;
+        row[i] = f32_to_bf16(r0);
+        row[i + half] = f32_to_bf16(r1);
+      }
+    }
+  }
+}
+
+// T4: split-KV decode attention for one (sequence, KV head, chunk).  Chunk c of C covers cache
+// rows [c*len/C, (c+1)*len/C) with len = position + 1, so the last chunk holds the new row.
+// Output per query head of the group: sum_t exp(s_t - m) V_t (d floats), m, l = sum_t exp(s_t - m).
+__device__ void body_attn_partial(const TaskDesc& t, const StepArgs& a, float* lds) {
+  const uint32_t d = a.head_dim, nq = a.n_q, nkv = a.n_kv, grp = nq / nkv;
+  const uint32_t per = grp * (d + 2), C = t.p1;
+  const uint32_t b = t.b0, u = t.c0 / per, g = u / C, c = u % C;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t nmax = (a.max_seq + C - 1) / C + 1;
+  float* qs = lds;                       // [grp][d]
+  float* sc = qs + grp * d;              // [grp][nmax]
+  float* wpart = sc + grp * nmax;        // [8][grp][d]
+  float* ml = wpart + (kThreads / 64) * grp * d;   // [grp][2]
+  float* outp = t.out + (size_t)b * t.ld_out + t.c0;
+  int32_t pos = a.positions[b];
+  if (pos < 0 || (uint32_t)pos >= a.max_seq) {
+    if (threadIdx.x == 0) report(a, DE_BAD_POSITION, b, (uint32_t)pos);
+    for (uint32_t i = threadIdx.x; i < per; i += kThreads) outp[i] = ((i % (d + 2)) == d) ? -INFINITY : 0.f;
+    return;
+  }
+  const uint32_t len = (uint32_t)pos + 1;
+  const uint32_t t0 = (uint32_t)((uint64_t)c * len / C), t1 = (uint32_t)((uint64_t)(c + 1) * len / C);
+  const uint32_t n = t1 - t0;
+  const float* qsrc = t.in + (size_t)b * t.ld_in + (size_t)g * grp * d;
+  for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) qs[i] = qsrc[i];
+  __syncthreads();
+  const uint16_t* Kb = (const uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.max_seq + t0) * d;
+  const uint16_t* Vb = (const uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.max_seq + t0) * d;
+  const uint32_t LPP = d / 8, PPW = 64 / LPP;   // lanes per position, positions per wavefront step
+  const uint32_t sub = lane % LPP, slot = lane / LPP;
+  const float inv_sqrt_d = 1.0f / sqrtf((float)d);
+  // ---- scores
+  for (uint32_t base = wave * PPW; base < n; base += (kThreads / 64) * PPW) {
+    uint32_t i = base + slot;
+    bool valid = i < n;
+    u32x4 kv = valid ? *(const u32x4*)(Kb + (size_t)i * d + sub * 8) : u32x4{0, 0, 0, 0};
+    for (uint32_t j = 0; j < grp; ++j) {
+      const float4* qp = (const float4*)(qs + j * d + sub * 8);
+      float s = dot8(kv, qp[0], qp[1], 0.f);
+      for (uint32_t off = 1; off < LPP; off <<= 1) s += __shfl_xor(s, off, 64);
+      if (valid && sub == 0) sc[j * nmax + i] = s * inv_sqrt_d;
+    }
+  }
+  __syncthreads();
+  // ---- softmax statistics of the chunk, one wavefront per query head
+  if ((uint32_t)wave < grp) {
+    float* s = sc + wave * nmax;
+    float m = -INFINITY;
+    for (uint32_t i = lane; i < n; i += 64) m = fmaxf(m, s[i]);
+    m = wave_max(m);
+    float l = 0.f;
+    for (uint32_t i = lane; i < n; i += 64) {
+      float p = expf(s[i] - m);
+      s[i] = p;
+      l += p;
+    }
+    l = wave_sum(l);
+    if (lane == 0) {
+      ml[wave * 2] = m;
+      ml[wave * 2 + 1] = l;
+    }
+  }
+  __syncthreads();
+  // ---- P.V
+  float acc[8][8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[j][e] = 0.f;
+  for (uint32_t base = wave * PPW; base < n; base += (kThreads / 64) * PPW) {
+    uint32_t i = base + slot;
+    if (i < n) {
+      u32x4 vv = *(const u32x4*)(Vb + (size_t)i * d + sub * 8);
+      float v[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
+                    bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if ((uint32_t)j < grp) {
+          float p = sc[j * nmax + i];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p, v[e], acc[j][e]);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    if ((uint32_t)j < grp) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float v = acc[j][e];
+        for (uint32_t off = LPP; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
+        if (slot == 0) wpart[((size_t)wave * grp + j) * d + sub * 8 + e] = v;
+      }
+    }
+  }
+  __syncthreads();
+  for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) {
+    uint32_t j = i / d, dim = i % d;
+    float s = 0.f;
+    for (uint32_t w = 0; w < kThreads / 64; ++w) s += wpart[((size_t)w * grp + j) * d + dim];
+    outp[j * (d + 2) + dim] = s;
+  }
+  if (threadIdx.x < grp) {
+    outp[threadIdx.x * (d + 2) + d] = ml[threadIdx.x * 2];
+    outp[threadIdx.x * (d + 2) + d + 1] = ml[threadIdx.x * 2 + 1];
+  }
+}
+
+// T5: merge the chunk partials of each query head with the log-sum-exp rule.
+__device__ void body_attn_merge(const TaskDesc& t, const StepArgs& a) {
+  const uint32_t d = a.head_dim, grp = a.n_q / a.n_kv, C = t.p1;
+  const uint32_t h0 = t.c0 / d, h1 = t.c1 / d;
+  for (uint32_t b = t.b0; b < t.b1; ++b) {
+    const float* part = t.in + (size_t)b * t.ld_in;
+    float* out = t.out + (size_t)b * t.ld_out;
+    for (uint32_t idx = threadIdx.x; idx < (h1 - h0) * d; idx += kThreads) {
+      uint32_t h = h0 + idx / d, dim = idx % d, g = h / grp, j = h % grp;
+      float M = -INFINITY;
+      for (uint32_t c = 0; c < C; ++c) M = fmaxf(M, part[((size_t)(g * C + c) * grp + j) * (d + 2) + d]);
+      float L = 0.f, o = 0.f;
+      for (uint32_t c = 0; c < C; ++c) {
+        const float* p = part + ((size_t)(g * C + c) * grp + j) * (d + 2);
+        float wgt = expf(p[d] - M);   // exp(-inf) = 0 for empty chunks
+        L = fmaf(wgt, p[d + 1], L);
+        o = fmaf(wgt, p[dim], o);
+      }
+      out[h * d + dim] = o / L;
+    }
+  }
+}
+
+__device__ void body_add(const TaskDesc& t) {
+  const uint32_t nc = t.c1 - t.c0;
+  for (uint32_t b = t.b0; b < t.b1; ++b)
+    for (uint32_t i = threadIdx.x; i < nc; i += kThreads) {
+      size_t o = (size_t)b * t.ld_out + t.c0 + i;
+      t.out[o] = t.in[o] + t.in2[o];
+    }
+}
+
+__device__ void body_swiglu(const TaskDesc& t) {
+  const uint32_t nc = t.c1 - t.c0, F = t.p0;
+  for (uint32_t b = t.b0; b < t.b1; ++b)
+    for (uint32_t i = threadIdx.x; i < nc; i += kThreads) {
+      const float* gu = t.in + (size_t)b * t.ld_in;
+      float gte = gu[t.c0 + i], up = gu[F + t.c0 + i];
+      t.out[(size_t)b * t.ld_out + t.c0 + i] = gte / (1.0f + expf(-gte)) * up;
+    }
+}
+
+__device__ void run_task(const TaskDesc& t, const StepArgs& a, float* lds) {
+  switch (t.kind) {
+    case TK_EMBED: body_embed(t, a); break;
+    case TK_RMSNORM: body_rmsnorm(t, lds); break;
+    case TK_LINEAR: {
+      uint32_t nb = t.b1 - t.b0;
+      if (nb == 1) body_linear<1, 4>(t, a, lds);
+      else if (nb == 2) body_linear<2, 4>(t, a, lds);
+      else if (nb <= 4) body_linear<4, 2>(t, a, lds);
+      else body_linear<8, 2>(t, a, lds);
+      break;
+    }
+    case TK_ROPE: body_rope(t, a); break;
+    case TK_ATTN_PARTIAL: body_attn_partial(t, a, lds); break;
+    case TK_ATTN_MERGE: body_attn_merge(t, a); break;
+    case TK_ADD: body_add(t); break;
+    case TK_SWIGLU: body_swiglu(t); break;
+    default: break;   // TK_DUMMY: no computation (normalization, Section 4.1)
+  }
+}
+
+// ------------------------------------------------------------------------------ runtime
+__device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Returns false when the step is being aborted (watchdog or a peer's failure).
+__device__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag) {
+  if (threadIdx.x == 0) {
+    const uint32_t target = a.epoch * a.events[e].required;
+    const uint32_t* cnt = a.counters + e;
+    uint32_t ok = 1;
+    if ((int32_t)(ld_relaxed(cnt) - target) < 0) {
+      const uint64_t t_start = wall_clock64();
+      uint32_t it = 0;
+      while ((int32_t)(ld_relaxed(cnt) - target) < 0) {
+        __builtin_amdgcn_s_sleep(1);
+        if ((++it & 127u) == 0) {
+          if (ld_relaxed(a.err + 1) != 0) { ok = 0; break; }
+          if (wall_clock64() - t_start > a.timeout_ticks) {
+            report(a, DE_TIMEOUT, (uint32_t)e, blockIdx.x);
+            __hip_atomic_store(a.err + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ok = 0;
+            break;
+          }
+        }
+      }
+    }
+    *s_flag = ok;
+  }
+  __syncthreads();
+  uint32_t ok = *s_flag;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  return ok != 0;
+}
+
+__device__ void signal_event(const StepArgs& a, int32_t e) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // every wavefront publishes its stores
+  __syncthreads();
+  if (threadIdx.x == 0)
+    __hip_atomic_fetch_add(a.counters + e, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+extern "C" __global__ void __launch_bounds__(kThreads)
+mpk_mega_kernel(StepArgs a) {
+  extern __shared__ __align__(16) float lds[];
+  __shared__ uint32_t s_flag;
+  const uint32_t w = blockIdx.x;
+  if (w >= a.n_workers) return;
+  const uint32_t q0 = a.aot_off[w], q1 = a.aot_off[w + 1];
+  for (uint32_t qi = q0; qi < q1; ++qi) {
+    const TaskDesc& t = a.tasks[a.aot[qi]];
+    if (t.dep_event >= 0 && a.events[t.dep_event].required != 0) {
+      if (!wait_event(a, t.dep_event, &s_flag)) break;
+    }
+    run_task(t, a, lds);
+    if (t.trig_event >= 0) signal_event(a, t.trig_event);
+    else __syncthreads();
+  }
+}
+
+// Kernel-per-operator baseline: the same task bodies, one launch per operator, dependencies
+// enforced by stream order (what the paper's comparison systems do, Section 6.5).
+extern "C" __global__ void __launch_bounds__(kThreads)
+mpk_op_kernel(StepArgs a, uint32_t first) {
+  extern __shared__ __align__(16) float lds[];
+  const TaskDesc& t = a.tasks[a.op_list[first + blockIdx.x]];
+  run_task(t, a, lds);
+}
+
+}  // namespace mpk
+
+// =============================================================================== host side
+using namespace mpk;
+
+struct mpk_graph {
+  HostGraph h;
+  bool host_only = true;
+  int device = -1;
+  // device allocations
+  TaskDesc* d_tasks = nullptr;
+  EventDesc* d_events = nullptr;
+  uint32_t* d_counters = nullptr;
+  uint32_t* d_aot_off = nullptr;
+  uint32_t* d_aot = nullptr;
+  uint32_t* d_op_list = nullptr;
+  uint32_t* d_err = nullptr;
+  float* d_arena = nullptr;
+  std::vector<uint32_t> op_first, op_count;   // per operator: range in op_list
+  uint32_t epoch = 0;
+  uint64_t timeout_ticks = 0;
+};
+
+#define HIP_TRY(expr)                                                              \
+  do {                                                                             \
+    hipError_t _e = (expr);                                                        \
+    if (_e != hipSuccess) {                                                        \
+      set_error("%s failed: %s", #expr, hipGetErrorString(_e));                    \
+      return MPK_ERR_HIP;                                                          \
+    }                                                                              \
+  } while (0)
+
+static void free_device(mpk_graph* g) {
+  if (g->host_only) return;
+  (void)hipFree(g->d_tasks); (void)hipFree(g->d_events); (void)hipFree(g->d_counters);
+  (void)hipFree(g->d_aot_off); (void)hipFree(g->d_aot); (void)hipFree(g->d_op_list);
+  (void)hipFree(g->d_err); (void)hipFree(g->d_arena);
+}
+
+static mpk_status resolve_options(const mpk_compile_options* in, mpk_compile_options* out,
+                                  int* n_cu) {
+  mpk_compile_options o{};
+  if (in) {
+    if (in->struct_size != sizeof(mpk_compile_options)) {
+      set_error("mpk_compile_options.struct_size is %u, expected %zu", in->struct_size, sizeof(mpk_compile_options));
+      return MPK_ERR_INVALID_ARG;
+    }
+    o = *in;
+  } else {
+    o.struct_size = sizeof(o);
+  }
+  if (o.launch_mode > MPK_LAUNCH_PER_OP) { set_error("unknown launch_mode %u", o.launch_mode); return MPK_ERR_INVALID_ARG; }
+  int cus = 256;
+  if (!o.host_only) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    hipDeviceProp_t p;
+    HIP_TRY(hipGetDeviceProperties(&p, dev));
+    cus = p.multiProcessorCount;
+  }
+  *n_cu = cus;
+  if (o.n_sched_wgs >= (uint32_t)cus) { set_error("n_sched_wgs %u leaves no worker", o.n_sched_wgs); return MPK_ERR_INVALID_ARG; }
+  if (o.n_workers == 0) o.n_workers = (uint32_t)cus - o.n_sched_wgs;
+  if (!o.host_only && o.launch_mode == MPK_LAUNCH_MEGA && o.n_workers + o.n_sched_wgs > (uint32_t)cus) {
+    set_error("%u workers + %u scheduler workgroups exceed the %d compute units: the persistent kernel could not be fully resident", o.n_workers, o.n_sched_wgs, cus);
+    return MPK_ERR_RESIDENCY;
+  }
+  if (o.spin_timeout_ms == 0) o.spin_timeout_ms = 2000;
+  *out = o;
+  return MPK_OK;
+}
+
+template <typename T>
+static mpk_status upload(T** dst, const std::vector<T>& src) {
+  size_t bytes = std::max<size_t>(src.size(), 1) * sizeof(T);
+  hipError_t e = hipMalloc((void**)dst, bytes);
+  if (e != hipSuccess) { set_error("hipMalloc(%zu) failed: %s", bytes, hipGetErrorString(e)); return MPK_ERR_OOM; }
+  if (!src.empty()) HIP_TRY(hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice));
+  return MPK_OK;
+}
+
+extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_ptrs* weights,
+                                  const mpk_kv_ptrs* kv, const mpk_compile_options* opts,
+                                  mpk_graph** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !out) { set_error("cfg or out is NULL"); return MPK_ERR_INVALID_ARG; }
+  mpk_compile_options o;
+  int n_cu = 0;
+  mpk_status st = resolve_options(opts, &o, &n_cu);
+  if (st != MPK_OK) return st;
+  if (!o.host_only && o.n_sched_wgs > 0 && !o.force_aot) {
+    set_error("scheduler workgroups (just-in-time launch) are not implemented on the device yet; use n_sched_wgs = 0 or host_only");
+    return MPK_ERR_UNSUPPORTED;
+  }
+  mpk_graph* g = new (std::nothrow) mpk_graph();
+  if (!g) { set_error("out of host memory"); return MPK_ERR_OOM; }
+  st = build_model_graph(*cfg, weights, kv, o, g->h);
+  if (st != MPK_OK) { delete g; return st; }
+  g->host_only = o.host_only != 0;
+  if (g->host_only) { *out = g; return MPK_OK; }
+
+  auto fail = [&](mpk_status s) { free_device(g); delete g; return s; };
+  if (hipGetDevice(&g->device) != hipSuccess) { set_error("hipGetDevice failed"); return fail(MPK_ERR_HIP); }
+  HostGraph& h = g->h;
+  // residency: dynamic LDS above half of a CU's 160 KB caps occupancy at one workgroup per CU
+  hipError_t e = hipFuncSetAttribute((const void*)mpk_mega_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h.lds_bytes);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)mpk_op_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h.lds_bytes);
+  if (e != hipSuccess) { set_error("cannot reserve %u bytes of LDS: %s", h.lds_bytes, hipGetErrorString(e)); return fail(MPK_ERR_RESIDENCY); }
+  int per_cu = 0;
+  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)mpk_mega_kernel, kThreads, h.lds_bytes);
+  if (e != hipSuccess || per_cu < 1) { set_error("persistent kernel does not fit on a CU (occupancy %d, %s)", per_cu, hipGetErrorString(e)); return fail(MPK_ERR_RESIDENCY); }
+  if (o.launch_mode == MPK_LAUNCH_MEGA && (uint64_t)per_cu * n_cu < (uint64_t)o.n_workers + o.n_sched_wgs) {
+    set_error("%u workgroups cannot be co-resident on %d CUs x %d", o.n_workers + o.n_sched_wgs, n_cu, per_cu);
+    return fail(MPK_ERR_RESIDENCY);
+  }
+  // activation arena + relocation of the descriptors
+  size_t arena_bytes = std::max<size_t>(h.arena_floats, 64) * sizeof(float);
+  e = hipMalloc((void**)&g->d_arena, arena_bytes);
+  if (e != hipSuccess) { set_error("hipMalloc(%zu) for activations failed: %s", arena_bytes, hipGetErrorString(e)); return fail(MPK_ERR_OOM); }
+  if (hipMemset(g->d_arena, 0, arena_bytes) != hipSuccess) { set_error("hipMemset failed"); return fail(MPK_ERR_HIP); }
+  std::vector<TaskDesc> descs = h.descs;
+  auto reloc = [&](const float* p) -> const float* {
+    if (!p) return nullptr;
+    return g->d_arena + ((uintptr_t)p / sizeof(float) - 1);
+  };
+  for (auto& t : descs) {
+    t.in = reloc(t.in);
+    t.in2 = reloc(t.in2);
+    t.out = const_cast<float*>(reloc(t.out));
+  }
+  // per-operator task lists (baseline launch mode)
+  std::vector<uint32_t> op_list;
+  g->op_first.assign(h.ops.size(), 0);
+  g->op_count.assign(h.ops.size(), 0);
+  {
+    std::vector<std::vector<uint32_t>> per(h.ops.size());
+    for (uint32_t i = 0; i < h.tasks.size(); ++i)
+      if (h.tasks[i].op != MPK_TASK_DUMMY_OP) per[h.tasks[i].op].push_back(i);
+    for (size_t oi = 0; oi < per.size(); ++oi) {
+      g->op_first[oi] = (uint32_t)op_list.size();
+      g->op_count[oi] = (uint32_t)per[oi].size();
+      op_list.insert(op_list.end(), per[oi].begin(), per[oi].end());
+    }
+  }
+  std::vector<uint32_t> zeros(h.events.size(), 0), err(8, 0);
+  if ((st = upload(&g->d_tasks, descs)) != MPK_OK) return fail(st);
+  if ((st = upload(&g->d_events, h.events)) != MPK_OK) return fail(st);
+  if ((st = upload(&g->d_counters, zeros)) != MPK_OK) return fail(st);
+  if ((st = upload(&g->d_aot_off, h.aot_off)) != MPK_OK) return fail(st);
+  if ((st = upload(&g->d_aot, h.aot)) != MPK_OK) return fail(st);
+  if ((st = upload(&g->d_op_list, op_list)) != MPK_OK) return fail(st);
+  if ((st = upload(&g->d_err, err)) != MPK_OK) return fail(st);
+  g->timeout_ticks = (uint64_t)o.spin_timeout_ms * 100000ull;   // wall clock counts at 100 MHz
+  *out = g;
+  return MPK_OK;
+}
+
+extern "C" mpk_status mpk_compile_dag(uint32_t n_tasks, const uint32_t* pairs, size_t n_pairs,
+                                      const mpk_compile_options* opts, mpk_graph** out) {
+  if (out) *out = nullptr;
+  if (!out) { set_error("out is NULL"); return MPK_ERR_INVALID_ARG; }
+  mpk_compile_options o{};
+  if (opts) {
+    if (opts->struct_size != sizeof(mpk_compile_options)) { set_error("bad mpk_compile_options.struct_size"); return MPK_ERR_INVALID_ARG; }
+    o = *opts;
+  }
+  o.host_only = 1;
+  if (o.n_workers == 0) o.n_workers = 256 - o.n_sched_wgs;
+  mpk_graph* g = new (std::nothrow) mpk_graph();
+  if (!g) { set_error("out of host memory"); return MPK_ERR_OOM; }
+  mpk_status st = build_dag_graph(n_tasks, pairs, n_pairs, o, g->h);
+  if (st != MPK_OK) { delete g; return st; }
+  *out = g;
+  return MPK_OK;
+}
+
+extern "C" mpk_status mpk_decode_step(mpk_graph* g, const int32_t* token_ids,
+                                      const int32_t* positions, float* logits_out, void* stream) {
+  if (!g || !token_ids || !positions || !logits_out) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
+  if (g->host_only) { set_error("graph was compiled host_only"); return MPK_ERR_INVALID_ARG; }
+  HostGraph& h = g->h;
+  StepArgs a{};
+  a.tasks = g->d_tasks; a.events = g->d_events; a.counters = g->d_counters;
+  a.aot_off = g->d_aot_off; a.aot = g->d_aot; a.op_list = g->d_op_list;
+  a.token_ids = token_ids; a.positions = positions; a.logits = logits_out; a.err = g->d_err;
+  a.timeout_ticks = g->timeout_ticks;
+  a.n_workers = h.opt.n_workers;
+  a.vocab = h.cfg.vocab; a.max_seq = h.cfg.max_seq; a.n_q = h.cfg.n_q_heads;
+  a.n_kv = h.cfg.n_kv_heads; a.head_dim = h.cfg.head_dim; a.batch = h.cfg.batch;
+  hipStream_t s = (hipStream_t)stream;
+  if (h.opt.launch_mode == MPK_LAUNCH_MEGA) {
+    a.epoch = ++g->epoch;
+    hipLaunchKernelGGL(mpk_mega_kernel, dim3(h.opt.n_workers + h.opt.n_sched_wgs), dim3(kThreads),
+                       h.lds_bytes, s, a);
+    HIP_TRY(hipGetLastError());
+  } else {
+    for (size_t oi = 0; oi < h.ops.size(); ++oi) {
+      if (!g->op_count[oi]) continue;
+      hipLaunchKernelGGL(mpk_op_kernel, dim3(g->op_count[oi]), dim3(kThreads), h.lds_bytes, s, a,
+                         g->op_first[oi]);
+    }
+    HIP_TRY(hipGetLastError());
+  }
+  return MPK_OK;
+}
+
+extern "C" mpk_status mpk_graph_status(mpk_graph* g) {
+  if (!g) { set_error("NULL graph"); return MPK_ERR_INVALID_ARG; }
+  if (g->host_only) return MPK_OK;
+  uint32_t err[4] = {0, 0, 0, 0};
+  HIP_TRY(hipMemcpy(err, g->d_err, sizeof(err), hipMemcpyDeviceToHost));
+  switch (err[0]) {
+    case DE_NONE: return MPK_OK;
+    case DE_TIMEOUT:
+      set_error("watchdog: worker %u waited too long on event %u; call mpk_graph_reset", err[3], err[2]);
+      return MPK_ERR_TIMEOUT;
+    case DE_BAD_POSITION:
+      set_error("sequence %u has position %d outside [0, max_seq)", err[2], (int)err[3]);
+      return MPK_ERR_DEVICE;
+    case DE_BAD_TOKEN:
+      set_error("sequence %u has token %d outside [0, vocab)", err[2], (int)err[3]);
+      return MPK_ERR_DEVICE;
+    default: set_error("unknown device error %u", err[0]); return MPK_ERR_DEVICE;
+  }
+}
+
+extern "C" mpk_status mpk_graph_reset(mpk_graph* g) {
+  if (!g) { set_error("NULL graph"); return MPK_ERR_INVALID_ARG; }
+  if (g->host_only) return MPK_OK;
+  HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(hipMemset(g->d_counters, 0, g->h.events.size() * sizeof(uint32_t)));
+  HIP_TRY(hipMemset(g->d_err, 0, 8 * sizeof(uint32_t)));
+  HIP_TRY(hipDeviceSynchronize());
+  g->epoch = 0;
+  return MPK_OK;
+}
+
+extern "C" mpk_status mpk_graph_stats(const mpk_graph* g, mpk_stats* out) {
+  if (!g || !out) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
+  *out = g->h.stats;
+  out->struct_size = sizeof(mpk_stats);
+  return MPK_OK;
+}
+
+extern "C" mpk_status mpk_graph_export(const mpk_graph* g, void* buf, size_t cap, size_t* need) {
+  if (!g) { set_error("NULL graph"); return MPK_ERR_INVALID_ARG; }
+  size_t n = export_size(g->h);
+  if (need) *need = n;
+  if (!buf) return MPK_OK;
+  if (cap < n) { set_error("export buffer too small: %zu < %zu", cap, n); return MPK_ERR_INVALID_ARG; }
+  export_graph(g->h, buf);
+  return MPK_OK;
+}
+
+extern "C" const char* mpk_last_error(void) { return mpk::last_error(); }
+
+extern "C" void mpk_graph_destroy(mpk_graph* g) {
+  if (!g) return;
+  if (!g->host_only) {
+    (void)hipSetDevice(g->device);
+    (void)hipDeviceSynchronize();
+    free_device(g);
+  }
+  delete g;
+}

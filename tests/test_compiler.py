@@ -1,0 +1,263 @@
+"""Host compiler (libmpk) against the task-graph oracle: dependency sets bit-exact, structure
+invariants, launch-mode labels, generic DAG passes, error handling.  No GPU needed."""
+import os
+import random
+import re
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+import paper_2512_22219_amd as M
+from oracle import tgraph as TG
+from synth import gen as G
+from tests import graph_util as GU
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "mpk.h")).read()
+    declared = set(re.findall(r"\b(mpk_[a-z_]+)\s*\(", hdr))
+    assert declared == set(M.binding.SYMBOLS), declared ^ set(M.binding.SYMBOLS)
+    L = M.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def host_graph(shape, **kw):
+    kw.setdefault("host_only", 1)
+    return M.compile_graph(shape, None, None, **kw)
+
+
+CASES = [
+    ("C1", {}, dict(fusion=0)),
+    ("C1", {}, dict(fusion=7)),
+    ("C1", dict(batch=3), dict(fusion=0, n_workers=16, attn_chunks=3)),
+    ("C1", dict(batch=2), dict(fusion=7, n_workers=7, attn_chunks=5, tiles_pointwise=3)),
+    ("C1", dict(batch=2), dict(fusion=3, n_workers=24, tiles_lm_head=100)),
+    ("C2", dict(n_layers=2), dict(fusion=0)),
+    ("C2", dict(n_layers=2), dict(fusion=7)),
+    ("C3", dict(n_layers=1), dict(fusion=7)),
+]
+
+
+@pytest.mark.parametrize("base,variant,opts", CASES)
+def test_dependency_sets_bit_exact_and_structure(base, variant, opts):
+    shape = G.small_variant(base, **variant)
+    g = host_graph(shape, **opts)
+    ex = g.export()
+    GU.check_structure(ex)
+    C = GU.attn_chunks_of(ex, shape)
+    ops, deg = GU.oracle_ops_and_degrees(shape, ex, opts.get("fusion", 0), C)
+    want = TG.producer_sets(ops, deg)
+    got = GU.compiled_producer_sets(ex)
+    assert TG.canonical_bytes(got) == TG.canonical_bytes(want)
+    st_ = g.stats()
+    assert st_["n_pair_deps"] == sum(len(p) for per in want for p in per)
+    assert st_["n_tasks"] == len(ex.tasks) and st_["n_events"] == len(ex.events)
+
+
+def closure_by_op_tile(psets):
+    memo = {}
+
+    def go(k):
+        if k in memo:
+            return memo[k]
+        acc = set()
+        for p in psets[k[0]][k[1]]:
+            acc.add(p)
+            acc |= go(p)
+        memo[k] = acc
+        return acc
+    return {(o, t): go((o, t)) for o in range(len(psets)) for t in range(len(psets[o]))}
+
+
+@pytest.mark.parametrize("base,variant,opts", CASES[:5])
+def test_transitive_reduction_keeps_closures(base, variant, opts):
+    shape = G.small_variant(base, **variant)
+    g = host_graph(shape, transitive_reduction=1, **opts)
+    ex = g.export()
+    GU.check_structure(ex)
+    C = GU.attn_chunks_of(ex, shape)
+    ops, deg = GU.oracle_ops_and_degrees(shape, ex, opts.get("fusion", 0), C)
+    want = TG.producer_sets(ops, deg)
+    got = GU.compiled_producer_sets(ex)
+    assert closure_by_op_tile(got) == closure_by_op_tile(want)
+    # every kept pair is one of the oracle's direct pairs
+    for o in range(len(want)):
+        for t in range(len(want[o])):
+            assert set(got[o][t]) <= set(want[o][t])
+    assert g.stats()["n_dummy_tasks"] <= host_graph(shape, **opts).stats()["n_dummy_tasks"]
+
+
+def test_simulated_execution_respects_oracle_producers():
+    """Random legal interleavings of the compiled graph in the runtime simulator: every task's
+    brute-force producers are finished before it runs, nothing deadlocks; and a dropped trigger
+    or an out-of-order AOT queue is detected."""
+    shape = G.small_variant("C1", batch=2)
+    for opts in (dict(fusion=0), dict(fusion=7, transitive_reduction=1),
+                 dict(fusion=7, n_sched_wgs=2)):
+        g = host_graph(shape, n_workers=6, attn_chunks=3, **opts)
+        ex = g.export()
+        C = GU.attn_chunks_of(ex, shape)
+        ops, deg = GU.oracle_ops_and_degrees(shape, ex, opts["fusion"], C)
+        want = TG.producer_sets(ops, deg)
+        lin = {(int(t["op"]), int(t["tile"])): i for i, t in enumerate(ex.tasks)
+               if t["op"] != GU.DUMMY}
+        producers = [set() for _ in ex.tasks]
+        for (o, tl), i in lin.items():
+            producers[i] = {lin[p] for p in want[o][tl]}
+        tasks, events, queues = GU.sim_inputs(ex)
+        n_sched = int(ex.header["n_sched_wgs"]) * 4
+        for seed in range(40):
+            log, hops = TG.simulate(tasks, events, queues, n_sched, random.Random(seed), producers)
+            assert len(log) == len(tasks)
+        if opts.get("n_sched_wgs"):
+            assert any(t["jit"] for t in tasks)
+            assert all(hops[i] == (2 if tasks[i]["jit"] else 1) for i in range(len(tasks)))
+        victim = next(i for i, t in enumerate(tasks) if t["trig"] != int(ex.header["terminal_event"]))
+        with pytest.raises(TG.Deadlock):
+            TG.simulate(tasks, events, queues, n_sched, random.Random(0), producers, drop_trigger=victim)
+        bad = [list(q) for q in queues]
+        w = next(w for w, q in enumerate(bad) if len(q) >= 2)
+        bad[w][0], bad[w][-1] = bad[w][-1], bad[w][0]
+        with pytest.raises((TG.Deadlock, AssertionError)):
+            for seed in range(5):
+                TG.simulate(tasks, events, bad, n_sched, random.Random(seed), producers)
+
+
+def test_launch_mode_labels_follow_the_barrier_rule():
+    """Attention is JIT; an operator downstream of a JIT operator stays JIT unless each of its
+    tasks waits for all tasks of that operator (Section 5.2).  Recomputed from the oracle sets."""
+    shape = G.small_variant("C1", batch=2)
+    for fusion in (0, 7):
+        g = host_graph(shape, n_workers=8, attn_chunks=3, n_sched_wgs=1, fusion=fusion)
+        ex = g.export()
+        ops, deg = GU.oracle_ops_and_degrees(shape, ex, fusion, 3)
+        want = TG.producer_sets(ops, deg)
+        jit = []
+        for oi, op in enumerate(ops):
+            if op.kind == TG.K_ATTN_PARTIAL:
+                jit.append(1)
+                continue
+            j = 0
+            for ps in want[oi]:
+                per = {}
+                for (po, pt) in ps:
+                    per[po] = per.get(po, 0) + 1
+                for po, n in per.items():
+                    if jit[po] and n != deg[po][0] * deg[po][1]:
+                        j = 1
+            jit.append(j)
+        assert list(ex.ops["jit"]) == jit
+        names = [o.name for o in ops]
+        assert jit[names.index("L0.attn_merge")] == 1 and jit[names.index("L0.o_proj")] == 0
+        # with no scheduler every task is pre-enqueued
+        ex0 = host_graph(shape, n_workers=8, attn_chunks=3, fusion=fusion).export()
+        assert not ex0.tasks["jit"].any()
+
+
+def test_no_dummies_when_nothing_forks_and_paper_style_stats():
+    """A purely sequential fused graph needs no normalization (Section 6.5: no fork/join groups in
+    the compiled LLM graphs); event storage after linearization is 8 bytes per event."""
+    shape = G.small_variant("C1", n_kv_heads=4)      # one query head per KV head
+    g = host_graph(shape, fusion=7, transitive_reduction=1, attn_chunks=1, n_workers=8,
+                   tiles_linear=4)
+    s = g.stats()
+    assert s["successor_bytes_linearized"] == 8 * s["n_events"]
+    assert s["successor_bytes_unlinearized"] >= 4 * (s["n_tasks"] - 1)
+    assert s["n_events_fused"] < s["n_pair_deps"]
+
+
+# ------------------------------------------------------------------ generic DAG entry point
+def export_as_sets(ex):
+    real_in = GU.real_in_sets(ex)
+    prod = {}
+    for i, t in enumerate(ex.tasks):
+        if t["op"] == GU.DUMMY:
+            continue
+        prod[int(t["tile"])] = {int(ex.tasks["tile"][p]) for p in real_in[int(t["dep_event"])]}
+    return prod
+
+
+def test_compile_dag_fig4_example():
+    names = ["Q", "K", "V", "X", "A1", "A2", "O1", "O2", "O3", "O4", "R"]
+    ix = {n: i for i, n in enumerate(names)}
+    pairs = []
+    for a in ("A1", "A2"):
+        pairs += [(ix[s], ix[a]) for s in ("Q", "K", "V")]
+        pairs += [(ix[a], ix[o]) for o in ("O1", "O2", "O3", "O4")] + [(ix[a], ix["R"])]
+    pairs += [(ix["X"], ix["R"])]
+    g = M.compile_dag(len(names), pairs, n_workers=4)
+    s, ex = g.stats(), g.export()
+    assert s["n_pair_deps"] == 17 and s["n_events_fused"] == 3 and s["n_dummy_tasks"] == 2
+    GU.check_structure(ex)
+    # the event that launches O1..O4 stores them as one range of four
+    o_pos = sorted(i for i, t in enumerate(ex.tasks) if t["op"] != GU.DUMMY and names[t["tile"]].startswith("O"))
+    assert o_pos == list(range(o_pos[0], o_pos[0] + 4))
+    e = int(ex.tasks["dep_event"][o_pos[0]])
+    assert (int(ex.events["first"][e]), int(ex.events["last"][e])) == (o_pos[0], o_pos[0] + 4)
+    prod = export_as_sets(ex)
+    assert prod[ix["R"]] == {ix["A1"], ix["A2"], ix["X"]} and prod[ix["O3"]] == {ix["A1"], ix["A2"]}
+
+
+@st.composite
+def random_dag(draw):
+    n = draw(st.integers(2, 16))
+    pairs = set()
+    for b in range(1, n):
+        for a in draw(st.lists(st.integers(0, b - 1), max_size=4)):
+            pairs.add((a, b))
+    return n, sorted(pairs)
+
+
+@settings(max_examples=100, deadline=None)
+@given(random_dag())
+def test_compile_dag_matches_oracle_passes(gr):
+    n, pairs = gr
+    if not pairs:
+        return
+    g = M.compile_dag(n, pairs, n_workers=3)
+    ex, s = g.export(), g.stats()
+    GU.check_structure(ex)
+    ev = TG.predecessor_set_fusion(TG.successor_set_fusion(TG.pair_events(pairs)))
+    n_ev, n_tasks, dummies = TG.normalize(ev, list(range(n)))
+    assert s["n_events_fused"] == len(ev)
+    assert s["n_dummy_tasks"] == len(dummies)
+    assert s["n_events"] == len(n_ev) + 2            # + start and terminal events
+    want = {}
+    for a, b in pairs:
+        want.setdefault(b, set()).add(a)
+    got = export_as_sets(ex)
+    for t in range(n):
+        assert got.get(t, set()) == want.get(t, set())
+
+
+# ------------------------------------------------------------------ error handling
+def test_error_paths():
+    s = G.CONFIGS["C1"]
+    with pytest.raises(M.MpkError) as e:
+        host_graph(G.small_variant("C1", head_dim=48))
+    assert e.value.status == M.binding.MPK_ERR_UNSUPPORTED
+    with pytest.raises(M.MpkError) as e:
+        host_graph(G.small_variant("C1", hidden=0))
+    assert e.value.status == M.binding.MPK_ERR_INVALID_ARG
+    with pytest.raises(M.MpkError) as e:
+        host_graph(s, fusion=1 << 9)
+    assert e.value.status == M.binding.MPK_ERR_INVALID_ARG
+    with pytest.raises(M.MpkError) as e:
+        host_graph(G.small_variant("C1", n_q_heads=3))
+    assert e.value.status == M.binding.MPK_ERR_UNSUPPORTED
+    cfg = M.binding.model_config(s)
+    cfg.struct_size = 4
+    import ctypes as C
+    h = C.c_void_p()
+    o = M.binding.compile_options(host_only=1)
+    assert M.lib().mpk_compile(C.byref(cfg), None, None, C.byref(o), C.byref(h)) == M.binding.MPK_ERR_INVALID_ARG
+    assert b"struct_size" in M.lib().mpk_last_error()
+    # a host-only graph refuses to run
+    g = host_graph(s)
+    assert M.lib().mpk_decode_step(g._h, 1, 1, 1, None) == M.binding.MPK_ERR_INVALID_ARG
+    with pytest.raises(M.MpkError):
+        M.compile_dag(3, [(0, 5)])
