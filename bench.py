@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Decode benchmark on one MI355X: the Qwen3-8B-shaped config, batch 1, KV 1024, greedy steps.
+
+A "step" is one decode step through the persistent mega-kernel (mpk_decode_step) followed by the
+greedy token feedback (arg max on the device, no host sync).  Prints ONE JSON line.
+Also measured and attached: the same task bodies launched one kernel per operator (eager and as
+a replayed HIP graph), and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def cpu_baseline(shape, seed, n_layers_sample=4, reps=3):
+    """The oracle as it stands, on the host cores: one decode step restricted to the first
+    `n_layers_sample` layers (weights generated beforehand, not timed) plus the LM head, scaled to
+    the full depth."""
+    import numpy as np
+    from oracle import decoder as D
+    from synth import gen as G
+    prov = G.SynthWeights(shape, seed, cache=True)
+    for l in range(n_layers_sample):
+        prov.layer(l)
+    prov.lm_head()
+    prov.final_norm()
+    o = D.DecoderOracle(shape, prov, "f32", n_layers=n_layers_sample)
+    for l in range(n_layers_sample):
+        o._kv(l)
+    tok, pos = G.tokens(seed, shape), G.kv_lengths(seed, shape)
+    t_layers, t_head = [], []
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        hid = o.step(tok, pos, return_hidden=True)
+        t1 = time.perf_counter()
+        g, W = prov.final_norm(), prov.lm_head()
+        for b in range(shape.batch):
+            o.ops.linear(W, o.ops.rmsnorm(hid[b], g, shape.rms_eps))
+        t2 = time.perf_counter()
+        t_layers.append(t1 - t0)
+        t_head.append(t2 - t1)
+    per_layer = min(t_layers) / n_layers_sample
+    step_s = per_layer * shape.n_layers + min(t_head)
+    return {"value": step_s * 1e3 / shape.batch, "unit": "ms/token",
+            "cores": int(D.lib("f32").orc_threads()), "kind": "oracle",
+            "sample": f"one decode step over the first {n_layers_sample} of {shape.n_layers} "
+                      f"layers + LM head, best of {reps}, layer time scaled to full depth"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=32)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--config", default="C2")
+    ap.add_argument("--fusion", type=int, default=7)
+    ap.add_argument("--no-baselines", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2512_22219_amd as M
+    from synth import gen as G
+    from synth.device import DeviceModel
+
+    shape = G.CONFIGS[args.config]
+    seed = 0
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    model = DeviceModel(shape, seed, dev)
+    tok0 = torch.as_tensor(G.tokens(seed, shape), device=dev)
+    pos0 = torch.as_tensor(G.kv_lengths(seed, shape), device=dev)
+    tok, pos = tok0.clone(), pos0.clone()
+    logits = torch.empty((shape.batch, shape.vocab), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    n_total = args.steps + args.warmup
+    assert int(pos0.max()) + n_total <= shape.max_seq
+
+    def run(graph, n, events=None):
+        for i in range(n):
+            if events is not None:
+                events[i][0].record()
+            graph.decode_step(tok.data_ptr(), pos.data_ptr(), logits.data_ptr(), stream)
+            if events is not None:
+                events[i][1].record()
+            torch.argmax(logits, dim=-1, out=tok64)
+            tok.copy_(tok64)
+            pos.add_(1)
+
+    tok64 = torch.empty(shape.batch, dtype=torch.int64, device=dev)
+
+    def timed(graph):
+        tok.copy_(tok0)
+        pos.copy_(pos0)
+        model.reset_kv()
+        run(graph, args.warmup)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(graph, args.steps, ev)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        graph.status()
+        kern_ms = [a.elapsed_time(b) for a, b in ev]
+        return dt, kern_ms
+
+    common = dict(fusion=args.fusion, transitive_reduction=1)
+    mega = M.compile_graph(shape, model.weight_ptrs(), model.kv_ptrs(), launch_mode=0, **common)
+    stats = mega.stats()
+    dt, kern_ms = timed(mega)
+    final_tokens = tok.cpu().numpy().tolist()
+    ms_per_step = dt * 1e3 / args.steps
+    # algorithmic bytes of one launch: weights streamed once + K/V rows read (grows by one row a
+    # step; averaged over the timed steps)
+    pos_avg = float(pos0.float().sum()) + shape.batch * (args.warmup + (args.steps - 1) / 2 + 1)
+    bytes_step = stats["weight_bytes"] + stats["kv_row_bytes"] * pos_avg
+    kern_avg_ms = sum(kern_ms) / len(kern_ms)
+    achieved = bytes_step / (kern_avg_ms * 1e-3) / 1e9
+    out = {
+        "metric": "decode_ms_per_token_batch1", "value": ms_per_step / shape.batch,
+        "unit": "ms/token", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 weights, fp32 activations/accumulation",
+        "data": "synthetic",
+        "config": {"workload": f"{shape.name}: {shape.n_layers} layers, hidden {shape.hidden}, "
+                               f"{shape.n_q_heads}q/{shape.n_kv_heads}kv heads, ffn {shape.ffn}, "
+                               f"vocab {shape.vocab}, batch {shape.batch}, KV "
+                               f"{shape.kv_len_lo} prior positions, greedy decode",
+                   "launch": "persistent mega-kernel", "fusion": args.fusion,
+                   "n_workers": stats["n_workers"], "tasks": stats["n_tasks"],
+                   "events": stats["n_events"]},
+        "tokens_per_s": shape.batch * 1e3 / ms_per_step,
+        "achieved_hbm_GBps": bytes_step / (ms_per_step * 1e-3) / 1e9,
+        "bytes_per_step": bytes_step,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": 8000.0, "unit": "GB/s",
+                     "frac": achieved / 8000.0, "traffic": None,
+                     "kernel": "mpk_mega_kernel", "kernel_avg_ms": kern_avg_ms},
+        "final_tokens": final_tokens,
+    }
+    mega.destroy()
+    if not args.no_baselines:
+        per_op = M.compile_graph(shape, model.weight_ptrs(), model.kv_ptrs(), launch_mode=1, **common)
+        dt_e, _ = timed(per_op)
+        out["per_op_eager_ms_per_step"] = dt_e * 1e3 / args.steps
+        out["per_op_tokens_match"] = tok.cpu().numpy().tolist() == final_tokens
+        # the same launches captured once and replayed as a HIP graph
+        tok.copy_(tok0); pos.copy_(pos0); model.reset_kv()
+        side = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            per_op.decode_step(tok.data_ptr(), pos.data_ptr(), logits.data_ptr(), side.cuda_stream)
+            side.synchronize()
+            tok.copy_(tok0); pos.copy_(pos0); model.reset_kv()
+            with torch.cuda.graph(g, stream=side):
+                per_op.decode_step(tok.data_ptr(), pos.data_ptr(), logits.data_ptr(), side.cuda_stream)
+                torch.argmax(logits, dim=-1, out=tok64)
+                tok.copy_(tok64)
+                pos.add_(1)
+        tok.copy_(tok0); pos.copy_(pos0); model.reset_kv()
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        out["per_op_graph_ms_per_step"] = (time.perf_counter() - t0) * 1e3 / args.steps
+        out["per_op_graph_tokens_match"] = tok.cpu().numpy().tolist() == final_tokens
+        per_op.status()
+        per_op.destroy()
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(shape, seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -56,6 +56,7 @@ def lib(prec: str = "f32"):
         L = ctypes.CDLL(build()[prec])
         vp, ci = ctypes.c_void_p, ctypes.c_int
         L.orc_real_bytes.restype = ci
+        L.orc_threads.restype = ci
         L.orc_bf16_to_f32.argtypes = [ctypes.c_uint16]
         L.orc_bf16_to_f32.restype = ctypes.c_float
         L.orc_f32_to_bf16.argtypes = [ctypes.c_float]

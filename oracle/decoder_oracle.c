@@ -33,6 +33,13 @@ typedef float real;
 
 int orc_real_bytes(void) { return (int)sizeof(real); }
 
+#ifdef _OPENMP
+#include <omp.h>
+int orc_threads(void) { return omp_get_max_threads(); }
+#else
+int orc_threads(void) { return 1; }
+#endif
+
 /* bf16 -> fp32 is exact: the 16 bits become the high half of the fp32 pattern. */
 static inline float bf16_to_f32(uint16_t b) {
   uint32_t u = (uint32_t)b << 16;

@@ -1,0 +1,144 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_22219_amd as M
+from oracle import decoder as D
+from synth import gen as G
+from tests.gpu_util import GpuDecoder, rel_err
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2   # the target's bound on logits (bf16 weights, fp32 accumulation)
+
+
+def test_device_generator_matches_host_bit_exact():
+    from synth.device import DeviceModel
+    s = G.CONFIGS["C1"]
+    m = DeviceModel(s, seed=3)
+    host = G.SynthWeights(s, 3)
+    w0 = host.layer(1)
+    assert np.array_equal(m.layers[1]["wqkv"].view(torch.int16).cpu().numpy().view(np.uint16), w0[G.L_WQKV])
+    assert np.array_equal(m.layers[1]["attn_norm"].view(torch.int16).cpu().numpy().view(np.uint16), w0[G.L_ATTN_NORM])
+    assert np.array_equal(m.lm_head.view(torch.int16).cpu().numpy().view(np.uint16), host.lm_head())
+    k, v = host.kv_layer(0)
+    assert np.array_equal(m.k[0].view(torch.int16).cpu().numpy().view(np.uint16), k)
+    assert np.array_equal(m.v[0].view(torch.int16).cpu().numpy().view(np.uint16), v)
+
+
+MODES = [
+    dict(fusion=0),
+    dict(fusion=0, launch_mode=1),
+    dict(fusion=7),
+    dict(fusion=7, transitive_reduction=1),
+    dict(fusion=7, transitive_reduction=1, launch_mode=1),
+    dict(fusion=3, transitive_reduction=1, n_workers=37, attn_chunks=5, tiles_pointwise=3),
+]
+
+
+@pytest.mark.parametrize("opts", MODES)
+def test_c1_one_step_matches_oracle(opts):
+    s = G.CONFIGS["C1"]
+    tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 0), "f32")
+    want = ref.step(tok, pos)
+    gpu = GpuDecoder(s, 0, **opts)
+    got = gpu.step(tok, pos)
+    assert np.isfinite(got).all()
+    assert rel_err(got, want) < TOL
+    assert np.abs(got - want).max() / np.abs(want).max() < 1e-4     # fp32 activations end to end
+    assert got.argmax(-1).tolist() == want.argmax(-1).tolist()
+    # the appended K/V rows: bf16 patterns equal to the oracle's (value within one bf16 ulp where
+    # the fp32 value before rounding differed in its last bits)
+    p = int(pos[0])
+    for l in range(s.n_layers):
+        for dev_c, host_c in ((gpu.model.k, ref.kv[l][0]), (gpu.model.v, ref.kv[l][1])):
+            g_rows = dev_c[l, :, :, p].view(torch.int16).cpu().numpy().view(np.uint16)
+            h_rows = host_c[:, :, p]
+            diff = np.abs(g_rows.astype(np.int32) - h_rows.astype(np.int32))
+            assert diff.max() <= 1 and (diff != 0).mean() < 0.02
+            # nothing else in the cache changed
+            before = G.host_kv_layer(0, s, l)[0 if dev_c is gpu.model.k else 1]
+            g_all = dev_c[l].view(torch.int16).cpu().numpy().view(np.uint16)
+            mask = np.ones(s.max_seq, bool)
+            mask[p] = False
+            assert np.array_equal(g_all[:, :, mask], before[:, :, mask])
+    gpu.close()
+
+
+@pytest.mark.parametrize("opts", [dict(fusion=0), dict(fusion=7, transitive_reduction=1)])
+def test_small_batch_and_ragged_positions(opts):
+    """Batch 3 with different KV lengths (one of them tiny), ragged tiles (n_workers = 37)."""
+    s = G.small_variant("C1", batch=3, n_layers=2)
+    tok = G.tokens(1, s)
+    pos = np.array([0, 77, 150], np.int32)
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 1), "f32")
+    want = ref.step(tok, pos)
+    gpu = GpuDecoder(s, 1, n_workers=37, **opts)
+    got = gpu.step(tok, pos)
+    assert rel_err(got, want) < TOL
+    assert np.abs(got - want).max() / np.abs(want).max() < 1e-4
+    gpu.close()
+
+
+def test_greedy_32_steps_free_running_and_teacher_forced():
+    s = G.small_variant("C1", max_seq=192)
+    tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 0), "f32")
+    want_t, want_l = ref.greedy(tok, pos, 32)
+    for opts in (dict(fusion=0), dict(fusion=7, transitive_reduction=1)):
+        gpu = GpuDecoder(s, 0, **opts)
+        t, p, toks = np.array(tok), np.array(pos), []
+        for i in range(32):
+            lg = gpu.step(t, p)
+            assert rel_err(lg, want_l[i]) < TOL, i
+            t = lg.argmax(-1).astype(np.int32)
+            p = p + 1
+            toks.append(t.copy())
+        assert np.array_equal(np.stack(toks), want_t)
+        gpu.model.reset_kv()
+        gpu.graph.reset()
+        t, p = np.array(tok), np.array(pos)
+        for i in range(32):              # teacher forced: fed the oracle's tokens
+            lg = gpu.step(t, p)
+            assert lg.argmax(-1).tolist() == want_t[i].tolist(), i
+            t, p = want_t[i].astype(np.int32), p + 1
+        gpu.close()
+
+
+def test_full_width_two_layers_of_the_8b_shape():
+    """Two layers of the Qwen3-8B-shaped config at full width and vocabulary: every tile shape
+    the benchmark launches (24/16/96-row tiles, the ragged 593/594-row LM-head tiles)."""
+    s = G.small_variant("C2", n_layers=2)
+    tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 0), "f32")
+    want = ref.step(tok, pos)
+    from synth.device import DeviceModel
+    model = DeviceModel(s, 0)
+    for opts in (dict(fusion=0), dict(fusion=7, transitive_reduction=1),
+                 dict(fusion=7, transitive_reduction=1, launch_mode=1)):
+        model.reset_kv()
+        gpu = GpuDecoder(s, 0, model=model, **opts)
+        got = gpu.step(tok, pos)
+        assert rel_err(got, want) < TOL
+        assert np.abs(got - want).max() / np.abs(want).max() < 1e-4
+        assert got.argmax(-1).tolist() == want.argmax(-1).tolist()
+        gpu.close()
+
+
+def test_device_errors_are_reported_not_fatal():
+    s = G.CONFIGS["C1"]
+    gpu = GpuDecoder(s, 0, fusion=0)
+    tok = G.tokens(0, s)
+    with pytest.raises(M.MpkError) as e:
+        gpu.step(tok, np.array([s.max_seq], np.int32))
+    assert e.value.status == M.binding.MPK_ERR_DEVICE
+    gpu.graph.reset()
+    with pytest.raises(M.MpkError) as e:
+        gpu.step(np.array([s.vocab + 5], np.int32), G.kv_lengths(0, s))
+    assert e.value.status == M.binding.MPK_ERR_DEVICE
+    gpu.graph.reset()
+    gpu.model.reset_kv()
+    want = D.DecoderOracle(s, G.SynthWeights(s, 0), "f32").step(tok, G.kv_lengths(0, s))
+    assert rel_err(gpu.step(tok, G.kv_lengths(0, s)), want) < TOL
+    gpu.close()
