@@ -5,11 +5,16 @@
 // counter has reached epoch * required, after it they publish their stores and add one to the
 // triggering event's counter.  Event counters only ever grow (no reset between steps).
 //
-// Memory ordering (the GPU has 8 XCDs with private L2s): producer side = every wavefront issues
-// an agent-scope release fence after its stores, workgroup barrier, then one lane does the
-// relaxed agent-scope atomic add.  Consumer side = one lane polls with relaxed agent-scope
-// atomic loads, workgroup barrier, then every wavefront issues an agent-scope acquire fence
-// before touching activations.  Weights never depend on an event.
+// Memory ordering (the GPU has 8 XCDs with private, mutually non-coherent L2s).  Whole-cache
+// write-back / invalidate fences cost tens of microseconds per hop with 256 workgroups, so the
+// runtime never issues them.  Instead every datum that crosses workgroups inside the kernel
+// (activations, split-KV partials, the K/V row appended this step, event counters) is written
+// with agent-scope stores and read with agent-scope loads (ld_act / st_act below): such accesses
+// are performed at the device coherence point, not in an XCD-private cache.  Producer side:
+// agent-scope stores, every wavefront waits for its own stores to complete (vmcnt 0), workgroup
+// barrier, one lane adds to the event counter.  Consumer side: one lane polls the counter,
+// workgroup barrier, then agent-scope loads.  Weights, descriptors and cache rows of earlier
+// steps are immutable during a step and use ordinary (non-temporal) loads.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -82,6 +87,26 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Agent-coherent accessors for data produced and consumed by different workgroups in one launch.
+__device__ __forceinline__ float ld_act(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_act(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_act2(const float* p) {   // p 8-byte aligned
+  uint64_t u = __hip_atomic_load((const uint64_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32)));
+}
+__device__ __forceinline__ void st_act_u32(uint32_t* p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ u32x4 ld_row16_coherent(const uint16_t* p) {   // p 16-byte aligned
+  uint64_t a = __hip_atomic_load((const uint64_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  uint64_t b = __hip_atomic_load((const uint64_t*)p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return u32x4{(uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32)};
+}
+
 __device__ __forceinline__ float dot8(const u32x4& w, const float4& x0, const float4& x1, float acc) {
   acc = fmaf(bf16_lo(w.x), x0.x, acc);
   acc = fmaf(bf16_hi(w.x), x0.y, acc);
@@ -112,7 +137,7 @@ __device__ void body_embed(const TaskDesc& t, const StepArgs& a) {
     }
     const uint16_t* row = (const uint16_t*)t.w + (size_t)tok * t.K;
     float* out = t.out + (size_t)b * t.ld_out;
-    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) out[i] = bf16_to_f32(row[i]);
+    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) st_act(out + i, bf16_to_f32(row[i]));
   }
 }
 
@@ -123,10 +148,13 @@ __device__ void body_rmsnorm(const TaskDesc& t, float* lds) {
     const float* x = t.in + (size_t)b * t.ld_in;
     float* y = t.out + (size_t)b * t.ld_out;
     float ss = 0.f;
-    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) ss = fmaf(x[i], x[i], ss);
+    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) {
+      float v = ld_act(x + i);
+      ss = fmaf(v, v, ss);
+    }
     ss = block_sum(ss, lds);
     float inv = 1.0f / sqrtf(ss / (float)t.K + t.f0);
-    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) y[i] = x[i] * inv * bf16_to_f32(g[i]);
+    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) st_act(y + i, ld_act(x + i) * inv * bf16_to_f32(g[i]));
   }
 }
 
@@ -144,9 +172,9 @@ __device__ void body_linear(const TaskDesc& t, const StepArgs& a, float* lds) {
   // ---- stage the input rows
   for (uint32_t b = 0; b < NB; ++b) {
     if (b < nb) {
-      const float4* src = (const float4*)(t.in + (size_t)(t.b0 + b) * t.ld_in);
-      float4* dst = (float4*)(xs + (size_t)b * K);
-      for (uint32_t i = threadIdx.x; i < K / 4; i += kThreads) dst[i] = src[i];
+      const float* src = t.in + (size_t)(t.b0 + b) * t.ld_in;
+      float2* dst = (float2*)(xs + (size_t)b * K);
+      for (uint32_t i = threadIdx.x; i < K / 2; i += kThreads) dst[i] = ld_act2(src + 2 * i);
     } else {
       float4* dst = (float4*)(xs + (size_t)b * K);
       for (uint32_t i = threadIdx.x; i < K / 4; i += kThreads) dst[i] = make_float4(0, 0, 0, 0);
@@ -212,7 +240,7 @@ __device__ void body_linear(const TaskDesc& t, const StepArgs& a, float* lds) {
           if (col[i] < t.c1) {
             for (uint32_t b = 0; b < nb; ++b) {
               float gte = acc[i][b], up = acc[i + 1][b];
-              outp[(size_t)(t.b0 + b) * t.ld_out + col[i]] = gte / (1.0f + expf(-gte)) * up;
+              st_act(outp + (size_t)(t.b0 + b) * t.ld_out + col[i], gte / (1.0f + expf(-gte)) * up);
             }
           }
         }
@@ -223,8 +251,8 @@ __device__ void body_linear(const TaskDesc& t, const StepArgs& a, float* lds) {
             for (uint32_t b = 0; b < nb; ++b) {
               float v = acc[i][b];
               size_t o = (size_t)(t.b0 + b) * t.ld_out + col[i];
-              if (t.flags & TF_EPI_RESID) v = t.in2[o] + v;
-              outp[o] = v;
+              if (t.flags & TF_EPI_RESID) v = ld_act(t.in2 + o) + v;
+              st_act(outp + o, v);
             }
           }
         }
@@ -246,29 +274,36 @@ __device__ void body_rope(const TaskDesc& t, const StepArgs& a) {
     }
     const float* src = t.in + (size_t)b * t.ld_in;
     float* dst = t.out + (size_t)b * t.ld_out;
-    for (uint32_t idx = threadIdx.x; idx < (s1 - s0) * half; idx += kThreads) {
-      uint32_t s = s0 + idx / half, i = idx % half;
-      float u0 = src[s * d + i], u1 = src[s * d + i + half];
-      float r0, r1;
+    // each thread owns two adjacent rotation pairs (i, i+1) so that cache rows are written as
+    // 4-byte (two bf16) coherent stores
+    for (uint32_t idx = threadIdx.x; idx < (s1 - s0) * (half / 2); idx += kThreads) {
+      uint32_t s = s0 + idx / (half / 2), i = 2 * (idx % (half / 2));
+      float2 lo = ld_act2(src + s * d + i), hi = ld_act2(src + s * d + i + half);
+      float r[4];   // lo.x, lo.y, hi.x, hi.y after rotation
       if (s < nq + nkv) {
-        double f = pow((double)t.f1, -2.0 * (double)i / (double)d);
-        double ang = (double)pos * f;
-        float c = (float)cos(ang), sn = (float)sin(ang);
-        r0 = u0 * c - u1 * sn;
-        r1 = u1 * c + u0 * sn;
+        float u0[2] = {lo.x, lo.y}, u1[2] = {hi.x, hi.y};
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          double f = pow((double)t.f1, -2.0 * (double)(i + e) / (double)d);
+          double ang = (double)pos * f;
+          float c = (float)cos(ang), sn = (float)sin(ang);
+          r[e] = u0[e] * c - u1[e] * sn;
+          r[2 + e] = u1[e] * c + u0[e] * sn;
+        }
       } else {
-        r0 = u0;
-        r1 = u1;
+        r[0] = lo.x; r[1] = lo.y; r[2] = hi.x; r[3] = hi.y;
       }
-      dst[s * d + i] = r0;
-      dst[s * d + i + half] = r1;
+      st_act(dst + s * d + i, r[0]);
+      st_act(dst + s * d + i + 1, r[1]);
+      st_act(dst + s * d + i + half, r[2]);
+      st_act(dst + s * d + i + half + 1, r[3]);
       if (s >= nq) {
         bool is_k = s < nq + nkv;
         uint32_t g = is_k ? s - nq : s - nq - nkv;
         uint16_t* cache = (uint16_t*)(is_k ? t.aux0 : t.aux1);
         uint16_t* row = cache + (((size_t)b * nkv + g) * a.max_seq + (uint32_t)pos) * d;
-        row[i] = f32_to_bf16(r0);
-        row[i + half] = f32_to_bf16(r1);
+        st_act_u32((uint32_t*)(row + i), (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16));
+        st_act_u32((uint32_t*)(row + i + half), (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16));
       }
     }
   }
@@ -291,14 +326,14 @@ __device__ void body_attn_partial(const TaskDesc& t, const StepArgs& a, float* l
   int32_t pos = a.positions[b];
   if (pos < 0 || (uint32_t)pos >= a.max_seq) {
     if (threadIdx.x == 0) report(a, DE_BAD_POSITION, b, (uint32_t)pos);
-    for (uint32_t i = threadIdx.x; i < per; i += kThreads) outp[i] = ((i % (d + 2)) == d) ? -INFINITY : 0.f;
+    for (uint32_t i = threadIdx.x; i < per; i += kThreads) st_act(outp + i, ((i % (d + 2)) == d) ? -INFINITY : 0.f);
     return;
   }
   const uint32_t len = (uint32_t)pos + 1;
   const uint32_t t0 = (uint32_t)((uint64_t)c * len / C), t1 = (uint32_t)((uint64_t)(c + 1) * len / C);
   const uint32_t n = t1 - t0;
   const float* qsrc = t.in + (size_t)b * t.ld_in + (size_t)g * grp * d;
-  for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) qs[i] = qsrc[i];
+  for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) qs[i] = ld_act(qsrc + i);
   __syncthreads();
   const uint16_t* Kb = (const uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.max_seq + t0) * d;
   const uint16_t* Vb = (const uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.max_seq + t0) * d;
@@ -309,7 +344,12 @@ __device__ void body_attn_partial(const TaskDesc& t, const StepArgs& a, float* l
   for (uint32_t base = wave * PPW; base < n; base += (kThreads / 64) * PPW) {
     uint32_t i = base + slot;
     bool valid = i < n;
-    u32x4 kv = valid ? *(const u32x4*)(Kb + (size_t)i * d + sub * 8) : u32x4{0, 0, 0, 0};
+    // the row appended during this step was written by another workgroup: coherent load
+    u32x4 kv = u32x4{0, 0, 0, 0};
+    if (valid) {
+      const uint16_t* kp = Kb + (size_t)i * d + sub * 8;
+      kv = (t0 + i == (uint32_t)pos) ? ld_row16_coherent(kp) : __builtin_nontemporal_load((const u32x4*)kp);
+    }
     for (uint32_t j = 0; j < grp; ++j) {
       const float4* qp = (const float4*)(qs + j * d + sub * 8);
       float s = dot8(kv, qp[0], qp[1], 0.f);
@@ -346,7 +386,8 @@ __device__ void body_attn_partial(const TaskDesc& t, const StepArgs& a, float* l
   for (uint32_t base = wave * PPW; base < n; base += (kThreads / 64) * PPW) {
     uint32_t i = base + slot;
     if (i < n) {
-      u32x4 vv = *(const u32x4*)(Vb + (size_t)i * d + sub * 8);
+      const uint16_t* vp = Vb + (size_t)i * d + sub * 8;
+      u32x4 vv = (t0 + i == (uint32_t)pos) ? ld_row16_coherent(vp) : __builtin_nontemporal_load((const u32x4*)vp);
       float v[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
                     bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
 #pragma unroll
@@ -375,11 +416,11 @@ __device__ void body_attn_partial(const TaskDesc& t, const StepArgs& a, float* l
     uint32_t j = i / d, dim = i % d;
     float s = 0.f;
     for (uint32_t w = 0; w < kThreads / 64; ++w) s += wpart[((size_t)w * grp + j) * d + dim];
-    outp[j * (d + 2) + dim] = s;
+    st_act(outp + j * (d + 2) + dim, s);
   }
   if (threadIdx.x < grp) {
-    outp[threadIdx.x * (d + 2) + d] = ml[threadIdx.x * 2];
-    outp[threadIdx.x * (d + 2) + d + 1] = ml[threadIdx.x * 2 + 1];
+    st_act(outp + threadIdx.x * (d + 2) + d, ml[threadIdx.x * 2]);
+    st_act(outp + threadIdx.x * (d + 2) + d + 1, ml[threadIdx.x * 2 + 1]);
   }
 }
 
@@ -393,15 +434,15 @@ __device__ void body_attn_merge(const TaskDesc& t, const StepArgs& a) {
     for (uint32_t idx = threadIdx.x; idx < (h1 - h0) * d; idx += kThreads) {
       uint32_t h = h0 + idx / d, dim = idx % d, g = h / grp, j = h % grp;
       float M = -INFINITY;
-      for (uint32_t c = 0; c < C; ++c) M = fmaxf(M, part[((size_t)(g * C + c) * grp + j) * (d + 2) + d]);
+      for (uint32_t c = 0; c < C; ++c) M = fmaxf(M, ld_act(part + ((size_t)(g * C + c) * grp + j) * (d + 2) + d));
       float L = 0.f, o = 0.f;
       for (uint32_t c = 0; c < C; ++c) {
         const float* p = part + ((size_t)(g * C + c) * grp + j) * (d + 2);
-        float wgt = expf(p[d] - M);   // exp(-inf) = 0 for empty chunks
-        L = fmaf(wgt, p[d + 1], L);
-        o = fmaf(wgt, p[dim], o);
+        float wgt = expf(ld_act(p + d) - M);   // exp(-inf) = 0 for empty chunks
+        L = fmaf(wgt, ld_act(p + d + 1), L);
+        o = fmaf(wgt, ld_act(p + dim), o);
       }
-      out[h * d + dim] = o / L;
+      st_act(out + h * d + dim, o / L);
     }
   }
 }
@@ -411,7 +452,7 @@ __device__ void body_add(const TaskDesc& t) {
   for (uint32_t b = t.b0; b < t.b1; ++b)
     for (uint32_t i = threadIdx.x; i < nc; i += kThreads) {
       size_t o = (size_t)b * t.ld_out + t.c0 + i;
-      t.out[o] = t.in[o] + t.in2[o];
+      st_act(t.out + o, ld_act(t.in + o) + ld_act(t.in2 + o));
     }
 }
 
@@ -420,8 +461,8 @@ __device__ void body_swiglu(const TaskDesc& t) {
   for (uint32_t b = t.b0; b < t.b1; ++b)
     for (uint32_t i = threadIdx.x; i < nc; i += kThreads) {
       const float* gu = t.in + (size_t)b * t.ld_in;
-      float gte = gu[t.c0 + i], up = gu[F + t.c0 + i];
-      t.out[(size_t)b * t.ld_out + t.c0 + i] = gte / (1.0f + expf(-gte)) * up;
+      float gte = ld_act(gu + t.c0 + i), up = ld_act(gu + F + t.c0 + i);
+      st_act(t.out + (size_t)b * t.ld_out + t.c0 + i, gte / (1.0f + expf(-gte)) * up);
     }
 }
 
@@ -475,14 +516,14 @@ __device__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag) {
     }
     *s_flag = ok;
   }
-  __syncthreads();
-  uint32_t ok = *s_flag;
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-  return ok != 0;
+  __syncthreads();   // later agent-scope loads cannot move above this barrier
+  return *s_flag != 0;
 }
 
 __device__ void signal_event(const StepArgs& a, int32_t e) {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // every wavefront publishes its stores
+  // every wavefront waits until its own agent-scope stores have completed at the coherence point
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (threadIdx.x == 0)
     __hip_atomic_fetch_add(a.counters + e, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
