@@ -158,26 +158,72 @@ __device__ void body_rmsnorm(const TaskDesc& t, float* lds) {
   }
 }
 
+__device__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag);
+
 // T2/T6/T9/T11/T14: y[b][c] = sum_j W[c][j] x[b][j] for output columns [c0, c1), all batch rows
-// at once.  The input rows are staged in LDS (fp32); every wavefront owns groups of RW weight
-// rows and streams them with 16-byte loads, 64 lanes x 8 bf16 = 512 input elements per step.
+// at once.  Every wavefront owns groups of RW weight rows (groups wave, wave+8, ...) and walks
+// them in blocks of RW rows x KU chunks, a chunk being 64 lanes x 16 bytes = 512 input elements.
+// The RW*KU 16-byte loads of a block live in a register ring: each slot is refilled with the same
+// slot of the NEXT block right after it has been consumed, so a full block per lane (RW*KU*16
+// bytes, 128-256 KB per CU) is always in flight.
+// Cross-task pre-loading (paper Section 5.3): the first block is requested BEFORE the task waits
+// for its dependent event -- weights never depend on an event -- so the weight stream keeps
+// flowing while the input vector is still being produced elsewhere.
 // Optional stages: RMSNorm of the input (TF_PRO_NORM), residual add (TF_EPI_RESID), fused
 // silu(gate) * up (TF_GATEUP: column c needs weight rows c and F + c).
-template <int NB, int RW>
-__device__ void body_linear(const TaskDesc& t, const StepArgs& a, float* lds) {
+template <int NB, int RW, int KU>
+__device__ bool body_linear(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
+                            uint32_t* s_flag) {
   const uint32_t K = t.K, nb = t.b1 - t.b0;
   float* xs = lds;                 // [NB][K]
   float* red = lds + (size_t)NB * K;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  // ---- stage the input rows
+  constexpr uint32_t NW = kThreads / 64;
+  const bool gateup = t.flags & TF_GATEUP;
+  const uint32_t ncols = t.c1 - t.c0;
+  const uint32_t G = gateup ? RW / 2 : RW;          // output columns per group
+  const uint32_t ngroups = (ncols + G - 1) / G;
+  const uint32_t nkb = (K + 512 * KU - 1) / (512 * KU);   // blocks per group
+  const uint16_t* W = (const uint16_t*)t.w;
+
+  auto row_ptrs = [&](uint32_t grp, const uint16_t* (&rp)[RW]) {
+#pragma unroll
+    for (int i = 0; i < RW; ++i) {
+      uint32_t c = t.c0 + grp * G + (gateup ? (i >> 1) : i);
+      uint32_t cc = c < t.c1 ? c : t.c1 - 1;   // masked rows re-read a valid row (result dropped)
+      uint32_t row = gateup ? ((i & 1) ? t.p0 + cc : cc) : cc;
+      rp[i] = W + (size_t)row * K + lane * 8;
+    }
+  };
+
+  u32x4 ring[RW][KU];
+#pragma unroll
+  for (int i = 0; i < RW; ++i)
+#pragma unroll
+    for (int u = 0; u < KU; ++u) ring[i][u] = u32x4{0, 0, 0, 0};
+  uint32_t grp = wave, kb = 0;
+  bool have = grp < ngroups;
+  if (have) {
+    const uint16_t* rp[RW];
+    row_ptrs(grp, rp);
+#pragma unroll
+    for (int u = 0; u < KU; ++u) {
+      uint32_t k = (uint32_t)u * 512 + lane * 8;
+      if (k < K) {
+#pragma unroll
+        for (int i = 0; i < RW; ++i) ring[i][u] = __builtin_nontemporal_load((const u32x4*)(rp[i] + (size_t)u * 512));
+      }
+    }
+  }
+  // ---- the input vector: only now does the task need its dependent event
+  if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
   for (uint32_t b = 0; b < NB; ++b) {
+    float2* dst = (float2*)(xs + (size_t)b * K);
     if (b < nb) {
       const float* src = t.in + (size_t)(t.b0 + b) * t.ld_in;
-      float2* dst = (float2*)(xs + (size_t)b * K);
       for (uint32_t i = threadIdx.x; i < K / 2; i += kThreads) dst[i] = ld_act2(src + 2 * i);
     } else {
-      float4* dst = (float4*)(xs + (size_t)b * K);
-      for (uint32_t i = threadIdx.x; i < K / 4; i += kThreads) dst[i] = make_float4(0, 0, 0, 0);
+      for (uint32_t i = threadIdx.x; i < K / 2; i += kThreads) dst[i] = make_float2(0.f, 0.f);
     }
   }
   __syncthreads();
@@ -194,71 +240,82 @@ __device__ void body_linear(const TaskDesc& t, const StepArgs& a, float* lds) {
     __syncthreads();
   }
   // ---- stream the weight rows
-  const bool gateup = t.flags & TF_GATEUP;
-  const uint32_t ncols = t.c1 - t.c0;
-  const uint32_t G = gateup ? RW / 2 : RW;          // output columns per group
-  const uint32_t ngroups = (ncols + G - 1) / G;
-  const uint16_t* W = (const uint16_t*)t.w;
   float* outp = (t.flags & TF_OUT_LOGITS) ? a.logits : t.out;
-  for (uint32_t grp = wave; grp < ngroups; grp += kThreads / 64) {
-    const uint16_t* wp[RW];
-    uint32_t col[RW];
+  float acc[RW][NB];
 #pragma unroll
-    for (int i = 0; i < RW; ++i) {
-      uint32_t c = t.c0 + grp * G + (gateup ? (i >> 1) : i);
-      col[i] = c;
-      uint32_t cc = c < t.c1 ? c : t.c1 - 1;   // clamp: masked rows re-read a valid row
-      uint32_t row = gateup ? ((i & 1) ? t.p0 + cc : cc) : cc;
-      wp[i] = W + (size_t)row * K;
+  for (int i = 0; i < RW; ++i)
+#pragma unroll
+    for (int b = 0; b < NB; ++b) acc[i][b] = 0.f;
+  while (have) {
+    uint32_t ngrp = grp, nkb_i = kb + 1;
+    if (nkb_i == nkb) {
+      nkb_i = 0;
+      ngrp = grp + NW;
     }
-    float acc[RW][NB];
+    const bool nhave = ngrp < ngroups;
+    const uint16_t* np[RW];
+    row_ptrs(nhave ? ngrp : grp, np);
 #pragma unroll
-    for (int i = 0; i < RW; ++i)
+    for (int u = 0; u < KU; ++u) {
+      const uint32_t k = (kb * KU + u) * 512 + lane * 8;
+      const uint32_t nk = (nkb_i * KU + u) * 512 + lane * 8;
+      if (k < K) {
 #pragma unroll
-      for (int b = 0; b < NB; ++b) acc[i][b] = 0.f;
-#pragma unroll 2
-    for (uint32_t k = lane * 8; k < K; k += 512) {
-      u32x4 wv[RW];
+        for (int b = 0; b < NB; ++b) {
+          const float4* xp = (const float4*)(xs + (size_t)b * K + k);
+          float4 x0 = xp[0], x1 = xp[1];
 #pragma unroll
-      for (int i = 0; i < RW; ++i) wv[i] = __builtin_nontemporal_load((const u32x4*)(wp[i] + k));
+          for (int i = 0; i < RW; ++i) acc[i][b] = dot8(ring[i][u], x0, x1, acc[i][b]);
+        }
+      }
+      if (nhave && nk < K) {
 #pragma unroll
-      for (int b = 0; b < NB; ++b) {
-        const float4* xp = (const float4*)(xs + (size_t)b * K + k);
-        float4 x0 = xp[0], x1 = xp[1];
-#pragma unroll
-        for (int i = 0; i < RW; ++i) acc[i][b] = dot8(wv[i], x0, x1, acc[i][b]);
+        for (int i = 0; i < RW; ++i)
+          ring[i][u] = __builtin_nontemporal_load((const u32x4*)(np[i] + (size_t)(nkb_i * KU + u) * 512));
       }
     }
+    if (nkb_i == 0) {   // the group is complete: reduce across lanes and write its columns
 #pragma unroll
-    for (int i = 0; i < RW; ++i)
+      for (int i = 0; i < RW; ++i)
 #pragma unroll
-      for (int b = 0; b < NB; ++b) acc[i][b] = wave_sum(acc[i][b]);
-    if (lane == 0) {
-      if (gateup) {
+        for (int b = 0; b < NB; ++b) acc[i][b] = wave_sum(acc[i][b]);
+      if (lane == 0) {
+        if (gateup) {
 #pragma unroll
-        for (int i = 0; i < RW; i += 2) {
-          if (col[i] < t.c1) {
-            for (uint32_t b = 0; b < nb; ++b) {
-              float gte = acc[i][b], up = acc[i + 1][b];
-              st_act(outp + (size_t)(t.b0 + b) * t.ld_out + col[i], gte / (1.0f + expf(-gte)) * up);
+          for (int i = 0; i < RW; i += 2) {
+            uint32_t col = t.c0 + grp * G + (i >> 1);
+            if (col < t.c1) {
+              for (uint32_t b = 0; b < nb; ++b) {
+                float gte = acc[i][b], up = acc[i + 1][b];
+                st_act(outp + (size_t)(t.b0 + b) * t.ld_out + col, gte / (1.0f + expf(-gte)) * up);
+              }
+            }
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < RW; ++i) {
+            uint32_t col = t.c0 + grp * G + i;
+            if (col < t.c1) {
+              for (uint32_t b = 0; b < nb; ++b) {
+                float v = acc[i][b];
+                size_t o = (size_t)(t.b0 + b) * t.ld_out + col;
+                if (t.flags & TF_EPI_RESID) v = ld_act(t.in2 + o) + v;
+                st_act(outp + o, v);
+              }
             }
           }
         }
-      } else {
-#pragma unroll
-        for (int i = 0; i < RW; ++i) {
-          if (col[i] < t.c1) {
-            for (uint32_t b = 0; b < nb; ++b) {
-              float v = acc[i][b];
-              size_t o = (size_t)(t.b0 + b) * t.ld_out + col[i];
-              if (t.flags & TF_EPI_RESID) v = ld_act(t.in2 + o) + v;
-              st_act(outp + o, v);
-            }
-          }
-        }
       }
+#pragma unroll
+      for (int i = 0; i < RW; ++i)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) acc[i][b] = 0.f;
     }
+    grp = ngrp;
+    kb = nkb_i;
+    have = nhave;
   }
+  return true;
 }
 
 // T3: rotate q and k heads by the sequence position (half-split pairing), copy v, and append the
@@ -466,18 +523,26 @@ __device__ void body_swiglu(const TaskDesc& t) {
     }
 }
 
-__device__ void run_task(const TaskDesc& t, const StepArgs& a, float* lds) {
+// Runs one task.  wait_ev >= 0: the task must first wait for that event (persistent kernel);
+// linear tasks do so after requesting their first weight block.  Returns false on abort.
+__device__ bool run_task(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
+                         uint32_t* s_flag) {
+  if (t.kind == TK_LINEAR) {
+    const uint32_t nb = t.b1 - t.b0;
+    const uint32_t G = (t.flags & TF_GATEUP) ? 2u : 1u;
+    const uint32_t rows_per_wave = ((t.c1 - t.c0) * G + kThreads / 64 - 1) / (kThreads / 64);
+    if (nb == 1) {
+      if (rows_per_wave <= 2) return body_linear<1, 2, 8>(t, a, lds, wait_ev, s_flag);
+      return body_linear<1, 4, 8>(t, a, lds, wait_ev, s_flag);
+    }
+    if (nb == 2) return body_linear<2, 4, 4>(t, a, lds, wait_ev, s_flag);
+    if (nb <= 4) return body_linear<4, 2, 4>(t, a, lds, wait_ev, s_flag);
+    return body_linear<8, 2, 4>(t, a, lds, wait_ev, s_flag);
+  }
+  if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
   switch (t.kind) {
     case TK_EMBED: body_embed(t, a); break;
     case TK_RMSNORM: body_rmsnorm(t, lds); break;
-    case TK_LINEAR: {
-      uint32_t nb = t.b1 - t.b0;
-      if (nb == 1) body_linear<1, 4>(t, a, lds);
-      else if (nb == 2) body_linear<2, 4>(t, a, lds);
-      else if (nb <= 4) body_linear<4, 2>(t, a, lds);
-      else body_linear<8, 2>(t, a, lds);
-      break;
-    }
     case TK_ROPE: body_rope(t, a); break;
     case TK_ATTN_PARTIAL: body_attn_partial(t, a, lds); break;
     case TK_ATTN_MERGE: body_attn_merge(t, a); break;
@@ -485,6 +550,7 @@ __device__ void run_task(const TaskDesc& t, const StepArgs& a, float* lds) {
     case TK_SWIGLU: body_swiglu(t); break;
     default: break;   // TK_DUMMY: no computation (normalization, Section 4.1)
   }
+  return true;
 }
 
 // ------------------------------------------------------------------------------ runtime
@@ -538,10 +604,8 @@ mpk_mega_kernel(StepArgs a) {
   const uint32_t q0 = a.aot_off[w], q1 = a.aot_off[w + 1];
   for (uint32_t qi = q0; qi < q1; ++qi) {
     const TaskDesc& t = a.tasks[a.aot[qi]];
-    if (t.dep_event >= 0 && a.events[t.dep_event].required != 0) {
-      if (!wait_event(a, t.dep_event, &s_flag)) break;
-    }
-    run_task(t, a, lds);
+    const int32_t wait_ev = (t.dep_event >= 0 && a.events[t.dep_event].required != 0) ? t.dep_event : -1;
+    if (!run_task(t, a, lds, wait_ev, &s_flag)) break;
     if (t.trig_event >= 0) signal_event(a, t.trig_event);
     else __syncthreads();
   }
@@ -553,7 +617,7 @@ extern "C" __global__ void __launch_bounds__(kThreads)
 mpk_op_kernel(StepArgs a, uint32_t first) {
   extern __shared__ __align__(16) float lds[];
   const TaskDesc& t = a.tasks[a.op_list[first + blockIdx.x]];
-  run_task(t, a, lds);
+  run_task(t, a, lds, -1, nullptr);
 }
 
 }  // namespace mpk
