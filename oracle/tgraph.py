@@ -170,9 +170,10 @@ def read_elements(op: OpSpec, tb: int, tc: int, tile: int, shapes: dict):
         for u in range(c0 // per, c1 // per):
             g, c = divmod(u, C)
             m[b0:b1, g * grp * d:(g + 1) * grp * d] = True         # the group's query heads
-            if c == C - 1:                                         # chunk holding the new row
-                m[b0:b1, (nq + g) * d:(nq + g + 1) * d] = True          # this step's key
-                m[b0:b1, (nq + nkv + g) * d:(nq + nkv + g + 1) * d] = True   # this step's value
+            # this step's key and value of the KV head: which chunk holds the appended row is
+            # only known at run time, so every chunk task statically depends on it
+            m[b0:b1, (nq + g) * d:(nq + g + 1) * d] = True
+            m[b0:b1, (nq + nkv + g) * d:(nq + nkv + g + 1) * d] = True
     elif k == K_ATTN_MERGE:
         M = op.meta
         C, grp, d = M["C"], M["grp"], M["d"]

@@ -12,6 +12,7 @@
 //
 // Integer-only; runs once per mpk_compile.
 #include <algorithm>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -421,7 +422,7 @@ static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
     int qkv = b.new_tensor(B, QKV);
     {
       HostOp& op = b.add(MPK_OP_LINEAR, l, "qkv", qkv, 1, qkv_in);
-      op.w = lw.wqkv; op.K = H;
+      op.w = lw.wqkv; op.K = H; op.align_unit = d;
       if (f & MPK_FUSE_NORM) { op.flags |= TF_PRO_NORM; op.w2 = lw.attn_norm; op.f0 = c.rms_eps; }
     }
     int qsrc = qkv;
@@ -437,24 +438,32 @@ static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
       op.p0 = l; op.p1 = C; op.f1 = c.rope_theta;
       if (f & MPK_FUSE_ROPE) op.flags |= TF_ROPE_FUSED;
     }
-    int osrc = part;
+    int osrc = part, o_body = -1;
     uint32_t oK = nq * d;
     if (!(f & MPK_FUSE_MERGE)) {
       int ot = b.new_tensor(B, nq * d);
       HostOp& op = b.add(MPK_OP_ATTN_MERGE, l, "attn_merge", ot, d, part);
       op.p1 = C;
       osrc = ot;
+    } else {
+      // The chunk task that finishes last for a (sequence, KV head) merges the partials into o;
+      // the O projection depends on the partial buffer (all chunk tasks) and loads o.
+      o_body = b.new_tensor(B, nq * d);
+      HostOp& at = g.ops.back();
+      at.flags |= TF_ATTN_MERGE;
+      at.side_out_tensor = o_body;
+      at.p2 = l * B * nkv;   // first arrival counter of this layer
     }
     int x1 = b.new_tensor(B, H);
     if (f & MPK_FUSE_RESID) {
       HostOp& op = b.add(MPK_OP_LINEAR, l, "o_proj", x1, 1, osrc, x);
       op.w = lw.wo; op.K = oK; op.flags |= TF_EPI_RESID;
-      if (f & MPK_FUSE_MERGE) { op.flags |= TF_PRO_MERGE; op.p1 = C; }
+      op.body_in_tensor = o_body;
     } else {
       int a = b.new_tensor(B, H);
       HostOp& op = b.add(MPK_OP_LINEAR, l, "o_proj", a, 1, osrc);
       op.w = lw.wo; op.K = oK;
-      if (f & MPK_FUSE_MERGE) { op.flags |= TF_PRO_MERGE; op.p1 = C; }
+      op.body_in_tensor = o_body;
       b.add(MPK_OP_ADD, l, "resid1", x1, 1, x, a);
     }
     int gin = x1;
@@ -531,6 +540,17 @@ static void choose_partitions(const mpk_model_config& c, const mpk_compile_optio
         uint32_t cap = std::max(1u, nu / 8);   // at least 8 output rows per task
         op.tb = 1;
         op.tc = std::max(1u, std::min(want, cap));
+        if (op.align_unit && nu % op.align_unit == 0) {
+          // QKV projection: tiles that never straddle a head keep every tile in exactly one
+          // attention group's producer set (no fork, hence no dummy tasks).  Pick the smallest
+          // rows-per-tile that divides head_dim and needs no more than `want` tiles.
+          for (uint32_t rows = 8; rows <= op.align_unit; rows += 8) {
+            if (op.align_unit % rows == 0 && nu / rows <= std::max(want, nu / op.align_unit)) {
+              op.tc = nu / rows;
+              break;
+            }
+          }
+        }
         break;
       }
       case MPK_OP_ROPE:
@@ -585,11 +605,13 @@ static void input_rects(const mpk_model_config& c, const HostOp& op, uint32_t ti
       uint32_t per = grp * (d + 2), C = op.p1;
       for (uint32_t u = c0 / per; u < c1 / per; ++u) {
         uint32_t gidx = u / C, ch = u % C;
+        (void)ch;
+        // every chunk task waits for the group's query heads AND this step's key/value of its KV
+        // head: which chunk holds the appended row is a run-time fact, so the static set is the
+        // superset (it also keeps all chunk tasks of a group on one event)
         out.push_back({op.in_tensor, b0, b1, gidx * grp * d, (gidx + 1) * grp * d});
-        if (ch == C - 1) {
-          out.push_back({op.in_tensor, b0, b1, (nq + gidx) * d, (nq + gidx + 1) * d});
-          out.push_back({op.in_tensor, b0, b1, (nq + nkv + gidx) * d, (nq + nkv + gidx + 1) * d});
-        }
+        out.push_back({op.in_tensor, b0, b1, (nq + gidx) * d, (nq + gidx + 1) * d});
+        out.push_back({op.in_tensor, b0, b1, (nq + nkv + gidx) * d, (nq + nkv + gidx + 1) * d});
       }
       break;
     }
@@ -695,10 +717,13 @@ static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGr
     t.K = op.K;
     t.w = op.w; t.w2 = op.w2; t.f0 = op.f0; t.f1 = op.f1;
     t.p0 = op.p0; t.p1 = op.p1; t.p2 = op.p2; t.p3 = op.p3;
-    t.in = act_ref(g, op.in_tensor);
-    t.in2 = act_ref(g, op.in2_tensor);
+    t.in = act_ref(g, op.body_in_tensor >= 0 ? op.body_in_tensor : op.in_tensor);
+    t.in2 = act_ref(g, op.side_out_tensor >= 0 ? op.side_out_tensor : op.in2_tensor);
     t.out = const_cast<float*>(act_ref(g, op.out_tensor));
-    t.ld_in = op.in_tensor >= 0 ? g.tensors[op.in_tensor].cols : 0;
+    {
+      int it = op.body_in_tensor >= 0 ? op.body_in_tensor : op.in_tensor;
+      t.ld_in = it >= 0 ? g.tensors[it].cols : 0;
+    }
     t.ld_out = op.cols;
     switch (op.kind) {
       case MPK_OP_EMBED: t.kind = TK_EMBED; break;
@@ -754,7 +779,6 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
   if (c.batch > 8) { set_error("batch %u unsupported by the dense linear bodies (max 8)", c.batch); return MPK_ERR_UNSUPPORTED; }
   if (o.debug_flags) { set_error("debug_flags must be 0"); return MPK_ERR_INVALID_ARG; }
   if (o.fusion & ~(MPK_FUSE_NORM | MPK_FUSE_RESID | MPK_FUSE_SWIGLU | MPK_FUSE_MERGE | MPK_FUSE_ROPE)) { set_error("unknown fusion bits"); return MPK_ERR_INVALID_ARG; }
-  if (o.fusion & (MPK_FUSE_MERGE | MPK_FUSE_ROPE)) { set_error("MPK_FUSE_MERGE / MPK_FUSE_ROPE are not implemented yet"); return MPK_ERR_UNSUPPORTED; }
   if (!o.host_only) {
     if (!w || !kv || !w->layers) { set_error("weights / kv pointers are NULL"); return MPK_ERR_INVALID_ARG; }
     auto bad = [](const void* p) { return p == nullptr || ((uintptr_t)p & 15u); };
@@ -776,8 +800,8 @@ mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs*
   if (opt.n_workers == 0) { set_error("n_workers unresolved"); return MPK_ERR_INTERNAL; }
   uint32_t C = opt.attn_chunks;
   if (C == 0) {
-    C = std::max(1u, opt.n_workers / (cfg.batch * cfg.n_kv_heads));
-    C = std::min(C, std::max(1u, cfg.max_seq / 32));
+    C = std::max(1u, opt.n_workers / (2 * cfg.batch * cfg.n_kv_heads));
+    C = std::min(C, std::max(1u, cfg.max_seq / 64));
     C = std::min(C, 64u);
   }
   if (C > 64) { set_error("attn_chunks %u too large (max 64)", C); return MPK_ERR_INVALID_ARG; }
@@ -787,6 +811,10 @@ mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs*
   st = build_ops(cfg, w, opt, C, g);
   if (st != MPK_OK) return st;
   choose_partitions(cfg, opt, g);
+  g.n_group_counters = cfg.n_layers * cfg.batch * cfg.n_kv_heads;
+  g.inv_freq.resize(cfg.head_dim / 2);
+  for (uint32_t i = 0; i < cfg.head_dim / 2; ++i)
+    g.inv_freq[i] = std::pow((double)cfg.rope_theta, -2.0 * (double)i / (double)cfg.head_dim);
   PassInput pi;
   dependency_analysis(cfg, g, pi);
   label_ops(g, pi, pi.op_jit);   // labels follow the paper's rule on the full dependency sets

@@ -33,6 +33,8 @@ enum TaskFlags : uint16_t {
   TF_GATEUP = 8,      // linear: out_c = silu(W[c] x) * (W[F + c] x), F = p0
   TF_OUT_LOGITS = 16, // output pointer is the caller's logits buffer of this step
   TF_ROPE_FUSED = 32, // attention: rotate q (and the new k) itself, append k/v itself
+  TF_ATTN_MERGE = 64, // attention: the last chunk task of a (sequence, KV head) to finish merges
+                      // all chunk partials into the attention output (in2), counter index p2
 };
 
 struct alignas(16) TaskDesc {
@@ -70,7 +72,10 @@ struct HostOp {
   uint32_t jit;
   // tensors
   int out_tensor;
-  int in_tensor, in2_tensor;   // -1 if none
+  int in_tensor, in2_tensor;   // -1 if none (dependency analysis reads these)
+  int body_in_tensor = -1;     // tensor the body actually loads when it differs from in_tensor
+  int side_out_tensor = -1;    // second output written by the body (merged attention output)
+  uint32_t align_unit = 0;     // linear: tile rows must divide this (head_dim) when non-zero
   // parameters
   uint32_t K;
   uint16_t flags;
@@ -105,6 +110,8 @@ struct HostGraph {
   uint32_t n_real = 0, start_event = 0, terminal_event = 0;
   size_t arena_floats = 0;
   uint32_t lds_bytes = 0;
+  uint32_t n_group_counters = 0;   // per (layer, sequence, KV head) arrival counters
+  std::vector<double> inv_freq;    // RoPE frequencies theta^(-2i/d), i < d/2
   mpk_stats stats{};
 };
 

@@ -41,6 +41,8 @@ struct StepArgs {
   const int32_t* positions;
   float* logits;
   uint32_t* err;   // [0] error code, [1] abort flag, [2..3] detail
+  const double* inv_freq;    // RoPE frequencies theta^(-2i/d), i < head_dim / 2
+  uint32_t* grp_counters;    // arrival counters per (layer, sequence, KV head), monotonic
   uint64_t timeout_ticks;
   uint32_t epoch, n_workers;
   uint32_t vocab, max_seq, n_q, n_kv, head_dim, batch;
@@ -318,6 +320,17 @@ __device__ bool body_linear(const TaskDesc& t, const StepArgs& a, float* lds, in
   return true;
 }
 
+// cos and sin of position * inv_freq[i]: the angle is formed and reduced to [-pi, pi] in double.
+__device__ __forceinline__ void rope_cs(const StepArgs& a, int32_t pos, uint32_t i, float* c, float* s) {
+  double ang = (double)pos * a.inv_freq[i];
+  const double two_pi = 6.283185307179586476925286766559;
+  ang -= two_pi * rint(ang / two_pi);
+  double sd, cd;
+  sincos(ang, &sd, &cd);
+  *c = (float)cd;
+  *s = (float)sd;
+}
+
 // T3: rotate q and k heads by the sequence position (half-split pairing), copy v, and append the
 // new k and v rows to the cache as bf16.  Angles are evaluated in double precision.
 __device__ void body_rope(const TaskDesc& t, const StepArgs& a) {
@@ -341,9 +354,8 @@ __device__ void body_rope(const TaskDesc& t, const StepArgs& a) {
         float u0[2] = {lo.x, lo.y}, u1[2] = {hi.x, hi.y};
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-          double f = pow((double)t.f1, -2.0 * (double)(i + e) / (double)d);
-          double ang = (double)pos * f;
-          float c = (float)cos(ang), sn = (float)sin(ang);
+          float c, sn;
+          rope_cs(a, pos, i + e, &c, &sn);
           r[e] = u0[e] * c - u1[e] * sn;
           r[2 + e] = u1[e] * c + u0[e] * sn;
         }
@@ -390,7 +402,45 @@ __device__ void body_attn_partial(const TaskDesc& t, const StepArgs& a, float* l
   const uint32_t t0 = (uint32_t)((uint64_t)c * len / C), t1 = (uint32_t)((uint64_t)(c + 1) * len / C);
   const uint32_t n = t1 - t0;
   const float* qsrc = t.in + (size_t)b * t.ld_in + (size_t)g * grp * d;
-  for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) qs[i] = ld_act(qsrc + i);
+  if (t.flags & TF_ROPE_FUSED) {
+    // the input is the raw QKV projection: rotate the group's query heads here; the task of the
+    // last chunk also rotates this step's key, and appends key and value to the cache
+    const uint32_t half = d / 2;
+    for (uint32_t i = threadIdx.x; i < grp * half; i += kThreads) {
+      uint32_t j = i / half, e = i % half;
+      float u0 = ld_act(qsrc + j * d + e), u1 = ld_act(qsrc + j * d + e + half), cs, sn;
+      rope_cs(a, pos, e, &cs, &sn);
+      qs[j * d + e] = u0 * cs - u1 * sn;
+      qs[j * d + e + half] = u1 * cs + u0 * sn;
+    }
+    if (c == C - 1) {
+      const float* ksrc = t.in + (size_t)b * t.ld_in + (size_t)(nq + g) * d;
+      const float* vsrc = t.in + (size_t)b * t.ld_in + (size_t)(nq + nkv + g) * d;
+      uint16_t* krow = (uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.max_seq + (uint32_t)pos) * d;
+      uint16_t* vrow = (uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.max_seq + (uint32_t)pos) * d;
+      for (uint32_t i = threadIdx.x; i < half / 2 + half; i += kThreads) {
+        if (i < half / 2) {   // two adjacent rotation pairs of the key
+          uint32_t e = 2 * i;
+          float2 lo = ld_act2(ksrc + e), hi = ld_act2(ksrc + e + half);
+          float c0, s0, c1, s1;
+          rope_cs(a, pos, e, &c0, &s0);
+          rope_cs(a, pos, e + 1, &c1, &s1);
+          float r0 = lo.x * c0 - hi.x * s0, r1 = lo.y * c1 - hi.y * s1;
+          float r2 = hi.x * c0 + lo.x * s0, r3 = hi.y * c1 + lo.y * s1;
+          st_act_u32((uint32_t*)(krow + e), (uint32_t)f32_to_bf16(r0) | ((uint32_t)f32_to_bf16(r1) << 16));
+          st_act_u32((uint32_t*)(krow + e + half), (uint32_t)f32_to_bf16(r2) | ((uint32_t)f32_to_bf16(r3) << 16));
+        } else {              // two adjacent value elements
+          uint32_t e = 2 * (i - half / 2);
+          float2 v2 = ld_act2(vsrc + e);
+          st_act_u32((uint32_t*)(vrow + e), (uint32_t)f32_to_bf16(v2.x) | ((uint32_t)f32_to_bf16(v2.y) << 16));
+        }
+      }
+      // the appended row is read back below with coherent loads: the stores must have completed
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+  } else {
+    for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) qs[i] = ld_act(qsrc + i);
+  }
   __syncthreads();
   const uint16_t* Kb = (const uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.max_seq + t0) * d;
   const uint16_t* Vb = (const uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.max_seq + t0) * d;
@@ -478,6 +528,37 @@ __device__ void body_attn_partial(const TaskDesc& t, const StepArgs& a, float* l
   if (threadIdx.x < grp) {
     st_act(outp + threadIdx.x * (d + 2) + d, ml[threadIdx.x * 2]);
     st_act(outp + threadIdx.x * (d + 2) + d + 1, ml[threadIdx.x * 2 + 1]);
+  }
+  if (t.flags & TF_ATTN_MERGE) {
+    // Arrival counter of (layer, sequence, KV head): the chunk task that arrives last sees all C
+    // partials complete and merges them (log-sum-exp) into the attention output.
+    uint32_t* flag = (uint32_t*)(ml + 2 * 8);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint32_t* cnt = a.grp_counters + t.p2 + b * nkv + g;
+      uint32_t old = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      *flag = ((old + 1u) % C == 0u) ? 1u : 0u;   // every step adds exactly C
+    }
+    __syncthreads();
+    if (*flag) {
+      const float* part = t.out + (size_t)b * t.ld_out + (size_t)g * C * per;
+      float* o = const_cast<float*>(t.in2) + (size_t)b * nq * d + (size_t)g * grp * d;
+      for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) {
+        uint32_t j = i / d, dim = i % d;
+        float M = -INFINITY;
+        for (uint32_t cc = 0; cc < C; ++cc) M = fmaxf(M, ld_act(part + ((size_t)cc * grp + j) * (d + 2) + d));
+        float L = 0.f, acc_o = 0.f;
+        for (uint32_t cc = 0; cc < C; ++cc) {
+          const float* pp = part + ((size_t)cc * grp + j) * (d + 2);
+          float wgt = expf(ld_act(pp + d) - M);
+          L = fmaf(wgt, ld_act(pp + d + 1), L);
+          acc_o = fmaf(wgt, ld_act(pp + dim), acc_o);
+        }
+        st_act(o + i, acc_o / L);
+      }
+    }
   }
 }
 
@@ -637,6 +718,8 @@ struct mpk_graph {
   uint32_t* d_aot = nullptr;
   uint32_t* d_op_list = nullptr;
   uint32_t* d_err = nullptr;
+  double* d_inv_freq = nullptr;
+  uint32_t* d_grp = nullptr;
   float* d_arena = nullptr;
   std::vector<uint32_t> op_first, op_count;   // per operator: range in op_list
   uint32_t epoch = 0;
@@ -657,6 +740,7 @@ static void free_device(mpk_graph* g) {
   (void)hipFree(g->d_tasks); (void)hipFree(g->d_events); (void)hipFree(g->d_counters);
   (void)hipFree(g->d_aot_off); (void)hipFree(g->d_aot); (void)hipFree(g->d_op_list);
   (void)hipFree(g->d_err); (void)hipFree(g->d_arena);
+  (void)hipFree(g->d_inv_freq); (void)hipFree(g->d_grp);
 }
 
 static mpk_status resolve_options(const mpk_compile_options* in, mpk_compile_options* out,
@@ -772,6 +856,11 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
   if ((st = upload(&g->d_aot, h.aot)) != MPK_OK) return fail(st);
   if ((st = upload(&g->d_op_list, op_list)) != MPK_OK) return fail(st);
   if ((st = upload(&g->d_err, err)) != MPK_OK) return fail(st);
+  if ((st = upload(&g->d_inv_freq, h.inv_freq)) != MPK_OK) return fail(st);
+  {
+    std::vector<uint32_t> gz(h.n_group_counters, 0);
+    if ((st = upload(&g->d_grp, gz)) != MPK_OK) return fail(st);
+  }
   g->timeout_ticks = (uint64_t)o.spin_timeout_ms * 100000ull;   // wall clock counts at 100 MHz
   *out = g;
   return MPK_OK;
@@ -806,12 +895,13 @@ extern "C" mpk_status mpk_decode_step(mpk_graph* g, const int32_t* token_ids,
   a.aot_off = g->d_aot_off; a.aot = g->d_aot; a.op_list = g->d_op_list;
   a.token_ids = token_ids; a.positions = positions; a.logits = logits_out; a.err = g->d_err;
   a.timeout_ticks = g->timeout_ticks;
+  a.inv_freq = g->d_inv_freq; a.grp_counters = g->d_grp;
   a.n_workers = h.opt.n_workers;
   a.vocab = h.cfg.vocab; a.max_seq = h.cfg.max_seq; a.n_q = h.cfg.n_q_heads;
   a.n_kv = h.cfg.n_kv_heads; a.head_dim = h.cfg.head_dim; a.batch = h.cfg.batch;
   hipStream_t s = (hipStream_t)stream;
+  a.epoch = ++g->epoch;
   if (h.opt.launch_mode == MPK_LAUNCH_MEGA) {
-    a.epoch = ++g->epoch;
     hipLaunchKernelGGL(mpk_mega_kernel, dim3(h.opt.n_workers + h.opt.n_sched_wgs), dim3(kThreads),
                        h.lds_bytes, s, a);
     HIP_TRY(hipGetLastError());
@@ -852,6 +942,7 @@ extern "C" mpk_status mpk_graph_reset(mpk_graph* g) {
   HIP_TRY(hipDeviceSynchronize());
   HIP_TRY(hipMemset(g->d_counters, 0, g->h.events.size() * sizeof(uint32_t)));
   HIP_TRY(hipMemset(g->d_err, 0, 8 * sizeof(uint32_t)));
+  HIP_TRY(hipMemset(g->d_grp, 0, std::max<size_t>(g->h.n_group_counters, 1) * sizeof(uint32_t)));
   HIP_TRY(hipDeviceSynchronize());
   g->epoch = 0;
   return MPK_OK;

@@ -39,6 +39,8 @@ CASES = [
     ("C2", dict(n_layers=2), dict(fusion=0)),
     ("C2", dict(n_layers=2), dict(fusion=7)),
     ("C3", dict(n_layers=1), dict(fusion=7)),
+    ("C1", dict(batch=2), dict(fusion=31, n_workers=24, attn_chunks=3)),
+    ("C2", dict(n_layers=2), dict(fusion=31)),
 ]
 
 
@@ -73,7 +75,7 @@ def closure_by_op_tile(psets):
     return {(o, t): go((o, t)) for o in range(len(psets)) for t in range(len(psets[o]))}
 
 
-@pytest.mark.parametrize("base,variant,opts", CASES[:5])
+@pytest.mark.parametrize("base,variant,opts", CASES[:5] + CASES[8:])
 def test_transitive_reduction_keeps_closures(base, variant, opts):
     shape = G.small_variant(base, **variant)
     g = host_graph(shape, transitive_reduction=1, **opts)
@@ -156,6 +158,23 @@ def test_launch_mode_labels_follow_the_barrier_rule():
         # with no scheduler every task is pre-enqueued
         ex0 = host_graph(shape, n_workers=8, attn_chunks=3, fusion=fusion).export()
         assert not ex0.tasks["jit"].any()
+
+
+def test_fully_fused_8b_graph_has_no_fork_join_and_five_events_per_layer():
+    """With every fusion, head-aligned QKV tiles and transitive reduction the compiled graph of
+    the 8B shape is purely sequential: no dummy tasks (Section 6.5 reports none for its LLM
+    graphs) and one event per operator."""
+    shape = G.small_variant("C2", n_layers=3)
+    g = host_graph(shape, fusion=31, transitive_reduction=1)
+    s = g.stats()
+    assert s["n_dummy_tasks"] == 0
+    assert s["n_ops"] == 1 + 5 * 3 + 1
+    ex = g.export()
+    qkv = [o for o in ex.ops if o["kind"] == M.binding.OP_LINEAR and o["cols"] == 6144][0]
+    assert 128 % (6144 // int(qkv["tc"])) == 0
+    # start and terminal events, the LM head's event, and per layer one event each for qkv, the
+    # 8 attention groups, o_proj, gate_up and down
+    assert s["n_events"] == 2 + 1 + 3 * (1 + 8 + 1 + 1 + 1)
 
 
 def test_no_dummies_when_nothing_forks_and_paper_style_stats():

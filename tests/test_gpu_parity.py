@@ -33,6 +33,11 @@ MODES = [
     dict(fusion=7, transitive_reduction=1),
     dict(fusion=7, transitive_reduction=1, launch_mode=1),
     dict(fusion=3, transitive_reduction=1, n_workers=37, attn_chunks=5, tiles_pointwise=3),
+    dict(fusion=31, transitive_reduction=1),
+    dict(fusion=31, transitive_reduction=1, launch_mode=1),
+    dict(fusion=16 + 7),
+    dict(fusion=8 + 7, attn_chunks=1),
+    dict(fusion=31, transitive_reduction=1, n_workers=37, attn_chunks=5),
 ]
 
 
@@ -66,7 +71,8 @@ def test_c1_one_step_matches_oracle(opts):
     gpu.close()
 
 
-@pytest.mark.parametrize("opts", [dict(fusion=0), dict(fusion=7, transitive_reduction=1)])
+@pytest.mark.parametrize("opts", [dict(fusion=0), dict(fusion=7, transitive_reduction=1),
+                                  dict(fusion=31, transitive_reduction=1)])
 def test_small_batch_and_ragged_positions(opts):
     """Batch 3 with different KV lengths (one of them tiny), ragged tiles (n_workers = 37)."""
     s = G.small_variant("C1", batch=3, n_layers=2)
@@ -86,7 +92,8 @@ def test_greedy_32_steps_free_running_and_teacher_forced():
     tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
     ref = D.DecoderOracle(s, G.SynthWeights(s, 0), "f32")
     want_t, want_l = ref.greedy(tok, pos, 32)
-    for opts in (dict(fusion=0), dict(fusion=7, transitive_reduction=1)):
+    for opts in (dict(fusion=0), dict(fusion=7, transitive_reduction=1),
+                 dict(fusion=31, transitive_reduction=1)):
         gpu = GpuDecoder(s, 0, **opts)
         t, p, toks = np.array(tok), np.array(pos), []
         for i in range(32):
@@ -116,7 +123,9 @@ def test_full_width_two_layers_of_the_8b_shape():
     from synth.device import DeviceModel
     model = DeviceModel(s, 0)
     for opts in (dict(fusion=0), dict(fusion=7, transitive_reduction=1),
-                 dict(fusion=7, transitive_reduction=1, launch_mode=1)):
+                 dict(fusion=7, transitive_reduction=1, launch_mode=1),
+                 dict(fusion=31, transitive_reduction=1),
+                 dict(fusion=31, transitive_reduction=1, launch_mode=1)):
         model.reset_kv()
         gpu = GpuDecoder(s, 0, model=model, **opts)
         got = gpu.step(tok, pos)

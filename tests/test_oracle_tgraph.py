@@ -212,15 +212,14 @@ def test_producer_sets_spot_checks_unfused():
     for b in range(2):
         for h in range(nslots):
             assert ps[ix["L0.rope"]][b * nslots + h] == [(ix["L0.qkv"], h // 2)]
-    # attention partial (b, g, c): q heads of group g; the last chunk also this step's k and v
+    # attention partial (b, g, c): q heads of group g and this step's k and v of KV head g
     C, grp = 3, s.n_q_heads // s.n_kv_heads
     for b in range(2):
         for g in range(s.n_kv_heads):
             for c in range(C):
                 want = {(ix["L0.rope"], b * nslots + h) for h in range(g * grp, (g + 1) * grp)}
-                if c == C - 1:
-                    want |= {(ix["L0.rope"], b * nslots + s.n_q_heads + g),
-                             (ix["L0.rope"], b * nslots + s.n_q_heads + s.n_kv_heads + g)}
+                want |= {(ix["L0.rope"], b * nslots + s.n_q_heads + g),
+                         (ix["L0.rope"], b * nslots + s.n_q_heads + s.n_kv_heads + g)}
                 assert set(ps[ix["L0.attn_partial"]][(b * s.n_kv_heads + g) * C + c]) == want
     # merge tile = 2 heads = one group -> all chunks of that (b, group)
     for b in range(2):
