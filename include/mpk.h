@@ -90,6 +90,8 @@ typedef struct mpk_kv_ptrs {
 #define MPK_FUSE_MERGE 8u  /* split-KV merge folded into the O projection's input stage         */
 #define MPK_FUSE_ROPE 16u  /* RoPE + KV append folded into the attention tasks                  */
 
+#define MPK_DEBUG_TRACE 1u /* record per-task timestamps inside the persistent kernel           */
+
 #define MPK_LAUNCH_MEGA 0u   /* one persistent kernel per decode step (Section 5)               */
 #define MPK_LAUNCH_PER_OP 1u /* same task bodies, one kernel launch per operator (baseline)     */
 
@@ -115,7 +117,7 @@ typedef struct mpk_compile_options {
   uint32_t host_only;       /* 1 = build the task graph on the host only: no device is touched,
                                weight/KV pointers may be NULL; mpk_decode_step is refused       */
   uint32_t spin_timeout_ms; /* in-kernel watchdog for every wait; 0 = 2000 ms                   */
-  uint32_t debug_flags;     /* reserved, must be 0                                              */
+  uint32_t debug_flags;     /* MPK_DEBUG_* bits                                                 */
 } mpk_compile_options;
 
 typedef struct mpk_graph mpk_graph;
@@ -223,6 +225,14 @@ enum {
 };
 
 mpk_status mpk_graph_export(const mpk_graph *g, void *buf, size_t cap, size_t *need);
+
+/* Per-task timeline of the LAST decode step of a graph compiled with MPK_DEBUG_TRACE (the
+ * counterpart of the paper's run-time overhead accounting, Section 6.5 "kernel-launch
+ * reduction").  buf: host u64 [n_tasks][6] in linearized task order: 0 task picked up, 1 dependent
+ * event seen, 2 input staged (linear tasks), 3 body finished, 4 triggering event notified, all in
+ * ticks of the 100 MHz device wall clock, 5 worker index.  Call after synchronising the stream.
+ * buf == NULL returns the element count in *need. */
+mpk_status mpk_graph_trace(mpk_graph *g, uint64_t *buf, size_t cap, size_t *need);
 
 const char *mpk_last_error(void);
 void mpk_graph_destroy(mpk_graph *g);

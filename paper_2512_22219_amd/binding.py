@@ -79,8 +79,8 @@ EXPORT_EVENT = np.dtype([("required", "<u4"), ("first", "<u4"), ("last", "<u4"),
                          ("flags", "<u4")])
 
 SYMBOLS = ("mpk_compile", "mpk_compile_dag", "mpk_decode_step", "mpk_graph_status",
-           "mpk_graph_reset", "mpk_graph_stats", "mpk_graph_export", "mpk_last_error",
-           "mpk_graph_destroy")
+           "mpk_graph_reset", "mpk_graph_stats", "mpk_graph_export", "mpk_graph_trace",
+           "mpk_last_error", "mpk_graph_destroy")
 
 _lib = None
 
@@ -103,10 +103,11 @@ def lib():
         L.mpk_graph_reset.argtypes = [vp]
         L.mpk_graph_stats.argtypes = [vp, C.POINTER(Stats)]
         L.mpk_graph_export.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
+        L.mpk_graph_trace.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
         L.mpk_last_error.restype = C.c_char_p
         L.mpk_graph_destroy.argtypes = [vp]
         L.mpk_graph_destroy.restype = None
-        for n in SYMBOLS[:7]:
+        for n in SYMBOLS[:8]:
             getattr(L, n).restype = C.c_int
         _lib = L
     return _lib
@@ -191,6 +192,13 @@ class Graph:
         buf = C.create_string_buffer(need.value)
         _check(lib().mpk_graph_export(self._h, buf, need.value, C.byref(need)))
         return Export(buf.raw)
+
+    def trace(self) -> np.ndarray:
+        need = C.c_size_t(0)
+        _check(lib().mpk_graph_trace(self._h, None, 0, C.byref(need)))
+        buf = np.zeros(need.value, np.uint64)
+        _check(lib().mpk_graph_trace(self._h, buf.ctypes.data, need.value, C.byref(need)))
+        return buf.reshape(-1, 6)
 
     def destroy(self):
         if self._h:

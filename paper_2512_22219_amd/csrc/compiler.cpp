@@ -777,7 +777,7 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
   if (c.n_q_heads / c.n_kv_heads > 8) { set_error("more than 8 query heads per KV head unsupported"); return MPK_ERR_UNSUPPORTED; }
   if (c.hidden % 8 || c.ffn % 8 || (c.n_q_heads * c.head_dim) % 8) { set_error("hidden, ffn and n_q*head_dim must be multiples of 8"); return MPK_ERR_UNSUPPORTED; }
   if (c.batch > 8) { set_error("batch %u unsupported by the dense linear bodies (max 8)", c.batch); return MPK_ERR_UNSUPPORTED; }
-  if (o.debug_flags) { set_error("debug_flags must be 0"); return MPK_ERR_INVALID_ARG; }
+  if (o.debug_flags & ~MPK_DEBUG_TRACE) { set_error("unknown debug_flags bits"); return MPK_ERR_INVALID_ARG; }
   if (o.fusion & ~(MPK_FUSE_NORM | MPK_FUSE_RESID | MPK_FUSE_SWIGLU | MPK_FUSE_MERGE | MPK_FUSE_ROPE)) { set_error("unknown fusion bits"); return MPK_ERR_INVALID_ARG; }
   if (!o.host_only) {
     if (!w || !kv || !w->layers) { set_error("weights / kv pointers are NULL"); return MPK_ERR_INVALID_ARG; }

@@ -43,10 +43,16 @@ struct StepArgs {
   uint32_t* err;   // [0] error code, [1] abort flag, [2..3] detail
   const double* inv_freq;    // RoPE frequencies theta^(-2i/d), i < head_dim / 2
   uint32_t* grp_counters;    // arrival counters per (layer, sequence, KV head), monotonic
+  uint64_t* trace;           // optional [n_tasks][kTraceSlots] timestamps (100 MHz), or null
   uint64_t timeout_ticks;
   uint32_t epoch, n_workers;
   uint32_t vocab, max_seq, n_q, n_kv, head_dim, batch;
 };
+
+constexpr int kTraceSlots = 6;
+__device__ __forceinline__ void trace_mark(const StepArgs& a, const TaskDesc& t, int slot) {
+  if (a.trace && threadIdx.x == 0) a.trace[(size_t)(&t - a.tasks) * kTraceSlots + slot] = wall_clock64();
+}
 
 enum DevErr : uint32_t { DE_NONE = 0, DE_TIMEOUT = 1, DE_BAD_POSITION = 2, DE_BAD_TOKEN = 3 };
 
@@ -219,6 +225,7 @@ __device__ bool body_linear(const TaskDesc& t, const StepArgs& a, float* lds, in
   }
   // ---- the input vector: only now does the task need its dependent event
   if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
+  trace_mark(a, t, 1);
   for (uint32_t b = 0; b < NB; ++b) {
     float2* dst = (float2*)(xs + (size_t)b * K);
     if (b < nb) {
@@ -242,6 +249,7 @@ __device__ bool body_linear(const TaskDesc& t, const StepArgs& a, float* lds, in
     __syncthreads();
   }
   // ---- stream the weight rows
+  trace_mark(a, t, 2);
   float* outp = (t.flags & TF_OUT_LOGITS) ? a.logits : t.out;
   float acc[RW][NB];
 #pragma unroll
@@ -621,6 +629,7 @@ __device__ bool run_task(const TaskDesc& t, const StepArgs& a, float* lds, int32
     return body_linear<8, 2, 4>(t, a, lds, wait_ev, s_flag);
   }
   if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
+  trace_mark(a, t, 1);
   switch (t.kind) {
     case TK_EMBED: body_embed(t, a); break;
     case TK_RMSNORM: body_rmsnorm(t, lds); break;
@@ -686,9 +695,13 @@ mpk_mega_kernel(StepArgs a) {
   for (uint32_t qi = q0; qi < q1; ++qi) {
     const TaskDesc& t = a.tasks[a.aot[qi]];
     const int32_t wait_ev = (t.dep_event >= 0 && a.events[t.dep_event].required != 0) ? t.dep_event : -1;
+    trace_mark(a, t, 0);
     if (!run_task(t, a, lds, wait_ev, &s_flag)) break;
+    trace_mark(a, t, 3);
     if (t.trig_event >= 0) signal_event(a, t.trig_event);
     else __syncthreads();
+    trace_mark(a, t, 4);
+    if (a.trace && threadIdx.x == 0) a.trace[(size_t)(&t - a.tasks) * kTraceSlots + 5] = blockIdx.x;
   }
 }
 
@@ -719,6 +732,7 @@ struct mpk_graph {
   uint32_t* d_op_list = nullptr;
   uint32_t* d_err = nullptr;
   double* d_inv_freq = nullptr;
+  uint64_t* d_trace = nullptr;
   uint32_t* d_grp = nullptr;
   float* d_arena = nullptr;
   std::vector<uint32_t> op_first, op_count;   // per operator: range in op_list
@@ -740,7 +754,7 @@ static void free_device(mpk_graph* g) {
   (void)hipFree(g->d_tasks); (void)hipFree(g->d_events); (void)hipFree(g->d_counters);
   (void)hipFree(g->d_aot_off); (void)hipFree(g->d_aot); (void)hipFree(g->d_op_list);
   (void)hipFree(g->d_err); (void)hipFree(g->d_arena);
-  (void)hipFree(g->d_inv_freq); (void)hipFree(g->d_grp);
+  (void)hipFree(g->d_inv_freq); (void)hipFree(g->d_grp); (void)hipFree(g->d_trace);
 }
 
 static mpk_status resolve_options(const mpk_compile_options* in, mpk_compile_options* out,
@@ -861,6 +875,10 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
     std::vector<uint32_t> gz(h.n_group_counters, 0);
     if ((st = upload(&g->d_grp, gz)) != MPK_OK) return fail(st);
   }
+  if (o.debug_flags & MPK_DEBUG_TRACE) {
+    std::vector<uint64_t> tz(h.tasks.size() * kTraceSlots, 0);
+    if ((st = upload(&g->d_trace, tz)) != MPK_OK) return fail(st);
+  }
   g->timeout_ticks = (uint64_t)o.spin_timeout_ms * 100000ull;   // wall clock counts at 100 MHz
   *out = g;
   return MPK_OK;
@@ -895,7 +913,7 @@ extern "C" mpk_status mpk_decode_step(mpk_graph* g, const int32_t* token_ids,
   a.aot_off = g->d_aot_off; a.aot = g->d_aot; a.op_list = g->d_op_list;
   a.token_ids = token_ids; a.positions = positions; a.logits = logits_out; a.err = g->d_err;
   a.timeout_ticks = g->timeout_ticks;
-  a.inv_freq = g->d_inv_freq; a.grp_counters = g->d_grp;
+  a.inv_freq = g->d_inv_freq; a.grp_counters = g->d_grp; a.trace = g->d_trace;
   a.n_workers = h.opt.n_workers;
   a.vocab = h.cfg.vocab; a.max_seq = h.cfg.max_seq; a.n_q = h.cfg.n_q_heads;
   a.n_kv = h.cfg.n_kv_heads; a.head_dim = h.cfg.head_dim; a.batch = h.cfg.batch;
@@ -962,6 +980,17 @@ extern "C" mpk_status mpk_graph_export(const mpk_graph* g, void* buf, size_t cap
   if (!buf) return MPK_OK;
   if (cap < n) { set_error("export buffer too small: %zu < %zu", cap, n); return MPK_ERR_INVALID_ARG; }
   export_graph(g->h, buf);
+  return MPK_OK;
+}
+
+extern "C" mpk_status mpk_graph_trace(mpk_graph* g, uint64_t* buf, size_t cap, size_t* need) {
+  if (!g) { set_error("NULL graph"); return MPK_ERR_INVALID_ARG; }
+  if (g->host_only || !g->d_trace) { set_error("graph was not compiled with MPK_DEBUG_TRACE"); return MPK_ERR_INVALID_ARG; }
+  size_t n = g->h.tasks.size() * kTraceSlots;
+  if (need) *need = n;
+  if (!buf) return MPK_OK;
+  if (cap < n) { set_error("trace buffer too small: %zu < %zu", cap, n); return MPK_ERR_INVALID_ARG; }
+  HIP_TRY(hipMemcpy(buf, g->d_trace, n * sizeof(uint64_t), hipMemcpyDeviceToHost));
   return MPK_OK;
 }
 
