@@ -228,9 +228,10 @@ mpk_status mpk_graph_export(const mpk_graph *g, void *buf, size_t cap, size_t *n
 
 /* Per-task timeline of the LAST decode step of a graph compiled with MPK_DEBUG_TRACE (the
  * counterpart of the paper's run-time overhead accounting, Section 6.5 "kernel-launch
- * reduction").  buf: host u64 [n_tasks][6] in linearized task order: 0 task picked up, 1 dependent
- * event seen, 2 input staged (linear tasks), 3 body finished, 4 triggering event notified, all in
- * ticks of the 100 MHz device wall clock, 5 worker index.  Call after synchronising the stream.
+ * reduction").  buf: host u64 [n_tasks][8] in linearized task order: 0 task picked up, 1 dependent
+ * event seen, 2 input staged (linear and attention tasks), 3 body finished (first wavefront),
+ * 4 triggering event notified, 6 first wavefront's stores completed, 7 all wavefronts' stores
+ * completed, all in ticks of the 100 MHz device wall clock; 5 worker index.  Call after synchronising the stream.
  * buf == NULL returns the element count in *need. */
 mpk_status mpk_graph_trace(mpk_graph *g, uint64_t *buf, size_t cap, size_t *need);
 

@@ -198,7 +198,7 @@ class Graph:
         _check(lib().mpk_graph_trace(self._h, None, 0, C.byref(need)))
         buf = np.zeros(need.value, np.uint64)
         _check(lib().mpk_graph_trace(self._h, buf.ctypes.data, need.value, C.byref(need)))
-        return buf.reshape(-1, 6)
+        return buf.reshape(-1, 12)
 
     def destroy(self):
         if self._h:

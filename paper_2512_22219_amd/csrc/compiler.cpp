@@ -284,6 +284,29 @@ static mpk_status run_passes(PassInput& in, const mpk_compile_options& opt, Host
   }
   g.aot_off[W] = (uint32_t)g.aot.size();
 
+  // Wide events whose producers all have a fixed worker (AOT) count arrivals per worker group.
+  g.n_hier_events = 0;
+  {
+    std::vector<std::vector<uint32_t>> sub(g.events.size(), std::vector<uint32_t>(8, 0));
+    std::vector<uint8_t> has_jit_producer(g.events.size(), 0);
+    for (uint32_t i = 0; i < n_tasks; ++i) {
+      int32_t e = g.tasks[i].trig_event;
+      if (g.tasks[i].jit) has_jit_producer[e] = 1;
+      else sub[e][(uint32_t)g.tasks[i].worker & 7u]++;
+    }
+    for (size_t e = 0; e < g.events.size(); ++e) {
+      EventDesc& ev = g.events[e];
+      if (ev.required < kHierMinRequired || has_jit_producer[e]) continue;
+      ev.flags |= EV_HIER;
+      ev.hier_slot = g.n_hier_events++;
+      ev.n_groups = 0;
+      for (int k = 0; k < 8; ++k) {
+        ev.sub_required[k] = sub[e][k];
+        ev.n_groups += sub[e][k] ? 1u : 0u;
+      }
+    }
+  }
+
   g.stats.n_tasks = n_tasks;
   g.stats.n_events = (uint32_t)events.size();
   g.stats.n_jit_tasks = n_jit;
@@ -756,9 +779,8 @@ static uint32_t lds_requirement(const mpk_model_config& c, const HostGraph& g, u
     }
     else if (op.kind == MPK_OP_RMSNORM) f = 0;
     else if (op.kind == MPK_OP_ATTN_PARTIAL)
-      f = (size_t)grp * c.head_dim                                   // q
-          + (size_t)grp * ((c.max_seq + C - 1) / C + 1)              // scores of one chunk
-          + (size_t)(kThreads / 64) * grp * c.head_dim;              // per-wave partial outputs
+      f = (size_t)grp * c.head_dim                                        // q
+          + (size_t)(kThreads / 64) * grp * (c.head_dim + 2) + 16 + 64;   // per-wave partials
     need = std::max(need, f);
   }
   size_t bytes = (need + kLdsReduceFloats) * sizeof(float);
@@ -774,7 +796,10 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
   if (!c.ffn) { set_error("ffn is zero"); return MPK_ERR_INVALID_ARG; }
   if (c.head_dim != 64 && c.head_dim != 128) { set_error("head_dim %u unsupported (64 or 128)", c.head_dim); return MPK_ERR_UNSUPPORTED; }
   if (c.n_q_heads % c.n_kv_heads) { set_error("n_q_heads must be a multiple of n_kv_heads"); return MPK_ERR_UNSUPPORTED; }
-  if (c.n_q_heads / c.n_kv_heads > 8) { set_error("more than 8 query heads per KV head unsupported"); return MPK_ERR_UNSUPPORTED; }
+  {
+    uint32_t grp = c.n_q_heads / c.n_kv_heads;
+    if (grp != 1 && grp != 2 && grp != 4 && grp != 8) { set_error("%u query heads per KV head unsupported (1, 2, 4 or 8)", grp); return MPK_ERR_UNSUPPORTED; }
+  }
   if (c.hidden % 8 || c.ffn % 8 || (c.n_q_heads * c.head_dim) % 8) { set_error("hidden, ffn and n_q*head_dim must be multiples of 8"); return MPK_ERR_UNSUPPORTED; }
   if (c.batch > 8) { set_error("batch %u unsupported by the dense linear bodies (max 8)", c.batch); return MPK_ERR_UNSUPPORTED; }
   if (o.debug_flags & ~MPK_DEBUG_TRACE) { set_error("unknown debug_flags bits"); return MPK_ERR_INVALID_ARG; }
@@ -800,11 +825,17 @@ mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs*
   if (opt.n_workers == 0) { set_error("n_workers unresolved"); return MPK_ERR_INTERNAL; }
   uint32_t C = opt.attn_chunks;
   if (C == 0) {
-    C = std::max(1u, opt.n_workers / (2 * cfg.batch * cfg.n_kv_heads));
-    C = std::min(C, std::max(1u, cfg.max_seq / 64));
+    // one chunk = what a task can request before its event fires: 8 rounds of 8 wavefronts x
+    // 64 / (head_dim / 8) positions held in registers
+    const uint32_t window = 8u * 8u * (64u / (cfg.head_dim / 8u));
+    C = (cfg.max_seq + window - 1) / window;
     C = std::min(C, 64u);
   }
   if (C > 64) { set_error("attn_chunks %u too large (max 64)", C); return MPK_ERR_INVALID_ARG; }
+  {
+    const uint32_t window = 8u * 8u * (64u / (cfg.head_dim / 8u));
+    if ((cfg.max_seq + C - 1) / C > window) { set_error("attn_chunks %u too small: a chunk of max_seq %u would exceed the %u positions an attention task holds in registers", C, cfg.max_seq, window); return MPK_ERR_INVALID_ARG; }
+  }
   opt.attn_chunks = C;
   g.cfg = cfg;
   g.opt = opt;

@@ -58,8 +58,21 @@ struct alignas(16) TaskDesc {
 static_assert(sizeof(TaskDesc) == 128, "TaskDesc must stay 128 bytes");
 
 struct EventDesc {   // paper Section 4.1 "tGraph linearization" / Fig. 4(f)
-  uint32_t required, first, last, flags;
+  uint32_t required, first, last;
+  uint32_t flags;       // bit 0: launches JIT tasks; bit 1: hierarchical arrival (see EV_HIER)
+  uint32_t hier_slot;   // index into the hierarchical counter blocks
+  uint32_t n_groups;    // worker groups (worker index mod 8) that hold at least one producer
+  uint32_t sub_required[8];   // producers per worker group
+  uint32_t pad[2];
 };
+static_assert(sizeof(EventDesc) == 64, "EventDesc is 64 bytes");
+constexpr uint32_t EV_JIT = 1, EV_HIER = 2;
+// A hierarchical event owns 17 words, each on its own 256-byte line: the top counter, 8 group
+// counters and 8 ready flags (one per worker group).  256 same-address atomics plus 256 pollers on
+// one line cost about 4 us per hop on this GPU; arrival by group and one flag line per 32
+// pollers brings that to about 2 us.
+constexpr uint32_t kHierStrideWords = 64, kHierWordsPerEvent = 17 * kHierStrideWords;
+constexpr uint32_t kHierMinRequired = 48;
 
 // ---------------------------------------------------------------- host-side graph
 struct HostOp {
@@ -111,6 +124,7 @@ struct HostGraph {
   size_t arena_floats = 0;
   uint32_t lds_bytes = 0;
   uint32_t n_group_counters = 0;   // per (layer, sequence, KV head) arrival counters
+  uint32_t n_hier_events = 0;
   std::vector<double> inv_freq;    // RoPE frequencies theta^(-2i/d), i < d/2
   mpk_stats stats{};
 };

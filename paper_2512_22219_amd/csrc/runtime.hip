@@ -30,28 +30,39 @@ const char* last_error();
 size_t export_size(const HostGraph& g);
 void export_graph(const HostGraph& g, void* buf);
 
-struct StepArgs {
+// Everything that is fixed for the lifetime of a graph lives in one device-resident record that
+// the kernels reach through a pointer (uniform address -> scalar loads on demand, nothing is
+// pinned in registers for the whole kernel).
+struct GraphConst {
   const TaskDesc* tasks;
   const EventDesc* events;
   uint32_t* counters;
+  uint32_t* hier;            // counter blocks of hierarchical events
   const uint32_t* aot_off;
   const uint32_t* aot;
   const uint32_t* op_list;   // per-operator launch: task indices grouped by operator
-  const int32_t* token_ids;
-  const int32_t* positions;
-  float* logits;
-  uint32_t* err;   // [0] error code, [1] abort flag, [2..3] detail
+  uint32_t* err;             // [0] error code, [1] abort flag, [2..3] detail
   const double* inv_freq;    // RoPE frequencies theta^(-2i/d), i < head_dim / 2
   uint32_t* grp_counters;    // arrival counters per (layer, sequence, KV head), monotonic
   uint64_t* trace;           // optional [n_tasks][kTraceSlots] timestamps (100 MHz), or null
   uint64_t timeout_ticks;
-  uint32_t epoch, n_workers;
+  uint32_t n_workers;
   uint32_t vocab, max_seq, n_q, n_kv, head_dim, batch;
 };
 
-constexpr int kTraceSlots = 6;
+// Per-step kernel arguments, passed by value.  Every device function taking it is force-inlined:
+// a real call with a reference to it would make the compiler copy the struct to private memory.
+struct StepArgs {
+  const GraphConst* g;
+  const int32_t* token_ids;
+  const int32_t* positions;
+  float* logits;
+  uint32_t epoch;
+};
+
+constexpr int kTraceSlots = 12;
 __device__ __forceinline__ void trace_mark(const StepArgs& a, const TaskDesc& t, int slot) {
-  if (a.trace && threadIdx.x == 0) a.trace[(size_t)(&t - a.tasks) * kTraceSlots + slot] = wall_clock64();
+  if (a.g->trace && threadIdx.x == 0) a.g->trace[(size_t)(&t - a.g->tasks) * kTraceSlots + slot] = wall_clock64();
 }
 
 enum DevErr : uint32_t { DE_NONE = 0, DE_TIMEOUT = 1, DE_BAD_POSITION = 2, DE_BAD_TOKEN = 3 };
@@ -128,18 +139,18 @@ __device__ __forceinline__ float dot8(const u32x4& w, const float4& x0, const fl
 }
 
 __device__ __forceinline__ void report(const StepArgs& a, uint32_t code, uint32_t d0, uint32_t d1) {
-  if (atomicCAS(&a.err[0], 0u, code) == 0u) {
-    a.err[2] = d0;
-    a.err[3] = d1;
+  if (atomicCAS(&a.g->err[0], 0u, code) == 0u) {
+    a.g->err[2] = d0;
+    a.g->err[3] = d1;
   }
 }
 
 // ------------------------------------------------------------------------------ task bodies
 // T0: x[b] = E[token[b]] widened to fp32.
-__device__ void body_embed(const TaskDesc& t, const StepArgs& a) {
+__device__ __forceinline__ void body_embed(const TaskDesc& t, const StepArgs& a) {
   for (uint32_t b = t.b0; b < t.b1; ++b) {
     int32_t tok = a.token_ids[b];
-    if (tok < 0 || (uint32_t)tok >= a.vocab) {
+    if (tok < 0 || (uint32_t)tok >= a.g->vocab) {
       if (threadIdx.x == 0) report(a, DE_BAD_TOKEN, b, (uint32_t)tok);
       tok = 0;
     }
@@ -150,7 +161,7 @@ __device__ void body_embed(const TaskDesc& t, const StepArgs& a) {
 }
 
 // T1/T8/T13: y = x * (1 / sqrt(mean(x^2) + eps)) * g, one batch row per task.
-__device__ void body_rmsnorm(const TaskDesc& t, float* lds) {
+__device__ __forceinline__ void body_rmsnorm(const TaskDesc& t, float* lds) {
   const uint16_t* g = (const uint16_t*)t.w2;
   for (uint32_t b = t.b0; b < t.b1; ++b) {
     const float* x = t.in + (size_t)b * t.ld_in;
@@ -166,7 +177,7 @@ __device__ void body_rmsnorm(const TaskDesc& t, float* lds) {
   }
 }
 
-__device__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag);
+__device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag);
 
 // T2/T6/T9/T11/T14: y[b][c] = sum_j W[c][j] x[b][j] for output columns [c0, c1), all batch rows
 // at once.  Every wavefront owns groups of RW weight rows (groups wave, wave+8, ...) and walks
@@ -180,7 +191,7 @@ __device__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag);
 // Optional stages: RMSNorm of the input (TF_PRO_NORM), residual add (TF_EPI_RESID), fused
 // silu(gate) * up (TF_GATEUP: column c needs weight rows c and F + c).
 template <int NB, int RW, int KU>
-__device__ bool body_linear(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
+__device__ __forceinline__ bool body_linear(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
                             uint32_t* s_flag) {
   const uint32_t K = t.K, nb = t.b1 - t.b0;
   float* xs = lds;                 // [NB][K]
@@ -226,28 +237,60 @@ __device__ bool body_linear(const TaskDesc& t, const StepArgs& a, float* lds, in
   // ---- the input vector: only now does the task need its dependent event
   if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
   trace_mark(a, t, 1);
+  // Input rows -> LDS.  With TF_PRO_NORM the gain is folded in here (x * g) and the row's
+  // 1/rms factor is applied to the finished dot products: W (x g inv) = inv * W (x g).
+  const bool pro_norm = t.flags & TF_PRO_NORM;
+  const uint16_t* gain = (const uint16_t*)t.w2;
+  float inv_rms[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) inv_rms[b] = 1.0f;
   for (uint32_t b = 0; b < NB; ++b) {
     float2* dst = (float2*)(xs + (size_t)b * K);
+    float ss = 0.f;
     if (b < nb) {
       const float* src = t.in + (size_t)(t.b0 + b) * t.ld_in;
-      for (uint32_t i = threadIdx.x; i < K / 2; i += kThreads) dst[i] = ld_act2(src + 2 * i);
+      for (uint32_t i0 = 0; i0 < K / 2; i0 += kThreads * 8) {   // 8 coherent loads in flight per lane
+        float2 tmp[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          uint32_t i = i0 + u * kThreads + threadIdx.x;
+          if (i < K / 2) tmp[u] = ld_act2(src + 2 * i);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          uint32_t i = i0 + u * kThreads + threadIdx.x;
+          if (i < K / 2) {
+            float2 v = tmp[u];
+            if (pro_norm) {
+              ss = fmaf(v.x, v.x, ss);
+              ss = fmaf(v.y, v.y, ss);
+              uint32_t g2 = *(const uint32_t*)(gain + 2 * i);
+              v.x *= bf16_lo(g2);
+              v.y *= bf16_hi(g2);
+            }
+            dst[i] = v;
+          }
+        }
+      }
     } else {
       for (uint32_t i = threadIdx.x; i < K / 2; i += kThreads) dst[i] = make_float2(0.f, 0.f);
     }
+    if (pro_norm && b < nb) {
+      ss = block_sum(ss, red);
+      inv_rms[b] = 1.0f / sqrtf(ss / (float)K + t.f0);
+    }
+  }
+  // residual slice of this tile (tile-local, small): fetched now, off the tail of the task
+  const uint32_t ncols_all = t.c1 - t.c0;
+  float* res_lds = red + 16;
+  const bool resid_in_lds = (t.flags & TF_EPI_RESID) && (size_t)nb * ncols_all <= kLdsReduceFloats - 16;
+  if (resid_in_lds) {
+    for (uint32_t i = threadIdx.x; i < nb * ncols_all; i += kThreads) {
+      uint32_t bb = i / ncols_all, cc = i % ncols_all;
+      res_lds[i] = ld_act(t.in2 + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc);
+    }
   }
   __syncthreads();
-  if (t.flags & TF_PRO_NORM) {
-    const uint16_t* g = (const uint16_t*)t.w2;
-    for (uint32_t b = 0; b < nb; ++b) {
-      float* x = xs + (size_t)b * K;
-      float ss = 0.f;
-      for (uint32_t i = threadIdx.x; i < K; i += kThreads) ss = fmaf(x[i], x[i], ss);
-      ss = block_sum(ss, red);
-      float inv = 1.0f / sqrtf(ss / (float)K + t.f0);
-      for (uint32_t i = threadIdx.x; i < K; i += kThreads) x[i] = x[i] * inv * bf16_to_f32(g[i]);
-    }
-    __syncthreads();
-  }
   // ---- stream the weight rows
   trace_mark(a, t, 2);
   float* outp = (t.flags & TF_OUT_LOGITS) ? a.logits : t.out;
@@ -296,7 +339,7 @@ __device__ bool body_linear(const TaskDesc& t, const StepArgs& a, float* lds, in
             uint32_t col = t.c0 + grp * G + (i >> 1);
             if (col < t.c1) {
               for (uint32_t b = 0; b < nb; ++b) {
-                float gte = acc[i][b], up = acc[i + 1][b];
+                float gte = acc[i][b] * inv_rms[b], up = acc[i + 1][b] * inv_rms[b];
                 st_act(outp + (size_t)(t.b0 + b) * t.ld_out + col, gte / (1.0f + expf(-gte)) * up);
               }
             }
@@ -307,9 +350,10 @@ __device__ bool body_linear(const TaskDesc& t, const StepArgs& a, float* lds, in
             uint32_t col = t.c0 + grp * G + i;
             if (col < t.c1) {
               for (uint32_t b = 0; b < nb; ++b) {
-                float v = acc[i][b];
+                float v = acc[i][b] * inv_rms[b];
                 size_t o = (size_t)(t.b0 + b) * t.ld_out + col;
-                if (t.flags & TF_EPI_RESID) v = ld_act(t.in2 + o) + v;
+                if (t.flags & TF_EPI_RESID)
+                  v = (resid_in_lds ? res_lds[b * ncols_all + (col - t.c0)] : ld_act(t.in2 + o)) + v;
                 st_act(outp + o, v);
               }
             }
@@ -330,7 +374,7 @@ __device__ bool body_linear(const TaskDesc& t, const StepArgs& a, float* lds, in
 
 // cos and sin of position * inv_freq[i]: the angle is formed and reduced to [-pi, pi] in double.
 __device__ __forceinline__ void rope_cs(const StepArgs& a, int32_t pos, uint32_t i, float* c, float* s) {
-  double ang = (double)pos * a.inv_freq[i];
+  double ang = (double)pos * a.g->inv_freq[i];
   const double two_pi = 6.283185307179586476925286766559;
   ang -= two_pi * rint(ang / two_pi);
   double sd, cd;
@@ -341,12 +385,12 @@ __device__ __forceinline__ void rope_cs(const StepArgs& a, int32_t pos, uint32_t
 
 // T3: rotate q and k heads by the sequence position (half-split pairing), copy v, and append the
 // new k and v rows to the cache as bf16.  Angles are evaluated in double precision.
-__device__ void body_rope(const TaskDesc& t, const StepArgs& a) {
-  const uint32_t d = a.head_dim, half = d / 2, nq = a.n_q, nkv = a.n_kv;
+__device__ __forceinline__ void body_rope(const TaskDesc& t, const StepArgs& a) {
+  const uint32_t d = a.g->head_dim, half = d / 2, nq = a.g->n_q, nkv = a.g->n_kv;
   const uint32_t s0 = t.c0 / d, s1 = t.c1 / d;
   for (uint32_t b = t.b0; b < t.b1; ++b) {
     int32_t pos = a.positions[b];
-    if (pos < 0 || (uint32_t)pos >= a.max_seq) {
+    if (pos < 0 || (uint32_t)pos >= a.g->max_seq) {
       if (threadIdx.x == 0) report(a, DE_BAD_POSITION, b, (uint32_t)pos);
       continue;
     }
@@ -378,7 +422,7 @@ __device__ void body_rope(const TaskDesc& t, const StepArgs& a) {
         bool is_k = s < nq + nkv;
         uint32_t g = is_k ? s - nq : s - nq - nkv;
         uint16_t* cache = (uint16_t*)(is_k ? t.aux0 : t.aux1);
-        uint16_t* row = cache + (((size_t)b * nkv + g) * a.max_seq + (uint32_t)pos) * d;
+        uint16_t* row = cache + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
         st_act_u32((uint32_t*)(row + i), (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16));
         st_act_u32((uint32_t*)(row + i + half), (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16));
       }
@@ -386,34 +430,76 @@ __device__ void body_rope(const TaskDesc& t, const StepArgs& a) {
   }
 }
 
+// Sum over the LPP (8 or 16) adjacent lanes that share one cache position, with DPP lane
+// permutations (register-to-register, no LDS round trip); every lane gets the sum.
+template <int LPP>
+__device__ __forceinline__ float group_sum(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // lane ^ 1
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // lane ^ 2
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // mirror in 8
+  if (LPP == 16)
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // mirror in 16
+  return v;
+}
+
 // T4: split-KV decode attention for one (sequence, KV head, chunk).  Chunk c of C covers cache
 // rows [c*len/C, (c+1)*len/C) with len = position + 1, so the last chunk holds the new row.
-// Output per query head of the group: sum_t exp(s_t - m) V_t (d floats), m, l = sum_t exp(s_t - m).
-__device__ void body_attn_partial(const TaskDesc& t, const StepArgs& a, float* lds) {
-  const uint32_t d = a.head_dim, nq = a.n_q, nkv = a.n_kv, grp = nq / nkv;
-  const uint32_t per = grp * (d + 2), C = t.p1;
+// Output per query head of the group: sum_t exp(s_t - m) V_t (D floats), m, l = sum_t exp(s_t - m).
+// Layout of the work: D/8 adjacent lanes share one position (16 bytes of the row each), a
+// wavefront covers 64/(D/8) positions per round, the 8 wavefronts of the workgroup take rounds
+// of 8 x that many positions; kAttnRounds rounds fit in registers and the compiler picks the chunk
+// count so that a chunk never exceeds them.
+// Cache rows of earlier steps are immutable during a step, so the task requests its K and V rows
+// BEFORE it waits for its dependent event; only the query (and the row appended this step)
+// arrive later.  Scores, probabilities and the running sums stay in registers.
+constexpr int kAttnRounds = 8;
+
+template <int D, int GRP>
+__device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepArgs& a, float* lds,
+                                                  int32_t wait_ev, uint32_t* s_flag) {
+  constexpr uint32_t d = D, grp = GRP, LPP = D / 8, PPW = 64 / LPP, NW = kThreads / 64;
+  constexpr uint32_t stride = NW * PPW, per = grp * (d + 2);
+  const uint32_t nq = a.g->n_q, nkv = a.g->n_kv, C = t.p1;
   const uint32_t b = t.b0, u = t.c0 / per, g = u / C, c = u % C;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t nmax = (a.max_seq + C - 1) / C + 1;
   float* qs = lds;                       // [grp][d]
-  float* sc = qs + grp * d;              // [grp][nmax]
-  float* wpart = sc + grp * nmax;        // [8][grp][d]
-  float* ml = wpart + (kThreads / 64) * grp * d;   // [grp][2]
+  float* wpart = qs + grp * d;           // [NW][grp][d + 2]: partial output, max, sum per wavefront
+  uint32_t* flag = (uint32_t*)(wpart + NW * grp * (d + 2));   // then [16..) the maxima exchange
   float* outp = t.out + (size_t)b * t.ld_out + t.c0;
-  int32_t pos = a.positions[b];
-  if (pos < 0 || (uint32_t)pos >= a.max_seq) {
-    if (threadIdx.x == 0) report(a, DE_BAD_POSITION, b, (uint32_t)pos);
-    for (uint32_t i = threadIdx.x; i < per; i += kThreads) st_act(outp + i, ((i % (d + 2)) == d) ? -INFINITY : 0.f);
-    return;
-  }
-  const uint32_t len = (uint32_t)pos + 1;
+  const int32_t pos = a.positions[b];    // written by the host before the launch
+  const bool bad_pos = pos < 0 || (uint32_t)pos >= a.g->max_seq;
+  const uint32_t len = bad_pos ? 0u : (uint32_t)pos + 1;
   const uint32_t t0 = (uint32_t)((uint64_t)c * len / C), t1 = (uint32_t)((uint64_t)(c + 1) * len / C);
   const uint32_t n = t1 - t0;
+  const uint16_t* Kb = (const uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.g->max_seq + t0) * d;
+  const uint16_t* Vb = (const uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.g->max_seq + t0) * d;
+  const uint32_t sub = lane % LPP, slot = lane / LPP;
+  const uint32_t i_first = wave * PPW + slot;
+  const uint32_t n_rounds = (n + stride - 1) / stride;
+  // ---- pre-load: K and V rows of earlier steps
+  u32x4 kreg[kAttnRounds], vreg[kAttnRounds];
+#pragma unroll
+  for (int r = 0; r < kAttnRounds; ++r) {
+    const uint32_t i = i_first + r * stride;
+    kreg[r] = u32x4{0, 0, 0, 0};
+    vreg[r] = u32x4{0, 0, 0, 0};
+    if (i < n && t0 + i != (uint32_t)pos) {
+      kreg[r] = __builtin_nontemporal_load((const u32x4*)(Kb + (size_t)i * d + sub * 8));
+      vreg[r] = __builtin_nontemporal_load((const u32x4*)(Vb + (size_t)i * d + sub * 8));
+    }
+  }
+  if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
+  trace_mark(a, t, 1);
+  if (bad_pos || n_rounds > (uint32_t)kAttnRounds) {
+    if (threadIdx.x == 0) report(a, DE_BAD_POSITION, b, (uint32_t)pos);
+    for (uint32_t i = threadIdx.x; i < per; i += kThreads) st_act(outp + i, ((i % (d + 2)) == d) ? -INFINITY : 0.f);
+    return true;
+  }
   const float* qsrc = t.in + (size_t)b * t.ld_in + (size_t)g * grp * d;
   if (t.flags & TF_ROPE_FUSED) {
     // the input is the raw QKV projection: rotate the group's query heads here; the task of the
     // last chunk also rotates this step's key, and appends key and value to the cache
-    const uint32_t half = d / 2;
+    constexpr uint32_t half = d / 2;
     for (uint32_t i = threadIdx.x; i < grp * half; i += kThreads) {
       uint32_t j = i / half, e = i % half;
       float u0 = ld_act(qsrc + j * d + e), u1 = ld_act(qsrc + j * d + e + half), cs, sn;
@@ -424,9 +510,10 @@ __device__ void body_attn_partial(const TaskDesc& t, const StepArgs& a, float* l
     if (c == C - 1) {
       const float* ksrc = t.in + (size_t)b * t.ld_in + (size_t)(nq + g) * d;
       const float* vsrc = t.in + (size_t)b * t.ld_in + (size_t)(nq + nkv + g) * d;
-      uint16_t* krow = (uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.max_seq + (uint32_t)pos) * d;
-      uint16_t* vrow = (uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.max_seq + (uint32_t)pos) * d;
-      for (uint32_t i = threadIdx.x; i < half / 2 + half; i += kThreads) {
+      uint16_t* krow = (uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
+      uint16_t* vrow = (uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
+      // threads from the top of the workgroup, so that they do not also rotate query pairs
+      for (uint32_t i = kThreads - 1 - threadIdx.x; i < half / 2 + half; i += kThreads) {
         if (i < half / 2) {   // two adjacent rotation pairs of the key
           uint32_t e = 2 * i;
           float2 lo = ld_act2(ksrc + e), hi = ld_act2(ksrc + e + half);
@@ -450,102 +537,135 @@ __device__ void body_attn_partial(const TaskDesc& t, const StepArgs& a, float* l
     for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) qs[i] = ld_act(qsrc + i);
   }
   __syncthreads();
-  const uint16_t* Kb = (const uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.max_seq + t0) * d;
-  const uint16_t* Vb = (const uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.max_seq + t0) * d;
-  const uint32_t LPP = d / 8, PPW = 64 / LPP;   // lanes per position, positions per wavefront step
-  const uint32_t sub = lane % LPP, slot = lane / LPP;
-  const float inv_sqrt_d = 1.0f / sqrtf((float)d);
-  // ---- scores
-  for (uint32_t base = wave * PPW; base < n; base += (kThreads / 64) * PPW) {
-    uint32_t i = base + slot;
-    bool valid = i < n;
-    // the row appended during this step was written by another workgroup: coherent load
-    u32x4 kv = u32x4{0, 0, 0, 0};
-    if (valid) {
-      const uint16_t* kp = Kb + (size_t)i * d + sub * 8;
-      kv = (t0 + i == (uint32_t)pos) ? ld_row16_coherent(kp) : __builtin_nontemporal_load((const u32x4*)kp);
-    }
-    for (uint32_t j = 0; j < grp; ++j) {
-      const float4* qp = (const float4*)(qs + j * d + sub * 8);
-      float s = dot8(kv, qp[0], qp[1], 0.f);
-      for (uint32_t off = 1; off < LPP; off <<= 1) s += __shfl_xor(s, off, 64);
-      if (valid && sub == 0) sc[j * nmax + i] = s * inv_sqrt_d;
-    }
-  }
-  __syncthreads();
-  // ---- softmax statistics of the chunk, one wavefront per query head
-  if ((uint32_t)wave < grp) {
-    float* s = sc + wave * nmax;
-    float m = -INFINITY;
-    for (uint32_t i = lane; i < n; i += 64) m = fmaxf(m, s[i]);
-    m = wave_max(m);
-    float l = 0.f;
-    for (uint32_t i = lane; i < n; i += 64) {
-      float p = expf(s[i] - m);
-      s[i] = p;
-      l += p;
-    }
-    l = wave_sum(l);
-    if (lane == 0) {
-      ml[wave * 2] = m;
-      ml[wave * 2 + 1] = l;
-    }
-  }
-  __syncthreads();
-  // ---- P.V
-  float acc[8][8];
+  trace_mark(a, t, 2);
+  // The row appended during this step is read with coherent loads (it was written after the
+  // pre-load, by this or another workgroup); it can only be the last position of the last chunk.
+  if (c == C - 1) {
+    const uint32_t i_new = n - 1;
 #pragma unroll
-  for (int j = 0; j < 8; ++j)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[j][e] = 0.f;
-  for (uint32_t base = wave * PPW; base < n; base += (kThreads / 64) * PPW) {
-    uint32_t i = base + slot;
-    if (i < n) {
-      const uint16_t* vp = Vb + (size_t)i * d + sub * 8;
-      u32x4 vv = (t0 + i == (uint32_t)pos) ? ld_row16_coherent(vp) : __builtin_nontemporal_load((const u32x4*)vp);
-      float v[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
-                    bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        if ((uint32_t)j < grp) {
-          float p = sc[j * nmax + i];
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p, v[e], acc[j][e]);
-        }
+    for (int r = 0; r < kAttnRounds; ++r) {
+      if (i_first + r * stride == i_new) {
+        kreg[r] = ld_row16_coherent(Kb + (size_t)i_new * d + sub * 8);
+        vreg[r] = ld_row16_coherent(Vb + (size_t)i_new * d + sub * 8);
       }
     }
   }
+  // ---- per block of HB heads (bounds the register footprint): scores, softmax statistics and
+  // P.V, all in registers; sreg[r][j] belongs to position i_first + r * stride, head jb + j
+  constexpr int HB = GRP < 4 ? GRP : 4;
+  const float inv_sqrt_d = 1.0f / sqrtf((float)d);
+  float* mxch = wpart + NW * grp * (d + 2) + 16;   // [NW][HB] maxima exchange
+  float m_all[GRP];
+#pragma unroll 1
+  for (int jb = 0; jb < GRP; jb += HB) {
+    float q[HB][8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    if ((uint32_t)j < grp) {
+    for (int j = 0; j < HB; ++j) {
+      const float4* qp = (const float4*)(qs + (jb + j) * d + sub * 8);
+      float4 q0 = qp[0], q1 = qp[1];
+      q[j][0] = q0.x; q[j][1] = q0.y; q[j][2] = q0.z; q[j][3] = q0.w;
+      q[j][4] = q1.x; q[j][5] = q1.y; q[j][6] = q1.z; q[j][7] = q1.w;
+    }
+    float sreg[kAttnRounds][HB];
+    float mloc[HB];
+#pragma unroll
+    for (int j = 0; j < HB; ++j) mloc[j] = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < kAttnRounds; ++r) {
+      const bool valid = i_first + r * stride < n;
+      const u32x4 kv = kreg[r];
+      const float k8[8] = {bf16_lo(kv.x), bf16_hi(kv.x), bf16_lo(kv.y), bf16_hi(kv.y),
+                           bf16_lo(kv.z), bf16_hi(kv.z), bf16_lo(kv.w), bf16_hi(kv.w)};
+#pragma unroll
+      for (int j = 0; j < HB; ++j) {
+        float sv = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sv = fmaf(k8[e], q[j][e], sv);
+        sv = group_sum<LPP>(sv) * inv_sqrt_d;
+        sreg[r][j] = valid ? sv : -INFINITY;
+        mloc[j] = fmaxf(mloc[j], sreg[r][j]);
+      }
+    }
+    // chunk maximum per head: across position slots, then across wavefronts
+#pragma unroll
+    for (int j = 0; j < HB; ++j) {
+#pragma unroll
+      for (uint32_t off = LPP; off < 64; off <<= 1) mloc[j] = fmaxf(mloc[j], __shfl_xor(mloc[j], off, 64));
+      if (lane == 0) mxch[wave * HB + j] = mloc[j];
+    }
+    __syncthreads();
+    float m[HB];
+#pragma unroll
+    for (int j = 0; j < HB; ++j) {
+      float v = mxch[j];
+#pragma unroll
+      for (uint32_t w = 1; w < NW; ++w) v = fmaxf(v, mxch[w * HB + j]);
+      m[j] = v;
+      m_all[jb + j] = v;
+    }
+    // ---- probabilities and P.V
+    float acc[HB][8], lsum[HB];
+#pragma unroll
+    for (int j = 0; j < HB; ++j) {
+      lsum[j] = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[j][e] = 0.f;
+    }
+#pragma unroll
+    for (int r = 0; r < kAttnRounds; ++r) {
+      const u32x4 vv = vreg[r];
+      const float v8[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
+                           bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
+#pragma unroll
+      for (int j = 0; j < HB; ++j) {
+        const float p = (sreg[r][j] == -INFINITY) ? 0.f : expf(sreg[r][j] - m[j]);
+        lsum[j] += p;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p, v8[e], acc[j][e]);
+      }
+    }
+    // reduce over the position slots of the wavefront; wavefront partials go to LDS
+#pragma unroll
+    for (int j = 0; j < HB; ++j) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         float v = acc[j][e];
+#pragma unroll
         for (uint32_t off = LPP; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
-        if (slot == 0) wpart[((size_t)wave * grp + j) * d + sub * 8 + e] = v;
+        if (slot == 0) wpart[((size_t)wave * grp + jb + j) * (d + 2) + sub * 8 + e] = v;
       }
+      float lv = lsum[j];   // every lane of a position group holds the same p: count each once
+#pragma unroll
+      for (uint32_t off = LPP; off < 64; off <<= 1) lv += __shfl_xor(lv, off, 64);
+      if (lane == 0) wpart[((size_t)wave * grp + jb + j) * (d + 2) + d + 1] = lv;
     }
+    __syncthreads();   // also protects mxch before the next block
   }
-  __syncthreads();
-  for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) {
-    uint32_t j = i / d, dim = i % d;
-    float s = 0.f;
-    for (uint32_t w = 0; w < kThreads / 64; ++w) s += wpart[((size_t)w * grp + j) * d + dim];
-    st_act(outp + j * (d + 2) + dim, s);
+  trace_mark(a, t, 10);
+  for (uint32_t i = threadIdx.x; i < grp * (d + 2); i += kThreads) {
+    const uint32_t j = i / (d + 2), dim = i % (d + 2);
+    float sv;
+    if (dim == d) {
+      sv = m_all[0];
+#pragma unroll
+      for (int jj = 1; jj < GRP; ++jj) sv = (j == (uint32_t)jj) ? m_all[jj] : sv;
+    } else {
+      sv = 0.f;
+#pragma unroll
+      for (uint32_t w = 0; w < NW; ++w) sv += wpart[((size_t)w * grp + j) * (d + 2) + dim];
+    }
+    st_act(outp + i, sv);
   }
-  if (threadIdx.x < grp) {
-    st_act(outp + threadIdx.x * (d + 2) + d, ml[threadIdx.x * 2]);
-    st_act(outp + threadIdx.x * (d + 2) + d + 1, ml[threadIdx.x * 2 + 1]);
-  }
+  trace_mark(a, t, 11);
   if (t.flags & TF_ATTN_MERGE) {
     // Arrival counter of (layer, sequence, KV head): the chunk task that arrives last sees all C
-    // partials complete and merges them (log-sum-exp) into the attention output.
-    uint32_t* flag = (uint32_t*)(ml + 2 * 8);
+    // partials complete and merges them (log-sum-exp, one pass with running maximum) into the
+    // attention output.
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
-      uint32_t* cnt = a.grp_counters + t.p2 + b * nkv + g;
+      uint32_t* cnt = a.g->grp_counters + t.p2 + b * nkv + g;
       uint32_t old = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       *flag = ((old + 1u) % C == 0u) ? 1u : 0u;   // every step adds exactly C
     }
@@ -555,24 +675,40 @@ __device__ void body_attn_partial(const TaskDesc& t, const StepArgs& a, float* l
       float* o = const_cast<float*>(t.in2) + (size_t)b * nq * d + (size_t)g * grp * d;
       for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) {
         uint32_t j = i / d, dim = i % d;
-        float M = -INFINITY;
-        for (uint32_t cc = 0; cc < C; ++cc) M = fmaxf(M, ld_act(part + ((size_t)cc * grp + j) * (d + 2) + d));
-        float L = 0.f, acc_o = 0.f;
-        for (uint32_t cc = 0; cc < C; ++cc) {
-          const float* pp = part + ((size_t)cc * grp + j) * (d + 2);
-          float wgt = expf(ld_act(pp + d) - M);
-          L = fmaf(wgt, ld_act(pp + d + 1), L);
-          acc_o = fmaf(wgt, ld_act(pp + dim), acc_o);
+        float M = -INFINITY, L = 0.f, acc_o = 0.f;
+        for (uint32_t c0 = 0; c0 < C; c0 += 4) {   // 12 coherent loads in flight
+          float mm[4], ll[4], oo[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            if (c0 + k < C) {
+              const float* pp = part + ((size_t)(c0 + k) * grp + j) * (d + 2);
+              mm[k] = ld_act(pp + d);
+              ll[k] = ld_act(pp + d + 1);
+              oo[k] = ld_act(pp + dim);
+            } else {
+              mm[k] = -INFINITY; ll[k] = 0.f; oo[k] = 0.f;
+            }
+          }
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            float Mn = fmaxf(M, mm[k]);
+            if (Mn == -INFINITY) continue;   // empty chunks only so far
+            float sc_old = expf(M - Mn), sc_new = expf(mm[k] - Mn);
+            L = L * sc_old + ll[k] * sc_new;
+            acc_o = acc_o * sc_old + oo[k] * sc_new;
+            M = Mn;
+          }
         }
         st_act(o + i, acc_o / L);
       }
     }
   }
+  return true;
 }
 
 // T5: merge the chunk partials of each query head with the log-sum-exp rule.
-__device__ void body_attn_merge(const TaskDesc& t, const StepArgs& a) {
-  const uint32_t d = a.head_dim, grp = a.n_q / a.n_kv, C = t.p1;
+__device__ __forceinline__ void body_attn_merge(const TaskDesc& t, const StepArgs& a) {
+  const uint32_t d = a.g->head_dim, grp = a.g->n_q / a.g->n_kv, C = t.p1;
   const uint32_t h0 = t.c0 / d, h1 = t.c1 / d;
   for (uint32_t b = t.b0; b < t.b1; ++b) {
     const float* part = t.in + (size_t)b * t.ld_in;
@@ -593,7 +729,7 @@ __device__ void body_attn_merge(const TaskDesc& t, const StepArgs& a) {
   }
 }
 
-__device__ void body_add(const TaskDesc& t) {
+__device__ __forceinline__ void body_add(const TaskDesc& t) {
   const uint32_t nc = t.c1 - t.c0;
   for (uint32_t b = t.b0; b < t.b1; ++b)
     for (uint32_t i = threadIdx.x; i < nc; i += kThreads) {
@@ -602,7 +738,7 @@ __device__ void body_add(const TaskDesc& t) {
     }
 }
 
-__device__ void body_swiglu(const TaskDesc& t) {
+__device__ __forceinline__ void body_swiglu(const TaskDesc& t) {
   const uint32_t nc = t.c1 - t.c0, F = t.p0;
   for (uint32_t b = t.b0; b < t.b1; ++b)
     for (uint32_t i = threadIdx.x; i < nc; i += kThreads) {
@@ -613,20 +749,42 @@ __device__ void body_swiglu(const TaskDesc& t) {
 }
 
 // Runs one task.  wait_ev >= 0: the task must first wait for that event (persistent kernel);
-// linear tasks do so after requesting their first weight block.  Returns false on abort.
-__device__ bool run_task(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
-                         uint32_t* s_flag) {
+// linear and attention tasks do so after requesting their first weight / cache block.
+// D, GRP, NB pin head_dim, query heads per KV head and the batch class at compile time (0 = decide
+// at run time): a kernel that carries a single attention and a single linear variant keeps its
+// register allocation free of spills, the fully generic kernel does not.
+template <int D, int GRP, int NB>
+__device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, float* lds,
+                                         int32_t wait_ev, uint32_t* s_flag) {
   if (t.kind == TK_LINEAR) {
     const uint32_t nb = t.b1 - t.b0;
     const uint32_t G = (t.flags & TF_GATEUP) ? 2u : 1u;
     const uint32_t rows_per_wave = ((t.c1 - t.c0) * G + kThreads / 64 - 1) / (kThreads / 64);
-    if (nb == 1) {
+    if (NB == 1 || (NB == 0 && nb == 1)) {
       if (rows_per_wave <= 2) return body_linear<1, 2, 8>(t, a, lds, wait_ev, s_flag);
       return body_linear<1, 4, 8>(t, a, lds, wait_ev, s_flag);
     }
-    if (nb == 2) return body_linear<2, 4, 4>(t, a, lds, wait_ev, s_flag);
-    if (nb <= 4) return body_linear<4, 2, 4>(t, a, lds, wait_ev, s_flag);
-    return body_linear<8, 2, 4>(t, a, lds, wait_ev, s_flag);
+    if (NB == 8) return body_linear<8, 2, 4>(t, a, lds, wait_ev, s_flag);
+    if (NB == 0) {
+      if (nb == 2) return body_linear<2, 4, 4>(t, a, lds, wait_ev, s_flag);
+      if (nb <= 4) return body_linear<4, 2, 4>(t, a, lds, wait_ev, s_flag);
+      return body_linear<8, 2, 4>(t, a, lds, wait_ev, s_flag);
+    }
+    return false;
+  }
+  if (t.kind == TK_ATTN_PARTIAL) {
+    if (D != 0) return body_attn_partial<(D ? D : 128), (GRP ? GRP : 1)>(t, a, lds, wait_ev, s_flag);
+    const uint32_t grp = a.g->n_q / a.g->n_kv;
+    if (a.g->head_dim == 128) {
+      if (grp == 8) return body_attn_partial<128, 8>(t, a, lds, wait_ev, s_flag);
+      if (grp == 4) return body_attn_partial<128, 4>(t, a, lds, wait_ev, s_flag);
+      if (grp == 2) return body_attn_partial<128, 2>(t, a, lds, wait_ev, s_flag);
+      return body_attn_partial<128, 1>(t, a, lds, wait_ev, s_flag);
+    }
+    if (grp == 8) return body_attn_partial<64, 8>(t, a, lds, wait_ev, s_flag);
+    if (grp == 4) return body_attn_partial<64, 4>(t, a, lds, wait_ev, s_flag);
+    if (grp == 2) return body_attn_partial<64, 2>(t, a, lds, wait_ev, s_flag);
+    return body_attn_partial<64, 1>(t, a, lds, wait_ev, s_flag);
   }
   if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
   trace_mark(a, t, 1);
@@ -634,7 +792,6 @@ __device__ bool run_task(const TaskDesc& t, const StepArgs& a, float* lds, int32
     case TK_EMBED: body_embed(t, a); break;
     case TK_RMSNORM: body_rmsnorm(t, lds); break;
     case TK_ROPE: body_rope(t, a); break;
-    case TK_ATTN_PARTIAL: body_attn_partial(t, a, lds); break;
     case TK_ATTN_MERGE: body_attn_merge(t, a); break;
     case TK_ADD: body_add(t); break;
     case TK_SWIGLU: body_swiglu(t); break;
@@ -649,21 +806,30 @@ __device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p) {
 }
 
 // Returns false when the step is being aborted (watchdog or a peer's failure).
-__device__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag) {
+// Simple events: wait until counter >= epoch * required.  Hierarchical events: wait until this
+// worker group's ready flag has reached the epoch.
+__device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag) {
   if (threadIdx.x == 0) {
-    const uint32_t target = a.epoch * a.events[e].required;
-    const uint32_t* cnt = a.counters + e;
+    const EventDesc& ev = a.g->events[e];
+    const uint32_t* word;
+    uint32_t target;
+    if (ev.flags & EV_HIER) {
+      word = a.g->hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
+      target = a.epoch;
+    } else {
+      word = a.g->counters + e;
+      target = a.epoch * ev.required;
+    }
     uint32_t ok = 1;
-    if ((int32_t)(ld_relaxed(cnt) - target) < 0) {
+    if ((int32_t)(ld_relaxed(word) - target) < 0) {
       const uint64_t t_start = wall_clock64();
       uint32_t it = 0;
-      while ((int32_t)(ld_relaxed(cnt) - target) < 0) {
-        __builtin_amdgcn_s_sleep(1);
-        if ((++it & 127u) == 0) {
-          if (ld_relaxed(a.err + 1) != 0) { ok = 0; break; }
-          if (wall_clock64() - t_start > a.timeout_ticks) {
+      while ((int32_t)(ld_relaxed(word) - target) < 0) {
+        if ((++it & 255u) == 0) {
+          if (ld_relaxed(a.g->err + 1) != 0) { ok = 0; break; }
+          if (wall_clock64() - t_start > a.g->timeout_ticks) {
             report(a, DE_TIMEOUT, (uint32_t)e, blockIdx.x);
-            __hip_atomic_store(a.err + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(a.g->err + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             ok = 0;
             break;
           }
@@ -676,42 +842,79 @@ __device__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag) {
   return *s_flag != 0;
 }
 
-__device__ void signal_event(const StepArgs& a, int32_t e) {
+__device__ __forceinline__ void signal_event(const StepArgs& a, const TaskDesc& t, int32_t e) {
   // every wavefront waits until its own agent-scope stores have completed at the coherence point
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  trace_mark(a, t, 6);
   __syncthreads();
-  if (threadIdx.x == 0)
-    __hip_atomic_fetch_add(a.counters + e, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  trace_mark(a, t, 7);
+  if (threadIdx.x == 0) {
+    const EventDesc& ev = a.g->events[e];
+    if (ev.flags & EV_HIER) {
+      uint32_t* blk = a.g->hier + (size_t)ev.hier_slot * kHierWordsPerEvent;
+      const uint32_t grp = blockIdx.x & 7u;
+      uint32_t old = __hip_atomic_fetch_add(blk + (1 + grp) * kHierStrideWords, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (old + 1u == a.epoch * ev.sub_required[grp]) {          // last arrival of this group
+        old = __hip_atomic_fetch_add(blk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old + 1u == a.epoch * ev.n_groups) {                 // last group: the event is activated
+#pragma unroll
+          for (uint32_t k = 0; k < 8; ++k)
+            __hip_atomic_store(blk + (9 + k) * kHierStrideWords, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+    } else {
+      __hip_atomic_fetch_add(a.g->counters + e, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
 }
 
-extern "C" __global__ void __launch_bounds__(kThreads)
-mpk_mega_kernel(StepArgs a) {
+template <int D, int GRP, int NB>
+__global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
   extern __shared__ __align__(16) float lds[];
   __shared__ uint32_t s_flag;
   const uint32_t w = blockIdx.x;
-  if (w >= a.n_workers) return;
-  const uint32_t q0 = a.aot_off[w], q1 = a.aot_off[w + 1];
+  if (w >= a.g->n_workers) return;
+  const uint32_t q0 = a.g->aot_off[w], q1 = a.g->aot_off[w + 1];
   for (uint32_t qi = q0; qi < q1; ++qi) {
-    const TaskDesc& t = a.tasks[a.aot[qi]];
-    const int32_t wait_ev = (t.dep_event >= 0 && a.events[t.dep_event].required != 0) ? t.dep_event : -1;
+    const TaskDesc& t = a.g->tasks[a.g->aot[qi]];
+    const int32_t wait_ev = (t.dep_event >= 0 && a.g->events[t.dep_event].required != 0) ? t.dep_event : -1;
     trace_mark(a, t, 0);
-    if (!run_task(t, a, lds, wait_ev, &s_flag)) break;
+    if (!run_task<D, GRP, NB>(t, a, lds, wait_ev, &s_flag)) break;
     trace_mark(a, t, 3);
-    if (t.trig_event >= 0) signal_event(a, t.trig_event);
+    if (t.trig_event >= 0) signal_event(a, t, t.trig_event);
     else __syncthreads();
     trace_mark(a, t, 4);
-    if (a.trace && threadIdx.x == 0) a.trace[(size_t)(&t - a.tasks) * kTraceSlots + 5] = blockIdx.x;
+    if (a.g->trace && threadIdx.x == 0) a.g->trace[(size_t)(&t - a.g->tasks) * kTraceSlots + 5] = blockIdx.x;
   }
 }
 
 // Kernel-per-operator baseline: the same task bodies, one launch per operator, dependencies
 // enforced by stream order (what the paper's comparison systems do, Section 6.5).
-extern "C" __global__ void __launch_bounds__(kThreads)
-mpk_op_kernel(StepArgs a, uint32_t first) {
+template <int D, int GRP, int NB>
+__global__ void __launch_bounds__(kThreads) mpk_op_kernel(StepArgs a, uint32_t first) {
   extern __shared__ __align__(16) float lds[];
-  const TaskDesc& t = a.tasks[a.op_list[first + blockIdx.x]];
-  run_task(t, a, lds, -1, nullptr);
+  const TaskDesc& t = a.g->tasks[a.g->op_list[first + blockIdx.x]];
+  run_task<D, GRP, NB>(t, a, lds, -1, nullptr);
+}
+
+// Specialised kernel pairs; {0, 0, 0} is the generic fallback.
+struct KernelVariant {
+  int d, grp, nb;
+  void (*mega)(StepArgs);
+  void (*op)(StepArgs, uint32_t);
+};
+#define MPK_VARIANT(D, G, N) {D, G, N, mpk_mega_kernel<D, G, N>, mpk_op_kernel<D, G, N>}
+static const KernelVariant kVariants[] = {
+    MPK_VARIANT(64, 2, 1), MPK_VARIANT(128, 4, 1), MPK_VARIANT(128, 8, 1),
+    MPK_VARIANT(128, 4, 8), MPK_VARIANT(0, 0, 0),
+};
+static const KernelVariant* pick_variant(uint32_t d, uint32_t grp, uint32_t batch) {
+  int nb = batch == 1 ? 1 : (batch > 4 && batch <= 8 ? 8 : -1);
+  const int n = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+  for (int i = 0; i < n; ++i)
+    if (kVariants[i].d == (int)d && kVariants[i].grp == (int)grp && kVariants[i].nb == nb) return &kVariants[i];
+  return &kVariants[n - 1];
 }
 
 }  // namespace mpk
@@ -733,7 +936,10 @@ struct mpk_graph {
   uint32_t* d_err = nullptr;
   double* d_inv_freq = nullptr;
   uint64_t* d_trace = nullptr;
+  GraphConst* d_const = nullptr;
+  const KernelVariant* kv = nullptr;
   uint32_t* d_grp = nullptr;
+  uint32_t* d_hier = nullptr;
   float* d_arena = nullptr;
   std::vector<uint32_t> op_first, op_count;   // per operator: range in op_list
   uint32_t epoch = 0;
@@ -754,7 +960,7 @@ static void free_device(mpk_graph* g) {
   (void)hipFree(g->d_tasks); (void)hipFree(g->d_events); (void)hipFree(g->d_counters);
   (void)hipFree(g->d_aot_off); (void)hipFree(g->d_aot); (void)hipFree(g->d_op_list);
   (void)hipFree(g->d_err); (void)hipFree(g->d_arena);
-  (void)hipFree(g->d_inv_freq); (void)hipFree(g->d_grp); (void)hipFree(g->d_trace);
+  (void)hipFree(g->d_inv_freq); (void)hipFree(g->d_grp); (void)hipFree(g->d_trace); (void)hipFree(g->d_hier); (void)hipFree(g->d_const);
 }
 
 static mpk_status resolve_options(const mpk_compile_options* in, mpk_compile_options* out,
@@ -823,11 +1029,12 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
   if (hipGetDevice(&g->device) != hipSuccess) { set_error("hipGetDevice failed"); return fail(MPK_ERR_HIP); }
   HostGraph& h = g->h;
   // residency: dynamic LDS above half of a CU's 160 KB caps occupancy at one workgroup per CU
-  hipError_t e = hipFuncSetAttribute((const void*)mpk_mega_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h.lds_bytes);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)mpk_op_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h.lds_bytes);
+  g->kv = pick_variant(cfg->head_dim, cfg->n_q_heads / cfg->n_kv_heads, cfg->batch);
+  hipError_t e = hipFuncSetAttribute((const void*)g->kv->mega, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h.lds_bytes);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)g->kv->op, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h.lds_bytes);
   if (e != hipSuccess) { set_error("cannot reserve %u bytes of LDS: %s", h.lds_bytes, hipGetErrorString(e)); return fail(MPK_ERR_RESIDENCY); }
   int per_cu = 0;
-  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)mpk_mega_kernel, kThreads, h.lds_bytes);
+  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)g->kv->mega, kThreads, h.lds_bytes);
   if (e != hipSuccess || per_cu < 1) { set_error("persistent kernel does not fit on a CU (occupancy %d, %s)", per_cu, hipGetErrorString(e)); return fail(MPK_ERR_RESIDENCY); }
   if (o.launch_mode == MPK_LAUNCH_MEGA && (uint64_t)per_cu * n_cu < (uint64_t)o.n_workers + o.n_sched_wgs) {
     set_error("%u workgroups cannot be co-resident on %d CUs x %d", o.n_workers + o.n_sched_wgs, n_cu, per_cu);
@@ -875,11 +1082,27 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
     std::vector<uint32_t> gz(h.n_group_counters, 0);
     if ((st = upload(&g->d_grp, gz)) != MPK_OK) return fail(st);
   }
+  {
+    std::vector<uint32_t> hz((size_t)std::max(h.n_hier_events, 1u) * kHierWordsPerEvent, 0);
+    if ((st = upload(&g->d_hier, hz)) != MPK_OK) return fail(st);
+  }
   if (o.debug_flags & MPK_DEBUG_TRACE) {
     std::vector<uint64_t> tz(h.tasks.size() * kTraceSlots, 0);
     if ((st = upload(&g->d_trace, tz)) != MPK_OK) return fail(st);
   }
   g->timeout_ticks = (uint64_t)o.spin_timeout_ms * 100000ull;   // wall clock counts at 100 MHz
+  {
+    GraphConst c{};
+    c.tasks = g->d_tasks; c.events = g->d_events; c.counters = g->d_counters; c.hier = g->d_hier;
+    c.aot_off = g->d_aot_off; c.aot = g->d_aot; c.op_list = g->d_op_list; c.err = g->d_err;
+    c.inv_freq = g->d_inv_freq; c.grp_counters = g->d_grp; c.trace = g->d_trace;
+    c.timeout_ticks = g->timeout_ticks;
+    c.n_workers = h.opt.n_workers;
+    c.vocab = h.cfg.vocab; c.max_seq = h.cfg.max_seq; c.n_q = h.cfg.n_q_heads;
+    c.n_kv = h.cfg.n_kv_heads; c.head_dim = h.cfg.head_dim; c.batch = h.cfg.batch;
+    std::vector<GraphConst> cv(1, c);
+    if ((st = upload(&g->d_const, cv)) != MPK_OK) return fail(st);
+  }
   *out = g;
   return MPK_OK;
 }
@@ -909,24 +1132,18 @@ extern "C" mpk_status mpk_decode_step(mpk_graph* g, const int32_t* token_ids,
   if (g->host_only) { set_error("graph was compiled host_only"); return MPK_ERR_INVALID_ARG; }
   HostGraph& h = g->h;
   StepArgs a{};
-  a.tasks = g->d_tasks; a.events = g->d_events; a.counters = g->d_counters;
-  a.aot_off = g->d_aot_off; a.aot = g->d_aot; a.op_list = g->d_op_list;
-  a.token_ids = token_ids; a.positions = positions; a.logits = logits_out; a.err = g->d_err;
-  a.timeout_ticks = g->timeout_ticks;
-  a.inv_freq = g->d_inv_freq; a.grp_counters = g->d_grp; a.trace = g->d_trace;
-  a.n_workers = h.opt.n_workers;
-  a.vocab = h.cfg.vocab; a.max_seq = h.cfg.max_seq; a.n_q = h.cfg.n_q_heads;
-  a.n_kv = h.cfg.n_kv_heads; a.head_dim = h.cfg.head_dim; a.batch = h.cfg.batch;
+  a.g = g->d_const;
+  a.token_ids = token_ids; a.positions = positions; a.logits = logits_out;
   hipStream_t s = (hipStream_t)stream;
   a.epoch = ++g->epoch;
   if (h.opt.launch_mode == MPK_LAUNCH_MEGA) {
-    hipLaunchKernelGGL(mpk_mega_kernel, dim3(h.opt.n_workers + h.opt.n_sched_wgs), dim3(kThreads),
+    hipLaunchKernelGGL(g->kv->mega, dim3(h.opt.n_workers + h.opt.n_sched_wgs), dim3(kThreads),
                        h.lds_bytes, s, a);
     HIP_TRY(hipGetLastError());
   } else {
     for (size_t oi = 0; oi < h.ops.size(); ++oi) {
       if (!g->op_count[oi]) continue;
-      hipLaunchKernelGGL(mpk_op_kernel, dim3(g->op_count[oi]), dim3(kThreads), h.lds_bytes, s, a,
+      hipLaunchKernelGGL(g->kv->op, dim3(g->op_count[oi]), dim3(kThreads), h.lds_bytes, s, a,
                          g->op_first[oi]);
     }
     HIP_TRY(hipGetLastError());
@@ -960,6 +1177,7 @@ extern "C" mpk_status mpk_graph_reset(mpk_graph* g) {
   HIP_TRY(hipDeviceSynchronize());
   HIP_TRY(hipMemset(g->d_counters, 0, g->h.events.size() * sizeof(uint32_t)));
   HIP_TRY(hipMemset(g->d_err, 0, 8 * sizeof(uint32_t)));
+  HIP_TRY(hipMemset(g->d_hier, 0, (size_t)std::max(g->h.n_hier_events, 1u) * kHierWordsPerEvent * sizeof(uint32_t)));
   HIP_TRY(hipMemset(g->d_grp, 0, std::max<size_t>(g->h.n_group_counters, 1) * sizeof(uint32_t)));
   HIP_TRY(hipDeviceSynchronize());
   g->epoch = 0;
