@@ -57,9 +57,14 @@ def main():
     ap.add_argument("--steps", type=int, default=32)
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--config", default="C2")
-    ap.add_argument("--fusion", type=int, default=7)
+    ap.add_argument("--fusion", type=int, default=31)
     ap.add_argument("--no-baselines", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one plain copy kernel of this many MiB (synth_copy_kernel): "
+                         "a launch of known HBM traffic to scale profiler byte counters by")
+    ap.add_argument("--opt", action="append", default=[], metavar="NAME=INT",
+                    help="extra mpk_compile_options field, e.g. --opt attn_chunks=32")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -116,6 +121,7 @@ def main():
         return dt, kern_ms
 
     common = dict(fusion=args.fusion, transitive_reduction=1)
+    common.update({k: int(v) for k, v in (o.split("=", 1) for o in args.opt)})
     mega = M.compile_graph(shape, model.weight_ptrs(), model.kv_ptrs(), launch_mode=0, **common)
     stats = mega.stats()
     dt, kern_ms = timed(mega)
@@ -149,6 +155,12 @@ def main():
         "final_tokens": final_tokens,
     }
     mega.destroy()
+    if args.calib_copy_mib:
+        a = torch.zeros(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        G.copy_device(b, a)
+        torch.cuda.synchronize()
+        del a, b
     if not args.no_baselines:
         per_op = M.compile_graph(shape, model.weight_ptrs(), model.kv_ptrs(), launch_mode=1, **common)
         dt_e, _ = timed(per_op)

@@ -211,6 +211,9 @@ def _hip_lib():
                                            ctypes.c_uint64, ctypes.c_uint64, ctypes.c_void_p,
                                            ctypes.c_void_p]
     lib.synth_fill_bf16_device.restype = ctypes.c_int
+    lib.synth_copy_device.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
+                                      ctypes.c_void_p]
+    lib.synth_copy_device.restype = ctypes.c_int
     return lib
 
 
@@ -230,6 +233,18 @@ def fill_device(t, seed: int, tid: int, i0: int = 0, kind: str = "w"):
     if rc != 0:
         raise RuntimeError(f"synth_fill_bf16_device: hip error {rc}")
     return t
+
+
+def copy_device(dst, src):
+    """Plain device copy kernel of known traffic (reads and writes dst.nbytes once each)."""
+    import torch
+    assert dst.is_cuda and src.is_cuda and dst.is_contiguous() and src.is_contiguous()
+    n = dst.numel() * dst.element_size()
+    assert n == src.numel() * src.element_size()
+    rc = _hip_lib().synth_copy_device(dst.data_ptr(), src.data_ptr(), n,
+                                      torch.cuda.current_stream().cuda_stream)
+    if rc != 0:
+        raise RuntimeError(f"synth_copy_device: error {rc}")
 
 
 # ----------------------------------------------------------------------------- workload pieces

@@ -31,3 +31,17 @@ extern "C" int synth_fill_bf16_device(void* out, uint64_t seed, uint64_t tid, ui
                      (const uint16_t*)table);
   return (int)hipGetLastError();
 }
+
+// Plain copy of n 16-byte words (counter calibration: a kernel whose HBM traffic is known, to
+// scale profiler byte counters by).  Asynchronous on `stream`.
+__global__ void synth_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, uint64_t n) {
+  uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += stride) dst[k] = src[k];
+}
+
+extern "C" int synth_copy_device(void* dst, const void* src, uint64_t bytes, void* stream) {
+  if (bytes == 0 || (bytes & 15)) return bytes ? 1 : 0;
+  hipLaunchKernelGGL(synth_copy_kernel, dim3(4096), dim3(256), 0, (hipStream_t)stream,
+                     (const uint4*)src, (uint4*)dst, bytes / 16);
+  return (int)hipGetLastError();
+}

@@ -1,0 +1,64 @@
+#!/usr/bin/env python3
+"""Writes the expected-output fixtures for the full-size configurations by running ONLY the CPU
+oracle (oracle/) on the seeded synthetic inputs (synth/).  Nothing here touches the GPU library.
+
+    python tests/golden/make_golden.py C2        # Qwen3-8B-shaped, batch 1, 32 greedy steps
+
+Each fixture is a small JSON file: greedy tokens of every step, the top-8 logits (index, value)
+of every step, and 512 pseudo-randomly sampled logits of step 0 and of the last step.
+"""
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+from oracle import decoder as D  # noqa: E402
+from synth import gen as G  # noqa: E402
+
+
+def sample_indices(vocab, n=512):
+    return (G.mix64(99, 77, np.arange(n, dtype=np.uint64)) % np.uint64(vocab)).astype(np.int64)
+
+
+def main():
+    name = sys.argv[1] if len(sys.argv) > 1 else "C2"
+    steps = int(sys.argv[2]) if len(sys.argv) > 2 else G.CONFIGS[name].steps
+    s = G.CONFIGS[name]
+    seed = 0
+    cache = s.n_layers * s.hidden * (3 * s.ffn + 2 * s.hidden) * 2 < 40e9
+    o = D.DecoderOracle(s, G.SynthWeights(s, seed, cache=cache), "f32")
+    tok, pos = G.tokens(seed, s).astype(np.int64), G.kv_lengths(seed, s).astype(np.int64)
+    idx = sample_indices(s.vocab)
+    out = {"config": name, "seed": seed, "steps": steps, "start_tokens": tok.tolist(),
+           "start_positions": pos.tolist(), "sample_indices": idx.tolist(), "tokens": [],
+           "top8": [], "samples": {}, "top2_gap_min": None}
+    gap = np.inf
+    t0 = time.time()
+    for i in range(steps):
+        lg = o.step(tok, pos)
+        nxt = np.array([o.ops.argmax(lg[b]) for b in range(s.batch)], np.int64)
+        top = []
+        for b in range(s.batch):
+            order = np.argsort(-lg[b], kind="stable")[:8]
+            top.append([[int(j), float(lg[b, j])] for j in order])
+            gap = min(gap, float(lg[b, order[0]] - lg[b, order[1]]))
+        out["tokens"].append(nxt.tolist())
+        out["top8"].append(top)
+        if i in (0, steps - 1):
+            out["samples"][str(i)] = [[float(v) for v in lg[b, idx]] for b in range(s.batch)]
+            out["absmax_%d" % i] = [float(np.abs(lg[b]).max()) for b in range(s.batch)]
+        tok, pos = nxt, pos + 1
+        print(f"step {i}: tokens {nxt.tolist()}  ({time.time() - t0:.0f} s)", flush=True)
+    out["top2_gap_min"] = gap
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"{name}_greedy.json")
+    with open(path, "w") as f:
+        json.dump(out, f)
+    print("wrote", path)
+
+
+if __name__ == "__main__":
+    main()

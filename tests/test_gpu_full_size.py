@@ -1,0 +1,73 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The expected values are fixtures written by tests/golden/make_golden.py, which calls only the CPU
+oracle: greedy tokens of every step, the eight largest logits of every step and 512 sampled
+logits of the first and the last step."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from synth import gen as G
+from tests.gpu_util import GpuDecoder
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+BENCH_OPTS = dict(fusion=31, transitive_reduction=1)
+
+
+def _load(name):
+    path = os.path.join(GOLDEN, f"{name}_greedy.json")
+    if not os.path.exists(path):
+        pytest.skip(f"no fixture {path}")
+    with open(path) as f:
+        return json.load(f)
+
+
+def _check_against_fixture(name, opts, free_running=True):
+    gold = _load(name)
+    s = G.CONFIGS[name]
+    need = s.n_layers * s.hidden * (3 * s.ffn + 2 * s.hidden) * 2 * 1.2
+    if torch.cuda.mem_get_info()[0] < need:
+        pytest.skip("not enough free device memory for this configuration")
+    gpu = GpuDecoder(s, gold["seed"], **opts)
+    tok = np.array(gold["start_tokens"], np.int32)
+    pos = np.array(gold["start_positions"], np.int32)
+    idx = np.array(gold["sample_indices"])
+    steps = gold["steps"]
+    for i in range(steps):
+        lg = gpu.step(tok, pos)
+        assert np.isfinite(lg).all(), i
+        want_tok = np.array(gold["tokens"][i])
+        assert lg.argmax(-1).tolist() == want_tok.tolist(), f"step {i}"
+        for b in range(s.batch):
+            top = gold["top8"][i][b]
+            scale = abs(top[0][1])
+            for j, v in top:
+                assert abs(lg[b, j] - v) <= TOL * max(abs(v), 1e-3 * scale), (i, b, j)
+            # the oracle's best eight are the GPU's best eight (as a set: adjacent ranks closer
+            # than the fp32 noise may swap)
+            got8 = set(np.argsort(-lg[b], kind="stable")[:8].tolist())
+            want8 = {j for j, _ in top}
+            assert len(got8 ^ want8) <= 2, (i, b)
+        if str(i) in gold["samples"]:
+            for b in range(s.batch):
+                want = np.array(gold["samples"][str(i)][b])
+                amax = gold["absmax_%d" % i][b]
+                err = np.abs(lg[b, idx] - want) / np.maximum(np.abs(want), 1e-3 * amax)
+                assert err.max() < TOL, (i, b, float(err.max()))
+                assert np.abs(lg[b, idx] - want).max() / amax < 1e-4   # fp32 activations throughout
+        tok = (lg.argmax(-1) if free_running else want_tok).astype(np.int32)
+        pos = pos + 1
+    gpu.close()
+
+
+def test_c2_full_size_32_greedy_steps_mega_kernel():
+    _check_against_fixture("C2", BENCH_OPTS)
+
+
+def test_c2_full_size_per_operator_launch():
+    _check_against_fixture("C2", dict(launch_mode=1, **BENCH_OPTS), free_running=False)
