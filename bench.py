@@ -51,6 +51,18 @@ def cpu_baseline(shape, seed, n_layers_sample=4, reps=3):
                       f"layers + LM head, best of {reps}, layer time scaled to full depth"}
 
 
+def measured_traffic(config):
+    """HBM bytes per launch of the persistent kernel from the committed counter summary of this
+    workload (two rocprofv3 --pmc runs, scaled by a copy kernel of known size), or None."""
+    import glob
+    import re
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", f"mpk_mega_kernel_{config}_*.md"))):
+        m = re.search(r"traffic_bytes_per_launch:\s*(\d+)", open(path).read())
+        if m:
+            return int(m.group(1))
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -150,7 +162,7 @@ def main():
         "achieved_hbm_GBps": bytes_step / (ms_per_step * 1e-3) / 1e9,
         "bytes_per_step": bytes_step,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": 8000.0, "unit": "GB/s",
-                     "frac": achieved / 8000.0, "traffic": None,
+                     "frac": achieved / 8000.0, "traffic": measured_traffic(args.config),
                      "kernel": "mpk_mega_kernel", "kernel_avg_ms": kern_avg_ms},
         "final_tokens": final_tokens,
     }
