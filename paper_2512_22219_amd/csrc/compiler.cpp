@@ -733,6 +733,7 @@ static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGr
     TaskDesc& t = g.descs[i];
     t.dep_event = ht.dep_event;
     t.trig_event = ht.trig_event;
+    t.pad = i;   // own index in the linearized task list (trace slots are indexed by it)
     if (ht.op == MPK_TASK_DUMMY_OP) { t.kind = TK_DUMMY; continue; }
     const HostOp& op = g.ops[ht.op];
     tile_bounds(op, ht.tile, &t.b0, &t.b1, &t.c0, &t.c1);
@@ -768,22 +769,28 @@ static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGr
   }
 }
 
-static uint32_t lds_requirement(const mpk_model_config& c, const HostGraph& g, uint32_t C) {
+static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_t C) {
   size_t need = 0;
   const uint32_t grp = c.n_q_heads / c.n_kv_heads;
+  const uint32_t nb = c.batch <= 2 ? c.batch : (c.batch <= 4 ? 4u : 8u);   // body template sizes
+  // linear tasks: staged input rows | per-row results | residual slice | partial sums of squares
+  uint32_t rows_max = 0;
+  for (auto& op : g.ops) {
+    if (op.kind != MPK_OP_LINEAR && op.kind != MPK_OP_GATEUP) continue;
+    uint32_t nu = op.cols / op.unit, per = (nu + op.tc - 1) / op.tc * op.unit;
+    rows_max = std::max(rows_max, per * ((op.flags & TF_GATEUP) ? 2u : 1u));
+  }
+  g.lin_rows_max = rows_max;
   for (auto& op : g.ops) {
     size_t f = 0;
-    if (op.kind == MPK_OP_LINEAR || op.kind == MPK_OP_GATEUP) {
-      uint32_t nb = c.batch <= 2 ? c.batch : (c.batch <= 4 ? 4u : 8u);   // body template sizes
-      f = (size_t)nb * op.K;
-    }
-    else if (op.kind == MPK_OP_RMSNORM) f = 0;
+    if (op.kind == MPK_OP_LINEAR || op.kind == MPK_OP_GATEUP)
+      f = (size_t)nb * ((op.K + 4095u) / 4096u * 4096u) + 2 * (size_t)rows_max * nb + 8 * nb;
     else if (op.kind == MPK_OP_ATTN_PARTIAL)
       f = (size_t)grp * c.head_dim                                        // q
           + (size_t)(kThreads / 64) * grp * (c.head_dim + 2) + 16 + 64;   // per-wave partials
     need = std::max(need, f);
   }
-  size_t bytes = (need + kLdsReduceFloats) * sizeof(float);
+  size_t bytes = (need + kLdsReduceFloats + 16) * sizeof(float);   // + 64 bytes of control words
   return (uint32_t)std::max<size_t>(bytes, kMinLdsBytes);
 }
 
@@ -825,15 +832,18 @@ mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs*
   if (opt.n_workers == 0) { set_error("n_workers unresolved"); return MPK_ERR_INTERNAL; }
   uint32_t C = opt.attn_chunks;
   if (C == 0) {
-    // one chunk = what a task can request before its event fires: 8 rounds of 8 wavefronts x
-    // 64 / (head_dim / 8) positions held in registers
-    const uint32_t window = 8u * 8u * (64u / (cfg.head_dim / 8u));
-    C = (cfg.max_seq + window - 1) / window;
+    // A chunk may not exceed what a task holds in registers (the pre-load window: 8 rounds of
+    // one cache position per 128-bit lane group and wavefront); a bit more than half of it
+    // measured best (shorter attention tasks against more partials to merge).
+    const uint32_t window = 8u * (kThreads / 64u) * (64u / (cfg.head_dim / 8u));
+    const uint32_t target = std::max(1u, window * 9u / 16u);
+    C = (cfg.max_seq + target - 1) / target;
     C = std::min(C, 64u);
+    C = std::max(C, (cfg.max_seq + window - 1) / window);
   }
   if (C > 64) { set_error("attn_chunks %u too large (max 64)", C); return MPK_ERR_INVALID_ARG; }
   {
-    const uint32_t window = 8u * 8u * (64u / (cfg.head_dim / 8u));
+    const uint32_t window = 8u * (kThreads / 64u) * (64u / (cfg.head_dim / 8u));
     if ((cfg.max_seq + C - 1) / C > window) { set_error("attn_chunks %u too small: a chunk of max_seq %u would exceed the %u positions an attention task holds in registers", C, cfg.max_seq, window); return MPK_ERR_INVALID_ARG; }
   }
   opt.attn_chunks = C;

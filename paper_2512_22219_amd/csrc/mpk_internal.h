@@ -125,6 +125,7 @@ struct HostGraph {
   uint32_t lds_bytes = 0;
   uint32_t n_group_counters = 0;   // per (layer, sequence, KV head) arrival counters
   uint32_t n_hier_events = 0;
+  uint32_t lin_rows_max = 0;       // largest weight-row count of one linear task (gate/up pairs twice)
   std::vector<double> inv_freq;    // RoPE frequencies theta^(-2i/d), i < d/2
   mpk_stats stats{};
 };
@@ -138,7 +139,7 @@ mpk_status build_dag_graph(uint32_t n_tasks, const uint32_t* pairs, size_t n_pai
                            const mpk_compile_options& opt, HostGraph& g);
 
 // LDS layout constants shared with the kernels
-constexpr uint32_t kThreads = 512;        // worker workgroup size (8 wavefronts)
+constexpr uint32_t kThreads = 512;        // worker workgroup size (8 wavefronts, two per SIMD)
 constexpr uint32_t kLdsReduceFloats = 1024;  // scratch for cross-wave reductions
 constexpr uint32_t kMinLdsBytes = 84 * 1024; // > half of 160 KB: at most one worker per CU
 

@@ -48,21 +48,57 @@ struct GraphConst {
   uint64_t timeout_ticks;
   uint32_t n_workers;
   uint32_t vocab, max_seq, n_q, n_kv, head_dim, batch;
+  uint32_t lin_rows_max;     // largest number of weight rows (gate/up pairs count twice) of a linear task
 };
 
 // Per-step kernel arguments, passed by value.  Every device function taking it is force-inlined:
 // a real call with a reference to it would make the compiler copy the struct to private memory.
+// Tables that no kernel ever writes (the graph record, task and event descriptors, queues) are
+// read through the constant address space: uniform reads then become scalar loads, which use
+// their own counter and never queue behind (or wait for) the vector-memory weight stream.
+#define MPK_CONST __attribute__((address_space(4)))
 struct StepArgs {
-  const GraphConst* g;
+  const MPK_CONST GraphConst* g;
   const int32_t* token_ids;
   const int32_t* positions;
   float* logits;
   uint32_t epoch;
 };
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Pointers that arrive through descriptors in memory are "generic" to the compiler, which then
+// emits FLAT memory instructions: those may complete out of order, so every use has to wait for
+// ALL outstanding memory operations (vmcnt(0) lgkmcnt(0)) and nothing pipelines.  Everything the
+// kernels touch outside LDS is device memory: say so, and loads/stores become GLOBAL instructions
+// that complete in order and can be waited for one by one.
+#define MPK_GLOBAL __attribute__((address_space(1)))
+template <typename T>
+__device__ __forceinline__ MPK_GLOBAL T* as_global(T* p) {
+  return (MPK_GLOBAL T*)p;
+}
+// 16-byte non-temporal load (weights, cache rows: streamed once, keep them out of the caches)
+__device__ __forceinline__ u32x4 ld_stream16(const void* p) {
+  return __builtin_nontemporal_load(as_global((const u32x4*)p));
+}
+
+template <typename T>
+__device__ __forceinline__ T ld_const_record(const T* p) {   // sizeof(T) a multiple of 16
+  union {
+    T rec;
+    u32x4 v[sizeof(T) / 16];
+  } u;
+  const MPK_CONST u32x4* src = (const MPK_CONST u32x4*)p;
+#pragma unroll
+  for (unsigned i = 0; i < sizeof(T) / 16; ++i) u.v[i] = src[i];
+  return u.rec;
+}
+__device__ __forceinline__ TaskDesc ld_task(const StepArgs& a, uint32_t i) { return ld_const_record(a.g->tasks + i); }
+__device__ __forceinline__ uint32_t ld_u32c(const uint32_t* p) { return *(const MPK_CONST uint32_t*)p; }
+
 constexpr int kTraceSlots = 12;
 __device__ __forceinline__ void trace_mark(const StepArgs& a, const TaskDesc& t, int slot) {
-  if (a.g->trace && threadIdx.x == 0) a.g->trace[(size_t)(&t - a.g->tasks) * kTraceSlots + slot] = wall_clock64();
+  if (a.g->trace && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + slot] = wall_clock64();
 }
 
 enum DevErr : uint32_t { DE_NONE = 0, DE_TIMEOUT = 1, DE_BAD_POSITION = 2, DE_BAD_TOKEN = 3 };
@@ -94,7 +130,7 @@ __device__ __forceinline__ float wave_max(float v) {
 // Sum over the whole workgroup; every thread gets the result.  red: >= 16 floats of LDS.
 __device__ __forceinline__ float block_sum(float v, float* red) {
   v = wave_sum(v);
-  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   __syncthreads();
   if (lane == 0) red[wave] = v;
   __syncthreads();
@@ -104,25 +140,23 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return s;
 }
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 // Agent-coherent accessors for data produced and consumed by different workgroups in one launch.
 __device__ __forceinline__ float ld_act(const float* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void st_act(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ float2 ld_act2(const float* p) {   // p 8-byte aligned
-  uint64_t u = __hip_atomic_load((const uint64_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  uint64_t u = __hip_atomic_load(as_global((const uint64_t*)p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   return make_float2(__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32)));
 }
 __device__ __forceinline__ void st_act_u32(uint32_t* p, uint32_t v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ u32x4 ld_row16_coherent(const uint16_t* p) {   // p 16-byte aligned
-  uint64_t a = __hip_atomic_load((const uint64_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  uint64_t b = __hip_atomic_load((const uint64_t*)p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  uint64_t a = __hip_atomic_load(as_global((const uint64_t*)p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  uint64_t b = __hip_atomic_load(as_global((const uint64_t*)p + 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   return u32x4{(uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32)};
 }
 
@@ -156,7 +190,7 @@ __device__ __forceinline__ void body_embed(const TaskDesc& t, const StepArgs& a)
     }
     const uint16_t* row = (const uint16_t*)t.w + (size_t)tok * t.K;
     float* out = t.out + (size_t)b * t.ld_out;
-    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) st_act(out + i, bf16_to_f32(row[i]));
+    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) st_act(out + i, bf16_to_f32(as_global(row)[i]));
   }
 }
 
@@ -173,83 +207,201 @@ __device__ __forceinline__ void body_rmsnorm(const TaskDesc& t, float* lds) {
     }
     ss = block_sum(ss, lds);
     float inv = 1.0f / sqrtf(ss / (float)t.K + t.f0);
-    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) st_act(y + i, ld_act(x + i) * inv * bf16_to_f32(g[i]));
+    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) st_act(y + i, ld_act(x + i) * inv * bf16_to_f32(as_global(g)[i]));
   }
 }
 
 __device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag);
 
+// ------------------------------------------------------------------------------ linear tasks
 // T2/T6/T9/T11/T14: y[b][c] = sum_j W[c][j] x[b][j] for output columns [c0, c1), all batch rows
-// at once.  Every wavefront owns groups of RW weight rows (groups wave, wave+8, ...) and walks
-// them in blocks of RW rows x KU chunks, a chunk being 64 lanes x 16 bytes = 512 input elements.
-// The RW*KU 16-byte loads of a block live in a register ring: each slot is refilled with the same
-// slot of the NEXT block right after it has been consumed, so a full block per lane (RW*KU*16
-// bytes, 128-256 KB per CU) is always in flight.
-// Cross-task pre-loading (paper Section 5.3): the first block is requested BEFORE the task waits
-// for its dependent event -- weights never depend on an event -- so the weight stream keeps
-// flowing while the input vector is still being produced elsewhere.
-// Optional stages: RMSNorm of the input (TF_PRO_NORM), residual add (TF_EPI_RESID), fused
-// silu(gate) * up (TF_GATEUP: column c needs weight rows c and F + c).
-template <int NB, int RW, int KU>
-__device__ __forceinline__ bool body_linear(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
-                            uint32_t* s_flag) {
-  const uint32_t K = t.K, nb = t.b1 - t.b0;
-  float* xs = lds;                 // [NB][K]
-  float* red = lds + (size_t)NB * K;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+// at once, with optional fused stages: RMSNorm of the input (TF_PRO_NORM), residual add
+// (TF_EPI_RESID), silu(gate) * up (TF_GATEUP: column c needs weight rows c and F + c).
+//
+// Weight rows of a task ("ring rows": one per column, or the (gate, up) pair of each column) are
+// split into 8 contiguous ranges, one per wavefront.  A wavefront walks its rows in groups of 4
+// and every group in segments of 4096 input elements; one (group, segment) is a block of
+// 4 rows x 8 stages, a stage being 64 lanes x 16 bytes = 512 elements: 32 sixteen-byte loads per
+// lane, 32 KB per wavefront, 256 KB per CU.  Steady state is deliberately plain: request a whole
+// block, then consume it stage by stage as it arrives (the loads of a wavefront complete in
+// order, so the wait for stage u is "at most 4 (7 - u) loads outstanding"); the other seven
+// wavefronts of the CU keep the memory system busy meanwhile.  Measured on this GPU that order
+// streams at 6.6 TB/s, whereas refilling each slot right after its use -- a register ring that is
+// live around the loop -- makes the compiler drain the whole queue before every use (2.8 TB/s).
+//
+// Cross-task pipelining (paper Section 5.3).  Weights never depend on an event, so a task
+// requests its first block (256 KB per CU) BEFORE it waits for its dependent event: the block
+// streams in while the input vector is still being produced elsewhere.  And a task ends for
+// wavefronts 1..7 as soon as the workgroup's results are in LDS: they walk straight into the
+// worker's next task and issue its first block, while wavefront 0 alone applies the epilogue,
+// writes the outputs with coherent stores, waits for exactly those stores and notifies the
+// triggering event -- with no weight loads queued ahead of them, because memory operations of one
+// wavefront complete in order -- and only then requests its own share and polls the next event.
+// The block buffer is local to a task on purpose: carried around the task loop instead, the
+// compiler moves parts of it to scratch memory, and a scratch access in the middle of a request
+// waits for every load issued before it.
+constexpr int kRingRows = 4, kRingStages = 8;
+constexpr uint32_t kSegLen = 512u * kRingStages;   // input elements per block row
+struct Ring {
+  u32x4 s[kRingRows][kRingStages];
+};
+
+__device__ __forceinline__ void ring_clear(Ring& ring) {
+#pragma unroll
+  for (int i = 0; i < kRingRows; ++i)
+#pragma unroll
+    for (int u = 0; u < kRingStages; ++u) ring.s[i][u] = u32x4{0, 0, 0, 0};
+}
+
+// Wavefront-uniform view of one linear task for one wavefront.
+struct LinGeom {
+  const uint16_t* W;
+  uint32_t K, c0, F, gateup;
+  uint32_t r0, r1;    // ring rows [r0, r1) of this wavefront within the task
+  uint32_t nseg;      // segments per row
+  uint32_t nblocks;   // groups of 4 rows x segments
+};
+
+__device__ __forceinline__ LinGeom lin_geom(const TaskDesc& t, uint32_t wave) {
+  LinGeom g;
+  g.W = (const uint16_t*)t.w;
+  g.K = t.K;
+  g.c0 = t.c0;
+  g.F = t.p0;
+  g.gateup = (t.flags & TF_GATEUP) ? 1u : 0u;
+  const uint32_t R = (t.c1 - t.c0) << g.gateup;
   constexpr uint32_t NW = kThreads / 64;
-  const bool gateup = t.flags & TF_GATEUP;
-  const uint32_t ncols = t.c1 - t.c0;
-  const uint32_t G = gateup ? RW / 2 : RW;          // output columns per group
-  const uint32_t ngroups = (ncols + G - 1) / G;
-  const uint32_t nkb = (K + 512 * KU - 1) / (512 * KU);   // blocks per group
-  const uint16_t* W = (const uint16_t*)t.w;
+  uint32_t rpw = (R + NW - 1u) / NW;
+  if (g.gateup) rpw = (rpw + 1u) & ~1u;   // a (gate, up) pair stays in one wavefront
+  g.r0 = min(wave * rpw, R);
+  g.r1 = min(g.r0 + rpw, R);
+  g.nseg = (t.K + kSegLen - 1u) / kSegLen;
+  g.nblocks = (g.r1 - g.r0 + kRingRows - 1u) / kRingRows * g.nseg;
+  return g;
+}
 
-  auto row_ptrs = [&](uint32_t grp, const uint16_t* (&rp)[RW]) {
-#pragma unroll
-    for (int i = 0; i < RW; ++i) {
-      uint32_t c = t.c0 + grp * G + (gateup ? (i >> 1) : i);
-      uint32_t cc = c < t.c1 ? c : t.c1 - 1;   // masked rows re-read a valid row (result dropped)
-      uint32_t row = gateup ? ((i & 1) ? t.p0 + cc : cc) : cc;
-      rp[i] = W + (size_t)row * K + lane * 8;
-    }
-  };
+// Block `blk` of a wavefront: rows [row0, row0 + nrows) of the task, segment `seg`.
+struct LinBlock {
+  const uint16_t* p[kRingRows];   // address of the lane's 16 bytes of stage 0 (rows past nrows repeat the last)
+  uint32_t row0, nrows, seg, seglen;
+};
 
-  u32x4 ring[RW][KU];
+__device__ __forceinline__ LinBlock lin_block(const LinGeom& g, uint32_t blk, int lane) {
+  LinBlock B;
+  const uint32_t grp = blk / g.nseg;
+  B.seg = blk - grp * g.nseg;
+  B.row0 = g.r0 + grp * kRingRows;
+  B.nrows = min(g.r1 - B.row0, (uint32_t)kRingRows);
+  B.seglen = min(kSegLen, g.K - B.seg * kSegLen);
 #pragma unroll
-  for (int i = 0; i < RW; ++i)
+  for (int i = 0; i < kRingRows; ++i) {
+    const uint32_t r = B.row0 + min((uint32_t)i, B.nrows - 1u);
+    const uint32_t wrow = g.gateup ? (g.c0 + (r >> 1) + ((r & 1u) ? g.F : 0u)) : g.c0 + r;
+    B.p[i] = g.W + (size_t)wrow * g.K + B.seg * kSegLen;
+  }
+  return B;
+}
+
+// Requests rows [0, ROWS) of a block, stage by stage.  Lanes past the end of a short segment
+// re-read its last 16 bytes (the staged input is zero there), so every lane takes part in every
+// load.
+template <int ROWS>
+__device__ __forceinline__ void lin_request(const LinBlock& B, Ring& ring, int lane) {
+  if (B.seglen == kSegLen) {   // full segment: one base address per row, constant stage offsets
 #pragma unroll
-    for (int u = 0; u < KU; ++u) ring[i][u] = u32x4{0, 0, 0, 0};
-  uint32_t grp = wave, kb = 0;
-  bool have = grp < ngroups;
-  if (have) {
-    const uint16_t* rp[RW];
-    row_ptrs(grp, rp);
+    for (int u = 0; u < kRingStages; ++u)
 #pragma unroll
-    for (int u = 0; u < KU; ++u) {
-      uint32_t k = (uint32_t)u * 512 + lane * 8;
-      if (k < K) {
+      for (int i = 0; i < ROWS; ++i) ring.s[i][u] = ld_stream16(B.p[i] + lane * 8 + u * 512);
+  } else {
 #pragma unroll
-        for (int i = 0; i < RW; ++i) ring[i][u] = __builtin_nontemporal_load((const u32x4*)(rp[i] + (size_t)u * 512));
-      }
+    for (int u = 0; u < kRingStages; ++u) {
+      const uint32_t o = min((uint32_t)u * 512u + (uint32_t)lane * 8u, B.seglen - 8u);
+#pragma unroll
+      for (int i = 0; i < ROWS; ++i) ring.s[i][u] = ld_stream16(B.p[i] + o);
     }
   }
-  // ---- the input vector: only now does the task need its dependent event
-  if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
+}
+// The two arms end in different (empty) assembly statements on purpose: otherwise the compiler
+// merges their identical last load into one whose destination slot is chosen at run time, and a
+// ring slot addressed that way is moved from registers to scratch memory.
+__device__ __forceinline__ void lin_request_any(const LinBlock& B, Ring& ring, int lane) {
+  if (B.nrows > 2) {
+    lin_request<4>(B, ring, lane);
+    asm volatile("; four rows requested" ::: "memory");
+  } else {
+    lin_request<2>(B, ring, lane);
+    asm volatile("; two rows requested" ::: "memory");
+  }
+}
+
+// Adds the block's partial dot products to acc.
+template <int NB, int ROWS>
+__device__ __forceinline__ void lin_consume(const LinBlock& B, const Ring& ring, const float* xs, uint32_t Kp,
+                                            int lane, float (&acc)[kRingRows][NB]) {
+#pragma unroll
+  for (int u = 0; u < kRingStages; ++u) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const float4* xp = (const float4*)(xs + (size_t)b * Kp + B.seg * kSegLen + u * 512 + lane * 8);
+      const float4 x0 = xp[0], x1 = xp[1];
+#pragma unroll
+      for (int i = 0; i < ROWS; ++i) acc[i][b] = dot8(ring.s[i][u], x0, x1, acc[i][b]);
+    }
+  }
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() carries a release fence, for
+// which the compiler drains the vector-memory queue (s_waitcnt vmcnt(0)): with a pre-load of
+// the next task in flight that would stall every wavefront, and the event notification behind
+// it, until the whole pre-load has landed.  What the barriers of a linear task publish lives in
+// LDS; data for other workgroups is published by wavefront 0 with its own wait.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ void signal_from_wave0(const StepArgs& a, const TaskDesc& t, int32_t e, int lane);
+__device__ __forceinline__ void poll_event_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane);
+
+// LDS layout of a linear task (floats): xs [NB][K rounded up to 4096] | outbuf [max ring rows][NB]
+// | resid [max columns][NB] | ssq [8][NB]; the two middle regions are sized by the compiler from
+// the largest task of the graph (GraphConst::lin_rows_max).
+//
+// Runs task `t`.  wait_ev >= 0: wait for that event first (persistent kernel).  Returns whether
+// the step is still alive (false: watchdog / abort).
+template <int NB, bool MEGA>
+__device__ __forceinline__ bool linear_task(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
+                                            uint32_t* s_flag) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: geometry stays scalar
+  const uint32_t K = t.K, nb = t.b1 - t.b0, ncols = t.c1 - t.c0;
+  const uint32_t Kp = (K + kSegLen - 1u) / kSegLen * kSegLen;
+  const uint32_t rows_max = a.g->lin_rows_max;
+  float* xs = lds;                                   // [NB][Kp]
+  float* outbuf = xs + (size_t)NB * Kp;              // [rows_max][NB]
+  float* res_lds = outbuf + (size_t)rows_max * NB;   // [rows_max][NB]
+  float* ssq = res_lds + (size_t)rows_max * NB;      // [8][NB]
+  const LinGeom g = lin_geom(t, wave);
+  Ring ring;   // local to the task: nothing is live around the task loop, so it stays in registers
+  ring_clear(ring);
+  if (g.nblocks > 0) lin_request_any(lin_block(g, 0, lane), ring, lane);
+  // ---- dependent event: wavefront 0 polls, the others wait at the barrier
+  if (wait_ev >= 0) {
+    if (wave == 0) poll_event_wave0(a, wait_ev, s_flag, lane);
+    lds_barrier();
+    if (__builtin_amdgcn_readfirstlane(*s_flag) == 0) return false;   // (uniform; tell the compiler)
+  }
   trace_mark(a, t, 1);
-  // Input rows -> LDS.  With TF_PRO_NORM the gain is folded in here (x * g) and the row's
-  // 1/rms factor is applied to the finished dot products: W (x g inv) = inv * W (x g).
+  // ---- stage the input rows in LDS.  With TF_PRO_NORM the gain is folded in here (x * g) and
+  // the row's 1/rms factor is applied to the finished dot products: W (x g inv) = inv * W (x g).
   const bool pro_norm = t.flags & TF_PRO_NORM;
   const uint16_t* gain = (const uint16_t*)t.w2;
-  float inv_rms[NB];
 #pragma unroll
-  for (int b = 0; b < NB; ++b) inv_rms[b] = 1.0f;
-  for (uint32_t b = 0; b < NB; ++b) {
-    float2* dst = (float2*)(xs + (size_t)b * K);
+  for (uint32_t b = 0; b < (uint32_t)NB; ++b) {
+    float2* dst = (float2*)(xs + (size_t)b * Kp);
     float ss = 0.f;
     if (b < nb) {
       const float* src = t.in + (size_t)(t.b0 + b) * t.ld_in;
-      for (uint32_t i0 = 0; i0 < K / 2; i0 += kThreads * 8) {   // 8 coherent loads in flight per lane
+      for (uint32_t i0 = 0; i0 < Kp / 2; i0 += kThreads * 8) {   // 8 coherent loads in flight per lane
         float2 tmp[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -264,117 +416,107 @@ __device__ __forceinline__ bool body_linear(const TaskDesc& t, const StepArgs& a
             if (pro_norm) {
               ss = fmaf(v.x, v.x, ss);
               ss = fmaf(v.y, v.y, ss);
-              uint32_t g2 = *(const uint32_t*)(gain + 2 * i);
+              uint32_t g2 = *as_global((const uint32_t*)(gain + 2 * i));
               v.x *= bf16_lo(g2);
               v.y *= bf16_hi(g2);
             }
             dst[i] = v;
+          } else if (i < Kp / 2) {
+            dst[i] = make_float2(0.f, 0.f);
           }
         }
       }
     } else {
-      for (uint32_t i = threadIdx.x; i < K / 2; i += kThreads) dst[i] = make_float2(0.f, 0.f);
+      for (uint32_t i = threadIdx.x; i < Kp / 2; i += kThreads) dst[i] = make_float2(0.f, 0.f);
     }
-    if (pro_norm && b < nb) {
-      ss = block_sum(ss, red);
-      inv_rms[b] = 1.0f / sqrtf(ss / (float)K + t.f0);
+    if (pro_norm) {
+      ss = wave_sum(ss);
+      if (lane == 0) ssq[wave * NB + b] = ss;
     }
   }
-  // residual slice of this tile (tile-local, small): fetched now, off the tail of the task
-  const uint32_t ncols_all = t.c1 - t.c0;
-  float* res_lds = red + 16;
-  const bool resid_in_lds = (t.flags & TF_EPI_RESID) && (size_t)nb * ncols_all <= kLdsReduceFloats - 16;
-  if (resid_in_lds) {
-    for (uint32_t i = threadIdx.x; i < nb * ncols_all; i += kThreads) {
-      uint32_t bb = i / ncols_all, cc = i % ncols_all;
+  // residual slice of this tile (tile-local, small)
+  if (t.flags & TF_EPI_RESID) {
+    for (uint32_t i = threadIdx.x; i < nb * ncols; i += kThreads) {
+      uint32_t bb = i / ncols, cc = i % ncols;
       res_lds[i] = ld_act(t.in2 + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc);
     }
   }
-  __syncthreads();
-  // ---- stream the weight rows
+  lds_barrier();
   trace_mark(a, t, 2);
-  float* outp = (t.flags & TF_OUT_LOGITS) ? a.logits : t.out;
-  float acc[RW][NB];
+  // ---- stream this wavefront's rows, block by block
+  {
+    float acc[kRingRows][NB];
 #pragma unroll
-  for (int i = 0; i < RW; ++i)
+    for (int i = 0; i < kRingRows; ++i)
 #pragma unroll
-    for (int b = 0; b < NB; ++b) acc[i][b] = 0.f;
-  while (have) {
-    uint32_t ngrp = grp, nkb_i = kb + 1;
-    if (nkb_i == nkb) {
-      nkb_i = 0;
-      ngrp = grp + NW;
-    }
-    const bool nhave = ngrp < ngroups;
-    const uint16_t* np[RW];
-    row_ptrs(nhave ? ngrp : grp, np);
-#pragma unroll
-    for (int u = 0; u < KU; ++u) {
-      const uint32_t k = (kb * KU + u) * 512 + lane * 8;
-      const uint32_t nk = (nkb_i * KU + u) * 512 + lane * 8;
-      if (k < K) {
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-          const float4* xp = (const float4*)(xs + (size_t)b * K + k);
-          float4 x0 = xp[0], x1 = xp[1];
-#pragma unroll
-          for (int i = 0; i < RW; ++i) acc[i][b] = dot8(ring[i][u], x0, x1, acc[i][b]);
+      for (int b = 0; b < NB; ++b) acc[i][b] = 0.f;
+    for (uint32_t blk = 0; blk < g.nblocks; ++blk) {
+      const LinBlock B = lin_block(g, blk, lane);
+      if (B.nrows > 2) {
+        if (blk > 0) {   // block 0 was requested before the event wait
+          lin_request<4>(B, ring, lane);
+          asm volatile("; four rows requested" ::: "memory");
         }
-      }
-      if (nhave && nk < K) {
-#pragma unroll
-        for (int i = 0; i < RW; ++i)
-          ring[i][u] = __builtin_nontemporal_load((const u32x4*)(np[i] + (size_t)(nkb_i * KU + u) * 512));
-      }
-    }
-    if (nkb_i == 0) {   // the group is complete: reduce across lanes and write its columns
-#pragma unroll
-      for (int i = 0; i < RW; ++i)
-#pragma unroll
-        for (int b = 0; b < NB; ++b) acc[i][b] = wave_sum(acc[i][b]);
-      if (lane == 0) {
-        if (gateup) {
-#pragma unroll
-          for (int i = 0; i < RW; i += 2) {
-            uint32_t col = t.c0 + grp * G + (i >> 1);
-            if (col < t.c1) {
-              for (uint32_t b = 0; b < nb; ++b) {
-                float gte = acc[i][b] * inv_rms[b], up = acc[i + 1][b] * inv_rms[b];
-                st_act(outp + (size_t)(t.b0 + b) * t.ld_out + col, gte / (1.0f + expf(-gte)) * up);
-              }
-            }
-          }
-        } else {
-#pragma unroll
-          for (int i = 0; i < RW; ++i) {
-            uint32_t col = t.c0 + grp * G + i;
-            if (col < t.c1) {
-              for (uint32_t b = 0; b < nb; ++b) {
-                float v = acc[i][b] * inv_rms[b];
-                size_t o = (size_t)(t.b0 + b) * t.ld_out + col;
-                if (t.flags & TF_EPI_RESID)
-                  v = (resid_in_lds ? res_lds[b * ncols_all + (col - t.c0)] : ld_act(t.in2 + o)) + v;
-                st_act(outp + o, v);
-              }
-            }
-          }
+        lin_consume<NB, 4>(B, ring, xs, Kp, lane, acc);
+      } else {
+        if (blk > 0) {
+          lin_request<2>(B, ring, lane);
+          asm volatile("; two rows requested" ::: "memory");
         }
+        lin_consume<NB, 2>(B, ring, xs, Kp, lane, acc);
       }
+      if (B.seg + 1 == g.nseg) {   // the group of rows is complete: reduce across lanes, results to LDS
 #pragma unroll
-      for (int i = 0; i < RW; ++i)
+        for (int i = 0; i < kRingRows; ++i)
 #pragma unroll
-        for (int b = 0; b < NB; ++b) acc[i][b] = 0.f;
+          for (int b = 0; b < NB; ++b) {
+            const float v = wave_sum(acc[i][b]);
+            if (lane == 0 && (uint32_t)i < B.nrows) outbuf[(size_t)(B.row0 + i) * NB + b] = v;
+            acc[i][b] = 0.f;
+          }
+      }
     }
-    grp = ngrp;
-    kb = nkb_i;
-    have = nhave;
+  }
+  lds_barrier();
+  trace_mark(a, t, 3);
+  // ---- wavefront 0: epilogue, outputs, notification, then its own share of the pre-load
+  if (wave == 0) {
+    float* outp = (t.flags & TF_OUT_LOGITS) ? a.logits : t.out;
+    float inv_rms[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      inv_rms[b] = 1.0f;
+      if (pro_norm && (uint32_t)b < nb) {
+        float ss = 0.f;
+#pragma unroll
+        for (int w = 0; w < (int)(kThreads / 64); ++w) ss += ssq[w * NB + b];
+        inv_rms[b] = 1.0f / sqrtf(ss / (float)K + t.f0);
+      }
+    }
+    for (uint32_t i = lane; i < ncols * nb; i += 64) {
+      const uint32_t cc = i % ncols, bb = i / ncols;
+      float inv = inv_rms[0];
+#pragma unroll
+      for (int b = 1; b < NB; ++b) inv = (bb == (uint32_t)b) ? inv_rms[b] : inv;
+      float v;
+      if (g.gateup) {
+        const float gte = outbuf[(size_t)(2 * cc) * NB + bb] * inv, up = outbuf[(size_t)(2 * cc + 1) * NB + bb] * inv;
+        v = gte / (1.0f + expf(-gte)) * up;
+      } else {
+        v = outbuf[(size_t)cc * NB + bb] * inv;
+      }
+      if (t.flags & TF_EPI_RESID) v = res_lds[bb * ncols + cc] + v;
+      st_act(outp + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc, v);
+    }
+    if (MEGA && t.trig_event >= 0) signal_from_wave0(a, t, t.trig_event, lane);
+    trace_mark(a, t, 4);
   }
   return true;
 }
 
 // cos and sin of position * inv_freq[i]: the angle is formed and reduced to [-pi, pi] in double.
 __device__ __forceinline__ void rope_cs(const StepArgs& a, int32_t pos, uint32_t i, float* c, float* s) {
-  double ang = (double)pos * a.g->inv_freq[i];
+  double ang = (double)pos * as_global(a.g->inv_freq)[i];
   const double two_pi = 6.283185307179586476925286766559;
   ang -= two_pi * rint(ang / two_pi);
   double sd, cd;
@@ -461,7 +603,7 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
   constexpr uint32_t stride = NW * PPW, per = grp * (d + 2);
   const uint32_t nq = a.g->n_q, nkv = a.g->n_kv, C = t.p1;
   const uint32_t b = t.b0, u = t.c0 / per, g = u / C, c = u % C;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   float* qs = lds;                       // [grp][d]
   float* wpart = qs + grp * d;           // [NW][grp][d + 2]: partial output, max, sum per wavefront
   uint32_t* flag = (uint32_t*)(wpart + NW * grp * (d + 2));   // then [16..) the maxima exchange
@@ -484,8 +626,8 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
     kreg[r] = u32x4{0, 0, 0, 0};
     vreg[r] = u32x4{0, 0, 0, 0};
     if (i < n && t0 + i != (uint32_t)pos) {
-      kreg[r] = __builtin_nontemporal_load((const u32x4*)(Kb + (size_t)i * d + sub * 8));
-      vreg[r] = __builtin_nontemporal_load((const u32x4*)(Vb + (size_t)i * d + sub * 8));
+      kreg[r] = ld_stream16(Kb + (size_t)i * d + sub * 8);
+      vreg[r] = ld_stream16(Vb + (size_t)i * d + sub * 8);
     }
   }
   if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
@@ -666,7 +808,7 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
     __syncthreads();
     if (threadIdx.x == 0) {
       uint32_t* cnt = a.g->grp_counters + t.p2 + b * nkv + g;
-      uint32_t old = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      uint32_t old = __hip_atomic_fetch_add(as_global(cnt), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       *flag = ((old + 1u) % C == 0u) ? 1u : 0u;   // every step adds exactly C
     }
     __syncthreads();
@@ -753,25 +895,21 @@ __device__ __forceinline__ void body_swiglu(const TaskDesc& t) {
 // D, GRP, NB pin head_dim, query heads per KV head and the batch class at compile time (0 = decide
 // at run time): a kernel that carries a single attention and a single linear variant keeps its
 // register allocation free of spills, the fully generic kernel does not.
+// Batch class -> body instance (NB = 0: decided at run time).
+template <int NB, bool MEGA>
+__device__ __forceinline__ bool run_linear(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
+                                           uint32_t* s_flag) {
+  if (NB != 0) return linear_task<(NB ? NB : 1), MEGA>(t, a, lds, wait_ev, s_flag);
+  const uint32_t nb = t.b1 - t.b0;
+  if (nb == 1) return linear_task<1, MEGA>(t, a, lds, wait_ev, s_flag);
+  if (nb == 2) return linear_task<2, MEGA>(t, a, lds, wait_ev, s_flag);
+  if (nb <= 4) return linear_task<4, MEGA>(t, a, lds, wait_ev, s_flag);
+  return linear_task<8, MEGA>(t, a, lds, wait_ev, s_flag);
+}
+
 template <int D, int GRP, int NB>
 __device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, float* lds,
                                          int32_t wait_ev, uint32_t* s_flag) {
-  if (t.kind == TK_LINEAR) {
-    const uint32_t nb = t.b1 - t.b0;
-    const uint32_t G = (t.flags & TF_GATEUP) ? 2u : 1u;
-    const uint32_t rows_per_wave = ((t.c1 - t.c0) * G + kThreads / 64 - 1) / (kThreads / 64);
-    if (NB == 1 || (NB == 0 && nb == 1)) {
-      if (rows_per_wave <= 2) return body_linear<1, 2, 8>(t, a, lds, wait_ev, s_flag);
-      return body_linear<1, 4, 8>(t, a, lds, wait_ev, s_flag);
-    }
-    if (NB == 8) return body_linear<8, 2, 4>(t, a, lds, wait_ev, s_flag);
-    if (NB == 0) {
-      if (nb == 2) return body_linear<2, 4, 4>(t, a, lds, wait_ev, s_flag);
-      if (nb <= 4) return body_linear<4, 2, 4>(t, a, lds, wait_ev, s_flag);
-      return body_linear<8, 2, 4>(t, a, lds, wait_ev, s_flag);
-    }
-    return false;
-  }
   if (t.kind == TK_ATTN_PARTIAL) {
     if (D != 0) return body_attn_partial<(D ? D : 128), (GRP ? GRP : 1)>(t, a, lds, wait_ev, s_flag);
     const uint32_t grp = a.g->n_q / a.g->n_kv;
@@ -802,7 +940,7 @@ __device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, f
 
 // ------------------------------------------------------------------------------ runtime
 __device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Returns false when the step is being aborted (watchdog or a peer's failure).
@@ -810,7 +948,7 @@ __device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p) {
 // worker group's ready flag has reached the epoch.
 __device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag) {
   if (threadIdx.x == 0) {
-    const EventDesc& ev = a.g->events[e];
+    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.g->events + e);
     const uint32_t* word;
     uint32_t target;
     if (ev.flags & EV_HIER) {
@@ -829,7 +967,7 @@ __device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_
           if (ld_relaxed(a.g->err + 1) != 0) { ok = 0; break; }
           if (wall_clock64() - t_start > a.g->timeout_ticks) {
             report(a, DE_TIMEOUT, (uint32_t)e, blockIdx.x);
-            __hip_atomic_store(a.g->err + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(as_global(a.g->err + 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             ok = 0;
             break;
           }
@@ -839,7 +977,7 @@ __device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_
     *s_flag = ok;
   }
   __syncthreads();   // later agent-scope loads cannot move above this barrier
-  return *s_flag != 0;
+  return __builtin_amdgcn_readfirstlane(*s_flag) != 0;
 }
 
 __device__ __forceinline__ void signal_event(const StepArgs& a, const TaskDesc& t, int32_t e) {
@@ -850,42 +988,137 @@ __device__ __forceinline__ void signal_event(const StepArgs& a, const TaskDesc& 
   __syncthreads();
   trace_mark(a, t, 7);
   if (threadIdx.x == 0) {
-    const EventDesc& ev = a.g->events[e];
+    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.g->events + e);
     if (ev.flags & EV_HIER) {
       uint32_t* blk = a.g->hier + (size_t)ev.hier_slot * kHierWordsPerEvent;
       const uint32_t grp = blockIdx.x & 7u;
-      uint32_t old = __hip_atomic_fetch_add(blk + (1 + grp) * kHierStrideWords, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      uint32_t old = __hip_atomic_fetch_add(as_global(blk + (1 + grp) * kHierStrideWords), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (old + 1u == a.epoch * ev.sub_required[grp]) {          // last arrival of this group
-        old = __hip_atomic_fetch_add(blk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        old = __hip_atomic_fetch_add(as_global(blk), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (old + 1u == a.epoch * ev.n_groups) {                 // last group: the event is activated
 #pragma unroll
           for (uint32_t k = 0; k < 8; ++k)
-            __hip_atomic_store(blk + (9 + k) * kHierStrideWords, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(as_global(blk + (9 + k) * kHierStrideWords), a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
       }
     } else {
-      __hip_atomic_fetch_add(a.g->counters + e, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_fetch_add(as_global(a.g->counters + e), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 }
 
-template <int D, int GRP, int NB>
-__global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
-  extern __shared__ __align__(16) float lds[];
-  __shared__ uint32_t s_flag;
-  const uint32_t w = blockIdx.x;
-  if (w >= a.g->n_workers) return;
-  const uint32_t q0 = a.g->aot_off[w], q1 = a.g->aot_off[w + 1];
-  for (uint32_t qi = q0; qi < q1; ++qi) {
-    const TaskDesc& t = a.g->tasks[a.g->aot[qi]];
-    const int32_t wait_ev = (t.dep_event >= 0 && a.g->events[t.dep_event].required != 0) ? t.dep_event : -1;
+// Wavefront 0 only: poll the dependent event of the next task; result in *s_flag (LDS).
+__device__ __forceinline__ void poll_event_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane) {
+  if (lane == 0) {
+    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.g->events + e);
+    const uint32_t* word;
+    uint32_t target;
+    if (ev.flags & EV_HIER) {
+      word = a.g->hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
+      target = a.epoch;
+    } else {
+      word = a.g->counters + e;
+      target = a.epoch * ev.required;
+    }
+    uint32_t ok = 1;
+    if ((int32_t)(ld_relaxed(word) - target) < 0) {
+      const uint64_t t_start = wall_clock64();
+      uint32_t it = 0;
+      while ((int32_t)(ld_relaxed(word) - target) < 0) {
+        if ((++it & 255u) == 0) {
+          if (ld_relaxed(a.g->err + 1) != 0) { ok = 0; break; }
+          if (wall_clock64() - t_start > a.g->timeout_ticks) {
+            report(a, DE_TIMEOUT, (uint32_t)e, blockIdx.x);
+            __hip_atomic_store(as_global(a.g->err + 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ok = 0;
+            break;
+          }
+        }
+      }
+    }
+    *s_flag = ok;
+  }
+}
+
+// Wavefront 0 only, after a workgroup barrier: wait for this wavefront's own coherent stores,
+// then notify the event.
+__device__ __forceinline__ void signal_from_wave0(const StepArgs& a, const TaskDesc& t, int32_t e, int lane) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  trace_mark(a, t, 7);
+  if (lane == 0) {
+    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.g->events + e);
+    if (ev.flags & EV_HIER) {
+      uint32_t* blk = a.g->hier + (size_t)ev.hier_slot * kHierWordsPerEvent;
+      const uint32_t grp = blockIdx.x & 7u;
+      uint32_t old = __hip_atomic_fetch_add(as_global(blk + (1 + grp) * kHierStrideWords), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (old + 1u == a.epoch * ev.sub_required[grp]) {
+        old = __hip_atomic_fetch_add(as_global(blk), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old + 1u == a.epoch * ev.n_groups) {
+#pragma unroll
+          for (uint32_t k = 0; k < 8; ++k)
+            __hip_atomic_store(as_global(blk + (9 + k) * kHierStrideWords), a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+    } else {
+      __hip_atomic_fetch_add(as_global(a.g->counters + e), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
+
+// The first 64 bytes of the dynamic LDS are control words ([0] = result of the last event wait);
+// task bodies use the rest.
+constexpr uint32_t kLdsCtrlFloats = 16;
+
+// Everything that is not a linear task runs in a function of its own (a real call): its
+// thread-index arithmetic and temporaries then get their own register allocation instead of being
+// hoisted to the top of the persistent loop, where they would crowd out the weight ring and
+// force spills of registers that have loads in flight.
+// Returns false when the step is being aborted.
+template <int D, int GRP, int NB, bool MEGA>
+__device__ __noinline__ bool run_other_task(StepArgs a, uint32_t task_index) {
+  extern __shared__ __align__(16) float dyn_lds[];
+  float* lds = dyn_lds + kLdsCtrlFloats;
+  uint32_t* s_flag = (uint32_t*)dyn_lds;
+  const TaskDesc t = ld_task(a, task_index);
+  int32_t wait_ev = -1;
+  if (MEGA) {
+    wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.g->events + t.dep_event))->required != 0) ? t.dep_event : -1;
     trace_mark(a, t, 0);
-    if (!run_task<D, GRP, NB>(t, a, lds, wait_ev, &s_flag)) break;
+    if (a.g->trace && threadIdx.x == 0) as_global(a.g->trace)[(size_t)task_index * kTraceSlots + 5] = blockIdx.x;
+  }
+  if (!run_task<D, GRP, NB>(t, a, lds, wait_ev, s_flag)) return false;
+  if (MEGA) {
     trace_mark(a, t, 3);
     if (t.trig_event >= 0) signal_event(a, t, t.trig_event);
     else __syncthreads();
     trace_mark(a, t, 4);
-    if (a.g->trace && threadIdx.x == 0) a.g->trace[(size_t)(&t - a.g->tasks) * kTraceSlots + 5] = blockIdx.x;
+  }
+  return true;
+}
+
+template <int D, int GRP, int NB>
+__global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
+  extern __shared__ __align__(16) float dyn_lds[];
+  float* lds = dyn_lds + kLdsCtrlFloats;
+  uint32_t* s_flag = (uint32_t*)dyn_lds;
+  const uint32_t w = blockIdx.x;
+  if (w >= a.g->n_workers) return;
+  const uint32_t q0 = ld_u32c(a.g->aot_off + w), q1 = ld_u32c(a.g->aot_off + w + 1);
+  for (uint32_t qi = q0; qi < q1; ++qi) {
+    const uint32_t ti = ld_u32c(a.g->aot + qi);
+    const TaskDesc t = ld_task(a, ti);
+    if (t.kind == TK_LINEAR) {
+      const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.g->events + t.dep_event))->required != 0) ? t.dep_event : -1;
+      trace_mark(a, t, 0);
+      if (a.g->trace && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
+      if (!run_linear<NB, true>(t, a, lds, wait_ev, s_flag)) break;
+    } else {
+      // the callee's result comes back in a vector register: make it scalar again, or the whole
+      // task loop (and every descriptor load in it) turns into per-lane code
+      if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true>(a, ti))) break;
+    }
   }
 }
 
@@ -893,9 +1126,15 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
 // enforced by stream order (what the paper's comparison systems do, Section 6.5).
 template <int D, int GRP, int NB>
 __global__ void __launch_bounds__(kThreads) mpk_op_kernel(StepArgs a, uint32_t first) {
-  extern __shared__ __align__(16) float lds[];
-  const TaskDesc& t = a.g->tasks[a.g->op_list[first + blockIdx.x]];
-  run_task<D, GRP, NB>(t, a, lds, -1, nullptr);
+  extern __shared__ __align__(16) float dyn_lds[];
+  float* lds = dyn_lds + kLdsCtrlFloats;
+  const uint32_t ti = ld_u32c(a.g->op_list + first + blockIdx.x);
+  const TaskDesc t = ld_task(a, ti);
+  if (t.kind == TK_LINEAR) {
+    run_linear<NB, false>(t, a, lds, -1, nullptr);
+  } else {
+    run_other_task<D, GRP, NB, false>(a, ti);
+  }
 }
 
 // Specialised kernel pairs; {0, 0, 0} is the generic fallback.
@@ -1100,6 +1339,7 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
     c.n_workers = h.opt.n_workers;
     c.vocab = h.cfg.vocab; c.max_seq = h.cfg.max_seq; c.n_q = h.cfg.n_q_heads;
     c.n_kv = h.cfg.n_kv_heads; c.head_dim = h.cfg.head_dim; c.batch = h.cfg.batch;
+    c.lin_rows_max = h.lin_rows_max;
     std::vector<GraphConst> cv(1, c);
     if ((st = upload(&g->d_const, cv)) != MPK_OK) return fail(st);
   }
@@ -1132,7 +1372,7 @@ extern "C" mpk_status mpk_decode_step(mpk_graph* g, const int32_t* token_ids,
   if (g->host_only) { set_error("graph was compiled host_only"); return MPK_ERR_INVALID_ARG; }
   HostGraph& h = g->h;
   StepArgs a{};
-  a.g = g->d_const;
+  a.g = (const MPK_CONST GraphConst*)g->d_const;
   a.token_ids = token_ids; a.positions = positions; a.logits = logits_out;
   hipStream_t s = (hipStream_t)stream;
   a.epoch = ++g->epoch;
