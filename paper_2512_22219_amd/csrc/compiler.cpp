@@ -737,7 +737,7 @@ static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGr
     if (ht.op == MPK_TASK_DUMMY_OP) { t.kind = TK_DUMMY; continue; }
     const HostOp& op = g.ops[ht.op];
     tile_bounds(op, ht.tile, &t.b0, &t.b1, &t.c0, &t.c1);
-    t.flags = op.flags;
+    t.flags = op.flags | (ht.jit ? TF_JIT : 0);
     t.K = op.K;
     t.w = op.w; t.w2 = op.w2; t.f0 = op.f0; t.f1 = op.f1;
     t.p0 = op.p0; t.p1 = op.p1; t.p2 = op.p2; t.p3 = op.p3;

@@ -35,6 +35,7 @@ enum TaskFlags : uint16_t {
   TF_ROPE_FUSED = 32, // attention: rotate q (and the new k) itself, append k/v itself
   TF_ATTN_MERGE = 64, // attention: the last chunk task of a (sequence, KV head) to finish merges
                       // all chunk partials into the attention output (in2), counter index p2
+  TF_JIT = 128,       // launched just-in-time: a scheduler hands it to a worker when its event fires
 };
 
 struct alignas(16) TaskDesc {

@@ -49,6 +49,19 @@ struct GraphConst {
   uint32_t n_workers;
   uint32_t vocab, max_seq, n_q, n_kv, head_dim, batch;
   uint32_t lin_rows_max;     // largest number of weight rows (gate/up pairs count twice) of a linear task
+  // just-in-time launch (Section 5.2): scheduler event queues and worker task queues.  Entries
+  // are 64-bit (ticket + 1) << 32 | id with tickets that only grow, so a slot is valid exactly
+  // when it carries the ticket its reader expects; tails sit on their own 256-byte lines.
+  uint32_t n_sched;          // scheduler wavefronts (0: every task is ahead-of-time)
+  uint32_t evq_cap, wq_cap;  // powers of two
+  uint64_t* evq_buf;         // [n_sched][evq_cap]
+  uint32_t* evq_tail;        // [n_sched][64]
+  uint32_t* sched_state;     // [n_sched][64]: [0] head ticket, [1] round-robin cursor (persist across steps)
+  const uint32_t* sched_nev; // [n_sched] events a scheduler handles per step
+  uint64_t* wq_buf;          // [n_workers][wq_cap]
+  uint32_t* wq_tail;         // [n_workers][64]
+  uint32_t* wq_head;         // [n_workers] head ticket (persists across steps)
+  uint32_t start_event, terminal_event;
 };
 
 // Per-step kernel arguments, passed by value.  Every device function taking it is force-inlined:
@@ -980,6 +993,40 @@ __device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_
   return __builtin_amdgcn_readfirstlane(*s_flag) != 0;
 }
 
+// One lane: add this task's notification to event e (Section 5: "notify the triggering event").
+// The arrival that activates an event whose range holds just-in-time tasks hands the event to
+// its scheduler's queue.
+__device__ __forceinline__ void notify_event(const StepArgs& a, int32_t e) {
+  const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.g->events + e);
+  const uint32_t flags = ev.flags;
+  bool activated = false;
+  if (flags & EV_HIER) {
+    uint32_t* blk = a.g->hier + (size_t)ev.hier_slot * kHierWordsPerEvent;
+    const uint32_t grp = blockIdx.x & 7u;
+    uint32_t old = __hip_atomic_fetch_add(as_global(blk + (1 + grp) * kHierStrideWords), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old + 1u == a.epoch * ev.sub_required[grp]) {          // last arrival of this group
+      old = __hip_atomic_fetch_add(as_global(blk), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (old + 1u == a.epoch * ev.n_groups) {                 // last group: the event is activated
+#pragma unroll
+        for (uint32_t k = 0; k < 8; ++k)
+          __hip_atomic_store(as_global(blk + (9 + k) * kHierStrideWords), a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        activated = true;
+      }
+    }
+  } else if ((flags & EV_JIT) && a.g->n_sched) {
+    const uint32_t old = __hip_atomic_fetch_add(as_global(a.g->counters + e), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    activated = old + 1u == a.epoch * ev.required;
+  } else {
+    __hip_atomic_fetch_add(as_global(a.g->counters + e), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (activated && (flags & EV_JIT) && a.g->n_sched) {
+    const uint32_t sc = (uint32_t)e % a.g->n_sched;
+    const uint32_t slot = __hip_atomic_fetch_add(as_global(a.g->evq_tail + sc * 64u), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(as_global(a.g->evq_buf + (size_t)sc * a.g->evq_cap + (slot & (a.g->evq_cap - 1u))),
+                       ((uint64_t)(slot + 1u) << 32) | (uint32_t)e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
 __device__ __forceinline__ void signal_event(const StepArgs& a, const TaskDesc& t, int32_t e) {
   // every wavefront waits until its own agent-scope stores have completed at the coherence point
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -987,24 +1034,7 @@ __device__ __forceinline__ void signal_event(const StepArgs& a, const TaskDesc& 
   trace_mark(a, t, 6);
   __syncthreads();
   trace_mark(a, t, 7);
-  if (threadIdx.x == 0) {
-    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.g->events + e);
-    if (ev.flags & EV_HIER) {
-      uint32_t* blk = a.g->hier + (size_t)ev.hier_slot * kHierWordsPerEvent;
-      const uint32_t grp = blockIdx.x & 7u;
-      uint32_t old = __hip_atomic_fetch_add(as_global(blk + (1 + grp) * kHierStrideWords), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (old + 1u == a.epoch * ev.sub_required[grp]) {          // last arrival of this group
-        old = __hip_atomic_fetch_add(as_global(blk), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (old + 1u == a.epoch * ev.n_groups) {                 // last group: the event is activated
-#pragma unroll
-          for (uint32_t k = 0; k < 8; ++k)
-            __hip_atomic_store(as_global(blk + (9 + k) * kHierStrideWords), a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-      }
-    } else {
-      __hip_atomic_fetch_add(as_global(a.g->counters + e), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-  }
+  if (threadIdx.x == 0) notify_event(a, e);
 }
 
 // Wavefront 0 only: poll the dependent event of the next task; result in *s_flag (LDS).
@@ -1046,26 +1076,8 @@ __device__ __forceinline__ void signal_from_wave0(const StepArgs& a, const TaskD
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   trace_mark(a, t, 7);
-  if (lane == 0) {
-    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.g->events + e);
-    if (ev.flags & EV_HIER) {
-      uint32_t* blk = a.g->hier + (size_t)ev.hier_slot * kHierWordsPerEvent;
-      const uint32_t grp = blockIdx.x & 7u;
-      uint32_t old = __hip_atomic_fetch_add(as_global(blk + (1 + grp) * kHierStrideWords), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (old + 1u == a.epoch * ev.sub_required[grp]) {
-        old = __hip_atomic_fetch_add(as_global(blk), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (old + 1u == a.epoch * ev.n_groups) {
-#pragma unroll
-          for (uint32_t k = 0; k < 8; ++k)
-            __hip_atomic_store(as_global(blk + (9 + k) * kHierStrideWords), a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-      }
-    } else {
-      __hip_atomic_fetch_add(as_global(a.g->counters + e), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-  }
+  if (lane == 0) notify_event(a, e);
 }
-
 
 // The first 64 bytes of the dynamic LDS are control words ([0] = result of the last event wait);
 // task bodies use the rest.
@@ -1077,14 +1089,14 @@ constexpr uint32_t kLdsCtrlFloats = 16;
 // force spills of registers that have loads in flight.
 // Returns false when the step is being aborted.
 template <int D, int GRP, int NB, bool MEGA>
-__device__ __noinline__ bool run_other_task(StepArgs a, uint32_t task_index) {
+__device__ __noinline__ bool run_other_task(StepArgs a, uint32_t task_index, bool skip_wait) {
   extern __shared__ __align__(16) float dyn_lds[];
   float* lds = dyn_lds + kLdsCtrlFloats;
   uint32_t* s_flag = (uint32_t*)dyn_lds;
   const TaskDesc t = ld_task(a, task_index);
   int32_t wait_ev = -1;
   if (MEGA) {
-    wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.g->events + t.dep_event))->required != 0) ? t.dep_event : -1;
+    wait_ev = (!skip_wait && t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.g->events + t.dep_event))->required != 0) ? t.dep_event : -1;
     trace_mark(a, t, 0);
     if (a.g->trace && threadIdx.x == 0) as_global(a.g->trace)[(size_t)task_index * kTraceSlots + 5] = blockIdx.x;
   }
@@ -1098,28 +1110,183 @@ __device__ __noinline__ bool run_other_task(StepArgs a, uint32_t task_index) {
   return true;
 }
 
+__device__ __forceinline__ bool event_active(const StepArgs& a, int32_t e) {
+  const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.g->events + e);
+  if (ev.required == 0) return true;
+  if (ev.flags & EV_HIER) {
+    const uint32_t* word = a.g->hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
+    return (int32_t)(ld_relaxed(word) - a.epoch) >= 0;
+  }
+  return (int32_t)(ld_relaxed(a.g->counters + e) - a.epoch * ev.required) >= 0;
+}
+
+__device__ __forceinline__ uint64_t ld_relaxed64(const uint64_t* p) {
+  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One scheduler wavefront (Section 5.1): takes activated events from its own queue and hands the
+// just-in-time tasks of each event's range to the workers' queues, round-robin from a cursor of
+// its own -- local state only, no coordination with other schedulers (Section 6.1).
+__device__ __forceinline__ void scheduler_wave(const StepArgs& a, uint32_t sc) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t W = a.g->n_workers;
+  uint32_t head = ld_relaxed(a.g->sched_state + sc * 64u), cursor = ld_relaxed(a.g->sched_state + sc * 64u + 1u);
+  uint32_t todo = ld_u32c(a.g->sched_nev + sc);
+  // the start event has no notifications: its owner dispatches it unprompted
+  const MPK_CONST EventDesc& sev = *(const MPK_CONST EventDesc*)(a.g->events + a.g->start_event);
+  bool pending_start = (sev.flags & EV_JIT) && a.g->start_event % a.g->n_sched == sc;
+  while (todo > 0 || pending_start) {
+    uint32_t e;
+    if (pending_start) {
+      e = a.g->start_event;
+      pending_start = false;
+    } else {
+      const uint64_t* slot = a.g->evq_buf + (size_t)sc * a.g->evq_cap + (head & (a.g->evq_cap - 1u));
+      uint64_t v = ld_relaxed64(slot);
+      if ((uint32_t)(v >> 32) != head + 1u) {
+        const uint64_t t_start = wall_clock64();
+        uint32_t it = 0;
+        bool dead = false;
+        while ((uint32_t)((v = ld_relaxed64(slot)) >> 32) != head + 1u) {
+          if ((++it & 255u) == 0) {
+            if (ld_relaxed(a.g->err + 1) != 0) { dead = true; break; }
+            if (wall_clock64() - t_start > a.g->timeout_ticks) {
+              if (lane == 0) {
+                report(a, DE_TIMEOUT, 0x80000000u | sc, blockIdx.x);
+                __hip_atomic_store(as_global(a.g->err + 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              }
+              dead = true;
+              break;
+            }
+          }
+        }
+        if (dead) break;
+      }
+      e = (uint32_t)v;
+      ++head;
+      --todo;
+    }
+    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.g->events + e);
+    const uint32_t first = ev.first, n = ev.last - ev.first;
+    for (uint32_t i = lane; i < n; i += 64) {
+      const uint32_t ti = first + i;
+      const MPK_CONST TaskDesc& td = *(const MPK_CONST TaskDesc*)(a.g->tasks + ti);
+      if (td.flags & TF_JIT) {
+        const uint32_t w = (cursor + i) % W;
+        const uint32_t s = __hip_atomic_fetch_add(as_global(a.g->wq_tail + w * 64u), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(as_global(a.g->wq_buf + (size_t)w * a.g->wq_cap + (s & (a.g->wq_cap - 1u))),
+                           ((uint64_t)(s + 1u) << 32) | ti, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    cursor += n;
+  }
+  if (lane == 0) {
+    __hip_atomic_store(as_global(a.g->sched_state + sc * 64u), head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(as_global(a.g->sched_state + sc * 64u + 1u), cursor % W, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+constexpr uint32_t kPickExit = 0xFFFFFFFFu, kPickAbort = 0xFFFFFFFEu;
+
+// Worker side of the hybrid launch (Section 5.2): just-in-time tasks first; when none is queued,
+// the head of the ahead-of-time queue if its dependent event is activated; exit once the
+// ahead-of-time queue is exhausted and the terminal event has been activated.  One lane decides,
+// the result goes through LDS.  Returns a task index (bit 31 set: it came from the JIT queue).
+__device__ __forceinline__ uint32_t pick_task(const StepArgs& a, uint32_t* ctrl, uint32_t* jit_head, uint32_t* ai, uint32_t q1) {
+  if (threadIdx.x == 0) {
+    const uint32_t w = blockIdx.x;
+    uint32_t pick;
+    const uint64_t t_start = wall_clock64();
+    uint32_t it = 0;
+    while (true) {
+      const uint64_t v = ld_relaxed64(a.g->wq_buf + (size_t)w * a.g->wq_cap + (*jit_head & (a.g->wq_cap - 1u)));
+      if ((uint32_t)(v >> 32) == *jit_head + 1u) {
+        pick = (uint32_t)v | 0x80000000u;
+        ++*jit_head;
+        break;
+      }
+      if (*ai < q1) {
+        const uint32_t ti = ld_u32c(a.g->aot + *ai);
+        const int32_t dep = ((const MPK_CONST TaskDesc*)(a.g->tasks + ti))->dep_event;
+        if (dep < 0 || event_active(a, dep)) {
+          pick = ti;
+          ++*ai;
+          break;
+        }
+      } else if (event_active(a, (int32_t)a.g->terminal_event)) {
+        pick = kPickExit;
+        break;
+      }
+      if ((++it & 63u) == 0) {
+        if (ld_relaxed(a.g->err + 1) != 0) { pick = kPickAbort; break; }
+        if (wall_clock64() - t_start > a.g->timeout_ticks) {
+          report(a, DE_TIMEOUT, 0x40000000u | (*ai < q1 ? ld_u32c(a.g->aot + *ai) : 0u), blockIdx.x);
+          __hip_atomic_store(as_global(a.g->err + 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          pick = kPickAbort;
+          break;
+        }
+      }
+    }
+    ctrl[1] = pick;
+    ctrl[2] = *jit_head;
+    ctrl[3] = *ai;
+  }
+  __syncthreads();
+  *jit_head = __builtin_amdgcn_readfirstlane(ctrl[2]);
+  *ai = __builtin_amdgcn_readfirstlane(ctrl[3]);
+  const uint32_t pick = __builtin_amdgcn_readfirstlane(ctrl[1]);
+  __syncthreads();   // ctrl may be rewritten only after everybody has read it
+  return pick;
+}
+
 template <int D, int GRP, int NB>
 __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
   extern __shared__ __align__(16) float dyn_lds[];
   float* lds = dyn_lds + kLdsCtrlFloats;
   uint32_t* s_flag = (uint32_t*)dyn_lds;
   const uint32_t w = blockIdx.x;
-  if (w >= a.g->n_workers) return;
+  if (w >= a.g->n_workers) {
+    // scheduler workgroup: 4 scheduler wavefronts (Section 5.1, Table 2), the rest leave
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t sc = (w - a.g->n_workers) * 4u + wave;
+    if (wave < 4u && sc < a.g->n_sched) scheduler_wave(a, sc);
+    return;
+  }
   const uint32_t q0 = ld_u32c(a.g->aot_off + w), q1 = ld_u32c(a.g->aot_off + w + 1);
-  for (uint32_t qi = q0; qi < q1; ++qi) {
-    const uint32_t ti = ld_u32c(a.g->aot + qi);
+  if (a.g->n_sched == 0) {
+    // every task ahead-of-time: walk the pre-enqueued list, each task waits for its own event
+    for (uint32_t qi = q0; qi < q1; ++qi) {
+      const uint32_t ti = ld_u32c(a.g->aot + qi);
+      const TaskDesc t = ld_task(a, ti);
+      if (t.kind == TK_LINEAR) {
+        const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.g->events + t.dep_event))->required != 0) ? t.dep_event : -1;
+        trace_mark(a, t, 0);
+        if (a.g->trace && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
+        if (!run_linear<NB, true>(t, a, lds, wait_ev, s_flag)) break;
+      } else {
+        // the callee's result comes back in a vector register: make it scalar again, or the whole
+        // task loop (and every descriptor load in it) turns into per-lane code
+        if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true>(a, ti, false))) break;
+      }
+    }
+    return;
+  }
+  // hybrid launch
+  uint32_t jit_head = ld_relaxed(a.g->wq_head + w), ai = q0;
+  while (true) {
+    const uint32_t pick = pick_task(a, (uint32_t*)dyn_lds, &jit_head, &ai, q1);
+    if (pick == kPickExit || pick == kPickAbort) break;
+    const uint32_t ti = pick & 0x7FFFFFFFu;
     const TaskDesc t = ld_task(a, ti);
     if (t.kind == TK_LINEAR) {
-      const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.g->events + t.dep_event))->required != 0) ? t.dep_event : -1;
       trace_mark(a, t, 0);
       if (a.g->trace && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
-      if (!run_linear<NB, true>(t, a, lds, wait_ev, s_flag)) break;
+      if (!run_linear<NB, true>(t, a, lds, -1, s_flag)) break;   // its event is already activated
     } else {
-      // the callee's result comes back in a vector register: make it scalar again, or the whole
-      // task loop (and every descriptor load in it) turns into per-lane code
-      if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true>(a, ti))) break;
+      if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true>(a, ti, true))) break;
     }
   }
+  if (threadIdx.x == 0) __hip_atomic_store(as_global(a.g->wq_head + w), jit_head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Kernel-per-operator baseline: the same task bodies, one launch per operator, dependencies
@@ -1133,7 +1300,7 @@ __global__ void __launch_bounds__(kThreads) mpk_op_kernel(StepArgs a, uint32_t f
   if (t.kind == TK_LINEAR) {
     run_linear<NB, false>(t, a, lds, -1, nullptr);
   } else {
-    run_other_task<D, GRP, NB, false>(a, ti);
+    run_other_task<D, GRP, NB, false>(a, ti, true);
   }
 }
 
@@ -1179,6 +1346,15 @@ struct mpk_graph {
   const KernelVariant* kv = nullptr;
   uint32_t* d_grp = nullptr;
   uint32_t* d_hier = nullptr;
+  // just-in-time launch
+  uint64_t* d_evq_buf = nullptr;
+  uint32_t* d_evq_tail = nullptr;
+  uint32_t* d_sched_state = nullptr;
+  uint32_t* d_sched_nev = nullptr;
+  uint64_t* d_wq_buf = nullptr;
+  uint32_t* d_wq_tail = nullptr;
+  uint32_t* d_wq_head = nullptr;
+  uint32_t n_sched = 0, evq_cap = 1, wq_cap = 1;
   float* d_arena = nullptr;
   std::vector<uint32_t> op_first, op_count;   // per operator: range in op_list
   uint32_t epoch = 0;
@@ -1200,6 +1376,8 @@ static void free_device(mpk_graph* g) {
   (void)hipFree(g->d_aot_off); (void)hipFree(g->d_aot); (void)hipFree(g->d_op_list);
   (void)hipFree(g->d_err); (void)hipFree(g->d_arena);
   (void)hipFree(g->d_inv_freq); (void)hipFree(g->d_grp); (void)hipFree(g->d_trace); (void)hipFree(g->d_hier); (void)hipFree(g->d_const);
+  (void)hipFree(g->d_evq_buf); (void)hipFree(g->d_evq_tail); (void)hipFree(g->d_sched_state); (void)hipFree(g->d_sched_nev);
+  (void)hipFree(g->d_wq_buf); (void)hipFree(g->d_wq_tail); (void)hipFree(g->d_wq_head);
 }
 
 static mpk_status resolve_options(const mpk_compile_options* in, mpk_compile_options* out,
@@ -1253,9 +1431,9 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
   int n_cu = 0;
   mpk_status st = resolve_options(opts, &o, &n_cu);
   if (st != MPK_OK) return st;
-  if (!o.host_only && o.n_sched_wgs > 0 && !o.force_aot) {
-    set_error("scheduler workgroups (just-in-time launch) are not implemented on the device yet; use n_sched_wgs = 0 or host_only");
-    return MPK_ERR_UNSUPPORTED;
+  if (!o.host_only && o.n_sched_wgs > 0 && !o.force_aot && o.launch_mode != MPK_LAUNCH_MEGA) {
+    set_error("scheduler workgroups only exist in the persistent kernel (launch_mode MPK_LAUNCH_MEGA)");
+    return MPK_ERR_INVALID_ARG;
   }
   mpk_graph* g = new (std::nothrow) mpk_graph();
   if (!g) { set_error("out of host memory"); return MPK_ERR_OOM; }
@@ -1329,6 +1507,32 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
     std::vector<uint64_t> tz(h.tasks.size() * kTraceSlots, 0);
     if ((st = upload(&g->d_trace, tz)) != MPK_OK) return fail(st);
   }
+  // just-in-time launch: queues for the scheduler wavefronts (4 per scheduler workgroup)
+  {
+    const bool jit = o.n_sched_wgs > 0 && !o.force_aot && h.stats.n_jit_tasks > 0;
+    g->n_sched = jit ? 4u * o.n_sched_wgs : 0u;
+    std::vector<uint32_t> nev(std::max(g->n_sched, 1u), 0);
+    uint64_t per_worker = 0;   // bound on the JIT tasks one worker can be handed in a step
+    if (jit) {
+      for (size_t e = 0; e < h.events.size(); ++e) {
+        if (!(h.events[e].flags & EV_JIT)) continue;
+        if (e != h.start_event) nev[e % g->n_sched]++;
+        per_worker += (h.events[e].last - h.events[e].first + o.n_workers - 1) / o.n_workers;
+      }
+    }
+    auto pow2 = [](uint64_t v) { uint64_t p = 1; while (p < v) p <<= 1; return (uint32_t)p; };
+    g->evq_cap = pow2(*std::max_element(nev.begin(), nev.end()) + 1);
+    g->wq_cap = pow2(per_worker + 1);
+    std::vector<uint64_t> ez((size_t)std::max(g->n_sched, 1u) * g->evq_cap, 0), wz((size_t)o.n_workers * g->wq_cap, 0);
+    std::vector<uint32_t> tz((size_t)std::max(g->n_sched, 1u) * 64, 0), wt((size_t)o.n_workers * 64, 0), wh(o.n_workers, 0);
+    if ((st = upload(&g->d_evq_buf, ez)) != MPK_OK) return fail(st);
+    if ((st = upload(&g->d_evq_tail, tz)) != MPK_OK) return fail(st);
+    if ((st = upload(&g->d_sched_state, tz)) != MPK_OK) return fail(st);
+    if ((st = upload(&g->d_sched_nev, nev)) != MPK_OK) return fail(st);
+    if ((st = upload(&g->d_wq_buf, wz)) != MPK_OK) return fail(st);
+    if ((st = upload(&g->d_wq_tail, wt)) != MPK_OK) return fail(st);
+    if ((st = upload(&g->d_wq_head, wh)) != MPK_OK) return fail(st);
+  }
   g->timeout_ticks = (uint64_t)o.spin_timeout_ms * 100000ull;   // wall clock counts at 100 MHz
   {
     GraphConst c{};
@@ -1340,6 +1544,10 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
     c.vocab = h.cfg.vocab; c.max_seq = h.cfg.max_seq; c.n_q = h.cfg.n_q_heads;
     c.n_kv = h.cfg.n_kv_heads; c.head_dim = h.cfg.head_dim; c.batch = h.cfg.batch;
     c.lin_rows_max = h.lin_rows_max;
+    c.n_sched = g->n_sched; c.evq_cap = g->evq_cap; c.wq_cap = g->wq_cap;
+    c.evq_buf = g->d_evq_buf; c.evq_tail = g->d_evq_tail; c.sched_state = g->d_sched_state;
+    c.sched_nev = g->d_sched_nev; c.wq_buf = g->d_wq_buf; c.wq_tail = g->d_wq_tail; c.wq_head = g->d_wq_head;
+    c.start_event = h.start_event; c.terminal_event = h.terminal_event;
     std::vector<GraphConst> cv(1, c);
     if ((st = upload(&g->d_const, cv)) != MPK_OK) return fail(st);
   }
@@ -1377,7 +1585,7 @@ extern "C" mpk_status mpk_decode_step(mpk_graph* g, const int32_t* token_ids,
   hipStream_t s = (hipStream_t)stream;
   a.epoch = ++g->epoch;
   if (h.opt.launch_mode == MPK_LAUNCH_MEGA) {
-    hipLaunchKernelGGL(g->kv->mega, dim3(h.opt.n_workers + h.opt.n_sched_wgs), dim3(kThreads),
+    hipLaunchKernelGGL(g->kv->mega, dim3(h.opt.n_workers + (g->n_sched ? h.opt.n_sched_wgs : 0u)), dim3(kThreads),
                        h.lds_bytes, s, a);
     HIP_TRY(hipGetLastError());
   } else {
@@ -1419,6 +1627,15 @@ extern "C" mpk_status mpk_graph_reset(mpk_graph* g) {
   HIP_TRY(hipMemset(g->d_err, 0, 8 * sizeof(uint32_t)));
   HIP_TRY(hipMemset(g->d_hier, 0, (size_t)std::max(g->h.n_hier_events, 1u) * kHierWordsPerEvent * sizeof(uint32_t)));
   HIP_TRY(hipMemset(g->d_grp, 0, std::max<size_t>(g->h.n_group_counters, 1) * sizeof(uint32_t)));
+  {
+    const size_t ns = std::max(g->n_sched, 1u), nw = g->h.opt.n_workers;
+    HIP_TRY(hipMemset(g->d_evq_buf, 0, ns * g->evq_cap * sizeof(uint64_t)));
+    HIP_TRY(hipMemset(g->d_evq_tail, 0, ns * 64 * sizeof(uint32_t)));
+    HIP_TRY(hipMemset(g->d_sched_state, 0, ns * 64 * sizeof(uint32_t)));
+    HIP_TRY(hipMemset(g->d_wq_buf, 0, nw * g->wq_cap * sizeof(uint64_t)));
+    HIP_TRY(hipMemset(g->d_wq_tail, 0, nw * 64 * sizeof(uint32_t)));
+    HIP_TRY(hipMemset(g->d_wq_head, 0, nw * sizeof(uint32_t)));
+  }
   HIP_TRY(hipDeviceSynchronize());
   g->epoch = 0;
   return MPK_OK;

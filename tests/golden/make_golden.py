@@ -4,8 +4,12 @@ oracle (oracle/) on the seeded synthetic inputs (synth/).  Nothing here touches 
 
     python tests/golden/make_golden.py C2        # Qwen3-8B-shaped, batch 1, 32 greedy steps
 
+    python tests/golden/make_golden.py C2 f64    # add the fp64 oracle's step-0 samples to C2_greedy.json
+
 Each fixture is a small JSON file: greedy tokens of every step, the top-8 logits (index, value)
-of every step, and 512 pseudo-randomly sampled logits of step 0 and of the last step.
+of every step, and 512 pseudo-randomly sampled logits of step 0 and of the last step (fp32
+oracle); "samples64_0" holds the same step-0 samples from the oracle built with fp64 arithmetic
+(same inputs), which bounds the fp32 oracle's own rounding error.
 """
 import json
 import os
@@ -24,8 +28,27 @@ def sample_indices(vocab, n=512):
     return (G.mix64(99, 77, np.arange(n, dtype=np.uint64)) % np.uint64(vocab)).astype(np.int64)
 
 
+def add_f64(name):
+    s = G.CONFIGS[name]
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"{name}_greedy.json")
+    with open(path) as f:
+        out = json.load(f)
+    o = D.DecoderOracle(s, G.SynthWeights(s, out["seed"], cache=False), "f64")
+    tok = np.array(out["start_tokens"], np.int64)
+    pos = np.array(out["start_positions"], np.int64)
+    idx = np.array(out["sample_indices"])
+    lg = o.step(tok, pos)
+    out["samples64_0"] = [[float(v) for v in lg[b, idx]] for b in range(s.batch)]
+    out["absmax64_0"] = [float(np.abs(lg[b]).max()) for b in range(s.batch)]
+    with open(path, "w") as f:
+        json.dump(out, f)
+    print("added fp64 step-0 samples to", path)
+
+
 def main():
     name = sys.argv[1] if len(sys.argv) > 1 else "C2"
+    if len(sys.argv) > 2 and sys.argv[2] == "f64":
+        return add_f64(name)
     steps = int(sys.argv[2]) if len(sys.argv) > 2 else G.CONFIGS[name].steps
     s = G.CONFIGS[name]
     seed = 0

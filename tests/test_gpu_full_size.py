@@ -42,7 +42,15 @@ def _check_against_fixture(name, opts, free_running=True):
         lg = gpu.step(tok, pos)
         assert np.isfinite(lg).all(), i
         want_tok = np.array(gold["tokens"][i])
-        assert lg.argmax(-1).tolist() == want_tok.tolist(), f"step {i}"
+        for b in range(s.batch):
+            got_tok = int(lg[b].argmax())
+            if got_tok != int(want_tok[b]):
+                # only a near-tie of the oracle's two best logits may resolve the other way
+                # (fp32 summation order, bf16 rounding of appended K/V rows): the gap must be
+                # below 2e-3 of the largest logit and the GPU's choice must be the runner-up
+                (j0, v0), (j1, v1) = gold["top8"][i][b][0], gold["top8"][i][b][1]
+                assert got_tok == j1 and (v0 - v1) < 2e-3 * abs(v0), f"step {i} sequence {b}"
+                free_running = False   # keep both sides on the oracle's token sequence from here on
         for b in range(s.batch):
             top = gold["top8"][i][b]
             scale = abs(top[0][1])
@@ -80,3 +88,8 @@ def test_c2_full_size_32_greedy_steps_mega_kernel():
 
 def test_c2_full_size_per_operator_launch():
     _check_against_fixture("C2", dict(launch_mode=1, **BENCH_OPTS), free_running=False)
+
+
+def test_c5_70b_shaped_16_greedy_steps_mega_kernel():
+    """141 GB of weights resident in HBM (generated on the device), KV 2048, 16 steps."""
+    _check_against_fixture("C5", BENCH_OPTS)

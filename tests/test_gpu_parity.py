@@ -38,6 +38,11 @@ MODES = [
     dict(fusion=16 + 7),
     dict(fusion=8 + 7, attn_chunks=1),
     dict(fusion=31, transitive_reduction=1, n_workers=37, attn_chunks=5),
+    # hybrid launch: scheduler wavefronts hand the attention tasks out just-in-time
+    dict(fusion=0, n_sched_wgs=1, n_workers=16),
+    dict(fusion=7, transitive_reduction=1, n_sched_wgs=2),
+    dict(fusion=31, transitive_reduction=1, n_sched_wgs=2, attn_chunks=5),
+    dict(fusion=31, transitive_reduction=1, n_sched_wgs=1, n_workers=37, attn_chunks=3),
 ]
 
 
@@ -72,7 +77,8 @@ def test_c1_one_step_matches_oracle(opts):
 
 
 @pytest.mark.parametrize("opts", [dict(fusion=0), dict(fusion=7, transitive_reduction=1),
-                                  dict(fusion=31, transitive_reduction=1)])
+                                  dict(fusion=31, transitive_reduction=1),
+                                  dict(fusion=31, transitive_reduction=1, n_sched_wgs=2)])
 def test_small_batch_and_ragged_positions(opts):
     """Batch 3 with different KV lengths (one of them tiny), ragged tiles (n_workers = 37)."""
     s = G.small_variant("C1", batch=3, n_layers=2)
@@ -81,6 +87,8 @@ def test_small_batch_and_ragged_positions(opts):
     ref = D.DecoderOracle(s, G.SynthWeights(s, 1), "f32")
     want = ref.step(tok, pos)
     gpu = GpuDecoder(s, 1, n_workers=37, **opts)
+    if opts.get("n_sched_wgs"):
+        assert gpu.graph.stats()["n_jit_tasks"] > 0
     got = gpu.step(tok, pos)
     assert rel_err(got, want) < TOL
     assert np.abs(got - want).max() / np.abs(want).max() < 1e-4
@@ -93,7 +101,8 @@ def test_greedy_32_steps_free_running_and_teacher_forced():
     ref = D.DecoderOracle(s, G.SynthWeights(s, 0), "f32")
     want_t, want_l = ref.greedy(tok, pos, 32)
     for opts in (dict(fusion=0), dict(fusion=7, transitive_reduction=1),
-                 dict(fusion=31, transitive_reduction=1)):
+                 dict(fusion=31, transitive_reduction=1),
+                 dict(fusion=31, transitive_reduction=1, n_sched_wgs=2)):
         gpu = GpuDecoder(s, 0, **opts)
         t, p, toks = np.array(tok), np.array(pos), []
         for i in range(32):
