@@ -67,10 +67,18 @@ def _check_against_fixture(name, opts, free_running=True):
                 amax = gold["absmax_%d" % i][b]
                 diff = np.abs(lg[b, idx] - want)
                 if i == 0:
-                    # identical inputs on both sides: the element-wise bound of the target
-                    err = diff / np.maximum(np.abs(want), 1e-3 * amax)
+                    # identical inputs on both sides: the element-wise bound of the target, taken
+                    # against the fp64 build of the oracle.  (The fp32 build sums every dot
+                    # product sequentially in fp32; on the widest shapes its own rounding error,
+                    # stored in the fixture as the fp32/fp64 difference, reaches 1e-3 of the
+                    # largest logit, far more than the GPU's.)
+                    want64 = np.array(gold["samples64_0"][b])
+                    d64 = np.abs(lg[b, idx] - want64)
+                    err = d64 / np.maximum(np.abs(want64), 1e-3 * amax)
                     assert err.max() < TOL, (i, b, float(err.max()))
-                    assert diff.max() / amax < 1e-4   # fp32 activations throughout
+                    assert d64.max() / amax < 1e-4   # fp32 activations throughout
+                    own = np.abs(want - want64).max() / amax   # the fp32 oracle's own error
+                    assert diff.max() / amax < own + 1e-4, (float(diff.max() / amax), float(own))
                 else:
                     # later steps read K/V rows each side appended itself: a row element whose
                     # fp32 value sits on a bf16 rounding boundary may round the other way (one
