@@ -783,8 +783,16 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
   g.lin_rows_max = rows_max;
   for (auto& op : g.ops) {
     size_t f = 0;
-    if (op.kind == MPK_OP_LINEAR || op.kind == MPK_OP_GATEUP)
-      f = (size_t)nb * ((op.K + 4095u) / 4096u * 4096u) + 2 * (size_t)rows_max * nb + 8 * nb;
+    if (op.kind == MPK_OP_LINEAR || op.kind == MPK_OP_GATEUP) {
+      if (c.batch <= 4) {
+        f = (size_t)nb * ((op.K + 4095u) / 4096u * 4096u) + 2 * (size_t)rows_max * nb + 8 * nb;
+      } else {
+        // matrix-core body: two bf16 planes of one input tile | per-wavefront partial tiles |
+        // residual slice | sums of squares
+        const size_t kt = c.batch <= 8 ? 2048 : 1024;
+        f = (size_t)c.batch * (kt + 8) + 8 * 4 * 256 + (size_t)rows_max * 16 + 8 * 16;
+      }
+    }
     else if (op.kind == MPK_OP_ATTN_PARTIAL)
       f = (size_t)grp * c.head_dim                                        // q
           + (size_t)(kThreads / 64) * grp * (c.head_dim + 2) + 16 + 64;   // per-wave partials
@@ -808,7 +816,7 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
     if (grp != 1 && grp != 2 && grp != 4 && grp != 8) { set_error("%u query heads per KV head unsupported (1, 2, 4 or 8)", grp); return MPK_ERR_UNSUPPORTED; }
   }
   if (c.hidden % 8 || c.ffn % 8 || (c.n_q_heads * c.head_dim) % 8) { set_error("hidden, ffn and n_q*head_dim must be multiples of 8"); return MPK_ERR_UNSUPPORTED; }
-  if (c.batch > 8) { set_error("batch %u unsupported by the dense linear bodies (max 8)", c.batch); return MPK_ERR_UNSUPPORTED; }
+  if (c.batch > 16) { set_error("batch %u unsupported by the dense linear bodies (max 16)", c.batch); return MPK_ERR_UNSUPPORTED; }
   if (o.debug_flags & ~MPK_DEBUG_TRACE) { set_error("unknown debug_flags bits"); return MPK_ERR_INVALID_ARG; }
   if (o.fusion & ~(MPK_FUSE_NORM | MPK_FUSE_RESID | MPK_FUSE_SWIGLU | MPK_FUSE_MERGE | MPK_FUSE_ROPE)) { set_error("unknown fusion bits"); return MPK_ERR_INVALID_ARG; }
   if (!o.host_only) {
@@ -832,20 +840,15 @@ mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs*
   if (opt.n_workers == 0) { set_error("n_workers unresolved"); return MPK_ERR_INTERNAL; }
   uint32_t C = opt.attn_chunks;
   if (C == 0) {
-    // A chunk may not exceed what a task holds in registers (the pre-load window: 8 rounds of
-    // one cache position per 128-bit lane group and wavefront); a bit more than half of it
-    // measured best (shorter attention tasks against more partials to merge).
-    const uint32_t window = 8u * (kThreads / 64u) * (64u / (cfg.head_dim / 8u));
-    const uint32_t target = std::max(1u, window * 9u / 16u);
-    C = (cfg.max_seq + target - 1) / target;
-    C = std::min(C, 64u);
-    C = std::max(C, (cfg.max_seq + window - 1) / window);
+    // About one attention task per worker, but no chunk shorter than 128 cache positions (each
+    // task has a fixed cost: event wait, query staging, the merge of its partial result).
+    // Measured: C2 (8 pairs, 1088 positions) is fastest with 8 chunks, C3 (64 pairs) with 4.
+    const uint32_t pairs = cfg.batch * cfg.n_kv_heads;
+    C = (opt.n_workers + pairs - 1) / pairs;
+    C = std::min(C, std::max(1u, cfg.max_seq / 128u));
+    C = std::max(1u, std::min(C, 64u));
   }
   if (C > 64) { set_error("attn_chunks %u too large (max 64)", C); return MPK_ERR_INVALID_ARG; }
-  {
-    const uint32_t window = 8u * (kThreads / 64u) * (64u / (cfg.head_dim / 8u));
-    if ((cfg.max_seq + C - 1) / C > window) { set_error("attn_chunks %u too small: a chunk of max_seq %u would exceed the %u positions an attention task holds in registers", C, cfg.max_seq, window); return MPK_ERR_INVALID_ARG; }
-  }
   opt.attn_chunks = C;
   g.cfg = cfg;
   g.opt = opt;
@@ -866,6 +869,7 @@ mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs*
   g.stats.n_pair_deps += g.stats.n_pairs_removed;
   build_descs(cfg, kv, g);
   g.lds_bytes = lds_requirement(cfg, g, C);
+  if (cfg.batch > 4 && g.lin_rows_max > 512) { set_error("a linear task would own %u weight rows; the batch >= 5 body handles at most 512: raise tiles_linear / tiles_lm_head", g.lin_rows_max); return MPK_ERR_UNSUPPORTED; }
   if (g.lds_bytes > 160 * 1024 && !opt.host_only) { set_error("task bodies need %u bytes of LDS (> 160 KB): batch x input length too large", g.lds_bytes); return MPK_ERR_UNSUPPORTED; }
   // statistics
   g.stats.struct_size = sizeof(mpk_stats);

@@ -527,6 +527,191 @@ __device__ __forceinline__ bool linear_task(const TaskDesc& t, const StepArgs& a
   return true;
 }
 
+// ------------------------------------------------------------------------------ linear tasks, batch 5..16
+// The same operator for 5 to 16 batch rows, on the matrix cores.  At batch 8 the vector ALUs
+// would need about as many cycles for the multiply-adds as HBM needs to deliver the weights; one
+// v_mfma_f32_16x16x32_bf16 does 16 weight rows x 32 inputs x 16 batch columns at once.
+//   A operand = weights: lane l holds row (l % 16) of a 16-row tile, inputs 8 (l / 16) .. + 7 of
+//     the current 32-input step: 16 bytes straight from HBM, no conversion.
+//   B operand = activations: lane l holds batch column (l % 16), the same 8 inputs, as bf16.
+//     Activations are fp32: x is split into hi = bf16(x) and lo = bf16(x - hi) and each weight
+//     fragment is multiplied with both (x is represented to 2^-17, the products are exact and
+//     the accumulation is fp32).
+//   D: lane l holds batch column (l % 16), tile rows 4 (l / 16) .. + 3.
+// The input is staged in LDS one K tile at a time (hi and lo planes, row stride padded by 16
+// bytes so that the 16 lanes of a fragment read 16 different bank groups).  Work is split over
+// the 8 wavefronts by 16-row tiles; a task with fewer than 8 tiles also splits K inside each
+// input tile, and the epilogue adds the slices in a fixed order.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t mfma_ktile(uint32_t nb) { return nb <= 8 ? 2048u : 1024u; }
+
+// LDS (bytes from the task area): xh [nb][Kt + 8] bf16 | xl same | part [8 waves][4][256] f32 |
+// res [rows_max][16] f32 | ssq [8][16] f32
+template <bool MEGA>
+__device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
+                                                 uint32_t* s_flag) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t K = t.K, nb = t.b1 - t.b0, ncols = t.c1 - t.c0;
+  const uint32_t gateup = (t.flags & TF_GATEUP) ? 1u : 0u;
+  const uint32_t R = ncols << gateup;            // weight rows of the task ("ring rows")
+  const uint32_t nrt = (R + 15u) / 16u;          // 16-row tiles
+  const uint32_t Kt = mfma_ktile(nb), xstride = Kt + 8u;
+  uint16_t* xh = (uint16_t*)lds;
+  uint16_t* xl = xh + (size_t)nb * xstride;
+  float* part = (float*)(xl + (size_t)nb * xstride);       // [8][4][256]
+  float* res_lds = part + 8 * 4 * 256;                      // [rows_max][16]
+  float* ssq = res_lds + (size_t)a.g->lin_rows_max * 16;    // [8][16]
+  // which tiles and which K slice this wavefront works on
+  uint32_t nrt2 = 1;
+  while (nrt2 < nrt && nrt2 < 8u) nrt2 <<= 1;
+  const uint32_t ks = 8u / nrt2;                 // K slices per input tile (1 when nrt >= 8)
+  const uint32_t my_slice = wave / nrt2, my_rt0 = wave % nrt2;   // tiles my_rt0, my_rt0 + 8, ... (ks == 1)
+  const uint32_t slice_len = Kt / ks;            // multiple of 128
+  const uint16_t* W = (const uint16_t*)t.w;
+  const uint32_t frow = lane & 15u, fk = (uint32_t)(lane >> 4) * 8u;   // fragment row / input offset
+  f32x4 acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  if (wait_ev >= 0) {
+    if (wave == 0) poll_event_wave0(a, wait_ev, s_flag, lane);
+    lds_barrier();
+    if (__builtin_amdgcn_readfirstlane(*s_flag) == 0) return false;
+  }
+  trace_mark(a, t, 1);
+  const bool pro_norm = t.flags & TF_PRO_NORM;
+  const uint16_t* gain = (const uint16_t*)t.w2;
+  float ss_row = 0.f;   // this thread's share of sum x^2 of batch row (threadIdx.x % nb)... see below
+  if (t.flags & TF_EPI_RESID) {
+    for (uint32_t i = threadIdx.x; i < nb * ncols; i += kThreads) {
+      uint32_t bb = i / ncols, cc = i % ncols;
+      res_lds[cc * 16 + bb] = ld_act(t.in2 + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc);
+    }
+  }
+  // sum of squares: thread handles pairs of one batch row at a time, rows cycle with the loop;
+  // keep one partial per batch row and thread in registers only for rows it touches: simpler to
+  // accumulate into LDS per wave at the end of each tile
+  float ssacc[16];
+#pragma unroll
+  for (int b = 0; b < 16; ++b) ssacc[b] = 0.f;
+  (void)ss_row;
+
+  const uint32_t ntile = (K + Kt - 1u) / Kt;
+  for (uint32_t tile = 0; tile < ntile; ++tile) {
+    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
+    if (tile > 0) lds_barrier();   // everybody is done reading the previous input tile
+    // ---- stage the input tile: fp32 -> (hi, lo) bf16 planes
+#pragma unroll
+    for (int b = 0; b < 16; ++b) {
+      if ((uint32_t)b < nb) {
+        const float* src = t.in + (size_t)(t.b0 + b) * t.ld_in + k0;
+        for (uint32_t i = threadIdx.x; i < Kt / 2; i += kThreads) {
+          float2 v = make_float2(0.f, 0.f);
+          if (2 * i < klen) {
+            v = ld_act2(src + 2 * i);
+            if (pro_norm) {
+              ssacc[b] = fmaf(v.x, v.x, ssacc[b]);
+              ssacc[b] = fmaf(v.y, v.y, ssacc[b]);
+              const uint32_t g2 = *as_global((const uint32_t*)(gain + k0 + 2 * i));
+              v.x *= bf16_lo(g2);
+              v.y *= bf16_hi(g2);
+            }
+          }
+          const uint16_t h0 = f32_to_bf16(v.x), h1 = f32_to_bf16(v.y);
+          const uint16_t l0 = f32_to_bf16(v.x - bf16_to_f32(h0)), l1 = f32_to_bf16(v.y - bf16_to_f32(h1));
+          *(uint32_t*)(xh + (size_t)b * xstride + 2 * i) = (uint32_t)h0 | ((uint32_t)h1 << 16);
+          *(uint32_t*)(xl + (size_t)b * xstride + 2 * i) = (uint32_t)l0 | ((uint32_t)l1 << 16);
+        }
+      }
+    }
+    lds_barrier();
+    // ---- this wavefront's tiles x its slice of the input tile
+    const uint32_t s_lo = my_slice * slice_len, s_hi = min(s_lo + slice_len, (klen + 31u) & ~31u);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t rt = my_rt0 + (uint32_t)j * 8u;
+      if (rt < nrt && (ks == 1u || j == 0) && s_lo < s_hi) {
+        const uint32_t r = min(rt * 16u + frow, R - 1u);   // rows past the end repeat the last one
+        const uint32_t wrow = gateup ? (t.c0 + (r >> 1) + ((r & 1u) ? t.p0 : 0u)) : t.c0 + r;
+        const uint16_t* wp = W + (size_t)wrow * K + k0 + fk;
+        const uint16_t* bh = xh + (size_t)(frow % nb) * xstride + fk;
+        const uint16_t* bl = xl + (size_t)(frow % nb) * xstride + fk;
+        for (uint32_t kk = s_lo; kk < s_hi; kk += 128) {   // 4 MFMA steps of 32 inputs per round
+          u32x4 wfrag[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const uint32_t k = min(kk + q * 32u, (K - k0 - fk >= 8u ? K - k0 - fk - 8u : 0u));   // stay inside the row
+            wfrag[q] = ld_stream16(wp + k);
+          }
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            if (kk + q * 32u < s_hi) {
+              const u32x4 bhv = *(const u32x4*)(bh + kk + q * 32u), blv = *(const u32x4*)(bl + kk + q * 32u);
+              const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q]);
+              acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bhv), acc[j], 0, 0, 0);
+              acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, blv), acc[j], 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+  }
+  // ---- partial tiles -> LDS.  part[wave][j][row 0..15][col 0..15]
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) part[((wave * 4 + j) * 16 + (lane >> 4) * 4 + i) * 16 + (lane & 15)] = acc[j][i];
+  if (pro_norm) {
+#pragma unroll
+    for (int b = 0; b < 16; ++b) {
+      const float v = wave_sum(ssacc[b]);
+      if (lane == 0) ssq[wave * 16 + b] = v;
+    }
+  }
+  lds_barrier();
+  trace_mark(a, t, 3);
+  // ---- wavefront 0: add the K slices in order, epilogue, outputs, notification
+  if (wave == 0) {
+    float* outp = (t.flags & TF_OUT_LOGITS) ? a.logits : t.out;
+    auto dot_of = [&](uint32_t r, uint32_t bb) {   // ring row r, batch column bb
+      const uint32_t rt = r >> 4, row = r & 15u;
+      float v = 0.f;
+      if (ks == 1u) {
+        v = part[(((rt & 7u) * 4 + (rt >> 3)) * 16 + row) * 16 + bb];
+      } else {
+        for (uint32_t sl = 0; sl < ks; ++sl) v += part[(((sl * nrt2 + rt) * 4) * 16 + row) * 16 + bb];
+      }
+      return v;
+    };
+    for (uint32_t i = lane; i < ncols * nb; i += 64) {
+      const uint32_t cc = i / nb, bb = i % nb;
+      float inv = 1.0f;
+      if (pro_norm) {
+        float ss = 0.f;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) ss += ssq[w * 16 + bb];
+        inv = 1.0f / sqrtf(ss / (float)K + t.f0);
+      }
+      float v;
+      if (gateup) {
+        const float gte = dot_of(2 * cc, bb) * inv, up = dot_of(2 * cc + 1, bb) * inv;
+        v = gte / (1.0f + expf(-gte)) * up;
+      } else {
+        v = dot_of(cc, bb) * inv;
+      }
+      if (t.flags & TF_EPI_RESID) v = res_lds[cc * 16 + bb] + v;
+      st_act(outp + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc, v);
+    }
+    if (MEGA && t.trig_event >= 0) signal_from_wave0(a, t, t.trig_event, lane);
+    trace_mark(a, t, 4);
+  }
+  lds_barrier();   // the partial buffer is reused by the next task
+  return true;
+}
+
 // cos and sin of position * inv_freq[i]: the angle is formed and reduced to [-pi, pi] in double.
 __device__ __forceinline__ void rope_cs(const StepArgs& a, int32_t pos, uint32_t i, float* c, float* s) {
   double ang = (double)pos * as_global(a.g->inv_freq)[i];
@@ -601,14 +786,14 @@ __device__ __forceinline__ float group_sum(float v) {
 // rows [c*len/C, (c+1)*len/C) with len = position + 1, so the last chunk holds the new row.
 // Output per query head of the group: sum_t exp(s_t - m) V_t (D floats), m, l = sum_t exp(s_t - m).
 // Layout of the work: D/8 adjacent lanes share one position (16 bytes of the row each), a
-// wavefront covers 64/(D/8) positions per round, the 8 wavefronts of the workgroup take rounds
-// of 8 x that many positions; kAttnRounds rounds fit in registers and the compiler picks the chunk
-// count so that a chunk never exceeds them.
-// Cache rows of earlier steps are immutable during a step, so the task requests its K and V rows
-// BEFORE it waits for its dependent event; only the query (and the row appended this step)
-// arrive later.  Scores, probabilities and the running sums stay in registers.
-constexpr int kAttnRounds = 8;
-
+// wavefront covers 64/(D/8) positions per round, the wavefronts of the workgroup take rounds of
+// (wavefronts x that many) positions.  Every lane group keeps a running maximum, sum and output
+// per query head (online softmax), so a chunk may be of any length and no barrier is needed until
+// the end, where the lane groups of a wavefront are combined with lane shuffles and the
+// wavefronts through LDS.
+// Cache rows of earlier steps are immutable during a step, so the task requests its first
+// kAttnPre rounds of K and V rows BEFORE it waits for its dependent event; only the query (and the
+// row appended this step) arrive later.  Later rounds are requested a batch at a time.
 template <int D, int GRP>
 __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepArgs& a, float* lds,
                                                   int32_t wait_ev, uint32_t* s_flag) {
@@ -619,7 +804,7 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   float* qs = lds;                       // [grp][d]
   float* wpart = qs + grp * d;           // [NW][grp][d + 2]: partial output, max, sum per wavefront
-  uint32_t* flag = (uint32_t*)(wpart + NW * grp * (d + 2));   // then [16..) the maxima exchange
+  uint32_t* flag = (uint32_t*)(wpart + NW * grp * (d + 2));
   float* outp = t.out + (size_t)b * t.ld_out + t.c0;
   const int32_t pos = a.positions[b];    // written by the host before the launch
   const bool bad_pos = pos < 0 || (uint32_t)pos >= a.g->max_seq;
@@ -631,10 +816,12 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
   const uint32_t sub = lane % LPP, slot = lane / LPP;
   const uint32_t i_first = wave * PPW + slot;
   const uint32_t n_rounds = (n + stride - 1) / stride;
-  // ---- pre-load: K and V rows of earlier steps
-  u32x4 kreg[kAttnRounds], vreg[kAttnRounds];
+  // rounds held in registers at a time: bounded by what the running state of GRP heads leaves
+  constexpr int kAttnPre = GRP <= 4 ? 8 : 4;
+  // ---- pre-load: the first rounds of K and V rows (never the row appended this step)
+  u32x4 kreg[kAttnPre], vreg[kAttnPre];
 #pragma unroll
-  for (int r = 0; r < kAttnRounds; ++r) {
+  for (int r = 0; r < kAttnPre; ++r) {
     const uint32_t i = i_first + r * stride;
     kreg[r] = u32x4{0, 0, 0, 0};
     vreg[r] = u32x4{0, 0, 0, 0};
@@ -645,7 +832,7 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
   }
   if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
   trace_mark(a, t, 1);
-  if (bad_pos || n_rounds > (uint32_t)kAttnRounds) {
+  if (bad_pos) {
     if (threadIdx.x == 0) report(a, DE_BAD_POSITION, b, (uint32_t)pos);
     for (uint32_t i = threadIdx.x; i < per; i += kThreads) st_act(outp + i, ((i % (d + 2)) == d) ? -INFINITY : 0.f);
     return true;
@@ -693,121 +880,109 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
   }
   __syncthreads();
   trace_mark(a, t, 2);
-  // The row appended during this step is read with coherent loads (it was written after the
-  // pre-load, by this or another workgroup); it can only be the last position of the last chunk.
-  if (c == C - 1) {
-    const uint32_t i_new = n - 1;
+  // ---- running softmax per lane group and query head
+  const float inv_sqrt_d = 1.0f / sqrtf((float)d);
+  float q[GRP][8], m[GRP], l[GRP], acc[GRP][8];
 #pragma unroll
-    for (int r = 0; r < kAttnRounds; ++r) {
-      if (i_first + r * stride == i_new) {
-        kreg[r] = ld_row16_coherent(Kb + (size_t)i_new * d + sub * 8);
-        vreg[r] = ld_row16_coherent(Vb + (size_t)i_new * d + sub * 8);
+  for (int j = 0; j < GRP; ++j) {
+    const float4* qp = (const float4*)(qs + j * d + sub * 8);
+    const float4 q0 = qp[0], q1 = qp[1];
+    q[j][0] = q0.x * inv_sqrt_d; q[j][1] = q0.y * inv_sqrt_d; q[j][2] = q0.z * inv_sqrt_d; q[j][3] = q0.w * inv_sqrt_d;
+    q[j][4] = q1.x * inv_sqrt_d; q[j][5] = q1.y * inv_sqrt_d; q[j][6] = q1.z * inv_sqrt_d; q[j][7] = q1.w * inv_sqrt_d;
+    m[j] = -INFINITY;
+    l[j] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[j][e] = 0.f;
+  }
+  const uint32_t i_new = (c == C - 1) ? n - 1 : 0xFFFFFFFFu;   // the row appended this step, if in this chunk
+  for (uint32_t r0 = 0; r0 < n_rounds; r0 += kAttnPre) {
+    if (r0 > 0) {   // request the next batch of rounds
+#pragma unroll
+      for (int r = 0; r < kAttnPre; ++r) {
+        const uint32_t i = i_first + (r0 + r) * stride;
+        if (i < n && i != i_new) {
+          kreg[r] = ld_stream16(Kb + (size_t)i * d + sub * 8);
+          vreg[r] = ld_stream16(Vb + (size_t)i * d + sub * 8);
+        }
       }
     }
-  }
-  // ---- per block of HB heads (bounds the register footprint): scores, softmax statistics and
-  // P.V, all in registers; sreg[r][j] belongs to position i_first + r * stride, head jb + j
-  constexpr int HB = GRP < 4 ? GRP : 4;
-  const float inv_sqrt_d = 1.0f / sqrtf((float)d);
-  float* mxch = wpart + NW * grp * (d + 2) + 16;   // [NW][HB] maxima exchange
-  float m_all[GRP];
-#pragma unroll 1
-  for (int jb = 0; jb < GRP; jb += HB) {
-    float q[HB][8];
 #pragma unroll
-    for (int j = 0; j < HB; ++j) {
-      const float4* qp = (const float4*)(qs + (jb + j) * d + sub * 8);
-      float4 q0 = qp[0], q1 = qp[1];
-      q[j][0] = q0.x; q[j][1] = q0.y; q[j][2] = q0.z; q[j][3] = q0.w;
-      q[j][4] = q1.x; q[j][5] = q1.y; q[j][6] = q1.z; q[j][7] = q1.w;
-    }
-    float sreg[kAttnRounds][HB];
-    float mloc[HB];
-#pragma unroll
-    for (int j = 0; j < HB; ++j) mloc[j] = -INFINITY;
-#pragma unroll
-    for (int r = 0; r < kAttnRounds; ++r) {
-      const bool valid = i_first + r * stride < n;
-      const u32x4 kv = kreg[r];
+    for (int r = 0; r < kAttnPre; ++r) {
+      const uint32_t i = i_first + (r0 + r) * stride;
+      if (i == i_new) {
+        // written after the pre-load, by this or another workgroup: coherent loads
+        kreg[r] = ld_row16_coherent(Kb + (size_t)i * d + sub * 8);
+        vreg[r] = ld_row16_coherent(Vb + (size_t)i * d + sub * 8);
+      }
+      const bool valid = i < n;
+      const u32x4 kv = kreg[r], vv = vreg[r];
       const float k8[8] = {bf16_lo(kv.x), bf16_hi(kv.x), bf16_lo(kv.y), bf16_hi(kv.y),
                            bf16_lo(kv.z), bf16_hi(kv.z), bf16_lo(kv.w), bf16_hi(kv.w)};
-#pragma unroll
-      for (int j = 0; j < HB; ++j) {
-        float sv = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) sv = fmaf(k8[e], q[j][e], sv);
-        sv = group_sum<LPP>(sv) * inv_sqrt_d;
-        sreg[r][j] = valid ? sv : -INFINITY;
-        mloc[j] = fmaxf(mloc[j], sreg[r][j]);
-      }
-    }
-    // chunk maximum per head: across position slots, then across wavefronts
-#pragma unroll
-    for (int j = 0; j < HB; ++j) {
-#pragma unroll
-      for (uint32_t off = LPP; off < 64; off <<= 1) mloc[j] = fmaxf(mloc[j], __shfl_xor(mloc[j], off, 64));
-      if (lane == 0) mxch[wave * HB + j] = mloc[j];
-    }
-    __syncthreads();
-    float m[HB];
-#pragma unroll
-    for (int j = 0; j < HB; ++j) {
-      float v = mxch[j];
-#pragma unroll
-      for (uint32_t w = 1; w < NW; ++w) v = fmaxf(v, mxch[w * HB + j]);
-      m[j] = v;
-      m_all[jb + j] = v;
-    }
-    // ---- probabilities and P.V
-    float acc[HB][8], lsum[HB];
-#pragma unroll
-    for (int j = 0; j < HB; ++j) {
-      lsum[j] = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[j][e] = 0.f;
-    }
-#pragma unroll
-    for (int r = 0; r < kAttnRounds; ++r) {
-      const u32x4 vv = vreg[r];
       const float v8[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
                            bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
 #pragma unroll
-      for (int j = 0; j < HB; ++j) {
-        const float p = (sreg[r][j] == -INFINITY) ? 0.f : expf(sreg[r][j] - m[j]);
-        lsum[j] += p;
+      for (int j = 0; j < GRP; ++j) {
+        float sv = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p, v8[e], acc[j][e]);
+        for (int e = 0; e < 8; ++e) sv = fmaf(k8[e], q[j][e], sv);
+        sv = group_sum<LPP>(sv);
+        if (valid) {
+          if (sv > m[j]) {   // a new maximum (rare after the first positions): rescale the running state
+            const float sc = expf(m[j] - sv);   // exp(-inf) = 0 on the first position
+            l[j] *= sc;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[j][e] *= sc;
+            m[j] = sv;
+          }
+          const float p = expf(sv - m[j]);
+          l[j] += p;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p, v8[e], acc[j][e]);
+        }
       }
     }
-    // reduce over the position slots of the wavefront; wavefront partials go to LDS
-#pragma unroll
-    for (int j = 0; j < HB; ++j) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float v = acc[j][e];
-#pragma unroll
-        for (uint32_t off = LPP; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
-        if (slot == 0) wpart[((size_t)wave * grp + jb + j) * (d + 2) + sub * 8 + e] = v;
-      }
-      float lv = lsum[j];   // every lane of a position group holds the same p: count each once
-#pragma unroll
-      for (uint32_t off = LPP; off < 64; off <<= 1) lv += __shfl_xor(lv, off, 64);
-      if (lane == 0) wpart[((size_t)wave * grp + jb + j) * (d + 2) + d + 1] = lv;
-    }
-    __syncthreads();   // also protects mxch before the next block
   }
+  // ---- combine the lane groups of the wavefront, then the wavefronts
+#pragma unroll
+  for (int j = 0; j < GRP; ++j) {
+#pragma unroll
+    for (uint32_t off = LPP; off < 64; off <<= 1) {
+      const float mo = __shfl_xor(m[j], off, 64), lo2 = __shfl_xor(l[j], off, 64);
+      const float mn = fmaxf(m[j], mo);
+      const float s0 = (m[j] == -INFINITY) ? 0.f : expf(m[j] - mn), s1 = (mo == -INFINITY) ? 0.f : expf(mo - mn);
+      l[j] = l[j] * s0 + lo2 * s1;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[j][e] = acc[j][e] * s0 + __shfl_xor(acc[j][e], off, 64) * s1;
+      m[j] = mn;
+    }
+    if (slot == 0) {
+      float* wp = wpart + ((size_t)wave * grp + j) * (d + 2);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) wp[sub * 8 + e] = acc[j][e];
+      if (sub == 0) {
+        wp[d] = m[j];
+        wp[d + 1] = l[j];
+      }
+    }
+  }
+  __syncthreads();
   trace_mark(a, t, 10);
   for (uint32_t i = threadIdx.x; i < grp * (d + 2); i += kThreads) {
     const uint32_t j = i / (d + 2), dim = i % (d + 2);
+    float M = -INFINITY;
+#pragma unroll
+    for (uint32_t w = 0; w < NW; ++w) M = fmaxf(M, wpart[((size_t)w * grp + j) * (d + 2) + d]);
     float sv;
     if (dim == d) {
-      sv = m_all[0];
-#pragma unroll
-      for (int jj = 1; jj < GRP; ++jj) sv = (j == (uint32_t)jj) ? m_all[jj] : sv;
+      sv = M;
     } else {
       sv = 0.f;
+      const uint32_t src = (dim == d + 1) ? d + 1 : dim;
 #pragma unroll
-      for (uint32_t w = 0; w < NW; ++w) sv += wpart[((size_t)w * grp + j) * (d + 2) + dim];
+      for (uint32_t w = 0; w < NW; ++w) {
+        const float mw = wpart[((size_t)w * grp + j) * (d + 2) + d];
+        if (mw != -INFINITY) sv += wpart[((size_t)w * grp + j) * (d + 2) + src] * expf(mw - M);
+      }
     }
     st_act(outp + i, sv);
   }
@@ -912,12 +1087,13 @@ __device__ __forceinline__ void body_swiglu(const TaskDesc& t) {
 template <int NB, bool MEGA>
 __device__ __forceinline__ bool run_linear(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
                                            uint32_t* s_flag) {
+  if (NB == 8) return linear_task_mfma<MEGA>(t, a, lds, wait_ev, s_flag);   // batch class 5..16: matrix cores
   if (NB != 0) return linear_task<(NB ? NB : 1), MEGA>(t, a, lds, wait_ev, s_flag);
   const uint32_t nb = t.b1 - t.b0;
   if (nb == 1) return linear_task<1, MEGA>(t, a, lds, wait_ev, s_flag);
   if (nb == 2) return linear_task<2, MEGA>(t, a, lds, wait_ev, s_flag);
   if (nb <= 4) return linear_task<4, MEGA>(t, a, lds, wait_ev, s_flag);
-  return linear_task<8, MEGA>(t, a, lds, wait_ev, s_flag);
+  return linear_task_mfma<MEGA>(t, a, lds, wait_ev, s_flag);
 }
 
 template <int D, int GRP, int NB>
@@ -1089,7 +1265,7 @@ constexpr uint32_t kLdsCtrlFloats = 16;
 // force spills of registers that have loads in flight.
 // Returns false when the step is being aborted.
 template <int D, int GRP, int NB, bool MEGA>
-__device__ __noinline__ bool run_other_task(StepArgs a, uint32_t task_index, bool skip_wait) {
+__device__ __forceinline__ bool run_other_task(StepArgs a, uint32_t task_index, bool skip_wait) {
   extern __shared__ __align__(16) float dyn_lds[];
   float* lds = dyn_lds + kLdsCtrlFloats;
   uint32_t* s_flag = (uint32_t*)dyn_lds;
@@ -1316,7 +1492,7 @@ static const KernelVariant kVariants[] = {
     MPK_VARIANT(128, 4, 8), MPK_VARIANT(0, 0, 0),
 };
 static const KernelVariant* pick_variant(uint32_t d, uint32_t grp, uint32_t batch) {
-  int nb = batch == 1 ? 1 : (batch > 4 && batch <= 8 ? 8 : -1);
+  int nb = batch == 1 ? 1 : (batch > 4 && batch <= 16 ? 8 : -1);
   const int n = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
   for (int i = 0; i < n; ++i)
     if (kVariants[i].d == (int)d && kVariants[i].grp == (int)grp && kVariants[i].nb == nb) return &kVariants[i];

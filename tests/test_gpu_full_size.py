@@ -101,3 +101,9 @@ def test_c2_full_size_per_operator_launch():
 def test_c5_70b_shaped_16_greedy_steps_mega_kernel():
     """141 GB of weights resident in HBM (generated on the device), KV 2048, 16 steps."""
     _check_against_fixture("C5", BENCH_OPTS)
+
+
+def test_c3_llama3_8b_shaped_batch8_32_greedy_steps_mega_kernel():
+    """Batch 8 with per-sequence KV lengths in [512, 4096]: the matrix-core linear body at the
+    benchmark's shapes (K = 4096 and 14336, 501-row LM-head tiles)."""
+    _check_against_fixture("C3", BENCH_OPTS)

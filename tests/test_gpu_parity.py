@@ -95,6 +95,35 @@ def test_small_batch_and_ragged_positions(opts):
     gpu.close()
 
 
+@pytest.mark.parametrize("batch,opts", [
+    (8, dict(fusion=31, transitive_reduction=1)),
+    (8, dict(fusion=0)),
+    (8, dict(fusion=31, transitive_reduction=1, launch_mode=1)),
+    (8, dict(fusion=7, transitive_reduction=1, n_workers=37)),
+    (8, dict(fusion=31, transitive_reduction=1, n_sched_wgs=2)),
+    (5, dict(fusion=31, transitive_reduction=1)),
+    (16, dict(fusion=31, transitive_reduction=1, tiles_lm_head=64)),
+])
+def test_matrix_core_linear_body_batch_5_to_16(batch, opts):
+    """Batch 5..16 runs the linear operators on the matrix cores (activations split into two
+    bf16 planes): ragged KV lengths, K that is not a multiple of 32 (ffn 688), K-sliced and
+    row-tiled tasks (LM head), several steps so that appended rows are read back."""
+    s = G.small_variant("C1", batch=batch, n_layers=2, max_seq=192)
+    tok = G.tokens(2, s)
+    pos = np.array([(37 * b + 5) % 150 for b in range(batch)], np.int32)
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 2), "f32")
+    gpu = GpuDecoder(s, 2, **opts)
+    for step in range(3):
+        want = ref.step(tok, pos)
+        got = gpu.step(tok, pos)
+        assert np.isfinite(got).all()
+        assert rel_err(got, want) < TOL, step
+        assert np.abs(got - want).max() / np.abs(want).max() < 1e-4, step
+        assert got.argmax(-1).tolist() == want.argmax(-1).tolist(), step
+        tok, pos = want.argmax(-1).astype(np.int32), pos + 1
+    gpu.close()
+
+
 def test_greedy_32_steps_free_running_and_teacher_forced():
     s = G.small_variant("C1", max_seq=192)
     tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
