@@ -1,5 +1,6 @@
 #!/usr/bin/env python3
-"""Decode benchmark on one MI355X: the Qwen3-8B-shaped config, batch 1, KV 1024, greedy steps.
+"""Decode benchmark on one MI355X.  Default workload: the Qwen3-8B-shaped config, batch 1, KV
+1024, greedy steps (--config C3: Llama-3-8B-shaped, batch 8, ragged KV; --config C5: 70B-shaped).
 
 A "step" is one decode step through the persistent mega-kernel (mpk_decode_step) followed by the
 greedy token feedback (arg max on the device, no host sync).  Prints ONE JSON line.
@@ -146,7 +147,7 @@ def main():
     kern_avg_ms = sum(kern_ms) / len(kern_ms)
     achieved = bytes_step / (kern_avg_ms * 1e-3) / 1e9
     out = {
-        "metric": "decode_ms_per_token_batch1", "value": ms_per_step / shape.batch,
+        "metric": f"decode_ms_per_token_batch{shape.batch}", "value": ms_per_step / shape.batch,
         "unit": "ms/token", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 weights, fp32 activations/accumulation",
@@ -154,7 +155,8 @@ def main():
         "config": {"workload": f"{shape.name}: {shape.n_layers} layers, hidden {shape.hidden}, "
                                f"{shape.n_q_heads}q/{shape.n_kv_heads}kv heads, ffn {shape.ffn}, "
                                f"vocab {shape.vocab}, batch {shape.batch}, KV "
-                               f"{shape.kv_len_lo} prior positions, greedy decode",
+                               f"{shape.kv_len_lo}" + (f"..{shape.kv_len_hi}" if shape.kv_len_hi != shape.kv_len_lo else "")
+                               + " prior positions, greedy decode",
                    "launch": "persistent mega-kernel", "fusion": args.fusion,
                    "n_workers": stats["n_workers"], "tasks": stats["n_tasks"],
                    "events": stats["n_events"]},

@@ -781,16 +781,23 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
     rows_max = std::max(rows_max, per * ((op.flags & TF_GATEUP) ? 2u : 1u));
   }
   g.lin_rows_max = rows_max;
+  uint32_t res_rows = 0;   // columns of the largest task that adds a residual
+  for (auto& op : g.ops) {
+    if ((op.kind != MPK_OP_LINEAR && op.kind != MPK_OP_GATEUP) || !(op.flags & TF_EPI_RESID)) continue;
+    uint32_t nu = op.cols / op.unit;
+    res_rows = std::max(res_rows, (nu + op.tc - 1) / op.tc * op.unit);
+  }
+  g.lin_res_rows_max = res_rows;
   for (auto& op : g.ops) {
     size_t f = 0;
     if (op.kind == MPK_OP_LINEAR || op.kind == MPK_OP_GATEUP) {
       if (c.batch <= 4) {
         f = (size_t)nb * ((op.K + 4095u) / 4096u * 4096u) + 2 * (size_t)rows_max * nb + 8 * nb;
       } else {
-        // matrix-core body: two bf16 planes of one input tile | per-wavefront partial tiles |
-        // residual slice | sums of squares
+        // matrix-core body: two buffers of two bf16 planes of one input tile (reused for the
+        // per-wavefront partial tiles) | residual slice | sums of squares
         const size_t kt = c.batch <= 8 ? 2048 : 1024;
-        f = (size_t)c.batch * (kt + 8) + 8 * 4 * 256 + (size_t)rows_max * 16 + 8 * 16;
+        f = std::max<size_t>(2 * (size_t)c.batch * (kt + 8), 8 * 4 * 256) + (size_t)res_rows * 16 + 8 * 16;
       }
     }
     else if (op.kind == MPK_OP_ATTN_PARTIAL)

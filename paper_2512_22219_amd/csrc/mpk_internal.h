@@ -127,6 +127,7 @@ struct HostGraph {
   uint32_t n_group_counters = 0;   // per (layer, sequence, KV head) arrival counters
   uint32_t n_hier_events = 0;
   uint32_t lin_rows_max = 0;       // largest weight-row count of one linear task (gate/up pairs twice)
+  uint32_t lin_res_rows_max = 0;   // largest column count of a linear task with a residual epilogue
   std::vector<double> inv_freq;    // RoPE frequencies theta^(-2i/d), i < d/2
   mpk_stats stats{};
 };

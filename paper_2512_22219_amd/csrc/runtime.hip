@@ -49,6 +49,7 @@ struct GraphConst {
   uint32_t n_workers;
   uint32_t vocab, max_seq, n_q, n_kv, head_dim, batch;
   uint32_t lin_rows_max;     // largest number of weight rows (gate/up pairs count twice) of a linear task
+  uint32_t lin_res_rows_max; // largest number of columns of a linear task that adds a residual
   // just-in-time launch (Section 5.2): scheduler event queues and worker task queues.  Entries
   // are 64-bit (ticket + 1) << 32 | id with tickets that only grow, so a slot is valid exactly
   // when it carries the ticket its reader expects; tails sit on their own 256-byte lines.
@@ -547,8 +548,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint32_t mfma_ktile(uint32_t nb) { return nb <= 8 ? 2048u : 1024u; }
 
-// LDS (bytes from the task area): xh [nb][Kt + 8] bf16 | xl same | part [8 waves][4][256] f32 |
-// res [rows_max][16] f32 | ssq [8][16] f32
+// LDS (from the task area): xh [2][nb][Kt + 8] bf16 | xl same | res [residual columns][16] f32 |
+// ssq [8][16] f32; the per-wavefront partial tiles part [8][4][256] f32 reuse the input buffers
+// once the last input tile has been consumed.
 template <bool MEGA>
 __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
                                                  uint32_t* s_flag) {
@@ -559,11 +561,12 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
   const uint32_t R = ncols << gateup;            // weight rows of the task ("ring rows")
   const uint32_t nrt = (R + 15u) / 16u;          // 16-row tiles
   const uint32_t Kt = mfma_ktile(nb), xstride = Kt + 8u;
-  uint16_t* xh = (uint16_t*)lds;
-  uint16_t* xl = xh + (size_t)nb * xstride;
-  float* part = (float*)(xl + (size_t)nb * xstride);       // [8][4][256]
-  float* res_lds = part + 8 * 4 * 256;                      // [rows_max][16]
-  float* ssq = res_lds + (size_t)a.g->lin_rows_max * 16;    // [8][16]
+  const uint32_t xplane = nb * xstride;                     // one plane of one buffer, in bf16
+  uint16_t* xh = (uint16_t*)lds;                            // [2 buffers][nb][xstride]
+  uint16_t* xl = xh + 2 * (size_t)xplane;
+  float* part = lds;                                        // [8][4][256], reuses the input buffers at the end
+  float* res_lds = (float*)(xl + 2 * (size_t)xplane);       // [rows_max][16]
+  float* ssq = res_lds + (size_t)a.g->lin_res_rows_max * 16;   // [8][16]
   // which tiles and which K slice this wavefront works on
   uint32_t nrt2 = 1;
   while (nrt2 < nrt && nrt2 < 8u) nrt2 <<= 1;
@@ -575,6 +578,26 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
   f32x4 acc[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // Weight fragments are requested a round at a time: kMfmaRound steps of 32 inputs, 16 bytes per
+  // lane and step (16 KB per wavefront in flight), then multiplied as they arrive.  The first
+  // round is requested before the event wait (cross-task pre-loading, Section 5.3).
+  constexpr int kMfmaRound = 16;
+  u32x4 wfrag[kMfmaRound];
+  auto row_ptr = [&](uint32_t rt) {
+    const uint32_t r = min(rt * 16u + frow, R - 1u);   // rows past the end repeat the last one
+    const uint32_t wrow = gateup ? (t.c0 + (r >> 1) + ((r & 1u) ? t.p0 : 0u)) : t.c0 + r;
+    return W + (size_t)wrow * K + fk;
+  };
+  auto request = [&](const uint16_t* wp, uint32_t k0, uint32_t kk) {   // inputs k0 + kk + 32 q + fk .. + 7
+#pragma unroll
+    for (int q = 0; q < kMfmaRound; ++q) {
+      const uint32_t k = min(k0 + kk + q * 32u, K - fk - 8u);   // stay inside the row
+      wfrag[q] = ld_stream16(wp + k);
+    }
+  };
+  const bool has_work = my_rt0 < nrt;
+  if (has_work) request(row_ptr(my_rt0), 0u, my_slice * slice_len);
 
   if (wait_ev >= 0) {
     if (wave == 0) poll_event_wave0(a, wait_ev, s_flag, lane);
@@ -599,55 +622,68 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
   for (int b = 0; b < 16; ++b) ssacc[b] = 0.f;
   (void)ss_row;
 
+  // The input tile of 2048 (1024) inputs x nb rows is dealt to the threads in pairs, round-robin:
+  // at most 16 pairs per thread.  A tile is requested (coherent loads into registers) while the
+  // previous tile is being multiplied, and converted into the other LDS buffer afterwards.
   const uint32_t ntile = (K + Kt - 1u) / Kt;
-  for (uint32_t tile = 0; tile < ntile; ++tile) {
+  const uint32_t half = Kt / 2, npairs = nb * half;
+  float2 sv[16];
+  auto stage_issue = [&](uint32_t tile) {
     const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
-    if (tile > 0) lds_barrier();   // everybody is done reading the previous input tile
-    // ---- stage the input tile: fp32 -> (hi, lo) bf16 planes
 #pragma unroll
-    for (int b = 0; b < 16; ++b) {
-      if ((uint32_t)b < nb) {
-        const float* src = t.in + (size_t)(t.b0 + b) * t.ld_in + k0;
-        for (uint32_t i = threadIdx.x; i < Kt / 2; i += kThreads) {
-          float2 v = make_float2(0.f, 0.f);
-          if (2 * i < klen) {
-            v = ld_act2(src + 2 * i);
-            if (pro_norm) {
-              ssacc[b] = fmaf(v.x, v.x, ssacc[b]);
-              ssacc[b] = fmaf(v.y, v.y, ssacc[b]);
-              const uint32_t g2 = *as_global((const uint32_t*)(gain + k0 + 2 * i));
-              v.x *= bf16_lo(g2);
-              v.y *= bf16_hi(g2);
-            }
-          }
-          const uint16_t h0 = f32_to_bf16(v.x), h1 = f32_to_bf16(v.y);
-          const uint16_t l0 = f32_to_bf16(v.x - bf16_to_f32(h0)), l1 = f32_to_bf16(v.y - bf16_to_f32(h1));
-          *(uint32_t*)(xh + (size_t)b * xstride + 2 * i) = (uint32_t)h0 | ((uint32_t)h1 << 16);
-          *(uint32_t*)(xl + (size_t)b * xstride + 2 * i) = (uint32_t)l0 | ((uint32_t)l1 << 16);
+    for (int q = 0; q < 16; ++q) {
+      const uint32_t p = q * kThreads + threadIdx.x;
+      const uint32_t b = p / half, i = p - b * half;
+      sv[q] = make_float2(0.f, 0.f);
+      if (p < npairs && 2 * i < klen) sv[q] = ld_act2(t.in + (size_t)(t.b0 + b) * t.ld_in + k0 + 2 * i);
+    }
+  };
+  auto stage_write = [&](uint32_t tile) {
+    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
+    uint16_t* dh = xh + (size_t)(tile & 1u) * xplane;
+    uint16_t* dl = xl + (size_t)(tile & 1u) * xplane;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const uint32_t p = q * kThreads + threadIdx.x;
+      if (p < npairs) {
+        const uint32_t b = p / half, i = p - b * half;
+        float2 w2 = sv[q];
+        if (pro_norm && 2 * i < klen) {
+          const float sq = fmaf(w2.x, w2.x, w2.y * w2.y);
+#pragma unroll
+          for (int bb = 0; bb < 16; ++bb) ssacc[bb] += (b == (uint32_t)bb) ? sq : 0.f;
+          const uint32_t g2 = *as_global((const uint32_t*)(gain + k0 + 2 * i));
+          w2.x *= bf16_lo(g2);
+          w2.y *= bf16_hi(g2);
         }
+        const uint16_t h0 = f32_to_bf16(w2.x), h1 = f32_to_bf16(w2.y);
+        const uint16_t l0 = f32_to_bf16(w2.x - bf16_to_f32(h0)), l1 = f32_to_bf16(w2.y - bf16_to_f32(h1));
+        *(uint32_t*)(dh + (size_t)b * xstride + 2 * i) = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        *(uint32_t*)(dl + (size_t)b * xstride + 2 * i) = (uint32_t)l0 | ((uint32_t)l1 << 16);
       }
     }
-    lds_barrier();
+  };
+  stage_issue(0);
+  stage_write(0);
+  lds_barrier();
+  for (uint32_t tile = 0; tile < ntile; ++tile) {
+    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
+    if (tile + 1 < ntile) stage_issue(tile + 1);   // in flight during this tile's arithmetic
+    const uint16_t* ch = xh + (size_t)(tile & 1u) * xplane;
+    const uint16_t* cl = xl + (size_t)(tile & 1u) * xplane;
     // ---- this wavefront's tiles x its slice of the input tile
     const uint32_t s_lo = my_slice * slice_len, s_hi = min(s_lo + slice_len, (klen + 31u) & ~31u);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const uint32_t rt = my_rt0 + (uint32_t)j * 8u;
       if (rt < nrt && (ks == 1u || j == 0) && s_lo < s_hi) {
-        const uint32_t r = min(rt * 16u + frow, R - 1u);   // rows past the end repeat the last one
-        const uint32_t wrow = gateup ? (t.c0 + (r >> 1) + ((r & 1u) ? t.p0 : 0u)) : t.c0 + r;
-        const uint16_t* wp = W + (size_t)wrow * K + k0 + fk;
-        const uint16_t* bh = xh + (size_t)(frow % nb) * xstride + fk;
-        const uint16_t* bl = xl + (size_t)(frow % nb) * xstride + fk;
-        for (uint32_t kk = s_lo; kk < s_hi; kk += 128) {   // 4 MFMA steps of 32 inputs per round
-          u32x4 wfrag[4];
+        const uint16_t* wp = row_ptr(rt);
+        const uint16_t* bh = ch + (size_t)(frow % nb) * xstride + fk;
+        const uint16_t* bl = cl + (size_t)(frow % nb) * xstride + fk;
+        for (uint32_t kk = s_lo; kk < s_hi; kk += 32u * kMfmaRound) {
+          if (!(tile == 0 && j == 0 && kk == s_lo)) request(wp, k0, kk);   // the first round is already under way
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const uint32_t k = min(kk + q * 32u, (K - k0 - fk >= 8u ? K - k0 - fk - 8u : 0u));   // stay inside the row
-            wfrag[q] = ld_stream16(wp + k);
-          }
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
+          for (int q = 0; q < kMfmaRound; ++q) {
             if (kk + q * 32u < s_hi) {
               const u32x4 bhv = *(const u32x4*)(bh + kk + q * 32u), blv = *(const u32x4*)(bl + kk + q * 32u);
               const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q]);
@@ -658,6 +694,8 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
         }
       }
     }
+    if (tile + 1 < ntile) stage_write(tile + 1);   // into the other buffer: nobody reads it now
+    lds_barrier();
   }
   // ---- partial tiles -> LDS.  part[wave][j][row 0..15][col 0..15]
 #pragma unroll
@@ -1719,7 +1757,7 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
     c.n_workers = h.opt.n_workers;
     c.vocab = h.cfg.vocab; c.max_seq = h.cfg.max_seq; c.n_q = h.cfg.n_q_heads;
     c.n_kv = h.cfg.n_kv_heads; c.head_dim = h.cfg.head_dim; c.batch = h.cfg.batch;
-    c.lin_rows_max = h.lin_rows_max;
+    c.lin_rows_max = h.lin_rows_max; c.lin_res_rows_max = h.lin_res_rows_max;
     c.n_sched = g->n_sched; c.evq_cap = g->evq_cap; c.wq_cap = g->wq_cap;
     c.evq_buf = g->d_evq_buf; c.evq_tail = g->d_evq_tail; c.sched_state = g->d_sched_state;
     c.sched_nev = g->d_sched_nev; c.wq_buf = g->d_wq_buf; c.wq_tail = g->d_wq_tail; c.wq_head = g->d_wq_head;
