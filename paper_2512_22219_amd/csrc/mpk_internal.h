@@ -68,10 +68,13 @@ struct EventDesc {   // paper Section 4.1 "tGraph linearization" / Fig. 4(f)
 };
 static_assert(sizeof(EventDesc) == 64, "EventDesc is 64 bytes");
 constexpr uint32_t EV_JIT = 1, EV_HIER = 2;
-// A hierarchical event owns 17 words, each on its own 256-byte line: the top counter, 8 group
-// counters and 8 ready flags (one per worker group).  256 same-address atomics plus 256 pollers on
-// one line cost about 4 us per hop on this GPU; arrival by group and one flag line per 32
-// pollers brings that to about 2 us.
+// A hierarchical event owns 17 words, each on its own 256-byte line: a top counter (used only
+// when a scheduler has to learn which arrival was the last), 8 producer-group counters and 8
+// poller words (one per worker group).  The last arrival of a producer group adds one to every
+// poller word; a poller waits until its word has counted all producer groups.  256 same-address
+// atomics plus 256 pollers on one line cost about 4 us per hop on this GPU; arrival by group and
+// one word per 32 pollers brings that to about 2 us, and no arrival waits for more than one
+// atomic to return.
 constexpr uint32_t kHierStrideWords = 64, kHierWordsPerEvent = 17 * kHierStrideWords;
 constexpr uint32_t kHierMinRequired = 48;
 

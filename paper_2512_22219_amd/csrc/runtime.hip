@@ -73,6 +73,14 @@ struct GraphConst {
 #define MPK_CONST __attribute__((address_space(4)))
 struct StepArgs {
   const MPK_CONST GraphConst* g;
+  // what every wait and notification needs, by value: kernel arguments are in scalar registers
+  // when the kernel starts, a field behind `g` costs a memory round trip on the critical path
+  const TaskDesc* tasks;
+  const EventDesc* events;
+  uint32_t* counters;
+  uint32_t* hier;
+  uint64_t* trace;
+  uint32_t n_sched;
   const int32_t* token_ids;
   const int32_t* positions;
   float* logits;
@@ -107,12 +115,12 @@ __device__ __forceinline__ T ld_const_record(const T* p) {   // sizeof(T) a mult
   for (unsigned i = 0; i < sizeof(T) / 16; ++i) u.v[i] = src[i];
   return u.rec;
 }
-__device__ __forceinline__ TaskDesc ld_task(const StepArgs& a, uint32_t i) { return ld_const_record(a.g->tasks + i); }
+__device__ __forceinline__ TaskDesc ld_task(const StepArgs& a, uint32_t i) { return ld_const_record(a.tasks + i); }
 __device__ __forceinline__ uint32_t ld_u32c(const uint32_t* p) { return *(const MPK_CONST uint32_t*)p; }
 
 constexpr int kTraceSlots = 12;
 __device__ __forceinline__ void trace_mark(const StepArgs& a, const TaskDesc& t, int slot) {
-  if (a.g->trace && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + slot] = wall_clock64();
+  if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)t.pad * kTraceSlots + slot] = wall_clock64();
 }
 
 enum DevErr : uint32_t { DE_NONE = 0, DE_TIMEOUT = 1, DE_BAD_POSITION = 2, DE_BAD_TOKEN = 3 };
@@ -820,6 +828,272 @@ __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
+// T4, short chunks: the same task when a chunk never exceeds kAttnRounds rounds (8 x 32 = 256 cache
+// positions at head_dim 128): all of its K and V rows are requested before the event wait and
+// stay in registers, scores are formed once, one chunk-wide maximum, one exp per score.  Fewer
+// instructions than the running-softmax body below; the decoder at batch 1 spends its attention
+// phase on latency, not bandwidth, so that is what counts there.
+// Layout of the work: D/8 adjacent lanes share one position (16 bytes of the row each), a
+// wavefront covers 64/(D/8) positions per round, the 8 wavefronts of the workgroup take rounds
+// of 8 x that many positions; kAttnRounds rounds fit in registers and the compiler picks the chunk
+// count so that a chunk never exceeds them.
+// Cache rows of earlier steps are immutable during a step, so the task requests its K and V rows
+// BEFORE it waits for its dependent event; only the query (and the row appended this step)
+// arrive later.  Scores, probabilities and the running sums stay in registers.
+constexpr int kAttnRounds = 8;
+
+template <int D, int GRP>
+__device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const StepArgs& a, float* lds,
+                                                  int32_t wait_ev, uint32_t* s_flag) {
+  constexpr uint32_t d = D, grp = GRP, LPP = D / 8, PPW = 64 / LPP, NW = kThreads / 64;
+  constexpr uint32_t stride = NW * PPW, per = grp * (d + 2);
+  const uint32_t nq = a.g->n_q, nkv = a.g->n_kv, C = t.p1;
+  const uint32_t b = t.b0, u = t.c0 / per, g = u / C, c = u % C;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  float* qs = lds;                       // [grp][d]
+  float* wpart = qs + grp * d;           // [NW][grp][d + 2]: partial output, max, sum per wavefront
+  uint32_t* flag = (uint32_t*)(wpart + NW * grp * (d + 2));   // then [16..) the maxima exchange
+  float* outp = t.out + (size_t)b * t.ld_out + t.c0;
+  const int32_t pos = a.positions[b];    // written by the host before the launch
+  const bool bad_pos = pos < 0 || (uint32_t)pos >= a.g->max_seq;
+  const uint32_t len = bad_pos ? 0u : (uint32_t)pos + 1;
+  const uint32_t t0 = (uint32_t)((uint64_t)c * len / C), t1 = (uint32_t)((uint64_t)(c + 1) * len / C);
+  const uint32_t n = t1 - t0;
+  const uint16_t* Kb = (const uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.g->max_seq + t0) * d;
+  const uint16_t* Vb = (const uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.g->max_seq + t0) * d;
+  const uint32_t sub = lane % LPP, slot = lane / LPP;
+  const uint32_t i_first = wave * PPW + slot;
+  const uint32_t n_rounds = (n + stride - 1) / stride;
+  // ---- pre-load: K and V rows of earlier steps
+  u32x4 kreg[kAttnRounds], vreg[kAttnRounds];
+#pragma unroll
+  for (int r = 0; r < kAttnRounds; ++r) {
+    const uint32_t i = i_first + r * stride;
+    kreg[r] = u32x4{0, 0, 0, 0};
+    vreg[r] = u32x4{0, 0, 0, 0};
+    if (i < n && t0 + i != (uint32_t)pos) {
+      kreg[r] = ld_stream16(Kb + (size_t)i * d + sub * 8);
+      vreg[r] = ld_stream16(Vb + (size_t)i * d + sub * 8);
+    }
+  }
+  if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
+  trace_mark(a, t, 1);
+  if (bad_pos || n_rounds > (uint32_t)kAttnRounds) {
+    if (threadIdx.x == 0) report(a, DE_BAD_POSITION, b, (uint32_t)pos);
+    for (uint32_t i = threadIdx.x; i < per; i += kThreads) st_act(outp + i, ((i % (d + 2)) == d) ? -INFINITY : 0.f);
+    return true;
+  }
+  const float* qsrc = t.in + (size_t)b * t.ld_in + (size_t)g * grp * d;
+  if (t.flags & TF_ROPE_FUSED) {
+    // the input is the raw QKV projection: rotate the group's query heads here; the task of the
+    // last chunk also rotates this step's key, and appends key and value to the cache
+    constexpr uint32_t half = d / 2;
+    for (uint32_t i = threadIdx.x; i < grp * half; i += kThreads) {
+      uint32_t j = i / half, e = i % half;
+      float u0 = ld_act(qsrc + j * d + e), u1 = ld_act(qsrc + j * d + e + half), cs, sn;
+      rope_cs(a, pos, e, &cs, &sn);
+      qs[j * d + e] = u0 * cs - u1 * sn;
+      qs[j * d + e + half] = u1 * cs + u0 * sn;
+    }
+    if (c == C - 1) {
+      const float* ksrc = t.in + (size_t)b * t.ld_in + (size_t)(nq + g) * d;
+      const float* vsrc = t.in + (size_t)b * t.ld_in + (size_t)(nq + nkv + g) * d;
+      uint16_t* krow = (uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
+      uint16_t* vrow = (uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
+      // threads from the top of the workgroup, so that they do not also rotate query pairs
+      for (uint32_t i = kThreads - 1 - threadIdx.x; i < half / 2 + half; i += kThreads) {
+        if (i < half / 2) {   // two adjacent rotation pairs of the key
+          uint32_t e = 2 * i;
+          float2 lo = ld_act2(ksrc + e), hi = ld_act2(ksrc + e + half);
+          float c0, s0, c1, s1;
+          rope_cs(a, pos, e, &c0, &s0);
+          rope_cs(a, pos, e + 1, &c1, &s1);
+          float r0 = lo.x * c0 - hi.x * s0, r1 = lo.y * c1 - hi.y * s1;
+          float r2 = hi.x * c0 + lo.x * s0, r3 = hi.y * c1 + lo.y * s1;
+          st_act_u32((uint32_t*)(krow + e), (uint32_t)f32_to_bf16(r0) | ((uint32_t)f32_to_bf16(r1) << 16));
+          st_act_u32((uint32_t*)(krow + e + half), (uint32_t)f32_to_bf16(r2) | ((uint32_t)f32_to_bf16(r3) << 16));
+        } else {              // two adjacent value elements
+          uint32_t e = 2 * (i - half / 2);
+          float2 v2 = ld_act2(vsrc + e);
+          st_act_u32((uint32_t*)(vrow + e), (uint32_t)f32_to_bf16(v2.x) | ((uint32_t)f32_to_bf16(v2.y) << 16));
+        }
+      }
+      // the appended row is read back below with coherent loads: the stores must have completed
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+  } else {
+    for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) qs[i] = ld_act(qsrc + i);
+  }
+  __syncthreads();
+  trace_mark(a, t, 2);
+  // The row appended during this step is read with coherent loads (it was written after the
+  // pre-load, by this or another workgroup); it can only be the last position of the last chunk.
+  if (c == C - 1) {
+    const uint32_t i_new = n - 1;
+#pragma unroll
+    for (int r = 0; r < kAttnRounds; ++r) {
+      if (i_first + r * stride == i_new) {
+        kreg[r] = ld_row16_coherent(Kb + (size_t)i_new * d + sub * 8);
+        vreg[r] = ld_row16_coherent(Vb + (size_t)i_new * d + sub * 8);
+      }
+    }
+  }
+  // ---- per block of HB heads (bounds the register footprint): scores, softmax statistics and
+  // P.V, all in registers; sreg[r][j] belongs to position i_first + r * stride, head jb + j
+  constexpr int HB = GRP < 4 ? GRP : 4;
+  const float inv_sqrt_d = 1.0f / sqrtf((float)d);
+  float* mxch = wpart + NW * grp * (d + 2) + 16;   // [NW][HB] maxima exchange
+  float m_all[GRP];
+#pragma unroll 1
+  for (int jb = 0; jb < GRP; jb += HB) {
+    float q[HB][8];
+#pragma unroll
+    for (int j = 0; j < HB; ++j) {
+      const float4* qp = (const float4*)(qs + (jb + j) * d + sub * 8);
+      float4 q0 = qp[0], q1 = qp[1];
+      q[j][0] = q0.x; q[j][1] = q0.y; q[j][2] = q0.z; q[j][3] = q0.w;
+      q[j][4] = q1.x; q[j][5] = q1.y; q[j][6] = q1.z; q[j][7] = q1.w;
+    }
+    float sreg[kAttnRounds][HB];
+    float mloc[HB];
+#pragma unroll
+    for (int j = 0; j < HB; ++j) mloc[j] = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < kAttnRounds; ++r) {
+      const bool valid = i_first + r * stride < n;
+      const u32x4 kv = kreg[r];
+      const float k8[8] = {bf16_lo(kv.x), bf16_hi(kv.x), bf16_lo(kv.y), bf16_hi(kv.y),
+                           bf16_lo(kv.z), bf16_hi(kv.z), bf16_lo(kv.w), bf16_hi(kv.w)};
+#pragma unroll
+      for (int j = 0; j < HB; ++j) {
+        float sv = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sv = fmaf(k8[e], q[j][e], sv);
+        sv = group_sum<LPP>(sv) * inv_sqrt_d;
+        sreg[r][j] = valid ? sv : -INFINITY;
+        mloc[j] = fmaxf(mloc[j], sreg[r][j]);
+      }
+    }
+    // chunk maximum per head: across position slots, then across wavefronts
+#pragma unroll
+    for (int j = 0; j < HB; ++j) {
+#pragma unroll
+      for (uint32_t off = LPP; off < 64; off <<= 1) mloc[j] = fmaxf(mloc[j], __shfl_xor(mloc[j], off, 64));
+      if (lane == 0) mxch[wave * HB + j] = mloc[j];
+    }
+    __syncthreads();
+    float m[HB];
+#pragma unroll
+    for (int j = 0; j < HB; ++j) {
+      float v = mxch[j];
+#pragma unroll
+      for (uint32_t w = 1; w < NW; ++w) v = fmaxf(v, mxch[w * HB + j]);
+      m[j] = v;
+      m_all[jb + j] = v;
+    }
+    // ---- probabilities and P.V
+    float acc[HB][8], lsum[HB];
+#pragma unroll
+    for (int j = 0; j < HB; ++j) {
+      lsum[j] = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[j][e] = 0.f;
+    }
+#pragma unroll
+    for (int r = 0; r < kAttnRounds; ++r) {
+      const u32x4 vv = vreg[r];
+      const float v8[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
+                           bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
+#pragma unroll
+      for (int j = 0; j < HB; ++j) {
+        const float p = (sreg[r][j] == -INFINITY) ? 0.f : expf(sreg[r][j] - m[j]);
+        lsum[j] += p;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p, v8[e], acc[j][e]);
+      }
+    }
+    // reduce over the position slots of the wavefront; wavefront partials go to LDS
+#pragma unroll
+    for (int j = 0; j < HB; ++j) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float v = acc[j][e];
+#pragma unroll
+        for (uint32_t off = LPP; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
+        if (slot == 0) wpart[((size_t)wave * grp + jb + j) * (d + 2) + sub * 8 + e] = v;
+      }
+      float lv = lsum[j];   // every lane of a position group holds the same p: count each once
+#pragma unroll
+      for (uint32_t off = LPP; off < 64; off <<= 1) lv += __shfl_xor(lv, off, 64);
+      if (lane == 0) wpart[((size_t)wave * grp + jb + j) * (d + 2) + d + 1] = lv;
+    }
+    __syncthreads();   // also protects mxch before the next block
+  }
+  trace_mark(a, t, 10);
+  for (uint32_t i = threadIdx.x; i < grp * (d + 2); i += kThreads) {
+    const uint32_t j = i / (d + 2), dim = i % (d + 2);
+    float sv;
+    if (dim == d) {
+      sv = m_all[0];
+#pragma unroll
+      for (int jj = 1; jj < GRP; ++jj) sv = (j == (uint32_t)jj) ? m_all[jj] : sv;
+    } else {
+      sv = 0.f;
+#pragma unroll
+      for (uint32_t w = 0; w < NW; ++w) sv += wpart[((size_t)w * grp + j) * (d + 2) + dim];
+    }
+    st_act(outp + i, sv);
+  }
+  trace_mark(a, t, 11);
+  if (t.flags & TF_ATTN_MERGE) {
+    // Arrival counter of (layer, sequence, KV head): the chunk task that arrives last sees all C
+    // partials complete and merges them (log-sum-exp, one pass with running maximum) into the
+    // attention output.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint32_t* cnt = a.g->grp_counters + t.p2 + b * nkv + g;
+      uint32_t old = __hip_atomic_fetch_add(as_global(cnt), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      *flag = ((old + 1u) % C == 0u) ? 1u : 0u;   // every step adds exactly C
+    }
+    __syncthreads();
+    if (*flag) {
+      const float* part = t.out + (size_t)b * t.ld_out + (size_t)g * C * per;
+      float* o = const_cast<float*>(t.in2) + (size_t)b * nq * d + (size_t)g * grp * d;
+      for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) {
+        uint32_t j = i / d, dim = i % d;
+        float M = -INFINITY, L = 0.f, acc_o = 0.f;
+        for (uint32_t c0 = 0; c0 < C; c0 += 4) {   // 12 coherent loads in flight
+          float mm[4], ll[4], oo[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            if (c0 + k < C) {
+              const float* pp = part + ((size_t)(c0 + k) * grp + j) * (d + 2);
+              mm[k] = ld_act(pp + d);
+              ll[k] = ld_act(pp + d + 1);
+              oo[k] = ld_act(pp + dim);
+            } else {
+              mm[k] = -INFINITY; ll[k] = 0.f; oo[k] = 0.f;
+            }
+          }
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            float Mn = fmaxf(M, mm[k]);
+            if (Mn == -INFINITY) continue;   // empty chunks only so far
+            float sc_old = expf(M - Mn), sc_new = expf(mm[k] - Mn);
+            L = L * sc_old + ll[k] * sc_new;
+            acc_o = acc_o * sc_old + oo[k] * sc_new;
+            M = Mn;
+          }
+        }
+        st_act(o + i, acc_o / L);
+      }
+    }
+  }
+  return true;
+}
+
 // T4: split-KV decode attention for one (sequence, KV head, chunk).  Chunk c of C covers cache
 // rows [c*len/C, (c+1)*len/C) with len = position + 1, so the last chunk holds the new row.
 // Output per query head of the group: sum_t exp(s_t - m) V_t (D floats), m, l = sum_t exp(s_t - m).
@@ -1138,7 +1412,13 @@ template <int D, int GRP, int NB>
 __device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, float* lds,
                                          int32_t wait_ev, uint32_t* s_flag) {
   if (t.kind == TK_ATTN_PARTIAL) {
-    if (D != 0) return body_attn_partial<(D ? D : 128), (GRP ? GRP : 1)>(t, a, lds, wait_ev, s_flag);
+    if (D != 0) {
+      // chunks that always fit the register-resident body (wavefront-uniform: graph constants)
+      constexpr uint32_t window = kAttnRounds * (kThreads / 64) * (64 / ((D ? D : 128) / 8));
+      if ((GRP ? GRP : 1) <= 4 && (a.g->max_seq + t.p1 - 1) / t.p1 <= window)
+        return body_attn_partial_regs<(D ? D : 128), (GRP ? GRP : 1)>(t, a, lds, wait_ev, s_flag);
+      return body_attn_partial<(D ? D : 128), (GRP ? GRP : 1)>(t, a, lds, wait_ev, s_flag);
+    }
     const uint32_t grp = a.g->n_q / a.g->n_kv;
     if (a.g->head_dim == 128) {
       if (grp == 8) return body_attn_partial<128, 8>(t, a, lds, wait_ev, s_flag);
@@ -1175,14 +1455,14 @@ __device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p) {
 // worker group's ready flag has reached the epoch.
 __device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag) {
   if (threadIdx.x == 0) {
-    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.g->events + e);
+    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
     const uint32_t* word;
     uint32_t target;
     if (ev.flags & EV_HIER) {
-      word = a.g->hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
-      target = a.epoch;
+      word = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
+      target = a.epoch * ev.n_groups;
     } else {
-      word = a.g->counters + e;
+      word = a.counters + e;
       target = a.epoch * ev.required;
     }
     uint32_t ok = 1;
@@ -1211,30 +1491,31 @@ __device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_
 // The arrival that activates an event whose range holds just-in-time tasks hands the event to
 // its scheduler's queue.
 __device__ __forceinline__ void notify_event(const StepArgs& a, int32_t e) {
-  const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.g->events + e);
+  const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
   const uint32_t flags = ev.flags;
   bool activated = false;
   if (flags & EV_HIER) {
-    uint32_t* blk = a.g->hier + (size_t)ev.hier_slot * kHierWordsPerEvent;
+    uint32_t* blk = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent;
     const uint32_t grp = blockIdx.x & 7u;
     uint32_t old = __hip_atomic_fetch_add(as_global(blk + (1 + grp) * kHierStrideWords), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old + 1u == a.epoch * ev.sub_required[grp]) {          // last arrival of this group
-      old = __hip_atomic_fetch_add(as_global(blk), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (old + 1u == a.epoch * ev.n_groups) {                 // last group: the event is activated
+      // tell every group of pollers: its word counts the producer groups that are complete
 #pragma unroll
-        for (uint32_t k = 0; k < 8; ++k)
-          __hip_atomic_store(as_global(blk + (9 + k) * kHierStrideWords), a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        activated = true;
+      for (uint32_t k = 0; k < 8; ++k)
+        __hip_atomic_fetch_add(as_global(blk + (9 + k) * kHierStrideWords), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if ((flags & EV_JIT) && a.n_sched) {                  // a scheduler needs to know who was last
+        old = __hip_atomic_fetch_add(as_global(blk), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        activated = old + 1u == a.epoch * ev.n_groups;
       }
     }
-  } else if ((flags & EV_JIT) && a.g->n_sched) {
-    const uint32_t old = __hip_atomic_fetch_add(as_global(a.g->counters + e), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  } else if ((flags & EV_JIT) && a.n_sched) {
+    const uint32_t old = __hip_atomic_fetch_add(as_global(a.counters + e), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     activated = old + 1u == a.epoch * ev.required;
   } else {
-    __hip_atomic_fetch_add(as_global(a.g->counters + e), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_fetch_add(as_global(a.counters + e), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  if (activated && (flags & EV_JIT) && a.g->n_sched) {
-    const uint32_t sc = (uint32_t)e % a.g->n_sched;
+  if (activated && (flags & EV_JIT) && a.n_sched) {
+    const uint32_t sc = (uint32_t)e % a.n_sched;
     const uint32_t slot = __hip_atomic_fetch_add(as_global(a.g->evq_tail + sc * 64u), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(as_global(a.g->evq_buf + (size_t)sc * a.g->evq_cap + (slot & (a.g->evq_cap - 1u))),
                        ((uint64_t)(slot + 1u) << 32) | (uint32_t)e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1254,14 +1535,14 @@ __device__ __forceinline__ void signal_event(const StepArgs& a, const TaskDesc& 
 // Wavefront 0 only: poll the dependent event of the next task; result in *s_flag (LDS).
 __device__ __forceinline__ void poll_event_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane) {
   if (lane == 0) {
-    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.g->events + e);
+    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
     const uint32_t* word;
     uint32_t target;
     if (ev.flags & EV_HIER) {
-      word = a.g->hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
-      target = a.epoch;
+      word = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
+      target = a.epoch * ev.n_groups;
     } else {
-      word = a.g->counters + e;
+      word = a.counters + e;
       target = a.epoch * ev.required;
     }
     uint32_t ok = 1;
@@ -1303,16 +1584,16 @@ constexpr uint32_t kLdsCtrlFloats = 16;
 // force spills of registers that have loads in flight.
 // Returns false when the step is being aborted.
 template <int D, int GRP, int NB, bool MEGA>
-__device__ __forceinline__ bool run_other_task(StepArgs a, uint32_t task_index, bool skip_wait) {
+__device__ __noinline__ bool run_other_task(StepArgs a, uint32_t task_index, bool skip_wait) {
   extern __shared__ __align__(16) float dyn_lds[];
   float* lds = dyn_lds + kLdsCtrlFloats;
   uint32_t* s_flag = (uint32_t*)dyn_lds;
   const TaskDesc t = ld_task(a, task_index);
   int32_t wait_ev = -1;
   if (MEGA) {
-    wait_ev = (!skip_wait && t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.g->events + t.dep_event))->required != 0) ? t.dep_event : -1;
+    wait_ev = (!skip_wait && t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
     trace_mark(a, t, 0);
-    if (a.g->trace && threadIdx.x == 0) as_global(a.g->trace)[(size_t)task_index * kTraceSlots + 5] = blockIdx.x;
+    if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)task_index * kTraceSlots + 5] = blockIdx.x;
   }
   if (!run_task<D, GRP, NB>(t, a, lds, wait_ev, s_flag)) return false;
   if (MEGA) {
@@ -1325,13 +1606,13 @@ __device__ __forceinline__ bool run_other_task(StepArgs a, uint32_t task_index, 
 }
 
 __device__ __forceinline__ bool event_active(const StepArgs& a, int32_t e) {
-  const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.g->events + e);
+  const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
   if (ev.required == 0) return true;
   if (ev.flags & EV_HIER) {
-    const uint32_t* word = a.g->hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
-    return (int32_t)(ld_relaxed(word) - a.epoch) >= 0;
+    const uint32_t* word = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
+    return (int32_t)(ld_relaxed(word) - a.epoch * ev.n_groups) >= 0;
   }
-  return (int32_t)(ld_relaxed(a.g->counters + e) - a.epoch * ev.required) >= 0;
+  return (int32_t)(ld_relaxed(a.counters + e) - a.epoch * ev.required) >= 0;
 }
 
 __device__ __forceinline__ uint64_t ld_relaxed64(const uint64_t* p) {
@@ -1347,8 +1628,8 @@ __device__ __forceinline__ void scheduler_wave(const StepArgs& a, uint32_t sc) {
   uint32_t head = ld_relaxed(a.g->sched_state + sc * 64u), cursor = ld_relaxed(a.g->sched_state + sc * 64u + 1u);
   uint32_t todo = ld_u32c(a.g->sched_nev + sc);
   // the start event has no notifications: its owner dispatches it unprompted
-  const MPK_CONST EventDesc& sev = *(const MPK_CONST EventDesc*)(a.g->events + a.g->start_event);
-  bool pending_start = (sev.flags & EV_JIT) && a.g->start_event % a.g->n_sched == sc;
+  const MPK_CONST EventDesc& sev = *(const MPK_CONST EventDesc*)(a.events + a.g->start_event);
+  bool pending_start = (sev.flags & EV_JIT) && a.g->start_event % a.n_sched == sc;
   while (todo > 0 || pending_start) {
     uint32_t e;
     if (pending_start) {
@@ -1380,11 +1661,11 @@ __device__ __forceinline__ void scheduler_wave(const StepArgs& a, uint32_t sc) {
       ++head;
       --todo;
     }
-    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.g->events + e);
+    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
     const uint32_t first = ev.first, n = ev.last - ev.first;
     for (uint32_t i = lane; i < n; i += 64) {
       const uint32_t ti = first + i;
-      const MPK_CONST TaskDesc& td = *(const MPK_CONST TaskDesc*)(a.g->tasks + ti);
+      const MPK_CONST TaskDesc& td = *(const MPK_CONST TaskDesc*)(a.tasks + ti);
       if (td.flags & TF_JIT) {
         const uint32_t w = (cursor + i) % W;
         const uint32_t s = __hip_atomic_fetch_add(as_global(a.g->wq_tail + w * 64u), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1421,7 +1702,7 @@ __device__ __forceinline__ uint32_t pick_task(const StepArgs& a, uint32_t* ctrl,
       }
       if (*ai < q1) {
         const uint32_t ti = ld_u32c(a.g->aot + *ai);
-        const int32_t dep = ((const MPK_CONST TaskDesc*)(a.g->tasks + ti))->dep_event;
+        const int32_t dep = ((const MPK_CONST TaskDesc*)(a.tasks + ti))->dep_event;
         if (dep < 0 || event_active(a, dep)) {
           pick = ti;
           ++*ai;
@@ -1463,19 +1744,19 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
     // scheduler workgroup: 4 scheduler wavefronts (Section 5.1, Table 2), the rest leave
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t sc = (w - a.g->n_workers) * 4u + wave;
-    if (wave < 4u && sc < a.g->n_sched) scheduler_wave(a, sc);
+    if (wave < 4u && sc < a.n_sched) scheduler_wave(a, sc);
     return;
   }
   const uint32_t q0 = ld_u32c(a.g->aot_off + w), q1 = ld_u32c(a.g->aot_off + w + 1);
-  if (a.g->n_sched == 0) {
+  if (a.n_sched == 0) {
     // every task ahead-of-time: walk the pre-enqueued list, each task waits for its own event
     for (uint32_t qi = q0; qi < q1; ++qi) {
       const uint32_t ti = ld_u32c(a.g->aot + qi);
       const TaskDesc t = ld_task(a, ti);
       if (t.kind == TK_LINEAR) {
-        const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.g->events + t.dep_event))->required != 0) ? t.dep_event : -1;
+        const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
         trace_mark(a, t, 0);
-        if (a.g->trace && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
+        if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
         if (!run_linear<NB, true>(t, a, lds, wait_ev, s_flag)) break;
       } else {
         // the callee's result comes back in a vector register: make it scalar again, or the whole
@@ -1494,7 +1775,7 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
     const TaskDesc t = ld_task(a, ti);
     if (t.kind == TK_LINEAR) {
       trace_mark(a, t, 0);
-      if (a.g->trace && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
+      if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
       if (!run_linear<NB, true>(t, a, lds, -1, s_flag)) break;   // its event is already activated
     } else {
       if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true>(a, ti, true))) break;
@@ -1795,6 +2076,8 @@ extern "C" mpk_status mpk_decode_step(mpk_graph* g, const int32_t* token_ids,
   HostGraph& h = g->h;
   StepArgs a{};
   a.g = (const MPK_CONST GraphConst*)g->d_const;
+  a.tasks = g->d_tasks; a.events = g->d_events; a.counters = g->d_counters; a.hier = g->d_hier;
+  a.n_sched = g->n_sched; a.trace = g->d_trace;
   a.token_ids = token_ids; a.positions = positions; a.logits = logits_out;
   hipStream_t s = (hipStream_t)stream;
   a.epoch = ++g->epoch;
