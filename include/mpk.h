@@ -118,6 +118,9 @@ typedef struct mpk_compile_options {
                                weight/KV pointers may be NULL; mpk_decode_step is refused       */
   uint32_t spin_timeout_ms; /* in-kernel watchdog for every wait; 0 = 2000 ms                   */
   uint32_t debug_flags;     /* MPK_DEBUG_* bits                                                 */
+  uint32_t tiles_moe;       /* expert tasks per expert stage of a mixture-of-experts layer
+                               (Section 6.4: expert tasks are fixed at compile time and split
+                               the active experts' rows evenly at run time); 0 = n_workers      */
 } mpk_compile_options;
 
 typedef struct mpk_graph mpk_graph;
@@ -130,7 +133,8 @@ typedef struct mpk_graph mpk_graph;
  *   out              : host, receives the graph handle (NULL on failure).
  * Errors: INVALID_ARG (null/zero/misaligned: every weight pointer must be 16-byte aligned),
  * UNSUPPORTED (head_dim not 64 or 128; hidden, ffn or n_q*head_dim not a multiple of 8;
- * n_q not a multiple of n_kv; batch > 8 for dense linear operators; MoE fields non-zero),
+ * n_q not a multiple of n_kv; batch > 16; mixture-of-experts layers with more than 512 experts,
+ * top_k > 16, batch x top_k > 256, expert_ffn not a multiple of 8 or hidden not of 16),
  * RESIDENCY, OOM, HIP. */
 mpk_status mpk_compile(const mpk_model_config *cfg, const mpk_weight_ptrs *weights,
                        const mpk_kv_ptrs *kv, const mpk_compile_options *opts, mpk_graph **out);
@@ -177,6 +181,10 @@ typedef struct mpk_stats {
   uint64_t weight_bytes;   /* bf16 weight bytes one step streams (embedding rows included)      */
   uint64_t kv_row_bytes;   /* K+V bytes read per cached position, summed over layers & kv heads */
   uint64_t act_bytes;      /* fp32 activation buffers owned by the graph                        */
+  uint64_t expert_bytes;   /* mixture-of-experts: bf16 bytes of ONE expert of one layer (gate, up
+                              and down matrices); weight_bytes then excludes the experts: a step
+                              streams weight_bytes + expert_bytes x (distinct experts selected,
+                              summed over layers, see mpk_graph_moe_active)                    */
 } mpk_stats;
 
 mpk_status mpk_graph_stats(const mpk_graph *g, mpk_stats *out);
@@ -221,7 +229,7 @@ typedef struct mpk_export_event {
 enum {
   MPK_OP_EMBED = 0, MPK_OP_RMSNORM = 1, MPK_OP_LINEAR = 2, MPK_OP_ROPE = 3,
   MPK_OP_ATTN_PARTIAL = 4, MPK_OP_ATTN_MERGE = 5, MPK_OP_ADD = 6, MPK_OP_SWIGLU = 7,
-  MPK_OP_GATEUP = 8, MPK_OP_ROUTER = 9, MPK_OP_EXPERT = 10
+  MPK_OP_GATEUP = 8, MPK_OP_ROUTER = 9, MPK_OP_EXPERT = 10, MPK_OP_COMBINE = 12
 };
 
 mpk_status mpk_graph_export(const mpk_graph *g, void *buf, size_t cap, size_t *need);
@@ -234,6 +242,19 @@ mpk_status mpk_graph_export(const mpk_graph *g, void *buf, size_t cap, size_t *n
  * completed, all in ticks of the 100 MHz device wall clock; 5 worker index.  Call after synchronising the stream.
  * buf == NULL returns the element count in *need. */
 mpk_status mpk_graph_trace(mpk_graph *g, uint64_t *buf, size_t cap, size_t *need);
+
+/* Mixture-of-experts graphs: the number of distinct experts the LAST decode step selected in each
+ * layer (word 0 of each layer's meta-tensor, Section 6.4), i.e. how many experts' weights that
+ * step streamed.  out: host u32 [n_layers].  Call after synchronising the stream; buf == NULL
+ * returns the element count in *need.  INVALID_ARG for a dense or host_only graph. */
+mpk_status mpk_graph_moe_active(mpk_graph *g, uint32_t *out, size_t cap, size_t *need);
+
+/* Mixture-of-experts graphs: the routing decision of the LAST decode step (from each layer's
+ * meta-tensor).  experts: host u32 [n_layers][batch][top_k], a token's experts in ascending index;
+ * weights: host fp32, same shape, the renormalised combine weights; either may be NULL.  cap is in
+ * elements; both NULL returns the element count in *need.  Call after synchronising the stream. */
+mpk_status mpk_graph_moe_selection(mpk_graph *g, uint32_t *experts, float *weights, size_t cap,
+                                   size_t *need);
 
 const char *mpk_last_error(void);
 void mpk_graph_destroy(mpk_graph *g);

@@ -73,7 +73,7 @@ def lib(prec: str = "f32"):
         L.orc_argmax.restype = ci
         L.orc_router_topk.argtypes = [vp, ci, ci, vp, vp]
         L.orc_layer.argtypes = [ctypes.POINTER(_LayerCfg), ctypes.POINTER(_LayerW), vp, vp, ci,
-                                vp, vp, vp]
+                                vp, vp, vp, vp]
         for f in ("orc_embed", "orc_rmsnorm", "orc_linear", "orc_rope", "orc_kv_store",
                   "orc_attention_head", "orc_swiglu", "orc_add", "orc_router_topk", "orc_layer"):
             getattr(L, f).restype = None
@@ -181,7 +181,8 @@ class DecoderOracle:
         self.dt = self.ops.dt
         self.n_layers = shape.n_layers if n_layers is None else n_layers
         self.kv = {}
-        self.last_moe_sel = None
+        self.last_moe_sel = None      # [layers, B, top_k] selected experts of the last step
+        self.last_moe_logits = None   # [layers, B, n_experts] router outputs of the last step
 
     def _kv(self, l):
         if l not in self.kv:
@@ -201,6 +202,7 @@ class DecoderOracle:
                         s.rms_eps, s.rope_theta, s.n_experts, s.top_k, s.expert_ffn)
         xs = [self.ops.embed(self.p.embed_row(int(t)).reshape(1, -1), 0) for t in tokens]
         moe_sel = np.zeros((self.n_layers, B, max(s.top_k, 1)), np.int32)
+        moe_logits = np.zeros((self.n_layers, B, max(s.n_experts, 1)), self.dt)
         from synth import gen as G
         for l in range(self.n_layers):
             wl = self.p.layer(l)
@@ -217,9 +219,10 @@ class DecoderOracle:
                 assert 0 <= positions[b] < s.max_seq
                 L.orc_layer(ctypes.byref(cfg), ctypes.byref(w), K[b].ctypes.data,
                             V[b].ctypes.data, int(positions[b]), _p(xs[b]), _p(work),
-                            moe_sel[l, b].ctypes.data)
+                            moe_sel[l, b].ctypes.data, moe_logits[l, b].ctypes.data)
             del keep
         self.last_moe_sel = moe_sel
+        self.last_moe_logits = moe_logits
         if return_hidden:
             return np.stack(xs)
         g = self.p.final_norm()

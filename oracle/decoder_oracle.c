@@ -205,7 +205,8 @@ typedef struct {
 
 void orc_layer(const orc_layer_cfg *c, const orc_layer_w *w, uint16_t *kc, uint16_t *vc, int pos,
                real *x /* in: layer input, out: layer output */, real *work,
-               int *moe_sel /* top_k, may be NULL */) {
+               int *moe_sel /* top_k, may be NULL */,
+               real *moe_logits /* n_experts router outputs, may be NULL */) {
   int H = c->hidden, d = c->d, nq = c->n_q, nkv = c->n_kv;
   int qkv_rows = (nq + 2 * nkv) * d;
   real *xn = work;
@@ -248,6 +249,8 @@ void orc_layer(const orc_layer_cfg *c, const orc_layer_w *w, uint16_t *kc, uint1
     real wts[64];
     int *sel = moe_sel ? moe_sel : sel_local;
     orc_linear(w->router, E, H, xn, rl);
+    if (moe_logits)
+      for (int e = 0; e < E; ++e) moe_logits[e] = rl[e];
     orc_router_topk(rl, E, K, sel, wts);
     for (int i = 0; i < H; ++i) y[i] = 0;
     for (int j = 0; j < K; ++j) { /* ascending expert index */

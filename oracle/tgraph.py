@@ -27,7 +27,7 @@ F_NORM, F_RESID, F_SWIGLU, F_MERGE, F_ROPE = 1, 2, 4, 8, 16
 
 # operator kinds (same numbering as the exported op table)
 (K_EMBED, K_RMSNORM, K_LINEAR, K_ROPE, K_ATTN_PARTIAL, K_ATTN_MERGE, K_ADD, K_SWIGLU,
- K_GATEUP, K_ROUTER, K_EXPERT, K_DUMMY) = range(12)
+ K_GATEUP, K_ROUTER, K_EXPERT, K_DUMMY, K_COMBINE) = range(13)
 
 
 def split_even(n: int, k: int):
@@ -53,9 +53,18 @@ class OpSpec:
     meta: dict = field(default_factory=dict)
 
 
-def build_ops(s, fusion: int, attn_chunks: int):
+def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0):
     """Operator list of one decode step for model shape `s` (synth.gen.ModelShape) under the
-    given fusion flags, in execution order.  Dense models only."""
+    given fusion flags, in execution order.
+
+    A mixture-of-experts block (Section 6.4: routing, expert computation, combine as chains of
+    tasks in the same graph) is five operators: the router's linear operator; `route` (softmax,
+    top-k, the meta-tensor: one task that needs every token's router output); the experts'
+    gate/up stage and their down stage, each cut at compile time into `moe_tasks` expert tasks
+    whose share of the work is refined at run time from the meta-tensor; and `combine` (weighted
+    sum of a token's expert outputs plus the residual).  Which token rows an expert task touches is
+    only known at run time, so an expert stage's output is modelled as one element per task and
+    every consumer of the stage reads all of them (the static superset)."""
     B, H, d, nq, nkv = s.batch, s.hidden, s.head_dim, s.n_q_heads, s.n_kv_heads
     F, V, C = s.ffn, s.vocab, attn_chunks
     grp = nq // nkv
@@ -95,12 +104,23 @@ def build_ops(s, fusion: int, attn_chunks: int):
         else:
             ops.append(OpSpec(p + "mlp_norm", K_RMSNORM, l, p + "xn2", B, H, H, [x1]))
             nsrc = p + "xn2"
+        xo = f"x{l + 1}"
+        if s.n_experts:
+            NT = moe_tasks
+            ops.append(OpSpec(p + "router", K_LINEAR, l, p + "rl", B, s.n_experts, 1, [nsrc], {"K": H}))
+            ops.append(OpSpec(p + "route", K_ROUTER, l, p + "meta", 1, 1, 1, [p + "rl"]))
+            ops.append(OpSpec(p + "expert_gate_up", K_EXPERT, l, p + "eh", 1, NT, 1,
+                              [p + "meta", nsrc]))
+            ops.append(OpSpec(p + "expert_down", K_EXPERT, l, p + "ey", 1, NT, 1,
+                              [p + "meta", p + "eh"]))
+            ops.append(OpSpec(p + "combine", K_COMBINE, l, xo, B, H, 1, [x1, p + "ey", p + "meta"]))
+            x = xo
+            continue
         if fusion & F_SWIGLU:
             ops.append(OpSpec(p + "gate_up", K_GATEUP, l, p + "h", B, F, 1, [nsrc], {"K": H}))
         else:
             ops.append(OpSpec(p + "gate_up", K_LINEAR, l, p + "gu", B, 2 * F, 1, [nsrc], {"K": H}))
             ops.append(OpSpec(p + "swiglu", K_SWIGLU, l, p + "h", B, F, 1, [p + "gu"], {"F": F}))
-        xo = f"x{l + 1}"
         if fusion & F_RESID:
             ops.append(OpSpec(p + "down", K_LINEAR, l, xo, B, H, 1, [p + "h", x1],
                               {"K": F, "resid": x1}))
@@ -191,6 +211,17 @@ def read_elements(op: OpSpec, tb: int, tc: int, tile: int, shapes: dict):
         m = mask(op.ins[0])
         m[b0:b1, c0:c1] = True
         m[b0:b1, F + c0:F + c1] = True
+    elif k == K_ROUTER:
+        mask(op.ins[0])[:, :] = True                    # top-k of every token, lists per expert
+    elif k == K_EXPERT:
+        # the meta-tensor, and whichever token rows / expert-stage results routing sends here:
+        # statically, all of them
+        for t in op.ins:
+            mask(t)[:, :] = True
+    elif k == K_COMBINE:
+        mask(op.ins[0])[b0:b1, c0:c1] = True            # residual at the same place
+        mask(op.ins[1])[:, :] = True                    # any expert task may hold a needed output
+        mask(op.ins[2])[:, :] = True                    # combine weights
     else:
         raise ValueError(k)
     return out

@@ -20,6 +20,7 @@ LAUNCH_MEGA, LAUNCH_PER_OP = 0, 1
 TASK_DUMMY_OP = 0xFFFFFFFF
 (OP_EMBED, OP_RMSNORM, OP_LINEAR, OP_ROPE, OP_ATTN_PARTIAL, OP_ATTN_MERGE, OP_ADD, OP_SWIGLU,
  OP_GATEUP, OP_ROUTER, OP_EXPERT) = range(11)
+OP_COMBINE = 12
 
 
 class ModelConfig(C.Structure):
@@ -49,7 +50,8 @@ class CompileOptions(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in
                 ("struct_size", "n_workers", "n_sched_wgs", "fusion", "transitive_reduction",
                  "attn_chunks", "tiles_linear", "tiles_lm_head", "tiles_pointwise", "launch_mode",
-                 "force_aot", "prefetch", "host_only", "spin_timeout_ms", "debug_flags")]
+                 "force_aot", "prefetch", "host_only", "spin_timeout_ms", "debug_flags",
+                 "tiles_moe")]
 
 
 class Stats(C.Structure):
@@ -61,7 +63,8 @@ class Stats(C.Structure):
                 ("n_sched_wgs", C.c_uint32), ("lds_bytes", C.c_uint32),
                 ("task_desc_bytes", C.c_uint32), ("successor_bytes_unlinearized", C.c_uint64),
                 ("successor_bytes_linearized", C.c_uint64), ("weight_bytes", C.c_uint64),
-                ("kv_row_bytes", C.c_uint64), ("act_bytes", C.c_uint64)]
+                ("kv_row_bytes", C.c_uint64), ("act_bytes", C.c_uint64),
+                ("expert_bytes", C.c_uint64)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -80,7 +83,8 @@ EXPORT_EVENT = np.dtype([("required", "<u4"), ("first", "<u4"), ("last", "<u4"),
 
 SYMBOLS = ("mpk_compile", "mpk_compile_dag", "mpk_decode_step", "mpk_graph_status",
            "mpk_graph_reset", "mpk_graph_stats", "mpk_graph_export", "mpk_graph_trace",
-           "mpk_last_error", "mpk_graph_destroy")
+           "mpk_graph_moe_active", "mpk_graph_moe_selection", "mpk_last_error",
+           "mpk_graph_destroy")
 
 _lib = None
 
@@ -104,10 +108,12 @@ def lib():
         L.mpk_graph_stats.argtypes = [vp, C.POINTER(Stats)]
         L.mpk_graph_export.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
         L.mpk_graph_trace.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
+        L.mpk_graph_moe_active.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
+        L.mpk_graph_moe_selection.argtypes = [vp, vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
         L.mpk_last_error.restype = C.c_char_p
         L.mpk_graph_destroy.argtypes = [vp]
         L.mpk_graph_destroy.restype = None
-        for n in SYMBOLS[:8]:
+        for n in SYMBOLS[:10]:
             getattr(L, n).restype = C.c_int
         _lib = L
     return _lib
@@ -199,6 +205,23 @@ class Graph:
         buf = np.zeros(need.value, np.uint64)
         _check(lib().mpk_graph_trace(self._h, buf.ctypes.data, need.value, C.byref(need)))
         return buf.reshape(-1, 12)
+
+    def moe_active(self) -> np.ndarray:
+        need = C.c_size_t(0)
+        _check(lib().mpk_graph_moe_active(self._h, None, 0, C.byref(need)))
+        buf = np.zeros(need.value, np.uint32)
+        _check(lib().mpk_graph_moe_active(self._h, buf.ctypes.data, need.value, C.byref(need)))
+        return buf
+
+    def moe_selection(self):
+        """(experts u32 [layers][batch*top_k], weights f32 same shape) of the last step."""
+        need = C.c_size_t(0)
+        _check(lib().mpk_graph_moe_selection(self._h, None, None, 0, C.byref(need)))
+        ex = np.zeros(need.value, np.uint32)
+        wt = np.zeros(need.value, np.float32)
+        _check(lib().mpk_graph_moe_selection(self._h, ex.ctypes.data, wt.ctypes.data, need.value,
+                                             C.byref(need)))
+        return ex, wt
 
     def destroy(self):
         if self._h:

@@ -496,6 +496,52 @@ static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
       op.w2 = lw.mlp_norm; op.f0 = c.rms_eps; op.K = H;
       gin = xn2;
     }
+    if (c.n_experts) {
+      // Mixture-of-experts block (Section 6.4): router, route (softmax + top-k -> meta-tensor),
+      // the experts' gate/up stage, their down stage, combine.  An expert stage is cut into a
+      // fixed number of expert tasks at compile time; which rows of which expert a task works on
+      // is refined at run time from the meta-tensor, so for the dependency analysis a stage's
+      // output is one element per task and every consumer reads all of them.
+      const uint32_t E = c.n_experts, TK = c.top_k, Fe = c.expert_ffn, P = B * TK;
+      const uint32_t NT = o.tiles_moe ? o.tiles_moe : o.n_workers;
+      int rl = b.new_tensor(B, E);
+      {
+        HostOp& op = b.add(MPK_OP_LINEAR, l, "router", rl, 1, gin);
+        op.w = lw.router; op.K = H;
+        if (f & MPK_FUSE_NORM) { op.flags |= TF_PRO_NORM; op.w2 = lw.mlp_norm; op.f0 = c.rms_eps; }
+      }
+      int meta = b.new_tensor(1, 1), meta_data = b.new_tensor(1, moe_meta_words(E, P));
+      g.moe_meta_offset.push_back(g.tensors[meta_data].offset);
+      {
+        HostOp& op = b.add(MPK_OP_ROUTER, l, "route", meta, 1, rl);
+        op.data_in = rl; op.data_out = meta_data;
+        op.p0 = E; op.p1 = TK; op.p2 = B; op.K = E;
+      }
+      int eh = b.new_tensor(1, NT), hbuf = b.new_tensor(P, Fe);
+      {
+        HostOp& op = b.add(MPK_OP_EXPERT, l, "expert_gate_up", eh, 1, meta, gin);
+        op.data_in = gin; op.data_in2 = meta_data; op.data_out = hbuf;
+        op.w = lw.expert_wgu; op.K = H; op.flags |= TF_GATEUP;
+        op.p0 = Fe; op.p1 = NT; op.p2 = 2 * Fe; op.p3 = E | (TK << 16);
+        if (f & MPK_FUSE_NORM) { op.flags |= TF_PRO_NORM; op.w2 = lw.mlp_norm; op.f0 = c.rms_eps; }
+      }
+      int ey = b.new_tensor(1, NT), ybuf = b.new_tensor(P, H);
+      {
+        HostOp& op = b.add(MPK_OP_EXPERT, l, "expert_down", ey, 1, meta, eh);
+        op.data_in = hbuf; op.data_in2 = meta_data; op.data_out = ybuf;
+        op.w = lw.expert_wd; op.K = Fe;
+        op.p0 = 0; op.p1 = NT; op.p2 = H; op.p3 = E | (TK << 16);
+      }
+      int xo = b.new_tensor(B, H);
+      {
+        HostOp& op = b.add(MPK_OP_COMBINE, l, "combine", xo, 1, x1, ey);
+        op.in3_tensor = meta;
+        op.data_in = ybuf; op.data_in2 = x1; op.data_aux = meta_data; op.data_out = xo;
+        op.p0 = E; op.p1 = TK; op.K = H;
+      }
+      x = xo;
+      continue;
+    }
     int h = b.new_tensor(B, F);
     if (f & MPK_FUSE_SWIGLU) {
       HostOp& op = b.add(MPK_OP_GATEUP, l, "gate_up", h, 1, gin);
@@ -563,6 +609,11 @@ static void choose_partitions(const mpk_model_config& c, const mpk_compile_optio
         uint32_t cap = std::max(1u, nu / 8);   // at least 8 output rows per task
         op.tb = 1;
         op.tc = std::max(1u, std::min(want, cap));
+        // the matrix-core body (batch > 4) holds at most 512 weight rows per task: whole extra
+        // rounds of tasks until the tiles fit (only when the tile count was not given)
+        const bool given = (op.flags & TF_OUT_LOGITS) ? o.tiles_lm_head != 0 : o.tiles_linear != 0;
+        const uint32_t per_row = (op.flags & TF_GATEUP) ? 2u : 1u;
+        while (c.batch > 4 && !given && op.tc < cap && (nu + op.tc - 1) / op.tc * per_row > 512) op.tc = std::min(cap, op.tc + W);
         if (op.align_unit && nu % op.align_unit == 0) {
           // QKV projection: tiles that never straddle a head keep every tile in exactly one
           // attention group's producer set (no fork, hence no dummy tasks).  Pick the smallest
@@ -589,6 +640,19 @@ static void choose_partitions(const mpk_model_config& c, const mpk_compile_optio
       case MPK_OP_SWIGLU:
         op.tb = op.rows;
         op.tc = std::max(1u, std::min(o.tiles_pointwise ? o.tiles_pointwise : 1u, nu));
+        break;
+      case MPK_OP_ROUTER:   // one task: the per-expert token lists need every token's choice
+        op.tb = 1;
+        op.tc = 1;
+        break;
+      case MPK_OP_EXPERT:   // one element per expert task
+        op.tb = 1;
+        op.tc = nu;
+        break;
+      case MPK_OP_COMBINE:
+        op.tb = op.rows;
+        op.tc = std::max(1u, std::min(o.tiles_pointwise ? o.tiles_pointwise
+                                                        : std::max(1u, W / op.rows), std::max(1u, nu / 256)));
         break;
       default:   // embed, rmsnorm: one task per batch row (needs the whole row)
         op.tb = op.rows;
@@ -657,6 +721,18 @@ static void input_rects(const mpk_model_config& c, const HostOp& op, uint32_t ti
       out.push_back({op.in_tensor, b0, b1, c0, c1});
       out.push_back({op.in_tensor, b0, b1, op.p0 + c0, op.p0 + c1});
       break;
+    case MPK_OP_ROUTER:   // every token's router output
+      out.push_back({op.in_tensor, 0, UINT32_MAX, 0, UINT32_MAX});
+      break;
+    case MPK_OP_EXPERT:   // the meta-tensor + whatever routing sends here: statically everything
+      out.push_back({op.in_tensor, 0, UINT32_MAX, 0, UINT32_MAX});
+      out.push_back({op.in2_tensor, 0, UINT32_MAX, 0, UINT32_MAX});
+      break;
+    case MPK_OP_COMBINE:
+      out.push_back({op.in_tensor, b0, b1, c0, c1});
+      out.push_back({op.in2_tensor, 0, UINT32_MAX, 0, UINT32_MAX});
+      out.push_back({op.in3_tensor, 0, UINT32_MAX, 0, UINT32_MAX});
+      break;
   }
 }
 
@@ -682,10 +758,10 @@ static void dependency_analysis(const mpk_model_config& c, HostGraph& g, PassInp
         int po = producer_op[r.tensor];
         if (po < 0) continue;
         const HostOp& p = g.ops[po];
-        uint32_t c1 = std::min(r.c1, p.cols);
-        if (r.b0 >= r.b1 || r.c0 >= c1) continue;
+        uint32_t c1 = std::min(r.c1, p.cols), rb1 = std::min(r.b1, p.rows);
+        if (r.b0 >= rb1 || r.c0 >= c1) continue;
         uint32_t nu = p.cols / p.unit;
-        uint32_t ib0 = tile_of(p.rows, p.tb, r.b0), ib1 = tile_of(p.rows, p.tb, r.b1 - 1);
+        uint32_t ib0 = tile_of(p.rows, p.tb, r.b0), ib1 = tile_of(p.rows, p.tb, rb1 - 1);
         uint32_t ic0 = tile_of(nu, p.tc, r.c0 / p.unit), ic1 = tile_of(nu, p.tc, (c1 - 1) / p.unit);
         for (uint32_t ib = ib0; ib <= ib1; ++ib)
           for (uint32_t ic = ic0; ic <= ic1; ++ic) P.push_back(p.task_base + ib * p.tc + ic);
@@ -696,14 +772,14 @@ static void dependency_analysis(const mpk_model_config& c, HostGraph& g, PassInp
 }
 
 // ------------------------------------------------------------------ K7 labels (operator level)
-// Attention has a data-dependent duration -> JIT.  A downstream operator stays JIT unless each of
+// Attention and expert tasks have a data-dependent duration -> JIT.  A downstream operator stays JIT unless each of
 // its tasks waits for ALL tasks of every JIT operator it reads from (a global barrier with
 // respect to the accumulated imbalance, Section 5.2).
 static void label_ops(HostGraph& g, const PassInput& pi, std::vector<uint32_t>& op_jit) {
   op_jit.assign(g.ops.size(), 0);
   for (size_t oi = 0; oi < g.ops.size(); ++oi) {
     const HostOp& op = g.ops[oi];
-    if (op.kind == MPK_OP_ATTN_PARTIAL) { op_jit[oi] = 1; continue; }
+    if (op.kind == MPK_OP_ATTN_PARTIAL || op.kind == MPK_OP_EXPERT) { op_jit[oi] = 1; continue; }
     bool jit = false;
     for (uint32_t tile = 0; tile < op.tb * op.tc && !jit; ++tile) {
       const auto& P = pi.prod[op.task_base + tile];
@@ -759,6 +835,17 @@ static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGr
       case MPK_OP_ATTN_MERGE: t.kind = TK_ATTN_MERGE; break;
       case MPK_OP_ADD: t.kind = TK_ADD; break;
       case MPK_OP_SWIGLU: t.kind = TK_SWIGLU; break;
+      case MPK_OP_ROUTER: t.kind = TK_MOE_ROUTE; break;
+      case MPK_OP_EXPERT: t.kind = TK_MOE_EXPERT; break;
+      case MPK_OP_COMBINE: t.kind = TK_MOE_COMBINE; break;
+    }
+    if (op.kind == MPK_OP_ROUTER || op.kind == MPK_OP_EXPERT || op.kind == MPK_OP_COMBINE) {
+      t.in = act_ref(g, op.data_in);
+      t.in2 = act_ref(g, op.data_in2);
+      t.out = const_cast<float*>(act_ref(g, op.data_out));
+      t.aux0 = (void*)act_ref(g, op.data_aux);   // relocated by the runtime like in / in2 / out
+      t.ld_in = g.tensors[op.data_in].cols;
+      t.ld_out = g.tensors[op.data_out].cols;
     }
     if (op.kind == MPK_OP_ROPE || op.kind == MPK_OP_ATTN_PARTIAL) {
       if (kv && kv->k && kv->v) {
@@ -800,6 +887,15 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
         f = std::max<size_t>(2 * (size_t)c.batch * (kt + 8), 8 * 4 * 256) + (size_t)res_rows * 16 + 8 * 16;
       }
     }
+    else if (op.kind == MPK_OP_EXPERT) {
+      // input tiles as in the matrix-core linear body: up to 8 token rows x 2048 inputs, or up
+      // to 16 x 1024; + sums of squares
+      const size_t t8 = 2 * (size_t)std::min(c.batch, 8u) * (2048 + 8);
+      const size_t t16 = c.batch > 8 ? 2 * (size_t)c.batch * (1024 + 8) : 0;
+      f = std::max<size_t>(std::max(t8, t16), 8 * 4 * 256) + 8 * 16 + 16;   // + sums of squares + staged row list
+    }
+    else if (op.kind == MPK_OP_ROUTER)
+      f = (size_t)c.batch * c.top_k * 2 + c.n_experts * 2 + 64;
     else if (op.kind == MPK_OP_ATTN_PARTIAL)
       f = (size_t)grp * c.head_dim                                        // q
           + (size_t)(kThreads / 64) * grp * (c.head_dim + 2) + 16 + 64;   // per-wave partials
@@ -814,15 +910,22 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
   if (c.struct_size != sizeof(mpk_model_config)) { set_error("mpk_model_config.struct_size is %u, expected %zu", c.struct_size, sizeof(mpk_model_config)); return MPK_ERR_INVALID_ARG; }
   if (!c.n_layers || !c.hidden || !c.n_q_heads || !c.n_kv_heads || !c.head_dim || !c.vocab || !c.batch || !c.max_seq) { set_error("a model dimension is zero"); return MPK_ERR_INVALID_ARG; }
   if (c.flags) { set_error("mpk_model_config.flags must be 0"); return MPK_ERR_INVALID_ARG; }
-  if (c.n_experts || c.top_k || c.expert_ffn) { set_error("mixture-of-experts layers are not supported yet"); return MPK_ERR_UNSUPPORTED; }
-  if (!c.ffn) { set_error("ffn is zero"); return MPK_ERR_INVALID_ARG; }
+  const bool moe = c.n_experts != 0;
+  if (moe) {
+    if (!c.top_k || !c.expert_ffn || c.top_k > c.n_experts) { set_error("mixture-of-experts: top_k and expert_ffn must be non-zero and top_k <= n_experts"); return MPK_ERR_INVALID_ARG; }
+    if (c.n_experts > kMoeMaxExperts || c.top_k > kMoeMaxTopK || c.batch * c.top_k > kMoeMaxPairs) { set_error("mixture-of-experts: at most %u experts, top_k %u, batch x top_k %u", kMoeMaxExperts, kMoeMaxTopK, kMoeMaxPairs); return MPK_ERR_UNSUPPORTED; }
+    if (c.expert_ffn % 8 || c.expert_ffn < 32 || c.hidden % 16) { set_error("mixture-of-experts: expert_ffn must be a multiple of 8 (at least 32) and hidden a multiple of 16"); return MPK_ERR_UNSUPPORTED; }
+  } else {
+    if (c.top_k || c.expert_ffn) { set_error("top_k / expert_ffn set without n_experts"); return MPK_ERR_INVALID_ARG; }
+    if (!c.ffn) { set_error("ffn is zero"); return MPK_ERR_INVALID_ARG; }
+  }
   if (c.head_dim != 64 && c.head_dim != 128) { set_error("head_dim %u unsupported (64 or 128)", c.head_dim); return MPK_ERR_UNSUPPORTED; }
   if (c.n_q_heads % c.n_kv_heads) { set_error("n_q_heads must be a multiple of n_kv_heads"); return MPK_ERR_UNSUPPORTED; }
   {
     uint32_t grp = c.n_q_heads / c.n_kv_heads;
     if (grp != 1 && grp != 2 && grp != 4 && grp != 8) { set_error("%u query heads per KV head unsupported (1, 2, 4 or 8)", grp); return MPK_ERR_UNSUPPORTED; }
   }
-  if (c.hidden % 8 || c.ffn % 8 || (c.n_q_heads * c.head_dim) % 8) { set_error("hidden, ffn and n_q*head_dim must be multiples of 8"); return MPK_ERR_UNSUPPORTED; }
+  if (c.hidden % 8 || (!moe && c.ffn % 8) || (c.n_q_heads * c.head_dim) % 8) { set_error("hidden, ffn and n_q*head_dim must be multiples of 8"); return MPK_ERR_UNSUPPORTED; }
   if (c.batch > 16) { set_error("batch %u unsupported by the dense linear bodies (max 16)", c.batch); return MPK_ERR_UNSUPPORTED; }
   if (o.debug_flags & ~MPK_DEBUG_TRACE) { set_error("unknown debug_flags bits"); return MPK_ERR_INVALID_ARG; }
   if (o.fusion & ~(MPK_FUSE_NORM | MPK_FUSE_RESID | MPK_FUSE_SWIGLU | MPK_FUSE_MERGE | MPK_FUSE_ROPE)) { set_error("unknown fusion bits"); return MPK_ERR_INVALID_ARG; }
@@ -832,7 +935,8 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
     if (bad(w->embed) || bad(w->final_norm) || bad(w->lm_head) || bad(kv->k) || bad(kv->v)) { set_error("a model-level pointer is NULL or not 16-byte aligned"); return MPK_ERR_INVALID_ARG; }
     for (uint32_t l = 0; l < c.n_layers; ++l) {
       const mpk_layer_weights& lw = w->layers[l];
-      if (bad(lw.attn_norm) || bad(lw.wqkv) || bad(lw.wo) || bad(lw.mlp_norm) || bad(lw.wgu) || bad(lw.wd)) { set_error("layer %u: a weight pointer is NULL or not 16-byte aligned", l); return MPK_ERR_INVALID_ARG; }
+      if (bad(lw.attn_norm) || bad(lw.wqkv) || bad(lw.wo) || bad(lw.mlp_norm) ||
+          (moe ? (bad(lw.router) || bad(lw.expert_wgu) || bad(lw.expert_wd)) : (bad(lw.wgu) || bad(lw.wd)))) { set_error("layer %u: a weight pointer is NULL or not 16-byte aligned", l); return MPK_ERR_INVALID_ARG; }
     }
   }
   return MPK_OK;
@@ -888,8 +992,10 @@ mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs*
   uint64_t qkv_rows = (uint64_t)(cfg.n_q_heads + 2 * cfg.n_kv_heads) * cfg.head_dim;
   wb += (uint64_t)cfg.n_layers * 2 * (2ull * cfg.hidden + qkv_rows * cfg.hidden +
                                       (uint64_t)cfg.hidden * cfg.n_q_heads * cfg.head_dim +
-                                      3ull * cfg.ffn * cfg.hidden);
+                                      (cfg.n_experts ? (uint64_t)cfg.n_experts * cfg.hidden
+                                                     : 3ull * cfg.ffn * cfg.hidden));
   g.stats.weight_bytes = wb;
+  g.stats.expert_bytes = cfg.n_experts ? 3ull * cfg.expert_ffn * cfg.hidden * 2 : 0;
   g.stats.kv_row_bytes = (uint64_t)cfg.n_layers * 2 * cfg.n_kv_heads * cfg.head_dim * 2;
   return MPK_OK;
 }

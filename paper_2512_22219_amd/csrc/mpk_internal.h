@@ -24,6 +24,9 @@ enum TaskKind : uint16_t {
   TK_ATTN_MERGE,
   TK_ADD,
   TK_SWIGLU,
+  TK_MOE_ROUTE,     // softmax + top-k of every token's router output, builds the meta-tensor
+  TK_MOE_EXPERT,    // a share of one expert stage (gate/up or down), sized from the meta-tensor
+  TK_MOE_COMBINE,   // weighted sum of a token's expert outputs + residual
 };
 
 enum TaskFlags : uint16_t {
@@ -92,6 +95,10 @@ struct HostOp {
   int in_tensor, in2_tensor;   // -1 if none (dependency analysis reads these)
   int body_in_tensor = -1;     // tensor the body actually loads when it differs from in_tensor
   int side_out_tensor = -1;    // second output written by the body (merged attention output)
+  int in3_tensor = -1;         // third tensor the dependency analysis reads (combine: meta-tensor)
+  // mixture-of-experts operators: the tensors the body really touches (the dependency analysis
+  // sees an expert stage's output as one element per task, see build_ops)
+  int data_in = -1, data_in2 = -1, data_out = -1, data_aux = -1;
   uint32_t align_unit = 0;     // linear: tile rows must divide this (head_dim) when non-zero
   // parameters
   uint32_t K;
@@ -131,6 +138,7 @@ struct HostGraph {
   uint32_t n_hier_events = 0;
   uint32_t lin_rows_max = 0;       // largest weight-row count of one linear task (gate/up pairs twice)
   uint32_t lin_res_rows_max = 0;   // largest column count of a linear task with a residual epilogue
+  std::vector<size_t> moe_meta_offset;   // per MoE layer: float offset of its meta-tensor in the arena
   std::vector<double> inv_freq;    // RoPE frequencies theta^(-2i/d), i < d/2
   mpk_stats stats{};
 };
@@ -142,6 +150,18 @@ mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs*
                              const mpk_kv_ptrs* kv, const mpk_compile_options& opt, HostGraph& g);
 mpk_status build_dag_graph(uint32_t n_tasks, const uint32_t* pairs, size_t n_pairs,
                            const mpk_compile_options& opt, HostGraph& g);
+
+// Meta-tensor of one mixture-of-experts layer (Section 6.4), 32-bit words, E experts, P = batch x
+// top_k (token, rank) pairs; pair p = token * top_k + rank, ranks in ascending expert index:
+//   [0] number of active experts   [1] largest token count of one expert
+//   [2 .. 2+E)        active experts, ascending
+//   [2+E .. 2+2E)     tokens per expert
+//   [2+2E .. 2+3E)    first entry of each expert in the pair list
+//   [2+3E .. +P)      pair list, sorted by (expert, token)
+//   [2+3E+P .. +P)    combine weight of pair p (float)
+//   [2+3E+2P .. +P)   expert of pair p
+inline uint32_t moe_meta_words(uint32_t E, uint32_t P) { return 2 + 3 * E + 3 * P; }
+constexpr uint32_t kMoeMaxExperts = 512, kMoeMaxPairs = 256, kMoeMaxTopK = 16;
 
 // LDS layout constants shared with the kernels
 constexpr uint32_t kThreads = 512;        // worker workgroup size (8 wavefronts, two per SIMD)

@@ -123,7 +123,7 @@ __device__ __forceinline__ void trace_mark(const StepArgs& a, const TaskDesc& t,
   if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)t.pad * kTraceSlots + slot] = wall_clock64();
 }
 
-enum DevErr : uint32_t { DE_NONE = 0, DE_TIMEOUT = 1, DE_BAD_POSITION = 2, DE_BAD_TOKEN = 3 };
+enum DevErr : uint32_t { DE_NONE = 0, DE_TIMEOUT = 1, DE_BAD_POSITION = 2, DE_BAD_TOKEN = 3, DE_BAD_META = 4 };
 
 // ------------------------------------------------------------------------------ device helpers
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
@@ -172,6 +172,9 @@ __device__ __forceinline__ void st_act(float* p, float v) {
 __device__ __forceinline__ float2 ld_act2(const float* p) {   // p 8-byte aligned
   uint64_t u = __hip_atomic_load(as_global((const uint64_t*)p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   return make_float2(__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32)));
+}
+__device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p) {
+  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void st_act_u32(uint32_t* p, uint32_t v) {
   __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -756,6 +759,335 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
   }
   lds_barrier();   // the partial buffer is reused by the next task
   return true;
+}
+
+// ------------------------------------------------------------------------------ mixture of experts
+// Section 6.4: an MoE block is a chain of tasks in the same graph.  `route` turns the router's
+// output into the meta-tensor (layout next to moe_meta_words); expert tasks are fixed at compile
+// time and use the meta-tensor to split the active experts' weight rows evenly among themselves
+// at run time; token rows are gathered while the input is staged (no separate gather step).
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = min(v, (uint32_t)__shfl_xor((int)v, off, 64));
+  return v;
+}
+
+// One task.  Softmax over all experts in fp32, the top_k largest probabilities (ties: lower expert
+// index), renormalised to sum one; ranks of a token's experts are in ascending expert index.
+__device__ __forceinline__ void body_moe_route(const TaskDesc& t, const StepArgs& a, float* lds) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t E = t.p0, TK = t.p1, B = t.p2, P = B * TK;
+  uint32_t* sel = (uint32_t*)lds;          // [P] expert of pair p
+  float* wsel = lds + P;                   // [P] weight of pair p
+  uint32_t* cnt = (uint32_t*)(lds + 2 * P);   // [E]
+  uint32_t* off = cnt + E;                 // [E]
+  uint32_t* misc = off + E;                // [0] active experts, [1] largest count
+  uint32_t* meta = (uint32_t*)t.out;
+  constexpr int kPerLane = (int)(kMoeMaxExperts / 64);
+  for (uint32_t p2 = threadIdx.x; p2 < P; p2 += kThreads) {   // a token whose router output is not finite selects nothing
+    sel[p2] = 0xFFFFFFFFu;
+    wsel[p2] = 0.f;
+  }
+  lds_barrier();
+  for (uint32_t tok = wave; tok < B; tok += kThreads / 64) {
+    float pr[kPerLane];
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < kPerLane; ++i) {
+      const uint32_t e = (uint32_t)lane + 64u * i;
+      pr[i] = e < E ? ld_act(t.in + (size_t)tok * t.ld_in + e) : -INFINITY;
+      m = fmaxf(m, pr[i]);
+    }
+    m = wave_max(m);
+    float l = 0.f;
+#pragma unroll
+    for (int i = 0; i < kPerLane; ++i) {
+      const uint32_t e = (uint32_t)lane + 64u * i;
+      pr[i] = e < E ? expf(pr[i] - m) : 0.f;
+      l += pr[i];
+    }
+    l = wave_sum(l);
+#pragma unroll
+    for (int i = 0; i < kPerLane; ++i) pr[i] = pr[i] / l;
+    uint32_t taken = 0;   // bit i: this lane's expert lane + 64 i is selected
+    for (uint32_t j = 0; j < TK; ++j) {
+      float best = -1.f;
+      uint32_t best_e = 0xFFFFFFFFu;
+#pragma unroll
+      for (int i = 0; i < kPerLane; ++i) {
+        const uint32_t e = (uint32_t)lane + 64u * i;
+        if (e < E && !((taken >> i) & 1u) && pr[i] > best) { best = pr[i]; best_e = e; }   // ascending e: ties keep the lower
+      }
+      const float wbest = wave_max(best);
+      const uint32_t we = wave_min_u32(best == wbest ? best_e : 0xFFFFFFFFu);
+      if (we != 0xFFFFFFFFu && (we & 63u) == (uint32_t)lane) taken |= 1u << (we >> 6);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < kPerLane; ++i) s += ((taken >> i) & 1u) ? pr[i] : 0.f;
+    s = wave_sum(s);
+    uint32_t before = 0;   // selected experts with a smaller index, so far
+#pragma unroll
+    for (int i = 0; i < kPerLane; ++i) {
+      const bool mine = (taken >> i) & 1u;
+      const uint64_t mask = __ballot(mine);
+      if (mine) {
+        const uint32_t rank = before + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+        sel[tok * TK + rank] = (uint32_t)lane + 64u * i;
+        wsel[tok * TK + rank] = pr[i] / s;
+      }
+      before += (uint32_t)__popcll(mask);
+    }
+  }
+  lds_barrier();
+  for (uint32_t e = threadIdx.x; e < E; e += kThreads) {
+    uint32_t c = 0;
+    for (uint32_t p2 = 0; p2 < P; ++p2) c += sel[p2] == e ? 1u : 0u;
+    cnt[e] = c;
+  }
+  lds_barrier();
+  if (threadIdx.x == 0) {
+    uint32_t run = 0, na = 0, mx = 0;
+    for (uint32_t e = 0; e < E; ++e) {
+      const uint32_t c = cnt[e];
+      off[e] = run;
+      run += c;
+      mx = max(mx, c);
+      if (c) st_act_u32(meta + 2 + na++, e);
+    }
+    misc[0] = na;
+    misc[1] = mx;
+    st_act_u32(meta, na);
+    st_act_u32(meta + 1, mx);
+  }
+  lds_barrier();
+  for (uint32_t e = threadIdx.x; e < E; e += kThreads) {
+    st_act_u32(meta + 2 + E + e, cnt[e]);
+    st_act_u32(meta + 2 + 2 * E + e, off[e]);
+    uint32_t o = off[e];
+    if (cnt[e])
+      for (uint32_t p2 = 0; p2 < P; ++p2)
+        if (sel[p2] == e) st_act_u32(meta + 2 + 3 * E + o++, p2);   // ascending pair = ascending token
+  }
+  for (uint32_t p2 = threadIdx.x; p2 < P; p2 += kThreads) {
+    st_act_u32(meta + 2 + 3 * E + P + p2, __float_as_uint(wsel[p2]));
+    st_act_u32(meta + 2 + 3 * E + 2 * P + p2, sel[p2]);
+  }
+}
+
+// Floats of LDS the input tiles (or the partial tiles that reuse them) of an expert job take.
+__device__ __forceinline__ uint32_t moe_x_floats(uint32_t batch) {
+  const uint32_t t8 = 2u * min(batch, 8u) * (2048u + 8u);
+  const uint32_t t16 = batch > 8u ? 2u * batch * (1024u + 8u) : 0u;
+  return max(max(t8, t16), 8u * 4u * 256u);
+}
+
+// `ntile` 16-row tiles of one expert's weight matrix, starting at tile `tile0`, times the `ne`
+// token rows routed to that expert: the matrix-core scheme of linear_task_mfma with the input rows
+// gathered through the expert's pair list.  All wavefronts take part; ntile <= 32, ne <= 16.
+__device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs& a, float* lds, const uint16_t* W,
+                                               uint32_t tile0, uint32_t ntile, uint32_t ne, const uint32_t* plist,
+                                               uint32_t TK) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t K = t.K;
+  const uint32_t gateup = (t.flags & TF_GATEUP) ? 1u : 0u;
+  const bool pro_norm = t.flags & TF_PRO_NORM;
+  const uint32_t Kt = mfma_ktile(ne), xstride = Kt + 8u, xplane = ne * xstride;
+  uint16_t* xh = (uint16_t*)lds;
+  uint16_t* xl = xh + 2 * (size_t)xplane;
+  float* part = lds;
+  float* ssq = lds + moe_x_floats(a.g->batch);   // [8][16]
+  uint32_t* rowidx = (uint32_t*)(ssq + 8 * 16);  // [16] pair of each staged row
+  if (threadIdx.x < ne) rowidx[threadIdx.x] = ld_relaxed(plist + threadIdx.x);
+  lds_barrier();
+  uint32_t nrt2 = 1;
+  while (nrt2 < ntile && nrt2 < 8u) nrt2 <<= 1;
+  const uint32_t ks = 8u / nrt2, my_slice = wave / nrt2, my_rt0 = wave % nrt2, slice_len = Kt / ks;
+  const uint32_t frow = lane & 15u, fk = (uint32_t)(lane >> 4) * 8u;
+  f32x4 acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  constexpr int kRound = 16;
+  u32x4 wfrag[kRound];
+  auto row_ptr = [&](uint32_t rt) {
+    const uint32_t r = (tile0 + rt) * 16u + frow;   // row of the expert's gate/up-interleaved (or plain) order
+    const uint32_t wrow = gateup ? ((r >> 1) + ((r & 1u) ? t.p0 : 0u)) : r;
+    return W + (size_t)wrow * K + fk;
+  };
+  auto request = [&](const uint16_t* wp, uint32_t k0, uint32_t kk) {
+#pragma unroll
+    for (int q = 0; q < kRound; ++q) {
+      const uint32_t k = min(k0 + kk + q * 32u, K - fk - 8u);
+      wfrag[q] = ld_stream16(wp + k);
+    }
+  };
+  float ssacc[16];
+#pragma unroll
+  for (int b = 0; b < 16; ++b) ssacc[b] = 0.f;
+  const uint16_t* gain = (const uint16_t*)t.w2;
+  const uint32_t ntk = (K + Kt - 1u) / Kt, half = Kt / 2, npairs = ne * half;
+  float2 sv[16];
+  auto stage_issue = [&](uint32_t tile) {
+    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const uint32_t p = q * kThreads + threadIdx.x;
+      const uint32_t b = p / half, i = p - b * half;
+      sv[q] = make_float2(0.f, 0.f);
+      if (p < npairs && 2 * i < klen) {
+        const uint32_t pair = rowidx[b];
+        const uint32_t row = gateup ? pair / TK : pair;   // gate/up reads the token's row, down the pair's
+        sv[q] = ld_act2(t.in + (size_t)row * t.ld_in + k0 + 2 * i);
+      }
+    }
+  };
+  auto stage_write = [&](uint32_t tile) {
+    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
+    uint16_t* dh = xh + (size_t)(tile & 1u) * xplane;
+    uint16_t* dl = xl + (size_t)(tile & 1u) * xplane;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const uint32_t p = q * kThreads + threadIdx.x;
+      if (p < npairs) {
+        const uint32_t b = p / half, i = p - b * half;
+        float2 w2 = sv[q];
+        if (pro_norm && 2 * i < klen) {
+          const float sq = fmaf(w2.x, w2.x, w2.y * w2.y);
+#pragma unroll
+          for (int bb = 0; bb < 16; ++bb) ssacc[bb] += (b == (uint32_t)bb) ? sq : 0.f;
+          const uint32_t g2 = *as_global((const uint32_t*)(gain + k0 + 2 * i));
+          w2.x *= bf16_lo(g2);
+          w2.y *= bf16_hi(g2);
+        }
+        const uint16_t h0 = f32_to_bf16(w2.x), h1 = f32_to_bf16(w2.y);
+        const uint16_t l0 = f32_to_bf16(w2.x - bf16_to_f32(h0)), l1 = f32_to_bf16(w2.y - bf16_to_f32(h1));
+        *(uint32_t*)(dh + (size_t)b * xstride + 2 * i) = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        *(uint32_t*)(dl + (size_t)b * xstride + 2 * i) = (uint32_t)l0 | ((uint32_t)l1 << 16);
+      }
+    }
+  };
+  stage_issue(0);
+  stage_write(0);
+  lds_barrier();
+  for (uint32_t tile = 0; tile < ntk; ++tile) {
+    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
+    if (tile + 1 < ntk) stage_issue(tile + 1);
+    const uint16_t* ch = xh + (size_t)(tile & 1u) * xplane;
+    const uint16_t* cl = xl + (size_t)(tile & 1u) * xplane;
+    const uint32_t s_lo = my_slice * slice_len, s_hi = min(s_lo + slice_len, (klen + 31u) & ~31u);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t rt = my_rt0 + (uint32_t)j * 8u;
+      if (rt < ntile && (ks == 1u || j == 0) && s_lo < s_hi) {
+        const uint16_t* wp = row_ptr(rt);
+        const uint16_t* bh = ch + (size_t)(frow % ne) * xstride + fk;
+        const uint16_t* bl = cl + (size_t)(frow % ne) * xstride + fk;
+        for (uint32_t kk = s_lo; kk < s_hi; kk += 32u * kRound) {
+          request(wp, k0, kk);
+#pragma unroll
+          for (int q = 0; q < kRound; ++q) {
+            if (kk + q * 32u < s_hi) {
+              const u32x4 bhv = *(const u32x4*)(bh + kk + q * 32u), blv = *(const u32x4*)(bl + kk + q * 32u);
+              const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q]);
+              acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bhv), acc[j], 0, 0, 0);
+              acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, blv), acc[j], 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+    if (tile + 1 < ntk) stage_write(tile + 1);
+    lds_barrier();
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) part[((wave * 4 + j) * 16 + (lane >> 4) * 4 + i) * 16 + (lane & 15)] = acc[j][i];
+  if (pro_norm) {
+#pragma unroll
+    for (int b = 0; b < 16; ++b) {
+      const float v = wave_sum(ssacc[b]);
+      if (lane == 0) ssq[wave * 16 + b] = v;
+    }
+  }
+  lds_barrier();
+  auto dot_of = [&](uint32_t r, uint32_t bb) {
+    const uint32_t rt = r >> 4, row = r & 15u;
+    float v = 0.f;
+    if (ks == 1u) {
+      v = part[(((rt & 7u) * 4 + (rt >> 3)) * 16 + row) * 16 + bb];
+    } else {
+      for (uint32_t sl = 0; sl < ks; ++sl) v += part[(((sl * nrt2 + rt) * 4) * 16 + row) * 16 + bb];
+    }
+    return v;
+  };
+  const uint32_t ncols = (ntile * 16u) >> gateup, col0 = (tile0 * 16u) >> gateup;
+  for (uint32_t i = threadIdx.x; i < ncols * ne; i += kThreads) {
+    const uint32_t cc = i / ne, bb = i % ne;
+    float inv = 1.0f;
+    if (pro_norm) {
+      float ss = 0.f;
+#pragma unroll
+      for (int w = 0; w < 8; ++w) ss += ssq[w * 16 + bb];
+      inv = 1.0f / sqrtf(ss / (float)K + t.f0);
+    }
+    float v;
+    if (gateup) {
+      const float gte = dot_of(2 * cc, bb) * inv, up = dot_of(2 * cc + 1, bb) * inv;
+      v = gte / (1.0f + expf(-gte)) * up;
+    } else {
+      v = dot_of(cc, bb);
+    }
+    st_act(t.out + (size_t)rowidx[bb] * t.ld_out + col0 + cc, v);
+  }
+  lds_barrier();   // the next job reuses the buffers
+}
+
+// Expert task `c0` of `p1`: the active experts' 16-row weight tiles, laid end to end in ascending
+// expert order, are dealt evenly to the expert tasks (the run-time refinement of Section 6.4);
+// a task's share is worked off in jobs of at most 32 tiles that stay inside one expert.
+__device__ __forceinline__ void body_moe_expert(const TaskDesc& t, const StepArgs& a, float* lds) {
+  const uint32_t* meta = (const uint32_t*)t.in2;
+  const uint32_t E = t.p3 & 0xFFFFu, TK = t.p3 >> 16, NT = t.p1, rows_per_expert = t.p2;
+  const uint32_t tiles_per_expert = rows_per_expert / 16u;
+  const uint32_t n_active = __builtin_amdgcn_readfirstlane(ld_relaxed(meta));
+  const uint32_t total = n_active * tiles_per_expert;
+  uint32_t u0 = (uint32_t)((uint64_t)total * t.c0 / NT);
+  const uint32_t u1 = (uint32_t)((uint64_t)total * (t.c0 + 1u) / NT);
+  while (u0 < u1) {
+    const uint32_t ai = u0 / tiles_per_expert, tile0 = u0 % tiles_per_expert;
+    const uint32_t ntile = min(min(u1 - u0, tiles_per_expert - tile0), 32u);
+    const uint32_t e = __builtin_amdgcn_readfirstlane(ld_relaxed(meta + 2 + ai));
+    const uint32_t ne = __builtin_amdgcn_readfirstlane(ld_relaxed(meta + 2 + E + e));
+    const uint32_t po = __builtin_amdgcn_readfirstlane(ld_relaxed(meta + 2 + 2 * E + e));
+    if (e >= E || ne == 0 || ne > 16u || po + ne > a.g->batch * TK) {   // never index with a damaged meta-tensor
+      if (threadIdx.x == 0) report(a, DE_BAD_META, e, ne);
+      return;
+    }
+    const uint16_t* W = (const uint16_t*)t.w + (size_t)e * rows_per_expert * t.K;
+    moe_expert_job(t, a, lds, W, tile0, ntile, ne, meta + 2 + 3 * E + po, TK);
+    u0 += ntile;
+  }
+}
+
+// out[b][c] = resid[b][c] + sum over the token's experts, in ascending expert index, of
+// weight x expert output.
+__device__ __forceinline__ void body_moe_combine(const TaskDesc& t, const StepArgs& a) {
+  const uint32_t E = t.p0, TK = t.p1, P = a.g->batch * TK, H = t.ld_out;
+  const uint32_t* meta = (const uint32_t*)t.aux0;
+  for (uint32_t b = t.b0; b < t.b1; ++b) {
+    for (uint32_t c = t.c0 + threadIdx.x; c < t.c1; c += kThreads) {
+      float acc = 0.f;
+      for (uint32_t k = 0; k < TK; ++k) {
+        const uint32_t p = b * TK + k;
+        const float wk = __uint_as_float(ld_relaxed(meta + 2 + 3 * E + P + p));
+        acc = fmaf(wk, ld_act(t.in + (size_t)p * t.ld_in + c), acc);
+      }
+      st_act(t.out + (size_t)b * H + c, ld_act(t.in2 + (size_t)b * H + c) + acc);
+    }
+  }
 }
 
 // cos and sin of position * inv_freq[i]: the angle is formed and reduced to [-pi, pi] in double.
@@ -1440,15 +1772,15 @@ __device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, f
     case TK_ATTN_MERGE: body_attn_merge(t, a); break;
     case TK_ADD: body_add(t); break;
     case TK_SWIGLU: body_swiglu(t); break;
+    case TK_MOE_ROUTE: body_moe_route(t, a, lds); break;
+    case TK_MOE_EXPERT: body_moe_expert(t, a, lds); break;
+    case TK_MOE_COMBINE: body_moe_combine(t, a); break;
     default: break;   // TK_DUMMY: no computation (normalization, Section 4.1)
   }
   return true;
 }
 
 // ------------------------------------------------------------------------------ runtime
-__device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p) {
-  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 // Returns false when the step is being aborted (watchdog or a peer's failure).
 // Simple events: wait until counter >= epoch * required.  Hierarchical events: wait until this
@@ -1808,7 +2140,7 @@ struct KernelVariant {
 #define MPK_VARIANT(D, G, N) {D, G, N, mpk_mega_kernel<D, G, N>, mpk_op_kernel<D, G, N>}
 static const KernelVariant kVariants[] = {
     MPK_VARIANT(64, 2, 1), MPK_VARIANT(128, 4, 1), MPK_VARIANT(128, 8, 1),
-    MPK_VARIANT(128, 4, 8), MPK_VARIANT(0, 0, 0),
+    MPK_VARIANT(128, 4, 8), MPK_VARIANT(128, 8, 8), MPK_VARIANT(0, 0, 0),
 };
 static const KernelVariant* pick_variant(uint32_t d, uint32_t grp, uint32_t batch) {
   int nb = batch == 1 ? 1 : (batch > 4 && batch <= 16 ? 8 : -1);
@@ -1966,6 +2298,8 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
     t.in = reloc(t.in);
     t.in2 = reloc(t.in2);
     t.out = const_cast<float*>(reloc(t.out));
+    if (t.kind == TK_MOE_ROUTE || t.kind == TK_MOE_EXPERT || t.kind == TK_MOE_COMBINE)
+      t.aux0 = (void*)reloc((const float*)t.aux0);
   }
   // per-operator task lists (baseline launch mode)
   std::vector<uint32_t> op_list;
@@ -2112,6 +2446,9 @@ extern "C" mpk_status mpk_graph_status(mpk_graph* g) {
     case DE_BAD_TOKEN:
       set_error("sequence %u has token %d outside [0, vocab)", err[2], (int)err[3]);
       return MPK_ERR_DEVICE;
+    case DE_BAD_META:
+      set_error("an expert task found an inconsistent meta-tensor (expert %u, %u tokens)", err[2], err[3]);
+      return MPK_ERR_DEVICE;
     default: set_error("unknown device error %u", err[0]); return MPK_ERR_DEVICE;
   }
 }
@@ -2163,6 +2500,33 @@ extern "C" mpk_status mpk_graph_trace(mpk_graph* g, uint64_t* buf, size_t cap, s
   if (!buf) return MPK_OK;
   if (cap < n) { set_error("trace buffer too small: %zu < %zu", cap, n); return MPK_ERR_INVALID_ARG; }
   HIP_TRY(hipMemcpy(buf, g->d_trace, n * sizeof(uint64_t), hipMemcpyDeviceToHost));
+  return MPK_OK;
+}
+
+extern "C" mpk_status mpk_graph_moe_active(mpk_graph* g, uint32_t* out, size_t cap, size_t* need) {
+  if (!g) { set_error("NULL graph"); return MPK_ERR_INVALID_ARG; }
+  if (g->host_only || g->h.moe_meta_offset.empty()) { set_error("not a mixture-of-experts graph on a device"); return MPK_ERR_INVALID_ARG; }
+  const size_t n = g->h.moe_meta_offset.size();
+  if (need) *need = n;
+  if (!out) return MPK_OK;
+  if (cap < n) { set_error("buffer too small: %zu < %zu", cap, n); return MPK_ERR_INVALID_ARG; }
+  for (size_t l = 0; l < n; ++l)
+    HIP_TRY(hipMemcpy(out + l, g->d_arena + g->h.moe_meta_offset[l], sizeof(uint32_t), hipMemcpyDeviceToHost));
+  return MPK_OK;
+}
+
+extern "C" mpk_status mpk_graph_moe_selection(mpk_graph* g, uint32_t* experts, float* weights, size_t cap, size_t* need) {
+  if (!g) { set_error("NULL graph"); return MPK_ERR_INVALID_ARG; }
+  if (g->host_only || g->h.moe_meta_offset.empty()) { set_error("not a mixture-of-experts graph on a device"); return MPK_ERR_INVALID_ARG; }
+  const size_t L = g->h.moe_meta_offset.size(), E = g->h.cfg.n_experts, P = (size_t)g->h.cfg.batch * g->h.cfg.top_k;
+  if (need) *need = L * P;
+  if (!experts && !weights) return MPK_OK;
+  if (cap < L * P) { set_error("buffer too small: %zu < %zu", cap, L * P); return MPK_ERR_INVALID_ARG; }
+  for (size_t l = 0; l < L; ++l) {
+    const float* meta = g->d_arena + g->h.moe_meta_offset[l];
+    if (weights) HIP_TRY(hipMemcpy(weights + l * P, meta + 2 + 3 * E + P, P * sizeof(float), hipMemcpyDeviceToHost));
+    if (experts) HIP_TRY(hipMemcpy(experts + l * P, meta + 2 + 3 * E + 2 * P, P * sizeof(uint32_t), hipMemcpyDeviceToHost));
+  }
   return MPK_OK;
 }
 

@@ -59,8 +59,16 @@ def compiled_producer_sets(ex):
     return psets
 
 
+def moe_tasks_of(ex):
+    """Expert tasks per expert stage of a compiled mixture-of-experts graph (0 for a dense one)."""
+    for eo in ex.ops:
+        if eo["kind"] == TG.K_EXPERT:
+            return int(eo["cols"])
+    return 0
+
+
 def oracle_ops_and_degrees(shape, ex, fusion, attn_chunks):
-    ops = TG.build_ops(shape, fusion, attn_chunks)
+    ops = TG.build_ops(shape, fusion, attn_chunks, moe_tasks_of(ex))
     assert len(ops) == len(ex.ops), (len(ops), len(ex.ops))
     for o, eo in zip(ops, ex.ops):
         assert o.kind == eo["kind"] and o.layer == eo["layer"], (o.name, o.kind, eo["kind"])

@@ -41,6 +41,10 @@ CASES = [
     ("C3", dict(n_layers=1), dict(fusion=7)),
     ("C1", dict(batch=2), dict(fusion=31, n_workers=24, attn_chunks=3)),
     ("C2", dict(n_layers=2), dict(fusion=31)),
+    # mixture-of-experts blocks
+    ("C1", dict(batch=2, ffn=0, n_experts=8, top_k=2, expert_ffn=64), dict(fusion=0, n_workers=12)),
+    ("C1", dict(batch=3, ffn=0, n_experts=16, top_k=4, expert_ffn=32), dict(fusion=31, n_workers=24, tiles_moe=10)),
+    ("C4", dict(n_layers=1), dict(fusion=31)),
 ]
 
 
@@ -75,7 +79,7 @@ def closure_by_op_tile(psets):
     return {(o, t): go((o, t)) for o in range(len(psets)) for t in range(len(psets[o]))}
 
 
-@pytest.mark.parametrize("base,variant,opts", CASES[:5] + CASES[8:])
+@pytest.mark.parametrize("base,variant,opts", CASES[:5] + CASES[8:12])
 def test_transitive_reduction_keeps_closures(base, variant, opts):
     shape = G.small_variant(base, **variant)
     g = host_graph(shape, transitive_reduction=1, **opts)

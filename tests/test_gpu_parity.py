@@ -189,3 +189,67 @@ def test_device_errors_are_reported_not_fatal():
     want = D.DecoderOracle(s, G.SynthWeights(s, 0), "f32").step(tok, G.kv_lengths(0, s))
     assert rel_err(gpu.step(tok, G.kv_lengths(0, s)), want) < TOL
     gpu.close()
+
+
+# ------------------------------------------------------------------ mixture of experts
+def _check_routing(gpu, ref, s):
+    """Selected expert sets and combine weights of the last step, layer by layer.  Where the
+    oracle's top_k-th and next router outputs are closer than 1e-5 either set is accepted (top-k
+    is discontinuous); returns the number of such decisions."""
+    ex, wt = gpu.graph.moe_selection()
+    ex = ex.reshape(s.n_layers, s.batch, s.top_k).astype(np.int64)
+    ambiguous = 0
+    for l in range(s.n_layers):
+        for b in range(s.batch):
+            want = ref.last_moe_sel[l, b].tolist()
+            got = ex[l, b].tolist()
+            assert got == sorted(got) and len(set(got)) == s.top_k
+            if got != want:
+                r = np.sort(ref.last_moe_logits[l, b].astype(np.float64))[::-1]
+                assert r[s.top_k - 1] - r[s.top_k] < 1e-5, (l, b, got, want)
+                ambiguous += 1
+    wt = wt.reshape(s.n_layers, s.batch, s.top_k)
+    assert np.allclose(wt.sum(-1), 1.0, atol=1e-5)
+    return ambiguous
+
+
+MOE_CASES = [
+    (dict(batch=1, n_experts=8, top_k=2, expert_ffn=64), dict(fusion=0)),
+    (dict(batch=2, n_experts=8, top_k=2, expert_ffn=64), dict(fusion=0, launch_mode=1)),
+    (dict(batch=3, n_experts=16, top_k=4, expert_ffn=96), dict(fusion=31, transitive_reduction=1)),
+    (dict(batch=16, n_experts=32, top_k=8, expert_ffn=160), dict(fusion=31, transitive_reduction=1)),
+    (dict(batch=16, n_experts=128, top_k=8, expert_ffn=768, hidden=512, n_q_heads=8, n_kv_heads=1,
+          head_dim=64), dict(fusion=31, transitive_reduction=1)),
+    (dict(batch=5, n_experts=12, top_k=3, expert_ffn=40), dict(fusion=7, n_workers=37, tiles_moe=9)),
+    (dict(batch=16, n_experts=32, top_k=8, expert_ffn=160),
+     dict(fusion=31, transitive_reduction=1, launch_mode=1)),
+    (dict(batch=4, n_experts=16, top_k=4, expert_ffn=96),
+     dict(fusion=31, transitive_reduction=1, n_sched_wgs=2)),
+]
+
+
+@pytest.mark.parametrize("variant,opts", MOE_CASES)
+def test_moe_three_steps_match_oracle(variant, opts):
+    """Router, top-k routing, expert stages sized at run time from the meta-tensor, combine
+    (Section 6.4), on small mixture-of-experts models: logits and routing decisions of three
+    teacher-forced steps with ragged positions."""
+    s = G.small_variant("C1", ffn=0, **variant)
+    rng = np.random.default_rng(7)
+    pos = rng.integers(60, 128, s.batch)
+    tok = rng.integers(0, s.vocab, s.batch)
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 1), "f32")
+    gpu = GpuDecoder(s, 1, **opts)
+    for step in range(3):
+        want = ref.step(tok, pos)
+        got = gpu.step(tok, pos)
+        assert np.isfinite(got).all()
+        ambiguous = _check_routing(gpu, ref, s)
+        if ambiguous == 0:
+            assert rel_err(got, want) < TOL, step
+            assert np.abs(got - want).max() / np.abs(want).max() < 1e-4
+        active = gpu.graph.moe_active()
+        sel = ref.last_moe_sel
+        assert ambiguous or active.tolist() == [len(np.unique(sel[l])) for l in range(s.n_layers)]
+        tok = want.argmax(-1)
+        pos = pos + 1
+    gpu.close()

@@ -251,6 +251,73 @@ def test_layer_is_identity_when_wo_and_wd_zero():
     assert np.allclose(lg[0], unbf(prov.lm).astype(np.float64) @ xn, rtol=1e-4, atol=1e-5)
 
 
+def _moe_shape(**kw):
+    base = dict(ffn=0, n_experts=4, top_k=2, expert_ffn=688)
+    base.update(kw)
+    return G.small_variant("C1", **base)
+
+
+def test_moe_block_with_identical_experts_is_the_dense_mlp():
+    """Special case that reduces to the pinned dense layer: if every expert carries the dense
+    MLP's matrices, the renormalised weights (sum one) make the block equal to the dense MLP,
+    whatever the router picks."""
+    dense = G.CONFIGS["C1"]
+    s = _moe_shape(n_experts=4, top_k=2, expert_ffn=dense.ffn)
+    pd = synth_provider_as_dict(dense)
+    pm = synth_provider_as_dict(s)
+    for l in range(s.n_layers):
+        w = pm.layers[l]
+        for k in (G.L_ATTN_NORM, G.L_WQKV, G.L_WO, G.L_MLP_NORM):
+            w[k] = pd.layers[l][k]
+        w[G.L_EXP_WGU] = np.tile(pd.layers[l][G.L_WGU], (s.n_experts, 1))
+        w[G.L_EXP_WD] = np.tile(pd.layers[l][G.L_WD], (s.n_experts, 1))
+    pm.kv = pd.kv
+    tok, pos = G.tokens(0, dense), G.kv_lengths(0, dense)
+    for prec, tol in (("f32", 2e-6), ("f64", 1e-12)):
+        a = D.DecoderOracle(dense, pd, prec).step(tok, pos, return_hidden=True)
+        b = D.DecoderOracle(s, pm, prec).step(tok, pos, return_hidden=True)
+        assert np.abs(a - b).max() <= tol * np.abs(a).max()
+
+
+def test_moe_block_closed_form_in_float64():
+    """One layer, attention switched off (Wo = 0): x' = x + sum_k w_k Wd_e(silu(Wg_e xn) * Wu_e xn)
+    with the experts and weights recomputed here from the router matrix with numpy."""
+    s = _moe_shape(n_layers=1, n_experts=8, top_k=3, expert_ffn=96)
+    prov = synth_provider_as_dict(s, zero=(G.L_WO,))
+    o = D.DecoderOracle(s, prov, "f64")
+    tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
+    hid = o.step(tok, pos, return_hidden=True)[0]
+    w = prov.layers[0]
+    x = unbf(prov.E[tok[0]]).astype(np.float64)
+    xn = x / np.sqrt((x * x).mean() + s.rms_eps) * unbf(w[G.L_MLP_NORM]).astype(np.float64).ravel()
+    r = unbf(w[G.L_ROUTER]).astype(np.float64) @ xn
+    pr = np.exp(r - r.max())
+    pr /= pr.sum()
+    top = np.sort(np.argsort(-pr, kind="stable")[:s.top_k])
+    assert o.last_moe_sel[0, 0].tolist() == top.tolist()
+    assert np.allclose(o.last_moe_logits[0, 0], r, rtol=1e-9, atol=1e-11)
+    F, H = s.expert_ffn, s.hidden
+    y = np.zeros(H)
+    for e in top:
+        wgu = unbf(w[G.L_EXP_WGU][e * 2 * F:(e + 1) * 2 * F]).astype(np.float64)
+        wd = unbf(w[G.L_EXP_WD][e * H:(e + 1) * H]).astype(np.float64)
+        gu = wgu @ xn
+        h = gu[:F] / (1 + np.exp(-gu[:F])) * gu[F:]
+        y += pr[e] / pr[top].sum() * (wd @ h)
+    assert np.allclose(hid, x + y, rtol=1e-8, atol=1e-10)
+    # dropping the renormalisation, a wrong expert order or a transposed expert slice would show:
+    assert np.abs(y).max() > 1e-4
+
+
+def test_moe_top_k_equal_to_all_experts_uses_plain_softmax_weights():
+    s = _moe_shape(n_layers=1, n_experts=4, top_k=4, expert_ffn=64)
+    prov = synth_provider_as_dict(s, zero=(G.L_WO,))
+    o = D.DecoderOracle(s, prov, "f64")
+    tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
+    o.step(tok, pos)
+    assert o.last_moe_sel[0, 0].tolist() == [0, 1, 2, 3]
+
+
 def test_f32_oracle_close_to_f64_oracle():
     s = G.CONFIGS["C1"]
     tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
