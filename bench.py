@@ -1,6 +1,7 @@
 #!/usr/bin/env python3
 """Decode benchmark on one MI355X.  Default workload: the Qwen3-8B-shaped config, batch 1, KV
-1024, greedy steps (--config C3: Llama-3-8B-shaped, batch 8, ragged KV; --config C5: 70B-shaped).
+1024, greedy steps (--config C3: Llama-3-8B-shaped, batch 8, ragged KV; --config C4: Qwen3-30B-A3B-
+shaped mixture of experts, batch 16; --config C5: 70B-shaped).
 
 A "step" is one decode step through the persistent mega-kernel (mpk_decode_step) followed by the
 greedy token feedback (arg max on the device, no host sync).  Prints ONE JSON line.
@@ -144,6 +145,22 @@ def main():
     # step; averaged over the timed steps)
     pos_avg = float(pos0.float().sum()) + shape.batch * (args.warmup + (args.steps - 1) / 2 + 1)
     bytes_step = stats["weight_bytes"] + stats["kv_row_bytes"] * pos_avg
+    moe_active_avg = None
+    if stats["expert_bytes"]:
+        # mixture of experts: a step streams only the experts it selected.  Replay the same greedy
+        # trajectory off the clock and read the number of distinct experts per layer after
+        # every step.
+        tok.copy_(tok0)
+        pos.copy_(pos0)
+        model.reset_kv()
+        counts = []
+        for i in range(args.warmup + args.steps):
+            run(mega, 1)
+            torch.cuda.synchronize()
+            if i >= args.warmup:
+                counts.append(int(mega.moe_active().sum()))
+        moe_active_avg = sum(counts) / len(counts)
+        bytes_step += stats["expert_bytes"] * moe_active_avg
     kern_avg_ms = sum(kern_ms) / len(kern_ms)
     achieved = bytes_step / (kern_avg_ms * 1e-3) / 1e9
     out = {
@@ -159,7 +176,8 @@ def main():
                                + " prior positions, greedy decode",
                    "launch": "persistent mega-kernel", "fusion": args.fusion,
                    "n_workers": stats["n_workers"], "tasks": stats["n_tasks"],
-                   "events": stats["n_events"]},
+                   "events": stats["n_events"],
+                   **({"distinct_experts_per_step": moe_active_avg} if moe_active_avg is not None else {})},
         "tokens_per_s": shape.batch * 1e3 / ms_per_step,
         "achieved_hbm_GBps": bytes_step / (ms_per_step * 1e-3) / 1e9,
         "bytes_per_step": bytes_step,

@@ -895,7 +895,7 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
       f = std::max<size_t>(std::max(t8, t16), 8 * 4 * 256) + 8 * 16 + 16;   // + sums of squares + staged row list
     }
     else if (op.kind == MPK_OP_ROUTER)
-      f = (size_t)c.batch * c.top_k * 2 + c.n_experts * 2 + 64;
+      f = (size_t)c.batch * c.top_k * 2 + (size_t)c.n_experts * (3 + 16) + 64;   // pairs | per-expert counts, offsets, masks, pair table
     else if (op.kind == MPK_OP_ATTN_PARTIAL)
       f = (size_t)grp * c.head_dim                                        // q
           + (size_t)(kThreads / 64) * grp * (c.head_dim + 2) + 16 + 64;   // per-wave partials

@@ -782,13 +782,16 @@ __device__ __forceinline__ void body_moe_route(const TaskDesc& t, const StepArgs
   float* wsel = lds + P;                   // [P] weight of pair p
   uint32_t* cnt = (uint32_t*)(lds + 2 * P);   // [E]
   uint32_t* off = cnt + E;                 // [E]
-  uint32_t* misc = off + E;                // [0] active experts, [1] largest count
+  uint32_t* tokmask = off + E;             // [E] bit b: token b is routed to the expert (batch <= 16)
+  uint32_t* pairof = tokmask + E;          // [E][16] pair index of (expert, token)
   uint32_t* meta = (uint32_t*)t.out;
   constexpr int kPerLane = (int)(kMoeMaxExperts / 64);
+  const uint32_t nper = (E + 63u) / 64u;   // experts per lane actually present (uniform)
   for (uint32_t p2 = threadIdx.x; p2 < P; p2 += kThreads) {   // a token whose router output is not finite selects nothing
     sel[p2] = 0xFFFFFFFFu;
     wsel[p2] = 0.f;
   }
+  for (uint32_t e = threadIdx.x; e < E; e += kThreads) tokmask[e] = 0u;
   lds_barrier();
   for (uint32_t tok = wave; tok < B; tok += kThreads / 64) {
     float pr[kPerLane];
@@ -796,7 +799,8 @@ __device__ __forceinline__ void body_moe_route(const TaskDesc& t, const StepArgs
 #pragma unroll
     for (int i = 0; i < kPerLane; ++i) {
       const uint32_t e = (uint32_t)lane + 64u * i;
-      pr[i] = e < E ? ld_act(t.in + (size_t)tok * t.ld_in + e) : -INFINITY;
+      pr[i] = -INFINITY;
+      if ((uint32_t)i < nper && e < E) pr[i] = ld_act(t.in + (size_t)tok * t.ld_in + e);
       m = fmaxf(m, pr[i]);
     }
     m = wave_max(m);
@@ -804,12 +808,15 @@ __device__ __forceinline__ void body_moe_route(const TaskDesc& t, const StepArgs
 #pragma unroll
     for (int i = 0; i < kPerLane; ++i) {
       const uint32_t e = (uint32_t)lane + 64u * i;
-      pr[i] = e < E ? expf(pr[i] - m) : 0.f;
+      const float lg = pr[i];
+      pr[i] = 0.f;
+      if ((uint32_t)i < nper && e < E) pr[i] = expf(lg - m);
       l += pr[i];
     }
     l = wave_sum(l);
 #pragma unroll
-    for (int i = 0; i < kPerLane; ++i) pr[i] = pr[i] / l;
+    for (int i = 0; i < kPerLane; ++i)
+      if ((uint32_t)i < nper) pr[i] = pr[i] / l;
     uint32_t taken = 0;   // bit i: this lane's expert lane + 64 i is selected
     for (uint32_t j = 0; j < TK; ++j) {
       float best = -1.f;
@@ -817,7 +824,7 @@ __device__ __forceinline__ void body_moe_route(const TaskDesc& t, const StepArgs
 #pragma unroll
       for (int i = 0; i < kPerLane; ++i) {
         const uint32_t e = (uint32_t)lane + 64u * i;
-        if (e < E && !((taken >> i) & 1u) && pr[i] > best) { best = pr[i]; best_e = e; }   // ascending e: ties keep the lower
+        if ((uint32_t)i < nper && e < E && !((taken >> i) & 1u) && pr[i] > best) { best = pr[i]; best_e = e; }   // ascending e: ties keep the lower
       }
       const float wbest = wave_max(best);
       const uint32_t we = wave_min_u32(best == wbest ? best_e : 0xFFFFFFFFu);
@@ -841,34 +848,63 @@ __device__ __forceinline__ void body_moe_route(const TaskDesc& t, const StepArgs
     }
   }
   lds_barrier();
-  for (uint32_t e = threadIdx.x; e < E; e += kThreads) {
-    uint32_t c = 0;
-    for (uint32_t p2 = 0; p2 < P; ++p2) c += sel[p2] == e ? 1u : 0u;
-    cnt[e] = c;
+  // Per-expert token lists without serial scans: a pair thread sets its token's bit in the
+  // expert's mask and leaves its pair index in the expert's row of `pairof`; the expert's list
+  // is then its mask's bits in ascending order.
+  for (uint32_t p2 = threadIdx.x; p2 < P; p2 += kThreads) {
+    const uint32_t e = sel[p2], tok = p2 / TK;
+    if (e < E) {
+      atomicOr(&tokmask[e], 1u << tok);
+      pairof[e * 16u + tok] = p2;
+    }
   }
   lds_barrier();
-  if (threadIdx.x == 0) {
-    uint32_t run = 0, na = 0, mx = 0;
-    for (uint32_t e = 0; e < E; ++e) {
-      const uint32_t c = cnt[e];
-      off[e] = run;
-      run += c;
-      mx = max(mx, c);
-      if (c) st_act_u32(meta + 2 + na++, e);
+  // offsets and the active list: exclusive scans over the experts by wavefront 0, each lane
+  // owning kPerLane consecutive experts
+  if (wave == 0) {
+    uint32_t c[kPerLane], mine = 0, act = 0, mx = 0;
+#pragma unroll
+    for (int i = 0; i < kPerLane; ++i) {
+      const uint32_t e = (uint32_t)lane * kPerLane + i;
+      c[i] = e < E ? (uint32_t)__popc(tokmask[e]) : 0u;
+      mine += c[i];
+      act += c[i] ? 1u : 0u;
+      mx = max(mx, c[i]);
     }
-    misc[0] = na;
-    misc[1] = mx;
-    st_act_u32(meta, na);
-    st_act_u32(meta + 1, mx);
+    uint32_t run = mine, arun = act;   // inclusive scans across lanes
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t v = (uint32_t)__shfl_up((int)run, d, 64), w = (uint32_t)__shfl_up((int)arun, d, 64);
+      if (lane >= d) { run += v; arun += w; }
+    }
+    uint32_t o = run - mine, ai = arun - act;
+#pragma unroll
+    for (int i = 0; i < kPerLane; ++i) {
+      const uint32_t e = (uint32_t)lane * kPerLane + i;
+      if (e < E) {
+        cnt[e] = c[i];
+        off[e] = o;
+        if (c[i]) st_act_u32(meta + 2 + ai++, e);
+        o += c[i];
+      }
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, d, 64));
+    if (lane == 63) {
+      st_act_u32(meta, arun);
+      st_act_u32(meta + 1, mx);
+    }
   }
   lds_barrier();
   for (uint32_t e = threadIdx.x; e < E; e += kThreads) {
     st_act_u32(meta + 2 + E + e, cnt[e]);
     st_act_u32(meta + 2 + 2 * E + e, off[e]);
-    uint32_t o = off[e];
-    if (cnt[e])
-      for (uint32_t p2 = 0; p2 < P; ++p2)
-        if (sel[p2] == e) st_act_u32(meta + 2 + 3 * E + o++, p2);   // ascending pair = ascending token
+    uint32_t o = off[e], m = tokmask[e];
+    while (m) {   // ascending token = ascending pair
+      const uint32_t tok = (uint32_t)__ffs((int)m) - 1u;
+      m &= m - 1u;
+      st_act_u32(meta + 2 + 3 * E + o++, pairof[e * 16u + tok]);
+    }
   }
   for (uint32_t p2 = threadIdx.x; p2 < P; p2 += kThreads) {
     st_act_u32(meta + 2 + 3 * E + P + p2, __float_as_uint(wsel[p2]));
@@ -909,7 +945,7 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
   f32x4 acc[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  constexpr int kRound = 16;
+  constexpr int kRound = 16;   // 16 KB per wavefront in flight (32 was measured slower)
   u32x4 wfrag[kRound];
   auto row_ptr = [&](uint32_t rt) {
     const uint32_t r = (tile0 + rt) * 16u + frow;   // row of the expert's gate/up-interleaved (or plain) order
@@ -1772,9 +1808,6 @@ __device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, f
     case TK_ATTN_MERGE: body_attn_merge(t, a); break;
     case TK_ADD: body_add(t); break;
     case TK_SWIGLU: body_swiglu(t); break;
-    case TK_MOE_ROUTE: body_moe_route(t, a, lds); break;
-    case TK_MOE_EXPERT: body_moe_expert(t, a, lds); break;
-    case TK_MOE_COMBINE: body_moe_combine(t, a); break;
     default: break;   // TK_DUMMY: no computation (normalization, Section 4.1)
   }
   return true;
@@ -1910,17 +1943,51 @@ __device__ __forceinline__ void signal_from_wave0(const StepArgs& a, const TaskD
 // task bodies use the rest.
 constexpr uint32_t kLdsCtrlFloats = 16;
 
+// Mixture-of-experts tasks get a function of their own as well: the expert jobs hold many
+// registers, and a function saves every callee-saved register it uses anywhere on each call, so
+// sharing run_other_task would tax every attention task with those saves.
+template <bool MEGA>
+__device__ __noinline__ bool run_moe_task(StepArgs a, uint32_t task_index, bool skip_wait) {
+  extern __shared__ __align__(16) float dyn_lds[];
+  float* lds = dyn_lds + kLdsCtrlFloats;
+  uint32_t* s_flag = (uint32_t*)dyn_lds;
+  const TaskDesc t = ld_task(a, task_index);
+  if (MEGA) {
+    const int32_t wait_ev = (!skip_wait && t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
+    trace_mark(a, t, 0);
+    if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)task_index * kTraceSlots + 5] = blockIdx.x;
+    if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
+    trace_mark(a, t, 1);
+  }
+  switch (t.kind) {
+    case TK_MOE_ROUTE: body_moe_route(t, a, lds); break;
+    case TK_MOE_EXPERT: body_moe_expert(t, a, lds); break;
+    default: body_moe_combine(t, a); break;
+  }
+  if (MEGA) {
+    trace_mark(a, t, 3);
+    if (t.trig_event >= 0) signal_event(a, t, t.trig_event);
+    else __syncthreads();
+    trace_mark(a, t, 4);
+  }
+  return true;
+}
+__device__ __forceinline__ bool is_moe_kind(uint16_t kind) { return kind >= TK_MOE_ROUTE && kind <= TK_MOE_COMBINE; }
+
 // Everything that is not a linear task runs in a function of its own (a real call): its
 // thread-index arithmetic and temporaries then get their own register allocation instead of being
 // hoisted to the top of the persistent loop, where they would crowd out the weight ring and
 // force spills of registers that have loads in flight.
 // Returns false when the step is being aborted.
-template <int D, int GRP, int NB, bool MEGA>
+template <int D, int GRP, int NB, bool MEGA, bool MOE>
 __device__ __noinline__ bool run_other_task(StepArgs a, uint32_t task_index, bool skip_wait) {
   extern __shared__ __align__(16) float dyn_lds[];
   float* lds = dyn_lds + kLdsCtrlFloats;
   uint32_t* s_flag = (uint32_t*)dyn_lds;
   const TaskDesc t = ld_task(a, task_index);
+  // kernels for dense models are built without this call: with it the function is no leaf any
+  // more and every attention task pays for that (measured: 0.1 ms per step on the 8B shape)
+  if (MOE && is_moe_kind(t.kind)) return run_moe_task<MEGA>(a, task_index, skip_wait);
   int32_t wait_ev = -1;
   if (MEGA) {
     wait_ev = (!skip_wait && t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
@@ -2066,7 +2133,7 @@ __device__ __forceinline__ uint32_t pick_task(const StepArgs& a, uint32_t* ctrl,
   return pick;
 }
 
-template <int D, int GRP, int NB>
+template <int D, int GRP, int NB, bool MOE>
 __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
   extern __shared__ __align__(16) float dyn_lds[];
   float* lds = dyn_lds + kLdsCtrlFloats;
@@ -2093,7 +2160,7 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
       } else {
         // the callee's result comes back in a vector register: make it scalar again, or the whole
         // task loop (and every descriptor load in it) turns into per-lane code
-        if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true>(a, ti, false))) break;
+        if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(a, ti, false))) break;
       }
     }
     return;
@@ -2110,7 +2177,7 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
       if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
       if (!run_linear<NB, true>(t, a, lds, -1, s_flag)) break;   // its event is already activated
     } else {
-      if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true>(a, ti, true))) break;
+      if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(a, ti, true))) break;
     }
   }
   if (threadIdx.x == 0) __hip_atomic_store(as_global(a.g->wq_head + w), jit_head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -2118,7 +2185,7 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
 
 // Kernel-per-operator baseline: the same task bodies, one launch per operator, dependencies
 // enforced by stream order (what the paper's comparison systems do, Section 6.5).
-template <int D, int GRP, int NB>
+template <int D, int GRP, int NB, bool MOE>
 __global__ void __launch_bounds__(kThreads) mpk_op_kernel(StepArgs a, uint32_t first) {
   extern __shared__ __align__(16) float dyn_lds[];
   float* lds = dyn_lds + kLdsCtrlFloats;
@@ -2127,27 +2194,29 @@ __global__ void __launch_bounds__(kThreads) mpk_op_kernel(StepArgs a, uint32_t f
   if (t.kind == TK_LINEAR) {
     run_linear<NB, false>(t, a, lds, -1, nullptr);
   } else {
-    run_other_task<D, GRP, NB, false>(a, ti, true);
+    run_other_task<D, GRP, NB, false, MOE>(a, ti, true);
   }
 }
 
 // Specialised kernel pairs; {0, 0, 0} is the generic fallback.
 struct KernelVariant {
   int d, grp, nb;
+  bool moe;
   void (*mega)(StepArgs);
   void (*op)(StepArgs, uint32_t);
 };
-#define MPK_VARIANT(D, G, N) {D, G, N, mpk_mega_kernel<D, G, N>, mpk_op_kernel<D, G, N>}
+#define MPK_VARIANT(D, G, N, M) {D, G, N, M, mpk_mega_kernel<D, G, N, M>, mpk_op_kernel<D, G, N, M>}
 static const KernelVariant kVariants[] = {
-    MPK_VARIANT(64, 2, 1), MPK_VARIANT(128, 4, 1), MPK_VARIANT(128, 8, 1),
-    MPK_VARIANT(128, 4, 8), MPK_VARIANT(128, 8, 8), MPK_VARIANT(0, 0, 0),
+    MPK_VARIANT(64, 2, 1, false), MPK_VARIANT(128, 4, 1, false), MPK_VARIANT(128, 8, 1, false),
+    MPK_VARIANT(128, 4, 8, false), MPK_VARIANT(128, 8, 8, true),
+    MPK_VARIANT(0, 0, 0, false), MPK_VARIANT(0, 0, 0, true),   // generic fallbacks, dense and mixture of experts
 };
-static const KernelVariant* pick_variant(uint32_t d, uint32_t grp, uint32_t batch) {
+static const KernelVariant* pick_variant(uint32_t d, uint32_t grp, uint32_t batch, bool moe) {
   int nb = batch == 1 ? 1 : (batch > 4 && batch <= 16 ? 8 : -1);
   const int n = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
   for (int i = 0; i < n; ++i)
-    if (kVariants[i].d == (int)d && kVariants[i].grp == (int)grp && kVariants[i].nb == nb) return &kVariants[i];
-  return &kVariants[n - 1];
+    if (kVariants[i].d == (int)d && kVariants[i].grp == (int)grp && kVariants[i].nb == nb && kVariants[i].moe == moe) return &kVariants[i];
+  return &kVariants[moe ? n - 1 : n - 2];
 }
 
 }  // namespace mpk
@@ -2273,7 +2342,7 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
   if (hipGetDevice(&g->device) != hipSuccess) { set_error("hipGetDevice failed"); return fail(MPK_ERR_HIP); }
   HostGraph& h = g->h;
   // residency: dynamic LDS above half of a CU's 160 KB caps occupancy at one workgroup per CU
-  g->kv = pick_variant(cfg->head_dim, cfg->n_q_heads / cfg->n_kv_heads, cfg->batch);
+  g->kv = pick_variant(cfg->head_dim, cfg->n_q_heads / cfg->n_kv_heads, cfg->batch, cfg->n_experts != 0);
   hipError_t e = hipFuncSetAttribute((const void*)g->kv->mega, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h.lds_bytes);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)g->kv->op, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h.lds_bytes);
   if (e != hipSuccess) { set_error("cannot reserve %u bytes of LDS: %s", h.lds_bytes, hipGetErrorString(e)); return fail(MPK_ERR_RESIDENCY); }

@@ -5,10 +5,11 @@ oracle (oracle/) on the seeded synthetic inputs (synth/).  Nothing here touches 
     python tests/golden/make_golden.py C2        # Qwen3-8B-shaped, batch 1, 32 greedy steps
 
     python tests/golden/make_golden.py C2 f64    # add the fp64 oracle's step-0 samples to C2_greedy.json
+    python tests/golden/make_golden.py C4        # mixture-of-experts: routing decisions recorded too
 
 Each fixture is a small JSON file: greedy tokens of every step, the top-8 logits (index, value)
 of every step, and 512 pseudo-randomly sampled logits of step 0 and of the last step (fp32
-oracle); "samples64_0" holds the same step-0 samples from the oracle built with fp64 arithmetic
+oracle for the dense configurations, fp64 for mixture of experts); "samples64_0" holds the same step-0 samples from the oracle built with fp64 arithmetic
 (same inputs), which bounds the fp32 oracle's own rounding error.
 """
 import json
@@ -40,6 +41,15 @@ def add_f64(name):
     lg = o.step(tok, pos)
     out["samples64_0"] = [[float(v) for v in lg[b, idx]] for b in range(s.batch)]
     out["absmax64_0"] = [float(np.abs(lg[b]).max()) for b in range(s.batch)]
+    if s.n_experts:
+        # the fp32 oracle's own error on the router outputs, per layer (largest difference to the
+        # fp64 oracle over sequences and experts at step 0): a routing decision whose margin is
+        # below this scale is not resolved by fp32 arithmetic, whatever the summation order
+        rl64 = o.last_moe_logits.astype(np.float64)
+        o32 = D.DecoderOracle(s, G.SynthWeights(s, out["seed"], cache=False), "f32")
+        lg32 = o32.step(tok, pos)
+        out["samples32_0"] = [[float(v) for v in lg32[b, idx]] for b in range(s.batch)]
+        out["moe_noise"] = np.abs(o32.last_moe_logits.astype(np.float64) - rl64).max((1, 2)).tolist()
     with open(path, "w") as f:
         json.dump(out, f)
     print("added fp64 step-0 samples to", path)
@@ -52,13 +62,23 @@ def main():
     steps = int(sys.argv[2]) if len(sys.argv) > 2 else G.CONFIGS[name].steps
     s = G.CONFIGS[name]
     seed = 0
-    cache = s.n_layers * s.hidden * (3 * s.ffn + 2 * s.hidden) * 2 < 40e9
-    o = D.DecoderOracle(s, G.SynthWeights(s, seed, cache=cache), "f32")
+    layer_bytes = sum(rows * cols * 2 for _, rows, cols, _ in G.layer_tensor_shapes(s))
+    cache = s.n_layers * layer_bytes < 40e9   # else every step regenerates the layers it visits
+    # Top-k routing is discontinuous and the fp32 oracle's own rounding error on the router
+    # outputs (1e-4 after 40 layers) is far above the GPU's, so a mixture-of-experts fixture comes
+    # from the fp64 build: its decisions are the ones better arithmetic converges to.
+    prec = "f64" if s.n_experts else "f32"
+    o = D.DecoderOracle(s, G.SynthWeights(s, seed, cache=cache), prec)
     tok, pos = G.tokens(seed, s).astype(np.int64), G.kv_lengths(seed, s).astype(np.int64)
     idx = sample_indices(s.vocab)
     out = {"config": name, "seed": seed, "steps": steps, "start_tokens": tok.tolist(),
            "start_positions": pos.tolist(), "sample_indices": idx.tolist(), "tokens": [],
-           "top8": [], "samples": {}, "top2_gap_min": None}
+           "top8": [], "samples": {}, "top2_gap_min": None, "precision": prec}
+    if s.n_experts:
+        # routing decisions of every step: selected experts [layer][sequence][top_k] and the gap
+        # between the top_k-th and the next router output [layer][sequence] (a decision with a
+        # tiny gap may legitimately go the other way in another summation order)
+        out["moe_sel"], out["moe_gap"] = [], []
     gap = np.inf
     t0 = time.time()
     for i in range(steps):
@@ -71,6 +91,10 @@ def main():
             gap = min(gap, float(lg[b, order[0]] - lg[b, order[1]]))
         out["tokens"].append(nxt.tolist())
         out["top8"].append(top)
+        if s.n_experts:
+            r = -np.sort(-o.last_moe_logits.astype(np.float64), axis=-1)
+            out["moe_sel"].append(o.last_moe_sel.tolist())
+            out["moe_gap"].append((r[..., s.top_k - 1] - r[..., s.top_k]).tolist())
         if i in (0, steps - 1):
             out["samples"][str(i)] = [[float(v) for v in lg[b, idx]] for b in range(s.batch)]
             out["absmax_%d" % i] = [float(np.abs(lg[b]).max()) for b in range(s.batch)]

@@ -30,7 +30,7 @@ def _load(name):
 def _check_against_fixture(name, opts, free_running=True):
     gold = _load(name)
     s = G.CONFIGS[name]
-    need = s.n_layers * s.hidden * (3 * s.ffn + 2 * s.hidden) * 2 * 1.2
+    need = s.n_layers * sum(r * c * 2 for _, r, c, _ in G.layer_tensor_shapes(s)) * 1.2
     if torch.cuda.mem_get_info()[0] < need:
         pytest.skip("not enough free device memory for this configuration")
     gpu = GpuDecoder(s, gold["seed"], **opts)
@@ -38,11 +38,29 @@ def _check_against_fixture(name, opts, free_running=True):
     pos = np.array(gold["start_positions"], np.int32)
     idx = np.array(gold["sample_indices"])
     steps = gold["steps"]
+    live = np.ones(s.batch, bool)   # sequences still comparable with the oracle's trajectory
     for i in range(steps):
         lg = gpu.step(tok, pos)
         assert np.isfinite(lg).all(), i
+        if s.n_experts:
+            # Routing decisions of the step against the oracle's.  Top-k is discontinuous: where
+            # the oracle's margin between its top_k-th and next router output is within a few
+            # times its own fp32 rounding error at that layer (fixture: fp32 against fp64 oracle),
+            # fp32 arithmetic does not resolve the decision and the other set is as valid.  A
+            # sequence routed differently there is "routing-ambiguous": everything downstream of
+            # the swap legitimately differs, so it leaves the comparison from then on.
+            ex, wt = gpu.graph.moe_selection()
+            ex = ex.reshape(s.n_layers, s.batch, s.top_k).astype(np.int64)
+            assert np.all(np.diff(ex, axis=-1) > 0) and ex.min() >= 0 and ex.max() < s.n_experts
+            assert np.allclose(wt.reshape(s.n_layers, s.batch, s.top_k).sum(-1), 1.0, atol=1e-5)
+            differs = (ex != np.array(gold["moe_sel"][i])).any(-1)      # [layer, sequence]
+            gap, noise = np.array(gold["moe_gap"][i]), np.array(gold["moe_noise"])
+            for b in np.flatnonzero(differs.any(0) & live):
+                l0 = int(np.argmax(differs[:, b]))
+                assert gap[l0, b] < 4 * noise[l0], f"step {i} layer {l0} sequence {b}: margin {gap[l0, b]}"
+                live[b] = False
         want_tok = np.array(gold["tokens"][i])
-        for b in range(s.batch):
+        for b in np.flatnonzero(live):
             got_tok = int(lg[b].argmax())
             if got_tok != int(want_tok[b]):
                 # only a near-tie of the oracle's two best logits may resolve the other way
@@ -51,7 +69,7 @@ def _check_against_fixture(name, opts, free_running=True):
                 (j0, v0), (j1, v1) = gold["top8"][i][b][0], gold["top8"][i][b][1]
                 assert got_tok == j1 and (v0 - v1) < 2e-3 * abs(v0), f"step {i} sequence {b}"
                 free_running = False   # keep both sides on the oracle's token sequence from here on
-        for b in range(s.batch):
+        for b in np.flatnonzero(live):
             top = gold["top8"][i][b]
             scale = abs(top[0][1])
             for j, v in top:
@@ -62,7 +80,7 @@ def _check_against_fixture(name, opts, free_running=True):
             want8 = {j for j, _ in top}
             assert len(got8 ^ want8) <= 2, (i, b)
         if str(i) in gold["samples"]:
-            for b in range(s.batch):
+            for b in np.flatnonzero(live):
                 want = np.array(gold["samples"][str(i)][b])
                 amax = gold["absmax_%d" % i][b]
                 diff = np.abs(lg[b, idx] - want)
@@ -74,10 +92,16 @@ def _check_against_fixture(name, opts, free_running=True):
                     # largest logit, far more than the GPU's.)
                     want64 = np.array(gold["samples64_0"][b])
                     d64 = np.abs(lg[b, idx] - want64)
-                    err = d64 / np.maximum(np.abs(want64), 1e-3 * amax)
-                    assert err.max() < TOL, (i, b, float(err.max()))
-                    assert d64.max() / amax < 1e-4   # fp32 activations throughout
-                    own = np.abs(want - want64).max() / amax   # the fp32 oracle's own error
+                    floor = np.maximum(np.abs(want64), 1e-3 * amax)
+                    err = d64 / floor
+                    # ... plus the reference's own uncertainty: the same measure of the fp32
+                    # oracle against the fp64 one (on the 48-layer mixture-of-experts shape it
+                    # reaches 2e-2 to 5e-2 by itself on logits near the floor)
+                    want32 = np.array(gold["samples32_0"][b]) if "samples32_0" in gold else want
+                    own_el = (np.abs(want32 - want64) / floor).max()
+                    assert err.max() < TOL + own_el, (i, b, float(err.max()), float(own_el))
+                    own = np.abs(want32 - want64).max() / amax   # the fp32 oracle's own error
+                    assert d64.max() / amax < max(1e-4, own)   # fp32 activations throughout
                     assert diff.max() / amax < own + 1e-4, (float(diff.max() / amax), float(own))
                 else:
                     # later steps read K/V rows each side appended itself: a row element whose
@@ -85,8 +109,10 @@ def _check_against_fixture(name, opts, free_running=True):
                     # bf16 ulp), which moves logits by ~1e-4 of their scale after 31 steps; the
                     # bound here is on the error relative to the largest logit
                     assert diff.max() / amax < 2e-3, (i, b, float(diff.max() / amax))
-        tok = (lg.argmax(-1) if free_running else want_tok).astype(np.int32)
+        own_tok = lg.argmax(-1)
+        tok = np.where(live & free_running, own_tok, want_tok).astype(np.int32)
         pos = pos + 1
+    assert live.sum() * 2 >= s.batch, f"only {int(live.sum())} of {s.batch} sequences stayed comparable"
     gpu.close()
 
 
@@ -107,3 +133,9 @@ def test_c3_llama3_8b_shaped_batch8_32_greedy_steps_mega_kernel():
     """Batch 8 with per-sequence KV lengths in [512, 4096]: the matrix-core linear body at the
     benchmark's shapes (K = 4096 and 14336, 501-row LM-head tiles)."""
     _check_against_fixture("C3", BENCH_OPTS)
+
+
+def test_c4_moe_30b_a3b_shaped_batch16_8_greedy_steps_mega_kernel():
+    """Mixture of experts at the benchmark's shapes: 128 experts, top-8, batch 16, 60 GB of
+    weights generated on the device; routing decisions of every layer and step included."""
+    _check_against_fixture("C4", BENCH_OPTS)
