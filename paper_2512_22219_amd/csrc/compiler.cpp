@@ -892,7 +892,7 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
       // to 16 x 1024; + sums of squares
       const size_t t8 = 2 * (size_t)std::min(c.batch, 8u) * (2048 + 8);
       const size_t t16 = c.batch > 8 ? 2 * (size_t)c.batch * (1024 + 8) : 0;
-      f = std::max<size_t>(std::max(t8, t16), 8 * 4 * 256) + 8 * 16 + 16;   // + sums of squares + staged row list
+      f = std::max<size_t>(std::max(t8, t16), 8 * 4 * 256) + 8 * 16 + 32;   // + sums of squares + staged row lists
     }
     else if (op.kind == MPK_OP_ROUTER)
       f = (size_t)c.batch * c.top_k * 2 + (size_t)c.n_experts * (3 + 16) + 64;   // pairs | per-expert counts, offsets, masks, pair table

@@ -555,6 +555,15 @@ __device__ __forceinline__ bool linear_task(const TaskDesc& t, const StepArgs& a
 // the 8 wavefronts by 16-row tiles; a task with fewer than 8 tiles also splits K inside each
 // input tile, and the epilogue adds the slices in a fixed order.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+// (x, y) -> packed bf16 pairs hi = bf16(x), lo = bf16(x - hi), round to nearest even (the
+// hardware conversion: two packed converts, two subtractions)
+__device__ __forceinline__ void split_hi_lo(float x, float y, uint32_t* hi, uint32_t* lo) {
+  const uint32_t h = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){x, y}, bf16x2));
+  *hi = h;
+  *lo = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){x - bf16_lo(h), y - bf16_hi(h)}, bf16x2));
+}
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint32_t mfma_ktile(uint32_t nb) { return nb <= 8 ? 2048u : 1024u; }
@@ -618,35 +627,31 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
   trace_mark(a, t, 1);
   const bool pro_norm = t.flags & TF_PRO_NORM;
   const uint16_t* gain = (const uint16_t*)t.w2;
-  float ss_row = 0.f;   // this thread's share of sum x^2 of batch row (threadIdx.x % nb)... see below
   if (t.flags & TF_EPI_RESID) {
     for (uint32_t i = threadIdx.x; i < nb * ncols; i += kThreads) {
       uint32_t bb = i / ncols, cc = i % ncols;
       res_lds[cc * 16 + bb] = ld_act(t.in2 + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc);
     }
   }
-  // sum of squares: thread handles pairs of one batch row at a time, rows cycle with the loop;
-  // keep one partial per batch row and thread in registers only for rows it touches: simpler to
-  // accumulate into LDS per wave at the end of each tile
-  float ssacc[16];
+  // The input tile of 2048 (1024) inputs x nb rows is dealt to the threads in pairs: pair slot q
+  // of a thread is row q >> sh, pair ((q & sh) << 9) + thread (sh = 1 for 2048-input tiles), so
+  // the row of a slot is the same for the whole wavefront and needs no division.  A tile is
+  // requested (coherent loads into registers) while the previous tile is being multiplied, and
+  // converted into the other LDS buffer afterwards.  Sums of squares are kept per slot.
+  static_assert(kThreads == 512, "the slot -> (row, pair) mapping assumes 512 threads");
+  const uint32_t sh = Kt == 2048u ? 1u : 0u;
+  float sqq[16];
 #pragma unroll
-  for (int b = 0; b < 16; ++b) ssacc[b] = 0.f;
-  (void)ss_row;
-
-  // The input tile of 2048 (1024) inputs x nb rows is dealt to the threads in pairs, round-robin:
-  // at most 16 pairs per thread.  A tile is requested (coherent loads into registers) while the
-  // previous tile is being multiplied, and converted into the other LDS buffer afterwards.
+  for (int q = 0; q < 16; ++q) sqq[q] = 0.f;
   const uint32_t ntile = (K + Kt - 1u) / Kt;
-  const uint32_t half = Kt / 2, npairs = nb * half;
   float2 sv[16];
   auto stage_issue = [&](uint32_t tile) {
     const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
-      const uint32_t p = q * kThreads + threadIdx.x;
-      const uint32_t b = p / half, i = p - b * half;
+      const uint32_t b = (uint32_t)q >> sh, i = (((uint32_t)q & sh) << 9) + threadIdx.x;
       sv[q] = make_float2(0.f, 0.f);
-      if (p < npairs && 2 * i < klen) sv[q] = ld_act2(t.in + (size_t)(t.b0 + b) * t.ld_in + k0 + 2 * i);
+      if (b < nb && 2 * i < klen) sv[q] = ld_act2(t.in + (size_t)(t.b0 + b) * t.ld_in + k0 + 2 * i);
     }
   };
   auto stage_write = [&](uint32_t tile) {
@@ -655,28 +660,26 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
     uint16_t* dl = xl + (size_t)(tile & 1u) * xplane;
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
-      const uint32_t p = q * kThreads + threadIdx.x;
-      if (p < npairs) {
-        const uint32_t b = p / half, i = p - b * half;
+      const uint32_t b = (uint32_t)q >> sh, i = (((uint32_t)q & sh) << 9) + threadIdx.x;
+      if (b < nb) {
         float2 w2 = sv[q];
         if (pro_norm && 2 * i < klen) {
-          const float sq = fmaf(w2.x, w2.x, w2.y * w2.y);
-#pragma unroll
-          for (int bb = 0; bb < 16; ++bb) ssacc[bb] += (b == (uint32_t)bb) ? sq : 0.f;
+          sqq[q] = fmaf(w2.x, w2.x, fmaf(w2.y, w2.y, sqq[q]));
           const uint32_t g2 = *as_global((const uint32_t*)(gain + k0 + 2 * i));
           w2.x *= bf16_lo(g2);
           w2.y *= bf16_hi(g2);
         }
-        const uint16_t h0 = f32_to_bf16(w2.x), h1 = f32_to_bf16(w2.y);
-        const uint16_t l0 = f32_to_bf16(w2.x - bf16_to_f32(h0)), l1 = f32_to_bf16(w2.y - bf16_to_f32(h1));
-        *(uint32_t*)(dh + (size_t)b * xstride + 2 * i) = (uint32_t)h0 | ((uint32_t)h1 << 16);
-        *(uint32_t*)(dl + (size_t)b * xstride + 2 * i) = (uint32_t)l0 | ((uint32_t)l1 << 16);
+        uint32_t hi, lo;
+        split_hi_lo(w2.x, w2.y, &hi, &lo);
+        *(uint32_t*)(dh + (size_t)b * xstride + 2 * i) = hi;
+        *(uint32_t*)(dl + (size_t)b * xstride + 2 * i) = lo;
       }
     }
   };
   stage_issue(0);
   stage_write(0);
   lds_barrier();
+  trace_mark(a, t, 2);
   for (uint32_t tile = 0; tile < ntile; ++tile) {
     const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
     if (tile + 1 < ntile) stage_issue(tile + 1);   // in flight during this tile's arithmetic
@@ -708,17 +711,20 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
     if (tile + 1 < ntile) stage_write(tile + 1);   // into the other buffer: nobody reads it now
     lds_barrier();
   }
+  trace_mark(a, t, 8);
   // ---- partial tiles -> LDS.  part[wave][j][row 0..15][col 0..15]
 #pragma unroll
   for (int j = 0; j < 4; ++j)
 #pragma unroll
     for (int i = 0; i < 4; ++i) part[((wave * 4 + j) * 16 + (lane >> 4) * 4 + i) * 16 + (lane & 15)] = acc[j][i];
   if (pro_norm) {
+    float rowsum = 0.f;   // lane b: this wavefront's sum of squares of row b
 #pragma unroll
-    for (int b = 0; b < 16; ++b) {
-      const float v = wave_sum(ssacc[b]);
-      if (lane == 0) ssq[wave * 16 + b] = v;
+    for (int q = 0; q < 16; ++q) {
+      const float v = wave_sum(sqq[q]);
+      if ((uint32_t)lane == ((uint32_t)q >> sh)) rowsum += v;
     }
+    if (lane < 16) ssq[wave * 16 + lane] = rowsum;
   }
   lds_barrier();
   trace_mark(a, t, 3);
@@ -935,8 +941,13 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
   uint16_t* xl = xh + 2 * (size_t)xplane;
   float* part = lds;
   float* ssq = lds + moe_x_floats(a.g->batch);   // [8][16]
-  uint32_t* rowidx = (uint32_t*)(ssq + 8 * 16);  // [16] pair of each staged row
-  if (threadIdx.x < ne) rowidx[threadIdx.x] = ld_relaxed(plist + threadIdx.x);
+  uint32_t* rowidx = (uint32_t*)(ssq + 8 * 16);  // [16] pair of each staged row (= output row)
+  uint32_t* rowin = rowidx + 16;                 // [16] input row: gate/up reads the token's row, down the pair's
+  if (threadIdx.x < ne) {
+    const uint32_t pair = ld_relaxed(plist + threadIdx.x);
+    rowidx[threadIdx.x] = pair;
+    rowin[threadIdx.x] = gateup ? pair / TK : pair;
+  }
   lds_barrier();
   uint32_t nrt2 = 1;
   while (nrt2 < ntile && nrt2 < 8u) nrt2 <<= 1;
@@ -959,24 +970,21 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
       wfrag[q] = ld_stream16(wp + k);
     }
   };
-  float ssacc[16];
+  // input staging as in linear_task_mfma (slot q = row q >> sh), rows gathered through the pair list
+  const uint32_t sh = Kt == 2048u ? 1u : 0u;
+  float sqq[16];
 #pragma unroll
-  for (int b = 0; b < 16; ++b) ssacc[b] = 0.f;
+  for (int q = 0; q < 16; ++q) sqq[q] = 0.f;
   const uint16_t* gain = (const uint16_t*)t.w2;
-  const uint32_t ntk = (K + Kt - 1u) / Kt, half = Kt / 2, npairs = ne * half;
+  const uint32_t ntk = (K + Kt - 1u) / Kt;
   float2 sv[16];
   auto stage_issue = [&](uint32_t tile) {
     const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
-      const uint32_t p = q * kThreads + threadIdx.x;
-      const uint32_t b = p / half, i = p - b * half;
+      const uint32_t b = (uint32_t)q >> sh, i = (((uint32_t)q & sh) << 9) + threadIdx.x;
       sv[q] = make_float2(0.f, 0.f);
-      if (p < npairs && 2 * i < klen) {
-        const uint32_t pair = rowidx[b];
-        const uint32_t row = gateup ? pair / TK : pair;   // gate/up reads the token's row, down the pair's
-        sv[q] = ld_act2(t.in + (size_t)row * t.ld_in + k0 + 2 * i);
-      }
+      if (b < ne && 2 * i < klen) sv[q] = ld_act2(t.in + (size_t)rowin[b] * t.ld_in + k0 + 2 * i);
     }
   };
   auto stage_write = [&](uint32_t tile) {
@@ -985,22 +993,19 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
     uint16_t* dl = xl + (size_t)(tile & 1u) * xplane;
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
-      const uint32_t p = q * kThreads + threadIdx.x;
-      if (p < npairs) {
-        const uint32_t b = p / half, i = p - b * half;
+      const uint32_t b = (uint32_t)q >> sh, i = (((uint32_t)q & sh) << 9) + threadIdx.x;
+      if (b < ne) {
         float2 w2 = sv[q];
         if (pro_norm && 2 * i < klen) {
-          const float sq = fmaf(w2.x, w2.x, w2.y * w2.y);
-#pragma unroll
-          for (int bb = 0; bb < 16; ++bb) ssacc[bb] += (b == (uint32_t)bb) ? sq : 0.f;
+          sqq[q] = fmaf(w2.x, w2.x, fmaf(w2.y, w2.y, sqq[q]));
           const uint32_t g2 = *as_global((const uint32_t*)(gain + k0 + 2 * i));
           w2.x *= bf16_lo(g2);
           w2.y *= bf16_hi(g2);
         }
-        const uint16_t h0 = f32_to_bf16(w2.x), h1 = f32_to_bf16(w2.y);
-        const uint16_t l0 = f32_to_bf16(w2.x - bf16_to_f32(h0)), l1 = f32_to_bf16(w2.y - bf16_to_f32(h1));
-        *(uint32_t*)(dh + (size_t)b * xstride + 2 * i) = (uint32_t)h0 | ((uint32_t)h1 << 16);
-        *(uint32_t*)(dl + (size_t)b * xstride + 2 * i) = (uint32_t)l0 | ((uint32_t)l1 << 16);
+        uint32_t hi, lo;
+        split_hi_lo(w2.x, w2.y, &hi, &lo);
+        *(uint32_t*)(dh + (size_t)b * xstride + 2 * i) = hi;
+        *(uint32_t*)(dl + (size_t)b * xstride + 2 * i) = lo;
       }
     }
   };
@@ -1042,11 +1047,13 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
 #pragma unroll
     for (int i = 0; i < 4; ++i) part[((wave * 4 + j) * 16 + (lane >> 4) * 4 + i) * 16 + (lane & 15)] = acc[j][i];
   if (pro_norm) {
+    float rowsum = 0.f;   // lane b: this wavefront's sum of squares of staged row b
 #pragma unroll
-    for (int b = 0; b < 16; ++b) {
-      const float v = wave_sum(ssacc[b]);
-      if (lane == 0) ssq[wave * 16 + b] = v;
+    for (int q = 0; q < 16; ++q) {
+      const float v = wave_sum(sqq[q]);
+      if ((uint32_t)lane == ((uint32_t)q >> sh)) rowsum += v;
     }
+    if (lane < 16) ssq[wave * 16 + lane] = rowsum;
   }
   lds_barrier();
   auto dot_of = [&](uint32_t r, uint32_t bb) {
