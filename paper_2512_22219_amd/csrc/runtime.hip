@@ -680,8 +680,41 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
   stage_write(0);
   lds_barrier();
   trace_mark(a, t, 2);
+  // One round: the fragments in wfrag times both planes of the input, steps kk + 32 q < s_hi.
+  // Whole groups of four steps run without per-step tests, their LDS reads ahead of the multiplies.
+  auto consume = [&](f32x4& c, const uint16_t* bh, const uint16_t* bl, uint32_t kk, uint32_t s_hi) {
+#pragma unroll
+    for (int q0 = 0; q0 < kMfmaRound; q0 += 4) {
+      if (kk + (q0 + 4) * 32u <= s_hi) {
+        u32x4 hv[4], lv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          hv[u] = *(const u32x4*)(bh + kk + (q0 + u) * 32u);
+          lv[u] = *(const u32x4*)(bl + kk + (q0 + u) * 32u);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
+          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, hv[u]), c, 0, 0, 0);
+          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, lv[u]), c, 0, 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (kk + (q0 + u) * 32u < s_hi) {
+            const u32x4 bhv = *(const u32x4*)(bh + kk + (q0 + u) * 32u), blv = *(const u32x4*)(bl + kk + (q0 + u) * 32u);
+            const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
+            c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bhv), c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, blv), c, 0, 0, 0);
+          }
+        }
+      }
+    }
+  };
   for (uint32_t tile = 0; tile < ntile; ++tile) {
     const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
+    // (this wavefront's first round of the tile is already under way: requested before the event
+    // wait, or at the end of the previous tile)
     if (tile + 1 < ntile) stage_issue(tile + 1);   // in flight during this tile's arithmetic
     const uint16_t* ch = xh + (size_t)(tile & 1u) * xplane;
     const uint16_t* cl = xl + (size_t)(tile & 1u) * xplane;
@@ -695,19 +728,13 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
         const uint16_t* bh = ch + (size_t)(frow % nb) * xstride + fk;
         const uint16_t* bl = cl + (size_t)(frow % nb) * xstride + fk;
         for (uint32_t kk = s_lo; kk < s_hi; kk += 32u * kMfmaRound) {
-          if (!(tile == 0 && j == 0 && kk == s_lo)) request(wp, k0, kk);   // the first round is already under way
-#pragma unroll
-          for (int q = 0; q < kMfmaRound; ++q) {
-            if (kk + q * 32u < s_hi) {
-              const u32x4 bhv = *(const u32x4*)(bh + kk + q * 32u), blv = *(const u32x4*)(bl + kk + q * 32u);
-              const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q]);
-              acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bhv), acc[j], 0, 0, 0);
-              acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, blv), acc[j], 0, 0, 0);
-            }
-          }
+          if (!(j == 0 && kk == s_lo)) request(wp, k0, kk);
+          consume(acc[j], bh, bl, kk, s_hi);
         }
       }
     }
+    // the next tile's first round goes out before the conversion and the barrier
+    if (tile + 1 < ntile && has_work) request(row_ptr(my_rt0), k0 + Kt, s_lo);
     if (tile + 1 < ntile) stage_write(tile + 1);   // into the other buffer: nobody reads it now
     lds_barrier();
   }
