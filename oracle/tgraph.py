@@ -53,7 +53,7 @@ class OpSpec:
     meta: dict = field(default_factory=dict)
 
 
-def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0):
+def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: int = 1):
     """Operator list of one decode step for model shape `s` (synth.gen.ModelShape) under the
     given fusion flags, in execution order.
 
@@ -64,13 +64,20 @@ def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0):
     whose share of the work is refined at run time from the meta-tensor; and `combine` (weighted
     sum of a token's expert outputs plus the residual).  Which token rows an expert task touches is
     only known at run time, so an expert stage's output is modelled as one element per task and
-    every consumer of the stage reads all of them (the static superset)."""
+    every consumer of the stage reads all of them (the static superset).
+
+    down_parts > 1 (fully fused list only): the down projection is decomposed along its input as
+    well.  Its output tensor is then the partial sums [B][parts x H] (part p of row r at column
+    p H + r); a task reads only its part of the input rows.  Whoever reads residual-stream element
+    (b, r) afterwards reads all `parts` partial sums of it (the task that adds them up is only
+    known at run time; it also adds the residual, so every part task statically reads that)."""
     B, H, d, nq, nkv = s.batch, s.hidden, s.head_dim, s.n_q_heads, s.n_kv_heads
     F, V, C = s.ffn, s.vocab, attn_chunks
     grp = nq // nkv
     QKV = (nq + 2 * nkv) * d
     ops = [OpSpec("embed", K_EMBED, -1, "x0", B, H, H, [])]
     x = "x0"
+    x_parts = 1   # > 1: x names a tensor of partial sums
     for l in range(s.n_layers):
         p = f"L{l}."
         if fusion & F_NORM:
@@ -94,7 +101,7 @@ def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0):
             osrc, oK = p + "o", nq * d
         if fusion & F_RESID:
             ops.append(OpSpec(p + "o_proj", K_LINEAR, l, p + "x1", B, H, 1, [osrc, x],
-                              {"K": oK, "resid": x}))
+                              {"K": oK, "resid": x, "resid_parts": x_parts}))
         else:
             ops.append(OpSpec(p + "o_proj", K_LINEAR, l, p + "a", B, H, 1, [osrc], {"K": oK}))
             ops.append(OpSpec(p + "resid1", K_ADD, l, p + "x1", B, H, 1, [x, p + "a"]))
@@ -121,6 +128,13 @@ def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0):
         else:
             ops.append(OpSpec(p + "gate_up", K_LINEAR, l, p + "gu", B, 2 * F, 1, [nsrc], {"K": H}))
             ops.append(OpSpec(p + "swiglu", K_SWIGLU, l, p + "h", B, F, 1, [p + "gu"], {"F": F}))
+        if down_parts > 1:
+            assert (fusion & F_RESID) and (fusion & F_NORM)
+            xo = p + "dpart"
+            ops.append(OpSpec(p + "down", K_LINEAR, l, xo, B, down_parts * H, 1, [p + "h", x1],
+                              {"K": F, "resid": x1, "parts": down_parts, "H": H}))
+            x, x_parts = xo, down_parts
+            continue
         if fusion & F_RESID:
             ops.append(OpSpec(p + "down", K_LINEAR, l, xo, B, H, 1, [p + "h", x1],
                               {"K": F, "resid": x1}))
@@ -171,10 +185,20 @@ def read_elements(op: OpSpec, tb: int, tc: int, tile: int, shapes: dict):
         pass                                            # token ids are external inputs
     elif k == K_RMSNORM:
         mask(op.ins[0])[b0:b1, :] = True                # every output needs the whole row's mean
+    elif k in (K_LINEAR, K_GATEUP) and op.meta.get("parts", 1) > 1:
+        P, H = op.meta["parts"], op.meta["H"]
+        klen = op.meta["K"] // P
+        for c in range(c0, c1):                         # partial sum (part, row): that part of the input
+            part, r = divmod(c, H)
+            mask(op.ins[0])[b0:b1, part * klen:(part + 1) * klen] = True
+            mask(op.meta["resid"])[b0:b1, r] = True
     elif k in (K_LINEAR, K_GATEUP):
         mask(op.ins[0])[b0:b1, :] = True                # a dot product over the whole input row
         if "resid" in op.meta:
-            mask(op.meta["resid"])[b0:b1, c0:c1] = True  # epilogue: + residual at the same place
+            rp = op.meta.get("resid_parts", 1)
+            Hh = op.cols
+            for part in range(rp):                      # epilogue: + residual at the same place
+                mask(op.meta["resid"])[b0:b1, part * Hh + c0:part * Hh + c1] = True
     elif k == K_ROPE:
         m = mask(op.ins[0])
         d = op.unit

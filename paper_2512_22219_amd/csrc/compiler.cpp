@@ -428,6 +428,15 @@ static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
   const uint32_t f = o.fusion;
   mpk_layer_weights none{};
   int x = b.new_tensor(B, H);
+  // When the residual stream comes out of a split-K operator, dependencies go through that
+  // operator's partial tensor x_dep ([B][x_parts x H]) while bodies load x.
+  int x_dep = -1;
+  uint32_t x_parts = 0;
+  auto reads_x = [&](HostOp& op, bool second) {   // op reads the residual stream as in (or in2)
+    if (x_dep < 0) return;
+    if (second) { op.in2_tensor = x_dep; op.body_in2_tensor = x; op.in2_kparts = x_parts; }
+    else { op.in_tensor = x_dep; op.body_in_tensor = x; op.in_kparts = x_parts; }
+  };
   {
     HostOp& op = b.add(MPK_OP_EMBED, -1, "embed", x, H, -1);
     op.w = w ? w->embed : nullptr;
@@ -446,7 +455,7 @@ static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
     {
       HostOp& op = b.add(MPK_OP_LINEAR, l, "qkv", qkv, 1, qkv_in);
       op.w = lw.wqkv; op.K = H; op.align_unit = d;
-      if (f & MPK_FUSE_NORM) { op.flags |= TF_PRO_NORM; op.w2 = lw.attn_norm; op.f0 = c.rms_eps; }
+      if (f & MPK_FUSE_NORM) { op.flags |= TF_PRO_NORM; op.w2 = lw.attn_norm; op.f0 = c.rms_eps; reads_x(op, false); }
     }
     int qsrc = qkv;
     if (!(f & MPK_FUSE_ROPE)) {
@@ -482,6 +491,7 @@ static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
       HostOp& op = b.add(MPK_OP_LINEAR, l, "o_proj", x1, 1, osrc, x);
       op.w = lw.wo; op.K = oK; op.flags |= TF_EPI_RESID;
       op.body_in_tensor = o_body;
+      reads_x(op, true);
     } else {
       int a = b.new_tensor(B, H);
       HostOp& op = b.add(MPK_OP_LINEAR, l, "o_proj", a, 1, osrc);
@@ -555,6 +565,31 @@ static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
       HostOp& sw = b.add(MPK_OP_SWIGLU, l, "swiglu", h, 1, gu);
       sw.p0 = F;
     }
+    // Batch > 4 and an input several staging tiles long: every task would re-read the whole
+    // input (as many bytes as its weights).  Split the input range over `parts` tasks per row
+    // block instead; the last task of a row block to arrive adds the parts (in order) and the
+    // residual.  Only in the fully fused operator list, where the readers of the result are
+    // linear operators.
+    uint32_t parts = 1;
+    if (B > 4 && (f & MPK_FUSE_RESID) && (f & MPK_FUSE_NORM) && !o.tiles_linear) {
+      const uint32_t kt = B <= 8 ? 2048u : 1024u, W = o.n_workers;
+      for (uint32_t kp = 4; kp >= 2 && parts == 1; kp >>= 1) {
+        const uint32_t per = (uint64_t)kp * H % W == 0 ? kp * H / W : 0;   // rows per task
+        if (F % (kp * 64) == 0 && F / kp >= kt && F >= 3 * kt && per >= 16 && per % 16 == 0 && per <= 512 && H % per == 0) parts = kp;
+      }
+    }
+    if (parts > 1) {
+      int dpart = b.new_tensor(B, parts * H);
+      int xo = b.new_tensor(B, H);
+      HostOp& op = b.add(MPK_OP_LINEAR, l, "down", dpart, 1, h, x1);
+      op.w = lw.wd; op.K = F; op.flags |= TF_EPI_RESID | TF_SPLITK;
+      op.p0 = parts; op.p1 = H; op.p2 = g.n_splitk_counters;
+      op.side_out_tensor = xo;
+      g.n_splitk_counters += o.n_workers / parts;   // one arrival counter per row block
+      x = xo; x_dep = dpart; x_parts = parts;
+      continue;
+    }
+    x_dep = -1; x_parts = 0;
     int xo = b.new_tensor(B, H);
     if (f & MPK_FUSE_RESID) {
       HostOp& op = b.add(MPK_OP_LINEAR, l, "down", xo, 1, h, x1);
@@ -578,7 +613,7 @@ static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
   {
     HostOp& op = b.add(MPK_OP_LINEAR, -1, "lm_head", logits, 1, lin);
     op.w = w ? w->lm_head : nullptr; op.K = H; op.flags |= TF_OUT_LOGITS;
-    if (f & MPK_FUSE_NORM) { op.flags |= TF_PRO_NORM; op.w2 = w ? w->final_norm : nullptr; op.f0 = c.rms_eps; }
+    if (f & MPK_FUSE_NORM) { op.flags |= TF_PRO_NORM; op.w2 = w ? w->final_norm : nullptr; op.f0 = c.rms_eps; reads_x(op, false); }
   }
   return MPK_OK;
 }
@@ -609,6 +644,7 @@ static void choose_partitions(const mpk_model_config& c, const mpk_compile_optio
         uint32_t cap = std::max(1u, nu / 8);   // at least 8 output rows per task
         op.tb = 1;
         op.tc = std::max(1u, std::min(want, cap));
+        if (op.flags & TF_SPLITK) { op.tc = W; break; }   // (row block, part) pairs, sized in build_ops
         // the matrix-core body (batch > 4) holds at most 512 weight rows per task: whole extra
         // rounds of tasks until the tiles fit (only when the tile count was not given)
         const bool given = (op.flags & TF_OUT_LOGITS) ? o.tiles_lm_head != 0 : o.tiles_linear != 0;
@@ -682,8 +718,23 @@ static void input_rects(const mpk_model_config& c, const HostOp& op, uint32_t ti
       break;
     case MPK_OP_LINEAR:
     case MPK_OP_GATEUP:
+      if (op.flags & TF_SPLITK) {
+        // output columns [part x H + rows): the task reads its part of the input rows, and (if it
+        // turns out to be the one that adds the parts up) the residual at its rows
+        const uint32_t Hh = op.p1, part = c0 / Hh, klen = op.K / op.p0;
+        out.push_back({op.in_tensor, b0, b1, part * klen, (part + 1) * klen});
+        out.push_back({op.in2_tensor, b0, b1, c0 - part * Hh, c1 - part * Hh});
+        break;
+      }
       out.push_back({op.in_tensor, b0, b1, 0, UINT32_MAX});   // whole input rows
-      if (op.flags & TF_EPI_RESID) out.push_back({op.in2_tensor, b0, b1, c0, c1});
+      if (op.flags & TF_EPI_RESID) {
+        if (op.in2_kparts) {   // the residual is the sum of a split-K operator's parts
+          const uint32_t Hh = op.cols;
+          for (uint32_t part = 0; part < op.in2_kparts; ++part) out.push_back({op.in2_tensor, b0, b1, part * Hh + c0, part * Hh + c1});
+        } else {
+          out.push_back({op.in2_tensor, b0, b1, c0, c1});
+        }
+      }
       break;
     case MPK_OP_ROPE:
       out.push_back({op.in_tensor, b0, b1, c0, c1});   // whole heads: partners included
@@ -818,7 +869,8 @@ static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGr
     t.w = op.w; t.w2 = op.w2; t.f0 = op.f0; t.f1 = op.f1;
     t.p0 = op.p0; t.p1 = op.p1; t.p2 = op.p2; t.p3 = op.p3;
     t.in = act_ref(g, op.body_in_tensor >= 0 ? op.body_in_tensor : op.in_tensor);
-    t.in2 = act_ref(g, op.side_out_tensor >= 0 ? op.side_out_tensor : op.in2_tensor);
+    t.in2 = act_ref(g, op.side_out_tensor >= 0 ? op.side_out_tensor
+                                               : (op.body_in2_tensor >= 0 ? op.body_in2_tensor : op.in2_tensor));
     t.out = const_cast<float*>(act_ref(g, op.out_tensor));
     {
       int it = op.body_in_tensor >= 0 ? op.body_in_tensor : op.in_tensor;
@@ -838,6 +890,17 @@ static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGr
       case MPK_OP_ROUTER: t.kind = TK_MOE_ROUTE; break;
       case MPK_OP_EXPERT: t.kind = TK_MOE_EXPERT; break;
       case MPK_OP_COMBINE: t.kind = TK_MOE_COMBINE; break;
+    }
+    if (op.flags & TF_SPLITK) {
+      const uint32_t Hh = op.p1, parts = op.p0, part = t.c0 / Hh, klen = op.K / parts;
+      t.K = klen;
+      t.p1 = op.K;                                   // weight row length
+      t.p3 = parts | (part << 8);
+      t.p2 = g.n_group_counters_attn + op.p2 + (t.c0 - part * Hh) / (t.c1 - t.c0);   // row block's arrival counter
+      t.w = op.w ? (const void*)((const uint16_t*)op.w + (size_t)part * klen) : nullptr;
+      t.in = (const float*)((const char*)act_ref(g, op.in_tensor) + (size_t)part * klen * sizeof(float));
+      t.in2 = act_ref(g, op.in2_tensor);             // residual [B][H]
+      t.aux0 = (void*)act_ref(g, op.side_out_tensor);   // the real output [B][H]; relocated by the runtime
     }
     if (op.kind == MPK_OP_ROUTER || op.kind == MPK_OP_EXPERT || op.kind == MPK_OP_COMBINE) {
       t.in = act_ref(g, op.data_in);
@@ -966,7 +1029,8 @@ mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs*
   st = build_ops(cfg, w, opt, C, g);
   if (st != MPK_OK) return st;
   choose_partitions(cfg, opt, g);
-  g.n_group_counters = cfg.n_layers * cfg.batch * cfg.n_kv_heads;
+  g.n_group_counters_attn = cfg.n_layers * cfg.batch * cfg.n_kv_heads;
+  g.n_group_counters = g.n_group_counters_attn + g.n_splitk_counters;
   g.inv_freq.resize(cfg.head_dim / 2);
   for (uint32_t i = 0; i < cfg.head_dim / 2; ++i)
     g.inv_freq[i] = std::pow((double)cfg.rope_theta, -2.0 * (double)i / (double)cfg.head_dim);

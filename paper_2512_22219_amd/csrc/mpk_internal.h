@@ -39,6 +39,10 @@ enum TaskFlags : uint16_t {
   TF_ATTN_MERGE = 64, // attention: the last chunk task of a (sequence, KV head) to finish merges
                       // all chunk partials into the attention output (in2), counter index p2
   TF_JIT = 128,       // launched just-in-time: a scheduler hands it to a worker when its event fires
+  TF_SPLITK = 256,    // linear (batch > 4): the task owns rows x ONE of `parts` input ranges; it writes
+                      // partial sums, and the task of a row block that arrives last (counter p2)
+                      // adds the parts in order plus the residual into the real output (aux0).
+                      // p1 = weight row length, p3 = parts | part << 8, K = length of the range
 };
 
 struct alignas(16) TaskDesc {
@@ -96,6 +100,8 @@ struct HostOp {
   int body_in_tensor = -1;     // tensor the body actually loads when it differs from in_tensor
   int side_out_tensor = -1;    // second output written by the body (merged attention output)
   int in3_tensor = -1;         // third tensor the dependency analysis reads (combine: meta-tensor)
+  int body_in2_tensor = -1;    // tensor the body loads as second input when it differs from in2_tensor
+  uint32_t in_kparts = 0, in2_kparts = 0;   // the input is a split-K operator's partial tensor with this many parts
   // mixture-of-experts operators: the tensors the body really touches (the dependency analysis
   // sees an expert stage's output as one element per task, see build_ops)
   int data_in = -1, data_in2 = -1, data_out = -1, data_aux = -1;
@@ -134,7 +140,8 @@ struct HostGraph {
   uint32_t n_real = 0, start_event = 0, terminal_event = 0;
   size_t arena_floats = 0;
   uint32_t lds_bytes = 0;
-  uint32_t n_group_counters = 0;   // per (layer, sequence, KV head) arrival counters
+  uint32_t n_group_counters = 0;   // arrival counters: per (layer, sequence, KV head), then per split-K row block
+  uint32_t n_group_counters_attn = 0, n_splitk_counters = 0;
   uint32_t n_hier_events = 0;
   uint32_t lin_rows_max = 0;       // largest weight-row count of one linear task (gate/up pairs twice)
   uint32_t lin_res_rows_max = 0;   // largest column count of a linear task with a residual epilogue

@@ -604,10 +604,16 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
   // round is requested before the event wait (cross-task pre-loading, Section 5.3).
   constexpr int kMfmaRound = 16;
   u32x4 wfrag[kMfmaRound];
+  // split-K task (TF_SPLITK): rows [row0, row0 + ncols) of the matrix, inputs of ONE part; the
+  // weight pointer is already advanced to the part, rows are ldw apart
+  const bool splitk = t.flags & TF_SPLITK;
+  const uint32_t parts = splitk ? (t.p3 & 0xFFu) : 1u, my_part = splitk ? (t.p3 >> 8) : 0u;
+  const uint32_t Hs = t.ld_out / parts;              // columns of the real output
+  const uint32_t row0 = t.c0 - my_part * Hs, ldw = splitk ? t.p1 : K;
   auto row_ptr = [&](uint32_t rt) {
     const uint32_t r = min(rt * 16u + frow, R - 1u);   // rows past the end repeat the last one
-    const uint32_t wrow = gateup ? (t.c0 + (r >> 1) + ((r & 1u) ? t.p0 : 0u)) : t.c0 + r;
-    return W + (size_t)wrow * K + fk;
+    const uint32_t wrow = gateup ? (row0 + (r >> 1) + ((r & 1u) ? t.p0 : 0u)) : row0 + r;
+    return W + (size_t)wrow * ldw + fk;
   };
   auto request = [&](const uint16_t* wp, uint32_t k0, uint32_t kk) {   // inputs k0 + kk + 32 q + fk .. + 7
 #pragma unroll
@@ -627,7 +633,7 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
   trace_mark(a, t, 1);
   const bool pro_norm = t.flags & TF_PRO_NORM;
   const uint16_t* gain = (const uint16_t*)t.w2;
-  if (t.flags & TF_EPI_RESID) {
+  if ((t.flags & TF_EPI_RESID) && !splitk) {
     for (uint32_t i = threadIdx.x; i < nb * ncols; i += kThreads) {
       uint32_t bb = i / ncols, cc = i % ncols;
       res_lds[cc * 16 + bb] = ld_act(t.in2 + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc);
@@ -784,8 +790,29 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
       } else {
         v = dot_of(cc, bb) * inv;
       }
-      if (t.flags & TF_EPI_RESID) v = res_lds[cc * 16 + bb] + v;
-      st_act(outp + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc, v);
+      if ((t.flags & TF_EPI_RESID) && !splitk) v = res_lds[cc * 16 + bb] + v;
+      st_act(outp + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc, v);   // split-K: the partial sums of this part
+    }
+    if (splitk) {
+      // arrival at the row block's counter once the partial sums are visible; the last of the
+      // `parts` tasks adds the parts in order, and the residual, into the real output
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      uint32_t last = 0;
+      if (lane == 0) {
+        const uint32_t old = __hip_atomic_fetch_add(as_global(a.g->grp_counters + t.p2), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last = (old + 1u == a.epoch * parts) ? 1u : 0u;
+      }
+      last = __builtin_amdgcn_readfirstlane(last);
+      if (last) {
+        float* xout = (float*)t.aux0;
+        for (uint32_t i = lane; i < ncols * nb; i += 64) {
+          const uint32_t cc = i / nb, bb = i % nb;
+          float v = ld_act(t.in2 + (size_t)(t.b0 + bb) * Hs + row0 + cc);
+          for (uint32_t pp = 0; pp < parts; ++pp) v += ld_act(t.out + (size_t)(t.b0 + bb) * t.ld_out + pp * Hs + row0 + cc);
+          st_act(xout + (size_t)(t.b0 + bb) * Hs + row0 + cc, v);
+        }
+      }
     }
     if (MEGA && t.trig_event >= 0) signal_from_wave0(a, t, t.trig_event, lane);
     trace_mark(a, t, 4);
@@ -2401,7 +2428,7 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
     t.in = reloc(t.in);
     t.in2 = reloc(t.in2);
     t.out = const_cast<float*>(reloc(t.out));
-    if (t.kind == TK_MOE_ROUTE || t.kind == TK_MOE_EXPERT || t.kind == TK_MOE_COMBINE)
+    if (t.kind == TK_MOE_ROUTE || t.kind == TK_MOE_EXPERT || t.kind == TK_MOE_COMBINE || (t.flags & TF_SPLITK))
       t.aux0 = (void*)reloc((const float*)t.aux0);
   }
   // per-operator task lists (baseline launch mode)

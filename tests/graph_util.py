@@ -67,8 +67,17 @@ def moe_tasks_of(ex):
     return 0
 
 
+def down_parts_of(ex, shape):
+    """Input parts of the down projection (1 unless it was decomposed along its input too): the
+    last linear operator of a dense layer writes hidden columns per part."""
+    if shape.n_experts:
+        return 1
+    last = [eo for eo in ex.ops if eo["layer"] == 0 and eo["kind"] == TG.K_LINEAR][-1]
+    return int(last["cols"]) // shape.hidden
+
+
 def oracle_ops_and_degrees(shape, ex, fusion, attn_chunks):
-    ops = TG.build_ops(shape, fusion, attn_chunks, moe_tasks_of(ex))
+    ops = TG.build_ops(shape, fusion, attn_chunks, moe_tasks_of(ex), down_parts_of(ex, shape))
     assert len(ops) == len(ex.ops), (len(ops), len(ex.ops))
     for o, eo in zip(ops, ex.ops):
         assert o.kind == eo["kind"] and o.layer == eo["layer"], (o.name, o.kind, eo["kind"])

@@ -45,6 +45,9 @@ CASES = [
     ("C1", dict(batch=2, ffn=0, n_experts=8, top_k=2, expert_ffn=64), dict(fusion=0, n_workers=12)),
     ("C1", dict(batch=3, ffn=0, n_experts=16, top_k=4, expert_ffn=32), dict(fusion=31, n_workers=24, tiles_moe=10)),
     ("C4", dict(n_layers=1), dict(fusion=31)),
+    # batch > 4 with a long down-projection input: decomposed along the input as well
+    ("C3", dict(n_layers=2), dict(fusion=31)),
+    ("C1", dict(batch=8, ffn=8192), dict(fusion=31, n_workers=32)),
 ]
 
 

@@ -124,6 +124,37 @@ def test_matrix_core_linear_body_batch_5_to_16(batch, opts):
     gpu.close()
 
 
+@pytest.mark.parametrize("batch,ffn,opts", [
+    (8, 8192, dict(fusion=31, transitive_reduction=1, n_workers=32)),            # 4 parts of 2048
+    (8, 6272, dict(fusion=31, transitive_reduction=1, n_workers=32)),            # 2 parts of 3136: ragged second tile
+    (16, 4096, dict(fusion=31, transitive_reduction=1, n_workers=64)),           # 1024-input tiles, 4 parts
+    (8, 8192, dict(fusion=31, transitive_reduction=1, n_workers=32, launch_mode=1)),
+    (8, 8192, dict(fusion=31, n_workers=32, n_sched_wgs=2)),
+])
+def test_down_projection_decomposed_along_its_input(batch, ffn, opts):
+    """Batch > 4 with a long down-projection input: (row block, input part) tasks write partial
+    sums and the last task of a row block to arrive adds them and the residual.  The compiled
+    graph must really contain such tasks, and logits must match over steps (the arrival counters
+    only ever grow)."""
+    s = G.small_variant("C1", batch=batch, ffn=ffn, n_layers=2, max_seq=192)
+    tok = G.tokens(3, s)
+    pos = np.array([(29 * b + 11) % 150 for b in range(batch)], np.int32)
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 3), "f32")
+    gpu = GpuDecoder(s, 3, **opts)
+    ex = gpu.graph.export()
+    down = [o for o in ex.ops if o["layer"] == 0 and o["kind"] == M.binding.OP_LINEAR][-1]
+    assert down["cols"] >= 2 * s.hidden, "the down projection of this graph is not decomposed"
+    for step in range(3):
+        want = ref.step(tok, pos)
+        got = gpu.step(tok, pos)
+        assert np.isfinite(got).all()
+        assert rel_err(got, want) < TOL, step
+        assert np.abs(got - want).max() / np.abs(want).max() < 1e-4, step
+        assert got.argmax(-1).tolist() == want.argmax(-1).tolist(), step
+        tok, pos = want.argmax(-1).astype(np.int32), pos + 1
+    gpu.close()
+
+
 def test_greedy_32_steps_free_running_and_teacher_forced():
     s = G.small_variant("C1", max_seq=192)
     tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
