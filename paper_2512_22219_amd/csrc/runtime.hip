@@ -420,21 +420,30 @@ __device__ __forceinline__ bool linear_task(const TaskDesc& t, const StepArgs& a
   // the row's 1/rms factor is applied to the finished dot products: W (x g inv) = inv * W (x g).
   const bool pro_norm = t.flags & TF_PRO_NORM;
   const uint16_t* gain = (const uint16_t*)t.w2;
+  // the residual slice of this tile goes out first (tile-local, small): its round trip then
+  // overlaps the staging instead of following it
+  const bool resid = t.flags & TF_EPI_RESID;
+  float resv = 0.f;
+  if (resid && threadIdx.x < nb * ncols) {
+    const uint32_t bb = threadIdx.x / ncols, cc = threadIdx.x % ncols;
+    resv = ld_act(t.in2 + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc);
+  }
+  constexpr int kStageLoads = 12;   // coherent loads in flight per lane: 12288 inputs in one round trip
 #pragma unroll
   for (uint32_t b = 0; b < (uint32_t)NB; ++b) {
     float2* dst = (float2*)(xs + (size_t)b * Kp);
     float ss = 0.f;
     if (b < nb) {
       const float* src = t.in + (size_t)(t.b0 + b) * t.ld_in;
-      for (uint32_t i0 = 0; i0 < Kp / 2; i0 += kThreads * 8) {   // 8 coherent loads in flight per lane
-        float2 tmp[8];
+      for (uint32_t i0 = 0; i0 < Kp / 2; i0 += kThreads * kStageLoads) {
+        float2 tmp[kStageLoads];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < kStageLoads; ++u) {
           uint32_t i = i0 + u * kThreads + threadIdx.x;
           if (i < K / 2) tmp[u] = ld_act2(src + 2 * i);
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < kStageLoads; ++u) {
           uint32_t i = i0 + u * kThreads + threadIdx.x;
           if (i < K / 2) {
             float2 v = tmp[u];
@@ -459,9 +468,9 @@ __device__ __forceinline__ bool linear_task(const TaskDesc& t, const StepArgs& a
       if (lane == 0) ssq[wave * NB + b] = ss;
     }
   }
-  // residual slice of this tile (tile-local, small)
-  if (t.flags & TF_EPI_RESID) {
-    for (uint32_t i = threadIdx.x; i < nb * ncols; i += kThreads) {
+  if (resid) {
+    if (threadIdx.x < nb * ncols) res_lds[threadIdx.x] = resv;
+    for (uint32_t i = threadIdx.x + kThreads; i < nb * ncols; i += kThreads) {   // more than 512 outputs per task: rare
       uint32_t bb = i / ncols, cc = i % ncols;
       res_lds[i] = ld_act(t.in2 + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc);
     }
