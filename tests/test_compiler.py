@@ -287,3 +287,38 @@ def test_error_paths():
     assert M.lib().mpk_decode_step(g._h, 1, 1, 1, None) == M.binding.MPK_ERR_INVALID_ARG
     with pytest.raises(M.MpkError):
         M.compile_dag(3, [(0, 5)])
+
+
+def test_moe_error_paths_and_graph_shape():
+    moe = dict(ffn=0, n_experts=8, top_k=2, expert_ffn=64)
+    for bad, status in ((dict(top_k=9), M.binding.MPK_ERR_INVALID_ARG),
+                        (dict(top_k=0), M.binding.MPK_ERR_INVALID_ARG),
+                        (dict(expert_ffn=60), M.binding.MPK_ERR_UNSUPPORTED),
+                        (dict(expert_ffn=24), M.binding.MPK_ERR_UNSUPPORTED),
+                        (dict(n_experts=1024, top_k=8), M.binding.MPK_ERR_UNSUPPORTED),
+                        (dict(n_experts=64, top_k=32), M.binding.MPK_ERR_UNSUPPORTED),
+                        (dict(batch=16, n_experts=64, top_k=16, hidden=264), M.binding.MPK_ERR_UNSUPPORTED)):
+        with pytest.raises(M.MpkError) as e:
+            host_graph(G.small_variant("C1", **{**moe, **bad}))
+        assert e.value.status == status, bad
+    with pytest.raises(M.MpkError) as e:      # dense model with stray MoE fields
+        host_graph(G.small_variant("C1", top_k=2))
+    assert e.value.status == M.binding.MPK_ERR_INVALID_ARG
+    g = host_graph(G.small_variant("C1", batch=2, **moe), fusion=31, n_workers=12, tiles_moe=7)
+    ex = g.export()
+    kinds = [int(o["kind"]) for o in ex.ops if o["layer"] == 0]
+    assert kinds == [M.binding.OP_LINEAR, M.binding.OP_ATTN_PARTIAL, M.binding.OP_LINEAR, M.binding.OP_LINEAR,
+                     M.binding.OP_ROUTER, M.binding.OP_EXPERT, M.binding.OP_EXPERT, M.binding.OP_COMBINE]
+    per_op = {int(o["kind"]): int(o["n_tasks"]) for o in ex.ops if o["layer"] == 0}
+    assert per_op[M.binding.OP_ROUTER] == 1 and per_op[M.binding.OP_EXPERT] == 7
+    st_ = g.stats()
+    s = G.small_variant("C1", batch=2, **moe)
+    assert st_["expert_bytes"] == 3 * s.expert_ffn * s.hidden * 2
+    # the selection read-back needs a device graph
+    with pytest.raises(M.MpkError) as e:
+        g.moe_active()
+    assert e.value.status == M.binding.MPK_ERR_INVALID_ARG
+    # hybrid launch labels the expert stages just-in-time and combine ahead-of-time again
+    gj = host_graph(G.small_variant("C1", batch=2, **moe), fusion=31, n_workers=12, n_sched_wgs=1)
+    jit = {int(o["kind"]): int(o["jit"]) for o in gj.export().ops if o["layer"] == 0}
+    assert jit[M.binding.OP_EXPERT] == 1 and jit[M.binding.OP_COMBINE] == 0 and jit[M.binding.OP_ROUTER] == 0

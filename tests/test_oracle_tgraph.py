@@ -246,6 +246,87 @@ def test_producer_sets_fused_residual_reads_only_its_tile():
         assert set(ps[ix["L1.o_proj"]][j]) == want
 
 
+def test_producer_sets_mixture_of_experts_block():
+    """Section 6.4 chain: router -> route -> expert gate/up -> expert down -> combine, with the
+    static supersets spelled out by hand."""
+    s = G.small_variant("C1", n_layers=1, batch=2, ffn=0, n_experts=8, top_k=2, expert_ffn=64)
+    fusion = TG.F_NORM | TG.F_RESID | TG.F_SWIGLU
+    NT = 5
+    ops = TG.build_ops(s, fusion, attn_chunks=2, moe_tasks=NT)
+    names = [o.name for o in ops]
+    assert names == ["embed", "L0.qkv", "L0.rope", "L0.attn_partial", "L0.attn_merge", "L0.o_proj",
+                     "L0.router", "L0.route", "L0.expert_gate_up", "L0.expert_down", "L0.combine",
+                     "lm_head"]
+    deg = []
+    for op in ops:
+        if op.kind == TG.K_EXPERT:
+            deg.append((1, NT))
+        elif op.kind == TG.K_ROUTER:
+            deg.append((1, 1))
+        elif op.kind == TG.K_COMBINE:
+            deg.append((op.rows, 2))
+        elif op.name == "L0.router":
+            deg.append((1, 2))
+        else:
+            deg.append(tiny_degrees([op])[0])
+    ps = TG.producer_sets(ops, deg)
+    ix = {n: i for i, n in enumerate(names)}
+    o_tiles = {(ix["L0.o_proj"], t) for t in range(4)}
+    # the router is a linear operator over x1: every o_proj tile, for both of its row tiles
+    assert all(set(p) == o_tiles for p in ps[ix["L0.router"]])
+    # route: one task, every router tile (it needs every token's choice)
+    assert ps[ix["L0.route"]] == [[(ix["L0.router"], 0), (ix["L0.router"], 1)]]
+    # an expert gate/up task: the meta-tensor (route) + all of x1, whatever the routing
+    for t in range(NT):
+        assert set(ps[ix["L0.expert_gate_up"]][t]) == {(ix["L0.route"], 0)} | o_tiles
+        # an expert down task: the meta-tensor + every gate/up task
+        assert set(ps[ix["L0.expert_down"]][t]) == {(ix["L0.route"], 0)} | {(ix["L0.expert_gate_up"], u) for u in range(NT)}
+    # combine tile (row b, column half c): every expert-down task, the meta-tensor, and the
+    # o_proj tiles that hold its residual slice (4 tiles of 64 columns; half c = tiles 2c, 2c+1)
+    for b in range(2):
+        for c in range(2):
+            want = {(ix["L0.expert_down"], u) for u in range(NT)} | {(ix["L0.route"], 0)} \
+                | {(ix["L0.o_proj"], 2 * c), (ix["L0.o_proj"], 2 * c + 1)}
+            assert set(ps[ix["L0.combine"]][b * 2 + c]) == want
+    # the next reader of the residual stream sees combine's tiles
+    assert all(set(p) == {(ix["L0.combine"], t) for t in range(4)} for p in ps[ix["lm_head"]])
+
+
+def test_producer_sets_down_projection_cut_along_its_input():
+    s = G.small_variant("C1", n_layers=2, batch=1, ffn=1024)
+    fusion = TG.F_NORM | TG.F_RESID | TG.F_SWIGLU
+    P, H = 4, s.hidden
+    ops = TG.build_ops(s, fusion, attn_chunks=2, down_parts=P)
+    names = [o.name for o in ops]
+    ix = {n: i for i, n in enumerate(names)}
+    down = ops[ix["L0.down"]]
+    assert (down.rows, down.cols) == (1, P * H)
+    deg = []
+    for op in ops:
+        if op.name.endswith(".down"):
+            deg.append((1, 8))          # 2 row blocks (128 rows) x 4 parts
+        elif op.name.endswith(".gate_up"):
+            deg.append((1, 8))          # 8 tiles of 128 of the 1024 columns of h
+        else:
+            deg.append(tiny_degrees([op])[0])
+    ps = TG.producer_sets(ops, deg)
+    # down tile = part * 2 + row block; part p reads h[256 p, 256 (p + 1)) = gate/up tiles 2p, 2p+1,
+    # and the residual x1 at its 128 rows = o_proj tiles 2 rb, 2 rb + 1 (4 tiles of 64)
+    for part in range(P):
+        for rb in range(2):
+            want = {(ix["L0.gate_up"], 2 * part), (ix["L0.gate_up"], 2 * part + 1),
+                    (ix["L0.o_proj"], 2 * rb), (ix["L0.o_proj"], 2 * rb + 1)}
+            assert set(ps[ix["L0.down"]][part * 2 + rb]) == want
+    # the next layer's QKV reads the whole residual stream: every (row block, part) task
+    assert all(set(p) == {(ix["L0.down"], t) for t in range(8)} for p in ps[ix["L1.qkv"]])
+    # the next layer's o_proj tile j (64 columns) adds residual columns [64 j, 64 j + 64): row
+    # block j // 2, all four parts
+    for j in range(4):
+        res = {(ix["L0.down"], part * 2 + j // 2) for part in range(P)}
+        assert res <= set(ps[ix["L1.o_proj"]][j])
+        assert not any(o == ix["L0.down"] and (o, t) not in res for o, t in ps[ix["L1.o_proj"]][j])
+
+
 # ------------------------------------------------------------------ runtime simulator
 def small_linear_graph():
     """a0,a1 -> e1 -> b0,b1,b2 -> e2 -> c0 ; start event 0 launches a*."""
