@@ -578,8 +578,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint32_t mfma_ktile(uint32_t nb) { return nb <= 8 ? 2048u : 1024u; }
 
 // LDS (from the task area): xh [2][nb][Kt + 8] bf16 | xl same | res [residual columns][16] f32 |
-// ssq [8][16] f32; the per-wavefront partial tiles part [8][4][256] f32 reuse the input buffers
-// once the last input tile has been consumed.
+// ssq [8][16] f32 | 1/rms [16] f32; the per-wavefront partial tiles part [8][4][256] f32 reuse the
+// input buffers once the last input tile has been consumed.
 template <bool MEGA>
 __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
                                                  uint32_t* s_flag) {
@@ -770,8 +770,18 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
   }
   lds_barrier();
   trace_mark(a, t, 3);
-  // ---- wavefront 0: add the K slices in order, epilogue, outputs, notification
-  if (wave == 0) {
+  // ---- all wavefronts: add the K slices in order, epilogue, outputs; then the notification
+  float* inv_lds = ssq + 8 * 16;   // [16] 1/rms of each batch row
+  if (pro_norm) {
+    if (threadIdx.x < 16) {
+      float ss = 0.f;
+#pragma unroll
+      for (int w = 0; w < 8; ++w) ss += ssq[w * 16 + threadIdx.x];
+      inv_lds[threadIdx.x] = 1.0f / sqrtf(ss / (float)K + t.f0);
+    }
+    lds_barrier();
+  }
+  {
     float* outp = (t.flags & TF_OUT_LOGITS) ? a.logits : t.out;
     auto dot_of = [&](uint32_t r, uint32_t bb) {   // ring row r, batch column bb
       const uint32_t rt = r >> 4, row = r & 15u;
@@ -783,15 +793,9 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
       }
       return v;
     };
-    for (uint32_t i = lane; i < ncols * nb; i += 64) {
+    for (uint32_t i = threadIdx.x; i < ncols * nb; i += kThreads) {
       const uint32_t cc = i / nb, bb = i % nb;
-      float inv = 1.0f;
-      if (pro_norm) {
-        float ss = 0.f;
-#pragma unroll
-        for (int w = 0; w < 8; ++w) ss += ssq[w * 16 + bb];
-        inv = 1.0f / sqrtf(ss / (float)K + t.f0);
-      }
+      const float inv = pro_norm ? inv_lds[bb] : 1.0f;
       float v;
       if (gateup) {
         const float gte = dot_of(2 * cc, bb) * inv, up = dot_of(2 * cc + 1, bb) * inv;
@@ -802,11 +806,17 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
       if ((t.flags & TF_EPI_RESID) && !splitk) v = res_lds[cc * 16 + bb] + v;
       st_act(outp + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc, v);   // split-K: the partial sums of this part
     }
+  }
+  if (MEGA || splitk) {
+    // every wavefront's coherent stores complete before anyone is told
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_barrier();
+  }
+  if (wave == 0) {
     if (splitk) {
-      // arrival at the row block's counter once the partial sums are visible; the last of the
+      // arrival at the row block's counter now that the partial sums are visible; the last of the
       // `parts` tasks adds the parts in order, and the residual, into the real output
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       uint32_t last = 0;
       if (lane == 0) {
         const uint32_t old = __hip_atomic_fetch_add(as_global(a.g->grp_counters + t.p2), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
