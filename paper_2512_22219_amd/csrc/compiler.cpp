@@ -951,11 +951,7 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
       }
     }
     else if (op.kind == MPK_OP_EXPERT) {
-      // input tiles as in the matrix-core linear body: up to 8 token rows x 2048 inputs, or up
-      // to 16 x 1024; + sums of squares
-      const size_t t8 = 2 * (size_t)std::min(c.batch, 8u) * (2048 + 8);
-      const size_t t16 = c.batch > 8 ? 2 * (size_t)c.batch * (1024 + 8) : 0;
-      f = std::max<size_t>(std::max(t8, t16), 8 * 4 * 256) + 8 * 16 + 32;   // + sums of squares + staged row lists
+      f = (size_t)moe_x_floats(c.batch) + 8 * 16 + 32;   // input tiles | sums of squares | staged row lists
     }
     else if (op.kind == MPK_OP_ROUTER)
       f = (size_t)c.batch * c.top_k * 2 + (size_t)c.n_experts * (3 + 16) + 64;   // pairs | per-expert counts, offsets, masks, pair table
@@ -977,6 +973,7 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
   if (moe) {
     if (!c.top_k || !c.expert_ffn || c.top_k > c.n_experts) { set_error("mixture-of-experts: top_k and expert_ffn must be non-zero and top_k <= n_experts"); return MPK_ERR_INVALID_ARG; }
     if (c.n_experts > kMoeMaxExperts || c.top_k > kMoeMaxTopK || c.batch * c.top_k > kMoeMaxPairs) { set_error("mixture-of-experts: at most %u experts, top_k %u, batch x top_k %u", kMoeMaxExperts, kMoeMaxTopK, kMoeMaxPairs); return MPK_ERR_UNSUPPORTED; }
+    if (o.tiles_moe > 4096) { set_error("tiles_moe %u too large (max 4096)", o.tiles_moe); return MPK_ERR_INVALID_ARG; }
     if (c.expert_ffn % 8 || c.expert_ffn < 32 || c.hidden % 16) { set_error("mixture-of-experts: expert_ffn must be a multiple of 8 (at least 32) and hidden a multiple of 16"); return MPK_ERR_UNSUPPORTED; }
   } else {
     if (c.top_k || c.expert_ffn) { set_error("top_k / expert_ffn set without n_experts"); return MPK_ERR_INVALID_ARG; }

@@ -170,6 +170,16 @@ mpk_status build_dag_graph(uint32_t n_tasks, const uint32_t* pairs, size_t n_pai
 inline uint32_t moe_meta_words(uint32_t E, uint32_t P) { return 2 + 3 * E + 3 * P; }
 constexpr uint32_t kMoeMaxExperts = 512, kMoeMaxPairs = 256, kMoeMaxTopK = 16;
 
+// LDS floats the input tiles of an expert job (or the partial tiles that reuse them) take: up to
+// 8 token rows x 2048 inputs or up to 16 x 1024, two bf16 planes, two buffers.  One definition
+// for the host's LDS requirement and the kernel's layout.
+constexpr uint32_t moe_x_floats(uint32_t batch) {
+  const uint32_t t8 = 2u * (batch < 8u ? batch : 8u) * (2048u + 8u);
+  const uint32_t t16 = batch > 8u ? 2u * batch * (1024u + 8u) : 0u;
+  const uint32_t m = t8 > t16 ? t8 : t16;
+  return m > 8u * 4u * 256u ? m : 8u * 4u * 256u;
+}
+
 // LDS layout constants shared with the kernels
 constexpr uint32_t kThreads = 512;        // worker workgroup size (8 wavefronts, two per SIMD)
 constexpr uint32_t kLdsReduceFloats = 1024;  // scratch for cross-wave reductions

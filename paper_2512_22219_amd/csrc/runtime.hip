@@ -991,13 +991,6 @@ __device__ __forceinline__ void body_moe_route(const TaskDesc& t, const StepArgs
   }
 }
 
-// Floats of LDS the input tiles (or the partial tiles that reuse them) of an expert job take.
-__device__ __forceinline__ uint32_t moe_x_floats(uint32_t batch) {
-  const uint32_t t8 = 2u * min(batch, 8u) * (2048u + 8u);
-  const uint32_t t16 = batch > 8u ? 2u * batch * (1024u + 8u) : 0u;
-  return max(max(t8, t16), 8u * 4u * 256u);
-}
-
 // `ntile` 16-row tiles of one expert's weight matrix, starting at tile `tile0`, times the `ne`
 // token rows routed to that expert: the matrix-core scheme of linear_task_mfma with the input rows
 // gathered through the expert's pair list.  All wavefronts take part; ntile <= 32, ne <= 16.

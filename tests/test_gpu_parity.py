@@ -284,3 +284,40 @@ def test_moe_three_steps_match_oracle(variant, opts):
         tok = want.argmax(-1)
         pos = pos + 1
     gpu.close()
+
+
+@pytest.mark.parametrize("batch", [1, 8])
+def test_moe_routing_ties_take_the_lower_expert_index(batch):
+    """Exact ties among router outputs (duplicated router rows): both sides must keep the lower
+    expert indices, in the GEMV path (batch 1) and the matrix-core path (batch 8)."""
+    from synth.device import DeviceModel
+    s = G.small_variant("C1", ffn=0, batch=batch, n_experts=8, top_k=2, expert_ffn=64)
+    prov = G.SynthWeights(s, 5)
+    model = DeviceModel(s, 5)
+    for l in range(s.n_layers):
+        host_r = prov.layer(l)[G.L_ROUTER]
+        dev_r = model.layers[l]["router"]
+        if l == 0:      # every expert ties with every other
+            host_r[1:] = host_r[0]
+            dev_r[1:] = dev_r[0:1].clone()
+        else:           # two groups of four identical rows
+            host_r[1:4] = host_r[0]
+            host_r[5:8] = host_r[4]
+            dev_r[1:4] = dev_r[0:1].clone()
+            dev_r[5:8] = dev_r[4:5].clone()
+    torch.cuda.synchronize()
+    ref = D.DecoderOracle(s, prov, "f32")
+    gpu = GpuDecoder(s, 5, model=model, fusion=31, transitive_reduction=1)
+    rng = np.random.default_rng(3)
+    tok, pos = rng.integers(0, s.vocab, batch), rng.integers(10, 120, batch)
+    want = ref.step(tok, pos)
+    got = gpu.step(tok, pos)
+    ex, wt = gpu.graph.moe_selection()
+    ex = ex.reshape(s.n_layers, batch, s.top_k)
+    wt = wt.reshape(s.n_layers, batch, s.top_k)
+    assert np.array_equal(ex[0], np.tile([0, 1], (batch, 1)))
+    assert np.allclose(wt[0], 0.5, atol=1e-6)
+    assert np.array_equal(ex, ref.last_moe_sel)
+    assert set(map(tuple, ex[1].tolist())) <= {(0, 1), (4, 5)}
+    assert rel_err(got, want) < TOL
+    gpu.close()
