@@ -176,6 +176,9 @@ __device__ __forceinline__ float2 ld_act2(const float* p) {   // p 8-byte aligne
 __device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p) {
   return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ uint64_t ld_relaxed64(const uint64_t* p) {
+  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ void st_act_u32(uint32_t* p, uint32_t v) {
   __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -386,6 +389,35 @@ __device__ __forceinline__ void lds_barrier() {
 
 __device__ __forceinline__ void signal_from_wave0(const StepArgs& a, const TaskDesc& t, int32_t e, int lane);
 __device__ __forceinline__ void poll_event_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane);
+__device__ __forceinline__ void poll_event_or_jit_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane, uint32_t jit_head);
+// Hybrid launch (Section 5.2): a worker may start the linear task at the head of its ahead-of-time
+// queue before that task's event is activated (so the weights are requested early), provided it
+// keeps an eye on its just-in-time queue while it waits: a worker that blocked regardless could
+// sit on the very tasks the awaited event depends on.  When a just-in-time task arrives first,
+// the linear task gives up (kLinPreempted, task index in s_flag[1]); the worker runs that task and
+// starts the linear task again.  (Running it from inside the wait would keep the pre-loaded
+// weights live across a call: the compiler then moves them to scratch memory for good.)
+// NoJit: all-ahead-of-time kernels, nothing to watch.
+constexpr uint32_t kLinAbort = 0, kLinDone = 1, kLinPreempted = 2;
+struct NoJit {
+  static constexpr bool enabled = false;
+  uint32_t jit_head = 0;
+};
+struct JitWatch {
+  static constexpr bool enabled = true;
+  uint32_t jit_head;   // the worker's consumer ticket of its just-in-time queue
+};
+// The wait of a linear task for its dependent event: kLinDone (activated), kLinAbort, kLinPreempted.
+template <class Svc>
+__device__ __forceinline__ uint32_t linear_wait(const StepArgs& a, int32_t wait_ev, uint32_t* s_flag, uint32_t wave, int lane,
+                                                const Svc& svc) {
+  if (wave == 0) {
+    if constexpr (Svc::enabled) poll_event_or_jit_wave0(a, wait_ev, s_flag, lane, svc.jit_head);
+    else poll_event_wave0(a, wait_ev, s_flag, lane);
+  }
+  lds_barrier();
+  return __builtin_amdgcn_readfirstlane(*s_flag);   // (uniform; tell the compiler)
+}
 
 // LDS layout of a linear task (floats): xs [NB][K rounded up to 4096] | outbuf [max ring rows][NB]
 // | resid [max columns][NB] | ssq [8][NB]; the two middle regions are sized by the compiler from
@@ -393,9 +425,9 @@ __device__ __forceinline__ void poll_event_wave0(const StepArgs& a, int32_t e, u
 //
 // Runs task `t`.  wait_ev >= 0: wait for that event first (persistent kernel).  Returns whether
 // the step is still alive (false: watchdog / abort).
-template <int NB, bool MEGA>
-__device__ __forceinline__ bool linear_task(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
-                                            uint32_t* s_flag) {
+template <int NB, bool MEGA, class Svc = NoJit>
+__device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
+                                                uint32_t* s_flag, const Svc& svc = Svc{}) {
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: geometry stays scalar
   const uint32_t K = t.K, nb = t.b1 - t.b0, ncols = t.c1 - t.c0;
@@ -411,9 +443,8 @@ __device__ __forceinline__ bool linear_task(const TaskDesc& t, const StepArgs& a
   if (g.nblocks > 0) lin_request_any(lin_block(g, 0, lane), ring, lane);
   // ---- dependent event: wavefront 0 polls, the others wait at the barrier
   if (wait_ev >= 0) {
-    if (wave == 0) poll_event_wave0(a, wait_ev, s_flag, lane);
-    lds_barrier();
-    if (__builtin_amdgcn_readfirstlane(*s_flag) == 0) return false;   // (uniform; tell the compiler)
+    const uint32_t w = linear_wait(a, wait_ev, s_flag, wave, lane, svc);
+    if (w != kLinDone) return w;   // aborted, or pre-empted by a just-in-time task: the requested weights are dropped
   }
   trace_mark(a, t, 1);
   // ---- stage the input rows in LDS.  With TF_PRO_NORM the gain is folded in here (x * g) and
@@ -545,7 +576,7 @@ __device__ __forceinline__ bool linear_task(const TaskDesc& t, const StepArgs& a
     if (MEGA && t.trig_event >= 0) signal_from_wave0(a, t, t.trig_event, lane);
     trace_mark(a, t, 4);
   }
-  return true;
+  return kLinDone;
 }
 
 // ------------------------------------------------------------------------------ linear tasks, batch 5..16
@@ -580,9 +611,9 @@ __device__ __forceinline__ uint32_t mfma_ktile(uint32_t nb) { return nb <= 8 ? 2
 // LDS (from the task area): xh [2][nb][Kt + 8] bf16 | xl same | res [residual columns][16] f32 |
 // ssq [8][16] f32 | 1/rms [16] f32; the per-wavefront partial tiles part [8][4][256] f32 reuse the
 // input buffers once the last input tile has been consumed.
-template <bool MEGA>
-__device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
-                                                 uint32_t* s_flag) {
+template <bool MEGA, class Svc = NoJit>
+__device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
+                                                     uint32_t* s_flag, const Svc& svc = Svc{}) {
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t K = t.K, nb = t.b1 - t.b0, ncols = t.c1 - t.c0;
@@ -635,9 +666,8 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
   if (has_work) request(row_ptr(my_rt0), 0u, my_slice * slice_len);
 
   if (wait_ev >= 0) {
-    if (wave == 0) poll_event_wave0(a, wait_ev, s_flag, lane);
-    lds_barrier();
-    if (__builtin_amdgcn_readfirstlane(*s_flag) == 0) return false;
+    const uint32_t w = linear_wait(a, wait_ev, s_flag, wave, lane, svc);
+    if (w != kLinDone) return w;   // aborted, or pre-empted by a just-in-time task: the requested weights are dropped
   }
   trace_mark(a, t, 1);
   const bool pro_norm = t.flags & TF_PRO_NORM;
@@ -837,7 +867,7 @@ __device__ __forceinline__ bool linear_task_mfma(const TaskDesc& t, const StepAr
     trace_mark(a, t, 4);
   }
   lds_barrier();   // the partial buffer is reused by the next task
-  return true;
+  return kLinDone;
 }
 
 // ------------------------------------------------------------------------------ mixture of experts
@@ -1837,16 +1867,16 @@ __device__ __forceinline__ void body_swiglu(const TaskDesc& t) {
 // at run time): a kernel that carries a single attention and a single linear variant keeps its
 // register allocation free of spills, the fully generic kernel does not.
 // Batch class -> body instance (NB = 0: decided at run time).
-template <int NB, bool MEGA>
-__device__ __forceinline__ bool run_linear(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
-                                           uint32_t* s_flag) {
-  if (NB == 8) return linear_task_mfma<MEGA>(t, a, lds, wait_ev, s_flag);   // batch class 5..16: matrix cores
-  if (NB != 0) return linear_task<(NB ? NB : 1), MEGA>(t, a, lds, wait_ev, s_flag);
+template <int NB, bool MEGA, class Svc = NoJit>
+__device__ __forceinline__ uint32_t run_linear(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
+                                           uint32_t* s_flag, const Svc& svc = Svc{}) {
+  if (NB == 8) return linear_task_mfma<MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);   // batch class 5..16: matrix cores
+  if (NB != 0) return linear_task<(NB ? NB : 1), MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
   const uint32_t nb = t.b1 - t.b0;
-  if (nb == 1) return linear_task<1, MEGA>(t, a, lds, wait_ev, s_flag);
-  if (nb == 2) return linear_task<2, MEGA>(t, a, lds, wait_ev, s_flag);
-  if (nb <= 4) return linear_task<4, MEGA>(t, a, lds, wait_ev, s_flag);
-  return linear_task_mfma<MEGA>(t, a, lds, wait_ev, s_flag);
+  if (nb == 1) return linear_task<1, MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
+  if (nb == 2) return linear_task<2, MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
+  if (nb <= 4) return linear_task<4, MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
+  return linear_task_mfma<MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
 }
 
 template <int D, int GRP, int NB>
@@ -2003,6 +2033,41 @@ __device__ __forceinline__ void poll_event_wave0(const StepArgs& a, int32_t e, u
   }
 }
 
+// Wavefront 0 only: like poll_event_wave0, but also watches the worker's just-in-time queue.
+// s_flag[0] = 1 event activated, 0 abort, 2 a just-in-time task (index in s_flag[1]) is queued.
+__device__ __forceinline__ void poll_event_or_jit_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane, uint32_t jit_head) {
+  if (lane == 0) {
+    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
+    const uint32_t* word;
+    uint32_t target;
+    if (ev.flags & EV_HIER) {
+      word = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
+      target = a.epoch * ev.n_groups;
+    } else {
+      word = a.counters + e;
+      target = a.epoch * ev.required;
+    }
+    const uint64_t* slot = a.g->wq_buf + (size_t)blockIdx.x * a.g->wq_cap + (jit_head & (a.g->wq_cap - 1u));
+    const uint64_t t_start = wall_clock64();
+    uint32_t ok, it = 0;
+    while (true) {
+      if ((int32_t)(ld_relaxed(word) - target) >= 0) { ok = 1; break; }
+      const uint64_t v = ld_relaxed64(slot);
+      if ((uint32_t)(v >> 32) == jit_head + 1u) { s_flag[1] = (uint32_t)v; ok = 2; break; }
+      if ((++it & 127u) == 0) {
+        if (ld_relaxed(a.g->err + 1) != 0) { ok = 0; break; }
+        if (wall_clock64() - t_start > a.g->timeout_ticks) {
+          report(a, DE_TIMEOUT, (uint32_t)e, blockIdx.x);
+          __hip_atomic_store(as_global(a.g->err + 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          ok = 0;
+          break;
+        }
+      }
+    }
+    s_flag[0] = ok;
+  }
+}
+
 // Wavefront 0 only, after a workgroup barrier: wait for this wavefront's own coherent stores,
 // then notify the event.
 __device__ __forceinline__ void signal_from_wave0(const StepArgs& a, const TaskDesc& t, int32_t e, int lane) {
@@ -2087,9 +2152,6 @@ __device__ __forceinline__ bool event_active(const StepArgs& a, int32_t e) {
   return (int32_t)(ld_relaxed(a.counters + e) - a.epoch * ev.required) >= 0;
 }
 
-__device__ __forceinline__ uint64_t ld_relaxed64(const uint64_t* p) {
-  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 // One scheduler wavefront (Section 5.1): takes activated events from its own queue and hands the
 // just-in-time tasks of each event's range to the workers' queues, round-robin from a cursor of
@@ -2099,6 +2161,9 @@ __device__ __forceinline__ void scheduler_wave(const StepArgs& a, uint32_t sc) {
   const uint32_t W = a.g->n_workers;
   uint32_t head = ld_relaxed(a.g->sched_state + sc * 64u), cursor = ld_relaxed(a.g->sched_state + sc * 64u + 1u);
   uint32_t todo = ld_u32c(a.g->sched_nev + sc);
+  // schedulers that hand out the same number of tasks per layer move their cursors in lock-step:
+  // start them evenly spread over the workers, or they would all pile onto the same few
+  const uint32_t spread = sc * (W / a.n_sched);
   // the start event has no notifications: its owner dispatches it unprompted
   const MPK_CONST EventDesc& sev = *(const MPK_CONST EventDesc*)(a.events + a.g->start_event);
   bool pending_start = (sev.flags & EV_JIT) && a.g->start_event % a.n_sched == sc;
@@ -2139,7 +2204,7 @@ __device__ __forceinline__ void scheduler_wave(const StepArgs& a, uint32_t sc) {
       const uint32_t ti = first + i;
       const MPK_CONST TaskDesc& td = *(const MPK_CONST TaskDesc*)(a.tasks + ti);
       if (td.flags & TF_JIT) {
-        const uint32_t w = (cursor + i) % W;
+        const uint32_t w = (cursor + spread + i) % W;
         const uint32_t s = __hip_atomic_fetch_add(as_global(a.g->wq_tail + w * 64u), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(as_global(a.g->wq_buf + (size_t)w * a.g->wq_cap + (s & (a.g->wq_cap - 1u))),
                            ((uint64_t)(s + 1u) << 32) | ti, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -2156,7 +2221,8 @@ __device__ __forceinline__ void scheduler_wave(const StepArgs& a, uint32_t sc) {
 constexpr uint32_t kPickExit = 0xFFFFFFFFu, kPickAbort = 0xFFFFFFFEu;
 
 // Worker side of the hybrid launch (Section 5.2): just-in-time tasks first; when none is queued,
-// the head of the ahead-of-time queue if its dependent event is activated; exit once the
+// the head of the ahead-of-time queue if its dependent event is activated (or, for a linear task,
+// regardless: see linear_wait); exit once the
 // ahead-of-time queue is exhausted and the terminal event has been activated.  One lane decides,
 // the result goes through LDS.  Returns a task index (bit 31 set: it came from the JIT queue).
 __device__ __forceinline__ uint32_t pick_task(const StepArgs& a, uint32_t* ctrl, uint32_t* jit_head, uint32_t* ai, uint32_t q1) {
@@ -2174,8 +2240,11 @@ __device__ __forceinline__ uint32_t pick_task(const StepArgs& a, uint32_t* ctrl,
       }
       if (*ai < q1) {
         const uint32_t ti = ld_u32c(a.g->aot + *ai);
-        const int32_t dep = ((const MPK_CONST TaskDesc*)(a.tasks + ti))->dep_event;
-        if (dep < 0 || event_active(a, dep)) {
+        const MPK_CONST TaskDesc* td = (const MPK_CONST TaskDesc*)(a.tasks + ti);
+        const int32_t dep = td->dep_event;
+        // a linear task may start before its event: it requests its weights, then waits for the
+        // event itself while serving this worker's just-in-time queue (linear_wait)
+        if (dep < 0 || td->kind == TK_LINEAR || event_active(a, dep)) {
           pick = ti;
           ++*ai;
           break;
@@ -2248,7 +2317,16 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
     if (t.kind == TK_LINEAR) {
       trace_mark(a, t, 0);
       if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
-      if (!run_linear<NB, true>(t, a, lds, -1, s_flag)) break;   // its event is already activated
+      const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
+      uint32_t r;
+      // started before its event is activated; a just-in-time task that arrives first pre-empts it
+      while ((r = run_linear<NB, true>(t, a, lds, wait_ev, s_flag, JitWatch{jit_head})) == kLinPreempted) {
+        const uint32_t tj = __builtin_amdgcn_readfirstlane(((uint32_t*)dyn_lds)[1]);
+        lds_barrier();   // everybody has read the control word
+        ++jit_head;
+        if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(a, tj, true))) { r = kLinAbort; break; }
+      }
+      if (r == kLinAbort) break;
     } else {
       if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(a, ti, true))) break;
     }
