@@ -236,11 +236,14 @@ mpk_status mpk_graph_export(const mpk_graph *g, void *buf, size_t cap, size_t *n
 
 /* Per-task timeline of the LAST decode step of a graph compiled with MPK_DEBUG_TRACE (the
  * counterpart of the paper's run-time overhead accounting, Section 6.5 "kernel-launch
- * reduction").  buf: host u64 [n_tasks][8] in linearized task order: 0 task picked up, 1 dependent
- * event seen, 2 input staged (linear and attention tasks), 3 body finished (first wavefront),
- * 4 triggering event notified, 6 first wavefront's stores completed, 7 all wavefronts' stores
- * completed, all in ticks of the 100 MHz device wall clock; 5 worker index.  Call after synchronising the stream.
- * buf == NULL returns the element count in *need. */
+ * reduction").  buf: host u64 [n_tasks][12] in linearized task order, ticks of the 100 MHz device
+ * wall clock unless noted: 0 task picked up, 1 dependent event seen, 2 input staged (linear and
+ * attention tasks), 3 body finished (first wavefront), 4 triggering event notified, 5 worker
+ * index (not a time), 6 first wavefront's stores completed, 7 all wavefronts' stores completed,
+ * 8 multiply phase finished (matrix-core linear tasks), 10 attention: this task's partial result
+ * combined over its wavefronts, 11 attention: partial result stored.  Slots a task kind does not
+ * use stay 0.
+ * Call after synchronising the stream.  buf == NULL returns the element count in *need. */
 mpk_status mpk_graph_trace(mpk_graph *g, uint64_t *buf, size_t cap, size_t *need);
 
 /* Mixture-of-experts graphs: the number of distinct experts the LAST decode step selected in each
