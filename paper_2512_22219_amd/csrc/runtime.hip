@@ -1124,12 +1124,30 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
         for (uint32_t kk = s_lo; kk < s_hi; kk += 32u * kRound) {
           request(wp, k0, kk);
 #pragma unroll
-          for (int q = 0; q < kRound; ++q) {
-            if (kk + q * 32u < s_hi) {
-              const u32x4 bhv = *(const u32x4*)(bh + kk + q * 32u), blv = *(const u32x4*)(bl + kk + q * 32u);
-              const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q]);
-              acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bhv), acc[j], 0, 0, 0);
-              acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, blv), acc[j], 0, 0, 0);
+          for (int q0 = 0; q0 < kRound; q0 += 4) {
+            if (kk + (q0 + 4) * 32u <= s_hi) {   // four steps without per-step tests, their LDS reads first
+              u32x4 hv[4], lv[4];
+#pragma unroll
+              for (int u = 0; u < 4; ++u) {
+                hv[u] = *(const u32x4*)(bh + kk + (q0 + u) * 32u);
+                lv[u] = *(const u32x4*)(bl + kk + (q0 + u) * 32u);
+              }
+#pragma unroll
+              for (int u = 0; u < 4; ++u) {
+                const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, hv[u]), acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, lv[u]), acc[j], 0, 0, 0);
+              }
+            } else {
+#pragma unroll
+              for (int u = 0; u < 4; ++u) {
+                if (kk + (q0 + u) * 32u < s_hi) {
+                  const u32x4 bhv = *(const u32x4*)(bh + kk + (q0 + u) * 32u), blv = *(const u32x4*)(bl + kk + (q0 + u) * 32u);
+                  const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
+                  acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bhv), acc[j], 0, 0, 0);
+                  acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, blv), acc[j], 0, 0, 0);
+                }
+              }
             }
           }
         }
