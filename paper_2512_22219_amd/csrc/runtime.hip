@@ -758,8 +758,8 @@ __device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const St
   };
   for (uint32_t tile = 0; tile < ntile; ++tile) {
     const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
-    // (this wavefront's first round of the tile is already under way: requested before the event
-    // wait, or at the end of the previous tile)
+    // (the very first round is already under way: requested before the event wait.  Requesting
+    // each next tile's first round before the conversion and the barrier was measured: no gain.)
     if (tile + 1 < ntile) stage_issue(tile + 1);   // in flight during this tile's arithmetic
     const uint16_t* ch = xh + (size_t)(tile & 1u) * xplane;
     const uint16_t* cl = xl + (size_t)(tile & 1u) * xplane;
@@ -773,13 +773,11 @@ __device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const St
         const uint16_t* bh = ch + (size_t)(frow % nb) * xstride + fk;
         const uint16_t* bl = cl + (size_t)(frow % nb) * xstride + fk;
         for (uint32_t kk = s_lo; kk < s_hi; kk += 32u * kMfmaRound) {
-          if (!(j == 0 && kk == s_lo)) request(wp, k0, kk);
+          if (!(tile == 0 && j == 0 && kk == s_lo)) request(wp, k0, kk);
           consume(acc[j], bh, bl, kk, s_hi);
         }
       }
     }
-    // the next tile's first round goes out before the conversion and the barrier
-    if (tile + 1 < ntile && has_work) request(row_ptr(my_rt0), k0 + Kt, s_lo);
     if (tile + 1 < ntile) stage_write(tile + 1);   // into the other buffer: nobody reads it now
     lds_barrier();
   }
