@@ -1103,12 +1103,14 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
       }
     }
   };
-  stage_issue(0);
-  stage_write(0);
-  lds_barrier();
   for (uint32_t tile = 0; tile < ntk; ++tile) {
     const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
-    if (tile + 1 < ntk) stage_issue(tile + 1);
+    // An expert's input is nearly always a single tile (up to 8 tokens x 2048 inputs), so the
+    // staging is not overlapped with the multiplies here: its registers are then free during the
+    // multiply loop, which is what this function is short of.
+    stage_issue(tile);
+    stage_write(tile);
+    lds_barrier();
     const uint16_t* ch = xh + (size_t)(tile & 1u) * xplane;
     const uint16_t* cl = xl + (size_t)(tile & 1u) * xplane;
     const uint32_t s_lo = my_slice * slice_len, s_hi = min(s_lo + slice_len, (klen + 31u) & ~31u);
@@ -1151,9 +1153,8 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
         }
       }
     }
-    if (tile + 1 < ntk) stage_write(tile + 1);
-    lds_barrier();
   }
+  lds_barrier();   // the partial tiles reuse the input buffers
 #pragma unroll
   for (int j = 0; j < 4; ++j)
 #pragma unroll
