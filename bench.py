@@ -77,6 +77,10 @@ def main():
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain copy kernel of this many MiB (synth_copy_kernel): "
                          "a launch of known HBM traffic to scale profiler byte counters by")
+    ap.add_argument("--tokens-per-launch", type=int, default=1,
+                    help="N > 1: compile the graph with the sampling operator and decode N tokens per "
+                         "launch of the persistent kernel (no arg max / copy kernels between tokens); "
+                         "--steps must be a multiple of N")
     ap.add_argument("--opt", action="append", default=[], metavar="NAME=INT",
                     help="extra mpk_compile_options field, e.g. --opt attn_chunks=32")
     args = ap.parse_args()
@@ -105,7 +109,18 @@ def main():
     n_total = args.steps + args.warmup
     assert int(pos0.max()) + n_total <= shape.max_seq
 
+    tpl = args.tokens_per_launch
+    assert tpl >= 1 and args.steps % tpl == 0 and args.warmup % tpl == 0, "--steps and --warmup must be multiples of --tokens-per-launch"
+
     def run(graph, n, events=None):
+        if tpl > 1 and getattr(graph, "multi", False):
+            for i in range(0, n, tpl):
+                if events is not None:
+                    events[i][0].record()
+                graph.decode_steps(tpl, tok.data_ptr(), pos.data_ptr(), 0, logits.data_ptr(), 0, stream)
+                if events is not None:
+                    events[i][1].record()
+            return
         for i in range(n):
             if events is not None:
                 events[i][0].record()
@@ -131,12 +146,15 @@ def main():
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         graph.status()
-        kern_ms = [a.elapsed_time(b) for a, b in ev]
+        step = tpl if getattr(graph, "multi", False) else 1
+        kern_ms = [ev[i][0].elapsed_time(ev[i][1]) / step for i in range(0, args.steps, step)]
         return dt, kern_ms
 
     common = dict(fusion=args.fusion, transitive_reduction=1)
     common.update({k: int(v) for k, v in (o.split("=", 1) for o in args.opt)})
-    mega = M.compile_graph(shape, model.weight_ptrs(), model.kv_ptrs(), launch_mode=0, **common)
+    mega = M.compile_graph(shape, model.weight_ptrs(), model.kv_ptrs(), launch_mode=0,
+                           **common, **({"greedy_loop": 1} if tpl > 1 else {}))
+    mega.multi = tpl > 1
     stats = mega.stats()
     dt, kern_ms = timed(mega)
     final_tokens = tok.cpu().numpy().tolist()
@@ -146,6 +164,7 @@ def main():
     pos_avg = float(pos0.float().sum()) + shape.batch * (args.warmup + (args.steps - 1) / 2 + 1)
     bytes_step = stats["weight_bytes"] + stats["kv_row_bytes"] * pos_avg
     moe_active_avg = None
+    assert not (stats["expert_bytes"] and tpl > 1), "--tokens-per-launch > 1 is not wired up for the MoE byte count"
     if stats["expert_bytes"]:
         # mixture of experts: a step streams only the experts it selected.  Replay the same greedy
         # trajectory off the clock and read the number of distinct experts per layer after
@@ -174,7 +193,8 @@ def main():
                                f"vocab {shape.vocab}, batch {shape.batch}, KV "
                                f"{shape.kv_len_lo}" + (f"..{shape.kv_len_hi}" if shape.kv_len_hi != shape.kv_len_lo else "")
                                + " prior positions, greedy decode",
-                   "launch": "persistent mega-kernel", "fusion": args.fusion,
+                   "launch": "persistent mega-kernel" + (f", {tpl} tokens per launch" if tpl > 1 else ""),
+                   "fusion": args.fusion,
                    "n_workers": stats["n_workers"], "tasks": stats["n_tasks"],
                    "events": stats["n_events"],
                    **({"distinct_experts_per_step": moe_active_avg} if moe_active_avg is not None else {})},

@@ -121,6 +121,11 @@ typedef struct mpk_compile_options {
   uint32_t tiles_moe;       /* expert tasks per expert stage of a mixture-of-experts layer
                                (Section 6.4: expert tasks are fixed at compile time and split
                                the active experts' rows evenly at run time); 0 = n_workers      */
+  uint32_t greedy_loop;     /* 1 = append a greedy-sampling operator (arg max of the logits,
+                               lowest index on ties, one task per sequence) so that several
+                               tokens can be decoded in ONE launch (mpk_decode_steps): the
+                               kernel runs until its workload is done (Section 5).  Such a
+                               graph is run with mpk_decode_steps only                          */
 } mpk_compile_options;
 
 typedef struct mpk_graph mpk_graph;
@@ -155,6 +160,20 @@ mpk_status mpk_compile_dag(uint32_t n_tasks, const uint32_t *pairs, size_t n_pai
  * mpk_graph_status.  Steps of one graph must not overlap (same stream, or externally ordered). */
 mpk_status mpk_decode_step(mpk_graph *g, const int32_t *token_ids, const int32_t *positions,
                            float *logits_out, void *stream);
+
+/* Decode n_steps tokens greedily in one launch of the persistent kernel (Section 5: the kernel
+ * keeps running until the workload completes; no host round trip between tokens).  Only for graphs
+ * compiled with greedy_loop = 1 and without scheduler workgroups; with MPK_LAUNCH_PER_OP the host
+ * issues the operator kernels of every step instead.
+ *   token_ids  : device int32 [batch], IN: the tokens to feed first; OUT: the last tokens sampled
+ *   positions  : device int32 [batch], IN: rows already cached; OUT: advanced by n_steps
+ *   tokens_out : device int32 [n_steps][batch] or NULL: the token sampled at every step
+ *   logits_out : device fp32 [batch][vocab]: logits of the LAST step
+ *   logits_all : device fp32 [n_steps][batch][vocab] or NULL: a copy of every step's logits
+ * Step s reads and appends K/V rows at positions[b] + s; every position must stay below max_seq.
+ * Asynchronous on `stream`; errors as mpk_decode_step. */
+mpk_status mpk_decode_steps(mpk_graph *g, uint32_t n_steps, int32_t *token_ids, int32_t *positions,
+                            int32_t *tokens_out, float *logits_out, float *logits_all, void *stream);
 
 /* After the stream has been synchronised by the caller: translate the device error word.
  * MPK_OK, MPK_ERR_TIMEOUT (watchdog; the graph must be reset) or MPK_ERR_DEVICE. */
@@ -229,7 +248,7 @@ typedef struct mpk_export_event {
 enum {
   MPK_OP_EMBED = 0, MPK_OP_RMSNORM = 1, MPK_OP_LINEAR = 2, MPK_OP_ROPE = 3,
   MPK_OP_ATTN_PARTIAL = 4, MPK_OP_ATTN_MERGE = 5, MPK_OP_ADD = 6, MPK_OP_SWIGLU = 7,
-  MPK_OP_GATEUP = 8, MPK_OP_ROUTER = 9, MPK_OP_EXPERT = 10, MPK_OP_COMBINE = 12
+  MPK_OP_GATEUP = 8, MPK_OP_ROUTER = 9, MPK_OP_EXPERT = 10, MPK_OP_COMBINE = 12, MPK_OP_ARGMAX = 13
 };
 
 mpk_status mpk_graph_export(const mpk_graph *g, void *buf, size_t cap, size_t *need);

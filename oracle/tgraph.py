@@ -27,7 +27,7 @@ F_NORM, F_RESID, F_SWIGLU, F_MERGE, F_ROPE = 1, 2, 4, 8, 16
 
 # operator kinds (same numbering as the exported op table)
 (K_EMBED, K_RMSNORM, K_LINEAR, K_ROPE, K_ATTN_PARTIAL, K_ATTN_MERGE, K_ADD, K_SWIGLU,
- K_GATEUP, K_ROUTER, K_EXPERT, K_DUMMY, K_COMBINE) = range(13)
+ K_GATEUP, K_ROUTER, K_EXPERT, K_DUMMY, K_COMBINE, K_ARGMAX) = range(14)
 
 
 def split_even(n: int, k: int):
@@ -53,7 +53,8 @@ class OpSpec:
     meta: dict = field(default_factory=dict)
 
 
-def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: int = 1):
+def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: int = 1,
+              greedy_loop: bool = False):
     """Operator list of one decode step for model shape `s` (synth.gen.ModelShape) under the
     given fusion flags, in execution order.
 
@@ -147,6 +148,8 @@ def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: 
     else:
         ops.append(OpSpec("final_norm", K_RMSNORM, -1, "xnf", B, H, H, [x]))
         ops.append(OpSpec("lm_head", K_LINEAR, -1, "logits", B, V, 1, ["xnf"], {"K": H}))
+    if greedy_loop:   # greedy sampling as an operator: next token of each sequence
+        ops.append(OpSpec("argmax", K_ARGMAX, -1, "ntok", B, 1, 1, ["logits"]))
     return ops
 
 
@@ -235,6 +238,8 @@ def read_elements(op: OpSpec, tb: int, tc: int, tile: int, shapes: dict):
         m = mask(op.ins[0])
         m[b0:b1, c0:c1] = True
         m[b0:b1, F + c0:F + c1] = True
+    elif k == K_ARGMAX:
+        mask(op.ins[0])[b0:b1, :] = True                # the largest of all logits of the sequence
     elif k == K_ROUTER:
         mask(op.ins[0])[:, :] = True                    # top-k of every token, lists per expert
     elif k == K_EXPERT:

@@ -21,6 +21,7 @@ TASK_DUMMY_OP = 0xFFFFFFFF
 (OP_EMBED, OP_RMSNORM, OP_LINEAR, OP_ROPE, OP_ATTN_PARTIAL, OP_ATTN_MERGE, OP_ADD, OP_SWIGLU,
  OP_GATEUP, OP_ROUTER, OP_EXPERT) = range(11)
 OP_COMBINE = 12
+OP_ARGMAX = 13
 
 
 class ModelConfig(C.Structure):
@@ -51,7 +52,7 @@ class CompileOptions(C.Structure):
                 ("struct_size", "n_workers", "n_sched_wgs", "fusion", "transitive_reduction",
                  "attn_chunks", "tiles_linear", "tiles_lm_head", "tiles_pointwise", "launch_mode",
                  "force_aot", "prefetch", "host_only", "spin_timeout_ms", "debug_flags",
-                 "tiles_moe")]
+                 "tiles_moe", "greedy_loop")]
 
 
 class Stats(C.Structure):
@@ -81,7 +82,7 @@ EXPORT_TASK = np.dtype([("op", "<u4"), ("tile", "<u4"), ("dep_event", "<i4"),
 EXPORT_EVENT = np.dtype([("required", "<u4"), ("first", "<u4"), ("last", "<u4"),
                          ("flags", "<u4")])
 
-SYMBOLS = ("mpk_compile", "mpk_compile_dag", "mpk_decode_step", "mpk_graph_status",
+SYMBOLS = ("mpk_compile", "mpk_compile_dag", "mpk_decode_step", "mpk_decode_steps", "mpk_graph_status",
            "mpk_graph_reset", "mpk_graph_stats", "mpk_graph_export", "mpk_graph_trace",
            "mpk_graph_moe_active", "mpk_graph_moe_selection", "mpk_last_error",
            "mpk_graph_destroy")
@@ -103,6 +104,7 @@ def lib():
         L.mpk_compile_dag.argtypes = [C.c_uint32, vp, C.c_size_t, C.POINTER(CompileOptions),
                                       C.POINTER(vp)]
         L.mpk_decode_step.argtypes = [vp, vp, vp, vp, vp]
+        L.mpk_decode_steps.argtypes = [vp, C.c_uint32, vp, vp, vp, vp, vp, vp]
         L.mpk_graph_status.argtypes = [vp]
         L.mpk_graph_reset.argtypes = [vp]
         L.mpk_graph_stats.argtypes = [vp, C.POINTER(Stats)]
@@ -113,7 +115,7 @@ def lib():
         L.mpk_last_error.restype = C.c_char_p
         L.mpk_graph_destroy.argtypes = [vp]
         L.mpk_graph_destroy.restype = None
-        for n in SYMBOLS[:10]:
+        for n in SYMBOLS[:11]:
             getattr(L, n).restype = C.c_int
         _lib = L
     return _lib
@@ -180,6 +182,11 @@ class Graph:
 
     def decode_step(self, token_ids_ptr: int, positions_ptr: int, logits_ptr: int, stream: int = 0):
         _check(lib().mpk_decode_step(self._h, token_ids_ptr, positions_ptr, logits_ptr, stream))
+
+    def decode_steps(self, n_steps: int, token_ids_ptr: int, positions_ptr: int, tokens_out_ptr: int,
+                     logits_ptr: int, logits_all_ptr: int = 0, stream: int = 0):
+        _check(lib().mpk_decode_steps(self._h, n_steps, token_ids_ptr, positions_ptr, tokens_out_ptr or None,
+                                      logits_ptr, logits_all_ptr or None, stream))
 
     def status(self):
         _check(lib().mpk_graph_status(self._h))

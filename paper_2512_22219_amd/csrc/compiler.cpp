@@ -615,6 +615,13 @@ static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
     op.w = w ? w->lm_head : nullptr; op.K = H; op.flags |= TF_OUT_LOGITS;
     if (f & MPK_FUSE_NORM) { op.flags |= TF_PRO_NORM; op.w2 = w ? w->final_norm : nullptr; op.f0 = c.rms_eps; reads_x(op, false); }
   }
+  if (o.greedy_loop) {
+    // greedy sampling inside the graph: the tokens of the next step (one task per sequence);
+    // with it the kernel can go round again without the host (multi-token launch)
+    int ntok = b.new_tensor(B, 1);
+    HostOp& op = b.add(MPK_OP_ARGMAX, -1, "argmax", ntok, 1, logits);
+    op.K = V;
+  }
   return MPK_OK;
 }
 
@@ -676,6 +683,10 @@ static void choose_partitions(const mpk_model_config& c, const mpk_compile_optio
       case MPK_OP_SWIGLU:
         op.tb = op.rows;
         op.tc = std::max(1u, std::min(o.tiles_pointwise ? o.tiles_pointwise : 1u, nu));
+        break;
+      case MPK_OP_ARGMAX:
+        op.tb = op.rows;
+        op.tc = 1;
         break;
       case MPK_OP_ROUTER:   // one task: the per-expert token lists need every token's choice
         op.tb = 1;
@@ -774,6 +785,9 @@ static void input_rects(const mpk_model_config& c, const HostOp& op, uint32_t ti
       break;
     case MPK_OP_ROUTER:   // every token's router output
       out.push_back({op.in_tensor, 0, UINT32_MAX, 0, UINT32_MAX});
+      break;
+    case MPK_OP_ARGMAX:   // all logits of its sequences
+      out.push_back({op.in_tensor, b0, b1, 0, UINT32_MAX});
       break;
     case MPK_OP_EXPERT:   // the meta-tensor + whatever routing sends here: statically everything
       out.push_back({op.in_tensor, 0, UINT32_MAX, 0, UINT32_MAX});
@@ -890,6 +904,7 @@ static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGr
       case MPK_OP_ROUTER: t.kind = TK_MOE_ROUTE; break;
       case MPK_OP_EXPERT: t.kind = TK_MOE_EXPERT; break;
       case MPK_OP_COMBINE: t.kind = TK_MOE_COMBINE; break;
+      case MPK_OP_ARGMAX: t.kind = TK_ARGMAX; break;
     }
     if (op.flags & TF_SPLITK) {
       const uint32_t Hh = op.p1, parts = op.p0, part = t.c0 / Hh, klen = op.K / parts;
@@ -987,6 +1002,7 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
   }
   if (c.hidden % 8 || (!moe && c.ffn % 8) || (c.n_q_heads * c.head_dim) % 8) { set_error("hidden, ffn and n_q*head_dim must be multiples of 8"); return MPK_ERR_UNSUPPORTED; }
   if (c.batch > 16) { set_error("batch %u unsupported by the dense linear bodies (max 16)", c.batch); return MPK_ERR_UNSUPPORTED; }
+  if (o.greedy_loop > 1) { set_error("greedy_loop must be 0 or 1"); return MPK_ERR_INVALID_ARG; }
   if (o.debug_flags & ~MPK_DEBUG_TRACE) { set_error("unknown debug_flags bits"); return MPK_ERR_INVALID_ARG; }
   if (o.fusion & ~(MPK_FUSE_NORM | MPK_FUSE_RESID | MPK_FUSE_SWIGLU | MPK_FUSE_MERGE | MPK_FUSE_ROPE)) { set_error("unknown fusion bits"); return MPK_ERR_INVALID_ARG; }
   if (!o.host_only) {

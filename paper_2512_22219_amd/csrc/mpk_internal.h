@@ -27,6 +27,7 @@ enum TaskKind : uint16_t {
   TK_MOE_ROUTE,     // softmax + top-k of every token's router output, builds the meta-tensor
   TK_MOE_EXPERT,    // a share of one expert stage (gate/up or down), sized from the meta-tensor
   TK_MOE_COMBINE,   // weighted sum of a token's expert outputs + residual
+  TK_ARGMAX,        // greedy sampling: arg max of one sequence's logits -> next token
 };
 
 enum TaskFlags : uint16_t {

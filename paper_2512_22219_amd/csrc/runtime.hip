@@ -18,6 +18,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstddef>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -63,6 +64,9 @@ struct GraphConst {
   uint32_t* wq_tail;         // [n_workers][64]
   uint32_t* wq_head;         // [n_workers] head ticket (persists across steps)
   uint32_t start_event, terminal_event;
+  // multi-token launch: written by mpk_decode_steps before the launch (stream-ordered copy)
+  int32_t* tokens_out;   // [n_steps][batch] or null
+  float* logits_all;     // [n_steps][batch][vocab] or null
 };
 
 // Per-step kernel arguments, passed by value.  Every device function taking it is force-inlined:
@@ -85,7 +89,15 @@ struct StepArgs {
   const int32_t* positions;
   float* logits;
   uint32_t epoch;
+  // multi-token launch (greedy_loop graphs): the kernel runs n_steps decode steps; `step` counts
+  // them and `epoch` grows with it.  positions[] stays as the host wrote it until the last step
+  // (tasks run ahead of the sampling, so they take positions[b] + step).  16 bits each, in what
+  // was padding: the struct is passed by value to every non-inlined task function, and a larger
+  // one measurably slows the single-step launch; the output pointers of such a launch are in
+  // the graph record for the same reason.
+  uint16_t step, n_steps;
 };
+static_assert(sizeof(StepArgs) == 88, "StepArgs grew: check the single-step launch time");
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -211,7 +223,7 @@ __device__ __forceinline__ void report(const StepArgs& a, uint32_t code, uint32_
 // T0: x[b] = E[token[b]] widened to fp32.
 __device__ __forceinline__ void body_embed(const TaskDesc& t, const StepArgs& a) {
   for (uint32_t b = t.b0; b < t.b1; ++b) {
-    int32_t tok = a.token_ids[b];
+    int32_t tok = (int32_t)ld_relaxed((const uint32_t*)a.token_ids + b);   // may come from the previous step's sampling task
     if (tok < 0 || (uint32_t)tok >= a.g->vocab) {
       if (threadIdx.x == 0) report(a, DE_BAD_TOKEN, b, (uint32_t)tok);
       tok = 0;
@@ -1263,7 +1275,7 @@ __device__ __forceinline__ void body_rope(const TaskDesc& t, const StepArgs& a) 
   const uint32_t d = a.g->head_dim, half = d / 2, nq = a.g->n_q, nkv = a.g->n_kv;
   const uint32_t s0 = t.c0 / d, s1 = t.c1 / d;
   for (uint32_t b = t.b0; b < t.b1; ++b) {
-    int32_t pos = a.positions[b];
+    int32_t pos = a.positions[b] + (int32_t)a.step;
     if (pos < 0 || (uint32_t)pos >= a.g->max_seq) {
       if (threadIdx.x == 0) report(a, DE_BAD_POSITION, b, (uint32_t)pos);
       continue;
@@ -1342,7 +1354,7 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
   float* wpart = qs + grp * d;           // [NW][grp][d + 2]: partial output, max, sum per wavefront
   uint32_t* flag = (uint32_t*)(wpart + NW * grp * (d + 2));   // then [16..) the maxima exchange
   float* outp = t.out + (size_t)b * t.ld_out + t.c0;
-  const int32_t pos = a.positions[b];    // written by the host before the launch
+  const int32_t pos = a.positions[b] + (int32_t)a.step;    // written by the host before the launch
   const bool bad_pos = pos < 0 || (uint32_t)pos >= a.g->max_seq;
   const uint32_t len = bad_pos ? 0u : (uint32_t)pos + 1;
   const uint32_t t0 = (uint32_t)((uint64_t)c * len / C), t1 = (uint32_t)((uint64_t)(c + 1) * len / C);
@@ -1606,7 +1618,7 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
   float* wpart = qs + grp * d;           // [NW][grp][d + 2]: partial output, max, sum per wavefront
   uint32_t* flag = (uint32_t*)(wpart + NW * grp * (d + 2));
   float* outp = t.out + (size_t)b * t.ld_out + t.c0;
-  const int32_t pos = a.positions[b];    // written by the host before the launch
+  const int32_t pos = a.positions[b] + (int32_t)a.step;    // written by the host before the launch
   const bool bad_pos = pos < 0 || (uint32_t)pos >= a.g->max_seq;
   const uint32_t len = bad_pos ? 0u : (uint32_t)pos + 1;
   const uint32_t t0 = (uint32_t)((uint64_t)c * len / C), t1 = (uint32_t)((uint64_t)(c + 1) * len / C);
@@ -1880,6 +1892,46 @@ __device__ __forceinline__ void body_swiglu(const TaskDesc& t) {
 
 // Runs one task.  wait_ev >= 0: the task must first wait for that event (persistent kernel);
 // linear and attention tasks do so after requesting their first weight / cache block.
+// Greedy sampling (one task per sequence): the index of the largest logit, lowest index on ties;
+// the token goes to token_ids[b] for the next step's embedding task (and to tokens_out); the
+// last step of a launch also advances positions[b].  Optionally keeps a copy of the logits.
+__device__ __forceinline__ void body_argmax(const TaskDesc& t, const StepArgs& a, float* lds) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t V = t.K, B = a.g->batch;
+  float* vmax = lds;                          // [8]
+  uint32_t* imax = (uint32_t*)(lds + 8);      // [8]
+  for (uint32_t b = t.b0; b < t.b1; ++b) {
+    const float* row = a.logits + (size_t)b * V;
+    float* const logits_all = a.g->logits_all;
+    int32_t* const tokens_out = a.g->tokens_out;
+    float* copy = logits_all ? logits_all + ((size_t)a.step * B + b) * V : nullptr;
+    float best = -INFINITY;
+    uint32_t best_i = 0xFFFFFFFFu;
+    for (uint32_t i = threadIdx.x; i < V; i += kThreads) {   // ascending per thread: keeps the first maximum
+      const float v = ld_act(row + i);
+      if (copy) as_global(copy)[i] = v;
+      if (v > best || best_i == 0xFFFFFFFFu) { best = v; best_i = i; }
+    }
+    const float wbest = wave_max(best);
+    const uint32_t wi = wave_min_u32(best == wbest ? best_i : 0xFFFFFFFFu);
+    if (lane == 0) { vmax[wave] = wbest; imax[wave] = wi; }
+    lds_barrier();
+    if (threadIdx.x == 0) {
+      float m = vmax[0];
+      uint32_t mi = imax[0];
+      for (uint32_t w = 1; w < kThreads / 64; ++w)
+        if (vmax[w] > m || (vmax[w] == m && imax[w] < mi)) { m = vmax[w]; mi = imax[w]; }
+      if (mi >= V) mi = 0;   // logits that are not numbers: keep the token in range
+      st_act_u32((uint32_t*)const_cast<int32_t*>(a.token_ids) + b, mi);
+      if (tokens_out) st_act_u32((uint32_t*)tokens_out + (size_t)a.step * B + b, mi);
+      if ((uint32_t)a.step + 1u == a.n_steps)
+        st_act_u32((uint32_t*)const_cast<int32_t*>(a.positions) + b, (uint32_t)(a.positions[b] + (int32_t)a.n_steps));
+    }
+    lds_barrier();
+  }
+}
+
 // D, GRP, NB pin head_dim, query heads per KV head and the batch class at compile time (0 = decide
 // at run time): a kernel that carries a single attention and a single linear variant keeps its
 // register allocation free of spills, the fully generic kernel does not.
@@ -1928,6 +1980,7 @@ __device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, f
     case TK_ATTN_MERGE: body_attn_merge(t, a); break;
     case TK_ADD: body_add(t); break;
     case TK_SWIGLU: body_swiglu(t); break;
+    case TK_ARGMAX: body_argmax(t, a, lds); break;
     default: break;   // TK_DUMMY: no computation (normalization, Section 4.1)
   }
   return true;
@@ -2292,6 +2345,51 @@ __device__ __forceinline__ uint32_t pick_task(const StepArgs& a, uint32_t* ctrl,
   return pick;
 }
 
+// Every task ahead-of-time: the worker walks its pre-enqueued list, each task waits for its own
+// event.  after_first_step: a task without producers (an embedding task) first waits for the
+// previous step's terminal event, i.e. for that step's sampling tasks.  Returns false on abort.
+template <int D, int GRP, int NB, bool MOE>
+__device__ __forceinline__ bool aot_pass(const StepArgs& a, uint32_t q0, uint32_t q1, float* lds, uint32_t* s_flag,
+                                         bool after_first_step) {
+  for (uint32_t qi = q0; qi < q1; ++qi) {
+    const uint32_t ti = ld_u32c(a.g->aot + qi);
+    const TaskDesc t = ld_task(a, ti);
+    if (after_first_step && t.dep_event == (int32_t)a.g->start_event) {
+      StepArgs prev = a;
+      prev.epoch = a.epoch - 1u;
+      if (!__builtin_amdgcn_readfirstlane((int)wait_event(prev, (int32_t)a.g->terminal_event, s_flag))) return false;
+    }
+    if (t.kind == TK_LINEAR) {
+      const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
+      trace_mark(a, t, 0);
+      if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
+      if (!run_linear<NB, true>(t, a, lds, wait_ev, s_flag)) return false;
+    } else {
+      // the callee's result comes back in a vector register: make it scalar again, or the whole
+      // task loop (and every descriptor load in it) turns into per-lane code
+      if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(a, ti, false))) return false;
+    }
+  }
+  return true;
+}
+
+// Multi-token launch (graphs with the sampling operator, no schedulers): the task list is walked
+// n_steps times, the epoch -- hence every counter target -- growing by one each time.  A kernel of
+// its own: with the step loop in mpk_mega_kernel the single-step launch measured 2 to 4 % slower.
+template <int D, int GRP, int NB, bool MOE>
+__global__ void __launch_bounds__(kThreads) mpk_loop_kernel(StepArgs a) {
+  extern __shared__ __align__(16) float dyn_lds[];
+  float* lds = dyn_lds + kLdsCtrlFloats;
+  uint32_t* s_flag = (uint32_t*)dyn_lds;
+  const uint32_t w = blockIdx.x;
+  const uint32_t q0 = ld_u32c(a.g->aot_off + w), q1 = ld_u32c(a.g->aot_off + w + 1);
+  const uint32_t n_steps = a.n_steps;
+  for (uint32_t step = 0; step < n_steps; ++step, ++a.epoch) {
+    a.step = (uint16_t)step;
+    if (!aot_pass<D, GRP, NB, MOE>(a, q0, q1, lds, s_flag, step > 0)) return;
+  }
+}
+
 template <int D, int GRP, int NB, bool MOE>
 __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
   extern __shared__ __align__(16) float dyn_lds[];
@@ -2307,21 +2405,7 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
   }
   const uint32_t q0 = ld_u32c(a.g->aot_off + w), q1 = ld_u32c(a.g->aot_off + w + 1);
   if (a.n_sched == 0) {
-    // every task ahead-of-time: walk the pre-enqueued list, each task waits for its own event
-    for (uint32_t qi = q0; qi < q1; ++qi) {
-      const uint32_t ti = ld_u32c(a.g->aot + qi);
-      const TaskDesc t = ld_task(a, ti);
-      if (t.kind == TK_LINEAR) {
-        const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
-        trace_mark(a, t, 0);
-        if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
-        if (!run_linear<NB, true>(t, a, lds, wait_ev, s_flag)) break;
-      } else {
-        // the callee's result comes back in a vector register: make it scalar again, or the whole
-        // task loop (and every descriptor load in it) turns into per-lane code
-        if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(a, ti, false))) break;
-      }
-    }
+    aot_pass<D, GRP, NB, MOE>(a, q0, q1, lds, s_flag, false);
     return;
   }
   // hybrid launch
@@ -2372,8 +2456,9 @@ struct KernelVariant {
   bool moe;
   void (*mega)(StepArgs);
   void (*op)(StepArgs, uint32_t);
+  void (*loop)(StepArgs);
 };
-#define MPK_VARIANT(D, G, N, M) {D, G, N, M, mpk_mega_kernel<D, G, N, M>, mpk_op_kernel<D, G, N, M>}
+#define MPK_VARIANT(D, G, N, M) {D, G, N, M, mpk_mega_kernel<D, G, N, M>, mpk_op_kernel<D, G, N, M>, mpk_loop_kernel<D, G, N, M>}
 static const KernelVariant kVariants[] = {
     MPK_VARIANT(64, 2, 1, false), MPK_VARIANT(128, 4, 1, false), MPK_VARIANT(128, 8, 1, false),
     MPK_VARIANT(128, 4, 8, false), MPK_VARIANT(128, 8, 8, true),
@@ -2423,6 +2508,7 @@ struct mpk_graph {
   std::vector<uint32_t> op_first, op_count;   // per operator: range in op_list
   uint32_t epoch = 0;
   uint64_t timeout_ticks = 0;
+  void* launch_out[2] = {nullptr, nullptr};   // host copy of GraphConst::tokens_out / logits_all (source of the async copy)
 };
 
 #define HIP_TRY(expr)                                                              \
@@ -2513,6 +2599,7 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
   g->kv = pick_variant(cfg->head_dim, cfg->n_q_heads / cfg->n_kv_heads, cfg->batch, cfg->n_experts != 0);
   hipError_t e = hipFuncSetAttribute((const void*)g->kv->mega, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h.lds_bytes);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)g->kv->op, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h.lds_bytes);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)g->kv->loop, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h.lds_bytes);
   if (e != hipSuccess) { set_error("cannot reserve %u bytes of LDS: %s", h.lds_bytes, hipGetErrorString(e)); return fail(MPK_ERR_RESIDENCY); }
   int per_cu = 0;
   e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)g->kv->mega, kThreads, h.lds_bytes);
@@ -2640,10 +2727,8 @@ extern "C" mpk_status mpk_compile_dag(uint32_t n_tasks, const uint32_t* pairs, s
   return MPK_OK;
 }
 
-extern "C" mpk_status mpk_decode_step(mpk_graph* g, const int32_t* token_ids,
-                                      const int32_t* positions, float* logits_out, void* stream) {
-  if (!g || !token_ids || !positions || !logits_out) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
-  if (g->host_only) { set_error("graph was compiled host_only"); return MPK_ERR_INVALID_ARG; }
+static mpk_status launch_steps(mpk_graph* g, uint32_t n_steps, const int32_t* token_ids, const int32_t* positions,
+                               int32_t* tokens_out, float* logits_out, float* logits_all, void* stream) {
   HostGraph& h = g->h;
   StepArgs a{};
   a.g = (const MPK_CONST GraphConst*)g->d_const;
@@ -2651,20 +2736,53 @@ extern "C" mpk_status mpk_decode_step(mpk_graph* g, const int32_t* token_ids,
   a.n_sched = g->n_sched; a.trace = g->d_trace;
   a.token_ids = token_ids; a.positions = positions; a.logits = logits_out;
   hipStream_t s = (hipStream_t)stream;
-  a.epoch = ++g->epoch;
+  if (h.opt.greedy_loop) {   // output pointers of this launch -> graph record, ordered on the stream
+    g->launch_out[0] = tokens_out; g->launch_out[1] = logits_all;
+    HIP_TRY(hipMemcpyAsync((char*)g->d_const + offsetof(GraphConst, tokens_out), g->launch_out, sizeof(g->launch_out),
+                           hipMemcpyHostToDevice, s));
+  }
   if (h.opt.launch_mode == MPK_LAUNCH_MEGA) {
-    hipLaunchKernelGGL(g->kv->mega, dim3(h.opt.n_workers + (g->n_sched ? h.opt.n_sched_wgs : 0u)), dim3(kThreads),
-                       h.lds_bytes, s, a);
+    a.epoch = g->epoch + 1;
+    a.step = 0; a.n_steps = (uint16_t)n_steps;
+    g->epoch += n_steps;
+    if (n_steps > 1)   // (callers have checked: no scheduler workgroups)
+      hipLaunchKernelGGL(g->kv->loop, dim3(h.opt.n_workers), dim3(kThreads), h.lds_bytes, s, a);
+    else
+      hipLaunchKernelGGL(g->kv->mega, dim3(h.opt.n_workers + (g->n_sched ? h.opt.n_sched_wgs : 0u)), dim3(kThreads),
+                         h.lds_bytes, s, a);
     HIP_TRY(hipGetLastError());
   } else {
-    for (size_t oi = 0; oi < h.ops.size(); ++oi) {
-      if (!g->op_count[oi]) continue;
-      hipLaunchKernelGGL(g->kv->op, dim3(g->op_count[oi]), dim3(kThreads), h.lds_bytes, s, a,
-                         g->op_first[oi]);
+    a.n_steps = (uint16_t)n_steps;
+    for (uint32_t step = 0; step < n_steps; ++step) {
+      a.epoch = ++g->epoch;
+      a.step = (uint16_t)step;
+      for (size_t oi = 0; oi < h.ops.size(); ++oi) {
+        if (!g->op_count[oi]) continue;
+        hipLaunchKernelGGL(g->kv->op, dim3(g->op_count[oi]), dim3(kThreads), h.lds_bytes, s, a,
+                           g->op_first[oi]);
+      }
     }
     HIP_TRY(hipGetLastError());
   }
   return MPK_OK;
+}
+
+extern "C" mpk_status mpk_decode_step(mpk_graph* g, const int32_t* token_ids,
+                                      const int32_t* positions, float* logits_out, void* stream) {
+  if (!g || !token_ids || !positions || !logits_out) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
+  if (g->host_only) { set_error("graph was compiled host_only"); return MPK_ERR_INVALID_ARG; }
+  if (g->h.opt.greedy_loop) { set_error("graph was compiled with greedy_loop: it samples and advances tokens and positions itself, run it with mpk_decode_steps"); return MPK_ERR_INVALID_ARG; }
+  return launch_steps(g, 1, token_ids, positions, nullptr, logits_out, nullptr, stream);
+}
+
+extern "C" mpk_status mpk_decode_steps(mpk_graph* g, uint32_t n_steps, int32_t* token_ids, int32_t* positions,
+                                       int32_t* tokens_out, float* logits_out, float* logits_all, void* stream) {
+  if (!g || !token_ids || !positions || !logits_out) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
+  if (g->host_only) { set_error("graph was compiled host_only"); return MPK_ERR_INVALID_ARG; }
+  if (!g->h.opt.greedy_loop) { set_error("mpk_decode_steps needs a graph compiled with greedy_loop = 1"); return MPK_ERR_INVALID_ARG; }
+  if (n_steps == 0 || n_steps > g->h.cfg.max_seq || n_steps > 65535u) { set_error("n_steps %u out of range (1..min(max_seq, 65535))", n_steps); return MPK_ERR_INVALID_ARG; }
+  if (g->n_sched && n_steps > 1) { set_error("several steps per launch are only supported without scheduler workgroups"); return MPK_ERR_UNSUPPORTED; }
+  return launch_steps(g, n_steps, token_ids, positions, tokens_out, logits_out, logits_all, stream);
 }
 
 extern "C" mpk_status mpk_graph_status(mpk_graph* g) {

@@ -77,7 +77,8 @@ def down_parts_of(ex, shape):
 
 
 def oracle_ops_and_degrees(shape, ex, fusion, attn_chunks):
-    ops = TG.build_ops(shape, fusion, attn_chunks, moe_tasks_of(ex), down_parts_of(ex, shape))
+    greedy = any(eo["kind"] == TG.K_ARGMAX for eo in ex.ops)
+    ops = TG.build_ops(shape, fusion, attn_chunks, moe_tasks_of(ex), down_parts_of(ex, shape), greedy)
     assert len(ops) == len(ex.ops), (len(ops), len(ex.ops))
     for o, eo in zip(ops, ex.ops):
         assert o.kind == eo["kind"] and o.layer == eo["layer"], (o.name, o.kind, eo["kind"])

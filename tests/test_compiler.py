@@ -48,6 +48,9 @@ CASES = [
     # batch > 4 with a long down-projection input: decomposed along the input as well
     ("C3", dict(n_layers=2), dict(fusion=31)),
     ("C1", dict(batch=8, ffn=8192), dict(fusion=31, n_workers=32)),
+    # greedy sampling as an operator of the graph (multi-token launch)
+    ("C1", dict(batch=3), dict(fusion=31, n_workers=24, greedy_loop=1)),
+    ("C1", {}, dict(fusion=0, greedy_loop=1)),
 ]
 
 

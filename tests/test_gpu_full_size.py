@@ -139,3 +139,35 @@ def test_c4_moe_30b_a3b_shaped_batch16_8_greedy_steps_mega_kernel():
     """Mixture of experts at the benchmark's shapes: 128 experts, top-8, batch 16, 60 GB of
     weights generated on the device; routing decisions of every layer and step included."""
     _check_against_fixture("C4", BENCH_OPTS)
+
+
+def test_c2_full_size_32_tokens_from_one_launch():
+    """The sampling operator inside the graph: all 32 greedy steps of the fixture from ONE launch
+    of the persistent kernel (no host round trip between tokens)."""
+    gold = _load("C2")
+    s = G.CONFIGS["C2"]
+    gpu = GpuDecoder(s, gold["seed"], greedy_loop=1, **BENCH_OPTS)
+    dev = gpu.model.device
+    steps = gold["steps"]
+    tok = torch.as_tensor(np.array(gold["start_tokens"], np.int32), device=dev)
+    pos = torch.as_tensor(np.array(gold["start_positions"], np.int32), device=dev)
+    toks = torch.full((steps, s.batch), -1, dtype=torch.int32, device=dev)
+    gpu.graph.decode_steps(steps, tok.data_ptr(), pos.data_ptr(), toks.data_ptr(), gpu.logits.data_ptr(), 0,
+                           torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    gpu.graph.status()
+    got = toks.cpu().numpy()
+    want = np.array(gold["tokens"])
+    same = (got == want).all(1)
+    if not same.all():
+        # only a near-tie of the oracle's two best logits may resolve the other way; everything
+        # after it is a different (legitimate) trajectory
+        i = int(np.argmin(same))
+        (j0, v0), (j1, v1) = gold["top8"][i][0][0], gold["top8"][i][0][1]
+        assert got[i, 0] == j1 and (v0 - v1) < 2e-3 * abs(v0), f"step {i}"
+    else:
+        lg = gpu.logits.cpu().numpy()
+        for j, v in gold["top8"][steps - 1][0]:
+            assert abs(lg[0, j] - v) <= TOL * max(abs(v), 1e-3 * abs(gold["top8"][steps - 1][0][0][1]))
+        assert pos.cpu().numpy().tolist() == [p + steps for p in gold["start_positions"]]
+    gpu.close()

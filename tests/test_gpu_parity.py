@@ -321,3 +321,52 @@ def test_moe_routing_ties_take_the_lower_expert_index(batch):
     assert set(map(tuple, ex[1].tolist())) <= {(0, 1), (4, 5)}
     assert rel_err(got, want) < TOL
     gpu.close()
+
+
+# ------------------------------------------------------------------ several tokens per launch
+@pytest.mark.parametrize("variant,opts,n_steps", [
+    (dict(), dict(fusion=31, transitive_reduction=1), 32),
+    (dict(), dict(fusion=0), 8),
+    (dict(batch=3, n_layers=2), dict(fusion=31, transitive_reduction=1, n_workers=37), 12),
+    (dict(batch=8, n_layers=2), dict(fusion=31, transitive_reduction=1), 6),
+    (dict(batch=2), dict(fusion=31, transitive_reduction=1, launch_mode=1), 5),
+    (dict(batch=4, ffn=0, n_experts=16, top_k=4, expert_ffn=96), dict(fusion=31, transitive_reduction=1), 6),
+])
+def test_greedy_loop_decodes_several_tokens_in_one_launch(variant, opts, n_steps):
+    """Graph with the sampling operator: n_steps tokens from ONE launch of the persistent kernel
+    (the epoch advances inside the kernel) must be the oracle's greedy tokens, with every step's
+    logits within tolerance; tokens and positions come back advanced; a second launch continues."""
+    s = G.small_variant("C1", max_seq=192, **variant)
+    rng = np.random.default_rng(11)
+    tok0 = rng.integers(0, s.vocab, s.batch)
+    pos0 = rng.integers(20, 100, s.batch)
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 4), "f32")
+    want_t, want_l = ref.greedy(tok0, pos0, 2 * n_steps)
+    gpu = GpuDecoder(s, 4, greedy_loop=1, **opts)
+    dev = gpu.model.device
+    tok = torch.as_tensor(tok0.astype(np.int32), device=dev)
+    pos = torch.as_tensor(pos0.astype(np.int32), device=dev)
+    toks = torch.full((n_steps, s.batch), -1, dtype=torch.int32, device=dev)
+    all_l = torch.full((n_steps, s.batch, s.vocab), float("nan"), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    for launch in range(2):
+        gpu.graph.decode_steps(n_steps, tok.data_ptr(), pos.data_ptr(), toks.data_ptr(),
+                               gpu.logits.data_ptr(), all_l.data_ptr(), stream)
+        torch.cuda.synchronize()
+        gpu.graph.status()
+        lo = launch * n_steps
+        got_l = all_l.cpu().numpy()
+        for i in range(n_steps):
+            if lo + i == 0:
+                assert rel_err(got_l[i], want_l[0]) < TOL
+            # later steps read K/V rows each side appended itself (a bf16 rounding boundary may
+            # fall either way): bound relative to the largest logit
+            assert np.abs(got_l[i] - want_l[lo + i]).max() / np.abs(want_l[lo + i]).max() < 2e-3, (launch, i)
+        assert np.array_equal(toks.cpu().numpy(), want_t[lo:lo + n_steps])
+        assert np.array_equal(tok.cpu().numpy(), want_t[lo + n_steps - 1])
+        assert np.array_equal(pos.cpu().numpy(), pos0 + lo + n_steps)
+        assert np.array_equal(gpu.logits.cpu().numpy(), got_l[-1])
+    # the single-step entry point refuses such a graph (it would not advance tokens itself)
+    with pytest.raises(M.MpkError):
+        gpu.graph.decode_step(tok.data_ptr(), pos.data_ptr(), gpu.logits.data_ptr(), stream)
+    gpu.close()
