@@ -83,21 +83,22 @@ struct StepArgs {
   const EventDesc* events;
   uint32_t* counters;
   uint32_t* hier;
-  uint64_t* trace;
   uint32_t n_sched;
+  uint32_t epoch;
   const int32_t* token_ids;
   const int32_t* positions;
   float* logits;
-  uint32_t epoch;
   // multi-token launch (greedy_loop graphs): the kernel runs n_steps decode steps; `step` counts
   // them and `epoch` grows with it.  positions[] stays as the host wrote it until the last step
-  // (tasks run ahead of the sampling, so they take positions[b] + step).  16 bits each, in what
-  // was padding: the struct is passed by value to every non-inlined task function, and a larger
-  // one measurably slows the single-step launch; the output pointers of such a launch are in
-  // the graph record for the same reason.
+  // (tasks run ahead of the sampling, so they take positions[b] + step).  16 bits each: the
+  // struct is passed by value to every non-inlined task function and its fields sit in scalar
+  // registers throughout the kernel; 16 bytes more of it slowed the single-step launch by 1 to 4 %.
+  // For the same reason the output pointers of a multi-token launch and the trace buffer are in
+  // the graph record instead.
   uint16_t step, n_steps;
+  uint32_t flags;   // kTraceBit
 };
-static_assert(sizeof(StepArgs) == 88, "StepArgs grew: check the single-step launch time");
+static_assert(sizeof(StepArgs) == 80, "StepArgs grew: check the single-step launch time");
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -131,8 +132,9 @@ __device__ __forceinline__ TaskDesc ld_task(const StepArgs& a, uint32_t i) { ret
 __device__ __forceinline__ uint32_t ld_u32c(const uint32_t* p) { return *(const MPK_CONST uint32_t*)p; }
 
 constexpr int kTraceSlots = 12;
+constexpr uint32_t kTraceBit = 1u;   // StepArgs::flags: per-task timestamps are recorded (buffer: GraphConst::trace)
 __device__ __forceinline__ void trace_mark(const StepArgs& a, const TaskDesc& t, int slot) {
-  if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)t.pad * kTraceSlots + slot] = wall_clock64();
+  if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + slot] = wall_clock64();
 }
 
 enum DevErr : uint32_t { DE_NONE = 0, DE_TIMEOUT = 1, DE_BAD_POSITION = 2, DE_BAD_TOKEN = 3, DE_BAD_META = 4 };
@@ -2163,7 +2165,7 @@ __device__ __noinline__ bool run_moe_task(StepArgs a, uint32_t task_index, bool 
   if (MEGA) {
     const int32_t wait_ev = (!skip_wait && t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
     trace_mark(a, t, 0);
-    if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)task_index * kTraceSlots + 5] = blockIdx.x;
+    if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)task_index * kTraceSlots + 5] = blockIdx.x;
     if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
     trace_mark(a, t, 1);
   }
@@ -2200,7 +2202,7 @@ __device__ __noinline__ bool run_other_task(StepArgs a, uint32_t task_index, boo
   if (MEGA) {
     wait_ev = (!skip_wait && t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
     trace_mark(a, t, 0);
-    if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)task_index * kTraceSlots + 5] = blockIdx.x;
+    if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)task_index * kTraceSlots + 5] = blockIdx.x;
   }
   if (!run_task<D, GRP, NB>(t, a, lds, wait_ev, s_flag)) return false;
   if (MEGA) {
@@ -2362,7 +2364,7 @@ __device__ __forceinline__ bool aot_pass(const StepArgs& a, uint32_t q0, uint32_
     if (t.kind == TK_LINEAR) {
       const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
       trace_mark(a, t, 0);
-      if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
+      if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
       if (!run_linear<NB, true>(t, a, lds, wait_ev, s_flag)) return false;
     } else {
       // the callee's result comes back in a vector register: make it scalar again, or the whole
@@ -2417,7 +2419,7 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
     const TaskDesc t = ld_task(a, ti);
     if (t.kind == TK_LINEAR) {
       trace_mark(a, t, 0);
-      if (a.trace && threadIdx.x == 0) as_global(a.trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
+      if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
       const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
       uint32_t r;
       // started before its event is activated; a just-in-time task that arrives first pre-empts it
@@ -2733,7 +2735,7 @@ static mpk_status launch_steps(mpk_graph* g, uint32_t n_steps, const int32_t* to
   StepArgs a{};
   a.g = (const MPK_CONST GraphConst*)g->d_const;
   a.tasks = g->d_tasks; a.events = g->d_events; a.counters = g->d_counters; a.hier = g->d_hier;
-  a.n_sched = g->n_sched; a.trace = g->d_trace;
+  a.n_sched = g->n_sched; a.flags = g->d_trace ? kTraceBit : 0u;
   a.token_ids = token_ids; a.positions = positions; a.logits = logits_out;
   hipStream_t s = (hipStream_t)stream;
   if (h.opt.greedy_loop) {   // output pointers of this launch -> graph record, ordered on the stream
