@@ -102,6 +102,34 @@ static_assert(sizeof(StepArgs) == 80, "StepArgs grew: check the single-step laun
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// A struct passed by value to a real (non-inlined) function travels through private memory and
+// arrives in vector registers: to the compiler every field is then a per-lane value, so the
+// descriptor reads behind it become vector loads and every branch on them an exec-mask branch.
+// All lanes hold the same values: say so, field by field.
+__device__ __forceinline__ uint32_t uniform_u32(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+template <typename P>
+__device__ __forceinline__ P uniform_ptr(P p) {
+  const uint64_t v = (uint64_t)p;
+  return (P)(((uint64_t)uniform_u32((uint32_t)(v >> 32)) << 32) | uniform_u32((uint32_t)v));
+}
+__device__ __forceinline__ StepArgs uniform_args(const StepArgs& a) {
+  StepArgs u;
+  u.g = uniform_ptr(a.g);
+  u.tasks = uniform_ptr(a.tasks);
+  u.events = uniform_ptr(a.events);
+  u.counters = uniform_ptr(a.counters);
+  u.hier = uniform_ptr(a.hier);
+  u.n_sched = uniform_u32(a.n_sched);
+  u.epoch = uniform_u32(a.epoch);
+  u.token_ids = uniform_ptr(a.token_ids);
+  u.positions = uniform_ptr(a.positions);
+  u.logits = uniform_ptr(a.logits);
+  u.step = (uint16_t)uniform_u32(a.step);
+  u.n_steps = (uint16_t)uniform_u32(a.n_steps);
+  u.flags = uniform_u32(a.flags);
+  return u;
+}
+
 // Pointers that arrive through descriptors in memory are "generic" to the compiler, which then
 // emits FLAT memory instructions: those may complete out of order, so every use has to wait for
 // ALL outstanding memory operations (vmcnt(0) lgkmcnt(0)) and nothing pipelines.  Everything the
@@ -2157,7 +2185,10 @@ constexpr uint32_t kLdsCtrlFloats = 16;
 // registers, and a function saves every callee-saved register it uses anywhere on each call, so
 // sharing run_other_task would tax every attention task with those saves.
 template <bool MEGA>
-__device__ __noinline__ bool run_moe_task(StepArgs a, uint32_t task_index, bool skip_wait) {
+__device__ __noinline__ bool run_moe_task(StepArgs a_in, uint32_t task_index, bool skip_wait) {
+  const StepArgs a = uniform_args(a_in);
+  task_index = uniform_u32(task_index);
+  skip_wait = uniform_u32(skip_wait) != 0;
   extern __shared__ __align__(16) float dyn_lds[];
   float* lds = dyn_lds + kLdsCtrlFloats;
   uint32_t* s_flag = (uint32_t*)dyn_lds;
@@ -2190,14 +2221,17 @@ __device__ __forceinline__ bool is_moe_kind(uint16_t kind) { return kind >= TK_M
 // force spills of registers that have loads in flight.
 // Returns false when the step is being aborted.
 template <int D, int GRP, int NB, bool MEGA, bool MOE>
-__device__ __noinline__ bool run_other_task(StepArgs a, uint32_t task_index, bool skip_wait) {
+__device__ __noinline__ bool run_other_task(StepArgs a_in, uint32_t task_index, bool skip_wait) {
+  const StepArgs a = uniform_args(a_in);
+  task_index = uniform_u32(task_index);
+  skip_wait = uniform_u32(skip_wait) != 0;
   extern __shared__ __align__(16) float dyn_lds[];
   float* lds = dyn_lds + kLdsCtrlFloats;
   uint32_t* s_flag = (uint32_t*)dyn_lds;
   const TaskDesc t = ld_task(a, task_index);
   // kernels for dense models are built without this call: with it the function is no leaf any
   // more and every attention task pays for that (measured: 0.1 ms per step on the 8B shape)
-  if (MOE && is_moe_kind(t.kind)) return run_moe_task<MEGA>(a, task_index, skip_wait);
+  if (MOE && is_moe_kind(t.kind)) return run_moe_task<MEGA>(a_in, task_index, skip_wait);
   int32_t wait_ev = -1;
   if (MEGA) {
     wait_ev = (!skip_wait && t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
