@@ -39,13 +39,13 @@ class _LayerCfg(ctypes.Structure):
                 ("d", ctypes.c_int), ("ffn", ctypes.c_int), ("max_seq", ctypes.c_int),
                 ("eps", ctypes.c_float), ("theta", ctypes.c_double),
                 ("n_experts", ctypes.c_int), ("top_k", ctypes.c_int),
-                ("expert_ffn", ctypes.c_int)]
+                ("expert_ffn", ctypes.c_int), ("qk_norm", ctypes.c_int)]
 
 
 class _LayerW(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in
                 ("attn_norm", "wqkv", "wo", "mlp_norm", "wgu", "wd", "router", "exp_wgu",
-                 "exp_wd")]
+                 "exp_wd", "q_norm", "k_norm")]
 
 
 _libs = {}
@@ -199,7 +199,8 @@ class DecoderOracle:
         work = np.empty(6 * s.hidden + 2 * qkv_rows + 4 * ffn_like + s.max_seq
                         + max(s.n_experts, 1) + 64, self.dt)
         cfg = _LayerCfg(s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.ffn, s.max_seq,
-                        s.rms_eps, s.rope_theta, s.n_experts, s.top_k, s.expert_ffn)
+                        s.rms_eps, s.rope_theta, s.n_experts, s.top_k, s.expert_ffn,
+                        int(getattr(s, "qk_norm", False)))
         xs = [self.ops.embed(self.p.embed_row(int(t)).reshape(1, -1), 0) for t in tokens]
         moe_sel = np.zeros((self.n_layers, B, max(s.top_k, 1)), np.int32)
         moe_logits = np.zeros((self.n_layers, B, max(s.n_experts, 1)), self.dt)
@@ -213,7 +214,7 @@ class DecoderOracle:
                 return None if a is None else np.ascontiguousarray(a).ctypes.data
             w = _LayerW(ptr(G.L_ATTN_NORM), ptr(G.L_WQKV), ptr(G.L_WO), ptr(G.L_MLP_NORM),
                         ptr(G.L_WGU), ptr(G.L_WD), ptr(G.L_ROUTER), ptr(G.L_EXP_WGU),
-                        ptr(G.L_EXP_WD))
+                        ptr(G.L_EXP_WD), ptr(G.L_QNORM), ptr(G.L_KNORM))
             K, V = self._kv(l)
             for b in range(B):
                 assert 0 <= positions[b] < s.max_seq

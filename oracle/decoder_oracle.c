@@ -185,7 +185,7 @@ void orc_router_topk(const real *logits, int E, int k, int *sel, real *w) {
 
 /* ------------------------------------------------------------------------------------------
  * One decoder layer for one sequence, composed only of the functions above, in the operator
- * order  attn_norm, qkv_proj, rope + kv append, attention, o_proj, residual, mlp_norm,
+ * order  attn_norm, qkv_proj, (per-head q/k RMSNorm,) rope + kv append, attention, o_proj, residual, mlp_norm,
  * gate_up_proj, swiglu, down_proj, residual  (or the MoE block in place of the dense MLP).
  * pos = number of rows already cached; the new K/V row is written at `pos` and attention reads
  * rows 0..pos of the ROUNDED cache.  kc/vc: this sequence's cache [n_kv][max_seq][d].
@@ -196,11 +196,13 @@ typedef struct {
   float eps;
   double theta;
   int n_experts, top_k, expert_ffn;
+  int qk_norm; /* 1: RMSNorm over head_dim of every q and k head (gains q_norm / k_norm) before RoPE */
 } orc_layer_cfg;
 
 typedef struct {
   const uint16_t *attn_norm, *wqkv, *wo, *mlp_norm, *wgu, *wd;
   const uint16_t *router, *exp_wgu, *exp_wd;
+  const uint16_t *q_norm, *k_norm;
 } orc_layer_w;
 
 void orc_layer(const orc_layer_cfg *c, const orc_layer_w *w, uint16_t *kc, uint16_t *vc, int pos,
@@ -220,6 +222,10 @@ void orc_layer(const orc_layer_cfg *c, const orc_layer_w *w, uint16_t *kc, uint1
   orc_rmsnorm(x, w->attn_norm, H, c->eps, xn);
   orc_linear(w->wqkv, qkv_rows, H, xn, qkv);
   real *q = qkv, *k = qkv + nq * d, *v = k + nkv * d;
+  if (c->qk_norm) { /* element-wise, so in place is fine */
+    for (int h = 0; h < nq; ++h) orc_rmsnorm(q + h * d, w->q_norm, d, c->eps, q + h * d);
+    for (int g = 0; g < nkv; ++g) orc_rmsnorm(k + g * d, w->k_norm, d, c->eps, k + g * d);
+  }
   for (int h = 0; h < nq; ++h) orc_rope(q + h * d, d, pos, c->theta);
   for (int g = 0; g < nkv; ++g) {
     orc_rope(k + g * d, d, pos, c->theta);

@@ -27,7 +27,8 @@ class DeviceModel:
         self.lm_head = new(G.TID_LM_HEAD, s.vocab, s.hidden, "w")
         names = {G.L_ATTN_NORM: "attn_norm", G.L_WQKV: "wqkv", G.L_WO: "wo",
                  G.L_MLP_NORM: "mlp_norm", G.L_WGU: "wgu", G.L_WD: "wd", G.L_ROUTER: "router",
-                 G.L_EXP_WGU: "expert_wgu", G.L_EXP_WD: "expert_wd"}
+                 G.L_EXP_WGU: "expert_wgu", G.L_EXP_WD: "expert_wd", G.L_QNORM: "q_norm",
+                 G.L_KNORM: "k_norm"}
         self.layers = []
         for l in range(s.n_layers):
             d = {}

@@ -43,6 +43,7 @@ class ModelShape:
     n_experts: int = 0
     top_k: int = 0
     expert_ffn: int = 0
+    qk_norm: bool = False    # per-head RMSNorm of q and k before RoPE (Qwen3)
     # workload
     kv_len_lo: int = 0       # prior cached positions per sequence: uniform integer in [lo, hi]
     kv_len_hi: int = 0
@@ -82,7 +83,7 @@ def small_variant(base: str, **kw) -> ModelShape:
 # ----------------------------------------------------------------------------- tensor ids
 TID_EMBED, TID_FINAL_NORM, TID_LM_HEAD, TID_TOKENS, TID_KVLEN = 1, 2, 3, 4, 5
 (L_ATTN_NORM, L_WQKV, L_WO, L_MLP_NORM, L_WGU, L_WD, L_ROUTER, L_EXP_WGU, L_EXP_WD,
- L_KCACHE, L_VCACHE) = range(11)
+ L_KCACHE, L_VCACHE, L_QNORM, L_KNORM) = range(13)
 
 
 def layer_tid(layer: int, which: int) -> int:
@@ -96,6 +97,8 @@ def layer_tensor_shapes(s: ModelShape):
            (L_WQKV, qkv_rows, s.hidden, "w"),
            (L_WO, s.hidden, s.n_q_heads * s.head_dim, "w"),
            (L_MLP_NORM, 1, s.hidden, "gain")]
+    if s.qk_norm:
+        out += [(L_QNORM, 1, s.head_dim, "gain"), (L_KNORM, 1, s.head_dim, "gain")]
     if s.n_experts == 0:
         out += [(L_WGU, 2 * s.ffn, s.hidden, "w"), (L_WD, s.hidden, s.ffn, "w")]
     else:

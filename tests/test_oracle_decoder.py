@@ -394,3 +394,141 @@ def test_whole_model_vs_transformers_llama():
     err = np.abs(lg - ref).max() / np.abs(ref).max()
     assert err < 5e-3, err
     assert lg.argmax() == ref.argmax()
+
+
+def _hf_state(prov, s, moe):
+    """State dict of the `transformers` Qwen3 / Qwen3-MoE classes from the provider's tensors."""
+    t = lambda a: torch.from_numpy(unbf(a))
+    nq, nkv, d = s.n_q_heads, s.n_kv_heads, s.head_dim
+    sd = {"model.embed_tokens.weight": t(prov.E), "model.norm.weight": t(prov.fn),
+          "lm_head.weight": t(prov.lm)}
+    for l, w in enumerate(prov.layers):
+        p = f"model.layers.{l}."
+        qkv = t(w[G.L_WQKV])
+        sd[p + "self_attn.q_proj.weight"] = qkv[:nq * d]
+        sd[p + "self_attn.k_proj.weight"] = qkv[nq * d:(nq + nkv) * d]
+        sd[p + "self_attn.v_proj.weight"] = qkv[(nq + nkv) * d:]
+        sd[p + "self_attn.o_proj.weight"] = t(w[G.L_WO])
+        sd[p + "self_attn.q_norm.weight"] = t(w[G.L_QNORM]).reshape(-1)
+        sd[p + "self_attn.k_norm.weight"] = t(w[G.L_KNORM]).reshape(-1)
+        sd[p + "input_layernorm.weight"] = t(w[G.L_ATTN_NORM]).reshape(-1)
+        sd[p + "post_attention_layernorm.weight"] = t(w[G.L_MLP_NORM]).reshape(-1)
+        if not moe:
+            gu = t(w[G.L_WGU])
+            sd[p + "mlp.gate_proj.weight"] = gu[:s.ffn]
+            sd[p + "mlp.up_proj.weight"] = gu[s.ffn:]
+            sd[p + "mlp.down_proj.weight"] = t(w[G.L_WD])
+    return sd
+
+
+def _hf_logits(m, cfg, prov, s, tok, pos):
+    from transformers.cache_utils import DynamicCache
+    T = int(pos[0])
+    t = lambda a: torch.from_numpy(unbf(a))
+    cache = DynamicCache(config=cfg)
+    for l in range(s.n_layers):
+        K, V = prov.kv[l]
+        cache.update(t(K[:, :, :T]), t(V[:, :, :T]), l)
+    with torch.no_grad():
+        out = m(input_ids=torch.tensor([[int(tok[0])]]), past_key_values=cache,
+                position_ids=torch.tensor([[T]]), use_cache=True)
+    return out.logits[0, -1].numpy()
+
+
+def test_qk_norm_whole_model_vs_transformers_qwen3():
+    """Library pin for the per-head q/k RMSNorm (before RoPE): the `transformers` Qwen3
+    architecture as a black box, same seeded tensors, fp32 on CPU, one token with a 128-row past."""
+    from transformers import Qwen3Config, Qwen3ForCausalLM
+    s = G.small_variant("C1", qk_norm=True)
+    prov = synth_provider_as_dict(s, 0)
+    cfg = Qwen3Config(vocab_size=s.vocab, hidden_size=s.hidden, intermediate_size=s.ffn,
+                      num_hidden_layers=s.n_layers, num_attention_heads=s.n_q_heads,
+                      num_key_value_heads=s.n_kv_heads, head_dim=s.head_dim, rms_norm_eps=s.rms_eps,
+                      rope_theta=s.rope_theta, max_position_embeddings=4096, attention_bias=False,
+                      tie_word_embeddings=False, use_sliding_window=False,
+                      attn_implementation="eager")
+    try:
+        cfg.rope_parameters = {"rope_type": "default", "rope_theta": s.rope_theta}
+    except Exception:
+        pass
+    m = Qwen3ForCausalLM(cfg).float().eval()
+    missing, unexpected = m.load_state_dict(_hf_state(prov, s, moe=False), strict=False)
+    assert not [k for k in missing if "rotary" not in k] and not unexpected
+    tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
+    ref = _hf_logits(m, cfg, prov, s, tok, pos)
+    lg = D.DecoderOracle(s, prov, "f32").step(tok, pos)[0]
+    err = np.abs(lg - ref).max() / np.abs(ref).max()
+    assert err < 5e-3, err          # the library keeps the new K/V row in fp32, the method rounds it
+    assert lg.argmax() == ref.argmax()
+    # and the norm really is in the path: without it the logits are different ones
+    plain = D.DecoderOracle(G.small_variant("C1"), prov, "f32").step(tok, pos)[0]
+    assert np.abs(plain - ref).max() / np.abs(ref).max() > 5e-2
+
+
+def test_qk_norm_is_invariant_to_the_scale_of_q_and_k():
+    """RMSNorm over head_dim removes the scale of a head: doubling the q and k rows of the QKV
+    matrix (exact in bf16) changes nothing but the eps term."""
+    s = G.small_variant("C1", qk_norm=True)
+    tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
+    a = D.DecoderOracle(s, synth_provider_as_dict(s), "f64").step(tok, pos)
+    prov = synth_provider_as_dict(s)
+    nqk = (s.n_q_heads + s.n_kv_heads) * s.head_dim
+    for w in prov.layers:
+        qkv = unbf(w[G.L_WQKV]).copy()
+        qkv[:nqk] *= 2.0
+        w[G.L_WQKV] = bf(qkv)
+    b = D.DecoderOracle(s, prov, "f64").step(tok, pos)
+    # the K rows already cached are not re-normalised, only this step's q and k: still the
+    # softmax sees the same scores for the new row and q.k_old scales only through q's norm -> equal
+    assert np.abs(a - b).max() / np.abs(a).max() < 1e-5
+
+
+def test_moe_whole_model_vs_transformers_qwen3_moe():
+    """Library pin for the mixture-of-experts reading (softmax over all experts, top-k,
+    renormalised weights, SwiGLU experts, no shared expert): the `transformers` Qwen3-MoE
+    architecture as a black box on the same seeded tensors."""
+    from transformers import Qwen3MoeConfig, Qwen3MoeForCausalLM
+    s = G.small_variant("C1", qk_norm=True, ffn=0, n_experts=8, top_k=2, expert_ffn=64)
+    prov = synth_provider_as_dict(s, 0)
+    cfg = Qwen3MoeConfig(vocab_size=s.vocab, hidden_size=s.hidden, intermediate_size=4 * s.hidden,
+                         moe_intermediate_size=s.expert_ffn, num_experts=s.n_experts,
+                         num_experts_per_tok=s.top_k, norm_topk_prob=True, decoder_sparse_step=1,
+                         mlp_only_layers=[], num_hidden_layers=s.n_layers,
+                         num_attention_heads=s.n_q_heads, num_key_value_heads=s.n_kv_heads,
+                         head_dim=s.head_dim, rms_norm_eps=s.rms_eps, rope_theta=s.rope_theta,
+                         max_position_embeddings=4096, attention_bias=False, tie_word_embeddings=False,
+                         use_sliding_window=False, output_router_logits=False,
+                         attn_implementation="eager")
+    try:
+        cfg.rope_parameters = {"rope_type": "default", "rope_theta": s.rope_theta}
+    except Exception:
+        pass
+    m = Qwen3MoeForCausalLM(cfg).float().eval()
+    sd = _hf_state(prov, s, moe=True)
+    t = lambda a: torch.from_numpy(unbf(a))
+    names = set(m.state_dict().keys())
+    E, F, H = s.n_experts, s.expert_ffn, s.hidden
+    for l, w in enumerate(prov.layers):
+        p = f"model.layers.{l}.mlp."
+        sd[p + "gate.weight"] = t(w[G.L_ROUTER])
+        gu = t(w[G.L_EXP_WGU]).reshape(E, 2 * F, H)
+        dn = t(w[G.L_EXP_WD]).reshape(E, H, F)
+        if p + "experts.gate_up_proj" in names:            # fused expert tensors
+            want = m.state_dict()[p + "experts.gate_up_proj"].shape
+            sd[p + "experts.gate_up_proj"] = gu if tuple(want) == (E, 2 * F, H) else gu.transpose(1, 2).contiguous()
+            wantd = m.state_dict()[p + "experts.down_proj"].shape
+            sd[p + "experts.down_proj"] = dn if tuple(wantd) == (E, H, F) else dn.transpose(1, 2).contiguous()
+        else:                                               # one module per expert
+            for e in range(E):
+                sd[p + f"experts.{e}.gate_proj.weight"] = gu[e, :F]
+                sd[p + f"experts.{e}.up_proj.weight"] = gu[e, F:]
+                sd[p + f"experts.{e}.down_proj.weight"] = dn[e]
+    missing, unexpected = m.load_state_dict(sd, strict=False)
+    assert not [k for k in missing if "rotary" not in k] and not unexpected, (missing[:4], unexpected[:4])
+    tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
+    ref = _hf_logits(m, cfg, prov, s, tok, pos)
+    o = D.DecoderOracle(s, prov, "f32")
+    lg = o.step(tok, pos)[0]
+    err = np.abs(lg - ref).max() / np.abs(ref).max()
+    assert err < 5e-3, err
+    assert lg.argmax() == ref.argmax()
