@@ -53,8 +53,12 @@ typedef struct mpk_model_config {
                        runtime dynamism": one tGraph per batch size)                              */
   uint32_t max_seq; /* KV-cache capacity per sequence, in positions                              */
   uint32_t n_experts, top_k, expert_ffn; /* 0 = dense MLP                                        */
-  uint32_t flags;                        /* reserved, must be 0                                  */
+  uint32_t flags;                        /* MPK_MODEL_* bits                                     */
 } mpk_model_config;
+
+/* mpk_model_config.flags */
+#define MPK_MODEL_QK_NORM 1u /* RMSNorm over head_dim of every q and k head, with gains q_norm /
+                                k_norm and rms_eps, before RoPE (the Qwen3 family)              */
 
 typedef struct mpk_layer_weights {
   const void *attn_norm; /* device bf16 [hidden]                                   */
@@ -66,6 +70,8 @@ typedef struct mpk_layer_weights {
   const void *router;    /* device bf16 [n_experts][hidden]       (MoE)            */
   const void *expert_wgu; /* device bf16 [n_experts][2 expert_ffn][hidden] (MoE)   */
   const void *expert_wd;  /* device bf16 [n_experts][hidden][expert_ffn]   (MoE)   */
+  const void *q_norm;    /* device bf16 [head_dim]   (MPK_MODEL_QK_NORM)            */
+  const void *k_norm;    /* device bf16 [head_dim]   (MPK_MODEL_QK_NORM)            */
 } mpk_layer_weights;
 
 typedef struct mpk_weight_ptrs {

@@ -35,7 +35,7 @@ class ModelConfig(C.Structure):
 
 class LayerWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("attn_norm", "wqkv", "wo", "mlp_norm", "wgu", "wd",
-                                          "router", "expert_wgu", "expert_wd")]
+                                          "router", "expert_wgu", "expert_wd", "q_norm", "k_norm")]
 
 
 class WeightPtrs(C.Structure):
@@ -137,7 +137,7 @@ def model_config(shape) -> ModelConfig:
     return ModelConfig(C.sizeof(ModelConfig), shape.n_layers, shape.hidden, shape.n_q_heads,
                        shape.n_kv_heads, shape.head_dim, shape.ffn, shape.vocab, shape.rms_eps,
                        shape.rope_theta, shape.batch, shape.max_seq, shape.n_experts, shape.top_k,
-                       shape.expert_ffn, 0)
+                       shape.expert_ffn, 1 if getattr(shape, "qk_norm", False) else 0)
 
 
 def compile_options(**kw) -> CompileOptions:

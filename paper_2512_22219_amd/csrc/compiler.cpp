@@ -462,13 +462,17 @@ static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
       int rk = b.new_tensor(B, QKV);
       HostOp& op = b.add(MPK_OP_ROPE, l, "rope", rk, d, qkv);
       op.f1 = c.rope_theta; op.p0 = l;
+      if (c.flags & MPK_MODEL_QK_NORM) { op.flags |= TF_QK_NORM; op.w = lw.q_norm; op.w2 = lw.k_norm; op.f0 = c.rms_eps; }
       qsrc = rk;
     }
     int part = b.new_tensor(B, nkv * C * grp * (d + 2));
     {
       HostOp& op = b.add(MPK_OP_ATTN_PARTIAL, l, "attn_partial", part, grp * (d + 2), qsrc);
       op.p0 = l; op.p1 = C; op.f1 = c.rope_theta;
-      if (f & MPK_FUSE_ROPE) op.flags |= TF_ROPE_FUSED;
+      if (f & MPK_FUSE_ROPE) {
+        op.flags |= TF_ROPE_FUSED;
+        if (c.flags & MPK_MODEL_QK_NORM) { op.flags |= TF_QK_NORM; op.w = lw.q_norm; op.w2 = lw.k_norm; op.f0 = c.rms_eps; }
+      }
     }
     int osrc = part, o_body = -1;
     uint32_t oK = nq * d;
@@ -983,7 +987,7 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
                            const mpk_kv_ptrs* kv, const mpk_compile_options& o) {
   if (c.struct_size != sizeof(mpk_model_config)) { set_error("mpk_model_config.struct_size is %u, expected %zu", c.struct_size, sizeof(mpk_model_config)); return MPK_ERR_INVALID_ARG; }
   if (!c.n_layers || !c.hidden || !c.n_q_heads || !c.n_kv_heads || !c.head_dim || !c.vocab || !c.batch || !c.max_seq) { set_error("a model dimension is zero"); return MPK_ERR_INVALID_ARG; }
-  if (c.flags) { set_error("mpk_model_config.flags must be 0"); return MPK_ERR_INVALID_ARG; }
+  if (c.flags & ~MPK_MODEL_QK_NORM) { set_error("unknown mpk_model_config.flags bits"); return MPK_ERR_INVALID_ARG; }
   const bool moe = c.n_experts != 0;
   if (moe) {
     if (!c.top_k || !c.expert_ffn || c.top_k > c.n_experts) { set_error("mixture-of-experts: top_k and expert_ffn must be non-zero and top_k <= n_experts"); return MPK_ERR_INVALID_ARG; }
@@ -1011,6 +1015,7 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
     if (bad(w->embed) || bad(w->final_norm) || bad(w->lm_head) || bad(kv->k) || bad(kv->v)) { set_error("a model-level pointer is NULL or not 16-byte aligned"); return MPK_ERR_INVALID_ARG; }
     for (uint32_t l = 0; l < c.n_layers; ++l) {
       const mpk_layer_weights& lw = w->layers[l];
+      if ((c.flags & MPK_MODEL_QK_NORM) && (bad(lw.q_norm) || bad(lw.k_norm))) { set_error("layer %u: q_norm / k_norm pointer is NULL or not 16-byte aligned", l); return MPK_ERR_INVALID_ARG; }
       if (bad(lw.attn_norm) || bad(lw.wqkv) || bad(lw.wo) || bad(lw.mlp_norm) ||
           (moe ? (bad(lw.router) || bad(lw.expert_wgu) || bad(lw.expert_wd)) : (bad(lw.wgu) || bad(lw.wd)))) { set_error("layer %u: a weight pointer is NULL or not 16-byte aligned", l); return MPK_ERR_INVALID_ARG; }
     }

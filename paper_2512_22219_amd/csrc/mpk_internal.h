@@ -40,6 +40,8 @@ enum TaskFlags : uint16_t {
   TF_ATTN_MERGE = 64, // attention: the last chunk task of a (sequence, KV head) to finish merges
                       // all chunk partials into the attention output (in2), counter index p2
   TF_JIT = 128,       // launched just-in-time: a scheduler hands it to a worker when its event fires
+  TF_QK_NORM = 512,   // rope / attention with fused rope: RMSNorm over head_dim of every q head (gain w)
+                      // and k head (gain w2), eps f0, before the rotation
   TF_SPLITK = 256,    // linear (batch > 4): the task owns rows x ONE of `parts` input ranges; it writes
                       // partial sums, and the task of a row block that arrives last (counter p2)
                       // adds the parts in order plus the residual into the real output (aux0).

@@ -1299,6 +1299,14 @@ __device__ __forceinline__ void rope_cs(const StepArgs& a, int32_t pos, uint32_t
   *s = (float)sd;
 }
 
+// Sum over an aligned group of N adjacent lanes (N a power of two <= 64); every lane gets it.
+template <int N>
+__device__ __forceinline__ float lane_group_sum(float v) {
+#pragma unroll
+  for (int off = N / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
 // T3: rotate q and k heads by the sequence position (half-split pairing), copy v, and append the
 // new k and v rows to the cache as bf16.  Angles are evaluated in double precision.
 __device__ __forceinline__ void body_rope(const TaskDesc& t, const StepArgs& a) {
@@ -1317,6 +1325,16 @@ __device__ __forceinline__ void body_rope(const TaskDesc& t, const StepArgs& a) 
     for (uint32_t idx = threadIdx.x; idx < (s1 - s0) * (half / 2); idx += kThreads) {
       uint32_t s = s0 + idx / (half / 2), i = 2 * (idx % (half / 2));
       float2 lo = ld_act2(src + s * d + i), hi = ld_act2(src + s * d + i + half);
+      if ((t.flags & TF_QK_NORM) && s < nq + nkv) {
+        // RMSNorm over the head first: its half/2 threads are one aligned group of lanes
+        float ss = lo.x * lo.x + lo.y * lo.y + hi.x * hi.x + hi.y * hi.y;
+        ss = (half / 2 == 32) ? lane_group_sum<32>(ss) : lane_group_sum<16>(ss);
+        const float inv = 1.0f / sqrtf(ss / (float)d + t.f0);
+        const uint16_t* gn = (const uint16_t*)(s < nq ? t.w : t.w2);
+        const uint32_t g0 = *as_global((const uint32_t*)(gn + i)), g1 = *as_global((const uint32_t*)(gn + i + half));
+        lo.x *= inv * bf16_lo(g0); lo.y *= inv * bf16_hi(g0);
+        hi.x *= inv * bf16_lo(g1); hi.y *= inv * bf16_hi(g1);
+      }
       float r[4];   // lo.x, lo.y, hi.x, hi.y after rotation
       if (s < nq + nkv) {
         float u0[2] = {lo.x, lo.y}, u1[2] = {hi.x, hi.y};
@@ -1418,9 +1436,16 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
     // the input is the raw QKV projection: rotate the group's query heads here; the task of the
     // last chunk also rotates this step's key, and appends key and value to the cache
     constexpr uint32_t half = d / 2;
+    const bool qk_norm = t.flags & TF_QK_NORM;
     for (uint32_t i = threadIdx.x; i < grp * half; i += kThreads) {
       uint32_t j = i / half, e = i % half;
       float u0 = ld_act(qsrc + j * d + e), u1 = ld_act(qsrc + j * d + e + half), cs, sn;
+      if (qk_norm) {   // RMSNorm over the head: its `half` threads are one aligned group of lanes
+        const float inv = 1.0f / sqrtf(lane_group_sum<(int)half>(u0 * u0 + u1 * u1) / (float)d + t.f0);
+        const uint16_t* gq = (const uint16_t*)t.w;
+        u0 *= inv * bf16_to_f32(as_global(gq)[e]);
+        u1 *= inv * bf16_to_f32(as_global(gq)[e + half]);
+      }
       rope_cs(a, pos, e, &cs, &sn);
       qs[j * d + e] = u0 * cs - u1 * sn;
       qs[j * d + e + half] = u1 * cs + u0 * sn;
@@ -1435,6 +1460,14 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
         if (i < half / 2) {   // two adjacent rotation pairs of the key
           uint32_t e = 2 * i;
           float2 lo = ld_act2(ksrc + e), hi = ld_act2(ksrc + e + half);
+          if (qk_norm) {   // the key's half/2 threads: one aligned group of lanes at the top of the workgroup
+            const float ss = lane_group_sum<(int)(half / 2)>(lo.x * lo.x + lo.y * lo.y + hi.x * hi.x + hi.y * hi.y);
+            const float inv = 1.0f / sqrtf(ss / (float)d + t.f0);
+            const uint16_t* gk = (const uint16_t*)t.w2;
+            const uint32_t g0 = *as_global((const uint32_t*)(gk + e)), g1 = *as_global((const uint32_t*)(gk + e + half));
+            lo.x *= inv * bf16_lo(g0); lo.y *= inv * bf16_hi(g0);
+            hi.x *= inv * bf16_lo(g1); hi.y *= inv * bf16_hi(g1);
+          }
           float c0, s0, c1, s1;
           rope_cs(a, pos, e, &c0, &s0);
           rope_cs(a, pos, e + 1, &c1, &s1);
@@ -1684,9 +1717,16 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
     // the input is the raw QKV projection: rotate the group's query heads here; the task of the
     // last chunk also rotates this step's key, and appends key and value to the cache
     constexpr uint32_t half = d / 2;
+    const bool qk_norm = t.flags & TF_QK_NORM;
     for (uint32_t i = threadIdx.x; i < grp * half; i += kThreads) {
       uint32_t j = i / half, e = i % half;
       float u0 = ld_act(qsrc + j * d + e), u1 = ld_act(qsrc + j * d + e + half), cs, sn;
+      if (qk_norm) {   // RMSNorm over the head: its `half` threads are one aligned group of lanes
+        const float inv = 1.0f / sqrtf(lane_group_sum<(int)half>(u0 * u0 + u1 * u1) / (float)d + t.f0);
+        const uint16_t* gq = (const uint16_t*)t.w;
+        u0 *= inv * bf16_to_f32(as_global(gq)[e]);
+        u1 *= inv * bf16_to_f32(as_global(gq)[e + half]);
+      }
       rope_cs(a, pos, e, &cs, &sn);
       qs[j * d + e] = u0 * cs - u1 * sn;
       qs[j * d + e + half] = u1 * cs + u0 * sn;
@@ -1701,6 +1741,14 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
         if (i < half / 2) {   // two adjacent rotation pairs of the key
           uint32_t e = 2 * i;
           float2 lo = ld_act2(ksrc + e), hi = ld_act2(ksrc + e + half);
+          if (qk_norm) {   // the key's half/2 threads: one aligned group of lanes at the top of the workgroup
+            const float ss = lane_group_sum<(int)(half / 2)>(lo.x * lo.x + lo.y * lo.y + hi.x * hi.x + hi.y * hi.y);
+            const float inv = 1.0f / sqrtf(ss / (float)d + t.f0);
+            const uint16_t* gk = (const uint16_t*)t.w2;
+            const uint32_t g0 = *as_global((const uint32_t*)(gk + e)), g1 = *as_global((const uint32_t*)(gk + e + half));
+            lo.x *= inv * bf16_lo(g0); lo.y *= inv * bf16_hi(g0);
+            hi.x *= inv * bf16_lo(g1); hi.y *= inv * bf16_hi(g1);
+          }
           float c0, s0, c1, s1;
           rope_cs(a, pos, e, &c0, &s0);
           rope_cs(a, pos, e + 1, &c1, &s1);

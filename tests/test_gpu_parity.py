@@ -370,3 +370,35 @@ def test_greedy_loop_decodes_several_tokens_in_one_launch(variant, opts, n_steps
     with pytest.raises(M.MpkError):
         gpu.graph.decode_step(tok.data_ptr(), pos.data_ptr(), gpu.logits.data_ptr(), stream)
     gpu.close()
+
+
+@pytest.mark.parametrize("variant,opts", [
+    (dict(), dict(fusion=0)),                                                     # rope operator
+    (dict(), dict(fusion=31, transitive_reduction=1)),                            # fused, register-resident body
+    (dict(batch=3), dict(fusion=31, transitive_reduction=1, launch_mode=1)),
+    (dict(n_q_heads=8, n_kv_heads=1, batch=2), dict(fusion=31, transitive_reduction=1)),   # 8 heads per KV head: online body
+    (dict(head_dim=128, n_q_heads=4, n_kv_heads=2, batch=8), dict(fusion=31, transitive_reduction=1)),
+    (dict(head_dim=128, n_q_heads=2, n_kv_heads=1), dict(fusion=7)),
+    (dict(ffn=0, n_experts=8, top_k=2, expert_ffn=64, batch=4), dict(fusion=31, transitive_reduction=1)),   # Qwen3-MoE-like
+])
+def test_qk_norm_models_match_oracle(variant, opts):
+    """Per-head RMSNorm of q and k before RoPE (MPK_MODEL_QK_NORM): rope operator, both fused
+    attention bodies, head_dim 64 and 128, three steps so that normalised keys are read back."""
+    s = G.small_variant("C1", qk_norm=True, max_seq=192, **variant)
+    rng = np.random.default_rng(5)
+    tok, pos = rng.integers(0, s.vocab, s.batch), rng.integers(30, 120, s.batch)
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 6), "f32")
+    gpu = GpuDecoder(s, 6, **opts)
+    for step in range(3):
+        want = ref.step(tok, pos)
+        got = gpu.step(tok, pos)
+        assert np.isfinite(got).all()
+        assert rel_err(got, want) < TOL, step
+        assert np.abs(got - want).max() / np.abs(want).max() < 1e-4, step
+        assert got.argmax(-1).tolist() == want.argmax(-1).tolist(), step
+        tok, pos = want.argmax(-1), pos + 1
+    # the same weights without the flag give different logits: the norm is really applied
+    plain = GpuDecoder(G.small_variant("C1", max_seq=192, **variant), 6, model=gpu.model, **opts)
+    assert np.abs(plain.step(tok, pos) - ref.step(tok, pos)).max() > 1e-2
+    plain.close()
+    gpu.close()
