@@ -289,36 +289,38 @@ __device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_
 // (TF_EPI_RESID), silu(gate) * up (TF_GATEUP: column c needs weight rows c and F + c).
 //
 // Weight rows of a task ("ring rows": one per column, or the (gate, up) pair of each column) are
-// split into 8 contiguous ranges, one per wavefront.  A wavefront walks its rows in groups of 4
-// and every group in segments of 4096 input elements; one (group, segment) is a block of
-// 4 rows x 8 stages, a stage being 64 lanes x 16 bytes = 512 elements: 32 sixteen-byte loads per
-// lane, 32 KB per wavefront, 256 KB per CU.  Steady state is deliberately plain: request a whole
-// block, then consume it stage by stage as it arrives (the loads of a wavefront complete in
-// order, so the wait for stage u is "at most 4 (7 - u) loads outstanding"); the other seven
-// wavefronts of the CU keep the memory system busy meanwhile.  Measured on this GPU that order
-// streams at 6.6 TB/s, whereas refilling each slot right after its use -- a register ring that is
-// live around the loop -- makes the compiler drain the whole queue before every use (2.8 TB/s).
+// split into 8 contiguous ranges, one per wavefront.  A wavefront walks its rows in pairs and
+// every pair in segments of 4096 input elements; one (pair, segment) is a half block of
+// 2 rows x 8 stages, a stage being 64 lanes x 16 bytes = 512 elements: 16 sixteen-byte loads per
+// lane.  A wavefront owns two half-block buffers and keeps both requested: it consumes one stage
+// by stage as it arrives (the loads of a wavefront complete in order), requests that buffer's
+// next half block at once, and turns to the other buffer -- at least 16 KB per wavefront are in
+// flight at any time, 32 KB (256 KB per CU) at the peaks.  With ONE buffer of twice the size,
+// requested whole and then consumed whole, every block boundary cost a memory round trip with
+// nothing in flight; that showed in tasks of few blocks (three per wavefront in the gate/up and
+// down projections of the 8B shape).
 //
 // Cross-task pipelining (paper Section 5.3).  Weights never depend on an event, so a task
-// requests its first block (256 KB per CU) BEFORE it waits for its dependent event: the block
-// streams in while the input vector is still being produced elsewhere.  And a task ends for
+// requests its first two half blocks (256 KB per CU) BEFORE it waits for its dependent event:
+// they stream in while the input vector is still being produced elsewhere.  And a task ends for
 // wavefronts 1..7 as soon as the workgroup's results are in LDS: they walk straight into the
-// worker's next task and issue its first block, while wavefront 0 alone applies the epilogue,
+// worker's next task and issue its first requests, while wavefront 0 alone applies the epilogue,
 // writes the outputs with coherent stores, waits for exactly those stores and notifies the
 // triggering event -- with no weight loads queued ahead of them, because memory operations of one
 // wavefront complete in order -- and only then requests its own share and polls the next event.
-// The block buffer is local to a task on purpose: carried around the task loop instead, the
-// compiler moves parts of it to scratch memory, and a scratch access in the middle of a request
+// The buffers are local to a task on purpose: carried around the task loop instead, the
+// compiler moves parts of them to scratch memory, and a scratch access in the middle of a request
 // waits for every load issued before it.
-constexpr int kRingRows = 4, kRingStages = 8;
-constexpr uint32_t kSegLen = 512u * kRingStages;   // input elements per block row
-struct Ring {
-  u32x4 s[kRingRows][kRingStages];
+constexpr int kHalfRows = 2, kRingStages = 8;
+constexpr int kRingRows = 2 * kHalfRows;            // weight rows in flight per wavefront
+constexpr uint32_t kSegLen = 512u * kRingStages;   // input elements per half-block row
+struct HalfRing {
+  u32x4 s[kHalfRows][kRingStages];
 };
 
-__device__ __forceinline__ void ring_clear(Ring& ring) {
+__device__ __forceinline__ void ring_clear(HalfRing& ring) {
 #pragma unroll
-  for (int i = 0; i < kRingRows; ++i)
+  for (int i = 0; i < kHalfRows; ++i)
 #pragma unroll
     for (int u = 0; u < kRingStages; ++u) ring.s[i][u] = u32x4{0, 0, 0, 0};
 }
@@ -329,7 +331,6 @@ struct LinGeom {
   uint32_t K, c0, F, gateup;
   uint32_t r0, r1;    // ring rows [r0, r1) of this wavefront within the task
   uint32_t nseg;      // segments per row
-  uint32_t nblocks;   // groups of 4 rows x segments
 };
 
 __device__ __forceinline__ LinGeom lin_geom(const TaskDesc& t, uint32_t wave) {
@@ -346,68 +347,65 @@ __device__ __forceinline__ LinGeom lin_geom(const TaskDesc& t, uint32_t wave) {
   g.r0 = min(wave * rpw, R);
   g.r1 = min(g.r0 + rpw, R);
   g.nseg = (t.K + kSegLen - 1u) / kSegLen;
-  g.nblocks = (g.r1 - g.r0 + kRingRows - 1u) / kRingRows * g.nseg;
   return g;
 }
 
-// Block `blk` of a wavefront: rows [row0, row0 + nrows) of the task, segment `seg`.
-struct LinBlock {
-  const uint16_t* p[kRingRows];   // address of the lane's 16 bytes of stage 0 (rows past nrows repeat the last)
+// Position of a wavefront in its sequence of half blocks: rows [row0, row0 + 2) x segment `seg`,
+// segments of a pair first.  Two of them walk the sequence: one requests, one consumes.
+struct LinCursor {
+  uint32_t row0, seg;
+};
+__device__ __forceinline__ bool lin_valid(const LinGeom& g, const LinCursor& c) { return c.row0 < g.r1; }
+__device__ __forceinline__ void lin_advance(const LinGeom& g, LinCursor& c) {
+  if (++c.seg == g.nseg) {
+    c.seg = 0;
+    c.row0 += kHalfRows;
+  }
+}
+
+// The half block at a cursor.
+struct LinHalf {
+  const uint16_t* p[kHalfRows];   // row start + segment start (a second row past the end repeats the first)
   uint32_t row0, nrows, seg, seglen;
 };
 
-__device__ __forceinline__ LinBlock lin_block(const LinGeom& g, uint32_t blk, int lane) {
-  LinBlock B;
-  const uint32_t grp = blk / g.nseg;
-  B.seg = blk - grp * g.nseg;
-  B.row0 = g.r0 + grp * kRingRows;
-  B.nrows = min(g.r1 - B.row0, (uint32_t)kRingRows);
-  B.seglen = min(kSegLen, g.K - B.seg * kSegLen);
+__device__ __forceinline__ LinHalf lin_half(const LinGeom& g, const LinCursor& c) {
+  LinHalf B;
+  B.seg = c.seg;
+  B.row0 = c.row0;
+  B.nrows = min(g.r1 - c.row0, (uint32_t)kHalfRows);
+  B.seglen = min(kSegLen, g.K - c.seg * kSegLen);
 #pragma unroll
-  for (int i = 0; i < kRingRows; ++i) {
+  for (int i = 0; i < kHalfRows; ++i) {
     const uint32_t r = B.row0 + min((uint32_t)i, B.nrows - 1u);
     const uint32_t wrow = g.gateup ? (g.c0 + (r >> 1) + ((r & 1u) ? g.F : 0u)) : g.c0 + r;
-    B.p[i] = g.W + (size_t)wrow * g.K + B.seg * kSegLen;
+    B.p[i] = g.W + (size_t)wrow * g.K + c.seg * kSegLen;
   }
   return B;
 }
 
-// Requests rows [0, ROWS) of a block, stage by stage.  Lanes past the end of a short segment
-// re-read its last 16 bytes (the staged input is zero there), so every lane takes part in every
-// load.
-template <int ROWS>
-__device__ __forceinline__ void lin_request(const LinBlock& B, Ring& ring, int lane) {
+// Requests a half block, stage by stage.  Lanes past the end of a short segment re-read its last
+// 16 bytes (the staged input is zero there), so every lane takes part in every load.
+__device__ __forceinline__ void lin_request(const LinHalf& B, HalfRing& ring, int lane) {
   if (B.seglen == kSegLen) {   // full segment: one base address per row, constant stage offsets
 #pragma unroll
     for (int u = 0; u < kRingStages; ++u)
 #pragma unroll
-      for (int i = 0; i < ROWS; ++i) ring.s[i][u] = ld_stream16(B.p[i] + lane * 8 + u * 512);
+      for (int i = 0; i < kHalfRows; ++i) ring.s[i][u] = ld_stream16(B.p[i] + lane * 8 + u * 512);
   } else {
 #pragma unroll
     for (int u = 0; u < kRingStages; ++u) {
       const uint32_t o = min((uint32_t)u * 512u + (uint32_t)lane * 8u, B.seglen - 8u);
 #pragma unroll
-      for (int i = 0; i < ROWS; ++i) ring.s[i][u] = ld_stream16(B.p[i] + o);
+      for (int i = 0; i < kHalfRows; ++i) ring.s[i][u] = ld_stream16(B.p[i] + o);
     }
   }
 }
-// The two arms end in different (empty) assembly statements on purpose: otherwise the compiler
-// merges their identical last load into one whose destination slot is chosen at run time, and a
-// ring slot addressed that way is moved from registers to scratch memory.
-__device__ __forceinline__ void lin_request_any(const LinBlock& B, Ring& ring, int lane) {
-  if (B.nrows > 2) {
-    lin_request<4>(B, ring, lane);
-    asm volatile("; four rows requested" ::: "memory");
-  } else {
-    lin_request<2>(B, ring, lane);
-    asm volatile("; two rows requested" ::: "memory");
-  }
-}
 
-// Adds the block's partial dot products to acc.
-template <int NB, int ROWS>
-__device__ __forceinline__ void lin_consume(const LinBlock& B, const Ring& ring, const float* xs, uint32_t Kp,
-                                            int lane, float (&acc)[kRingRows][NB]) {
+// Adds the half block's partial dot products to acc.
+template <int NB>
+__device__ __forceinline__ void lin_consume(const LinHalf& B, const HalfRing& ring, const float* xs, uint32_t Kp,
+                                            int lane, float (&acc)[kHalfRows][NB]) {
 #pragma unroll
   for (int u = 0; u < kRingStages; ++u) {
 #pragma unroll
@@ -415,7 +413,7 @@ __device__ __forceinline__ void lin_consume(const LinBlock& B, const Ring& ring,
       const float4* xp = (const float4*)(xs + (size_t)b * Kp + B.seg * kSegLen + u * 512 + lane * 8);
       const float4 x0 = xp[0], x1 = xp[1];
 #pragma unroll
-      for (int i = 0; i < ROWS; ++i) acc[i][b] = dot8(ring.s[i][u], x0, x1, acc[i][b]);
+      for (int i = 0; i < kHalfRows; ++i) acc[i][b] = dot8(ring.s[i][u], x0, x1, acc[i][b]);
     }
   }
 }
@@ -480,9 +478,23 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
   float* res_lds = outbuf + (size_t)rows_max * NB;   // [rows_max][NB]
   float* ssq = res_lds + (size_t)rows_max * NB;      // [8][NB]
   const LinGeom g = lin_geom(t, wave);
-  Ring ring;   // local to the task: nothing is live around the task loop, so it stays in registers
-  ring_clear(ring);
-  if (g.nblocks > 0) lin_request_any(lin_block(g, 0, lane), ring, lane);
+  HalfRing h0, h1;   // local to the task: nothing is live around the task loop, so they stay in registers
+  ring_clear(h0);
+  ring_clear(h1);
+  LinCursor rq{g.r0, 0u};   // next half block to request
+  // (every request site ends in an (empty) assembly statement of its own: otherwise the compiler
+  // may merge the identical last loads of two sites into one whose destination is chosen at run
+  // time, and a buffer addressed that way is moved from registers to scratch memory)
+  if (lin_valid(g, rq)) {
+    lin_request(lin_half(g, rq), h0, lane);
+    lin_advance(g, rq);
+    asm volatile("; first half block requested" ::: "memory");
+  }
+  if (lin_valid(g, rq)) {
+    lin_request(lin_half(g, rq), h1, lane);
+    lin_advance(g, rq);
+    asm volatile("; second half block requested" ::: "memory");
+  }
   // ---- dependent event: wavefront 0 polls, the others wait at the barrier
   if (wait_ev >= 0) {
     const uint32_t w = linear_wait(a, wait_ev, s_flag, wave, lane, svc);
@@ -550,37 +562,50 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
   }
   lds_barrier();
   trace_mark(a, t, 2);
-  // ---- stream this wavefront's rows, block by block
+  // ---- stream this wavefront's rows: the two buffers in turn
   {
-    float acc[kRingRows][NB];
+    float acc[kHalfRows][NB];
 #pragma unroll
-    for (int i = 0; i < kRingRows; ++i)
+    for (int i = 0; i < kHalfRows; ++i)
 #pragma unroll
       for (int b = 0; b < NB; ++b) acc[i][b] = 0.f;
-    for (uint32_t blk = 0; blk < g.nblocks; ++blk) {
-      const LinBlock B = lin_block(g, blk, lane);
-      if (B.nrows > 2) {
-        if (blk > 0) {   // block 0 was requested before the event wait
-          lin_request<4>(B, ring, lane);
-          asm volatile("; four rows requested" ::: "memory");
-        }
-        lin_consume<NB, 4>(B, ring, xs, Kp, lane, acc);
-      } else {
-        if (blk > 0) {
-          lin_request<2>(B, ring, lane);
-          asm volatile("; two rows requested" ::: "memory");
-        }
-        lin_consume<NB, 2>(B, ring, xs, Kp, lane, acc);
-      }
-      if (B.seg + 1 == g.nseg) {   // the group of rows is complete: reduce across lanes, results to LDS
+    // the pair of rows is complete with its last segment: reduce across lanes, results to LDS
+    auto finish = [&](const LinHalf& B) {
+      if (B.seg + 1 == g.nseg) {
 #pragma unroll
-        for (int i = 0; i < kRingRows; ++i)
+        for (int i = 0; i < kHalfRows; ++i)
 #pragma unroll
           for (int b = 0; b < NB; ++b) {
             const float v = wave_sum(acc[i][b]);
             if (lane == 0 && (uint32_t)i < B.nrows) outbuf[(size_t)(B.row0 + i) * NB + b] = v;
             acc[i][b] = 0.f;
           }
+      }
+    };
+    LinCursor cs{g.r0, 0u};
+    while (lin_valid(g, cs)) {
+      {
+        const LinHalf B = lin_half(g, cs);
+        lin_consume<NB>(B, h0, xs, Kp, lane, acc);
+        finish(B);
+        lin_advance(g, cs);
+      }
+      if (lin_valid(g, rq)) {
+        lin_request(lin_half(g, rq), h0, lane);
+        lin_advance(g, rq);
+        asm volatile("; first buffer requested again" ::: "memory");
+      }
+      if (!lin_valid(g, cs)) break;
+      {
+        const LinHalf B = lin_half(g, cs);
+        lin_consume<NB>(B, h1, xs, Kp, lane, acc);
+        finish(B);
+        lin_advance(g, cs);
+      }
+      if (lin_valid(g, rq)) {
+        lin_request(lin_half(g, rq), h1, lane);
+        lin_advance(g, rq);
+        asm volatile("; second buffer requested again" ::: "memory");
       }
     }
   }
