@@ -93,7 +93,7 @@ typedef struct mpk_kv_ptrs {
 #define MPK_FUSE_NORM 1u   /* RMSNorm folded into the linear operator that consumes it          */
 #define MPK_FUSE_RESID 2u  /* residual add folded into the producing linear operator's epilogue */
 #define MPK_FUSE_SWIGLU 4u /* gate/up projection emits silu(gate)*up directly                   */
-#define MPK_FUSE_MERGE 8u  /* split-KV merge folded into the O projection's input stage         */
+#define MPK_FUSE_MERGE 8u  /* split-KV merge done by the last attention chunk task to finish    */
 #define MPK_FUSE_ROPE 16u  /* RoPE + KV append folded into the attention tasks                  */
 
 #define MPK_DEBUG_TRACE 1u /* record per-task timestamps inside the persistent kernel           */
@@ -163,7 +163,10 @@ mpk_status mpk_compile_dag(uint32_t n_tasks, const uint32_t *pairs, size_t n_pai
  *   positions  : device int32 [batch]; positions[b] = number of rows already cached for b
  *   logits_out : device fp32 [batch][vocab], written by the LM-head tasks
  * A position >= max_seq or a token outside [0, vocab) is detected in the kernel and reported by
- * mpk_graph_status.  Steps of one graph must not overlap (same stream, or externally ordered). */
+ * mpk_graph_status.  Steps of one graph must not overlap (same stream, or externally ordered).
+ * The step number is a launch argument that events are compared against: a persistent-kernel
+ * launch must not be captured into a HIP graph and replayed (the replays would carry the captured
+ * step number); MPK_LAUNCH_PER_OP launches use no events and may be captured. */
 mpk_status mpk_decode_step(mpk_graph *g, const int32_t *token_ids, const int32_t *positions,
                            float *logits_out, void *stream);
 

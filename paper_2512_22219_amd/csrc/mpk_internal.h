@@ -32,7 +32,7 @@ enum TaskKind : uint16_t {
 
 enum TaskFlags : uint16_t {
   TF_PRO_NORM = 1,    // linear: RMSNorm the input row first (gain = w2, eps = f0)
-  TF_PRO_MERGE = 2,   // linear: input is the split-KV partial buffer, merge while loading
+  // (2: unused)
   TF_EPI_RESID = 4,   // linear: out = in2 + W x
   TF_GATEUP = 8,      // linear: out_c = silu(W[c] x) * (W[F + c] x), F = p0
   TF_OUT_LOGITS = 16, // output pointer is the caller's logits buffer of this step

@@ -292,13 +292,14 @@ __device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_
 // split into 8 contiguous ranges, one per wavefront.  A wavefront walks its rows in pairs and
 // every pair in segments of 4096 input elements; one (pair, segment) is a half block of
 // 2 rows x 8 stages, a stage being 64 lanes x 16 bytes = 512 elements: 16 sixteen-byte loads per
-// lane.  A wavefront owns two half-block buffers and keeps both requested: it consumes one stage
-// by stage as it arrives (the loads of a wavefront complete in order), requests that buffer's
-// next half block at once, and turns to the other buffer -- at least 16 KB per wavefront are in
-// flight at any time, 32 KB (256 KB per CU) at the peaks.  With ONE buffer of twice the size,
-// requested whole and then consumed whole, every block boundary cost a memory round trip with
-// nothing in flight; that showed in tasks of few blocks (three per wavefront in the gate/up and
-// down projections of the 8B shape).
+// lane.  A wavefront owns two half-block buffers (32 KB, 256 KB per CU) and uses them in turn: it
+// consumes one, requests that buffer's next half block at once, and turns to the other.  The
+// compiler's count of the loads in flight does not survive the loop's back edge (it waits for
+// both buffers before the first use of either), so a wavefront still drains its queue once per
+// pair of half blocks; the eight wavefronts of a CU drift apart and cover for each other.
+// Against ONE buffer of twice the size, requested whole and then consumed whole: the first
+// buffer's request goes out half a block earlier, and a task with two rows per wavefront (the O
+// and down projections of the 8B shape) pre-loads two segments instead of one.
 //
 // Cross-task pipelining (paper Section 5.3).  Weights never depend on an event, so a task
 // requests its first two half blocks (256 KB per CU) BEFORE it waits for its dependent event:
@@ -915,7 +916,7 @@ __device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const St
       uint32_t last = 0;
       if (lane == 0) {
         const uint32_t old = __hip_atomic_fetch_add(as_global(a.g->grp_counters + t.p2), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        last = (old + 1u == a.epoch * parts) ? 1u : 0u;
+        last = ((old + 1u) % parts == 0u) ? 1u : 0u;   // every step adds exactly `parts` (also when a captured launch is replayed with its step number frozen)
       }
       last = __builtin_amdgcn_readfirstlane(last);
       if (last) {
@@ -2845,6 +2846,15 @@ static mpk_status launch_steps(mpk_graph* g, uint32_t n_steps, const int32_t* to
   a.n_sched = g->n_sched; a.flags = g->d_trace ? kTraceBit : 0u;
   a.token_ids = token_ids; a.positions = positions; a.logits = logits_out;
   hipStream_t s = (hipStream_t)stream;
+  if (h.opt.launch_mode == MPK_LAUNCH_MEGA) {
+    // events compare their counters with the step number, a launch argument: a captured launch
+    // replayed later would carry a stale one and wait for nothing
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (s != nullptr && hipStreamIsCapturing(s, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone) {
+      set_error("a persistent-kernel launch cannot be captured into a HIP graph");
+      return MPK_ERR_UNSUPPORTED;
+    }
+  }
   if (h.opt.greedy_loop) {   // output pointers of this launch -> graph record, ordered on the stream
     g->launch_out[0] = tokens_out; g->launch_out[1] = logits_all;
     HIP_TRY(hipMemcpyAsync((char*)g->d_const + offsetof(GraphConst, tokens_out), g->launch_out, sizeof(g->launch_out),

@@ -155,6 +155,50 @@ def test_down_projection_decomposed_along_its_input(batch, ffn, opts):
     gpu.close()
 
 
+def test_captured_per_operator_launches_replay_correctly_and_persistent_capture_is_refused():
+    """Kernel-per-operator launches of a graph with (row block, input part) tasks, captured once
+    into a HIP graph: every replay must give what an eager launch gives (the arrival counters of
+    the row blocks must not depend on the step number, which a replay carries frozen).  Replays
+    alternate with eager work and synchronisations.  Capturing a persistent-kernel launch is an
+    error: its events are compared with the step number."""
+    s = G.small_variant("C1", batch=8, ffn=8192, n_layers=2, max_seq=192)
+    tok = G.tokens(3, s)
+    pos = np.array([(29 * b + 11) % 150 for b in range(8)], np.int32)
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 3), "f32")
+    gpu = GpuDecoder(s, 3, fusion=31, transitive_reduction=1, n_workers=32, launch_mode=1)
+    side = torch.cuda.Stream()
+    gpu.tok.copy_(torch.as_tensor(tok)); gpu.pos.copy_(torch.as_tensor(pos))
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            gpu.graph.decode_step(gpu.tok.data_ptr(), gpu.pos.data_ptr(), gpu.logits.data_ptr(), side.cuda_stream)
+    for step in range(4):
+        want = ref.step(tok, pos)
+        gpu.tok.copy_(torch.as_tensor(tok)); gpu.pos.copy_(torch.as_tensor(pos))
+        gpu.logits.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        gpu.graph.status()
+        got = gpu.logits.cpu().numpy()
+        assert np.isfinite(got).all(), step
+        assert rel_err(got, want) < TOL, step
+        assert got.argmax(-1).tolist() == want.argmax(-1).tolist(), step
+        tok, pos = want.argmax(-1).astype(np.int32), pos + 1
+    gpu.close()
+    mega = GpuDecoder(s, 3, fusion=31, transitive_reduction=1, n_workers=32)
+    g2 = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g2, stream=side):
+            with pytest.raises(M.MpkError, match="captured"):
+                mega.graph.decode_step(mega.tok.data_ptr(), mega.pos.data_ptr(), mega.logits.data_ptr(), side.cuda_stream)
+    want = D.DecoderOracle(s, G.SynthWeights(s, 3), "f32").step(G.tokens(3, s), np.array([(29 * b + 11) % 150 for b in range(8)], np.int32))
+    got = mega.step(G.tokens(3, s), np.array([(29 * b + 11) % 150 for b in range(8)], np.int32))
+    assert rel_err(got, want) < TOL   # the graph is still usable after the refused launch
+    mega.close()
+
+
 def test_greedy_32_steps_free_running_and_teacher_forced():
     s = G.small_variant("C1", max_seq=192)
     tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
