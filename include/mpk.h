@@ -132,6 +132,10 @@ typedef struct mpk_compile_options {
                                tokens can be decoded in ONE launch (mpk_decode_steps): the
                                kernel runs until its workload is done (Section 5).  Such a
                                graph is run with mpk_decode_steps only                          */
+  uint32_t kv_batch;        /* number of sequences the KV cache is laid out for (the `batch`
+                               extent of mpk_kv_ptrs' layout); 0 = cfg.batch.  Lets a graph for
+                               fewer sequences run on the first cfg.batch slots of a larger
+                               cache (mpk_compile_set)                                          */
 } mpk_compile_options;
 
 typedef struct mpk_graph mpk_graph;
@@ -286,6 +290,32 @@ mpk_status mpk_graph_moe_active(mpk_graph *g, uint32_t *out, size_t cap, size_t 
  * elements; both NULL returns the element count in *need.  Call after synchronising the stream. */
 mpk_status mpk_graph_moe_selection(mpk_graph *g, uint32_t *experts, float *weights, size_t cap,
                                    size_t *need);
+
+/* One graph per representative batch size (Section 6.1, "Supporting runtime dynamism": task graphs
+ * specialised for the powers of two up to the maximum batch size, the one that fits the current
+ * batch is selected at run time).  mpk_compile_set compiles graphs for batch 1, 2, 4, ... below
+ * cfg->batch and for cfg->batch itself; all of them share the weights and the ONE KV cache, which
+ * is laid out for cfg->batch sequences (a smaller graph works on the first slots of it).
+ * opts->kv_batch must be 0.  Errors as mpk_compile; on failure nothing is left allocated. */
+typedef struct mpk_graph_set mpk_graph_set;
+mpk_status mpk_compile_set(const mpk_model_config *cfg, const mpk_weight_ptrs *weights,
+                           const mpk_kv_ptrs *kv, const mpk_compile_options *opts,
+                           mpk_graph_set **out);
+/* Number of graphs in the set; graph i (borrowed, ascending batch size, NULL if i is out of
+ * range) for stats / status / export; the batch size of the graph that runs n_active sequences
+ * (0 if n_active is 0 or above the maximum). */
+uint32_t mpk_set_size(const mpk_graph_set *s);
+mpk_graph *mpk_set_graph(mpk_graph_set *s, uint32_t i);
+uint32_t mpk_set_batch_for(const mpk_graph_set *s, uint32_t n_active);
+/* One decode step for the sequences in slots 0 .. n_active-1, on the smallest graph that holds
+ * them (batch b = mpk_set_batch_for(s, n_active)).  Slots n_active .. b-1 are computed as padding:
+ *   token_ids, positions : device int32, at least b entries, ALL valid (padding slots included:
+ *                          their cache rows at positions[slot] are overwritten)
+ *   logits_out           : device fp32 [b][vocab]; rows n_active .. b-1 belong to the padding
+ * Otherwise as mpk_decode_step.  INVALID_ARG if n_active is 0 or above the maximum batch. */
+mpk_status mpk_set_decode_step(mpk_graph_set *s, uint32_t n_active, const int32_t *token_ids,
+                               const int32_t *positions, float *logits_out, void *stream);
+void mpk_set_destroy(mpk_graph_set *s);
 
 const char *mpk_last_error(void);
 void mpk_graph_destroy(mpk_graph *g);

@@ -52,7 +52,7 @@ class CompileOptions(C.Structure):
                 ("struct_size", "n_workers", "n_sched_wgs", "fusion", "transitive_reduction",
                  "attn_chunks", "tiles_linear", "tiles_lm_head", "tiles_pointwise", "launch_mode",
                  "force_aot", "prefetch", "host_only", "spin_timeout_ms", "debug_flags",
-                 "tiles_moe", "greedy_loop")]
+                 "tiles_moe", "greedy_loop", "kv_batch")]
 
 
 class Stats(C.Structure):
@@ -84,8 +84,9 @@ EXPORT_EVENT = np.dtype([("required", "<u4"), ("first", "<u4"), ("last", "<u4"),
 
 SYMBOLS = ("mpk_compile", "mpk_compile_dag", "mpk_decode_step", "mpk_decode_steps", "mpk_graph_status",
            "mpk_graph_reset", "mpk_graph_stats", "mpk_graph_export", "mpk_graph_trace",
-           "mpk_graph_moe_active", "mpk_graph_moe_selection", "mpk_last_error",
-           "mpk_graph_destroy")
+           "mpk_graph_moe_active", "mpk_graph_moe_selection", "mpk_compile_set",
+           "mpk_set_decode_step", "mpk_set_size", "mpk_set_batch_for", "mpk_set_graph",
+           "mpk_set_destroy", "mpk_last_error", "mpk_graph_destroy")
 
 _lib = None
 
@@ -115,7 +116,17 @@ def lib():
         L.mpk_last_error.restype = C.c_char_p
         L.mpk_graph_destroy.argtypes = [vp]
         L.mpk_graph_destroy.restype = None
-        for n in SYMBOLS[:11]:
+        L.mpk_compile_set.argtypes = L.mpk_compile.argtypes
+        L.mpk_set_decode_step.argtypes = [vp, C.c_uint32, vp, vp, vp, vp]
+        L.mpk_set_size.argtypes = [vp]
+        L.mpk_set_size.restype = C.c_uint32
+        L.mpk_set_batch_for.argtypes = [vp, C.c_uint32]
+        L.mpk_set_batch_for.restype = C.c_uint32
+        L.mpk_set_graph.argtypes = [vp, C.c_uint32]
+        L.mpk_set_graph.restype = vp
+        L.mpk_set_destroy.argtypes = [vp]
+        L.mpk_set_destroy.restype = None
+        for n in SYMBOLS[:13]:
             getattr(L, n).restype = C.c_int
         _lib = L
     return _lib
@@ -240,6 +251,64 @@ class Graph:
             self.destroy()
         except Exception:
             pass
+
+
+class GraphSet:
+    """Owner of one mpk_graph_set handle: a graph per power-of-two batch size up to shape.batch."""
+
+    def __init__(self, handle, keepalive=None):
+        self._h = handle
+        self._keep = keepalive
+
+    def __len__(self):
+        return lib().mpk_set_size(self._h)
+
+    def batch_for(self, n_active: int) -> int:
+        return lib().mpk_set_batch_for(self._h, n_active)
+
+    def graph(self, i: int) -> Graph:
+        """Graph i of the set, borrowed: valid while the set lives, never destroyed through it."""
+        h = lib().mpk_set_graph(self._h, i)
+        if not h:
+            raise IndexError(i)
+        g = Graph(None, self)
+        g._h = C.c_void_p(h)
+        g.destroy = lambda: None
+        return g
+
+    def decode_step(self, n_active: int, token_ids_ptr: int, positions_ptr: int, logits_ptr: int, stream: int = 0):
+        _check(lib().mpk_set_decode_step(self._h, n_active, token_ids_ptr, positions_ptr, logits_ptr, stream))
+
+    def destroy(self):
+        if self._h:
+            lib().mpk_set_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def _marshal_model(shape, weights, kv):
+    arr = (LayerWeights * shape.n_layers)()
+    for l, lw in enumerate(weights["layers"]):
+        for k, v in lw.items():
+            setattr(arr[l], k, v)
+    wp = WeightPtrs(weights["embed"], weights["final_norm"], weights["lm_head"], arr)
+    kp = KvPtrs(kv[0], kv[1])
+    return arr, wp, kp
+
+
+def compile_set(shape, weights: dict, kv: tuple, **opts) -> GraphSet:
+    """Graphs for batch 1, 2, 4, ... and shape.batch over one KV cache laid out for shape.batch."""
+    cfg = model_config(shape)
+    o = compile_options(**opts)
+    h = C.c_void_p()
+    arr, wp, kp = _marshal_model(shape, weights, kv)
+    _check(lib().mpk_compile_set(C.byref(cfg), C.byref(wp), C.byref(kp), C.byref(o), C.byref(h)))
+    return GraphSet(h, [arr, wp, kp])
 
 
 def compile_graph(shape, weights: dict | None, kv: tuple | None, **opts) -> Graph:

@@ -872,7 +872,7 @@ static const float* act_ref(const HostGraph& g, int tensor) {
 
 static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGraph& g) {
   g.descs.assign(g.tasks.size(), TaskDesc{});
-  const size_t kv_layer = (size_t)c.batch * c.n_kv_heads * c.max_seq * c.head_dim;   // elements
+  const size_t kv_layer = (size_t)(g.opt.kv_batch ? g.opt.kv_batch : c.batch) * c.n_kv_heads * c.max_seq * c.head_dim;   // elements
   for (size_t i = 0; i < g.tasks.size(); ++i) {
     const HostTask& ht = g.tasks[i];
     TaskDesc& t = g.descs[i];
@@ -1008,6 +1008,7 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
   if (c.batch > 16) { set_error("batch %u unsupported by the dense linear bodies (max 16)", c.batch); return MPK_ERR_UNSUPPORTED; }
   if (o.greedy_loop > 1) { set_error("greedy_loop must be 0 or 1"); return MPK_ERR_INVALID_ARG; }
   if (o.debug_flags & ~MPK_DEBUG_TRACE) { set_error("unknown debug_flags bits"); return MPK_ERR_INVALID_ARG; }
+  if (o.kv_batch != 0 && o.kv_batch < c.batch) { set_error("kv_batch %u is below batch %u", o.kv_batch, c.batch); return MPK_ERR_INVALID_ARG; }
   if (o.fusion & ~(MPK_FUSE_NORM | MPK_FUSE_RESID | MPK_FUSE_SWIGLU | MPK_FUSE_MERGE | MPK_FUSE_ROPE)) { set_error("unknown fusion bits"); return MPK_ERR_INVALID_ARG; }
   if (!o.host_only) {
     if (!w || !kv || !w->layers) { set_error("weights / kv pointers are NULL"); return MPK_ERR_INVALID_ARG; }

@@ -21,6 +21,8 @@
 #include <cstddef>
 #include <cstdio>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -2682,6 +2684,20 @@ static mpk_status upload(T** dst, const std::vector<T>& src) {
   return MPK_OK;
 }
 
+// The dynamic-LDS limit is an attribute of the kernel function, shared by every graph that uses
+// the same kernel variant: it is only ever raised, or compiling a graph with a smaller requirement
+// would break the launches of an earlier one.
+static hipError_t reserve_lds(const void* fn, uint32_t bytes) {
+  static std::mutex mu;
+  static std::map<const void*, uint32_t> reserved;
+  std::lock_guard<std::mutex> lock(mu);
+  uint32_t& cur = reserved[fn];
+  if (bytes <= cur) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) cur = bytes;
+  return e;
+}
+
 extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_ptrs* weights,
                                   const mpk_kv_ptrs* kv, const mpk_compile_options* opts,
                                   mpk_graph** out) {
@@ -2707,9 +2723,9 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
   HostGraph& h = g->h;
   // residency: dynamic LDS above half of a CU's 160 KB caps occupancy at one workgroup per CU
   g->kv = pick_variant(cfg->head_dim, cfg->n_q_heads / cfg->n_kv_heads, cfg->batch, cfg->n_experts != 0);
-  hipError_t e = hipFuncSetAttribute((const void*)g->kv->mega, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h.lds_bytes);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)g->kv->op, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h.lds_bytes);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)g->kv->loop, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h.lds_bytes);
+  hipError_t e = reserve_lds((const void*)g->kv->mega, h.lds_bytes);
+  if (e == hipSuccess) e = reserve_lds((const void*)g->kv->op, h.lds_bytes);
+  if (e == hipSuccess) e = reserve_lds((const void*)g->kv->loop, h.lds_bytes);
   if (e != hipSuccess) { set_error("cannot reserve %u bytes of LDS: %s", h.lds_bytes, hipGetErrorString(e)); return fail(MPK_ERR_RESIDENCY); }
   int per_cu = 0;
   e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)g->kv->mega, kThreads, h.lds_bytes);
@@ -3002,6 +3018,79 @@ extern "C" mpk_status mpk_graph_moe_selection(mpk_graph* g, uint32_t* experts, f
     if (experts) HIP_TRY(hipMemcpy(experts + l * P, meta + 2 + 3 * E + 2 * P, P * sizeof(uint32_t), hipMemcpyDeviceToHost));
   }
   return MPK_OK;
+}
+
+// ------------------------------------------------------------------------------ graph sets
+// Section 6.1 ("Supporting runtime dynamism"): one task graph per representative batch size, the
+// powers of two up to the maximum; the smallest that holds the active sequences runs.
+struct mpk_graph_set {
+  std::vector<mpk_graph*> graphs;   // ascending batch size; the last one is the maximum batch
+  std::vector<uint32_t> batch;
+};
+
+extern "C" void mpk_set_destroy(mpk_graph_set* s) {
+  if (!s) return;
+  for (mpk_graph* g : s->graphs) mpk_graph_destroy(g);
+  delete s;
+}
+
+extern "C" mpk_status mpk_compile_set(const mpk_model_config* cfg, const mpk_weight_ptrs* weights,
+                                      const mpk_kv_ptrs* kv, const mpk_compile_options* opts,
+                                      mpk_graph_set** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !out) { set_error("cfg or out is NULL"); return MPK_ERR_INVALID_ARG; }
+  if (cfg->struct_size != sizeof(mpk_model_config)) { set_error("mpk_model_config.struct_size is %u, expected %zu", cfg->struct_size, sizeof(mpk_model_config)); return MPK_ERR_INVALID_ARG; }
+  if (cfg->batch == 0) { set_error("a model dimension is zero"); return MPK_ERR_INVALID_ARG; }
+  mpk_compile_options o{};
+  if (opts) {
+    if (opts->struct_size != sizeof(mpk_compile_options)) {
+      set_error("mpk_compile_options.struct_size is %u, expected %zu", opts->struct_size, sizeof(mpk_compile_options));
+      return MPK_ERR_INVALID_ARG;
+    }
+    o = *opts;
+  } else {
+    o.struct_size = sizeof(o);
+  }
+  if (o.kv_batch != 0) { set_error("kv_batch is set by mpk_compile_set itself"); return MPK_ERR_INVALID_ARG; }
+  o.kv_batch = cfg->batch;
+  mpk_graph_set* s = new (std::nothrow) mpk_graph_set();
+  if (!s) { set_error("out of host memory"); return MPK_ERR_OOM; }
+  std::vector<uint32_t> sizes;
+  for (uint32_t b = 1; b < cfg->batch; b *= 2) sizes.push_back(b);
+  sizes.push_back(cfg->batch);
+  for (uint32_t b : sizes) {
+    mpk_model_config c = *cfg;
+    c.batch = b;
+    mpk_graph* g = nullptr;
+    const mpk_status st = mpk_compile(&c, weights, kv, &o, &g);
+    if (st != MPK_OK) { mpk_set_destroy(s); return st; }   // (the message of the failed compile stands)
+    s->graphs.push_back(g);
+    s->batch.push_back(b);
+  }
+  *out = s;
+  return MPK_OK;
+}
+
+extern "C" uint32_t mpk_set_size(const mpk_graph_set* s) { return s ? (uint32_t)s->graphs.size() : 0u; }
+
+extern "C" mpk_graph* mpk_set_graph(mpk_graph_set* s, uint32_t i) {
+  return (s && i < s->graphs.size()) ? s->graphs[i] : nullptr;
+}
+
+extern "C" uint32_t mpk_set_batch_for(const mpk_graph_set* s, uint32_t n_active) {
+  if (!s || n_active == 0) return 0;
+  for (uint32_t b : s->batch)
+    if (b >= n_active) return b;
+  return 0;
+}
+
+extern "C" mpk_status mpk_set_decode_step(mpk_graph_set* s, uint32_t n_active, const int32_t* token_ids,
+                                          const int32_t* positions, float* logits_out, void* stream) {
+  if (!s) { set_error("set is NULL"); return MPK_ERR_INVALID_ARG; }
+  for (size_t i = 0; i < s->graphs.size(); ++i)
+    if (n_active != 0 && s->batch[i] >= n_active) return mpk_decode_step(s->graphs[i], token_ids, positions, logits_out, stream);
+  set_error("n_active %u is outside 1..%u", n_active, s->batch.empty() ? 0u : s->batch.back());
+  return MPK_ERR_INVALID_ARG;
 }
 
 extern "C" const char* mpk_last_error(void) { return mpk::last_error(); }

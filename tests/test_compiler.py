@@ -292,6 +292,17 @@ def test_error_paths():
         M.compile_dag(3, [(0, 5)])
 
 
+def test_kv_batch_option_is_validated_and_leaves_the_graph_alone():
+    """kv_batch only changes where a layer's cache starts: same task graph; below batch = error."""
+    s = G.small_variant("C1", batch=2)
+    a = host_graph(s, fusion=31).export()
+    b = host_graph(s, fusion=31, kv_batch=8).export()
+    assert np.array_equal(a.tasks, b.tasks) and np.array_equal(a.events, b.events)
+    with pytest.raises(M.MpkError) as e:
+        host_graph(s, kv_batch=1)
+    assert e.value.status == M.binding.MPK_ERR_INVALID_ARG
+
+
 def test_moe_error_paths_and_graph_shape():
     moe = dict(ffn=0, n_experts=8, top_k=2, expert_ffn=64)
     for bad, status in ((dict(top_k=9), M.binding.MPK_ERR_INVALID_ARG),

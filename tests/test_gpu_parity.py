@@ -6,6 +6,7 @@ import torch
 import paper_2512_22219_amd as M
 from oracle import decoder as D
 from synth import gen as G
+from synth.device import DeviceModel
 from tests.gpu_util import GpuDecoder, rel_err
 
 pytestmark = pytest.mark.gpu
@@ -446,3 +447,76 @@ def test_qk_norm_models_match_oracle(variant, opts):
     assert np.abs(plain.step(tok, pos) - ref.step(tok, pos)).max() > 1e-2
     plain.close()
     gpu.close()
+
+
+@pytest.mark.parametrize("variant,opts", [
+    (dict(batch=6, max_seq=192), dict(fusion=31, transitive_reduction=1)),
+    (dict(batch=8, max_seq=192, ffn=0, n_experts=8, top_k=2, expert_ffn=64), dict(fusion=31, transitive_reduction=1, n_workers=24)),
+    (dict(batch=5, max_seq=192), dict(fusion=0, launch_mode=1)),
+])
+def test_graph_set_runs_the_smallest_graph_that_holds_the_active_sequences(variant, opts):
+    """One graph per power-of-two batch size over ONE KV cache laid out for the maximum batch:
+    n_active sequences run on the smallest graph that holds them, and their logits must be what
+    the oracle computes for those sequences alone (sequences are independent; the synthetic cache
+    of sequence b does not depend on the batch size).  The number of active sequences changes
+    from step to step, so rows appended by one graph are read by another."""
+    s = G.small_variant("C1", n_layers=2, **variant)
+    B = s.batch
+    model = DeviceModel(s, 5)
+    gs = M.compile_set(s, model.weight_ptrs(), model.kv_ptrs(), **opts)
+    want_sizes = [b for b in (1, 2, 4, 8, 16) if b < B] + [B]
+    assert len(gs) == len(want_sizes)
+    assert all(gs.graph(i).stats()["n_workers"] > 0 for i in range(len(gs)))
+    assert gs.batch_for(0) == 0 and gs.batch_for(B + 1) == 0 and gs.batch_for(B) == B and gs.batch_for(3) == 4
+    # the oracle keeps ONE model of the maximum batch; a step on the first n sequences is a step
+    # of a batch-n oracle that shares its cache rows: run the full batch and compare n rows
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 5), "f32")
+    tok = G.tokens(5, s)
+    pos = np.array([(31 * b + 7) % 120 for b in range(B)], np.int32)
+    dev = model.device
+    d_tok = torch.zeros(B, dtype=torch.int32, device=dev)
+    d_pos = torch.zeros(B, dtype=torch.int32, device=dev)
+    logits = torch.empty((B, s.vocab), dtype=torch.float32, device=dev)
+    st = torch.cuda.current_stream().cuda_stream
+    for step, n in enumerate([B, 1, 3, 2, B - 1, B]):
+        b_run = gs.batch_for(n)
+        # padding slots n .. b_run-1 are computed too (and append their rows): the reference does
+        # the same for exactly those slots, so both caches stay identical
+        want = ref.step(tok, pos)
+        d_tok.copy_(torch.as_tensor(tok)); d_pos.copy_(torch.as_tensor(pos))
+        logits.fill_(float("nan"))
+        gs.decode_step(n, d_tok.data_ptr(), d_pos.data_ptr(), logits.data_ptr(), st)
+        torch.cuda.synchronize()
+        for i in range(len(gs)):
+            gs.graph(i).status()
+        got = logits.cpu().numpy().reshape(-1)[: b_run * s.vocab].reshape(b_run, s.vocab)
+        assert np.isfinite(got[:n]).all(), (step, n)
+        ambiguous = False
+        if s.n_experts:   # top-k is discontinuous: a decision may differ where the margin is below fp32 resolution
+            ex, _ = gs.graph(want_sizes.index(b_run)).moe_selection()
+            ex = ex.reshape(s.n_layers, b_run, s.top_k)
+            for l in range(s.n_layers):
+                for b in range(b_run):
+                    if ex[l, b].tolist() != ref.last_moe_sel[l, b].tolist():
+                        r = np.sort(ref.last_moe_logits[l, b].astype(np.float64))[::-1]
+                        assert r[s.top_k - 1] - r[s.top_k] < 1e-5, (step, l, b)
+                        ambiguous = True
+        if not ambiguous:
+            if step == 0:
+                assert rel_err(got[:n], want[:n]) < TOL, (step, n)
+            # later steps read K/V rows each side appended itself: a value on a bf16 rounding
+            # boundary may have gone the other way, so the bound is on the largest logit
+            assert np.abs(got[:n] - want[:n]).max() / np.abs(want[:n]).max() < 2e-3, (step, n)
+            assert got[:n].argmax(-1).tolist() == want[:n].argmax(-1).tolist(), (step, n)
+        # advance only the slots that ran (active and padding); the others keep token and position
+        nxt = want.argmax(-1).astype(np.int32)
+        ran = np.arange(B) < b_run
+        # the reference appended rows for ALL slots; slots that did not run on the GPU must not
+        # move on, so their next reference step rewrites the same row with the same token
+        tok = np.where(ran, nxt, tok).astype(np.int32)
+        pos = np.where(ran, pos + 1, pos).astype(np.int32)
+    with pytest.raises(M.MpkError):
+        gs.decode_step(0, d_tok.data_ptr(), d_pos.data_ptr(), logits.data_ptr(), st)
+    with pytest.raises(M.MpkError):
+        gs.decode_step(B + 1, d_tok.data_ptr(), d_pos.data_ptr(), logits.data_ptr(), st)
+    gs.destroy()
