@@ -1533,6 +1533,10 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
   // P.V, all in registers; sreg[r][j] belongs to position i_first + r * stride, head jb + j
   constexpr int HB = GRP < 4 ? GRP : 4;
   const float inv_sqrt_d = 1.0f / sqrtf((float)d);
+  // The body is bound by vector instructions, not by memory (two wavefronts per SIMD, about a
+  // thousand instructions each for a full chunk): rounds the chunk does not reach are skipped.
+  // The count is the same in every lane (it comes from positions[b]); say so to the compiler.
+  const uint32_t n_rounds_u = __builtin_amdgcn_readfirstlane(n_rounds);
   float* mxch = wpart + NW * grp * (d + 2) + 16;   // [NW][HB] maxima exchange
   float m_all[GRP];
 #pragma unroll 1
@@ -1551,6 +1555,7 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
     for (int j = 0; j < HB; ++j) mloc[j] = -INFINITY;
 #pragma unroll
     for (int r = 0; r < kAttnRounds; ++r) {
+      if ((uint32_t)r >= n_rounds_u) continue;   // (uniform) rounds past the chunk: nothing to do
       const bool valid = i_first + r * stride < n;
       const u32x4 kv = kreg[r];
       const float k8[8] = {bf16_lo(kv.x), bf16_hi(kv.x), bf16_lo(kv.y), bf16_hi(kv.y),
@@ -1592,6 +1597,7 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
     }
 #pragma unroll
     for (int r = 0; r < kAttnRounds; ++r) {
+      if ((uint32_t)r >= n_rounds_u) continue;
       const u32x4 vv = vreg[r];
       const float v8[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
                            bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
@@ -1655,10 +1661,10 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
       for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) {
         uint32_t j = i / d, dim = i % d;
         float M = -INFINITY, L = 0.f, acc_o = 0.f;
-        for (uint32_t c0 = 0; c0 < C; c0 += 4) {   // 12 coherent loads in flight
-          float mm[4], ll[4], oo[4];
+        for (uint32_t c0 = 0; c0 < C; c0 += 8) {   // 24 coherent loads in flight: one round trip for 8 chunks
+          float mm[8], ll[8], oo[8];
 #pragma unroll
-          for (int k = 0; k < 4; ++k) {
+          for (int k = 0; k < 8; ++k) {
             if (c0 + k < C) {
               const float* pp = part + ((size_t)(c0 + k) * grp + j) * (d + 2);
               mm[k] = ld_act(pp + d);
@@ -1669,7 +1675,7 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
             }
           }
 #pragma unroll
-          for (int k = 0; k < 4; ++k) {
+          for (int k = 0; k < 8; ++k) {
             float Mn = fmaxf(M, mm[k]);
             if (Mn == -INFINITY) continue;   // empty chunks only so far
             float sc_old = expf(M - Mn), sc_new = expf(mm[k] - Mn);
@@ -1924,10 +1930,10 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
       for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) {
         uint32_t j = i / d, dim = i % d;
         float M = -INFINITY, L = 0.f, acc_o = 0.f;
-        for (uint32_t c0 = 0; c0 < C; c0 += 4) {   // 12 coherent loads in flight
-          float mm[4], ll[4], oo[4];
+        for (uint32_t c0 = 0; c0 < C; c0 += 8) {   // 24 coherent loads in flight: one round trip for 8 chunks
+          float mm[8], ll[8], oo[8];
 #pragma unroll
-          for (int k = 0; k < 4; ++k) {
+          for (int k = 0; k < 8; ++k) {
             if (c0 + k < C) {
               const float* pp = part + ((size_t)(c0 + k) * grp + j) * (d + 2);
               mm[k] = ld_act(pp + d);
@@ -1938,7 +1944,7 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
             }
           }
 #pragma unroll
-          for (int k = 0; k < 4; ++k) {
+          for (int k = 0; k < 8; ++k) {
             float Mn = fmaxf(M, mm[k]);
             if (Mn == -INFINITY) continue;   // empty chunks only so far
             float sc_old = expf(M - Mn), sc_new = expf(mm[k] - Mn);
