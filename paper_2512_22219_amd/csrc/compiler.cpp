@@ -976,7 +976,7 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
       f = (size_t)c.batch * c.top_k * 2 + (size_t)c.n_experts * (3 + 16) + 64;   // pairs | per-expert counts, offsets, masks, pair table
     else if (op.kind == MPK_OP_ATTN_PARTIAL)
       f = (size_t)grp * c.head_dim                                        // q
-          + (size_t)(kThreads / 64) * grp * (c.head_dim + 2) + 16 + 64;   // per-wave partials
+          + (size_t)(kThreads * 8 / c.head_dim) * grp * (c.head_dim + 4) + 16 + 64;   // partials per position slot (register-resident body; the other keeps one per wavefront)
     need = std::max(need, f);
   }
   size_t bytes = (need + kLdsReduceFloats + 16) * sizeof(float);   // + 64 bytes of control words

@@ -1423,12 +1423,13 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
                                                   int32_t wait_ev, uint32_t* s_flag) {
   constexpr uint32_t d = D, grp = GRP, LPP = D / 8, PPW = 64 / LPP, NW = kThreads / 64;
   constexpr uint32_t stride = NW * PPW, per = grp * (d + 2);
+  constexpr uint32_t WS = d + 4;   // row of one partial in LDS: output, max, sum; 16-byte aligned rows
   const uint32_t nq = a.g->n_q, nkv = a.g->n_kv, C = t.p1;
   const uint32_t b = t.b0, u = t.c0 / per, g = u / C, c = u % C;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   float* qs = lds;                       // [grp][d]
-  float* wpart = qs + grp * d;           // [NW][grp][d + 2]: partial output, max, sum per wavefront
-  uint32_t* flag = (uint32_t*)(wpart + NW * grp * (d + 2));   // then [16..) the maxima exchange
+  float* wpart = qs + grp * d;           // [NW * PPW][grp][WS]: partial output and sum per position slot
+  uint32_t* flag = (uint32_t*)(wpart + stride * grp * WS);    // then [16..) the maxima exchange
   float* outp = t.out + (size_t)b * t.ld_out + t.c0;
   const int32_t pos = a.positions[b] + (int32_t)a.step;    // written by the host before the launch
   const bool bad_pos = pos < 0 || (uint32_t)pos >= a.g->max_seq;
@@ -1537,7 +1538,9 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
   // thousand instructions each for a full chunk): rounds the chunk does not reach are skipped.
   // The count is the same in every lane (it comes from positions[b]); say so to the compiler.
   const uint32_t n_rounds_u = __builtin_amdgcn_readfirstlane(n_rounds);
-  float* mxch = wpart + NW * grp * (d + 2) + 16;   // [NW][HB] maxima exchange
+  float* mxch = wpart + stride * grp * WS + 16;   // [NW][HB] maxima exchange
+  // scores are kept times log2(e): the probabilities are then one v_exp_f32 each
+  const float score_scale = inv_sqrt_d * 1.44269504088896341f;
   float m_all[GRP];
 #pragma unroll 1
   for (int jb = 0; jb < GRP; jb += HB) {
@@ -1565,7 +1568,7 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
         float sv = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) sv = fmaf(k8[e], q[j][e], sv);
-        sv = group_sum<LPP>(sv) * inv_sqrt_d;
+        sv = group_sum<LPP>(sv) * score_scale;
         sreg[r][j] = valid ? sv : -INFINITY;
         mloc[j] = fmaxf(mloc[j], sreg[r][j]);
       }
@@ -1585,7 +1588,7 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
 #pragma unroll
       for (uint32_t w = 1; w < NW; ++w) v = fmaxf(v, mxch[w * HB + j]);
       m[j] = v;
-      m_all[jb + j] = v;
+      m_all[jb + j] = v * 0.693147180559945309f;   // the partial's maximum is stored in natural units
     }
     // ---- probabilities and P.V
     float acc[HB][8], lsum[HB];
@@ -1603,26 +1606,22 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
                            bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
 #pragma unroll
       for (int j = 0; j < HB; ++j) {
-        const float p = (sreg[r][j] == -INFINITY) ? 0.f : expf(sreg[r][j] - m[j]);
+        const float p = (sreg[r][j] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sreg[r][j] - m[j]);
         lsum[j] += p;
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p, v8[e], acc[j][e]);
       }
     }
-    // reduce over the position slots of the wavefront; wavefront partials go to LDS
+    // every position slot's partial goes to LDS as it is (two 16-byte stores per head); the
+    // slots are added up below, by the threads that write the result.  (Adding them with lane
+    // shuffles first cost 4 instructions per value here, where instructions are what is scarce.)
 #pragma unroll
     for (int j = 0; j < HB; ++j) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float v = acc[j][e];
-#pragma unroll
-        for (uint32_t off = LPP; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
-        if (slot == 0) wpart[((size_t)wave * grp + jb + j) * (d + 2) + sub * 8 + e] = v;
-      }
-      float lv = lsum[j];   // every lane of a position group holds the same p: count each once
-#pragma unroll
-      for (uint32_t off = LPP; off < 64; off <<= 1) lv += __shfl_xor(lv, off, 64);
-      if (lane == 0) wpart[((size_t)wave * grp + jb + j) * (d + 2) + d + 1] = lv;
+      float4* wp = (float4*)(wpart + ((size_t)(wave * PPW + slot) * grp + jb + j) * WS + sub * 8);
+      wp[0] = make_float4(acc[j][0], acc[j][1], acc[j][2], acc[j][3]);
+      wp[1] = make_float4(acc[j][4], acc[j][5], acc[j][6], acc[j][7]);
+      // every lane of a position group holds the same p: one of them stores the sum
+      if (sub == 0) wpart[((size_t)(wave * PPW + slot) * grp + jb + j) * WS + d + 1] = lsum[j];
     }
     __syncthreads();   // also protects mxch before the next block
   }
@@ -1637,7 +1636,7 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
     } else {
       sv = 0.f;
 #pragma unroll
-      for (uint32_t w = 0; w < NW; ++w) sv += wpart[((size_t)w * grp + j) * (d + 2) + dim];
+      for (uint32_t w = 0; w < stride; ++w) sv += wpart[((size_t)w * grp + j) * WS + dim];
     }
     st_act(outp + i, sv);
   }
