@@ -1803,8 +1803,10 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
   }
   __syncthreads();
   trace_mark(a, t, 2);
-  // ---- running softmax per lane group and query head
-  const float inv_sqrt_d = 1.0f / sqrtf((float)d);
+  // ---- running softmax per lane group and query head.  Scores and maxima are kept times
+  // log2(e), folded into the query, so that every probability and rescale is one v_exp_f32 (the
+  // body is bound by vector instructions at 4 and 8 query heads per KV head).
+  const float inv_sqrt_d = 1.44269504088896341f / sqrtf((float)d);
   float q[GRP][8], m[GRP], l[GRP], acc[GRP][8];
 #pragma unroll
   for (int j = 0; j < GRP; ++j) {
@@ -1851,13 +1853,13 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
         sv = group_sum<LPP>(sv);
         if (valid) {
           if (sv > m[j]) {   // a new maximum (rare after the first positions): rescale the running state
-            const float sc = expf(m[j] - sv);   // exp(-inf) = 0 on the first position
+            const float sc = __builtin_amdgcn_exp2f(m[j] - sv);   // 2^(-inf) = 0 on the first position
             l[j] *= sc;
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[j][e] *= sc;
             m[j] = sv;
           }
-          const float p = expf(sv - m[j]);
+          const float p = __builtin_amdgcn_exp2f(sv - m[j]);
           l[j] += p;
 #pragma unroll
           for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p, v8[e], acc[j][e]);
@@ -1872,7 +1874,7 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
     for (uint32_t off = LPP; off < 64; off <<= 1) {
       const float mo = __shfl_xor(m[j], off, 64), lo2 = __shfl_xor(l[j], off, 64);
       const float mn = fmaxf(m[j], mo);
-      const float s0 = (m[j] == -INFINITY) ? 0.f : expf(m[j] - mn), s1 = (mo == -INFINITY) ? 0.f : expf(mo - mn);
+      const float s0 = (m[j] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m[j] - mn), s1 = (mo == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mo - mn);
       l[j] = l[j] * s0 + lo2 * s1;
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[j][e] = acc[j][e] * s0 + __shfl_xor(acc[j][e], off, 64) * s1;
@@ -1883,7 +1885,7 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
 #pragma unroll
       for (int e = 0; e < 8; ++e) wp[sub * 8 + e] = acc[j][e];
       if (sub == 0) {
-        wp[d] = m[j];
+        wp[d] = m[j] * 0.693147180559945309f;   // back to natural units for the merges
         wp[d + 1] = l[j];
       }
     }
