@@ -1820,19 +1820,26 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
     for (int e = 0; e < 8; ++e) acc[j][e] = 0.f;
   }
   const uint32_t i_new = (c == C - 1) ? n - 1 : 0xFFFFFFFFu;   // the row appended this step, if in this chunk
-  for (uint32_t r0 = 0; r0 < n_rounds; r0 += kAttnPre) {
-    if (r0 > 0) {   // request the next batch of rounds
+  // A batch of rounds lives in registers; its first half is requested again (for the next batch)
+  // as soon as it has been used, so that those loads travel while the second half is multiplied.
+  constexpr int kHalf = kAttnPre / 2;
+  auto request_next = [&](uint32_t r0, auto first_half) {
+    constexpr int lo = decltype(first_half)::value ? 0 : kHalf, hi = decltype(first_half)::value ? kHalf : kAttnPre;
+    if (r0 + kAttnPre < n_rounds) {
 #pragma unroll
-      for (int r = 0; r < kAttnPre; ++r) {
-        const uint32_t i = i_first + (r0 + r) * stride;
+      for (int r = lo; r < hi; ++r) {
+        const uint32_t i = i_first + (r0 + kAttnPre + r) * stride;
         if (i < n && i != i_new) {
           kreg[r] = ld_stream16(Kb + (size_t)i * d + sub * 8);
           vreg[r] = ld_stream16(Vb + (size_t)i * d + sub * 8);
         }
       }
     }
+  };
+  for (uint32_t r0 = 0; r0 < n_rounds; r0 += kAttnPre) {
 #pragma unroll
     for (int r = 0; r < kAttnPre; ++r) {
+      if (r == kHalf) request_next(r0, std::true_type{});
       const uint32_t i = i_first + (r0 + r) * stride;
       if (i == i_new) {
         // written after the pre-load, by this or another workgroup: coherent loads
@@ -1866,6 +1873,7 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
         }
       }
     }
+    request_next(r0, std::false_type{});
   }
   // ---- combine the lane groups of the wavefront, then the wavefronts
 #pragma unroll
