@@ -315,7 +315,6 @@ __device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_
 // compiler moves parts of them to scratch memory, and a scratch access in the middle of a request
 // waits for every load issued before it.
 constexpr int kHalfRows = 2, kRingStages = 8;
-constexpr int kRingRows = 2 * kHalfRows;            // weight rows in flight per wavefront
 constexpr uint32_t kSegLen = 512u * kRingStages;   // input elements per half-block row
 struct HalfRing {
   u32x4 s[kHalfRows][kRingStages];
@@ -690,12 +689,20 @@ __device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const St
   const uint32_t gateup = (t.flags & TF_GATEUP) ? 1u : 0u;
   const uint32_t R = ncols << gateup;            // weight rows of the task ("ring rows")
   const uint32_t nrt = (R + 15u) / 16u;          // 16-row tiles
-  const uint32_t Kt = mfma_ktile(nb), xstride = Kt + 8u;
+  // An input of at most two staging tiles is staged whole, as ONE tile in the space of the two
+  // buffers: one barrier instead of two, and the K slice of a wavefront is twice as long -- for a
+  // task of one 16-row tile (eight K slices) exactly the 16 fragments requested before the event
+  // wait, where two short tiles used half of that round each and paid a second round trip.
+  const uint32_t Kt1 = mfma_ktile(nb);                      // what one staging pass covers
+  // (Batch <= 8 only for now: at batch 16 the different summation order moves one logit near the
+  // floor of the 48-layer mixture-of-experts shape just past that test's element-wise bound.)
+  const bool whole = nb <= 8u && K > Kt1 && K <= 2u * Kt1;
+  const uint32_t Kt = whole ? 2u * Kt1 : Kt1, xstride = Kt + 8u, nbuf = whole ? 1u : 2u;
   const uint32_t xplane = nb * xstride;                     // one plane of one buffer, in bf16
-  uint16_t* xh = (uint16_t*)lds;                            // [2 buffers][nb][xstride]
-  uint16_t* xl = xh + 2 * (size_t)xplane;
+  uint16_t* xh = (uint16_t*)lds;                            // [nbuf buffers][nb][xstride]
+  uint16_t* xl = xh + nbuf * (size_t)xplane;
   float* part = lds;                                        // [8][4][256], reuses the input buffers at the end
-  float* res_lds = (float*)(xl + 2 * (size_t)xplane);       // [rows_max][16]
+  float* res_lds = (float*)(xl + nbuf * (size_t)xplane);    // [rows_max][16]
   float* ssq = res_lds + (size_t)a.g->lin_res_rows_max * 16;   // [8][16]
   // which tiles and which K slice this wavefront works on
   uint32_t nrt2 = 1;
@@ -754,30 +761,34 @@ __device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const St
   // requested (coherent loads into registers) while the previous tile is being multiplied, and
   // converted into the other LDS buffer afterwards.  Sums of squares are kept per slot.
   static_assert(kThreads == 512, "the slot -> (row, pair) mapping assumes 512 threads");
-  const uint32_t sh = Kt == 2048u ? 1u : 0u;
+  const uint32_t sh = Kt1 == 2048u ? 1u : 0u;
   float sqq[16];
 #pragma unroll
   for (int q = 0; q < 16; ++q) sqq[q] = 0.f;
   const uint32_t ntile = (K + Kt - 1u) / Kt;
   float2 sv[16];
+  // staging pass `tile`: inputs [tile * Kt1, + Kt1) into buffer tile & 1 -- or, staged whole,
+  // into columns tile * Kt1 .. of the one buffer
   auto stage_issue = [&](uint32_t tile) {
-    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
+    float2 (&dst)[16] = sv;
+    const uint32_t k0 = tile * Kt1, klen = min(Kt1, K - k0);
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
       const uint32_t b = (uint32_t)q >> sh, i = (((uint32_t)q & sh) << 9) + threadIdx.x;
-      sv[q] = make_float2(0.f, 0.f);
-      if (b < nb && 2 * i < klen) sv[q] = ld_act2(t.in + (size_t)(t.b0 + b) * t.ld_in + k0 + 2 * i);
+      dst[q] = make_float2(0.f, 0.f);
+      if (b < nb && 2 * i < klen) dst[q] = ld_act2(t.in + (size_t)(t.b0 + b) * t.ld_in + k0 + 2 * i);
     }
   };
   auto stage_write = [&](uint32_t tile) {
-    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
-    uint16_t* dh = xh + (size_t)(tile & 1u) * xplane;
-    uint16_t* dl = xl + (size_t)(tile & 1u) * xplane;
+    const float2 (&src)[16] = sv;
+    const uint32_t k0 = tile * Kt1, klen = min(Kt1, K - k0);
+    uint16_t* dh = whole ? xh + k0 : xh + (size_t)(tile & 1u) * xplane;
+    uint16_t* dl = whole ? xl + k0 : xl + (size_t)(tile & 1u) * xplane;
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
       const uint32_t b = (uint32_t)q >> sh, i = (((uint32_t)q & sh) << 9) + threadIdx.x;
       if (b < nb) {
-        float2 w2 = sv[q];
+        float2 w2 = src[q];
         if (pro_norm && 2 * i < klen) {
           sqq[q] = fmaf(w2.x, w2.x, fmaf(w2.y, w2.y, sqq[q]));
           const uint32_t g2 = *as_global((const uint32_t*)(gain + k0 + 2 * i));
@@ -793,6 +804,10 @@ __device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const St
   };
   stage_issue(0);
   stage_write(0);
+  if (whole) {   // (both passes in one round trip, with twice the registers: no faster -- the
+    stage_issue(1);   // coherent reads of a [8][4096] input by 256 workers are bound by bandwidth)
+    stage_write(1);
+  }
   lds_barrier();
   trace_mark(a, t, 2);
   // One round: the fragments in wfrag times both planes of the input, steps kk + 32 q < s_hi.
