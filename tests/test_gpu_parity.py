@@ -96,6 +96,36 @@ def test_small_batch_and_ragged_positions(opts):
     gpu.close()
 
 
+@pytest.mark.parametrize("variant,opts", [
+    # ffn 4360: the down projection's input is one full 4096-element segment plus a short one
+    (dict(hidden=1000, ffn=4360, batch=1), dict(fusion=31, transitive_reduction=1, n_workers=13)),
+    (dict(hidden=1000, ffn=4360, batch=3), dict(fusion=31, transitive_reduction=1, n_workers=13)),
+    # hidden 8200: every projection from the residual stream walks three segments, the last 8 long
+    (dict(hidden=8200, ffn=696, batch=2, vocab=520), dict(fusion=31, transitive_reduction=1, n_workers=29)),
+    (dict(hidden=4104, ffn=696, batch=4, vocab=520), dict(fusion=0, n_workers=29, launch_mode=1)),
+    # one weight row per wavefront and fewer rows than wavefronts (vocab 40 over 7 workers)
+    (dict(hidden=264, ffn=72, batch=1, vocab=40), dict(fusion=31, transitive_reduction=1, n_workers=7)),
+])
+def test_linear_stream_odd_shapes(variant, opts):
+    """The two-buffer weight stream of the batch <= 4 linear body on shapes that exercise its
+    corners: odd numbers of rows per wavefront (a pair with one row), inputs of several segments
+    with a short last one, tasks with fewer rows than wavefronts, more half blocks than buffers."""
+    s = G.small_variant("C1", n_layers=2, **variant)
+    rng = np.random.default_rng(11)
+    tok = rng.integers(0, s.vocab, s.batch).astype(np.int32)
+    pos = rng.integers(5, 150, s.batch).astype(np.int32)
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 2), "f32")
+    gpu = GpuDecoder(s, 2, **opts)
+    for step in range(2):
+        want = ref.step(tok, pos)
+        got = gpu.step(tok, pos)
+        assert np.isfinite(got).all()
+        assert rel_err(got, want) < TOL, step
+        assert np.abs(got - want).max() / np.abs(want).max() < 1e-4, step
+        tok, pos = want.argmax(-1).astype(np.int32), pos + 1
+    gpu.close()
+
+
 @pytest.mark.parametrize("batch,opts", [
     (8, dict(fusion=31, transitive_reduction=1)),
     (8, dict(fusion=0)),
