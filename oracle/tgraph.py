@@ -82,10 +82,10 @@ def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: 
     for l in range(s.n_layers):
         p = f"L{l}."
         if fusion & F_NORM:
-            ops.append(OpSpec(p + "qkv", K_LINEAR, l, p + "qkv", B, QKV, 1, [x], {"K": H}))
+            ops.append(OpSpec(p + "qkv", K_LINEAR, l, p + "qkv", B, QKV, 1, [x], {"K": H, "head": d}))
         else:
             ops.append(OpSpec(p + "attn_norm", K_RMSNORM, l, p + "xn", B, H, H, [x]))
-            ops.append(OpSpec(p + "qkv", K_LINEAR, l, p + "qkv", B, QKV, 1, [p + "xn"], {"K": H}))
+            ops.append(OpSpec(p + "qkv", K_LINEAR, l, p + "qkv", B, QKV, 1, [p + "xn"], {"K": H, "head": d}))
         if fusion & F_ROPE:
             qsrc = p + "qkv"
         else:
@@ -153,11 +153,26 @@ def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: 
     return ops
 
 
+def col_bounds(op: OpSpec, tc: int):
+    """Column boundaries (tc + 1 of them) of an operator's tiles.  One even split -- except for
+    the QKV projection (params["head"]), whose tiles never straddle a head: the columns are cut
+    into heads first and every head evenly into the same number of tiles (DESIGN: decomposition)."""
+    nu = op.cols // op.unit
+    head = op.meta.get("head")
+    if head and nu % head == 0 and tc % (nu // head) == 0:
+        per = tc // (nu // head)
+        b = []
+        for h in range(nu // head):
+            b += [h * head + x for x in split_even(head, per)[:-1]]
+        return [u * op.unit for u in b + [nu]]
+    return [u * op.unit for u in split_even(nu, tc)]
+
+
 def owner_map(op: OpSpec, tb: int, tc: int) -> np.ndarray:
     """owner[b, col] = tile index (ib * tc + ic) of the task that writes that output element."""
     assert op.cols % op.unit == 0
     rb = split_even(op.rows, tb)
-    cb = [u * op.unit for u in split_even(op.cols // op.unit, tc)]
+    cb = col_bounds(op, tc)
     own = np.empty((op.rows, op.cols), np.int32)
     for ib in range(tb):
         for ic in range(tc):
@@ -168,7 +183,7 @@ def owner_map(op: OpSpec, tb: int, tc: int) -> np.ndarray:
 def tile_bounds(op: OpSpec, tb: int, tc: int, tile: int):
     ib, ic = divmod(tile, tc)
     rb = split_even(op.rows, tb)
-    cb = [u * op.unit for u in split_even(op.cols // op.unit, tc)]
+    cb = col_bounds(op, tc)
     return rb[ib], rb[ib + 1], cb[ic], cb[ic + 1]
 
 

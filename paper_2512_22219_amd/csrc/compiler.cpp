@@ -47,6 +47,26 @@ static inline uint32_t tile_of(uint32_t n, uint32_t k, uint32_t u) {
   return r + (u - big) / q;   // q > 0 here because k <= n is enforced at decomposition
 }
 
+// Column tiles of an operator, in units.  Usually one even split; an operator with seg_tiles
+// (the QKV projection) is split twice: into segments of align_unit units (heads), and every
+// segment evenly into seg_tiles tiles, so that no tile straddles a head whatever its size.
+static inline uint32_t col_tile_begin(const HostOp& op, uint32_t ic) {
+  const uint32_t nu = op.cols / op.unit;
+  if (!op.seg_tiles) return tile_begin(nu, op.tc, ic);
+  if (ic >= op.tc) return nu;
+  return ic / op.seg_tiles * op.align_unit + tile_begin(op.align_unit, op.seg_tiles, ic % op.seg_tiles);
+}
+static inline uint32_t col_tile_of(const HostOp& op, uint32_t u) {
+  const uint32_t nu = op.cols / op.unit;
+  if (!op.seg_tiles) return tile_of(nu, op.tc, u);
+  return u / op.align_unit * op.seg_tiles + tile_of(op.align_unit, op.seg_tiles, u % op.align_unit);
+}
+static inline uint32_t col_tile_max_units(const HostOp& op) {
+  const uint32_t nu = op.cols / op.unit;
+  if (!op.seg_tiles) return (nu + op.tc - 1) / op.tc;
+  return (op.align_unit + op.seg_tiles - 1) / op.seg_tiles;
+}
+
 struct Rect {
   int tensor;
   uint32_t b0, b1, c0, c1;
@@ -635,8 +655,9 @@ static void tile_bounds(const HostOp& op, uint32_t tile, uint32_t* b0, uint32_t*
   uint32_t ib = tile / op.tc, ic = tile % op.tc, nu = op.cols / op.unit;
   *b0 = tile_begin(op.rows, op.tb, ib);
   *b1 = tile_begin(op.rows, op.tb, ib + 1);
-  *c0 = tile_begin(nu, op.tc, ic) * op.unit;
-  *c1 = tile_begin(nu, op.tc, ic + 1) * op.unit;
+  (void)nu;
+  *c0 = col_tile_begin(op, ic) * op.unit;
+  *c1 = col_tile_begin(op, ic + 1) * op.unit;
 }
 
 static void choose_partitions(const mpk_model_config& c, const mpk_compile_options& o,
@@ -663,14 +684,22 @@ static void choose_partitions(const mpk_model_config& c, const mpk_compile_optio
         while (c.batch > 4 && !given && op.tc < cap && (nu + op.tc - 1) / op.tc * per_row > 512) op.tc = std::min(cap, op.tc + W);
         if (op.align_unit && nu % op.align_unit == 0) {
           // QKV projection: tiles that never straddle a head keep every tile in exactly one
-          // attention group's producer set (no fork, hence no dummy tasks).  Pick the smallest
-          // rows-per-tile that divides head_dim and needs no more than `want` tiles.
-          for (uint32_t rows = 8; rows <= op.align_unit; rows += 8) {
-            if (op.align_unit % rows == 0 && nu / rows <= std::max(want, nu / op.align_unit)) {
-              op.tc = nu / rows;
-              break;
-            }
-          }
+          // attention group's producer set (no fork, hence no dummy tasks).  Every head gets the
+          // same number of tiles, as many as `want` allows (at least 8 rows each); a head need
+          // not divide evenly (tiles of 25 and 26 rows on the 8B shape: 240 tasks, where tiles
+          // that divide head_dim gave 192).
+          const uint32_t heads = nu / op.align_unit;
+          op.seg_tiles = std::max(1u, std::min(want / heads, op.align_unit / 8));
+          // A projection small enough to be pre-loaded whole (256 KB of weights per worker are
+          // requested before the event) is bound by latency, not bandwidth: then it pays to leave
+          // workers without a QKV task for the attention tasks that follow in the round-robin
+          // order -- they request their cache rows while the projection still runs (measured on
+          // the 8B shape: 192 + 64 tasks 3.47 ms, 240 + 64 tasks 3.62 ms per step).
+          const uint64_t bytes_per_worker = (uint64_t)nu * op.K * 2u / std::max(1u, W);
+          const uint32_t attn_tasks = c.batch * c.n_kv_heads * std::max(1u, o.attn_chunks);
+          if (bytes_per_worker <= 256u * 1024u && attn_tasks < want && (want - attn_tasks) / heads >= 1)
+            op.seg_tiles = std::min(op.seg_tiles, (want - attn_tasks) / heads);
+          op.tc = heads * op.seg_tiles;
         }
         break;
       }
@@ -831,7 +860,8 @@ static void dependency_analysis(const mpk_model_config& c, HostGraph& g, PassInp
         if (r.b0 >= rb1 || r.c0 >= c1) continue;
         uint32_t nu = p.cols / p.unit;
         uint32_t ib0 = tile_of(p.rows, p.tb, r.b0), ib1 = tile_of(p.rows, p.tb, rb1 - 1);
-        uint32_t ic0 = tile_of(nu, p.tc, r.c0 / p.unit), ic1 = tile_of(nu, p.tc, (c1 - 1) / p.unit);
+        (void)nu;
+        uint32_t ic0 = col_tile_of(p, r.c0 / p.unit), ic1 = col_tile_of(p, (c1 - 1) / p.unit);
         for (uint32_t ib = ib0; ib <= ib1; ++ib)
           for (uint32_t ic = ic0; ic <= ic1; ++ic) P.push_back(p.task_base + ib * p.tc + ic);
       }
@@ -946,7 +976,7 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
   uint32_t rows_max = 0;
   for (auto& op : g.ops) {
     if (op.kind != MPK_OP_LINEAR && op.kind != MPK_OP_GATEUP) continue;
-    uint32_t nu = op.cols / op.unit, per = (nu + op.tc - 1) / op.tc * op.unit;
+    uint32_t nu = op.cols / op.unit, per = col_tile_max_units(op) * op.unit;
     rows_max = std::max(rows_max, per * ((op.flags & TF_GATEUP) ? 2u : 1u));
   }
   g.lin_rows_max = rows_max;
@@ -954,7 +984,7 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
   for (auto& op : g.ops) {
     if ((op.kind != MPK_OP_LINEAR && op.kind != MPK_OP_GATEUP) || !(op.flags & TF_EPI_RESID)) continue;
     uint32_t nu = op.cols / op.unit;
-    res_rows = std::max(res_rows, (nu + op.tc - 1) / op.tc * op.unit);
+    res_rows = std::max(res_rows, col_tile_max_units(op) * op.unit);
   }
   g.lin_res_rows_max = res_rows;
   for (auto& op : g.ops) {

@@ -108,7 +108,8 @@ struct HostOp {
   // mixture-of-experts operators: the tensors the body really touches (the dependency analysis
   // sees an expert stage's output as one element per task, see build_ops)
   int data_in = -1, data_in2 = -1, data_out = -1, data_aux = -1;
-  uint32_t align_unit = 0;     // linear: tile rows must divide this (head_dim) when non-zero
+  uint32_t align_unit = 0;     // linear: no tile straddles a multiple of this (head_dim) when non-zero
+  uint32_t seg_tiles = 0;      // ... by a two-level split: segments of align_unit columns, this many tiles each
   // parameters
   uint32_t K;
   uint16_t flags;
