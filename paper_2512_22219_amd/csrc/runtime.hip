@@ -430,6 +430,7 @@ __device__ __forceinline__ void lds_barrier() {
 }
 
 __device__ __forceinline__ void signal_from_wave0(const StepArgs& a, const TaskDesc& t, int32_t e, int lane);
+__device__ __forceinline__ void notify_event(const StepArgs& a, int32_t e);
 __device__ __forceinline__ void poll_event_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane);
 __device__ __forceinline__ void poll_event_or_jit_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane, uint32_t jit_head);
 // Hybrid launch (Section 5.2): a worker may start the linear task at the head of its ahead-of-time
@@ -642,8 +643,23 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
       if (t.flags & TF_EPI_RESID) v = res_lds[bb * ncols + cc] + v;
       st_act(outp + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc, v);
     }
-    if (MEGA && t.trig_event >= 0) signal_from_wave0(a, t, t.trig_event, lane);
-    trace_mark(a, t, 4);
+    if (MEGA) {   // wait for exactly these stores
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      trace_mark(a, t, 7);
+    }
+  }
+  if (MEGA) {
+    // Wavefronts 1..7 issue the next task's requests only now.  Ordering inside ONE wavefront is
+    // not enough: all wavefronts of a CU share its path to memory, and behind 224 freshly issued
+    // 1 KB loads the few output stores of wavefront 0 were acknowledged up to 10 us late (in-kernel
+    // trace), which delays the event for every consumer -- the hop is the critical path, the
+    // pre-load has slack.
+    lds_barrier();
+    if (wave == 0) {
+      if (t.trig_event >= 0 && lane == 0) notify_event(a, t.trig_event);
+      trace_mark(a, t, 4);
+    }
   }
   return kLinDone;
 }
