@@ -305,12 +305,13 @@ __device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_
 //
 // Cross-task pipelining (paper Section 5.3).  Weights never depend on an event, so a task
 // requests its first two half blocks (256 KB per CU) BEFORE it waits for its dependent event:
-// they stream in while the input vector is still being produced elsewhere.  And a task ends for
-// wavefronts 1..7 as soon as the workgroup's results are in LDS: they walk straight into the
-// worker's next task and issue its first requests, while wavefront 0 alone applies the epilogue,
-// writes the outputs with coherent stores, waits for exactly those stores and notifies the
-// triggering event -- with no weight loads queued ahead of them, because memory operations of one
-// wavefront complete in order -- and only then requests its own share and polls the next event.
+// they stream in while the input vector is still being produced elsewhere.  At the end of a task
+// wavefront 0 alone applies the epilogue, writes the outputs with coherent stores and waits for
+// exactly those stores; the other wavefronts wait at a barrier meanwhile, and only then walk into
+// the worker's next task and issue its first requests, while wavefront 0 notifies the triggering
+// event, requests its own share and polls the next event.  (The others must not run ahead: all
+// wavefronts of a CU share its path to memory, and output stores queued behind their requests
+// were acknowledged up to 10 us late.)
 // The buffers are local to a task on purpose: carried around the task loop instead, the
 // compiler moves parts of them to scratch memory, and a scratch access in the middle of a request
 // waits for every load issued before it.
