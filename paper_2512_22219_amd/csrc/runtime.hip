@@ -469,7 +469,7 @@ __device__ __forceinline__ uint32_t linear_wait(const StepArgs& a, int32_t wait_
 //
 // Runs task `t`.  wait_ev >= 0: wait for that event first (persistent kernel).  Returns whether
 // the step is still alive (false: watchdog / abort).
-template <int NB, bool MEGA, class Svc = NoJit>
+template <int NB, bool MEGA, class Svc = NoJit, bool DEEP = false>
 __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
                                                 uint32_t* s_flag, const Svc& svc = Svc{}) {
   const int lane = threadIdx.x & 63;
@@ -498,6 +498,21 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
     lin_request(lin_half(g, rq), h1, lane);
     lin_advance(g, rq);
     asm volatile("; second half block requested" ::: "memory");
+  }
+  // DEEP: a third buffer -- 384 KB per CU requested before the event and a deeper queue while
+  // streaming.  A kernel variant of its own, picked for models whose linear tasks are large (70B
+  // shape: -3 % per step); small tasks are bound by the hops between operators, where a bigger
+  // burst ahead of the event poll and the input loads only delays those (8B shape: +3 %), and the
+  // mere presence of the third buffer in the kernel costs the small shape 2 %.
+  constexpr bool kThird = DEEP;
+  HalfRing h2;
+  if (kThird) {
+    ring_clear(h2);
+    if (lin_valid(g, rq)) {
+      lin_request(lin_half(g, rq), h2, lane);
+      lin_advance(g, rq);
+      asm volatile("; third half block requested" ::: "memory");
+    }
   }
   // ---- dependent event: wavefront 0 polls, the others wait at the barrier
   if (wait_ev >= 0) {
@@ -610,6 +625,20 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
         lin_request(lin_half(g, rq), h1, lane);
         lin_advance(g, rq);
         asm volatile("; second buffer requested again" ::: "memory");
+      }
+      if (kThird) {
+        if (!lin_valid(g, cs)) break;
+        {
+          const LinHalf B = lin_half(g, cs);
+          lin_consume<NB>(B, h2, xs, Kp, lane, acc);
+          finish(B);
+          lin_advance(g, cs);
+        }
+        if (lin_valid(g, rq)) {
+          lin_request(lin_half(g, rq), h2, lane);
+          lin_advance(g, rq);
+          asm volatile("; third buffer requested again" ::: "memory");
+        }
       }
     }
   }
@@ -2093,6 +2122,7 @@ template <int NB, bool MEGA, class Svc = NoJit>
 __device__ __forceinline__ uint32_t run_linear(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
                                            uint32_t* s_flag, const Svc& svc = Svc{}) {
   if (NB == 8) return linear_task_mfma<MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);   // batch class 5..16: matrix cores
+  if (NB == 9) return linear_task<1, MEGA, Svc, true>(t, a, lds, wait_ev, s_flag, svc);   // batch 1, large tasks: three buffers
   if (NB != 0) return linear_task<(NB ? NB : 1), MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
   const uint32_t nb = t.b1 - t.b0;
   if (nb == 1) return linear_task<1, MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
@@ -2620,14 +2650,17 @@ struct KernelVariant {
 #define MPK_VARIANT(D, G, N, M) {D, G, N, M, mpk_mega_kernel<D, G, N, M>, mpk_op_kernel<D, G, N, M>, mpk_loop_kernel<D, G, N, M>}
 static const KernelVariant kVariants[] = {
     MPK_VARIANT(64, 2, 1, false), MPK_VARIANT(128, 4, 1, false), MPK_VARIANT(128, 8, 1, false),
+    MPK_VARIANT(128, 8, 9, false),   // batch 1 with large linear tasks (the 70B shape)
     MPK_VARIANT(128, 4, 8, false), MPK_VARIANT(128, 8, 8, true),
     MPK_VARIANT(0, 0, 0, false), MPK_VARIANT(0, 0, 0, true),   // generic fallbacks, dense and mixture of experts
 };
-static const KernelVariant* pick_variant(uint32_t d, uint32_t grp, uint32_t batch, bool moe) {
-  int nb = batch == 1 ? 1 : (batch > 4 && batch <= 16 ? 8 : -1);
+static const KernelVariant* pick_variant(uint32_t d, uint32_t grp, uint32_t batch, bool moe, bool large_tasks) {
   const int n = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
-  for (int i = 0; i < n; ++i)
-    if (kVariants[i].d == (int)d && kVariants[i].grp == (int)grp && kVariants[i].nb == nb && kVariants[i].moe == moe) return &kVariants[i];
+  for (int pass = (batch == 1 && large_tasks) ? 0 : 1; pass < 2; ++pass) {
+    const int nb = batch == 1 ? (pass == 0 ? 9 : 1) : (batch > 4 && batch <= 16 ? 8 : -1);
+    for (int i = 0; i < n; ++i)
+      if (kVariants[i].d == (int)d && kVariants[i].grp == (int)grp && kVariants[i].nb == nb && kVariants[i].moe == moe) return &kVariants[i];
+  }
   return &kVariants[moe ? n - 1 : n - 2];
 }
 
@@ -2769,7 +2802,9 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
   if (hipGetDevice(&g->device) != hipSuccess) { set_error("hipGetDevice failed"); return fail(MPK_ERR_HIP); }
   HostGraph& h = g->h;
   // residency: dynamic LDS above half of a CU's 160 KB caps occupancy at one workgroup per CU
-  g->kv = pick_variant(cfg->head_dim, cfg->n_q_heads / cfg->n_kv_heads, cfg->batch, cfg->n_experts != 0);
+  // "large": 3 MB or more of weights per worker and layer (8B shape: 1.6 MB, 70B shape: 6.8 MB)
+  const bool large_tasks = h.stats.weight_bytes / std::max(1u, cfg->n_layers) / std::max(1u, o.n_workers) >= (3u << 20);
+  g->kv = pick_variant(cfg->head_dim, cfg->n_q_heads / cfg->n_kv_heads, cfg->batch, cfg->n_experts != 0, large_tasks);
   hipError_t e = reserve_lds((const void*)g->kv->mega, h.lds_bytes);
   if (e == hipSuccess) e = reserve_lds((const void*)g->kv->op, h.lds_bytes);
   if (e == hipSuccess) e = reserve_lds((const void*)g->kv->loop, h.lds_bytes);
