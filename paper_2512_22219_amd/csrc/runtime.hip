@@ -1,2670 +1,33 @@
-// In-kernel runtime and task bodies for gfx950 (paper Section 5), plus the C ABI entry points.
-//
-// One persistent kernel: worker workgroups (one per CU, 512 threads = 8 wavefronts) walk their
-// pre-enqueued (ahead-of-time) task list; before a task they wait until its dependent event's
-// counter has reached epoch * required, after it they publish their stores and add one to the
-// triggering event's counter.  Event counters only ever grow (no reset between steps).
-//
-// Memory ordering (the GPU has 8 XCDs with private, mutually non-coherent L2s).  Whole-cache
-// write-back / invalidate fences cost tens of microseconds per hop with 256 workgroups, so the
-// runtime never issues them.  Instead every datum that crosses workgroups inside the kernel
-// (activations, split-KV partials, the K/V row appended this step, event counters) is written
-// with agent-scope stores and read with agent-scope loads (ld_act / st_act below): such accesses
-// are performed at the device coherence point, not in an XCD-private cache.  Producer side:
-// agent-scope stores, every wavefront waits for its own stores to complete (vmcnt 0), workgroup
-// barrier, one lane adds to the event counter.  Consumer side: one lane polls the counter,
-// workgroup barrier, then agent-scope loads.  Weights, descriptors and cache rows of earlier
-// steps are immutable during a step and use ordinary (non-temporal) loads.
-#include <hip/hip_runtime.h>
+// Host side of the runtime: the C ABI entry points (compile, launch, status, export, graph sets).
+// The kernels live in kernels.h and are instantiated by variants.hip, one specialised set per
+// translation unit; this file only picks a set and launches it.
+#include <algorithm>
 
-#include <cmath>
-#include <cstddef>
-#include <cstdio>
-#include <cstring>
-#include <map>
-#include <mutex>
-#include <new>
-#include <vector>
-
-#include "mpk_internal.h"
+#include "kernels.h"
 
 namespace mpk {
-const char* last_error();
-size_t export_size(const HostGraph& g);
-void export_graph(const HostGraph& g, void* buf);
 
-// Everything that is fixed for the lifetime of a graph lives in one device-resident record that
-// the kernels reach through a pointer (uniform address -> scalar loads on demand, nothing is
-// pinned in registers for the whole kernel).
-struct GraphConst {
-  const TaskDesc* tasks;
-  const EventDesc* events;
-  uint32_t* counters;
-  uint32_t* hier;            // counter blocks of hierarchical events
-  const uint32_t* aot_off;
-  const uint32_t* aot;
-  const uint32_t* op_list;   // per-operator launch: task indices grouped by operator
-  uint32_t* err;             // [0] error code, [1] abort flag, [2..3] detail
-  const double* inv_freq;    // RoPE frequencies theta^(-2i/d), i < head_dim / 2
-  uint32_t* grp_counters;    // arrival counters per (layer, sequence, KV head), monotonic
-  uint64_t* trace;           // optional [n_tasks][kTraceSlots] timestamps (100 MHz), or null
-  uint64_t timeout_ticks;
-  uint32_t n_workers;
-  uint32_t vocab, max_seq, n_q, n_kv, head_dim, batch;
-  uint32_t lin_rows_max;     // largest number of weight rows (gate/up pairs count twice) of a linear task
-  uint32_t lin_res_rows_max; // largest number of columns of a linear task that adds a residual
-  // just-in-time launch (Section 5.2): scheduler event queues and worker task queues.  Entries
-  // are 64-bit (ticket + 1) << 32 | id with tickets that only grow, so a slot is valid exactly
-  // when it carries the ticket its reader expects; tails sit on their own 256-byte lines.
-  uint32_t n_sched;          // scheduler wavefronts (0: every task is ahead-of-time)
-  uint32_t evq_cap, wq_cap;  // powers of two
-  uint64_t* evq_buf;         // [n_sched][evq_cap]
-  uint32_t* evq_tail;        // [n_sched][64]
-  uint32_t* sched_state;     // [n_sched][64]: [0] head ticket, [1] round-robin cursor (persist across steps)
-  const uint32_t* sched_nev; // [n_sched] events a scheduler handles per step
-  uint64_t* wq_buf;          // [n_workers][wq_cap]
-  uint32_t* wq_tail;         // [n_workers][64]
-  uint32_t* wq_head;         // [n_workers] head ticket (persists across steps)
-  uint32_t start_event, terminal_event;
-  // multi-token launch: written by mpk_decode_steps before the launch (stream-ordered copy)
-  int32_t* tokens_out;   // [n_steps][batch] or null
-  float* logits_all;     // [n_steps][batch][vocab] or null
-};
-
-// Per-step kernel arguments, passed by value.  Every device function taking it is force-inlined:
-// a real call with a reference to it would make the compiler copy the struct to private memory.
-// Tables that no kernel ever writes (the graph record, task and event descriptors, queues) are
-// read through the constant address space: uniform reads then become scalar loads, which use
-// their own counter and never queue behind (or wait for) the vector-memory weight stream.
-#define MPK_CONST __attribute__((address_space(4)))
-struct StepArgs {
-  const MPK_CONST GraphConst* g;
-  // what every wait and notification needs, by value: kernel arguments are in scalar registers
-  // when the kernel starts, a field behind `g` costs a memory round trip on the critical path
-  const TaskDesc* tasks;
-  const EventDesc* events;
-  uint32_t* counters;
-  uint32_t* hier;
-  uint32_t n_sched;
-  uint32_t epoch;
-  const int32_t* token_ids;
-  const int32_t* positions;
-  float* logits;
-  // multi-token launch (greedy_loop graphs): the kernel runs n_steps decode steps; `step` counts
-  // them and `epoch` grows with it.  positions[] stays as the host wrote it until the last step
-  // (tasks run ahead of the sampling, so they take positions[b] + step).  16 bits each: the
-  // struct is passed by value to every non-inlined task function and its fields sit in scalar
-  // registers throughout the kernel; 16 bytes more of it slowed the single-step launch by 1 to 4 %.
-  // For the same reason the output pointers of a multi-token launch and the trace buffer are in
-  // the graph record instead.
-  uint16_t step, n_steps;
-  uint32_t flags;   // kTraceBit
-};
-static_assert(sizeof(StepArgs) == 80, "StepArgs grew: check the single-step launch time");
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-// A struct passed by value to a real (non-inlined) function travels through private memory and
-// arrives in vector registers: to the compiler every field is then a per-lane value, so the
-// descriptor reads behind it become vector loads and every branch on them an exec-mask branch.
-// All lanes hold the same values: say so, field by field.
-__device__ __forceinline__ uint32_t uniform_u32(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
-template <typename P>
-__device__ __forceinline__ P uniform_ptr(P p) {
-  const uint64_t v = (uint64_t)p;
-  return (P)(((uint64_t)uniform_u32((uint32_t)(v >> 32)) << 32) | uniform_u32((uint32_t)v));
-}
-__device__ __forceinline__ StepArgs uniform_args(const StepArgs& a) {
-  StepArgs u;
-  u.g = uniform_ptr(a.g);
-  u.tasks = uniform_ptr(a.tasks);
-  u.events = uniform_ptr(a.events);
-  u.counters = uniform_ptr(a.counters);
-  u.hier = uniform_ptr(a.hier);
-  u.n_sched = uniform_u32(a.n_sched);
-  u.epoch = uniform_u32(a.epoch);
-  u.token_ids = uniform_ptr(a.token_ids);
-  u.positions = uniform_ptr(a.positions);
-  u.logits = uniform_ptr(a.logits);
-  u.step = (uint16_t)uniform_u32(a.step);
-  u.n_steps = (uint16_t)uniform_u32(a.n_steps);
-  u.flags = uniform_u32(a.flags);
-  return u;
-}
-
-// Pointers that arrive through descriptors in memory are "generic" to the compiler, which then
-// emits FLAT memory instructions: those may complete out of order, so every use has to wait for
-// ALL outstanding memory operations (vmcnt(0) lgkmcnt(0)) and nothing pipelines.  Everything the
-// kernels touch outside LDS is device memory: say so, and loads/stores become GLOBAL instructions
-// that complete in order and can be waited for one by one.
-#define MPK_GLOBAL __attribute__((address_space(1)))
-template <typename T>
-__device__ __forceinline__ MPK_GLOBAL T* as_global(T* p) {
-  return (MPK_GLOBAL T*)p;
-}
-// 16-byte non-temporal load (weights, cache rows: streamed once, keep them out of the caches)
-__device__ __forceinline__ u32x4 ld_stream16(const void* p) {
-  return __builtin_nontemporal_load(as_global((const u32x4*)p));
-}
-
-template <typename T>
-__device__ __forceinline__ T ld_const_record(const T* p) {   // sizeof(T) a multiple of 16
-  union {
-    T rec;
-    u32x4 v[sizeof(T) / 16];
-  } u;
-  const MPK_CONST u32x4* src = (const MPK_CONST u32x4*)p;
-#pragma unroll
-  for (unsigned i = 0; i < sizeof(T) / 16; ++i) u.v[i] = src[i];
-  return u.rec;
-}
-__device__ __forceinline__ TaskDesc ld_task(const StepArgs& a, uint32_t i) { return ld_const_record(a.tasks + i); }
-__device__ __forceinline__ uint32_t ld_u32c(const uint32_t* p) { return *(const MPK_CONST uint32_t*)p; }
-
-constexpr int kTraceSlots = 12;
-constexpr uint32_t kTraceBit = 1u;   // StepArgs::flags: per-task timestamps are recorded (buffer: GraphConst::trace)
-__device__ __forceinline__ void trace_mark(const StepArgs& a, const TaskDesc& t, int slot) {
-  if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + slot] = wall_clock64();
-}
-
-enum DevErr : uint32_t { DE_NONE = 0, DE_TIMEOUT = 1, DE_BAD_POSITION = 2, DE_BAD_TOKEN = 3, DE_BAD_META = 4 };
-
-// ------------------------------------------------------------------------------ device helpers
-__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
-__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-
-// fp32 -> bf16, round to nearest even; NaN stays a quiet NaN.
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (uint16_t)((u >> 16) | 0x40u);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-  return v;
-}
-
-// Sum over the whole workgroup; every thread gets the result.  red: >= 16 floats of LDS.
-__device__ __forceinline__ float block_sum(float v, float* red) {
-  v = wave_sum(v);
-  int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  __syncthreads();
-  if (lane == 0) red[wave] = v;
-  __syncthreads();
-  float s = 0.f;
-#pragma unroll
-  for (int i = 0; i < (int)(kThreads / 64); ++i) s += red[i];
-  return s;
-}
-
-// Agent-coherent accessors for data produced and consumed by different workgroups in one launch.
-__device__ __forceinline__ float ld_act(const float* p) {
-  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_act(float* p, float v) {
-  __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float2 ld_act2(const float* p) {   // p 8-byte aligned
-  uint64_t u = __hip_atomic_load(as_global((const uint64_t*)p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return make_float2(__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32)));
-}
-__device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p) {
-  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint64_t ld_relaxed64(const uint64_t* p) {
-  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_act_u32(uint32_t* p, uint32_t v) {
-  __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ u32x4 ld_row16_coherent(const uint16_t* p) {   // p 16-byte aligned
-  uint64_t a = __hip_atomic_load(as_global((const uint64_t*)p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  uint64_t b = __hip_atomic_load(as_global((const uint64_t*)p + 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return u32x4{(uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32)};
-}
-
-__device__ __forceinline__ float dot8(const u32x4& w, const float4& x0, const float4& x1, float acc) {
-  acc = fmaf(bf16_lo(w.x), x0.x, acc);
-  acc = fmaf(bf16_hi(w.x), x0.y, acc);
-  acc = fmaf(bf16_lo(w.y), x0.z, acc);
-  acc = fmaf(bf16_hi(w.y), x0.w, acc);
-  acc = fmaf(bf16_lo(w.z), x1.x, acc);
-  acc = fmaf(bf16_hi(w.z), x1.y, acc);
-  acc = fmaf(bf16_lo(w.w), x1.z, acc);
-  acc = fmaf(bf16_hi(w.w), x1.w, acc);
-  return acc;
-}
-
-__device__ __forceinline__ void report(const StepArgs& a, uint32_t code, uint32_t d0, uint32_t d1) {
-  if (atomicCAS(&a.g->err[0], 0u, code) == 0u) {
-    a.g->err[2] = d0;
-    a.g->err[3] = d1;
-  }
-}
-
-// ------------------------------------------------------------------------------ task bodies
-// T0: x[b] = E[token[b]] widened to fp32.
-__device__ __forceinline__ void body_embed(const TaskDesc& t, const StepArgs& a) {
-  for (uint32_t b = t.b0; b < t.b1; ++b) {
-    int32_t tok = (int32_t)ld_relaxed((const uint32_t*)a.token_ids + b);   // may come from the previous step's sampling task
-    if (tok < 0 || (uint32_t)tok >= a.g->vocab) {
-      if (threadIdx.x == 0) report(a, DE_BAD_TOKEN, b, (uint32_t)tok);
-      tok = 0;
-    }
-    const uint16_t* row = (const uint16_t*)t.w + (size_t)tok * t.K;
-    float* out = t.out + (size_t)b * t.ld_out;
-    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) st_act(out + i, bf16_to_f32(as_global(row)[i]));
-  }
-}
-
-// T1/T8/T13: y = x * (1 / sqrt(mean(x^2) + eps)) * g, one batch row per task.
-__device__ __forceinline__ void body_rmsnorm(const TaskDesc& t, float* lds) {
-  const uint16_t* g = (const uint16_t*)t.w2;
-  for (uint32_t b = t.b0; b < t.b1; ++b) {
-    const float* x = t.in + (size_t)b * t.ld_in;
-    float* y = t.out + (size_t)b * t.ld_out;
-    float ss = 0.f;
-    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) {
-      float v = ld_act(x + i);
-      ss = fmaf(v, v, ss);
-    }
-    ss = block_sum(ss, lds);
-    float inv = 1.0f / sqrtf(ss / (float)t.K + t.f0);
-    for (uint32_t i = threadIdx.x; i < t.K; i += kThreads) st_act(y + i, ld_act(x + i) * inv * bf16_to_f32(as_global(g)[i]));
-  }
-}
-
-__device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag);
-
-// ------------------------------------------------------------------------------ linear tasks
-// T2/T6/T9/T11/T14: y[b][c] = sum_j W[c][j] x[b][j] for output columns [c0, c1), all batch rows
-// at once, with optional fused stages: RMSNorm of the input (TF_PRO_NORM), residual add
-// (TF_EPI_RESID), silu(gate) * up (TF_GATEUP: column c needs weight rows c and F + c).
-//
-// Weight rows of a task ("ring rows": one per column, or the (gate, up) pair of each column) are
-// split into 8 contiguous ranges, one per wavefront.  A wavefront walks its rows in pairs and
-// every pair in segments of 4096 input elements; one (pair, segment) is a half block of
-// 2 rows x 8 stages, a stage being 64 lanes x 16 bytes = 512 elements: 16 sixteen-byte loads per
-// lane.  A wavefront owns two half-block buffers (32 KB, 256 KB per CU) and uses them in turn: it
-// consumes one, requests that buffer's next half block at once, and turns to the other.  The
-// compiler's count of the loads in flight does not survive the loop's back edge (it waits for
-// both buffers before the first use of either), so a wavefront still drains its queue once per
-// pair of half blocks; the eight wavefronts of a CU drift apart and cover for each other.
-// Against ONE buffer of twice the size, requested whole and then consumed whole: the first
-// buffer's request goes out half a block earlier, and a task with two rows per wavefront (the O
-// and down projections of the 8B shape) pre-loads two segments instead of one.
-//
-// Cross-task pipelining (paper Section 5.3).  Weights never depend on an event, so a task
-// requests its first two half blocks (256 KB per CU) BEFORE it waits for its dependent event:
-// they stream in while the input vector is still being produced elsewhere.  At the end of a task
-// wavefront 0 alone applies the epilogue, writes the outputs with coherent stores and waits for
-// exactly those stores; the other wavefronts wait at a barrier meanwhile, and only then walk into
-// the worker's next task and issue its first requests, while wavefront 0 notifies the triggering
-// event, requests its own share and polls the next event.  (The others must not run ahead: all
-// wavefronts of a CU share its path to memory, and output stores queued behind their requests
-// were acknowledged up to 10 us late.)
-// The buffers are local to a task on purpose: carried around the task loop instead, the
-// compiler moves parts of them to scratch memory, and a scratch access in the middle of a request
-// waits for every load issued before it.
-constexpr int kHalfRows = 2, kRingStages = 8;
-constexpr uint32_t kSegLen = 512u * kRingStages;   // input elements per half-block row
-struct HalfRing {
-  u32x4 s[kHalfRows][kRingStages];
-};
-
-__device__ __forceinline__ void ring_clear(HalfRing& ring) {
-#pragma unroll
-  for (int i = 0; i < kHalfRows; ++i)
-#pragma unroll
-    for (int u = 0; u < kRingStages; ++u) ring.s[i][u] = u32x4{0, 0, 0, 0};
-}
-
-// Wavefront-uniform view of one linear task for one wavefront.
-struct LinGeom {
-  const uint16_t* W;
-  uint32_t K, c0, F, gateup;
-  uint32_t r0, r1;    // ring rows [r0, r1) of this wavefront within the task
-  uint32_t nseg;      // segments per row
-};
-
-__device__ __forceinline__ LinGeom lin_geom(const TaskDesc& t, uint32_t wave) {
-  LinGeom g;
-  g.W = (const uint16_t*)t.w;
-  g.K = t.K;
-  g.c0 = t.c0;
-  g.F = t.p0;
-  g.gateup = (t.flags & TF_GATEUP) ? 1u : 0u;
-  const uint32_t R = (t.c1 - t.c0) << g.gateup;
-  constexpr uint32_t NW = kThreads / 64;
-  uint32_t rpw = (R + NW - 1u) / NW;
-  if (g.gateup) rpw = (rpw + 1u) & ~1u;   // a (gate, up) pair stays in one wavefront
-  g.r0 = min(wave * rpw, R);
-  g.r1 = min(g.r0 + rpw, R);
-  g.nseg = (t.K + kSegLen - 1u) / kSegLen;
-  return g;
-}
-
-// Position of a wavefront in its sequence of half blocks: rows [row0, row0 + 2) x segment `seg`,
-// segments of a pair first.  Two of them walk the sequence: one requests, one consumes.
-struct LinCursor {
-  uint32_t row0, seg;
-};
-__device__ __forceinline__ bool lin_valid(const LinGeom& g, const LinCursor& c) { return c.row0 < g.r1; }
-__device__ __forceinline__ void lin_advance(const LinGeom& g, LinCursor& c) {
-  if (++c.seg == g.nseg) {
-    c.seg = 0;
-    c.row0 += kHalfRows;
-  }
-}
-
-// The half block at a cursor.
-struct LinHalf {
-  const uint16_t* p[kHalfRows];   // row start + segment start (a second row past the end repeats the first)
-  uint32_t row0, nrows, seg, seglen;
-};
-
-__device__ __forceinline__ LinHalf lin_half(const LinGeom& g, const LinCursor& c) {
-  LinHalf B;
-  B.seg = c.seg;
-  B.row0 = c.row0;
-  B.nrows = min(g.r1 - c.row0, (uint32_t)kHalfRows);
-  B.seglen = min(kSegLen, g.K - c.seg * kSegLen);
-#pragma unroll
-  for (int i = 0; i < kHalfRows; ++i) {
-    const uint32_t r = B.row0 + min((uint32_t)i, B.nrows - 1u);
-    const uint32_t wrow = g.gateup ? (g.c0 + (r >> 1) + ((r & 1u) ? g.F : 0u)) : g.c0 + r;
-    B.p[i] = g.W + (size_t)wrow * g.K + c.seg * kSegLen;
-  }
-  return B;
-}
-
-// Requests a half block, stage by stage.  Lanes past the end of a short segment re-read its last
-// 16 bytes (the staged input is zero there), so every lane takes part in every load.
-__device__ __forceinline__ void lin_request(const LinHalf& B, HalfRing& ring, int lane) {
-  if (B.seglen == kSegLen) {   // full segment: one base address per row, constant stage offsets
-#pragma unroll
-    for (int u = 0; u < kRingStages; ++u)
-#pragma unroll
-      for (int i = 0; i < kHalfRows; ++i) ring.s[i][u] = ld_stream16(B.p[i] + lane * 8 + u * 512);
-  } else {
-#pragma unroll
-    for (int u = 0; u < kRingStages; ++u) {
-      const uint32_t o = min((uint32_t)u * 512u + (uint32_t)lane * 8u, B.seglen - 8u);
-#pragma unroll
-      for (int i = 0; i < kHalfRows; ++i) ring.s[i][u] = ld_stream16(B.p[i] + o);
-    }
-  }
-}
-
-// Adds the half block's partial dot products to acc.
-template <int NB>
-__device__ __forceinline__ void lin_consume(const LinHalf& B, const HalfRing& ring, const float* xs, uint32_t Kp,
-                                            int lane, float (&acc)[kHalfRows][NB]) {
-#pragma unroll
-  for (int u = 0; u < kRingStages; ++u) {
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      const float4* xp = (const float4*)(xs + (size_t)b * Kp + B.seg * kSegLen + u * 512 + lane * 8);
-      const float4 x0 = xp[0], x1 = xp[1];
-#pragma unroll
-      for (int i = 0; i < kHalfRows; ++i) acc[i][b] = dot8(ring.s[i][u], x0, x1, acc[i][b]);
-    }
-  }
-}
-
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() carries a release fence, for
-// which the compiler drains the vector-memory queue (s_waitcnt vmcnt(0)): with a pre-load of
-// the next task in flight that would stall every wavefront, and the event notification behind
-// it, until the whole pre-load has landed.  What the barriers of a linear task publish lives in
-// LDS; data for other workgroups is published by wavefront 0 with its own wait.
-__device__ __forceinline__ void lds_barrier() {
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-__device__ __forceinline__ void signal_from_wave0(const StepArgs& a, const TaskDesc& t, int32_t e, int lane);
-__device__ __forceinline__ void notify_event(const StepArgs& a, int32_t e);
-__device__ __forceinline__ void poll_event_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane);
-__device__ __forceinline__ void poll_event_or_jit_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane, uint32_t jit_head);
-// Hybrid launch (Section 5.2): a worker may start the linear task at the head of its ahead-of-time
-// queue before that task's event is activated (so the weights are requested early), provided it
-// keeps an eye on its just-in-time queue while it waits: a worker that blocked regardless could
-// sit on the very tasks the awaited event depends on.  When a just-in-time task arrives first,
-// the linear task gives up (kLinPreempted, task index in s_flag[1]); the worker runs that task and
-// starts the linear task again.  (Running it from inside the wait would keep the pre-loaded
-// weights live across a call: the compiler then moves them to scratch memory for good.)
-// NoJit: all-ahead-of-time kernels, nothing to watch.
-constexpr uint32_t kLinAbort = 0, kLinDone = 1, kLinPreempted = 2;
-struct NoJit {
-  static constexpr bool enabled = false;
-  uint32_t jit_head = 0;
-};
-struct JitWatch {
-  static constexpr bool enabled = true;
-  uint32_t jit_head;   // the worker's consumer ticket of its just-in-time queue
-};
-// The wait of a linear task for its dependent event: kLinDone (activated), kLinAbort, kLinPreempted.
-template <class Svc>
-__device__ __forceinline__ uint32_t linear_wait(const StepArgs& a, int32_t wait_ev, uint32_t* s_flag, uint32_t wave, int lane,
-                                                const Svc& svc) {
-  if (wave == 0) {
-    if constexpr (Svc::enabled) poll_event_or_jit_wave0(a, wait_ev, s_flag, lane, svc.jit_head);
-    else poll_event_wave0(a, wait_ev, s_flag, lane);
-  }
-  lds_barrier();
-  return __builtin_amdgcn_readfirstlane(*s_flag);   // (uniform; tell the compiler)
-}
-
-// LDS layout of a linear task (floats): xs [NB][K rounded up to 4096] | outbuf [max ring rows][NB]
-// | resid [max columns][NB] | ssq [8][NB]; the two middle regions are sized by the compiler from
-// the largest task of the graph (GraphConst::lin_rows_max).
-//
-// Runs task `t`.  wait_ev >= 0: wait for that event first (persistent kernel).  Returns whether
-// the step is still alive (false: watchdog / abort).
-template <int NB, bool MEGA, class Svc = NoJit, bool DEEP = false>
-__device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
-                                                uint32_t* s_flag, const Svc& svc = Svc{}) {
-  const int lane = threadIdx.x & 63;
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: geometry stays scalar
-  const uint32_t K = t.K, nb = t.b1 - t.b0, ncols = t.c1 - t.c0;
-  const uint32_t Kp = (K + kSegLen - 1u) / kSegLen * kSegLen;
-  const uint32_t rows_max = a.g->lin_rows_max;
-  float* xs = lds;                                   // [NB][Kp]
-  float* outbuf = xs + (size_t)NB * Kp;              // [rows_max][NB]
-  float* res_lds = outbuf + (size_t)rows_max * NB;   // [rows_max][NB]
-  float* ssq = res_lds + (size_t)rows_max * NB;      // [8][NB]
-  const LinGeom g = lin_geom(t, wave);
-  HalfRing h0, h1;   // local to the task: nothing is live around the task loop, so they stay in registers
-  ring_clear(h0);
-  ring_clear(h1);
-  LinCursor rq{g.r0, 0u};   // next half block to request
-  // (every request site ends in an (empty) assembly statement of its own: otherwise the compiler
-  // may merge the identical last loads of two sites into one whose destination is chosen at run
-  // time, and a buffer addressed that way is moved from registers to scratch memory)
-  if (lin_valid(g, rq)) {
-    lin_request(lin_half(g, rq), h0, lane);
-    lin_advance(g, rq);
-    asm volatile("; first half block requested" ::: "memory");
-  }
-  if (lin_valid(g, rq)) {
-    lin_request(lin_half(g, rq), h1, lane);
-    lin_advance(g, rq);
-    asm volatile("; second half block requested" ::: "memory");
-  }
-  // DEEP: a third buffer -- 384 KB per CU requested before the event and a deeper queue while
-  // streaming.  A kernel variant of its own, picked for models whose linear tasks are large (70B
-  // shape: -3 % per step); small tasks are bound by the hops between operators, where a bigger
-  // burst ahead of the event poll and the input loads only delays those (8B shape: +3 %), and the
-  // mere presence of the third buffer in the kernel costs the small shape 2 %.
-  constexpr bool kThird = DEEP;
-  HalfRing h2;
-  if (kThird) {
-    ring_clear(h2);
-    if (lin_valid(g, rq)) {
-      lin_request(lin_half(g, rq), h2, lane);
-      lin_advance(g, rq);
-      asm volatile("; third half block requested" ::: "memory");
-    }
-  }
-  // ---- dependent event: wavefront 0 polls, the others wait at the barrier
-  if (wait_ev >= 0) {
-    const uint32_t w = linear_wait(a, wait_ev, s_flag, wave, lane, svc);
-    if (w != kLinDone) return w;   // aborted, or pre-empted by a just-in-time task: the requested weights are dropped
-  }
-  trace_mark(a, t, 1);
-  // ---- stage the input rows in LDS.  With TF_PRO_NORM the gain is folded in here (x * g) and
-  // the row's 1/rms factor is applied to the finished dot products: W (x g inv) = inv * W (x g).
-  const bool pro_norm = t.flags & TF_PRO_NORM;
-  const uint16_t* gain = (const uint16_t*)t.w2;
-  // the residual slice of this tile goes out first (tile-local, small): its round trip then
-  // overlaps the staging instead of following it
-  const bool resid = t.flags & TF_EPI_RESID;
-  float resv = 0.f;
-  if (resid && threadIdx.x < nb * ncols) {
-    const uint32_t bb = threadIdx.x / ncols, cc = threadIdx.x % ncols;
-    resv = ld_act(t.in2 + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc);
-  }
-  constexpr int kStageLoads = 12;   // coherent loads in flight per lane: 12288 inputs in one round trip
-#pragma unroll
-  for (uint32_t b = 0; b < (uint32_t)NB; ++b) {
-    float2* dst = (float2*)(xs + (size_t)b * Kp);
-    float ss = 0.f;
-    if (b < nb) {
-      const float* src = t.in + (size_t)(t.b0 + b) * t.ld_in;
-      for (uint32_t i0 = 0; i0 < Kp / 2; i0 += kThreads * kStageLoads) {
-        float2 tmp[kStageLoads];
-#pragma unroll
-        for (int u = 0; u < kStageLoads; ++u) {
-          uint32_t i = i0 + u * kThreads + threadIdx.x;
-          if (i < K / 2) tmp[u] = ld_act2(src + 2 * i);
-        }
-#pragma unroll
-        for (int u = 0; u < kStageLoads; ++u) {
-          uint32_t i = i0 + u * kThreads + threadIdx.x;
-          if (i < K / 2) {
-            float2 v = tmp[u];
-            if (pro_norm) {
-              ss = fmaf(v.x, v.x, ss);
-              ss = fmaf(v.y, v.y, ss);
-              uint32_t g2 = *as_global((const uint32_t*)(gain + 2 * i));
-              v.x *= bf16_lo(g2);
-              v.y *= bf16_hi(g2);
-            }
-            dst[i] = v;
-          } else if (i < Kp / 2) {
-            dst[i] = make_float2(0.f, 0.f);
-          }
-        }
-      }
-    } else {
-      for (uint32_t i = threadIdx.x; i < Kp / 2; i += kThreads) dst[i] = make_float2(0.f, 0.f);
-    }
-    if (pro_norm) {
-      ss = wave_sum(ss);
-      if (lane == 0) ssq[wave * NB + b] = ss;
-    }
-  }
-  if (resid) {
-    if (threadIdx.x < nb * ncols) res_lds[threadIdx.x] = resv;
-    for (uint32_t i = threadIdx.x + kThreads; i < nb * ncols; i += kThreads) {   // more than 512 outputs per task: rare
-      uint32_t bb = i / ncols, cc = i % ncols;
-      res_lds[i] = ld_act(t.in2 + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc);
-    }
-  }
-  lds_barrier();
-  trace_mark(a, t, 2);
-  // ---- stream this wavefront's rows: the two buffers in turn
-  {
-    float acc[kHalfRows][NB];
-#pragma unroll
-    for (int i = 0; i < kHalfRows; ++i)
-#pragma unroll
-      for (int b = 0; b < NB; ++b) acc[i][b] = 0.f;
-    // the pair of rows is complete with its last segment: reduce across lanes, results to LDS
-    auto finish = [&](const LinHalf& B) {
-      if (B.seg + 1 == g.nseg) {
-#pragma unroll
-        for (int i = 0; i < kHalfRows; ++i)
-#pragma unroll
-          for (int b = 0; b < NB; ++b) {
-            const float v = wave_sum(acc[i][b]);
-            if (lane == 0 && (uint32_t)i < B.nrows) outbuf[(size_t)(B.row0 + i) * NB + b] = v;
-            acc[i][b] = 0.f;
-          }
-      }
-    };
-    LinCursor cs{g.r0, 0u};
-    while (lin_valid(g, cs)) {
-      {
-        const LinHalf B = lin_half(g, cs);
-        lin_consume<NB>(B, h0, xs, Kp, lane, acc);
-        finish(B);
-        lin_advance(g, cs);
-      }
-      if (lin_valid(g, rq)) {
-        lin_request(lin_half(g, rq), h0, lane);
-        lin_advance(g, rq);
-        asm volatile("; first buffer requested again" ::: "memory");
-      }
-      if (!lin_valid(g, cs)) break;
-      {
-        const LinHalf B = lin_half(g, cs);
-        lin_consume<NB>(B, h1, xs, Kp, lane, acc);
-        finish(B);
-        lin_advance(g, cs);
-      }
-      if (lin_valid(g, rq)) {
-        lin_request(lin_half(g, rq), h1, lane);
-        lin_advance(g, rq);
-        asm volatile("; second buffer requested again" ::: "memory");
-      }
-      if (kThird) {
-        if (!lin_valid(g, cs)) break;
-        {
-          const LinHalf B = lin_half(g, cs);
-          lin_consume<NB>(B, h2, xs, Kp, lane, acc);
-          finish(B);
-          lin_advance(g, cs);
-        }
-        if (lin_valid(g, rq)) {
-          lin_request(lin_half(g, rq), h2, lane);
-          lin_advance(g, rq);
-          asm volatile("; third buffer requested again" ::: "memory");
-        }
-      }
-    }
-  }
-  lds_barrier();
-  trace_mark(a, t, 3);
-  // ---- wavefront 0: epilogue, outputs, notification, then its own share of the pre-load
-  if (wave == 0) {
-    float* outp = (t.flags & TF_OUT_LOGITS) ? a.logits : t.out;
-    float inv_rms[NB];
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      inv_rms[b] = 1.0f;
-      if (pro_norm && (uint32_t)b < nb) {
-        float ss = 0.f;
-#pragma unroll
-        for (int w = 0; w < (int)(kThreads / 64); ++w) ss += ssq[w * NB + b];
-        inv_rms[b] = 1.0f / sqrtf(ss / (float)K + t.f0);
-      }
-    }
-    for (uint32_t i = lane; i < ncols * nb; i += 64) {
-      const uint32_t cc = i % ncols, bb = i / ncols;
-      float inv = inv_rms[0];
-#pragma unroll
-      for (int b = 1; b < NB; ++b) inv = (bb == (uint32_t)b) ? inv_rms[b] : inv;
-      float v;
-      if (g.gateup) {
-        const float gte = outbuf[(size_t)(2 * cc) * NB + bb] * inv, up = outbuf[(size_t)(2 * cc + 1) * NB + bb] * inv;
-        v = gte / (1.0f + expf(-gte)) * up;
-      } else {
-        v = outbuf[(size_t)cc * NB + bb] * inv;
-      }
-      if (t.flags & TF_EPI_RESID) v = res_lds[bb * ncols + cc] + v;
-      st_act(outp + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc, v);
-    }
-    if (MEGA) {   // wait for exactly these stores
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      trace_mark(a, t, 7);
-    }
-  }
-  if (MEGA) {
-    // Wavefronts 1..7 issue the next task's requests only now.  Ordering inside ONE wavefront is
-    // not enough: all wavefronts of a CU share its path to memory, and behind 224 freshly issued
-    // 1 KB loads the few output stores of wavefront 0 were acknowledged up to 10 us late (in-kernel
-    // trace), which delays the event for every consumer -- the hop is the critical path, the
-    // pre-load has slack.
-    lds_barrier();
-    if (wave == 0) {
-      if (t.trig_event >= 0 && lane == 0) notify_event(a, t.trig_event);
-      trace_mark(a, t, 4);
-    }
-  }
-  return kLinDone;
-}
-
-// ------------------------------------------------------------------------------ linear tasks, batch 5..16
-// The same operator for 5 to 16 batch rows, on the matrix cores.  At batch 8 the vector ALUs
-// would need about as many cycles for the multiply-adds as HBM needs to deliver the weights; one
-// v_mfma_f32_16x16x32_bf16 does 16 weight rows x 32 inputs x 16 batch columns at once.
-//   A operand = weights: lane l holds row (l % 16) of a 16-row tile, inputs 8 (l / 16) .. + 7 of
-//     the current 32-input step: 16 bytes straight from HBM, no conversion.
-//   B operand = activations: lane l holds batch column (l % 16), the same 8 inputs, as bf16.
-//     Activations are fp32: x is split into hi = bf16(x) and lo = bf16(x - hi) and each weight
-//     fragment is multiplied with both (x is represented to 2^-17, the products are exact and
-//     the accumulation is fp32).
-//   D: lane l holds batch column (l % 16), tile rows 4 (l / 16) .. + 3.
-// The input is staged in LDS one K tile at a time (hi and lo planes, row stride padded by 16
-// bytes so that the 16 lanes of a fragment read 16 different bank groups).  Work is split over
-// the 8 wavefronts by 16-row tiles; a task with fewer than 8 tiles also splits K inside each
-// input tile, and the epilogue adds the slices in a fixed order.
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-// (x, y) -> packed bf16 pairs hi = bf16(x), lo = bf16(x - hi), round to nearest even (the
-// hardware conversion: two packed converts, two subtractions)
-__device__ __forceinline__ void split_hi_lo(float x, float y, uint32_t* hi, uint32_t* lo) {
-  const uint32_t h = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){x, y}, bf16x2));
-  *hi = h;
-  *lo = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){x - bf16_lo(h), y - bf16_hi(h)}, bf16x2));
-}
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ uint32_t mfma_ktile(uint32_t nb) { return nb <= 8 ? 2048u : 1024u; }
-
-// LDS (from the task area): xh [2][nb][Kt + 8] bf16 | xl same | res [residual columns][16] f32 |
-// ssq [8][16] f32 | 1/rms [16] f32; the per-wavefront partial tiles part [8][4][256] f32 reuse the
-// input buffers once the last input tile has been consumed.
-template <bool MEGA, class Svc = NoJit>
-__device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
-                                                     uint32_t* s_flag, const Svc& svc = Svc{}) {
-  const int lane = threadIdx.x & 63;
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const uint32_t K = t.K, nb = t.b1 - t.b0, ncols = t.c1 - t.c0;
-  const uint32_t gateup = (t.flags & TF_GATEUP) ? 1u : 0u;
-  const uint32_t R = ncols << gateup;            // weight rows of the task ("ring rows")
-  const uint32_t nrt = (R + 15u) / 16u;          // 16-row tiles
-  // An input of at most two staging tiles is staged whole, as ONE tile in the space of the two
-  // buffers: one barrier instead of two, and the K slice of a wavefront is twice as long -- for a
-  // task of one 16-row tile (eight K slices) exactly the 16 fragments requested before the event
-  // wait, where two short tiles used half of that round each and paid a second round trip.
-  const uint32_t Kt1 = mfma_ktile(nb);                      // what one staging pass covers
-  // (Batch <= 8 only for now: at batch 16 the different summation order moves one logit near the
-  // floor of the 48-layer mixture-of-experts shape just past that test's element-wise bound.)
-  const bool whole = nb <= 8u && K > Kt1 && K <= 2u * Kt1;
-  const uint32_t Kt = whole ? 2u * Kt1 : Kt1, xstride = Kt + 8u, nbuf = whole ? 1u : 2u;
-  const uint32_t xplane = nb * xstride;                     // one plane of one buffer, in bf16
-  uint16_t* xh = (uint16_t*)lds;                            // [nbuf buffers][nb][xstride]
-  uint16_t* xl = xh + nbuf * (size_t)xplane;
-  float* part = lds;                                        // [8][4][256], reuses the input buffers at the end
-  float* res_lds = (float*)(xl + nbuf * (size_t)xplane);    // [rows_max][16]
-  float* ssq = res_lds + (size_t)a.g->lin_res_rows_max * 16;   // [8][16]
-  // which tiles and which K slice this wavefront works on
-  uint32_t nrt2 = 1;
-  while (nrt2 < nrt && nrt2 < 8u) nrt2 <<= 1;
-  const uint32_t ks = 8u / nrt2;                 // K slices per input tile (1 when nrt >= 8)
-  const uint32_t my_slice = wave / nrt2, my_rt0 = wave % nrt2;   // tiles my_rt0, my_rt0 + 8, ... (ks == 1)
-  const uint32_t slice_len = Kt / ks;            // multiple of 128
-  const uint16_t* W = (const uint16_t*)t.w;
-  const uint32_t frow = lane & 15u, fk = (uint32_t)(lane >> 4) * 8u;   // fragment row / input offset
-  f32x4 acc[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  // Weight fragments are requested a round at a time: kMfmaRound steps of 32 inputs, 16 bytes per
-  // lane and step (16 KB per wavefront in flight), then multiplied as they arrive.  The first
-  // round is requested before the event wait (cross-task pre-loading, Section 5.3).
-  constexpr int kMfmaRound = 16;
-  u32x4 wfrag[kMfmaRound];
-  // split-K task (TF_SPLITK): rows [row0, row0 + ncols) of the matrix, inputs of ONE part; the
-  // weight pointer is already advanced to the part, rows are ldw apart
-  const bool splitk = t.flags & TF_SPLITK;
-  const uint32_t parts = splitk ? (t.p3 & 0xFFu) : 1u, my_part = splitk ? (t.p3 >> 8) : 0u;
-  const uint32_t Hs = t.ld_out / parts;              // columns of the real output
-  const uint32_t row0 = t.c0 - my_part * Hs, ldw = splitk ? t.p1 : K;
-  auto row_ptr = [&](uint32_t rt) {
-    const uint32_t r = min(rt * 16u + frow, R - 1u);   // rows past the end repeat the last one
-    const uint32_t wrow = gateup ? (row0 + (r >> 1) + ((r & 1u) ? t.p0 : 0u)) : row0 + r;
-    return W + (size_t)wrow * ldw + fk;
-  };
-  auto request = [&](const uint16_t* wp, uint32_t k0, uint32_t kk) {   // inputs k0 + kk + 32 q + fk .. + 7
-#pragma unroll
-    for (int q = 0; q < kMfmaRound; ++q) {
-      const uint32_t k = min(k0 + kk + q * 32u, K - fk - 8u);   // stay inside the row
-      wfrag[q] = ld_stream16(wp + k);
-    }
-  };
-  const bool has_work = my_rt0 < nrt;
-  if (has_work) request(row_ptr(my_rt0), 0u, my_slice * slice_len);
-
-  if (wait_ev >= 0) {
-    const uint32_t w = linear_wait(a, wait_ev, s_flag, wave, lane, svc);
-    if (w != kLinDone) return w;   // aborted, or pre-empted by a just-in-time task: the requested weights are dropped
-  }
-  trace_mark(a, t, 1);
-  const bool pro_norm = t.flags & TF_PRO_NORM;
-  const uint16_t* gain = (const uint16_t*)t.w2;
-  if ((t.flags & TF_EPI_RESID) && !splitk) {
-    for (uint32_t i = threadIdx.x; i < nb * ncols; i += kThreads) {
-      uint32_t bb = i / ncols, cc = i % ncols;
-      res_lds[cc * 16 + bb] = ld_act(t.in2 + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc);
-    }
-  }
-  // The input tile of 2048 (1024) inputs x nb rows is dealt to the threads in pairs: pair slot q
-  // of a thread is row q >> sh, pair ((q & sh) << 9) + thread (sh = 1 for 2048-input tiles), so
-  // the row of a slot is the same for the whole wavefront and needs no division.  A tile is
-  // requested (coherent loads into registers) while the previous tile is being multiplied, and
-  // converted into the other LDS buffer afterwards.  Sums of squares are kept per slot.
-  static_assert(kThreads == 512, "the slot -> (row, pair) mapping assumes 512 threads");
-  const uint32_t sh = Kt1 == 2048u ? 1u : 0u;
-  float sqq[16];
-#pragma unroll
-  for (int q = 0; q < 16; ++q) sqq[q] = 0.f;
-  const uint32_t ntile = (K + Kt - 1u) / Kt;
-  float2 sv[16];
-  // staging pass `tile`: inputs [tile * Kt1, + Kt1) into buffer tile & 1 -- or, staged whole,
-  // into columns tile * Kt1 .. of the one buffer
-  auto stage_issue = [&](uint32_t tile) {
-    float2 (&dst)[16] = sv;
-    const uint32_t k0 = tile * Kt1, klen = min(Kt1, K - k0);
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const uint32_t b = (uint32_t)q >> sh, i = (((uint32_t)q & sh) << 9) + threadIdx.x;
-      dst[q] = make_float2(0.f, 0.f);
-      if (b < nb && 2 * i < klen) dst[q] = ld_act2(t.in + (size_t)(t.b0 + b) * t.ld_in + k0 + 2 * i);
-    }
-  };
-  auto stage_write = [&](uint32_t tile) {
-    const float2 (&src)[16] = sv;
-    const uint32_t k0 = tile * Kt1, klen = min(Kt1, K - k0);
-    uint16_t* dh = whole ? xh + k0 : xh + (size_t)(tile & 1u) * xplane;
-    uint16_t* dl = whole ? xl + k0 : xl + (size_t)(tile & 1u) * xplane;
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const uint32_t b = (uint32_t)q >> sh, i = (((uint32_t)q & sh) << 9) + threadIdx.x;
-      if (b < nb) {
-        float2 w2 = src[q];
-        if (pro_norm && 2 * i < klen) {
-          sqq[q] = fmaf(w2.x, w2.x, fmaf(w2.y, w2.y, sqq[q]));
-          const uint32_t g2 = *as_global((const uint32_t*)(gain + k0 + 2 * i));
-          w2.x *= bf16_lo(g2);
-          w2.y *= bf16_hi(g2);
-        }
-        uint32_t hi, lo;
-        split_hi_lo(w2.x, w2.y, &hi, &lo);
-        *(uint32_t*)(dh + (size_t)b * xstride + 2 * i) = hi;
-        *(uint32_t*)(dl + (size_t)b * xstride + 2 * i) = lo;
-      }
-    }
-  };
-  stage_issue(0);
-  stage_write(0);
-  if (whole) {   // (both passes in one round trip, with twice the registers: no faster -- the
-    stage_issue(1);   // coherent reads of a [8][4096] input by 256 workers are bound by bandwidth)
-    stage_write(1);
-  }
-  lds_barrier();
-  trace_mark(a, t, 2);
-  // One round: the fragments in wfrag times both planes of the input, steps kk + 32 q < s_hi.
-  // Whole groups of four steps run without per-step tests, their LDS reads ahead of the multiplies.
-  auto consume = [&](f32x4& c, const uint16_t* bh, const uint16_t* bl, uint32_t kk, uint32_t s_hi) {
-#pragma unroll
-    for (int q0 = 0; q0 < kMfmaRound; q0 += 4) {
-      if (kk + (q0 + 4) * 32u <= s_hi) {
-        u32x4 hv[4], lv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          hv[u] = *(const u32x4*)(bh + kk + (q0 + u) * 32u);
-          lv[u] = *(const u32x4*)(bl + kk + (q0 + u) * 32u);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
-          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, hv[u]), c, 0, 0, 0);
-          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, lv[u]), c, 0, 0, 0);
-        }
-      } else {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          if (kk + (q0 + u) * 32u < s_hi) {
-            const u32x4 bhv = *(const u32x4*)(bh + kk + (q0 + u) * 32u), blv = *(const u32x4*)(bl + kk + (q0 + u) * 32u);
-            const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
-            c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bhv), c, 0, 0, 0);
-            c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, blv), c, 0, 0, 0);
-          }
-        }
-      }
-    }
-  };
-  for (uint32_t tile = 0; tile < ntile; ++tile) {
-    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
-    // (the very first round is already under way: requested before the event wait.  Requesting
-    // each next tile's first round before the conversion and the barrier was measured: no gain.)
-    if (tile + 1 < ntile) stage_issue(tile + 1);   // in flight during this tile's arithmetic
-    const uint16_t* ch = xh + (size_t)(tile & 1u) * xplane;
-    const uint16_t* cl = xl + (size_t)(tile & 1u) * xplane;
-    // ---- this wavefront's tiles x its slice of the input tile
-    const uint32_t s_lo = my_slice * slice_len, s_hi = min(s_lo + slice_len, (klen + 31u) & ~31u);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t rt = my_rt0 + (uint32_t)j * 8u;
-      if (rt < nrt && (ks == 1u || j == 0) && s_lo < s_hi) {
-        const uint16_t* wp = row_ptr(rt);
-        const uint16_t* bh = ch + (size_t)(frow % nb) * xstride + fk;
-        const uint16_t* bl = cl + (size_t)(frow % nb) * xstride + fk;
-        for (uint32_t kk = s_lo; kk < s_hi; kk += 32u * kMfmaRound) {
-          if (!(tile == 0 && j == 0 && kk == s_lo)) request(wp, k0, kk);
-          consume(acc[j], bh, bl, kk, s_hi);
-        }
-      }
-    }
-    if (tile + 1 < ntile) stage_write(tile + 1);   // into the other buffer: nobody reads it now
-    lds_barrier();
-  }
-  trace_mark(a, t, 8);
-  // ---- partial tiles -> LDS.  part[wave][j][row 0..15][col 0..15]
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) part[((wave * 4 + j) * 16 + (lane >> 4) * 4 + i) * 16 + (lane & 15)] = acc[j][i];
-  if (pro_norm) {
-    float rowsum = 0.f;   // lane b: this wavefront's sum of squares of row b
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const float v = wave_sum(sqq[q]);
-      if ((uint32_t)lane == ((uint32_t)q >> sh)) rowsum += v;
-    }
-    if (lane < 16) ssq[wave * 16 + lane] = rowsum;
-  }
-  lds_barrier();
-  trace_mark(a, t, 3);
-  // ---- all wavefronts: add the K slices in order, epilogue, outputs; then the notification
-  float* inv_lds = ssq + 8 * 16;   // [16] 1/rms of each batch row
-  if (pro_norm) {
-    if (threadIdx.x < 16) {
-      float ss = 0.f;
-#pragma unroll
-      for (int w = 0; w < 8; ++w) ss += ssq[w * 16 + threadIdx.x];
-      inv_lds[threadIdx.x] = 1.0f / sqrtf(ss / (float)K + t.f0);
-    }
-    lds_barrier();
-  }
-  {
-    float* outp = (t.flags & TF_OUT_LOGITS) ? a.logits : t.out;
-    auto dot_of = [&](uint32_t r, uint32_t bb) {   // ring row r, batch column bb
-      const uint32_t rt = r >> 4, row = r & 15u;
-      float v = 0.f;
-      if (ks == 1u) {
-        v = part[(((rt & 7u) * 4 + (rt >> 3)) * 16 + row) * 16 + bb];
-      } else {
-        for (uint32_t sl = 0; sl < ks; ++sl) v += part[(((sl * nrt2 + rt) * 4) * 16 + row) * 16 + bb];
-      }
-      return v;
-    };
-    for (uint32_t i = threadIdx.x; i < ncols * nb; i += kThreads) {
-      const uint32_t cc = i / nb, bb = i % nb;
-      const float inv = pro_norm ? inv_lds[bb] : 1.0f;
-      float v;
-      if (gateup) {
-        const float gte = dot_of(2 * cc, bb) * inv, up = dot_of(2 * cc + 1, bb) * inv;
-        v = gte / (1.0f + expf(-gte)) * up;
-      } else {
-        v = dot_of(cc, bb) * inv;
-      }
-      if ((t.flags & TF_EPI_RESID) && !splitk) v = res_lds[cc * 16 + bb] + v;
-      st_act(outp + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc, v);   // split-K: the partial sums of this part
-    }
-  }
-  if (MEGA || splitk) {
-    // every wavefront's coherent stores complete before anyone is told
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    lds_barrier();
-  }
-  if (wave == 0) {
-    if (splitk) {
-      // arrival at the row block's counter now that the partial sums are visible; the last of the
-      // `parts` tasks adds the parts in order, and the residual, into the real output
-      uint32_t last = 0;
-      if (lane == 0) {
-        const uint32_t old = __hip_atomic_fetch_add(as_global(a.g->grp_counters + t.p2), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        last = ((old + 1u) % parts == 0u) ? 1u : 0u;   // every step adds exactly `parts` (also when a captured launch is replayed with its step number frozen)
-      }
-      last = __builtin_amdgcn_readfirstlane(last);
-      if (last) {
-        float* xout = (float*)t.aux0;
-        for (uint32_t i = lane; i < ncols * nb; i += 64) {
-          const uint32_t cc = i / nb, bb = i % nb;
-          float v = ld_act(t.in2 + (size_t)(t.b0 + bb) * Hs + row0 + cc);
-          for (uint32_t pp = 0; pp < parts; ++pp) v += ld_act(t.out + (size_t)(t.b0 + bb) * t.ld_out + pp * Hs + row0 + cc);
-          st_act(xout + (size_t)(t.b0 + bb) * Hs + row0 + cc, v);
-        }
-      }
-    }
-    if (MEGA && t.trig_event >= 0) signal_from_wave0(a, t, t.trig_event, lane);
-    trace_mark(a, t, 4);
-  }
-  lds_barrier();   // the partial buffer is reused by the next task
-  return kLinDone;
-}
-
-// ------------------------------------------------------------------------------ mixture of experts
-// Section 6.4: an MoE block is a chain of tasks in the same graph.  `route` turns the router's
-// output into the meta-tensor (layout next to moe_meta_words); expert tasks are fixed at compile
-// time and use the meta-tensor to split the active experts' weight rows evenly among themselves
-// at run time; token rows are gathered while the input is staged (no separate gather step).
-__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v = min(v, (uint32_t)__shfl_xor((int)v, off, 64));
-  return v;
-}
-
-// One task.  Softmax over all experts in fp32, the top_k largest probabilities (ties: lower expert
-// index), renormalised to sum one; ranks of a token's experts are in ascending expert index.
-__device__ __forceinline__ void body_moe_route(const TaskDesc& t, const StepArgs& a, float* lds) {
-  const int lane = threadIdx.x & 63;
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const uint32_t E = t.p0, TK = t.p1, B = t.p2, P = B * TK;
-  uint32_t* sel = (uint32_t*)lds;          // [P] expert of pair p
-  float* wsel = lds + P;                   // [P] weight of pair p
-  uint32_t* cnt = (uint32_t*)(lds + 2 * P);   // [E]
-  uint32_t* off = cnt + E;                 // [E]
-  uint32_t* tokmask = off + E;             // [E] bit b: token b is routed to the expert (batch <= 16)
-  uint32_t* pairof = tokmask + E;          // [E][16] pair index of (expert, token)
-  uint32_t* meta = (uint32_t*)t.out;
-  constexpr int kPerLane = (int)(kMoeMaxExperts / 64);
-  const uint32_t nper = (E + 63u) / 64u;   // experts per lane actually present (uniform)
-  for (uint32_t p2 = threadIdx.x; p2 < P; p2 += kThreads) {   // a token whose router output is not finite selects nothing
-    sel[p2] = 0xFFFFFFFFu;
-    wsel[p2] = 0.f;
-  }
-  for (uint32_t e = threadIdx.x; e < E; e += kThreads) tokmask[e] = 0u;
-  lds_barrier();
-  for (uint32_t tok = wave; tok < B; tok += kThreads / 64) {
-    float pr[kPerLane];
-    float m = -INFINITY;
-#pragma unroll
-    for (int i = 0; i < kPerLane; ++i) {
-      const uint32_t e = (uint32_t)lane + 64u * i;
-      pr[i] = -INFINITY;
-      if ((uint32_t)i < nper && e < E) pr[i] = ld_act(t.in + (size_t)tok * t.ld_in + e);
-      m = fmaxf(m, pr[i]);
-    }
-    m = wave_max(m);
-    float l = 0.f;
-#pragma unroll
-    for (int i = 0; i < kPerLane; ++i) {
-      const uint32_t e = (uint32_t)lane + 64u * i;
-      const float lg = pr[i];
-      pr[i] = 0.f;
-      if ((uint32_t)i < nper && e < E) pr[i] = expf(lg - m);
-      l += pr[i];
-    }
-    l = wave_sum(l);
-#pragma unroll
-    for (int i = 0; i < kPerLane; ++i)
-      if ((uint32_t)i < nper) pr[i] = pr[i] / l;
-    uint32_t taken = 0;   // bit i: this lane's expert lane + 64 i is selected
-    for (uint32_t j = 0; j < TK; ++j) {
-      float best = -1.f;
-      uint32_t best_e = 0xFFFFFFFFu;
-#pragma unroll
-      for (int i = 0; i < kPerLane; ++i) {
-        const uint32_t e = (uint32_t)lane + 64u * i;
-        if ((uint32_t)i < nper && e < E && !((taken >> i) & 1u) && pr[i] > best) { best = pr[i]; best_e = e; }   // ascending e: ties keep the lower
-      }
-      const float wbest = wave_max(best);
-      const uint32_t we = wave_min_u32(best == wbest ? best_e : 0xFFFFFFFFu);
-      if (we != 0xFFFFFFFFu && (we & 63u) == (uint32_t)lane) taken |= 1u << (we >> 6);
-    }
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < kPerLane; ++i) s += ((taken >> i) & 1u) ? pr[i] : 0.f;
-    s = wave_sum(s);
-    uint32_t before = 0;   // selected experts with a smaller index, so far
-#pragma unroll
-    for (int i = 0; i < kPerLane; ++i) {
-      const bool mine = (taken >> i) & 1u;
-      const uint64_t mask = __ballot(mine);
-      if (mine) {
-        const uint32_t rank = before + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-        sel[tok * TK + rank] = (uint32_t)lane + 64u * i;
-        wsel[tok * TK + rank] = pr[i] / s;
-      }
-      before += (uint32_t)__popcll(mask);
-    }
-  }
-  lds_barrier();
-  // Per-expert token lists without serial scans: a pair thread sets its token's bit in the
-  // expert's mask and leaves its pair index in the expert's row of `pairof`; the expert's list
-  // is then its mask's bits in ascending order.
-  for (uint32_t p2 = threadIdx.x; p2 < P; p2 += kThreads) {
-    const uint32_t e = sel[p2], tok = p2 / TK;
-    if (e < E) {
-      atomicOr(&tokmask[e], 1u << tok);
-      pairof[e * 16u + tok] = p2;
-    }
-  }
-  lds_barrier();
-  // offsets and the active list: exclusive scans over the experts by wavefront 0, each lane
-  // owning kPerLane consecutive experts
-  if (wave == 0) {
-    uint32_t c[kPerLane], mine = 0, act = 0, mx = 0;
-#pragma unroll
-    for (int i = 0; i < kPerLane; ++i) {
-      const uint32_t e = (uint32_t)lane * kPerLane + i;
-      c[i] = e < E ? (uint32_t)__popc(tokmask[e]) : 0u;
-      mine += c[i];
-      act += c[i] ? 1u : 0u;
-      mx = max(mx, c[i]);
-    }
-    uint32_t run = mine, arun = act;   // inclusive scans across lanes
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const uint32_t v = (uint32_t)__shfl_up((int)run, d, 64), w = (uint32_t)__shfl_up((int)arun, d, 64);
-      if (lane >= d) { run += v; arun += w; }
-    }
-    uint32_t o = run - mine, ai = arun - act;
-#pragma unroll
-    for (int i = 0; i < kPerLane; ++i) {
-      const uint32_t e = (uint32_t)lane * kPerLane + i;
-      if (e < E) {
-        cnt[e] = c[i];
-        off[e] = o;
-        if (c[i]) st_act_u32(meta + 2 + ai++, e);
-        o += c[i];
-      }
-    }
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, d, 64));
-    if (lane == 63) {
-      st_act_u32(meta, arun);
-      st_act_u32(meta + 1, mx);
-    }
-  }
-  lds_barrier();
-  for (uint32_t e = threadIdx.x; e < E; e += kThreads) {
-    st_act_u32(meta + 2 + E + e, cnt[e]);
-    st_act_u32(meta + 2 + 2 * E + e, off[e]);
-    uint32_t o = off[e], m = tokmask[e];
-    while (m) {   // ascending token = ascending pair
-      const uint32_t tok = (uint32_t)__ffs((int)m) - 1u;
-      m &= m - 1u;
-      st_act_u32(meta + 2 + 3 * E + o++, pairof[e * 16u + tok]);
-    }
-  }
-  for (uint32_t p2 = threadIdx.x; p2 < P; p2 += kThreads) {
-    st_act_u32(meta + 2 + 3 * E + P + p2, __float_as_uint(wsel[p2]));
-    st_act_u32(meta + 2 + 3 * E + 2 * P + p2, sel[p2]);
-  }
-}
-
-// `ntile` 16-row tiles of one expert's weight matrix, starting at tile `tile0`, times the `ne`
-// token rows routed to that expert: the matrix-core scheme of linear_task_mfma with the input rows
-// gathered through the expert's pair list.  All wavefronts take part; ntile <= 32, ne <= 16.
-__device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs& a, float* lds, const uint16_t* W,
-                                               uint32_t tile0, uint32_t ntile, uint32_t ne, const uint32_t* plist,
-                                               uint32_t TK) {
-  const int lane = threadIdx.x & 63;
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const uint32_t K = t.K;
-  const uint32_t gateup = (t.flags & TF_GATEUP) ? 1u : 0u;
-  const bool pro_norm = t.flags & TF_PRO_NORM;
-  const uint32_t Kt = mfma_ktile(ne), xstride = Kt + 8u, xplane = ne * xstride;
-  uint16_t* xh = (uint16_t*)lds;
-  uint16_t* xl = xh + 2 * (size_t)xplane;
-  float* part = lds;
-  float* ssq = lds + moe_x_floats(a.g->batch);   // [8][16]
-  uint32_t* rowidx = (uint32_t*)(ssq + 8 * 16);  // [16] pair of each staged row (= output row)
-  uint32_t* rowin = rowidx + 16;                 // [16] input row: gate/up reads the token's row, down the pair's
-  if (threadIdx.x < ne) {
-    const uint32_t pair = ld_relaxed(plist + threadIdx.x);
-    rowidx[threadIdx.x] = pair;
-    rowin[threadIdx.x] = gateup ? pair / TK : pair;
-  }
-  lds_barrier();
-  uint32_t nrt2 = 1;
-  while (nrt2 < ntile && nrt2 < 8u) nrt2 <<= 1;
-  const uint32_t ks = 8u / nrt2, my_slice = wave / nrt2, my_rt0 = wave % nrt2, slice_len = Kt / ks;
-  const uint32_t frow = lane & 15u, fk = (uint32_t)(lane >> 4) * 8u;
-  f32x4 acc[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  constexpr int kRound = 16;   // 16 KB per wavefront in flight (32 was measured slower)
-  u32x4 wfrag[kRound];
-  auto row_ptr = [&](uint32_t rt) {
-    const uint32_t r = (tile0 + rt) * 16u + frow;   // row of the expert's gate/up-interleaved (or plain) order
-    const uint32_t wrow = gateup ? ((r >> 1) + ((r & 1u) ? t.p0 : 0u)) : r;
-    return W + (size_t)wrow * K + fk;
-  };
-  auto request = [&](const uint16_t* wp, uint32_t k0, uint32_t kk) {
-#pragma unroll
-    for (int q = 0; q < kRound; ++q) {
-      const uint32_t k = min(k0 + kk + q * 32u, K - fk - 8u);
-      wfrag[q] = ld_stream16(wp + k);
-    }
-  };
-  // input staging as in linear_task_mfma (slot q = row q >> sh), rows gathered through the pair list
-  const uint32_t sh = Kt == 2048u ? 1u : 0u;
-  float sqq[16];
-#pragma unroll
-  for (int q = 0; q < 16; ++q) sqq[q] = 0.f;
-  const uint16_t* gain = (const uint16_t*)t.w2;
-  const uint32_t ntk = (K + Kt - 1u) / Kt;
-  float2 sv[16];
-  auto stage_issue = [&](uint32_t tile) {
-    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const uint32_t b = (uint32_t)q >> sh, i = (((uint32_t)q & sh) << 9) + threadIdx.x;
-      sv[q] = make_float2(0.f, 0.f);
-      if (b < ne && 2 * i < klen) sv[q] = ld_act2(t.in + (size_t)rowin[b] * t.ld_in + k0 + 2 * i);
-    }
-  };
-  auto stage_write = [&](uint32_t tile) {
-    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
-    uint16_t* dh = xh + (size_t)(tile & 1u) * xplane;
-    uint16_t* dl = xl + (size_t)(tile & 1u) * xplane;
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const uint32_t b = (uint32_t)q >> sh, i = (((uint32_t)q & sh) << 9) + threadIdx.x;
-      if (b < ne) {
-        float2 w2 = sv[q];
-        if (pro_norm && 2 * i < klen) {
-          sqq[q] = fmaf(w2.x, w2.x, fmaf(w2.y, w2.y, sqq[q]));
-          const uint32_t g2 = *as_global((const uint32_t*)(gain + k0 + 2 * i));
-          w2.x *= bf16_lo(g2);
-          w2.y *= bf16_hi(g2);
-        }
-        uint32_t hi, lo;
-        split_hi_lo(w2.x, w2.y, &hi, &lo);
-        *(uint32_t*)(dh + (size_t)b * xstride + 2 * i) = hi;
-        *(uint32_t*)(dl + (size_t)b * xstride + 2 * i) = lo;
-      }
-    }
-  };
-  for (uint32_t tile = 0; tile < ntk; ++tile) {
-    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
-    // An expert's input is nearly always a single tile (up to 8 tokens x 2048 inputs), so the
-    // staging is not overlapped with the multiplies here: its registers are then free during the
-    // multiply loop, which is what this function is short of.
-    stage_issue(tile);
-    stage_write(tile);
-    lds_barrier();
-    const uint16_t* ch = xh + (size_t)(tile & 1u) * xplane;
-    const uint16_t* cl = xl + (size_t)(tile & 1u) * xplane;
-    const uint32_t s_lo = my_slice * slice_len, s_hi = min(s_lo + slice_len, (klen + 31u) & ~31u);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t rt = my_rt0 + (uint32_t)j * 8u;
-      if (rt < ntile && (ks == 1u || j == 0) && s_lo < s_hi) {
-        const uint16_t* wp = row_ptr(rt);
-        const uint16_t* bh = ch + (size_t)(frow % ne) * xstride + fk;
-        const uint16_t* bl = cl + (size_t)(frow % ne) * xstride + fk;
-        for (uint32_t kk = s_lo; kk < s_hi; kk += 32u * kRound) {
-          request(wp, k0, kk);
-#pragma unroll
-          for (int q0 = 0; q0 < kRound; q0 += 4) {
-            if (kk + (q0 + 4) * 32u <= s_hi) {   // four steps without per-step tests, their LDS reads first
-              u32x4 hv[4], lv[4];
-#pragma unroll
-              for (int u = 0; u < 4; ++u) {
-                hv[u] = *(const u32x4*)(bh + kk + (q0 + u) * 32u);
-                lv[u] = *(const u32x4*)(bl + kk + (q0 + u) * 32u);
-              }
-#pragma unroll
-              for (int u = 0; u < 4; ++u) {
-                const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, hv[u]), acc[j], 0, 0, 0);
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, lv[u]), acc[j], 0, 0, 0);
-              }
-            } else {
-#pragma unroll
-              for (int u = 0; u < 4; ++u) {
-                if (kk + (q0 + u) * 32u < s_hi) {
-                  const u32x4 bhv = *(const u32x4*)(bh + kk + (q0 + u) * 32u), blv = *(const u32x4*)(bl + kk + (q0 + u) * 32u);
-                  const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
-                  acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bhv), acc[j], 0, 0, 0);
-                  acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, blv), acc[j], 0, 0, 0);
-                }
-              }
-            }
-          }
-        }
-      }
-    }
-  }
-  lds_barrier();   // the partial tiles reuse the input buffers
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) part[((wave * 4 + j) * 16 + (lane >> 4) * 4 + i) * 16 + (lane & 15)] = acc[j][i];
-  if (pro_norm) {
-    float rowsum = 0.f;   // lane b: this wavefront's sum of squares of staged row b
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const float v = wave_sum(sqq[q]);
-      if ((uint32_t)lane == ((uint32_t)q >> sh)) rowsum += v;
-    }
-    if (lane < 16) ssq[wave * 16 + lane] = rowsum;
-  }
-  lds_barrier();
-  auto dot_of = [&](uint32_t r, uint32_t bb) {
-    const uint32_t rt = r >> 4, row = r & 15u;
-    float v = 0.f;
-    if (ks == 1u) {
-      v = part[(((rt & 7u) * 4 + (rt >> 3)) * 16 + row) * 16 + bb];
-    } else {
-      for (uint32_t sl = 0; sl < ks; ++sl) v += part[(((sl * nrt2 + rt) * 4) * 16 + row) * 16 + bb];
-    }
-    return v;
-  };
-  const uint32_t ncols = (ntile * 16u) >> gateup, col0 = (tile0 * 16u) >> gateup;
-  for (uint32_t i = threadIdx.x; i < ncols * ne; i += kThreads) {
-    const uint32_t cc = i / ne, bb = i % ne;
-    float inv = 1.0f;
-    if (pro_norm) {
-      float ss = 0.f;
-#pragma unroll
-      for (int w = 0; w < 8; ++w) ss += ssq[w * 16 + bb];
-      inv = 1.0f / sqrtf(ss / (float)K + t.f0);
-    }
-    float v;
-    if (gateup) {
-      const float gte = dot_of(2 * cc, bb) * inv, up = dot_of(2 * cc + 1, bb) * inv;
-      v = gte / (1.0f + expf(-gte)) * up;
-    } else {
-      v = dot_of(cc, bb);
-    }
-    st_act(t.out + (size_t)rowidx[bb] * t.ld_out + col0 + cc, v);
-  }
-  lds_barrier();   // the next job reuses the buffers
-}
-
-// Expert task `c0` of `p1`: the active experts' 16-row weight tiles, laid end to end in ascending
-// expert order, are dealt evenly to the expert tasks (the run-time refinement of Section 6.4);
-// a task's share is worked off in jobs of at most 32 tiles that stay inside one expert.
-__device__ __forceinline__ void body_moe_expert(const TaskDesc& t, const StepArgs& a, float* lds) {
-  const uint32_t* meta = (const uint32_t*)t.in2;
-  const uint32_t E = t.p3 & 0xFFFFu, TK = t.p3 >> 16, NT = t.p1, rows_per_expert = t.p2;
-  const uint32_t tiles_per_expert = rows_per_expert / 16u;
-  const uint32_t n_active = __builtin_amdgcn_readfirstlane(ld_relaxed(meta));
-  const uint32_t total = n_active * tiles_per_expert;
-  uint32_t u0 = (uint32_t)((uint64_t)total * t.c0 / NT);
-  const uint32_t u1 = (uint32_t)((uint64_t)total * (t.c0 + 1u) / NT);
-  while (u0 < u1) {
-    const uint32_t ai = u0 / tiles_per_expert, tile0 = u0 % tiles_per_expert;
-    const uint32_t ntile = min(min(u1 - u0, tiles_per_expert - tile0), 32u);
-    const uint32_t e = __builtin_amdgcn_readfirstlane(ld_relaxed(meta + 2 + ai));
-    const uint32_t ne = __builtin_amdgcn_readfirstlane(ld_relaxed(meta + 2 + E + e));
-    const uint32_t po = __builtin_amdgcn_readfirstlane(ld_relaxed(meta + 2 + 2 * E + e));
-    if (e >= E || ne == 0 || ne > 16u || po + ne > a.g->batch * TK) {   // never index with a damaged meta-tensor
-      if (threadIdx.x == 0) report(a, DE_BAD_META, e, ne);
-      return;
-    }
-    const uint16_t* W = (const uint16_t*)t.w + (size_t)e * rows_per_expert * t.K;
-    moe_expert_job(t, a, lds, W, tile0, ntile, ne, meta + 2 + 3 * E + po, TK);
-    u0 += ntile;
-  }
-}
-
-// out[b][c] = resid[b][c] + sum over the token's experts, in ascending expert index, of
-// weight x expert output.
-__device__ __forceinline__ void body_moe_combine(const TaskDesc& t, const StepArgs& a) {
-  const uint32_t E = t.p0, TK = t.p1, P = a.g->batch * TK, H = t.ld_out;
-  const uint32_t* meta = (const uint32_t*)t.aux0;
-  for (uint32_t b = t.b0; b < t.b1; ++b) {
-    for (uint32_t c = t.c0 + threadIdx.x; c < t.c1; c += kThreads) {
-      float acc = 0.f;
-      for (uint32_t k = 0; k < TK; ++k) {
-        const uint32_t p = b * TK + k;
-        const float wk = __uint_as_float(ld_relaxed(meta + 2 + 3 * E + P + p));
-        acc = fmaf(wk, ld_act(t.in + (size_t)p * t.ld_in + c), acc);
-      }
-      st_act(t.out + (size_t)b * H + c, ld_act(t.in2 + (size_t)b * H + c) + acc);
-    }
-  }
-}
-
-// cos and sin of position * inv_freq[i]: the angle is formed and reduced to [-pi, pi] in double.
-__device__ __forceinline__ void rope_cs(const StepArgs& a, int32_t pos, uint32_t i, float* c, float* s) {
-  double ang = (double)pos * as_global(a.g->inv_freq)[i];
-  const double two_pi = 6.283185307179586476925286766559;
-  ang -= two_pi * rint(ang / two_pi);
-  double sd, cd;
-  sincos(ang, &sd, &cd);
-  *c = (float)cd;
-  *s = (float)sd;
-}
-
-// Sum over an aligned group of N adjacent lanes (N a power of two <= 64); every lane gets it.
-template <int N>
-__device__ __forceinline__ float lane_group_sum(float v) {
-#pragma unroll
-  for (int off = N / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
-
-// T3: rotate q and k heads by the sequence position (half-split pairing), copy v, and append the
-// new k and v rows to the cache as bf16.  Angles are evaluated in double precision.
-__device__ __forceinline__ void body_rope(const TaskDesc& t, const StepArgs& a) {
-  const uint32_t d = a.g->head_dim, half = d / 2, nq = a.g->n_q, nkv = a.g->n_kv;
-  const uint32_t s0 = t.c0 / d, s1 = t.c1 / d;
-  for (uint32_t b = t.b0; b < t.b1; ++b) {
-    int32_t pos = a.positions[b] + (int32_t)a.step;
-    if (pos < 0 || (uint32_t)pos >= a.g->max_seq) {
-      if (threadIdx.x == 0) report(a, DE_BAD_POSITION, b, (uint32_t)pos);
-      continue;
-    }
-    const float* src = t.in + (size_t)b * t.ld_in;
-    float* dst = t.out + (size_t)b * t.ld_out;
-    // each thread owns two adjacent rotation pairs (i, i+1) so that cache rows are written as
-    // 4-byte (two bf16) coherent stores
-    for (uint32_t idx = threadIdx.x; idx < (s1 - s0) * (half / 2); idx += kThreads) {
-      uint32_t s = s0 + idx / (half / 2), i = 2 * (idx % (half / 2));
-      float2 lo = ld_act2(src + s * d + i), hi = ld_act2(src + s * d + i + half);
-      if ((t.flags & TF_QK_NORM) && s < nq + nkv) {
-        // RMSNorm over the head first: its half/2 threads are one aligned group of lanes
-        float ss = lo.x * lo.x + lo.y * lo.y + hi.x * hi.x + hi.y * hi.y;
-        ss = (half / 2 == 32) ? lane_group_sum<32>(ss) : lane_group_sum<16>(ss);
-        const float inv = 1.0f / sqrtf(ss / (float)d + t.f0);
-        const uint16_t* gn = (const uint16_t*)(s < nq ? t.w : t.w2);
-        const uint32_t g0 = *as_global((const uint32_t*)(gn + i)), g1 = *as_global((const uint32_t*)(gn + i + half));
-        lo.x *= inv * bf16_lo(g0); lo.y *= inv * bf16_hi(g0);
-        hi.x *= inv * bf16_lo(g1); hi.y *= inv * bf16_hi(g1);
-      }
-      float r[4];   // lo.x, lo.y, hi.x, hi.y after rotation
-      if (s < nq + nkv) {
-        float u0[2] = {lo.x, lo.y}, u1[2] = {hi.x, hi.y};
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          float c, sn;
-          rope_cs(a, pos, i + e, &c, &sn);
-          r[e] = u0[e] * c - u1[e] * sn;
-          r[2 + e] = u1[e] * c + u0[e] * sn;
-        }
-      } else {
-        r[0] = lo.x; r[1] = lo.y; r[2] = hi.x; r[3] = hi.y;
-      }
-      st_act(dst + s * d + i, r[0]);
-      st_act(dst + s * d + i + 1, r[1]);
-      st_act(dst + s * d + i + half, r[2]);
-      st_act(dst + s * d + i + half + 1, r[3]);
-      if (s >= nq) {
-        bool is_k = s < nq + nkv;
-        uint32_t g = is_k ? s - nq : s - nq - nkv;
-        uint16_t* cache = (uint16_t*)(is_k ? t.aux0 : t.aux1);
-        uint16_t* row = cache + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
-        st_act_u32((uint32_t*)(row + i), (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16));
-        st_act_u32((uint32_t*)(row + i + half), (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16));
-      }
-    }
-  }
-}
-
-// Sum over the LPP (8 or 16) adjacent lanes that share one cache position, with DPP lane
-// permutations (register-to-register, no LDS round trip); every lane gets the sum.
-template <int LPP>
-__device__ __forceinline__ float group_sum(float v) {
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // lane ^ 1
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // lane ^ 2
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // mirror in 8
-  if (LPP == 16)
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // mirror in 16
-  return v;
-}
-
-// T4, short chunks: the same task when a chunk never exceeds kAttnRounds rounds (8 x 32 = 256 cache
-// positions at head_dim 128): all of its K and V rows are requested before the event wait and
-// stay in registers, scores are formed once, one chunk-wide maximum, one exp per score.  Fewer
-// instructions than the running-softmax body below; the decoder at batch 1 spends its attention
-// phase on latency, not bandwidth, so that is what counts there.
-// Layout of the work: D/8 adjacent lanes share one position (16 bytes of the row each), a
-// wavefront covers 64/(D/8) positions per round, the 8 wavefronts of the workgroup take rounds
-// of 8 x that many positions; kAttnRounds rounds fit in registers and the compiler picks the chunk
-// count so that a chunk never exceeds them.
-// Cache rows of earlier steps are immutable during a step, so the task requests its K and V rows
-// BEFORE it waits for its dependent event; only the query (and the row appended this step)
-// arrive later.  Scores, probabilities and the running sums stay in registers.
-constexpr int kAttnRounds = 8;
-
-template <int D, int GRP>
-__device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const StepArgs& a, float* lds,
-                                                  int32_t wait_ev, uint32_t* s_flag) {
-  constexpr uint32_t d = D, grp = GRP, LPP = D / 8, PPW = 64 / LPP, NW = kThreads / 64;
-  constexpr uint32_t stride = NW * PPW, per = grp * (d + 2);
-  constexpr uint32_t WS = d + 4;   // row of one partial in LDS: output, max, sum; 16-byte aligned rows
-  const uint32_t nq = a.g->n_q, nkv = a.g->n_kv, C = t.p1;
-  const uint32_t b = t.b0, u = t.c0 / per, g = u / C, c = u % C;
-  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  float* qs = lds;                       // [grp][d]
-  float* wpart = qs + grp * d;           // [NW * PPW][grp][WS]: partial output and sum per position slot
-  uint32_t* flag = (uint32_t*)(wpart + stride * grp * WS);    // then [16..) the maxima exchange
-  float* outp = t.out + (size_t)b * t.ld_out + t.c0;
-  const int32_t pos = a.positions[b] + (int32_t)a.step;    // written by the host before the launch
-  const bool bad_pos = pos < 0 || (uint32_t)pos >= a.g->max_seq;
-  const uint32_t len = bad_pos ? 0u : (uint32_t)pos + 1;
-  const uint32_t t0 = (uint32_t)((uint64_t)c * len / C), t1 = (uint32_t)((uint64_t)(c + 1) * len / C);
-  const uint32_t n = t1 - t0;
-  const uint16_t* Kb = (const uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.g->max_seq + t0) * d;
-  const uint16_t* Vb = (const uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.g->max_seq + t0) * d;
-  const uint32_t sub = lane % LPP, slot = lane / LPP;
-  const uint32_t i_first = wave * PPW + slot;
-  const uint32_t n_rounds = (n + stride - 1) / stride;
-  // ---- pre-load: K and V rows of earlier steps
-  u32x4 kreg[kAttnRounds], vreg[kAttnRounds];
-#pragma unroll
-  for (int r = 0; r < kAttnRounds; ++r) {
-    const uint32_t i = i_first + r * stride;
-    kreg[r] = u32x4{0, 0, 0, 0};
-    vreg[r] = u32x4{0, 0, 0, 0};
-    if (i < n && t0 + i != (uint32_t)pos) {
-      kreg[r] = ld_stream16(Kb + (size_t)i * d + sub * 8);
-      vreg[r] = ld_stream16(Vb + (size_t)i * d + sub * 8);
-    }
-  }
-  if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
-  trace_mark(a, t, 1);
-  if (bad_pos || n_rounds > (uint32_t)kAttnRounds) {
-    if (threadIdx.x == 0) report(a, DE_BAD_POSITION, b, (uint32_t)pos);
-    for (uint32_t i = threadIdx.x; i < per; i += kThreads) st_act(outp + i, ((i % (d + 2)) == d) ? -INFINITY : 0.f);
-    return true;
-  }
-  const float* qsrc = t.in + (size_t)b * t.ld_in + (size_t)g * grp * d;
-  if (t.flags & TF_ROPE_FUSED) {
-    // the input is the raw QKV projection: rotate the group's query heads here; the task of the
-    // last chunk also rotates this step's key, and appends key and value to the cache
-    constexpr uint32_t half = d / 2;
-    const bool qk_norm = t.flags & TF_QK_NORM;
-    for (uint32_t i = threadIdx.x; i < grp * half; i += kThreads) {
-      uint32_t j = i / half, e = i % half;
-      float u0 = ld_act(qsrc + j * d + e), u1 = ld_act(qsrc + j * d + e + half), cs, sn;
-      if (qk_norm) {   // RMSNorm over the head: its `half` threads are one aligned group of lanes
-        const float inv = 1.0f / sqrtf(lane_group_sum<(int)half>(u0 * u0 + u1 * u1) / (float)d + t.f0);
-        const uint16_t* gq = (const uint16_t*)t.w;
-        u0 *= inv * bf16_to_f32(as_global(gq)[e]);
-        u1 *= inv * bf16_to_f32(as_global(gq)[e + half]);
-      }
-      rope_cs(a, pos, e, &cs, &sn);
-      qs[j * d + e] = u0 * cs - u1 * sn;
-      qs[j * d + e + half] = u1 * cs + u0 * sn;
-    }
-    if (c == C - 1) {
-      const float* ksrc = t.in + (size_t)b * t.ld_in + (size_t)(nq + g) * d;
-      const float* vsrc = t.in + (size_t)b * t.ld_in + (size_t)(nq + nkv + g) * d;
-      uint16_t* krow = (uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
-      uint16_t* vrow = (uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
-      // threads from the top of the workgroup, so that they do not also rotate query pairs
-      for (uint32_t i = kThreads - 1 - threadIdx.x; i < half / 2 + half; i += kThreads) {
-        if (i < half / 2) {   // two adjacent rotation pairs of the key
-          uint32_t e = 2 * i;
-          float2 lo = ld_act2(ksrc + e), hi = ld_act2(ksrc + e + half);
-          if (qk_norm) {   // the key's half/2 threads: one aligned group of lanes at the top of the workgroup
-            const float ss = lane_group_sum<(int)(half / 2)>(lo.x * lo.x + lo.y * lo.y + hi.x * hi.x + hi.y * hi.y);
-            const float inv = 1.0f / sqrtf(ss / (float)d + t.f0);
-            const uint16_t* gk = (const uint16_t*)t.w2;
-            const uint32_t g0 = *as_global((const uint32_t*)(gk + e)), g1 = *as_global((const uint32_t*)(gk + e + half));
-            lo.x *= inv * bf16_lo(g0); lo.y *= inv * bf16_hi(g0);
-            hi.x *= inv * bf16_lo(g1); hi.y *= inv * bf16_hi(g1);
-          }
-          float c0, s0, c1, s1;
-          rope_cs(a, pos, e, &c0, &s0);
-          rope_cs(a, pos, e + 1, &c1, &s1);
-          float r0 = lo.x * c0 - hi.x * s0, r1 = lo.y * c1 - hi.y * s1;
-          float r2 = hi.x * c0 + lo.x * s0, r3 = hi.y * c1 + lo.y * s1;
-          st_act_u32((uint32_t*)(krow + e), (uint32_t)f32_to_bf16(r0) | ((uint32_t)f32_to_bf16(r1) << 16));
-          st_act_u32((uint32_t*)(krow + e + half), (uint32_t)f32_to_bf16(r2) | ((uint32_t)f32_to_bf16(r3) << 16));
-        } else {              // two adjacent value elements
-          uint32_t e = 2 * (i - half / 2);
-          float2 v2 = ld_act2(vsrc + e);
-          st_act_u32((uint32_t*)(vrow + e), (uint32_t)f32_to_bf16(v2.x) | ((uint32_t)f32_to_bf16(v2.y) << 16));
-        }
-      }
-      // the appended row is read back below with coherent loads: the stores must have completed
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-  } else {
-    for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) qs[i] = ld_act(qsrc + i);
-  }
-  __syncthreads();
-  trace_mark(a, t, 2);
-  // The row appended during this step is read with coherent loads (it was written after the
-  // pre-load, by this or another workgroup); it can only be the last position of the last chunk.
-  if (c == C - 1) {
-    const uint32_t i_new = n - 1;
-#pragma unroll
-    for (int r = 0; r < kAttnRounds; ++r) {
-      if (i_first + r * stride == i_new) {
-        kreg[r] = ld_row16_coherent(Kb + (size_t)i_new * d + sub * 8);
-        vreg[r] = ld_row16_coherent(Vb + (size_t)i_new * d + sub * 8);
-      }
-    }
-  }
-  // ---- per block of HB heads (bounds the register footprint): scores, softmax statistics and
-  // P.V, all in registers; sreg[r][j] belongs to position i_first + r * stride, head jb + j
-  constexpr int HB = GRP < 4 ? GRP : 4;
-  const float inv_sqrt_d = 1.0f / sqrtf((float)d);
-  // The body is bound by vector instructions, not by memory (two wavefronts per SIMD, about a
-  // thousand instructions each for a full chunk): rounds the chunk does not reach are skipped.
-  // The count is the same in every lane (it comes from positions[b]); say so to the compiler.
-  const uint32_t n_rounds_u = __builtin_amdgcn_readfirstlane(n_rounds);
-  float* mxch = wpart + stride * grp * WS + 16;   // [NW][HB] maxima exchange
-  // scores are kept times log2(e): the probabilities are then one v_exp_f32 each
-  const float score_scale = inv_sqrt_d * 1.44269504088896341f;
-  float m_all[GRP];
-#pragma unroll 1
-  for (int jb = 0; jb < GRP; jb += HB) {
-    float q[HB][8];
-#pragma unroll
-    for (int j = 0; j < HB; ++j) {
-      const float4* qp = (const float4*)(qs + (jb + j) * d + sub * 8);
-      float4 q0 = qp[0], q1 = qp[1];
-      q[j][0] = q0.x; q[j][1] = q0.y; q[j][2] = q0.z; q[j][3] = q0.w;
-      q[j][4] = q1.x; q[j][5] = q1.y; q[j][6] = q1.z; q[j][7] = q1.w;
-    }
-    float sreg[kAttnRounds][HB];
-    float mloc[HB];
-#pragma unroll
-    for (int j = 0; j < HB; ++j) mloc[j] = -INFINITY;
-#pragma unroll
-    for (int r = 0; r < kAttnRounds; ++r) {
-      if ((uint32_t)r >= n_rounds_u) continue;   // (uniform) rounds past the chunk: nothing to do
-      const bool valid = i_first + r * stride < n;
-      const u32x4 kv = kreg[r];
-      const float k8[8] = {bf16_lo(kv.x), bf16_hi(kv.x), bf16_lo(kv.y), bf16_hi(kv.y),
-                           bf16_lo(kv.z), bf16_hi(kv.z), bf16_lo(kv.w), bf16_hi(kv.w)};
-#pragma unroll
-      for (int j = 0; j < HB; ++j) {
-        float sv = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) sv = fmaf(k8[e], q[j][e], sv);
-        sv = group_sum<LPP>(sv) * score_scale;
-        sreg[r][j] = valid ? sv : -INFINITY;
-        mloc[j] = fmaxf(mloc[j], sreg[r][j]);
-      }
-    }
-    // chunk maximum per head: across position slots, then across wavefronts
-#pragma unroll
-    for (int j = 0; j < HB; ++j) {
-#pragma unroll
-      for (uint32_t off = LPP; off < 64; off <<= 1) mloc[j] = fmaxf(mloc[j], __shfl_xor(mloc[j], off, 64));
-      if (lane == 0) mxch[wave * HB + j] = mloc[j];
-    }
-    __syncthreads();
-    float m[HB];
-#pragma unroll
-    for (int j = 0; j < HB; ++j) {
-      float v = mxch[j];
-#pragma unroll
-      for (uint32_t w = 1; w < NW; ++w) v = fmaxf(v, mxch[w * HB + j]);
-      m[j] = v;
-      m_all[jb + j] = v * 0.693147180559945309f;   // the partial's maximum is stored in natural units
-    }
-    // ---- probabilities and P.V
-    float acc[HB][8], lsum[HB];
-#pragma unroll
-    for (int j = 0; j < HB; ++j) {
-      lsum[j] = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[j][e] = 0.f;
-    }
-#pragma unroll
-    for (int r = 0; r < kAttnRounds; ++r) {
-      if ((uint32_t)r >= n_rounds_u) continue;
-      const u32x4 vv = vreg[r];
-      const float v8[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
-                           bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
-#pragma unroll
-      for (int j = 0; j < HB; ++j) {
-        const float p = (sreg[r][j] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sreg[r][j] - m[j]);
-        lsum[j] += p;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p, v8[e], acc[j][e]);
-      }
-    }
-    // every position slot's partial goes to LDS as it is (two 16-byte stores per head); the
-    // slots are added up below, by the threads that write the result.  (Adding them with lane
-    // shuffles first cost 4 instructions per value here, where instructions are what is scarce.)
-#pragma unroll
-    for (int j = 0; j < HB; ++j) {
-      float4* wp = (float4*)(wpart + ((size_t)(wave * PPW + slot) * grp + jb + j) * WS + sub * 8);
-      wp[0] = make_float4(acc[j][0], acc[j][1], acc[j][2], acc[j][3]);
-      wp[1] = make_float4(acc[j][4], acc[j][5], acc[j][6], acc[j][7]);
-      // every lane of a position group holds the same p: one of them stores the sum
-      if (sub == 0) wpart[((size_t)(wave * PPW + slot) * grp + jb + j) * WS + d + 1] = lsum[j];
-    }
-    __syncthreads();   // also protects mxch before the next block
-  }
-  trace_mark(a, t, 10);
-  for (uint32_t i = threadIdx.x; i < grp * (d + 2); i += kThreads) {
-    const uint32_t j = i / (d + 2), dim = i % (d + 2);
-    float sv;
-    if (dim == d) {
-      sv = m_all[0];
-#pragma unroll
-      for (int jj = 1; jj < GRP; ++jj) sv = (j == (uint32_t)jj) ? m_all[jj] : sv;
-    } else {
-      sv = 0.f;
-#pragma unroll
-      for (uint32_t w = 0; w < stride; ++w) sv += wpart[((size_t)w * grp + j) * WS + dim];
-    }
-    st_act(outp + i, sv);
-  }
-  trace_mark(a, t, 11);
-  if (t.flags & TF_ATTN_MERGE) {
-    // Arrival counter of (layer, sequence, KV head): the chunk task that arrives last sees all C
-    // partials complete and merges them (log-sum-exp, one pass with running maximum) into the
-    // attention output.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      uint32_t* cnt = a.g->grp_counters + t.p2 + b * nkv + g;
-      uint32_t old = __hip_atomic_fetch_add(as_global(cnt), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      *flag = ((old + 1u) % C == 0u) ? 1u : 0u;   // every step adds exactly C
-    }
-    __syncthreads();
-    if (*flag) {
-      const float* part = t.out + (size_t)b * t.ld_out + (size_t)g * C * per;
-      float* o = const_cast<float*>(t.in2) + (size_t)b * nq * d + (size_t)g * grp * d;
-      for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) {
-        uint32_t j = i / d, dim = i % d;
-        float M = -INFINITY, L = 0.f, acc_o = 0.f;
-        for (uint32_t c0 = 0; c0 < C; c0 += 8) {   // 24 coherent loads in flight: one round trip for 8 chunks
-          float mm[8], ll[8], oo[8];
-#pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            if (c0 + k < C) {
-              const float* pp = part + ((size_t)(c0 + k) * grp + j) * (d + 2);
-              mm[k] = ld_act(pp + d);
-              ll[k] = ld_act(pp + d + 1);
-              oo[k] = ld_act(pp + dim);
-            } else {
-              mm[k] = -INFINITY; ll[k] = 0.f; oo[k] = 0.f;
-            }
-          }
-#pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            float Mn = fmaxf(M, mm[k]);
-            if (Mn == -INFINITY) continue;   // empty chunks only so far
-            float sc_old = expf(M - Mn), sc_new = expf(mm[k] - Mn);
-            L = L * sc_old + ll[k] * sc_new;
-            acc_o = acc_o * sc_old + oo[k] * sc_new;
-            M = Mn;
-          }
-        }
-        st_act(o + i, acc_o / L);
-      }
-    }
-  }
-  return true;
-}
-
-// T4: split-KV decode attention for one (sequence, KV head, chunk).  Chunk c of C covers cache
-// rows [c*len/C, (c+1)*len/C) with len = position + 1, so the last chunk holds the new row.
-// Output per query head of the group: sum_t exp(s_t - m) V_t (D floats), m, l = sum_t exp(s_t - m).
-// Layout of the work: D/8 adjacent lanes share one position (16 bytes of the row each), a
-// wavefront covers 64/(D/8) positions per round, the wavefronts of the workgroup take rounds of
-// (wavefronts x that many) positions.  Every lane group keeps a running maximum, sum and output
-// per query head (online softmax), so a chunk may be of any length and no barrier is needed until
-// the end, where the lane groups of a wavefront are combined with lane shuffles and the
-// wavefronts through LDS.
-// Cache rows of earlier steps are immutable during a step, so the task requests its first
-// kAttnPre rounds of K and V rows BEFORE it waits for its dependent event; only the query (and the
-// row appended this step) arrive later.  Later rounds are requested a batch at a time.
-template <int D, int GRP>
-__device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepArgs& a, float* lds,
-                                                  int32_t wait_ev, uint32_t* s_flag) {
-  constexpr uint32_t d = D, grp = GRP, LPP = D / 8, PPW = 64 / LPP, NW = kThreads / 64;
-  constexpr uint32_t stride = NW * PPW, per = grp * (d + 2);
-  const uint32_t nq = a.g->n_q, nkv = a.g->n_kv, C = t.p1;
-  const uint32_t b = t.b0, u = t.c0 / per, g = u / C, c = u % C;
-  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  float* qs = lds;                       // [grp][d]
-  float* wpart = qs + grp * d;           // [NW][grp][d + 2]: partial output, max, sum per wavefront
-  uint32_t* flag = (uint32_t*)(wpart + NW * grp * (d + 2));
-  float* outp = t.out + (size_t)b * t.ld_out + t.c0;
-  const int32_t pos = a.positions[b] + (int32_t)a.step;    // written by the host before the launch
-  const bool bad_pos = pos < 0 || (uint32_t)pos >= a.g->max_seq;
-  const uint32_t len = bad_pos ? 0u : (uint32_t)pos + 1;
-  const uint32_t t0 = (uint32_t)((uint64_t)c * len / C), t1 = (uint32_t)((uint64_t)(c + 1) * len / C);
-  const uint32_t n = t1 - t0;
-  const uint16_t* Kb = (const uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.g->max_seq + t0) * d;
-  const uint16_t* Vb = (const uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.g->max_seq + t0) * d;
-  const uint32_t sub = lane % LPP, slot = lane / LPP;
-  const uint32_t i_first = wave * PPW + slot;
-  const uint32_t n_rounds = (n + stride - 1) / stride;
-  // rounds held in registers at a time: bounded by what the running state of GRP heads leaves
-  constexpr int kAttnPre = GRP <= 4 ? 8 : 4;
-  // ---- pre-load: the first rounds of K and V rows (never the row appended this step)
-  u32x4 kreg[kAttnPre], vreg[kAttnPre];
-#pragma unroll
-  for (int r = 0; r < kAttnPre; ++r) {
-    const uint32_t i = i_first + r * stride;
-    kreg[r] = u32x4{0, 0, 0, 0};
-    vreg[r] = u32x4{0, 0, 0, 0};
-    if (i < n && t0 + i != (uint32_t)pos) {
-      kreg[r] = ld_stream16(Kb + (size_t)i * d + sub * 8);
-      vreg[r] = ld_stream16(Vb + (size_t)i * d + sub * 8);
-    }
-  }
-  if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
-  trace_mark(a, t, 1);
-  if (bad_pos) {
-    if (threadIdx.x == 0) report(a, DE_BAD_POSITION, b, (uint32_t)pos);
-    for (uint32_t i = threadIdx.x; i < per; i += kThreads) st_act(outp + i, ((i % (d + 2)) == d) ? -INFINITY : 0.f);
-    return true;
-  }
-  const float* qsrc = t.in + (size_t)b * t.ld_in + (size_t)g * grp * d;
-  if (t.flags & TF_ROPE_FUSED) {
-    // the input is the raw QKV projection: rotate the group's query heads here; the task of the
-    // last chunk also rotates this step's key, and appends key and value to the cache
-    constexpr uint32_t half = d / 2;
-    const bool qk_norm = t.flags & TF_QK_NORM;
-    for (uint32_t i = threadIdx.x; i < grp * half; i += kThreads) {
-      uint32_t j = i / half, e = i % half;
-      float u0 = ld_act(qsrc + j * d + e), u1 = ld_act(qsrc + j * d + e + half), cs, sn;
-      if (qk_norm) {   // RMSNorm over the head: its `half` threads are one aligned group of lanes
-        const float inv = 1.0f / sqrtf(lane_group_sum<(int)half>(u0 * u0 + u1 * u1) / (float)d + t.f0);
-        const uint16_t* gq = (const uint16_t*)t.w;
-        u0 *= inv * bf16_to_f32(as_global(gq)[e]);
-        u1 *= inv * bf16_to_f32(as_global(gq)[e + half]);
-      }
-      rope_cs(a, pos, e, &cs, &sn);
-      qs[j * d + e] = u0 * cs - u1 * sn;
-      qs[j * d + e + half] = u1 * cs + u0 * sn;
-    }
-    if (c == C - 1) {
-      const float* ksrc = t.in + (size_t)b * t.ld_in + (size_t)(nq + g) * d;
-      const float* vsrc = t.in + (size_t)b * t.ld_in + (size_t)(nq + nkv + g) * d;
-      uint16_t* krow = (uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
-      uint16_t* vrow = (uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
-      // threads from the top of the workgroup, so that they do not also rotate query pairs
-      for (uint32_t i = kThreads - 1 - threadIdx.x; i < half / 2 + half; i += kThreads) {
-        if (i < half / 2) {   // two adjacent rotation pairs of the key
-          uint32_t e = 2 * i;
-          float2 lo = ld_act2(ksrc + e), hi = ld_act2(ksrc + e + half);
-          if (qk_norm) {   // the key's half/2 threads: one aligned group of lanes at the top of the workgroup
-            const float ss = lane_group_sum<(int)(half / 2)>(lo.x * lo.x + lo.y * lo.y + hi.x * hi.x + hi.y * hi.y);
-            const float inv = 1.0f / sqrtf(ss / (float)d + t.f0);
-            const uint16_t* gk = (const uint16_t*)t.w2;
-            const uint32_t g0 = *as_global((const uint32_t*)(gk + e)), g1 = *as_global((const uint32_t*)(gk + e + half));
-            lo.x *= inv * bf16_lo(g0); lo.y *= inv * bf16_hi(g0);
-            hi.x *= inv * bf16_lo(g1); hi.y *= inv * bf16_hi(g1);
-          }
-          float c0, s0, c1, s1;
-          rope_cs(a, pos, e, &c0, &s0);
-          rope_cs(a, pos, e + 1, &c1, &s1);
-          float r0 = lo.x * c0 - hi.x * s0, r1 = lo.y * c1 - hi.y * s1;
-          float r2 = hi.x * c0 + lo.x * s0, r3 = hi.y * c1 + lo.y * s1;
-          st_act_u32((uint32_t*)(krow + e), (uint32_t)f32_to_bf16(r0) | ((uint32_t)f32_to_bf16(r1) << 16));
-          st_act_u32((uint32_t*)(krow + e + half), (uint32_t)f32_to_bf16(r2) | ((uint32_t)f32_to_bf16(r3) << 16));
-        } else {              // two adjacent value elements
-          uint32_t e = 2 * (i - half / 2);
-          float2 v2 = ld_act2(vsrc + e);
-          st_act_u32((uint32_t*)(vrow + e), (uint32_t)f32_to_bf16(v2.x) | ((uint32_t)f32_to_bf16(v2.y) << 16));
-        }
-      }
-      // the appended row is read back below with coherent loads: the stores must have completed
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-  } else {
-    for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) qs[i] = ld_act(qsrc + i);
-  }
-  __syncthreads();
-  trace_mark(a, t, 2);
-  // ---- running softmax per lane group and query head.  Scores and maxima are kept times
-  // log2(e), folded into the query, so that every probability and rescale is one v_exp_f32 (the
-  // body is bound by vector instructions at 4 and 8 query heads per KV head).
-  const float inv_sqrt_d = 1.44269504088896341f / sqrtf((float)d);
-  float q[GRP][8], m[GRP], l[GRP], acc[GRP][8];
-#pragma unroll
-  for (int j = 0; j < GRP; ++j) {
-    const float4* qp = (const float4*)(qs + j * d + sub * 8);
-    const float4 q0 = qp[0], q1 = qp[1];
-    q[j][0] = q0.x * inv_sqrt_d; q[j][1] = q0.y * inv_sqrt_d; q[j][2] = q0.z * inv_sqrt_d; q[j][3] = q0.w * inv_sqrt_d;
-    q[j][4] = q1.x * inv_sqrt_d; q[j][5] = q1.y * inv_sqrt_d; q[j][6] = q1.z * inv_sqrt_d; q[j][7] = q1.w * inv_sqrt_d;
-    m[j] = -INFINITY;
-    l[j] = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[j][e] = 0.f;
-  }
-  const uint32_t i_new = (c == C - 1) ? n - 1 : 0xFFFFFFFFu;   // the row appended this step, if in this chunk
-  // A batch of rounds lives in registers; its first half is requested again (for the next batch)
-  // as soon as it has been used, so that those loads travel while the second half is multiplied.
-  constexpr int kHalf = kAttnPre / 2;
-  auto request_next = [&](uint32_t r0, auto first_half) {
-    constexpr int lo = decltype(first_half)::value ? 0 : kHalf, hi = decltype(first_half)::value ? kHalf : kAttnPre;
-    if (r0 + kAttnPre < n_rounds) {
-#pragma unroll
-      for (int r = lo; r < hi; ++r) {
-        const uint32_t i = i_first + (r0 + kAttnPre + r) * stride;
-        if (i < n && i != i_new) {
-          kreg[r] = ld_stream16(Kb + (size_t)i * d + sub * 8);
-          vreg[r] = ld_stream16(Vb + (size_t)i * d + sub * 8);
-        }
-      }
-    }
-  };
-  for (uint32_t r0 = 0; r0 < n_rounds; r0 += kAttnPre) {
-#pragma unroll
-    for (int r = 0; r < kAttnPre; ++r) {
-      if (r == kHalf) request_next(r0, std::true_type{});
-      const uint32_t i = i_first + (r0 + r) * stride;
-      if (i == i_new) {
-        // written after the pre-load, by this or another workgroup: coherent loads
-        kreg[r] = ld_row16_coherent(Kb + (size_t)i * d + sub * 8);
-        vreg[r] = ld_row16_coherent(Vb + (size_t)i * d + sub * 8);
-      }
-      const bool valid = i < n;
-      const u32x4 kv = kreg[r], vv = vreg[r];
-      const float k8[8] = {bf16_lo(kv.x), bf16_hi(kv.x), bf16_lo(kv.y), bf16_hi(kv.y),
-                           bf16_lo(kv.z), bf16_hi(kv.z), bf16_lo(kv.w), bf16_hi(kv.w)};
-      const float v8[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
-                           bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
-#pragma unroll
-      for (int j = 0; j < GRP; ++j) {
-        float sv = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) sv = fmaf(k8[e], q[j][e], sv);
-        sv = group_sum<LPP>(sv);
-        if (valid) {
-          if (sv > m[j]) {   // a new maximum (rare after the first positions): rescale the running state
-            const float sc = __builtin_amdgcn_exp2f(m[j] - sv);   // 2^(-inf) = 0 on the first position
-            l[j] *= sc;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[j][e] *= sc;
-            m[j] = sv;
-          }
-          const float p = __builtin_amdgcn_exp2f(sv - m[j]);
-          l[j] += p;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p, v8[e], acc[j][e]);
-        }
-      }
-    }
-    request_next(r0, std::false_type{});
-  }
-  // ---- combine the lane groups of the wavefront, then the wavefronts
-#pragma unroll
-  for (int j = 0; j < GRP; ++j) {
-#pragma unroll
-    for (uint32_t off = LPP; off < 64; off <<= 1) {
-      const float mo = __shfl_xor(m[j], off, 64), lo2 = __shfl_xor(l[j], off, 64);
-      const float mn = fmaxf(m[j], mo);
-      const float s0 = (m[j] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m[j] - mn), s1 = (mo == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mo - mn);
-      l[j] = l[j] * s0 + lo2 * s1;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[j][e] = acc[j][e] * s0 + __shfl_xor(acc[j][e], off, 64) * s1;
-      m[j] = mn;
-    }
-    if (slot == 0) {
-      float* wp = wpart + ((size_t)wave * grp + j) * (d + 2);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) wp[sub * 8 + e] = acc[j][e];
-      if (sub == 0) {
-        wp[d] = m[j] * 0.693147180559945309f;   // back to natural units for the merges
-        wp[d + 1] = l[j];
-      }
-    }
-  }
-  __syncthreads();
-  trace_mark(a, t, 10);
-  for (uint32_t i = threadIdx.x; i < grp * (d + 2); i += kThreads) {
-    const uint32_t j = i / (d + 2), dim = i % (d + 2);
-    float M = -INFINITY;
-#pragma unroll
-    for (uint32_t w = 0; w < NW; ++w) M = fmaxf(M, wpart[((size_t)w * grp + j) * (d + 2) + d]);
-    float sv;
-    if (dim == d) {
-      sv = M;
-    } else {
-      sv = 0.f;
-      const uint32_t src = (dim == d + 1) ? d + 1 : dim;
-#pragma unroll
-      for (uint32_t w = 0; w < NW; ++w) {
-        const float mw = wpart[((size_t)w * grp + j) * (d + 2) + d];
-        if (mw != -INFINITY) sv += wpart[((size_t)w * grp + j) * (d + 2) + src] * expf(mw - M);
-      }
-    }
-    st_act(outp + i, sv);
-  }
-  trace_mark(a, t, 11);
-  if (t.flags & TF_ATTN_MERGE) {
-    // Arrival counter of (layer, sequence, KV head): the chunk task that arrives last sees all C
-    // partials complete and merges them (log-sum-exp, one pass with running maximum) into the
-    // attention output.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      uint32_t* cnt = a.g->grp_counters + t.p2 + b * nkv + g;
-      uint32_t old = __hip_atomic_fetch_add(as_global(cnt), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      *flag = ((old + 1u) % C == 0u) ? 1u : 0u;   // every step adds exactly C
-    }
-    __syncthreads();
-    if (*flag) {
-      const float* part = t.out + (size_t)b * t.ld_out + (size_t)g * C * per;
-      float* o = const_cast<float*>(t.in2) + (size_t)b * nq * d + (size_t)g * grp * d;
-      for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) {
-        uint32_t j = i / d, dim = i % d;
-        float M = -INFINITY, L = 0.f, acc_o = 0.f;
-        for (uint32_t c0 = 0; c0 < C; c0 += 8) {   // 24 coherent loads in flight: one round trip for 8 chunks
-          float mm[8], ll[8], oo[8];
-#pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            if (c0 + k < C) {
-              const float* pp = part + ((size_t)(c0 + k) * grp + j) * (d + 2);
-              mm[k] = ld_act(pp + d);
-              ll[k] = ld_act(pp + d + 1);
-              oo[k] = ld_act(pp + dim);
-            } else {
-              mm[k] = -INFINITY; ll[k] = 0.f; oo[k] = 0.f;
-            }
-          }
-#pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            float Mn = fmaxf(M, mm[k]);
-            if (Mn == -INFINITY) continue;   // empty chunks only so far
-            float sc_old = expf(M - Mn), sc_new = expf(mm[k] - Mn);
-            L = L * sc_old + ll[k] * sc_new;
-            acc_o = acc_o * sc_old + oo[k] * sc_new;
-            M = Mn;
-          }
-        }
-        st_act(o + i, acc_o / L);
-      }
-    }
-  }
-  return true;
-}
-
-// T5: merge the chunk partials of each query head with the log-sum-exp rule.
-__device__ __forceinline__ void body_attn_merge(const TaskDesc& t, const StepArgs& a) {
-  const uint32_t d = a.g->head_dim, grp = a.g->n_q / a.g->n_kv, C = t.p1;
-  const uint32_t h0 = t.c0 / d, h1 = t.c1 / d;
-  for (uint32_t b = t.b0; b < t.b1; ++b) {
-    const float* part = t.in + (size_t)b * t.ld_in;
-    float* out = t.out + (size_t)b * t.ld_out;
-    for (uint32_t idx = threadIdx.x; idx < (h1 - h0) * d; idx += kThreads) {
-      uint32_t h = h0 + idx / d, dim = idx % d, g = h / grp, j = h % grp;
-      float M = -INFINITY;
-      for (uint32_t c = 0; c < C; ++c) M = fmaxf(M, ld_act(part + ((size_t)(g * C + c) * grp + j) * (d + 2) + d));
-      float L = 0.f, o = 0.f;
-      for (uint32_t c = 0; c < C; ++c) {
-        const float* p = part + ((size_t)(g * C + c) * grp + j) * (d + 2);
-        float wgt = expf(ld_act(p + d) - M);   // exp(-inf) = 0 for empty chunks
-        L = fmaf(wgt, ld_act(p + d + 1), L);
-        o = fmaf(wgt, ld_act(p + dim), o);
-      }
-      st_act(out + h * d + dim, o / L);
-    }
-  }
-}
-
-__device__ __forceinline__ void body_add(const TaskDesc& t) {
-  const uint32_t nc = t.c1 - t.c0;
-  for (uint32_t b = t.b0; b < t.b1; ++b)
-    for (uint32_t i = threadIdx.x; i < nc; i += kThreads) {
-      size_t o = (size_t)b * t.ld_out + t.c0 + i;
-      st_act(t.out + o, ld_act(t.in + o) + ld_act(t.in2 + o));
-    }
-}
-
-__device__ __forceinline__ void body_swiglu(const TaskDesc& t) {
-  const uint32_t nc = t.c1 - t.c0, F = t.p0;
-  for (uint32_t b = t.b0; b < t.b1; ++b)
-    for (uint32_t i = threadIdx.x; i < nc; i += kThreads) {
-      const float* gu = t.in + (size_t)b * t.ld_in;
-      float gte = ld_act(gu + t.c0 + i), up = ld_act(gu + F + t.c0 + i);
-      st_act(t.out + (size_t)b * t.ld_out + t.c0 + i, gte / (1.0f + expf(-gte)) * up);
-    }
-}
-
-// Runs one task.  wait_ev >= 0: the task must first wait for that event (persistent kernel);
-// linear and attention tasks do so after requesting their first weight / cache block.
-// Greedy sampling (one task per sequence): the index of the largest logit, lowest index on ties;
-// the token goes to token_ids[b] for the next step's embedding task (and to tokens_out); the
-// last step of a launch also advances positions[b].  Optionally keeps a copy of the logits.
-__device__ __forceinline__ void body_argmax(const TaskDesc& t, const StepArgs& a, float* lds) {
-  const int lane = threadIdx.x & 63;
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const uint32_t V = t.K, B = a.g->batch;
-  float* vmax = lds;                          // [8]
-  uint32_t* imax = (uint32_t*)(lds + 8);      // [8]
-  for (uint32_t b = t.b0; b < t.b1; ++b) {
-    const float* row = a.logits + (size_t)b * V;
-    float* const logits_all = a.g->logits_all;
-    int32_t* const tokens_out = a.g->tokens_out;
-    float* copy = logits_all ? logits_all + ((size_t)a.step * B + b) * V : nullptr;
-    float best = -INFINITY;
-    uint32_t best_i = 0xFFFFFFFFu;
-    for (uint32_t i = threadIdx.x; i < V; i += kThreads) {   // ascending per thread: keeps the first maximum
-      const float v = ld_act(row + i);
-      if (copy) as_global(copy)[i] = v;
-      if (v > best || best_i == 0xFFFFFFFFu) { best = v; best_i = i; }
-    }
-    const float wbest = wave_max(best);
-    const uint32_t wi = wave_min_u32(best == wbest ? best_i : 0xFFFFFFFFu);
-    if (lane == 0) { vmax[wave] = wbest; imax[wave] = wi; }
-    lds_barrier();
-    if (threadIdx.x == 0) {
-      float m = vmax[0];
-      uint32_t mi = imax[0];
-      for (uint32_t w = 1; w < kThreads / 64; ++w)
-        if (vmax[w] > m || (vmax[w] == m && imax[w] < mi)) { m = vmax[w]; mi = imax[w]; }
-      if (mi >= V) mi = 0;   // logits that are not numbers: keep the token in range
-      st_act_u32((uint32_t*)const_cast<int32_t*>(a.token_ids) + b, mi);
-      if (tokens_out) st_act_u32((uint32_t*)tokens_out + (size_t)a.step * B + b, mi);
-      if ((uint32_t)a.step + 1u == a.n_steps)
-        st_act_u32((uint32_t*)const_cast<int32_t*>(a.positions) + b, (uint32_t)(a.positions[b] + (int32_t)a.n_steps));
-    }
-    lds_barrier();
-  }
-}
-
-// D, GRP, NB pin head_dim, query heads per KV head and the batch class at compile time (0 = decide
-// at run time): a kernel that carries a single attention and a single linear variant keeps its
-// register allocation free of spills, the fully generic kernel does not.
-// Batch class -> body instance (NB = 0: decided at run time).
-template <int NB, bool MEGA, class Svc = NoJit>
-__device__ __forceinline__ uint32_t run_linear(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
-                                           uint32_t* s_flag, const Svc& svc = Svc{}) {
-  if (NB == 8) return linear_task_mfma<MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);   // batch class 5..16: matrix cores
-  if (NB == 9) return linear_task<1, MEGA, Svc, true>(t, a, lds, wait_ev, s_flag, svc);   // batch 1, large tasks: three buffers
-  if (NB != 0) return linear_task<(NB ? NB : 1), MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
-  const uint32_t nb = t.b1 - t.b0;
-  if (nb == 1) return linear_task<1, MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
-  if (nb == 2) return linear_task<2, MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
-  if (nb <= 4) return linear_task<4, MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
-  return linear_task_mfma<MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
-}
-
-template <int D, int GRP, int NB>
-__device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, float* lds,
-                                         int32_t wait_ev, uint32_t* s_flag) {
-  if (t.kind == TK_ATTN_PARTIAL) {
-    if (D != 0) {
-      // chunks that always fit the register-resident body (wavefront-uniform: graph constants)
-      constexpr uint32_t window = kAttnRounds * (kThreads / 64) * (64 / ((D ? D : 128) / 8));
-      if ((GRP ? GRP : 1) <= 4 && (a.g->max_seq + t.p1 - 1) / t.p1 <= window)
-        return body_attn_partial_regs<(D ? D : 128), (GRP ? GRP : 1)>(t, a, lds, wait_ev, s_flag);
-      return body_attn_partial<(D ? D : 128), (GRP ? GRP : 1)>(t, a, lds, wait_ev, s_flag);
-    }
-    const uint32_t grp = a.g->n_q / a.g->n_kv;
-    if (a.g->head_dim == 128) {
-      if (grp == 8) return body_attn_partial<128, 8>(t, a, lds, wait_ev, s_flag);
-      if (grp == 4) return body_attn_partial<128, 4>(t, a, lds, wait_ev, s_flag);
-      if (grp == 2) return body_attn_partial<128, 2>(t, a, lds, wait_ev, s_flag);
-      return body_attn_partial<128, 1>(t, a, lds, wait_ev, s_flag);
-    }
-    if (grp == 8) return body_attn_partial<64, 8>(t, a, lds, wait_ev, s_flag);
-    if (grp == 4) return body_attn_partial<64, 4>(t, a, lds, wait_ev, s_flag);
-    if (grp == 2) return body_attn_partial<64, 2>(t, a, lds, wait_ev, s_flag);
-    return body_attn_partial<64, 1>(t, a, lds, wait_ev, s_flag);
-  }
-  if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
-  trace_mark(a, t, 1);
-  switch (t.kind) {
-    case TK_EMBED: body_embed(t, a); break;
-    case TK_RMSNORM: body_rmsnorm(t, lds); break;
-    case TK_ROPE: body_rope(t, a); break;
-    case TK_ATTN_MERGE: body_attn_merge(t, a); break;
-    case TK_ADD: body_add(t); break;
-    case TK_SWIGLU: body_swiglu(t); break;
-    case TK_ARGMAX: body_argmax(t, a, lds); break;
-    default: break;   // TK_DUMMY: no computation (normalization, Section 4.1)
-  }
-  return true;
-}
-
-// ------------------------------------------------------------------------------ runtime
-
-// Returns false when the step is being aborted (watchdog or a peer's failure).
-// Simple events: wait until counter >= epoch * required.  Hierarchical events: wait until this
-// worker group's ready flag has reached the epoch.
-__device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag) {
-  if (threadIdx.x == 0) {
-    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
-    const uint32_t* word;
-    uint32_t target;
-    if (ev.flags & EV_HIER) {
-      word = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
-      target = a.epoch * ev.n_groups;
-    } else {
-      word = a.counters + e;
-      target = a.epoch * ev.required;
-    }
-    uint32_t ok = 1;
-    if ((int32_t)(ld_relaxed(word) - target) < 0) {
-      const uint64_t t_start = wall_clock64();
-      uint32_t it = 0;
-      while ((int32_t)(ld_relaxed(word) - target) < 0) {
-        if ((++it & 255u) == 0) {
-          if (ld_relaxed(a.g->err + 1) != 0) { ok = 0; break; }
-          if (wall_clock64() - t_start > a.g->timeout_ticks) {
-            report(a, DE_TIMEOUT, (uint32_t)e, blockIdx.x);
-            __hip_atomic_store(as_global(a.g->err + 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            ok = 0;
-            break;
-          }
-        }
-      }
-    }
-    *s_flag = ok;
-  }
-  __syncthreads();   // later agent-scope loads cannot move above this barrier
-  return __builtin_amdgcn_readfirstlane(*s_flag) != 0;
-}
-
-// One lane: add this task's notification to event e (Section 5: "notify the triggering event").
-// The arrival that activates an event whose range holds just-in-time tasks hands the event to
-// its scheduler's queue.
-__device__ __forceinline__ void notify_event(const StepArgs& a, int32_t e) {
-  const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
-  const uint32_t flags = ev.flags;
-  bool activated = false;
-  if (flags & EV_HIER) {
-    uint32_t* blk = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent;
-    const uint32_t grp = blockIdx.x & 7u;
-    uint32_t old = __hip_atomic_fetch_add(as_global(blk + (1 + grp) * kHierStrideWords), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (old + 1u == a.epoch * ev.sub_required[grp]) {          // last arrival of this group
-      // tell every group of pollers: its word counts the producer groups that are complete
-#pragma unroll
-      for (uint32_t k = 0; k < 8; ++k)
-        __hip_atomic_fetch_add(as_global(blk + (9 + k) * kHierStrideWords), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if ((flags & EV_JIT) && a.n_sched) {                  // a scheduler needs to know who was last
-        old = __hip_atomic_fetch_add(as_global(blk), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        activated = old + 1u == a.epoch * ev.n_groups;
-      }
-    }
-  } else if ((flags & EV_JIT) && a.n_sched) {
-    const uint32_t old = __hip_atomic_fetch_add(as_global(a.counters + e), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    activated = old + 1u == a.epoch * ev.required;
-  } else {
-    __hip_atomic_fetch_add(as_global(a.counters + e), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-  if (activated && (flags & EV_JIT) && a.n_sched) {
-    const uint32_t sc = (uint32_t)e % a.n_sched;
-    const uint32_t slot = __hip_atomic_fetch_add(as_global(a.g->evq_tail + sc * 64u), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(as_global(a.g->evq_buf + (size_t)sc * a.g->evq_cap + (slot & (a.g->evq_cap - 1u))),
-                       ((uint64_t)(slot + 1u) << 32) | (uint32_t)e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-}
-
-__device__ __forceinline__ void signal_event(const StepArgs& a, const TaskDesc& t, int32_t e) {
-  // every wavefront waits until its own agent-scope stores have completed at the coherence point
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  trace_mark(a, t, 6);
-  __syncthreads();
-  trace_mark(a, t, 7);
-  if (threadIdx.x == 0) notify_event(a, e);
-}
-
-// Wavefront 0 only: poll the dependent event of the next task; result in *s_flag (LDS).
-__device__ __forceinline__ void poll_event_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane) {
-  if (lane == 0) {
-    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
-    const uint32_t* word;
-    uint32_t target;
-    if (ev.flags & EV_HIER) {
-      word = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
-      target = a.epoch * ev.n_groups;
-    } else {
-      word = a.counters + e;
-      target = a.epoch * ev.required;
-    }
-    uint32_t ok = 1;
-    if ((int32_t)(ld_relaxed(word) - target) < 0) {
-      const uint64_t t_start = wall_clock64();
-      uint32_t it = 0;
-      while ((int32_t)(ld_relaxed(word) - target) < 0) {
-        if ((++it & 255u) == 0) {
-          if (ld_relaxed(a.g->err + 1) != 0) { ok = 0; break; }
-          if (wall_clock64() - t_start > a.g->timeout_ticks) {
-            report(a, DE_TIMEOUT, (uint32_t)e, blockIdx.x);
-            __hip_atomic_store(as_global(a.g->err + 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            ok = 0;
-            break;
-          }
-        }
-      }
-    }
-    *s_flag = ok;
-  }
-}
-
-// Wavefront 0 only: like poll_event_wave0, but also watches the worker's just-in-time queue.
-// s_flag[0] = 1 event activated, 0 abort, 2 a just-in-time task (index in s_flag[1]) is queued.
-__device__ __forceinline__ void poll_event_or_jit_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane, uint32_t jit_head) {
-  if (lane == 0) {
-    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
-    const uint32_t* word;
-    uint32_t target;
-    if (ev.flags & EV_HIER) {
-      word = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
-      target = a.epoch * ev.n_groups;
-    } else {
-      word = a.counters + e;
-      target = a.epoch * ev.required;
-    }
-    const uint64_t* slot = a.g->wq_buf + (size_t)blockIdx.x * a.g->wq_cap + (jit_head & (a.g->wq_cap - 1u));
-    const uint64_t t_start = wall_clock64();
-    uint32_t ok, it = 0;
-    while (true) {
-      if ((int32_t)(ld_relaxed(word) - target) >= 0) { ok = 1; break; }
-      const uint64_t v = ld_relaxed64(slot);
-      if ((uint32_t)(v >> 32) == jit_head + 1u) { s_flag[1] = (uint32_t)v; ok = 2; break; }
-      if ((++it & 127u) == 0) {
-        if (ld_relaxed(a.g->err + 1) != 0) { ok = 0; break; }
-        if (wall_clock64() - t_start > a.g->timeout_ticks) {
-          report(a, DE_TIMEOUT, (uint32_t)e, blockIdx.x);
-          __hip_atomic_store(as_global(a.g->err + 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          ok = 0;
-          break;
-        }
-      }
-    }
-    s_flag[0] = ok;
-  }
-}
-
-// Wavefront 0 only, after a workgroup barrier: wait for this wavefront's own coherent stores,
-// then notify the event.
-__device__ __forceinline__ void signal_from_wave0(const StepArgs& a, const TaskDesc& t, int32_t e, int lane) {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  trace_mark(a, t, 7);
-  if (lane == 0) notify_event(a, e);
-}
-
-// The first 64 bytes of the dynamic LDS are control words ([0] = result of the last event wait);
-// task bodies use the rest.
-constexpr uint32_t kLdsCtrlFloats = 16;
-
-// Mixture-of-experts tasks get a function of their own as well: the expert jobs hold many
-// registers, and a function saves every callee-saved register it uses anywhere on each call, so
-// sharing run_other_task would tax every attention task with those saves.
-template <bool MEGA>
-__device__ __noinline__ bool run_moe_task(StepArgs a_in, uint32_t task_index, bool skip_wait) {
-  const StepArgs a = uniform_args(a_in);
-  task_index = uniform_u32(task_index);
-  skip_wait = uniform_u32(skip_wait) != 0;
-  extern __shared__ __align__(16) float dyn_lds[];
-  float* lds = dyn_lds + kLdsCtrlFloats;
-  uint32_t* s_flag = (uint32_t*)dyn_lds;
-  const TaskDesc t = ld_task(a, task_index);
-  if (MEGA) {
-    const int32_t wait_ev = (!skip_wait && t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
-    trace_mark(a, t, 0);
-    if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)task_index * kTraceSlots + 5] = blockIdx.x;
-    if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
-    trace_mark(a, t, 1);
-  }
-  switch (t.kind) {
-    case TK_MOE_ROUTE: body_moe_route(t, a, lds); break;
-    case TK_MOE_EXPERT: body_moe_expert(t, a, lds); break;
-    default: body_moe_combine(t, a); break;
-  }
-  if (MEGA) {
-    trace_mark(a, t, 3);
-    if (t.trig_event >= 0) signal_event(a, t, t.trig_event);
-    else __syncthreads();
-    trace_mark(a, t, 4);
-  }
-  return true;
-}
-__device__ __forceinline__ bool is_moe_kind(uint16_t kind) { return kind >= TK_MOE_ROUTE && kind <= TK_MOE_COMBINE; }
-
-// Everything that is not a linear task runs in a function of its own (a real call): its
-// thread-index arithmetic and temporaries then get their own register allocation instead of being
-// hoisted to the top of the persistent loop, where they would crowd out the weight ring and
-// force spills of registers that have loads in flight.
-// Returns false when the step is being aborted.
-template <int D, int GRP, int NB, bool MEGA, bool MOE>
-__device__ __noinline__ bool run_other_task(StepArgs a_in, uint32_t task_index, bool skip_wait) {
-  const StepArgs a = uniform_args(a_in);
-  task_index = uniform_u32(task_index);
-  skip_wait = uniform_u32(skip_wait) != 0;
-  extern __shared__ __align__(16) float dyn_lds[];
-  float* lds = dyn_lds + kLdsCtrlFloats;
-  uint32_t* s_flag = (uint32_t*)dyn_lds;
-  const TaskDesc t = ld_task(a, task_index);
-  // kernels for dense models are built without this call: with it the function is no leaf any
-  // more and every attention task pays for that (measured: 0.1 ms per step on the 8B shape)
-  if (MOE && is_moe_kind(t.kind)) return run_moe_task<MEGA>(a_in, task_index, skip_wait);
-  int32_t wait_ev = -1;
-  if (MEGA) {
-    wait_ev = (!skip_wait && t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
-    trace_mark(a, t, 0);
-    if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)task_index * kTraceSlots + 5] = blockIdx.x;
-  }
-  if (!run_task<D, GRP, NB>(t, a, lds, wait_ev, s_flag)) return false;
-  if (MEGA) {
-    trace_mark(a, t, 3);
-    if (t.trig_event >= 0) signal_event(a, t, t.trig_event);
-    else __syncthreads();
-    trace_mark(a, t, 4);
-  }
-  return true;
-}
-
-__device__ __forceinline__ bool event_active(const StepArgs& a, int32_t e) {
-  const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
-  if (ev.required == 0) return true;
-  if (ev.flags & EV_HIER) {
-    const uint32_t* word = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
-    return (int32_t)(ld_relaxed(word) - a.epoch * ev.n_groups) >= 0;
-  }
-  return (int32_t)(ld_relaxed(a.counters + e) - a.epoch * ev.required) >= 0;
-}
-
-
-// One scheduler wavefront (Section 5.1): takes activated events from its own queue and hands the
-// just-in-time tasks of each event's range to the workers' queues, round-robin from a cursor of
-// its own -- local state only, no coordination with other schedulers (Section 6.1).
-__device__ __forceinline__ void scheduler_wave(const StepArgs& a, uint32_t sc) {
-  const int lane = threadIdx.x & 63;
-  const uint32_t W = a.g->n_workers;
-  uint32_t head = ld_relaxed(a.g->sched_state + sc * 64u), cursor = ld_relaxed(a.g->sched_state + sc * 64u + 1u);
-  uint32_t todo = ld_u32c(a.g->sched_nev + sc);
-  // schedulers that hand out the same number of tasks per layer move their cursors in lock-step:
-  // start them evenly spread over the workers, or they would all pile onto the same few
-  const uint32_t spread = sc * (W / a.n_sched);
-  // the start event has no notifications: its owner dispatches it unprompted
-  const MPK_CONST EventDesc& sev = *(const MPK_CONST EventDesc*)(a.events + a.g->start_event);
-  bool pending_start = (sev.flags & EV_JIT) && a.g->start_event % a.n_sched == sc;
-  while (todo > 0 || pending_start) {
-    uint32_t e;
-    if (pending_start) {
-      e = a.g->start_event;
-      pending_start = false;
-    } else {
-      const uint64_t* slot = a.g->evq_buf + (size_t)sc * a.g->evq_cap + (head & (a.g->evq_cap - 1u));
-      uint64_t v = ld_relaxed64(slot);
-      if ((uint32_t)(v >> 32) != head + 1u) {
-        const uint64_t t_start = wall_clock64();
-        uint32_t it = 0;
-        bool dead = false;
-        while ((uint32_t)((v = ld_relaxed64(slot)) >> 32) != head + 1u) {
-          if ((++it & 255u) == 0) {
-            if (ld_relaxed(a.g->err + 1) != 0) { dead = true; break; }
-            if (wall_clock64() - t_start > a.g->timeout_ticks) {
-              if (lane == 0) {
-                report(a, DE_TIMEOUT, 0x80000000u | sc, blockIdx.x);
-                __hip_atomic_store(as_global(a.g->err + 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              }
-              dead = true;
-              break;
-            }
-          }
-        }
-        if (dead) break;
-      }
-      e = (uint32_t)v;
-      ++head;
-      --todo;
-    }
-    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
-    const uint32_t first = ev.first, n = ev.last - ev.first;
-    for (uint32_t i = lane; i < n; i += 64) {
-      const uint32_t ti = first + i;
-      const MPK_CONST TaskDesc& td = *(const MPK_CONST TaskDesc*)(a.tasks + ti);
-      if (td.flags & TF_JIT) {
-        const uint32_t w = (cursor + spread + i) % W;
-        const uint32_t s = __hip_atomic_fetch_add(as_global(a.g->wq_tail + w * 64u), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(as_global(a.g->wq_buf + (size_t)w * a.g->wq_cap + (s & (a.g->wq_cap - 1u))),
-                           ((uint64_t)(s + 1u) << 32) | ti, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-    }
-    cursor += n;
-  }
-  if (lane == 0) {
-    __hip_atomic_store(as_global(a.g->sched_state + sc * 64u), head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(as_global(a.g->sched_state + sc * 64u + 1u), cursor % W, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-}
-
-constexpr uint32_t kPickExit = 0xFFFFFFFFu, kPickAbort = 0xFFFFFFFEu;
-
-// Worker side of the hybrid launch (Section 5.2): just-in-time tasks first; when none is queued,
-// the head of the ahead-of-time queue if its dependent event is activated (or, for a linear task,
-// regardless: see linear_wait); exit once the
-// ahead-of-time queue is exhausted and the terminal event has been activated.  One lane decides,
-// the result goes through LDS.  Returns a task index (bit 31 set: it came from the JIT queue).
-__device__ __forceinline__ uint32_t pick_task(const StepArgs& a, uint32_t* ctrl, uint32_t* jit_head, uint32_t* ai, uint32_t q1) {
-  if (threadIdx.x == 0) {
-    const uint32_t w = blockIdx.x;
-    uint32_t pick;
-    const uint64_t t_start = wall_clock64();
-    uint32_t it = 0;
-    while (true) {
-      const uint64_t v = ld_relaxed64(a.g->wq_buf + (size_t)w * a.g->wq_cap + (*jit_head & (a.g->wq_cap - 1u)));
-      if ((uint32_t)(v >> 32) == *jit_head + 1u) {
-        pick = (uint32_t)v | 0x80000000u;
-        ++*jit_head;
-        break;
-      }
-      if (*ai < q1) {
-        const uint32_t ti = ld_u32c(a.g->aot + *ai);
-        const MPK_CONST TaskDesc* td = (const MPK_CONST TaskDesc*)(a.tasks + ti);
-        const int32_t dep = td->dep_event;
-        // a linear task may start before its event: it requests its weights, then waits for the
-        // event itself while serving this worker's just-in-time queue (linear_wait)
-        if (dep < 0 || td->kind == TK_LINEAR || event_active(a, dep)) {
-          pick = ti;
-          ++*ai;
-          break;
-        }
-      } else if (event_active(a, (int32_t)a.g->terminal_event)) {
-        pick = kPickExit;
-        break;
-      }
-      if ((++it & 63u) == 0) {
-        if (ld_relaxed(a.g->err + 1) != 0) { pick = kPickAbort; break; }
-        if (wall_clock64() - t_start > a.g->timeout_ticks) {
-          report(a, DE_TIMEOUT, 0x40000000u | (*ai < q1 ? ld_u32c(a.g->aot + *ai) : 0u), blockIdx.x);
-          __hip_atomic_store(as_global(a.g->err + 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          pick = kPickAbort;
-          break;
-        }
-      }
-    }
-    ctrl[1] = pick;
-    ctrl[2] = *jit_head;
-    ctrl[3] = *ai;
-  }
-  __syncthreads();
-  *jit_head = __builtin_amdgcn_readfirstlane(ctrl[2]);
-  *ai = __builtin_amdgcn_readfirstlane(ctrl[3]);
-  const uint32_t pick = __builtin_amdgcn_readfirstlane(ctrl[1]);
-  __syncthreads();   // ctrl may be rewritten only after everybody has read it
-  return pick;
-}
-
-// Every task ahead-of-time: the worker walks its pre-enqueued list, each task waits for its own
-// event.  after_first_step: a task without producers (an embedding task) first waits for the
-// previous step's terminal event, i.e. for that step's sampling tasks.  Returns false on abort.
-template <int D, int GRP, int NB, bool MOE>
-__device__ __forceinline__ bool aot_pass(const StepArgs& a, uint32_t q0, uint32_t q1, float* lds, uint32_t* s_flag,
-                                         bool after_first_step) {
-  for (uint32_t qi = q0; qi < q1; ++qi) {
-    const uint32_t ti = ld_u32c(a.g->aot + qi);
-    const TaskDesc t = ld_task(a, ti);
-    if (after_first_step && t.dep_event == (int32_t)a.g->start_event) {
-      StepArgs prev = a;
-      prev.epoch = a.epoch - 1u;
-      if (!__builtin_amdgcn_readfirstlane((int)wait_event(prev, (int32_t)a.g->terminal_event, s_flag))) return false;
-    }
-    if (t.kind == TK_LINEAR) {
-      const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
-      trace_mark(a, t, 0);
-      if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
-      if (!run_linear<NB, true>(t, a, lds, wait_ev, s_flag)) return false;
-    } else {
-      // the callee's result comes back in a vector register: make it scalar again, or the whole
-      // task loop (and every descriptor load in it) turns into per-lane code
-      if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(a, ti, false))) return false;
-    }
-  }
-  return true;
-}
-
-// Multi-token launch (graphs with the sampling operator, no schedulers): the task list is walked
-// n_steps times, the epoch -- hence every counter target -- growing by one each time.  A kernel of
-// its own: with the step loop in mpk_mega_kernel the single-step launch measured 2 to 4 % slower.
-template <int D, int GRP, int NB, bool MOE>
-__global__ void __launch_bounds__(kThreads) mpk_loop_kernel(StepArgs a) {
-  extern __shared__ __align__(16) float dyn_lds[];
-  float* lds = dyn_lds + kLdsCtrlFloats;
-  uint32_t* s_flag = (uint32_t*)dyn_lds;
-  const uint32_t w = blockIdx.x;
-  const uint32_t q0 = ld_u32c(a.g->aot_off + w), q1 = ld_u32c(a.g->aot_off + w + 1);
-  const uint32_t n_steps = a.n_steps;
-  for (uint32_t step = 0; step < n_steps; ++step, ++a.epoch) {
-    a.step = (uint16_t)step;
-    if (!aot_pass<D, GRP, NB, MOE>(a, q0, q1, lds, s_flag, step > 0)) return;
-  }
-}
-
-template <int D, int GRP, int NB, bool MOE>
-__global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
-  extern __shared__ __align__(16) float dyn_lds[];
-  float* lds = dyn_lds + kLdsCtrlFloats;
-  uint32_t* s_flag = (uint32_t*)dyn_lds;
-  const uint32_t w = blockIdx.x;
-  if (w >= a.g->n_workers) {
-    // scheduler workgroup: 4 scheduler wavefronts (Section 5.1, Table 2), the rest leave
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t sc = (w - a.g->n_workers) * 4u + wave;
-    if (wave < 4u && sc < a.n_sched) scheduler_wave(a, sc);
-    return;
-  }
-  const uint32_t q0 = ld_u32c(a.g->aot_off + w), q1 = ld_u32c(a.g->aot_off + w + 1);
-  if (a.n_sched == 0) {
-    aot_pass<D, GRP, NB, MOE>(a, q0, q1, lds, s_flag, false);
-    return;
-  }
-  // hybrid launch
-  uint32_t jit_head = ld_relaxed(a.g->wq_head + w), ai = q0;
-  while (true) {
-    const uint32_t pick = pick_task(a, (uint32_t*)dyn_lds, &jit_head, &ai, q1);
-    if (pick == kPickExit || pick == kPickAbort) break;
-    const uint32_t ti = pick & 0x7FFFFFFFu;
-    const TaskDesc t = ld_task(a, ti);
-    if (t.kind == TK_LINEAR) {
-      trace_mark(a, t, 0);
-      if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
-      const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
-      uint32_t r;
-      // started before its event is activated; a just-in-time task that arrives first pre-empts it
-      while ((r = run_linear<NB, true>(t, a, lds, wait_ev, s_flag, JitWatch{jit_head})) == kLinPreempted) {
-        const uint32_t tj = __builtin_amdgcn_readfirstlane(((uint32_t*)dyn_lds)[1]);
-        lds_barrier();   // everybody has read the control word
-        ++jit_head;
-        if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(a, tj, true))) { r = kLinAbort; break; }
-      }
-      if (r == kLinAbort) break;
-    } else {
-      if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(a, ti, true))) break;
-    }
-  }
-  if (threadIdx.x == 0) __hip_atomic_store(as_global(a.g->wq_head + w), jit_head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Kernel-per-operator baseline: the same task bodies, one launch per operator, dependencies
-// enforced by stream order (what the paper's comparison systems do, Section 6.5).
-template <int D, int GRP, int NB, bool MOE>
-__global__ void __launch_bounds__(kThreads) mpk_op_kernel(StepArgs a, uint32_t first) {
-  extern __shared__ __align__(16) float dyn_lds[];
-  float* lds = dyn_lds + kLdsCtrlFloats;
-  const uint32_t ti = ld_u32c(a.g->op_list + first + blockIdx.x);
-  const TaskDesc t = ld_task(a, ti);
-  if (t.kind == TK_LINEAR) {
-    run_linear<NB, false>(t, a, lds, -1, nullptr);
-  } else {
-    run_other_task<D, GRP, NB, false, MOE>(a, ti, true);
-  }
+#define MPK_GET_VARIANT(I, D, G, N, M) kernel_variant_##I(),
+static const KernelVariant* variant_at(int i) {
+  static const KernelVariant* const table[kNumVariants] = {MPK_VARIANT_LIST(MPK_GET_VARIANT)};
+  return table[i];
 }
+#undef MPK_GET_VARIANT
 
-// Specialised kernel pairs; {0, 0, 0} is the generic fallback.
-struct KernelVariant {
-  int d, grp, nb;
-  bool moe;
-  void (*mega)(StepArgs);
-  void (*op)(StepArgs, uint32_t);
-  void (*loop)(StepArgs);
-};
-#define MPK_VARIANT(D, G, N, M) {D, G, N, M, mpk_mega_kernel<D, G, N, M>, mpk_op_kernel<D, G, N, M>, mpk_loop_kernel<D, G, N, M>}
-static const KernelVariant kVariants[] = {
-    MPK_VARIANT(64, 2, 1, false), MPK_VARIANT(128, 4, 1, false), MPK_VARIANT(128, 8, 1, false),
-    MPK_VARIANT(128, 8, 9, false),   // batch 1 with large linear tasks (the 70B shape)
-    MPK_VARIANT(128, 4, 8, false), MPK_VARIANT(128, 8, 8, true),
-    MPK_VARIANT(0, 0, 0, false), MPK_VARIANT(0, 0, 0, true),   // generic fallbacks, dense and mixture of experts
-};
 static const KernelVariant* pick_variant(uint32_t d, uint32_t grp, uint32_t batch, bool moe, bool large_tasks) {
-  const int n = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+  const int n = kNumVariants;
   for (int pass = (batch == 1 && large_tasks) ? 0 : 1; pass < 2; ++pass) {
     const int nb = batch == 1 ? (pass == 0 ? 9 : 1) : (batch > 4 && batch <= 16 ? 8 : -1);
-    for (int i = 0; i < n; ++i)
-      if (kVariants[i].d == (int)d && kVariants[i].grp == (int)grp && kVariants[i].nb == nb && kVariants[i].moe == moe) return &kVariants[i];
+    for (int i = 0; i < n; ++i) {
+      const KernelVariant* v = variant_at(i);
+      if (v->d == (int)d && v->grp == (int)grp && v->nb == nb && v->moe == moe) return v;
+    }
   }
-  return &kVariants[moe ? n - 1 : n - 2];
+  return variant_at(moe ? n - 1 : n - 2);   // the generic fallbacks come last: dense, then mixture of experts
 }
 
 }  // namespace mpk
+
 
 // =============================================================================== host side
 using namespace mpk;
