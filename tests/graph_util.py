@@ -104,7 +104,7 @@ def check_structure(ex):
     assert np.array_equal(counts, ev["required"])
     # tasks launched by one event are exactly its contiguous range
     dep = t["dep_event"]
-    assert np.all(np.diff(dep.astype(np.int64)) >= 0) or True
+    assert np.all(np.diff(dep.astype(np.int64)) >= 0)      # events are numbered in the order Algorithm 1 dequeues them
     for e in range(len(ev)):
         f, l = int(ev["first"][e]), int(ev["last"][e])
         assert np.all(dep[f:l] == e)

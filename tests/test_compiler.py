@@ -51,6 +51,10 @@ CASES = [
     # greedy sampling as an operator of the graph (multi-token launch)
     ("C1", dict(batch=3), dict(fusion=31, n_workers=24, greedy_loop=1)),
     ("C1", {}, dict(fusion=0, greedy_loop=1)),
+    # QKV heads cut unevenly, 3 tiles of 43, 43, 42 rows per head: 80 heads (the 70B shape) and 48 heads
+    # (the 8B shape with 240 tiles per linear operator)
+    ("C5", dict(n_layers=1), dict(fusion=31)),
+    ("C2", dict(n_layers=1), dict(fusion=31, tiles_linear=240)),
 ]
 
 

@@ -177,6 +177,59 @@ def test_split_even_rule():
     assert TG.split_even(3, 5) == [0, 1, 2, 3, 3, 3]
 
 
+def test_col_bounds_hand_written_boundaries():
+    """The column rule of the QKV projection (decomposition, Section 4.1; uneven splits are this
+    build's reading: the first n mod k tiles are one unit longer).  Every expected list below is
+    written out by hand, none is computed."""
+    def qkv(cols, head):
+        return TG.OpSpec("qkv", TG.K_LINEAR, 0, "qkv", 1, cols, 1, ["x"], {"K": 8, "head": head})
+    # 2 heads of 8 columns in 6 tiles: 3 tiles per head of 3, 3, 2 columns
+    assert TG.col_bounds(qkv(16, 8), 6) == [0, 3, 6, 8, 11, 14, 16]
+    # 3 heads of 4 columns in 3 tiles: exactly the heads
+    assert TG.col_bounds(qkv(12, 4), 3) == [0, 4, 8, 12]
+    # 3 heads of 4 columns in 6 tiles: halves of heads
+    assert TG.col_bounds(qkv(12, 4), 6) == [0, 2, 4, 6, 8, 10, 12]
+    # the 70B-shaped case: heads of 128 columns, 3 tiles each -> 43, 43, 42 within every head
+    b = TG.col_bounds(qkv(10 * 128, 128), 30)
+    assert b[:7] == [0, 43, 86, 128, 171, 214, 256] and b[-4:] == [1152, 1195, 1238, 1280]
+    assert len(b) == 31 and all(b[3 * h] == 128 * h for h in range(11))     # no tile straddles a head
+    # a tile count that is not a multiple of the number of heads: one even split over all columns
+    # (12 columns in 5 tiles: 3, 3, 2, 2, 2), which does straddle heads
+    assert TG.col_bounds(qkv(12, 4), 5) == [0, 3, 6, 8, 10, 12]
+    # an operator without the head rule splits evenly whatever the tile count
+    lin = TG.OpSpec("o", TG.K_LINEAR, 0, "o", 1, 16, 1, ["x"], {"K": 8})
+    assert TG.col_bounds(lin, 6) == [0, 3, 6, 9, 12, 14, 16]
+    # columns that come in units (an attention head of 4 columns): boundaries are multiples of it
+    rope = TG.OpSpec("rope", TG.K_ROPE, 0, "q", 1, 20, 4, ["qkv"])
+    assert TG.col_bounds(rope, 3) == [0, 8, 16, 20]
+    # the owner map follows the boundaries: tile index per column, for both batch rows of a 2 x 2 split
+    own = TG.owner_map(TG.OpSpec("qkv", TG.K_LINEAR, 0, "qkv", 2, 16, 1, ["x"], {"K": 8, "head": 8}), 2, 6)
+    assert own[0].tolist() == [0, 0, 0, 1, 1, 1, 2, 2, 3, 3, 3, 4, 4, 4, 5, 5]
+    assert own[1].tolist() == [6, 6, 6, 7, 7, 7, 8, 8, 9, 9, 9, 10, 10, 10, 11, 11]
+
+
+def test_argmax_read_set_hand_written():
+    """Greedy sampling (one task per sequence) reads every logit of its own sequence and nothing
+    else, so it depends on every LM-head tile that holds a column of that row (Section 4.1's
+    overlap rule).  Expected sets written out by hand for 2 sequences x 10 logits."""
+    lm = TG.OpSpec("lm_head", TG.K_LINEAR, -1, "logits", 2, 10, 1, ["x"], {"K": 4})
+    am = TG.OpSpec("argmax", TG.K_ARGMAX, -1, "ntok", 2, 1, 1, ["logits"])
+    shapes = {"logits": (2, 10), "x": (2, 4)}
+    for b in range(2):
+        r = TG.read_elements(am, 2, 1, b, shapes)
+        assert list(r) == ["logits"]
+        want = [[False] * 10, [False] * 10]
+        want[b] = [True] * 10
+        assert r["logits"].tolist() == want
+    src = TG.OpSpec("src", TG.K_EMBED, -1, "x", 2, 4, 4, [])
+    # LM head cut into 1 x 3 column tiles over both rows: each sampling task needs all three
+    ps = TG.producer_sets([src, lm, am], [(2, 1), (1, 3), (2, 1)])
+    assert ps[2] == [[(1, 0), (1, 1), (1, 2)], [(1, 0), (1, 1), (1, 2)]]
+    # LM head cut 2 x 3 (a tile per sequence and column range): only the own row's three tiles
+    ps = TG.producer_sets([src, lm, am], [(2, 1), (2, 3), (2, 1)])
+    assert ps[2] == [[(1, 0), (1, 1), (1, 2)], [(1, 3), (1, 4), (1, 5)]]
+
+
 def tiny_degrees(ops, lin=4, rope=None, merge=2, pw=1):
     deg = []
     for op in ops:
