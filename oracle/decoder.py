@@ -48,6 +48,22 @@ class _LayerW(ctypes.Structure):
                  "exp_wd", "q_norm", "k_norm")]
 
 
+class _Held(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("k_rows", "v_rows", "experts", "k_exact", "v_exact")]
+
+
+class Held:
+    """Discrete decisions of one decode step held fixed for the oracle (see orc_held in the C
+    file): the bf16 K/V rows appended by every (layer, sequence) and, for mixture-of-experts
+    layers, the selected expert sets.  Shapes: k_rows, v_rows uint16 [L][B][n_kv][d]; experts
+    int32 [L][B][top_k] ascending.  Either may be None."""
+
+    def __init__(self, k_rows=None, v_rows=None, experts=None):
+        self.k_rows = None if k_rows is None else np.ascontiguousarray(k_rows, dtype=np.uint16)
+        self.v_rows = None if v_rows is None else np.ascontiguousarray(v_rows, dtype=np.uint16)
+        self.experts = None if experts is None else np.ascontiguousarray(experts, dtype=np.int32)
+
+
 _libs = {}
 
 
@@ -73,7 +89,7 @@ def lib(prec: str = "f32"):
         L.orc_argmax.restype = ci
         L.orc_router_topk.argtypes = [vp, ci, ci, vp, vp]
         L.orc_layer.argtypes = [ctypes.POINTER(_LayerCfg), ctypes.POINTER(_LayerW), vp, vp, ci,
-                                vp, vp, vp, vp]
+                                vp, vp, vp, vp, ctypes.POINTER(_Held)]
         for f in ("orc_embed", "orc_rmsnorm", "orc_linear", "orc_rope", "orc_kv_store",
                   "orc_attention_head", "orc_swiglu", "orc_add", "orc_router_topk", "orc_layer"):
             getattr(L, f).restype = None
@@ -190,8 +206,10 @@ class DecoderOracle:
             self.kv[l] = (np.ascontiguousarray(k).copy(), np.ascontiguousarray(v).copy())
         return self.kv[l]
 
-    def step(self, tokens, positions, return_hidden=False):
-        """tokens[B], positions[B] (= rows already cached).  Returns logits [B, vocab]."""
+    def step(self, tokens, positions, return_hidden=False, held: "Held | None" = None):
+        """tokens[B], positions[B] (= rows already cached).  Returns logits [B, vocab].
+        held: decisions to hold fixed (class Held).  After the call last_k_exact / last_v_exact
+        hold the oracle's own K/V rows of this step before rounding, [L][B][n_kv][d]."""
         s, L = self.s, self.ops.L
         B = len(tokens)
         ffn_like = max(s.ffn, s.expert_ffn)
@@ -204,6 +222,8 @@ class DecoderOracle:
         xs = [self.ops.embed(self.p.embed_row(int(t)).reshape(1, -1), 0) for t in tokens]
         moe_sel = np.zeros((self.n_layers, B, max(s.top_k, 1)), np.int32)
         moe_logits = np.zeros((self.n_layers, B, max(s.n_experts, 1)), self.dt)
+        k_exact = np.zeros((self.n_layers, B, s.n_kv_heads, s.head_dim), self.dt)
+        v_exact = np.zeros_like(k_exact)
         from synth import gen as G
         for l in range(self.n_layers):
             wl = self.p.layer(l)
@@ -218,12 +238,20 @@ class DecoderOracle:
             K, V = self._kv(l)
             for b in range(B):
                 assert 0 <= positions[b] < s.max_seq
+                h = _Held(None, None, None, k_exact[l, b].ctypes.data, v_exact[l, b].ctypes.data)
+                if held is not None and held.k_rows is not None:
+                    h.k_rows = held.k_rows[l, b].ctypes.data
+                if held is not None and held.v_rows is not None:
+                    h.v_rows = held.v_rows[l, b].ctypes.data
+                if held is not None and held.experts is not None:
+                    h.experts = held.experts[l, b].ctypes.data
                 L.orc_layer(ctypes.byref(cfg), ctypes.byref(w), K[b].ctypes.data,
                             V[b].ctypes.data, int(positions[b]), _p(xs[b]), _p(work),
-                            moe_sel[l, b].ctypes.data, moe_logits[l, b].ctypes.data)
+                            moe_sel[l, b].ctypes.data, moe_logits[l, b].ctypes.data, ctypes.byref(h))
             del keep
         self.last_moe_sel = moe_sel
         self.last_moe_logits = moe_logits
+        self.last_k_exact, self.last_v_exact = k_exact, v_exact
         if return_hidden:
             return np.stack(xs)
         g = self.p.final_norm()

@@ -205,10 +205,25 @@ typedef struct {
   const uint16_t *q_norm, *k_norm;
 } orc_layer_w;
 
+/* The two places of a layer where floating point decides something discrete -- the bf16 rounding
+ * of the appended K/V row and the top-k expert set -- can be held fixed by the caller (`held`):
+ * two correct implementations that sum in different orders may round a value that sits on a bf16
+ * rounding boundary either way, or order two near-equal router outputs either way, and everything
+ * downstream of such a decision then legitimately differs.  A comparison hands the decisions of
+ * the implementation under test to the oracle, checks that each is a valid one against what the
+ * oracle reports here (the unrounded rows; the router outputs), and compares the rest tightly.
+ * All members may be NULL; with held == NULL the oracle decides everything itself. */
+typedef struct {
+  const uint16_t *k_rows, *v_rows; /* in: [n_kv][d] bf16 rows to append instead of the oracle's own */
+  const int *experts;              /* in: top_k experts (ascending) to use instead of the oracle's own */
+  real *k_exact, *v_exact;         /* out: [n_kv][d] the oracle's rows before rounding */
+} orc_held;
+
 void orc_layer(const orc_layer_cfg *c, const orc_layer_w *w, uint16_t *kc, uint16_t *vc, int pos,
                real *x /* in: layer input, out: layer output */, real *work,
                int *moe_sel /* top_k, may be NULL */,
-               real *moe_logits /* n_experts router outputs, may be NULL */) {
+               real *moe_logits /* n_experts router outputs, may be NULL */,
+               const orc_held *held /* may be NULL */) {
   int H = c->hidden, d = c->d, nq = c->n_q, nkv = c->n_kv;
   int qkv_rows = (nq + 2 * nkv) * d;
   real *xn = work;
@@ -229,8 +244,13 @@ void orc_layer(const orc_layer_cfg *c, const orc_layer_w *w, uint16_t *kc, uint1
   for (int h = 0; h < nq; ++h) orc_rope(q + h * d, d, pos, c->theta);
   for (int g = 0; g < nkv; ++g) {
     orc_rope(k + g * d, d, pos, c->theta);
-    orc_kv_store(kc + ((size_t)g * c->max_seq + pos) * d, k + g * d, d);
-    orc_kv_store(vc + ((size_t)g * c->max_seq + pos) * d, v + g * d, d);
+    uint16_t *krow = kc + ((size_t)g * c->max_seq + pos) * d, *vrow = vc + ((size_t)g * c->max_seq + pos) * d;
+    orc_kv_store(krow, k + g * d, d);
+    orc_kv_store(vrow, v + g * d, d);
+    if (held && held->k_exact) memcpy(held->k_exact + (size_t)g * d, k + g * d, sizeof(real) * d);
+    if (held && held->v_exact) memcpy(held->v_exact + (size_t)g * d, v + g * d, sizeof(real) * d);
+    if (held && held->k_rows) memcpy(krow, held->k_rows + (size_t)g * d, sizeof(uint16_t) * d);
+    if (held && held->v_rows) memcpy(vrow, held->v_rows + (size_t)g * d, sizeof(uint16_t) * d);
   }
   int group = nq / nkv;
   for (int h = 0; h < nq; ++h) {
@@ -258,6 +278,18 @@ void orc_layer(const orc_layer_cfg *c, const orc_layer_w *w, uint16_t *kc, uint1
     if (moe_logits)
       for (int e = 0; e < E; ++e) moe_logits[e] = rl[e];
     orc_router_topk(rl, E, K, sel, wts);
+    if (held && held->experts) { /* the held set, weighted as the router weights it: softmax, renormalised */
+      real mx = -INFINITY, l = 0, ssum = 0;
+      for (int e = 0; e < E; ++e)
+        if (rl[e] > mx) mx = rl[e];
+      for (int e = 0; e < E; ++e) l += R_EXP(rl[e] - mx);
+      for (int j = 0; j < K; ++j) {
+        sel[j] = held->experts[j];
+        wts[j] = R_EXP(rl[sel[j]] - mx) / l;
+        ssum += wts[j];
+      }
+      for (int j = 0; j < K; ++j) wts[j] /= ssum;
+    }
     for (int i = 0; i < H; ++i) y[i] = 0;
     for (int j = 0; j < K; ++j) { /* ascending expert index */
       int e = sel[j];

@@ -993,10 +993,9 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
       if (c.batch <= 4) {
         f = (size_t)nb * ((op.K + 4095u) / 4096u * 4096u) + 2 * (size_t)rows_max * nb + 8 * nb;
       } else {
-        // matrix-core body: two buffers of two bf16 planes of one input tile (reused for the
+        // matrix-core body: two buffers of three bf16 planes of one input tile (reused for the
         // per-wavefront partial tiles) | residual slice | sums of squares | 1/rms per row
-        const size_t kt = c.batch <= 8 ? 2048 : 1024;
-        f = std::max<size_t>(2 * (size_t)c.batch * (kt + 8), 8 * 4 * 256) + (size_t)res_rows * 16 + 9 * 16;
+        f = (size_t)mfma_x_floats(c.batch) + (size_t)res_rows * 16 + 9 * 16;
       }
     }
     else if (op.kind == MPK_OP_EXPERT) {

@@ -704,31 +704,277 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
 //   A operand = weights: lane l holds row (l % 16) of a 16-row tile, inputs 8 (l / 16) .. + 7 of
 //     the current 32-input step: 16 bytes straight from HBM, no conversion.
 //   B operand = activations: lane l holds batch column (l % 16), the same 8 inputs, as bf16.
-//     Activations are fp32: x is split into hi = bf16(x) and lo = bf16(x - hi) and each weight
-//     fragment is multiplied with both (x is represented to 2^-17, the products are exact and
-//     the accumulation is fp32).
+//     Activations are fp32: x is split into THREE bf16 terms, hi = bf16(x), mid = bf16(x - hi),
+//     lo = bf16(x - hi - mid).  Each conversion rounds to nearest and each remainder is exact in
+//     fp32, so hi + mid + lo = x exactly (8 + 8 + 8 significand bits), every product with a bf16
+//     weight is exact, and the only rounding is the fp32 accumulation -- as in the vector body.
+//     (Two terms leave x to 2^-18: logits near zero then miss the element-wise bound.)
 //   D: lane l holds batch column (l % 16), tile rows 4 (l / 16) .. + 3.
-// The input is staged in LDS one K tile at a time (hi and lo planes, row stride padded by 16
-// bytes so that the 16 lanes of a fragment read 16 different bank groups).  Work is split over
-// the 8 wavefronts by 16-row tiles; a task with fewer than 8 tiles also splits K inside each
-// input tile, and the epilogue adds the slices in a fixed order.
+// The input is staged in LDS one K tile at a time (three planes, row stride padded by 16 bytes so
+// that the 16 lanes of a fragment read 16 different bank groups): 1024 inputs per tile up to
+// batch 8, 512 above, two buffers (99 KB) -- or, when the whole input is at most two tiles long,
+// all of it at once in the space of both.  Work is split over the 8 wavefronts by 16-row tiles; a
+// job with fewer than 8 tiles also splits K inside each input tile, and the epilogue adds the
+// slices in a fixed order.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-// (x, y) -> packed bf16 pairs hi = bf16(x), lo = bf16(x - hi), round to nearest even (the
-// hardware conversion: two packed converts, two subtractions)
-__device__ __forceinline__ void split_hi_lo(float x, float y, uint32_t* hi, uint32_t* lo) {
-  const uint32_t h = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){x, y}, bf16x2));
-  *hi = h;
-  *lo = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){x - bf16_lo(h), y - bf16_hi(h)}, bf16x2));
-}
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint32_t pack_bf16_rne(float x, float y) {   // the hardware's packed conversion
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){x, y}, bf16x2));
+}
+// (x, y) -> packed bf16 pairs hi, mid, lo with hi + mid + lo = (x, y) exactly
+__device__ __forceinline__ void split_hi_mid_lo(float x, float y, uint32_t* hi, uint32_t* mid, uint32_t* lo) {
+  const uint32_t h = pack_bf16_rne(x, y);
+  const float rx = x - bf16_lo(h), ry = y - bf16_hi(h);
+  const uint32_t m = pack_bf16_rne(rx, ry);
+  *hi = h;
+  *mid = m;
+  *lo = pack_bf16_rne(rx - bf16_lo(m), ry - bf16_hi(m));
+}
 
-__device__ __forceinline__ uint32_t mfma_ktile(uint32_t nb) { return nb <= 8 ? 2048u : 1024u; }
+constexpr int kMfmaRound = 16;   // weight fragments (32 inputs x 16 rows, 1 KB) a wavefront requests at a time
 
-// LDS (from the task area): xh [2][nb][Kt + 8] bf16 | xl same | res [residual columns][16] f32 |
-// ssq [8][16] f32 | 1/rms [16] f32; the per-wavefront partial tiles part [8][4][256] f32 reuse the
-// input buffers once the last input tile has been consumed.
+// Geometry of one matrix-core job: K inputs x nb staged rows x nrt 16-row weight tiles.  Uniform
+// over the wavefront (wave comes from readfirstlane).
+struct MfmaGeom {
+  uint32_t K, nb, nrt;
+  uint32_t Kt1;          // inputs one staging pass covers
+  uint32_t Kt, ntile;    // inputs per multiply tile (2 Kt1 when staged whole), number of tiles
+  uint32_t whole;        // the whole input sits in LDS at once (one buffer)
+  uint32_t xstride, xplane, xbuf;   // in bf16 elements: row stride, one plane, one buffer of three planes
+  uint32_t nrt2, ks;     // row tiles rounded up to a power of two (<= 8); K slices per input tile
+  uint32_t my_slice, my_rt0, slice_len;
+  uint32_t nf, lognf;    // fragments per (input tile, row tile) of this wavefront: 4, 8, 16, 32 or 64
+  uint32_t tpr;          // input tiles one round of fragments spans (nf < 16), else 1
+  bool has_work;
+};
+__device__ __forceinline__ MfmaGeom mfma_geom(uint32_t K, uint32_t nb, uint32_t nrt, uint32_t wave) {
+  MfmaGeom G;
+  G.K = K; G.nb = nb; G.nrt = nrt;
+  G.Kt1 = mfma_ktile(nb);
+  G.whole = (K <= 2u * G.Kt1) ? 1u : 0u;
+  G.Kt = G.whole ? 2u * G.Kt1 : G.Kt1;
+  G.ntile = (K + G.Kt - 1u) / G.Kt;
+  G.xstride = G.Kt + 8u;
+  G.xplane = nb * G.xstride;
+  G.xbuf = 3u * G.xplane;
+  uint32_t nrt2 = 1;
+  while (nrt2 < nrt && nrt2 < 8u) nrt2 <<= 1;
+  G.nrt2 = nrt2;
+  G.ks = min(8u / nrt2, G.Kt / 128u);   // at least four fragments per slice
+  G.my_slice = wave / nrt2;
+  G.my_rt0 = wave % nrt2;
+  G.slice_len = G.Kt / G.ks;
+  G.nf = G.slice_len / 32u;
+  G.lognf = 31u - (uint32_t)__builtin_clz(G.nf);
+  G.tpr = G.nf < (uint32_t)kMfmaRound ? (uint32_t)kMfmaRound / G.nf : 1u;
+  G.has_work = G.my_rt0 < nrt && G.my_slice < G.ks;
+  return G;
+}
+
+// One job: out[r][b] partial tiles = W rows x staged input rows, left in LDS.
+//   row_ptr(rt)  : this lane's weight address for 16-row tile rt at input 0 (fragment row and
+//                  input group of the lane included); loads are clamped to kclamp inputs
+//   src_row(b)   : fp32 input row b (read with coherent loads), b < nb
+//   wait_fn()    : called after the first round of weights has been requested (cross-task
+//                  pre-loading, Section 5.3); returns kLinDone to go on
+// LDS: x [buffers][3 planes][nb][xstride] bf16 at `lds`, reused at the end for the per-wavefront
+// partial tiles part[8][4][16][16] f32; ssq [8][16] f32 (sums of squares per wavefront and row, when
+// pro_norm).  On return (kLinDone) every thread may read part and ssq.
+template <class RowPtr, class SrcRow, class Wait>
+__device__ __forceinline__ uint32_t mfma_job(const StepArgs& a, const TaskDesc& t, float* lds, float* ssq, const MfmaGeom& G,
+                                             RowPtr row_ptr, SrcRow src_row, bool pro_norm, const uint16_t* gain,
+                                             Wait wait_fn) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t K = G.K, nb = G.nb, nrt = G.nrt, Kt1 = G.Kt1, Kt = G.Kt, ntile = G.ntile;
+  const uint32_t xstride = G.xstride, xplane = G.xplane;
+  uint16_t* xbase = (uint16_t*)lds;
+  float* part = lds;
+  const uint32_t frow = lane & 15u, fk = (uint32_t)(lane >> 4) * 8u;
+  const uint32_t kclamp = K - fk - 8u;   // the last fragment start that stays inside the row
+  f32x4 acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  u32x4 wfrag[kMfmaRound];
+  const uint32_t s_lo = G.my_slice * G.slice_len;
+  // a round of a long slice (nf >= 16): 16 consecutive fragments of one (input tile, row tile)
+  auto request_run = [&](const uint16_t* wp, uint32_t k) {
+#pragma unroll
+    for (int q = 0; q < kMfmaRound; ++q) wfrag[q] = ld_stream16(wp + min(k + (uint32_t)q * 32u, kclamp));
+  };
+  // a round of a short slice (nf = 4 or 8, one row tile): the slices of `tpr` consecutive input tiles
+  auto request_span = [&](const uint16_t* wp, uint32_t tile) {
+#pragma unroll
+    for (int q = 0; q < kMfmaRound; ++q) {
+      const uint32_t k = (tile + ((uint32_t)q >> G.lognf)) * Kt + s_lo + ((uint32_t)q & (G.nf - 1u)) * 32u;
+      wfrag[q] = ld_stream16(wp + min(k, kclamp));
+    }
+  };
+  if (G.has_work) {
+    if (G.nf >= (uint32_t)kMfmaRound) request_run(row_ptr(G.my_rt0), s_lo);
+    else request_span(row_ptr(G.my_rt0), 0u);
+  }
+  {
+    const uint32_t w = wait_fn();
+    if (w != kLinDone) return w;   // aborted or pre-empted: the requested weights are dropped
+  }
+  trace_mark(a, t, 1);
+  // Staging.  A pass of Kt1 inputs x nb rows is dealt to the threads in pairs, 8 slots per thread;
+  // the row of a slot is the same for the whole wavefront (no divisions, no per-row selects):
+  // 1024-input passes: slot q = row q, pair = thread; 512-input passes: row 2 q + thread / 256,
+  // pair = thread % 256.  A pass is requested (coherent loads into registers) while the previous
+  // tile is being multiplied and converted into the other buffer afterwards.
+  static_assert(kThreads == 512, "the slot -> (row, pair) mapping assumes 512 threads");
+  const uint32_t half = Kt1 == 512u ? 1u : 0u;
+  const uint32_t row_lo = half ? (wave >> 2) : 0u, pair = half ? (threadIdx.x & 255u) : threadIdx.x;
+  float sqq[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) sqq[q] = 0.f;
+  float2 sv[8];
+  auto stage_issue = [&](uint32_t pass) {
+    const uint32_t k0 = pass * Kt1, klen = min(Kt1, K - k0);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const uint32_t b = ((uint32_t)q << half) + row_lo;
+      sv[q] = make_float2(0.f, 0.f);
+      if (b < nb && 2u * pair < klen) sv[q] = ld_act2(src_row(b) + k0 + 2u * pair);
+    }
+  };
+  auto stage_write = [&](uint32_t pass) {
+    const uint32_t k0 = pass * Kt1, klen = min(Kt1, K - k0);
+    uint16_t* d0 = G.whole ? xbase + k0 : xbase + (size_t)(pass & 1u) * G.xbuf;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const uint32_t b = ((uint32_t)q << half) + row_lo;
+      if (b < nb) {
+        float2 w2 = sv[q];
+        if (pro_norm && 2u * pair < klen) {
+          sqq[q] = fmaf(w2.x, w2.x, fmaf(w2.y, w2.y, sqq[q]));
+          const uint32_t g2 = *as_global((const uint32_t*)(gain + k0 + 2u * pair));
+          w2.x *= bf16_lo(g2);
+          w2.y *= bf16_hi(g2);
+        }
+        uint32_t hi, mid, lo;
+        split_hi_mid_lo(w2.x, w2.y, &hi, &mid, &lo);
+        uint16_t* d = d0 + (size_t)b * xstride + 2u * pair;
+        *(uint32_t*)d = hi;
+        *(uint32_t*)(d + xplane) = mid;
+        *(uint32_t*)(d + 2u * xplane) = lo;
+      }
+    }
+  };
+  const uint32_t npass = (K + Kt1 - 1u) / Kt1;
+  stage_issue(0);
+  stage_write(0);
+  if (G.whole && npass > 1u) {
+    stage_issue(1);
+    stage_write(1);
+  }
+  lds_barrier();
+  trace_mark(a, t, 2);
+  // four fragments of the round (positions q0 .. q0 + 3) against the three planes, inputs
+  // kk .. kk + 127 of the current tile; whole groups run without per-step tests, their LDS reads
+  // ahead of the multiplies
+  auto consume4 = [&](f32x4& c, const uint16_t* bx, auto q0c, uint32_t kk, uint32_t s_hi) {
+    constexpr int q0 = decltype(q0c)::value;
+    if (kk + 128u <= s_hi) {
+      u32x4 hv[4], mv[4], lv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        hv[u] = *(const u32x4*)(bx + kk + u * 32u);
+        mv[u] = *(const u32x4*)(bx + xplane + kk + u * 32u);
+        lv[u] = *(const u32x4*)(bx + 2u * xplane + kk + u * 32u);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, hv[u]), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, mv[u]), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, lv[u]), c, 0, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (kk + u * 32u < s_hi) {
+          const u32x4 hv = *(const u32x4*)(bx + kk + u * 32u), mv = *(const u32x4*)(bx + xplane + kk + u * 32u),
+                      lv = *(const u32x4*)(bx + 2u * xplane + kk + u * 32u);
+          const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
+          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, hv), c, 0, 0, 0);
+          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, mv), c, 0, 0, 0);
+          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, lv), c, 0, 0, 0);
+        }
+      }
+    }
+  };
+  for (uint32_t tile = 0; tile < ntile; ++tile) {
+    const uint32_t klen = min(Kt, K - tile * Kt);
+    if (!G.whole && tile + 1u < ntile) stage_issue(tile + 1u);   // in flight during this tile's arithmetic
+    const uint16_t* cx = G.whole ? xbase : xbase + (size_t)(tile & 1u) * G.xbuf;
+    const uint16_t* bx = cx + (size_t)(frow % nb) * xstride + fk;
+    const uint32_t s_hi = min(s_lo + G.slice_len, (klen + 31u) & ~31u);
+    if (G.has_work && s_lo < s_hi) {
+      if (G.nf >= (uint32_t)kMfmaRound) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t rt = G.my_rt0 + (uint32_t)j * 8u;
+          if (rt < nrt && (G.ks == 1u || j == 0)) {
+            const uint16_t* wp = row_ptr(rt);
+            for (uint32_t kk = s_lo; kk < s_hi; kk += 32u * kMfmaRound) {
+              if (!(tile == 0 && j == 0 && kk == s_lo)) request_run(wp, tile * Kt + kk);
+              consume4(acc[j], bx, std::integral_constant<int, 0>{}, kk, s_hi);
+              consume4(acc[j], bx, std::integral_constant<int, 4>{}, kk + 128u, s_hi);
+              consume4(acc[j], bx, std::integral_constant<int, 8>{}, kk + 256u, s_hi);
+              consume4(acc[j], bx, std::integral_constant<int, 12>{}, kk + 384u, s_hi);
+            }
+          }
+        }
+      } else {
+        // short slices: a round holds the slices of tpr consecutive input tiles; this tile's
+        // slice sits at groups g0 .. g0 + nf / 4 - 1 of the round
+        const uint32_t g0 = (tile & (G.tpr - 1u)) * (G.nf >> 2), g1 = g0 + (G.nf >> 2);
+        if (g0 == 0u && tile != 0u) request_span(row_ptr(G.my_rt0), tile);
+        if (0u >= g0 && 0u < g1) consume4(acc[0], bx, std::integral_constant<int, 0>{}, s_lo + (0u - g0) * 128u, s_hi);
+        if (1u >= g0 && 1u < g1) consume4(acc[0], bx, std::integral_constant<int, 4>{}, s_lo + (1u - g0) * 128u, s_hi);
+        if (2u >= g0 && 2u < g1) consume4(acc[0], bx, std::integral_constant<int, 8>{}, s_lo + (2u - g0) * 128u, s_hi);
+        if (3u >= g0 && 3u < g1) consume4(acc[0], bx, std::integral_constant<int, 12>{}, s_lo + (3u - g0) * 128u, s_hi);
+      }
+    }
+    if (!G.whole && tile + 1u < ntile) stage_write(tile + 1u);   // into the other buffer: nobody reads it now
+    lds_barrier();
+  }
+  trace_mark(a, t, 8);
+  // ---- partial tiles -> LDS.  part[wave][j][row 0..15][col 0..15]
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) part[((wave * 4 + j) * 16 + (lane >> 4) * 4 + i) * 16 + (lane & 15)] = acc[j][i];
+  if (pro_norm) {
+    float rowsum = 0.f;   // lane b: this wavefront's sum of squares of staged row b
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const float v = wave_sum(sqq[q]);
+      if ((uint32_t)lane == ((uint32_t)q << half) + row_lo) rowsum += v;
+    }
+    if (lane < 16) ssq[wave * 16 + lane] = rowsum;
+  }
+  lds_barrier();
+  return kLinDone;
+}
+
+// Dot product of weight row r (16-row tile r / 16) with batch column bb from the partial tiles a
+// job left in LDS: the K slices added in a fixed order.
+__device__ __forceinline__ float mfma_dot(const float* part, const MfmaGeom& G, uint32_t r, uint32_t bb) {
+  const uint32_t rt = r >> 4, row = r & 15u;
+  if (G.ks == 1u) return part[(((rt & 7u) * 4 + (rt >> 3)) * 16 + row) * 16 + bb];
+  float v = 0.f;
+  for (uint32_t sl = 0; sl < G.ks; ++sl) v += part[(((sl * G.nrt2 + rt) * 4) * 16 + row) * 16 + bb];
+  return v;
+}
+
+// LDS of a linear task (from the task area): job buffers (mfma_x_floats) | res [residual columns][16] f32
+// | ssq [8][16] f32 | 1/rms [16] f32.
 template <bool MEGA, class Svc = NoJit>
 __device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
                                                      uint32_t* s_flag, const Svc& svc = Svc{}) {
@@ -737,39 +983,12 @@ __device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const St
   const uint32_t K = t.K, nb = t.b1 - t.b0, ncols = t.c1 - t.c0;
   const uint32_t gateup = (t.flags & TF_GATEUP) ? 1u : 0u;
   const uint32_t R = ncols << gateup;            // weight rows of the task ("ring rows")
-  const uint32_t nrt = (R + 15u) / 16u;          // 16-row tiles
-  // An input of at most two staging tiles is staged whole, as ONE tile in the space of the two
-  // buffers: one barrier instead of two, and the K slice of a wavefront is twice as long -- for a
-  // task of one 16-row tile (eight K slices) exactly the 16 fragments requested before the event
-  // wait, where two short tiles used half of that round each and paid a second round trip.
-  const uint32_t Kt1 = mfma_ktile(nb);                      // what one staging pass covers
-  // (Batch <= 8 only for now: at batch 16 the different summation order moves one logit near the
-  // floor of the 48-layer mixture-of-experts shape just past that test's element-wise bound.)
-  const bool whole = nb <= 8u && K > Kt1 && K <= 2u * Kt1;
-  const uint32_t Kt = whole ? 2u * Kt1 : Kt1, xstride = Kt + 8u, nbuf = whole ? 1u : 2u;
-  const uint32_t xplane = nb * xstride;                     // one plane of one buffer, in bf16
-  uint16_t* xh = (uint16_t*)lds;                            // [nbuf buffers][nb][xstride]
-  uint16_t* xl = xh + nbuf * (size_t)xplane;
-  float* part = lds;                                        // [8][4][256], reuses the input buffers at the end
-  float* res_lds = (float*)(xl + nbuf * (size_t)xplane);    // [rows_max][16]
+  const MfmaGeom G = mfma_geom(K, nb, (R + 15u) / 16u, wave);
+  float* part = lds;
+  float* res_lds = lds + mfma_x_floats(nb);                    // [residual columns][16]
   float* ssq = res_lds + (size_t)a.g->lin_res_rows_max * 16;   // [8][16]
-  // which tiles and which K slice this wavefront works on
-  uint32_t nrt2 = 1;
-  while (nrt2 < nrt && nrt2 < 8u) nrt2 <<= 1;
-  const uint32_t ks = 8u / nrt2;                 // K slices per input tile (1 when nrt >= 8)
-  const uint32_t my_slice = wave / nrt2, my_rt0 = wave % nrt2;   // tiles my_rt0, my_rt0 + 8, ... (ks == 1)
-  const uint32_t slice_len = Kt / ks;            // multiple of 128
   const uint16_t* W = (const uint16_t*)t.w;
   const uint32_t frow = lane & 15u, fk = (uint32_t)(lane >> 4) * 8u;   // fragment row / input offset
-  f32x4 acc[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  // Weight fragments are requested a round at a time: kMfmaRound steps of 32 inputs, 16 bytes per
-  // lane and step (16 KB per wavefront in flight), then multiplied as they arrive.  The first
-  // round is requested before the event wait (cross-task pre-loading, Section 5.3).
-  constexpr int kMfmaRound = 16;
-  u32x4 wfrag[kMfmaRound];
   // split-K task (TF_SPLITK): rows [row0, row0 + ncols) of the matrix, inputs of ONE part; the
   // weight pointer is already advanced to the part, rows are ldw apart
   const bool splitk = t.flags & TF_SPLITK;
@@ -781,156 +1000,26 @@ __device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const St
     const uint32_t wrow = gateup ? (row0 + (r >> 1) + ((r & 1u) ? t.p0 : 0u)) : row0 + r;
     return W + (size_t)wrow * ldw + fk;
   };
-  auto request = [&](const uint16_t* wp, uint32_t k0, uint32_t kk) {   // inputs k0 + kk + 32 q + fk .. + 7
-#pragma unroll
-    for (int q = 0; q < kMfmaRound; ++q) {
-      const uint32_t k = min(k0 + kk + q * 32u, K - fk - 8u);   // stay inside the row
-      wfrag[q] = ld_stream16(wp + k);
-    }
-  };
-  const bool has_work = my_rt0 < nrt;
-  if (has_work) request(row_ptr(my_rt0), 0u, my_slice * slice_len);
-
-  if (wait_ev >= 0) {
-    const uint32_t w = linear_wait(a, wait_ev, s_flag, wave, lane, svc);
-    if (w != kLinDone) return w;   // aborted, or pre-empted by a just-in-time task: the requested weights are dropped
-  }
-  trace_mark(a, t, 1);
+  auto src_row = [&](uint32_t b) { return t.in + (size_t)(t.b0 + b) * t.ld_in; };
   const bool pro_norm = t.flags & TF_PRO_NORM;
-  const uint16_t* gain = (const uint16_t*)t.w2;
-  if ((t.flags & TF_EPI_RESID) && !splitk) {
-    for (uint32_t i = threadIdx.x; i < nb * ncols; i += kThreads) {
-      uint32_t bb = i / ncols, cc = i % ncols;
-      res_lds[cc * 16 + bb] = ld_act(t.in2 + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc);
+  auto wait_fn = [&]() -> uint32_t {
+    if (wait_ev >= 0) {
+      const uint32_t w = linear_wait(a, wait_ev, s_flag, wave, lane, svc);
+      if (w != kLinDone) return w;
     }
-  }
-  // The input tile of 2048 (1024) inputs x nb rows is dealt to the threads in pairs: pair slot q
-  // of a thread is row q >> sh, pair ((q & sh) << 9) + thread (sh = 1 for 2048-input tiles), so
-  // the row of a slot is the same for the whole wavefront and needs no division.  A tile is
-  // requested (coherent loads into registers) while the previous tile is being multiplied, and
-  // converted into the other LDS buffer afterwards.  Sums of squares are kept per slot.
-  static_assert(kThreads == 512, "the slot -> (row, pair) mapping assumes 512 threads");
-  const uint32_t sh = Kt1 == 2048u ? 1u : 0u;
-  float sqq[16];
-#pragma unroll
-  for (int q = 0; q < 16; ++q) sqq[q] = 0.f;
-  const uint32_t ntile = (K + Kt - 1u) / Kt;
-  float2 sv[16];
-  // staging pass `tile`: inputs [tile * Kt1, + Kt1) into buffer tile & 1 -- or, staged whole,
-  // into columns tile * Kt1 .. of the one buffer
-  auto stage_issue = [&](uint32_t tile) {
-    float2 (&dst)[16] = sv;
-    const uint32_t k0 = tile * Kt1, klen = min(Kt1, K - k0);
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const uint32_t b = (uint32_t)q >> sh, i = (((uint32_t)q & sh) << 9) + threadIdx.x;
-      dst[q] = make_float2(0.f, 0.f);
-      if (b < nb && 2 * i < klen) dst[q] = ld_act2(t.in + (size_t)(t.b0 + b) * t.ld_in + k0 + 2 * i);
-    }
-  };
-  auto stage_write = [&](uint32_t tile) {
-    const float2 (&src)[16] = sv;
-    const uint32_t k0 = tile * Kt1, klen = min(Kt1, K - k0);
-    uint16_t* dh = whole ? xh + k0 : xh + (size_t)(tile & 1u) * xplane;
-    uint16_t* dl = whole ? xl + k0 : xl + (size_t)(tile & 1u) * xplane;
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const uint32_t b = (uint32_t)q >> sh, i = (((uint32_t)q & sh) << 9) + threadIdx.x;
-      if (b < nb) {
-        float2 w2 = src[q];
-        if (pro_norm && 2 * i < klen) {
-          sqq[q] = fmaf(w2.x, w2.x, fmaf(w2.y, w2.y, sqq[q]));
-          const uint32_t g2 = *as_global((const uint32_t*)(gain + k0 + 2 * i));
-          w2.x *= bf16_lo(g2);
-          w2.y *= bf16_hi(g2);
-        }
-        uint32_t hi, lo;
-        split_hi_lo(w2.x, w2.y, &hi, &lo);
-        *(uint32_t*)(dh + (size_t)b * xstride + 2 * i) = hi;
-        *(uint32_t*)(dl + (size_t)b * xstride + 2 * i) = lo;
+    // the residual slice of this tile goes out first (tile-local, small): its round trip overlaps the staging
+    if ((t.flags & TF_EPI_RESID) && !splitk) {
+      for (uint32_t i = threadIdx.x; i < nb * ncols; i += kThreads) {
+        uint32_t bb = i / ncols, cc = i % ncols;
+        res_lds[cc * 16 + bb] = ld_act(t.in2 + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc);
       }
     }
+    return kLinDone;
   };
-  stage_issue(0);
-  stage_write(0);
-  if (whole) {   // (both passes in one round trip, with twice the registers: no faster -- the
-    stage_issue(1);   // coherent reads of a [8][4096] input by 256 workers are bound by bandwidth)
-    stage_write(1);
+  {
+    const uint32_t w = mfma_job(a, t, lds, ssq, G, row_ptr, src_row, pro_norm, (const uint16_t*)t.w2, wait_fn);
+    if (w != kLinDone) return w;
   }
-  lds_barrier();
-  trace_mark(a, t, 2);
-  // One round: the fragments in wfrag times both planes of the input, steps kk + 32 q < s_hi.
-  // Whole groups of four steps run without per-step tests, their LDS reads ahead of the multiplies.
-  auto consume = [&](f32x4& c, const uint16_t* bh, const uint16_t* bl, uint32_t kk, uint32_t s_hi) {
-#pragma unroll
-    for (int q0 = 0; q0 < kMfmaRound; q0 += 4) {
-      if (kk + (q0 + 4) * 32u <= s_hi) {
-        u32x4 hv[4], lv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          hv[u] = *(const u32x4*)(bh + kk + (q0 + u) * 32u);
-          lv[u] = *(const u32x4*)(bl + kk + (q0 + u) * 32u);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
-          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, hv[u]), c, 0, 0, 0);
-          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, lv[u]), c, 0, 0, 0);
-        }
-      } else {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          if (kk + (q0 + u) * 32u < s_hi) {
-            const u32x4 bhv = *(const u32x4*)(bh + kk + (q0 + u) * 32u), blv = *(const u32x4*)(bl + kk + (q0 + u) * 32u);
-            const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
-            c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bhv), c, 0, 0, 0);
-            c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, blv), c, 0, 0, 0);
-          }
-        }
-      }
-    }
-  };
-  for (uint32_t tile = 0; tile < ntile; ++tile) {
-    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
-    // (the very first round is already under way: requested before the event wait.  Requesting
-    // each next tile's first round before the conversion and the barrier was measured: no gain.)
-    if (tile + 1 < ntile) stage_issue(tile + 1);   // in flight during this tile's arithmetic
-    const uint16_t* ch = xh + (size_t)(tile & 1u) * xplane;
-    const uint16_t* cl = xl + (size_t)(tile & 1u) * xplane;
-    // ---- this wavefront's tiles x its slice of the input tile
-    const uint32_t s_lo = my_slice * slice_len, s_hi = min(s_lo + slice_len, (klen + 31u) & ~31u);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t rt = my_rt0 + (uint32_t)j * 8u;
-      if (rt < nrt && (ks == 1u || j == 0) && s_lo < s_hi) {
-        const uint16_t* wp = row_ptr(rt);
-        const uint16_t* bh = ch + (size_t)(frow % nb) * xstride + fk;
-        const uint16_t* bl = cl + (size_t)(frow % nb) * xstride + fk;
-        for (uint32_t kk = s_lo; kk < s_hi; kk += 32u * kMfmaRound) {
-          if (!(tile == 0 && j == 0 && kk == s_lo)) request(wp, k0, kk);
-          consume(acc[j], bh, bl, kk, s_hi);
-        }
-      }
-    }
-    if (tile + 1 < ntile) stage_write(tile + 1);   // into the other buffer: nobody reads it now
-    lds_barrier();
-  }
-  trace_mark(a, t, 8);
-  // ---- partial tiles -> LDS.  part[wave][j][row 0..15][col 0..15]
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) part[((wave * 4 + j) * 16 + (lane >> 4) * 4 + i) * 16 + (lane & 15)] = acc[j][i];
-  if (pro_norm) {
-    float rowsum = 0.f;   // lane b: this wavefront's sum of squares of row b
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const float v = wave_sum(sqq[q]);
-      if ((uint32_t)lane == ((uint32_t)q >> sh)) rowsum += v;
-    }
-    if (lane < 16) ssq[wave * 16 + lane] = rowsum;
-  }
-  lds_barrier();
   trace_mark(a, t, 3);
   // ---- all wavefronts: add the K slices in order, epilogue, outputs; then the notification
   float* inv_lds = ssq + 8 * 16;   // [16] 1/rms of each batch row
@@ -945,25 +1034,15 @@ __device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const St
   }
   {
     float* outp = (t.flags & TF_OUT_LOGITS) ? a.logits : t.out;
-    auto dot_of = [&](uint32_t r, uint32_t bb) {   // ring row r, batch column bb
-      const uint32_t rt = r >> 4, row = r & 15u;
-      float v = 0.f;
-      if (ks == 1u) {
-        v = part[(((rt & 7u) * 4 + (rt >> 3)) * 16 + row) * 16 + bb];
-      } else {
-        for (uint32_t sl = 0; sl < ks; ++sl) v += part[(((sl * nrt2 + rt) * 4) * 16 + row) * 16 + bb];
-      }
-      return v;
-    };
     for (uint32_t i = threadIdx.x; i < ncols * nb; i += kThreads) {
       const uint32_t cc = i / nb, bb = i % nb;
       const float inv = pro_norm ? inv_lds[bb] : 1.0f;
       float v;
       if (gateup) {
-        const float gte = dot_of(2 * cc, bb) * inv, up = dot_of(2 * cc + 1, bb) * inv;
+        const float gte = mfma_dot(part, G, 2 * cc, bb) * inv, up = mfma_dot(part, G, 2 * cc + 1, bb) * inv;
         v = gte / (1.0f + expf(-gte)) * up;
       } else {
-        v = dot_of(cc, bb) * inv;
+        v = mfma_dot(part, G, cc, bb) * inv;
       }
       if ((t.flags & TF_EPI_RESID) && !splitk) v = res_lds[cc * 16 + bb] + v;
       st_act(outp + (size_t)(t.b0 + bb) * t.ld_out + t.c0 + cc, v);   // split-K: the partial sums of this part
@@ -1154,8 +1233,9 @@ __device__ __forceinline__ void body_moe_route(const TaskDesc& t, const StepArgs
 }
 
 // `ntile` 16-row tiles of one expert's weight matrix, starting at tile `tile0`, times the `ne`
-// token rows routed to that expert: the matrix-core scheme of linear_task_mfma with the input rows
-// gathered through the expert's pair list.  All wavefronts take part; ntile <= 32, ne <= 16.
+// token rows routed to that expert: a matrix-core job (mfma_job) whose input rows are gathered
+// through the expert's pair list while they are staged.  All wavefronts take part; ntile <= 32,
+// ne <= 16.
 __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs& a, float* lds, const uint16_t* W,
                                                uint32_t tile0, uint32_t ntile, uint32_t ne, const uint32_t* plist,
                                                uint32_t TK) {
@@ -1164,9 +1244,7 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
   const uint32_t K = t.K;
   const uint32_t gateup = (t.flags & TF_GATEUP) ? 1u : 0u;
   const bool pro_norm = t.flags & TF_PRO_NORM;
-  const uint32_t Kt = mfma_ktile(ne), xstride = Kt + 8u, xplane = ne * xstride;
-  uint16_t* xh = (uint16_t*)lds;
-  uint16_t* xl = xh + 2 * (size_t)xplane;
+  const MfmaGeom G = mfma_geom(K, ne, ntile, wave);
   float* part = lds;
   float* ssq = lds + moe_x_floats(a.g->batch);   // [8][16]
   uint32_t* rowidx = (uint32_t*)(ssq + 8 * 16);  // [16] pair of each staged row (= output row)
@@ -1177,142 +1255,14 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
     rowin[threadIdx.x] = gateup ? pair / TK : pair;
   }
   lds_barrier();
-  uint32_t nrt2 = 1;
-  while (nrt2 < ntile && nrt2 < 8u) nrt2 <<= 1;
-  const uint32_t ks = 8u / nrt2, my_slice = wave / nrt2, my_rt0 = wave % nrt2, slice_len = Kt / ks;
   const uint32_t frow = lane & 15u, fk = (uint32_t)(lane >> 4) * 8u;
-  f32x4 acc[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  constexpr int kRound = 16;   // 16 KB per wavefront in flight (32 was measured slower)
-  u32x4 wfrag[kRound];
   auto row_ptr = [&](uint32_t rt) {
     const uint32_t r = (tile0 + rt) * 16u + frow;   // row of the expert's gate/up-interleaved (or plain) order
     const uint32_t wrow = gateup ? ((r >> 1) + ((r & 1u) ? t.p0 : 0u)) : r;
     return W + (size_t)wrow * K + fk;
   };
-  auto request = [&](const uint16_t* wp, uint32_t k0, uint32_t kk) {
-#pragma unroll
-    for (int q = 0; q < kRound; ++q) {
-      const uint32_t k = min(k0 + kk + q * 32u, K - fk - 8u);
-      wfrag[q] = ld_stream16(wp + k);
-    }
-  };
-  // input staging as in linear_task_mfma (slot q = row q >> sh), rows gathered through the pair list
-  const uint32_t sh = Kt == 2048u ? 1u : 0u;
-  float sqq[16];
-#pragma unroll
-  for (int q = 0; q < 16; ++q) sqq[q] = 0.f;
-  const uint16_t* gain = (const uint16_t*)t.w2;
-  const uint32_t ntk = (K + Kt - 1u) / Kt;
-  float2 sv[16];
-  auto stage_issue = [&](uint32_t tile) {
-    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const uint32_t b = (uint32_t)q >> sh, i = (((uint32_t)q & sh) << 9) + threadIdx.x;
-      sv[q] = make_float2(0.f, 0.f);
-      if (b < ne && 2 * i < klen) sv[q] = ld_act2(t.in + (size_t)rowin[b] * t.ld_in + k0 + 2 * i);
-    }
-  };
-  auto stage_write = [&](uint32_t tile) {
-    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
-    uint16_t* dh = xh + (size_t)(tile & 1u) * xplane;
-    uint16_t* dl = xl + (size_t)(tile & 1u) * xplane;
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const uint32_t b = (uint32_t)q >> sh, i = (((uint32_t)q & sh) << 9) + threadIdx.x;
-      if (b < ne) {
-        float2 w2 = sv[q];
-        if (pro_norm && 2 * i < klen) {
-          sqq[q] = fmaf(w2.x, w2.x, fmaf(w2.y, w2.y, sqq[q]));
-          const uint32_t g2 = *as_global((const uint32_t*)(gain + k0 + 2 * i));
-          w2.x *= bf16_lo(g2);
-          w2.y *= bf16_hi(g2);
-        }
-        uint32_t hi, lo;
-        split_hi_lo(w2.x, w2.y, &hi, &lo);
-        *(uint32_t*)(dh + (size_t)b * xstride + 2 * i) = hi;
-        *(uint32_t*)(dl + (size_t)b * xstride + 2 * i) = lo;
-      }
-    }
-  };
-  for (uint32_t tile = 0; tile < ntk; ++tile) {
-    const uint32_t k0 = tile * Kt, klen = min(Kt, K - k0);
-    // An expert's input is nearly always a single tile (up to 8 tokens x 2048 inputs), so the
-    // staging is not overlapped with the multiplies here: its registers are then free during the
-    // multiply loop, which is what this function is short of.
-    stage_issue(tile);
-    stage_write(tile);
-    lds_barrier();
-    const uint16_t* ch = xh + (size_t)(tile & 1u) * xplane;
-    const uint16_t* cl = xl + (size_t)(tile & 1u) * xplane;
-    const uint32_t s_lo = my_slice * slice_len, s_hi = min(s_lo + slice_len, (klen + 31u) & ~31u);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t rt = my_rt0 + (uint32_t)j * 8u;
-      if (rt < ntile && (ks == 1u || j == 0) && s_lo < s_hi) {
-        const uint16_t* wp = row_ptr(rt);
-        const uint16_t* bh = ch + (size_t)(frow % ne) * xstride + fk;
-        const uint16_t* bl = cl + (size_t)(frow % ne) * xstride + fk;
-        for (uint32_t kk = s_lo; kk < s_hi; kk += 32u * kRound) {
-          request(wp, k0, kk);
-#pragma unroll
-          for (int q0 = 0; q0 < kRound; q0 += 4) {
-            if (kk + (q0 + 4) * 32u <= s_hi) {   // four steps without per-step tests, their LDS reads first
-              u32x4 hv[4], lv[4];
-#pragma unroll
-              for (int u = 0; u < 4; ++u) {
-                hv[u] = *(const u32x4*)(bh + kk + (q0 + u) * 32u);
-                lv[u] = *(const u32x4*)(bl + kk + (q0 + u) * 32u);
-              }
-#pragma unroll
-              for (int u = 0; u < 4; ++u) {
-                const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, hv[u]), acc[j], 0, 0, 0);
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, lv[u]), acc[j], 0, 0, 0);
-              }
-            } else {
-#pragma unroll
-              for (int u = 0; u < 4; ++u) {
-                if (kk + (q0 + u) * 32u < s_hi) {
-                  const u32x4 bhv = *(const u32x4*)(bh + kk + (q0 + u) * 32u), blv = *(const u32x4*)(bl + kk + (q0 + u) * 32u);
-                  const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
-                  acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bhv), acc[j], 0, 0, 0);
-                  acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, blv), acc[j], 0, 0, 0);
-                }
-              }
-            }
-          }
-        }
-      }
-    }
-  }
-  lds_barrier();   // the partial tiles reuse the input buffers
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) part[((wave * 4 + j) * 16 + (lane >> 4) * 4 + i) * 16 + (lane & 15)] = acc[j][i];
-  if (pro_norm) {
-    float rowsum = 0.f;   // lane b: this wavefront's sum of squares of staged row b
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const float v = wave_sum(sqq[q]);
-      if ((uint32_t)lane == ((uint32_t)q >> sh)) rowsum += v;
-    }
-    if (lane < 16) ssq[wave * 16 + lane] = rowsum;
-  }
-  lds_barrier();
-  auto dot_of = [&](uint32_t r, uint32_t bb) {
-    const uint32_t rt = r >> 4, row = r & 15u;
-    float v = 0.f;
-    if (ks == 1u) {
-      v = part[(((rt & 7u) * 4 + (rt >> 3)) * 16 + row) * 16 + bb];
-    } else {
-      for (uint32_t sl = 0; sl < ks; ++sl) v += part[(((sl * nrt2 + rt) * 4) * 16 + row) * 16 + bb];
-    }
-    return v;
-  };
+  auto src_row = [&](uint32_t b) { return t.in + (size_t)rowin[b] * t.ld_in; };
+  mfma_job(a, t, lds, ssq, G, row_ptr, src_row, pro_norm, (const uint16_t*)t.w2, []() -> uint32_t { return kLinDone; });
   const uint32_t ncols = (ntile * 16u) >> gateup, col0 = (tile0 * 16u) >> gateup;
   for (uint32_t i = threadIdx.x; i < ncols * ne; i += kThreads) {
     const uint32_t cc = i / ne, bb = i % ne;
@@ -1325,10 +1275,10 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
     }
     float v;
     if (gateup) {
-      const float gte = dot_of(2 * cc, bb) * inv, up = dot_of(2 * cc + 1, bb) * inv;
+      const float gte = mfma_dot(part, G, 2 * cc, bb) * inv, up = mfma_dot(part, G, 2 * cc + 1, bb) * inv;
       v = gte / (1.0f + expf(-gte)) * up;
     } else {
-      v = dot_of(cc, bb);
+      v = mfma_dot(part, G, cc, bb);
     }
     st_act(t.out + (size_t)rowidx[bb] * t.ld_out + col0 + cc, v);
   }

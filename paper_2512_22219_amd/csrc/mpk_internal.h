@@ -174,14 +174,23 @@ mpk_status build_dag_graph(uint32_t n_tasks, const uint32_t* pairs, size_t n_pai
 inline uint32_t moe_meta_words(uint32_t E, uint32_t P) { return 2 + 3 * E + 3 * P; }
 constexpr uint32_t kMoeMaxExperts = 512, kMoeMaxPairs = 256, kMoeMaxTopK = 16;
 
-// LDS floats the input tiles of an expert job (or the partial tiles that reuse them) take: up to
-// 8 token rows x 2048 inputs or up to 16 x 1024, two bf16 planes, two buffers.  One definition
-// for the host's LDS requirement and the kernel's layout.
+// Matrix-core jobs (batch 5..16 and expert jobs) stage the input in LDS as three bf16 planes, one K
+// tile of this many inputs at a time, two buffers; one definition for the host's LDS requirement
+// and the kernels' layout.
+constexpr uint32_t mfma_ktile(uint32_t nb) { return nb <= 8u ? 1024u : 512u; }
+// LDS floats of a job with nb staged rows: two buffers x three planes x nb rows x (tile + 8) bf16
+// (an input of at most two tiles, staged whole, fits the same space), reused for the partial tiles
+// [8 wavefronts][4][16][16] f32 at the end.
+constexpr uint32_t mfma_x_floats(uint32_t nb) {
+  const uint32_t x = 3u * nb * (mfma_ktile(nb) + 8u);
+  return x > 8u * 4u * 256u ? x : 8u * 4u * 256u;
+}
+// ... of the expert jobs of a graph with this batch size: an expert holds between 1 and min(batch,
+// 16) token rows.
 constexpr uint32_t moe_x_floats(uint32_t batch) {
-  const uint32_t t8 = 2u * (batch < 8u ? batch : 8u) * (2048u + 8u);
-  const uint32_t t16 = batch > 8u ? 2u * batch * (1024u + 8u) : 0u;
-  const uint32_t m = t8 > t16 ? t8 : t16;
-  return m > 8u * 4u * 256u ? m : 8u * 4u * 256u;
+  const uint32_t t8 = mfma_x_floats(batch < 8u ? batch : 8u);
+  const uint32_t t16 = batch > 8u ? mfma_x_floats(batch < 16u ? batch : 16u) : 0u;
+  return t8 > t16 ? t8 : t16;
 }
 
 // LDS layout constants shared with the kernels

@@ -339,6 +339,118 @@ def test_kv_append_rounds_and_next_step_reads_rounded_row():
     assert set(map(tuple, changed)) == {(0, g, p) for g in range(s.n_kv_heads)}
 
 
+# ------------------------------------------------------------------ held decisions
+def test_held_rows_equal_to_the_oracles_own_rounding_change_nothing():
+    """Handing the oracle its own appended rows back is the identity, and the unrounded rows it
+    reports round (torch's conversion, not ours) to exactly what it stored."""
+    s = G.small_variant("C1", batch=2)
+    tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
+    for prec in ("f32", "f64"):
+        a = D.DecoderOracle(s, G.SynthWeights(s, 0), prec)
+        la = a.step(tok, pos)
+        stored_k = np.stack([[a._kv(l)[0][b, :, pos[b]] for b in range(s.batch)] for l in range(s.n_layers)])
+        stored_v = np.stack([[a._kv(l)[1][b, :, pos[b]] for b in range(s.batch)] for l in range(s.n_layers)])
+        assert np.array_equal(bf(a.last_k_exact), stored_k) and np.array_equal(bf(a.last_v_exact), stored_v)
+        b = D.DecoderOracle(s, G.SynthWeights(s, 0), prec)
+        lb = b.step(tok, pos, held=D.Held(stored_k, stored_v))
+        assert np.array_equal(la, lb)
+        assert np.array_equal(a.last_k_exact, b.last_k_exact)
+
+
+def test_held_rows_replace_the_appended_row_and_only_it():
+    """Attention over a single cached position returns the V row (pinned above), so with position
+    0 and a held V row of ones the attention output is the held row, not the computed one; the
+    held K row lands in the cache untouched; no other cache row changes."""
+    s = G.small_variant("C1", n_layers=1)
+    prov = synth_provider_as_dict(s, zero=(G.L_WO,))
+    tok = G.tokens(0, s)
+    pos = np.zeros(1, np.int32)
+    ones = np.full((1, 1, s.n_kv_heads, s.head_dim), 0x3F80, np.uint16)      # bf16 1.0
+    krow = np.full((1, 1, s.n_kv_heads, s.head_dim), 0x4000, np.uint16)      # bf16 2.0
+    o = D.DecoderOracle(s, prov, "f64")
+    before = [c.copy() for c in o._kv(0)]
+    o.step(tok, pos, held=D.Held(krow, ones))
+    K, V = o._kv(0)
+    assert (K[0, :, 0] == 0x4000).all() and (V[0, :, 0] == 0x3F80).all()
+    assert np.array_equal(K[0, :, 1:], before[0][0, :, 1:]) and np.array_equal(V[0, :, 1:], before[1][0, :, 1:])
+    # the unrounded rows reported are the oracle's own, not the held ones
+    assert not np.allclose(o.last_v_exact, 1.0)
+    # one layer with an identity-like O projection: hidden' = x + Wo o ... checked through the
+    # public pieces instead: attention of any query over the one held row is that row
+    q = RNG.standard_normal(s.head_dim)
+    assert np.array_equal(o.ops.attention_head(q, K[0, 0], V[0, 0], 1), np.ones(s.head_dim))
+
+
+def test_held_expert_set_is_used_with_renormalised_router_weights():
+    """float64 closed form as in the block test above, for a held set that is NOT the oracle's
+    own choice: the experts of lowest router output."""
+    s = _moe_shape(n_layers=1, n_experts=8, top_k=3, expert_ffn=96)
+    prov = synth_provider_as_dict(s, zero=(G.L_WO,))
+    tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
+    own = D.DecoderOracle(s, prov, "f64")
+    own.step(tok, pos)
+    r = own.last_moe_logits[0, 0].astype(np.float64)
+    held_set = np.sort(np.argsort(r, kind="stable")[:s.top_k]).astype(np.int32)
+    assert set(held_set.tolist()) != set(own.last_moe_sel[0, 0].tolist())
+    o = D.DecoderOracle(s, prov, "f64")
+    hid = o.step(tok, pos, return_hidden=True, held=D.Held(experts=held_set.reshape(1, 1, -1)))[0]
+    w = prov.layers[0]
+    x = unbf(prov.E[tok[0]]).astype(np.float64)
+    xn = x / np.sqrt((x * x).mean() + s.rms_eps) * unbf(w[G.L_MLP_NORM]).astype(np.float64).ravel()
+    pr = np.exp(r - r.max())
+    pr /= pr.sum()
+    F, H = s.expert_ffn, s.hidden
+    y = np.zeros(H)
+    for e in held_set:
+        wgu = unbf(w[G.L_EXP_WGU][e * 2 * F:(e + 1) * 2 * F]).astype(np.float64)
+        wd = unbf(w[G.L_EXP_WD][e * H:(e + 1) * H]).astype(np.float64)
+        gu = wgu @ xn
+        y += pr[e] / pr[held_set].sum() * (wd @ (gu[:F] / (1 + np.exp(-gu[:F])) * gu[F:]))
+    assert np.allclose(hid, x + y, rtol=1e-8, atol=1e-10)
+    # holding the oracle's own set is the identity
+    again = D.DecoderOracle(s, prov, "f64").step(tok, pos, return_hidden=True,
+                                                 held=D.Held(experts=own.last_moe_sel[:, :, :s.top_k]))[0]
+    assert np.array_equal(again, D.DecoderOracle(s, prov, "f64").step(tok, pos, return_hidden=True)[0])
+
+
+def kv_flip_shift(s, seed, n_flips, prec="f64"):
+    """Largest logit change, relative to the largest logit, when the n_flips appended K/V elements
+    that sit closest to a bf16 rounding boundary (per layer and sequence) are rounded the other
+    way -- what two correct implementations may legitimately disagree by."""
+    tok, pos = G.tokens(seed, s), G.kv_lengths(seed, s)
+    a = D.DecoderOracle(s, G.SynthWeights(s, seed), prec)
+    base = a.step(tok, pos)
+    rows = []
+    for exact in (a.last_k_exact, a.last_v_exact):
+        e = np.asarray(exact, np.float64)
+        own = bf(e)
+        near = unbf(own).astype(np.float64)
+        # the bf16 neighbour on the other side of e (magnitudes grow with the bit pattern)
+        up = np.where(np.signbit(near) == (e >= near), own - 1, own + 1).astype(np.uint16)
+        other = unbf(up).astype(np.float64)
+        dist = np.abs(e - (near + other) / 2) / np.maximum(np.abs(near - other), 1e-300)   # 0 = on the boundary
+        flat = dist.reshape(dist.shape[0], dist.shape[1], -1)
+        pick = np.argsort(flat, axis=-1)[..., :n_flips]
+        held = own.copy().reshape(flat.shape)
+        np.put_along_axis(held, pick, np.take_along_axis(up.reshape(flat.shape), pick, -1), -1)
+        rows.append(held.reshape(own.shape))
+    b = D.DecoderOracle(s, G.SynthWeights(s, seed), prec)
+    moved = b.step(tok, pos, held=D.Held(rows[0], rows[1]))
+    return float(np.abs(moved - base).max() / np.abs(base).max())
+
+
+def test_logit_shift_from_kv_rows_rounded_the_other_way():
+    """The size of the legitimate disagreement, measured: a handful of boundary elements per layer
+    and sequence rounded the other way moves the logits of the tiny model (128 cached positions,
+    so the appended row carries about 1 % of the attention weight) by 1e-5 .. 1e-3 of the largest
+    logit -- far above fp32 rounding order (1e-6), which is why comparisons that do not hold these
+    decisions need a bound on the largest logit of that size, and those that do can be tight."""
+    s = G.CONFIGS["C1"]
+    one = kv_flip_shift(s, 0, 1)
+    four = kv_flip_shift(s, 0, 4)
+    assert 1e-6 < one < 2e-3 and one <= four * 1.5 and four < 2e-3, (one, four)
+
+
 def test_whole_model_vs_transformers_llama():
     """Library pin: a randomly initialised Llama-architecture model from the `transformers`
     package, loaded with the same seeded tensors, fp32 on CPU, one token with a 128-row past."""
