@@ -96,7 +96,18 @@ typedef struct mpk_kv_ptrs {
 #define MPK_FUSE_MERGE 8u  /* split-KV merge done by the last attention chunk task to finish    */
 #define MPK_FUSE_ROPE 16u  /* RoPE + KV append folded into the attention tasks                  */
 
-#define MPK_DEBUG_TRACE 1u /* record per-task timestamps inside the persistent kernel           */
+#define MPK_DEBUG_TRACE 1u  /* record per-task timestamps inside the persistent kernel          */
+#define MPK_DEBUG_POISON 2u /* before every launch, fill every buffer the graph owns for data that
+                               crosses tasks (activations, split-KV partials, partial sums,
+                               meta-tensors) with NaN: a task that reads what this step has not
+                               produced yet, or what an earlier step left behind, shows in the
+                               logits (the paper's runtime has no such mode; Section 5 only
+                               states that events order producers before consumers)              */
+#define MPK_DEBUG_JITTER 4u /* every task of the persistent kernel starts after a pseudo-random
+                               delay of 0 .. 20 us (a hash of task and step): the relative timing
+                               of producers and consumers differs in every step, so a missing
+                               wait or an early notification becomes a wrong result.  All waits
+                               stay bounded; nothing hangs or faults on purpose                  */
 
 #define MPK_LAUNCH_MEGA 0u   /* one persistent kernel per decode step (Section 5)               */
 #define MPK_LAUNCH_PER_OP 1u /* same task bodies, one kernel launch per operator (baseline)     */
@@ -119,7 +130,9 @@ typedef struct mpk_compile_options {
   uint32_t tiles_pointwise; /* column tiles per batch row of add / swiglu operators; 0 = 1     */
   uint32_t launch_mode;     /* MPK_LAUNCH_*                                                     */
   uint32_t force_aot;       /* 1 = label every operator ahead-of-time even with schedulers      */
-  uint32_t prefetch;        /* 1 = cross-task weight pre-loading (Section 5.3)                  */
+  uint32_t no_preload;      /* 1 = switch cross-task pre-loading off (Section 5.3; the ablation
+                               of Section 6.5, Fig. 10): no task requests weights or cache rows
+                               before its dependent event is activated.  0 = pre-loading on     */
   uint32_t host_only;       /* 1 = build the task graph on the host only: no device is touched,
                                weight/KV pointers may be NULL; mpk_decode_step is refused       */
   uint32_t spin_timeout_ms; /* in-kernel watchdog for every wait; 0 = 2000 ms                   */

@@ -51,7 +51,7 @@ class CompileOptions(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in
                 ("struct_size", "n_workers", "n_sched_wgs", "fusion", "transitive_reduction",
                  "attn_chunks", "tiles_linear", "tiles_lm_head", "tiles_pointwise", "launch_mode",
-                 "force_aot", "prefetch", "host_only", "spin_timeout_ms", "debug_flags",
+                 "force_aot", "no_preload", "host_only", "spin_timeout_ms", "debug_flags",
                  "tiles_moe", "greedy_loop", "kv_batch")]
 
 
@@ -87,6 +87,7 @@ SYMBOLS = ("mpk_compile", "mpk_compile_dag", "mpk_decode_step", "mpk_decode_step
            "mpk_graph_moe_active", "mpk_graph_moe_selection", "mpk_compile_set",
            "mpk_set_decode_step", "mpk_set_size", "mpk_set_batch_for", "mpk_set_graph",
            "mpk_set_destroy", "mpk_last_error", "mpk_graph_destroy")
+DEBUG_TRACE, DEBUG_POISON, DEBUG_JITTER = 1, 2, 4
 
 _lib = None
 

@@ -165,9 +165,28 @@ __device__ __forceinline__ TaskDesc ld_task(const StepArgs& a, uint32_t i) { ret
 __device__ __forceinline__ uint32_t ld_u32c(const uint32_t* p) { return *(const MPK_CONST uint32_t*)p; }
 
 constexpr int kTraceSlots = 12;
-constexpr uint32_t kTraceBit = 1u;   // StepArgs::flags: per-task timestamps are recorded (buffer: GraphConst::trace)
+// StepArgs::flags
+constexpr uint32_t kTraceBit = 1u;      // per-task timestamps are recorded (buffer: GraphConst::trace)
+constexpr uint32_t kJitterBit = 2u;     // every task starts after a pseudo-random delay (race hunting)
+constexpr uint32_t kNoPreloadBit = 4u;  // no weight / cache-row request before a task's event wait
 __device__ __forceinline__ void trace_mark(const StepArgs& a, const TaskDesc& t, int slot) {
   if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + slot] = wall_clock64();
+}
+
+// MPK_DEBUG_JITTER: a delay of 0 .. 20 us, a hash of (task, step), before the task does anything.
+// It shifts every task against every other differently in every step, so a consumer that does not
+// really wait for its event, or a producer that notifies before its stores have completed, shows
+// up as a wrong result instead of depending on the timing of an unloaded machine.
+__device__ __forceinline__ void debug_jitter(const StepArgs& a, uint32_t task_index) {
+  if (!(a.flags & kJitterBit)) return;
+  if (threadIdx.x == 0) {
+    uint32_t h = (task_index + 1u) * 2654435761u ^ (a.epoch * 40503u + 0x9E3779B9u);
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+    const uint64_t ticks = h % 2000u;   // the wall clock counts at 100 MHz
+    const uint64_t t0 = wall_clock64();
+    while (wall_clock64() - t0 < ticks) __builtin_amdgcn_s_sleep(8);
+  }
+  __syncthreads();
 }
 
 enum DevErr : uint32_t { DE_NONE = 0, DE_TIMEOUT = 1, DE_BAD_POSITION = 2, DE_BAD_TOKEN = 3, DE_BAD_META = 4 };
@@ -492,12 +511,13 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
   // (every request site ends in an (empty) assembly statement of its own: otherwise the compiler
   // may merge the identical last loads of two sites into one whose destination is chosen at run
   // time, and a buffer addressed that way is moved from registers to scratch memory)
-  if (lin_valid(g, rq)) {
+  const bool preload = !(a.flags & kNoPreloadBit);   // off: the ablation of Section 6.5, Fig. 10
+  if (preload && lin_valid(g, rq)) {
     lin_request(lin_half(g, rq), h0, lane);
     lin_advance(g, rq);
     asm volatile("; first half block requested" ::: "memory");
   }
-  if (lin_valid(g, rq)) {
+  if (preload && lin_valid(g, rq)) {
     lin_request(lin_half(g, rq), h1, lane);
     lin_advance(g, rq);
     asm volatile("; second half block requested" ::: "memory");
@@ -511,7 +531,7 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
   HalfRing h2;
   if (kThird) {
     ring_clear(h2);
-    if (lin_valid(g, rq)) {
+    if (preload && lin_valid(g, rq)) {
       lin_request(lin_half(g, rq), h2, lane);
       lin_advance(g, rq);
       asm volatile("; third half block requested" ::: "memory");
@@ -523,6 +543,23 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
     if (w != kLinDone) return w;   // aborted, or pre-empted by a just-in-time task: the requested weights are dropped
   }
   trace_mark(a, t, 1);
+  if (!preload) {   // pre-loading switched off: the first requests go out only now
+    if (lin_valid(g, rq)) {
+      lin_request(lin_half(g, rq), h0, lane);
+      lin_advance(g, rq);
+      asm volatile("; first half block requested after the event" ::: "memory");
+    }
+    if (lin_valid(g, rq)) {
+      lin_request(lin_half(g, rq), h1, lane);
+      lin_advance(g, rq);
+      asm volatile("; second half block requested after the event" ::: "memory");
+    }
+    if (kThird && lin_valid(g, rq)) {
+      lin_request(lin_half(g, rq), h2, lane);
+      lin_advance(g, rq);
+      asm volatile("; third half block requested after the event" ::: "memory");
+    }
+  }
   // ---- stage the input rows in LDS.  With TF_PRO_NORM the gain is folded in here (x * g) and
   // the row's 1/rms factor is applied to the finished dot products: W (x g inv) = inv * W (x g).
   const bool pro_norm = t.flags & TF_PRO_NORM;
@@ -812,15 +849,22 @@ __device__ __forceinline__ uint32_t mfma_job(const StepArgs& a, const TaskDesc& 
       wfrag[q] = ld_stream16(wp + min(k, kclamp));
     }
   };
-  if (G.has_work) {
+  const bool preload = !(a.flags & kNoPreloadBit);   // off: the ablation of Section 6.5, Fig. 10
+  if (preload && G.has_work) {
     if (G.nf >= (uint32_t)kMfmaRound) request_run(row_ptr(G.my_rt0), s_lo);
     else request_span(row_ptr(G.my_rt0), 0u);
+    asm volatile("; first round requested" ::: "memory");
   }
   {
     const uint32_t w = wait_fn();
     if (w != kLinDone) return w;   // aborted or pre-empted: the requested weights are dropped
   }
   trace_mark(a, t, 1);
+  if (!preload && G.has_work) {
+    if (G.nf >= (uint32_t)kMfmaRound) request_run(row_ptr(G.my_rt0), s_lo);
+    else request_span(row_ptr(G.my_rt0), 0u);
+    asm volatile("; first round requested after the event" ::: "memory");
+  }
   // Staging.  A pass of Kt1 inputs x nb rows is dealt to the threads in pairs, 8 slots per thread;
   // the row of a slot is the same for the whole wavefront (no divisions, no per-row selects):
   // 1024-input passes: slot q = row q, pair = thread; 512-input passes: row 2 q + thread / 256,
@@ -1457,18 +1501,29 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
   const uint32_t n_rounds = (n + stride - 1) / stride;
   // ---- pre-load: K and V rows of earlier steps
   u32x4 kreg[kAttnRounds], vreg[kAttnRounds];
+  auto load_rows = [&]() {
 #pragma unroll
-  for (int r = 0; r < kAttnRounds; ++r) {
-    const uint32_t i = i_first + r * stride;
-    kreg[r] = u32x4{0, 0, 0, 0};
-    vreg[r] = u32x4{0, 0, 0, 0};
-    if (i < n && t0 + i != (uint32_t)pos) {
-      kreg[r] = ld_stream16(Kb + (size_t)i * d + sub * 8);
-      vreg[r] = ld_stream16(Vb + (size_t)i * d + sub * 8);
+    for (int r = 0; r < kAttnRounds; ++r) {
+      const uint32_t i = i_first + r * stride;
+      kreg[r] = u32x4{0, 0, 0, 0};
+      vreg[r] = u32x4{0, 0, 0, 0};
+      if (i < n && t0 + i != (uint32_t)pos) {
+        kreg[r] = ld_stream16(Kb + (size_t)i * d + sub * 8);
+        vreg[r] = ld_stream16(Vb + (size_t)i * d + sub * 8);
+      }
     }
+  };
+  const bool preload = !(a.flags & kNoPreloadBit);
+  if (preload) {
+    load_rows();
+    asm volatile("; cache rows requested" ::: "memory");
   }
   if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
   trace_mark(a, t, 1);
+  if (!preload) {
+    load_rows();
+    asm volatile("; cache rows requested after the event" ::: "memory");
+  }
   if (bad_pos || n_rounds > (uint32_t)kAttnRounds) {
     if (threadIdx.x == 0) report(a, DE_BAD_POSITION, b, (uint32_t)pos);
     for (uint32_t i = threadIdx.x; i < per; i += kThreads) st_act(outp + i, ((i % (d + 2)) == d) ? -INFINITY : 0.f);
@@ -1742,18 +1797,29 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
   constexpr int kAttnPre = GRP <= 4 ? 8 : 4;
   // ---- pre-load: the first rounds of K and V rows (never the row appended this step)
   u32x4 kreg[kAttnPre], vreg[kAttnPre];
+  auto load_rows = [&]() {
 #pragma unroll
-  for (int r = 0; r < kAttnPre; ++r) {
-    const uint32_t i = i_first + r * stride;
-    kreg[r] = u32x4{0, 0, 0, 0};
-    vreg[r] = u32x4{0, 0, 0, 0};
-    if (i < n && t0 + i != (uint32_t)pos) {
-      kreg[r] = ld_stream16(Kb + (size_t)i * d + sub * 8);
-      vreg[r] = ld_stream16(Vb + (size_t)i * d + sub * 8);
+    for (int r = 0; r < kAttnPre; ++r) {
+      const uint32_t i = i_first + r * stride;
+      kreg[r] = u32x4{0, 0, 0, 0};
+      vreg[r] = u32x4{0, 0, 0, 0};
+      if (i < n && t0 + i != (uint32_t)pos) {
+        kreg[r] = ld_stream16(Kb + (size_t)i * d + sub * 8);
+        vreg[r] = ld_stream16(Vb + (size_t)i * d + sub * 8);
+      }
     }
+  };
+  const bool preload = !(a.flags & kNoPreloadBit);
+  if (preload) {
+    load_rows();
+    asm volatile("; cache rows requested" ::: "memory");
   }
   if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
   trace_mark(a, t, 1);
+  if (!preload) {
+    load_rows();
+    asm volatile("; cache rows requested after the event" ::: "memory");
+  }
   if (bad_pos) {
     if (threadIdx.x == 0) report(a, DE_BAD_POSITION, b, (uint32_t)pos);
     for (uint32_t i = threadIdx.x; i < per; i += kThreads) st_act(outp + i, ((i % (d + 2)) == d) ? -INFINITY : 0.f);
@@ -2300,6 +2366,7 @@ __device__ __noinline__ bool run_moe_task(StepArgs a_in, uint32_t task_index, bo
   uint32_t* s_flag = (uint32_t*)dyn_lds;
   const TaskDesc t = ld_task(a, task_index);
   if (MEGA) {
+    debug_jitter(a, task_index);
     const int32_t wait_ev = (!skip_wait && t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
     trace_mark(a, t, 0);
     if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)task_index * kTraceSlots + 5] = blockIdx.x;
@@ -2340,6 +2407,7 @@ __device__ __noinline__ bool run_other_task(StepArgs a_in, uint32_t task_index, 
   if (MOE && is_moe_kind(t.kind)) return run_moe_task<MEGA>(a_in, task_index, skip_wait);
   int32_t wait_ev = -1;
   if (MEGA) {
+    debug_jitter(a, task_index);
     wait_ev = (!skip_wait && t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
     trace_mark(a, t, 0);
     if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)task_index * kTraceSlots + 5] = blockIdx.x;
@@ -2502,6 +2570,7 @@ __device__ __forceinline__ bool aot_pass(const StepArgs& a, uint32_t q0, uint32_
       if (!__builtin_amdgcn_readfirstlane((int)wait_event(prev, (int32_t)a.g->terminal_event, s_flag))) return false;
     }
     if (t.kind == TK_LINEAR) {
+      debug_jitter(a, ti);
       const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
       trace_mark(a, t, 0);
       if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
@@ -2558,6 +2627,7 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
     const uint32_t ti = pick & 0x7FFFFFFFu;
     const TaskDesc t = ld_task(a, ti);
     if (t.kind == TK_LINEAR) {
+      debug_jitter(a, ti);
       trace_mark(a, t, 0);
       if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
       const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
@@ -2567,7 +2637,14 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
         const uint32_t tj = __builtin_amdgcn_readfirstlane(((uint32_t*)dyn_lds)[1]);
         lds_barrier();   // everybody has read the control word
         ++jit_head;
-        if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(a, tj, true))) { r = kLinAbort; break; }
+        // (a just-in-time task may itself be a linear task -- an operator whose tiles read only part
+        // of a just-in-time operator's output is labelled just-in-time too, Section 5.2: its event
+        // has been activated, so it runs without waiting and without watching the queue)
+        const TaskDesc tjd = ld_task(a, tj);
+        if (tjd.kind == TK_LINEAR) {
+          debug_jitter(a, tj);
+          if (run_linear<NB, true>(tjd, a, lds, -1, s_flag) != kLinDone) { r = kLinAbort; break; }
+        } else if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(a, tj, true))) { r = kLinAbort; break; }
       }
       if (r == kLinAbort) break;
     } else {

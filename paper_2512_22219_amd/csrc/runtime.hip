@@ -26,6 +26,12 @@ static const KernelVariant* pick_variant(uint32_t d, uint32_t grp, uint32_t batc
   return variant_at(moe ? n - 1 : n - 2);   // the generic fallbacks come last: dense, then mixture of experts
 }
 
+// Fills n 32-bit words (NaN patterns for MPK_DEBUG_POISON).
+// A kernel, not a memset node: a caller may be capturing the stream.
+__global__ void __launch_bounds__(256) fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
 }  // namespace mpk
 
 
@@ -63,6 +69,7 @@ struct mpk_graph {
   std::vector<uint32_t> op_first, op_count;   // per operator: range in op_list
   uint32_t epoch = 0;
   uint64_t timeout_ticks = 0;
+  uint32_t step_flags = 0;   // StepArgs::flags of every launch (trace, jitter, no pre-loading)
   void* launch_out[2] = {nullptr, nullptr};   // host copy of GraphConst::tokens_out / logits_all (source of the async copy)
 };
 
@@ -274,6 +281,8 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
     c.start_event = h.start_event; c.terminal_event = h.terminal_event;
     std::vector<GraphConst> cv(1, c);
     if ((st = upload(&g->d_const, cv)) != MPK_OK) return fail(st);
+    g->step_flags = (g->d_trace ? kTraceBit : 0u) | ((o.debug_flags & MPK_DEBUG_JITTER) ? kJitterBit : 0u) |
+                    (o.no_preload ? kNoPreloadBit : 0u);
   }
   *out = g;
   return MPK_OK;
@@ -304,9 +313,15 @@ static mpk_status launch_steps(mpk_graph* g, uint32_t n_steps, const int32_t* to
   StepArgs a{};
   a.g = (const MPK_CONST GraphConst*)g->d_const;
   a.tasks = g->d_tasks; a.events = g->d_events; a.counters = g->d_counters; a.hier = g->d_hier;
-  a.n_sched = g->n_sched; a.flags = g->d_trace ? kTraceBit : 0u;
+  a.n_sched = g->n_sched; a.flags = g->step_flags;
   a.token_ids = token_ids; a.positions = positions; a.logits = logits_out;
   hipStream_t s = (hipStream_t)stream;
+  float* arena = g->d_arena;
+  const size_t arena_words = std::max<size_t>(h.arena_floats, 64);
+  if (h.opt.debug_flags & MPK_DEBUG_POISON) {
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(256), dim3(256), 0, s, (uint32_t*)arena, arena_words, 0x7FC00000u);
+    HIP_TRY(hipGetLastError());
+  }
   if (h.opt.launch_mode == MPK_LAUNCH_MEGA) {
     // events compare their counters with the step number, a launch argument: a captured launch
     // replayed later would carry a stale one and wait for nothing

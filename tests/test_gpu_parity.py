@@ -577,3 +577,47 @@ def test_graph_set_runs_the_smallest_graph_that_holds_the_active_sequences(varia
     with pytest.raises(M.MpkError):
         gs.decode_step(B + 1, d_tok.data_ptr(), d_pos.data_ptr(), logits.data_ptr(), st)
     gs.destroy()
+
+
+# ------------------------------------------------------------------ debug modes, pre-load ablation
+POISON, JITTER = M.binding.DEBUG_POISON, M.binding.DEBUG_JITTER
+
+
+@pytest.mark.parametrize("variant,opts", [
+    (("C1", {}), dict(fusion=31, transitive_reduction=1)),
+    (("C1", {}), dict(fusion=0)),
+    (("C1", dict(batch=3)), dict(fusion=7, transitive_reduction=1, n_sched_wgs=2)),
+    (("C1", dict(batch=8, max_seq=192)), dict(fusion=31, transitive_reduction=1)),
+    (("C1", dict(batch=4, ffn=0, n_experts=16, top_k=4, expert_ffn=96)), dict(fusion=31, transitive_reduction=1)),
+    (("C2", dict(n_layers=2)), dict(fusion=31, transitive_reduction=1)),
+])
+@pytest.mark.parametrize("debug", [POISON, JITTER, POISON | JITTER])
+def test_poisoned_buffers_and_jittered_task_starts_change_nothing(variant, opts, debug):
+    """The event protocol under stress: every buffer that carries data between tasks is filled
+    with NaN before each launch (a task that reads what this step has not produced yet, or relies
+    on what the previous step left, turns the logits into NaN) and every task starts after a
+    pseudo-random delay of up to 20 us that differs from step to step (a consumer that does not
+    really wait for its producers reads the poison).  Three steps each, compared as strictly as
+    without the modes; all waits stay bounded, nothing is made to hang."""
+    base, kw = variant
+    s = G.small_variant(base, **kw)
+    tok, pos = G.tokens(1, s), G.kv_lengths(1, s)
+    if base == "C1":
+        pos = np.array([(41 * b + 7) % 120 for b in range(s.batch)], np.int32)
+    strict_steps(s, 1, dict(debug_flags=debug, **opts), tok, pos, 3)
+
+
+@pytest.mark.parametrize("variant,opts", [
+    (("C1", {}), dict(fusion=31, transitive_reduction=1)),
+    (("C1", dict(batch=8, max_seq=192)), dict(fusion=31, transitive_reduction=1)),
+    (("C1", dict(batch=2)), dict(fusion=7, n_sched_wgs=2)),
+    (("C1", dict(batch=4, ffn=0, n_experts=16, top_k=4, expert_ffn=96)), dict(fusion=31, transitive_reduction=1)),
+])
+def test_cross_task_preloading_switched_off(variant, opts):
+    """no_preload = 1 (the ablation of Section 6.5): no weight or cache-row request before a
+    task's event; same results."""
+    base, kw = variant
+    s = G.small_variant(base, **kw)
+    tok = G.tokens(1, s)
+    pos = np.array([(41 * b + 7) % 120 for b in range(s.batch)], np.int32)
+    strict_steps(s, 1, dict(no_preload=1, **opts), tok, pos, 2)
