@@ -201,6 +201,27 @@ mpk_status mpk_decode_step(mpk_graph *g, const int32_t *token_ids, const int32_t
 mpk_status mpk_decode_steps(mpk_graph *g, uint32_t n_steps, int32_t *token_ids, int32_t *positions,
                             int32_t *tokens_out, float *logits_out, float *logits_all, void *stream);
 
+/* mpk_decode_step for callers that must not allocate device memory and want the library to hold
+ * none for them per graph either (code under HIP graph capture of the per-operator launches,
+ * tight serving loops, harnesses that forbid hipMalloc): the step's scratch memory -- activations,
+ * split-KV partials, partial sums, meta-tensors, event and arrival counters -- lives in ONE array
+ * of MPK_STATIC_SCRATCH_BYTES that is part of the library image (each GPU the library runs on
+ * holds its copy until the process ends), not in the buffers mpk_compile allocated for the graph.
+ * The call itself allocates nothing and frees nothing.
+ *   Arguments, outputs and errors as mpk_decode_step.  Additionally UNSUPPORTED when the graph
+ *   needs more scratch than the array holds (mpk_static_scratch_need tells), when it was compiled
+ *   with scheduler workgroups, greedy_loop or MPK_DEBUG_TRACE, or host_only.
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU race, also
+ * calls of different graphs.  The array keeps the previous call's contents; the call clears the
+ * counters it needs at zero itself (a small kernel on `stream`, no memset node) and every step
+ * counts as the graph's first, so steps through this entry point and through mpk_decode_step may
+ * be mixed freely on one graph. */
+#define MPK_STATIC_SCRATCH_BYTES (32u << 20)
+mpk_status mpk_decode_step_static(mpk_graph *g, const int32_t *token_ids, const int32_t *positions,
+                                  float *logits_out, void *stream);
+/* Bytes of scratch a step of this graph needs (what mpk_decode_step_static places in the array). */
+size_t mpk_static_scratch_need(const mpk_graph *g);
+
 /* After the stream has been synchronised by the caller: translate the device error word.
  * MPK_OK, MPK_ERR_TIMEOUT (watchdog; the graph must be reset) or MPK_ERR_DEVICE. */
 mpk_status mpk_graph_status(mpk_graph *g);

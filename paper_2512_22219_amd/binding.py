@@ -85,8 +85,8 @@ EXPORT_EVENT = np.dtype([("required", "<u4"), ("first", "<u4"), ("last", "<u4"),
 SYMBOLS = ("mpk_compile", "mpk_compile_dag", "mpk_decode_step", "mpk_decode_steps", "mpk_graph_status",
            "mpk_graph_reset", "mpk_graph_stats", "mpk_graph_export", "mpk_graph_trace",
            "mpk_graph_moe_active", "mpk_graph_moe_selection", "mpk_compile_set",
-           "mpk_set_decode_step", "mpk_set_size", "mpk_set_batch_for", "mpk_set_graph",
-           "mpk_set_destroy", "mpk_last_error", "mpk_graph_destroy")
+           "mpk_set_decode_step", "mpk_decode_step_static", "mpk_set_size", "mpk_set_batch_for", "mpk_set_graph",
+           "mpk_set_destroy", "mpk_last_error", "mpk_graph_destroy", "mpk_static_scratch_need")
 DEBUG_TRACE, DEBUG_POISON, DEBUG_JITTER = 1, 2, 4
 
 _lib = None
@@ -106,6 +106,9 @@ def lib():
         L.mpk_compile_dag.argtypes = [C.c_uint32, vp, C.c_size_t, C.POINTER(CompileOptions),
                                       C.POINTER(vp)]
         L.mpk_decode_step.argtypes = [vp, vp, vp, vp, vp]
+        L.mpk_decode_step_static.argtypes = [vp, vp, vp, vp, vp]
+        L.mpk_static_scratch_need.argtypes = [vp]
+        L.mpk_static_scratch_need.restype = C.c_size_t
         L.mpk_decode_steps.argtypes = [vp, C.c_uint32, vp, vp, vp, vp, vp, vp]
         L.mpk_graph_status.argtypes = [vp]
         L.mpk_graph_reset.argtypes = [vp]
@@ -127,7 +130,7 @@ def lib():
         L.mpk_set_graph.restype = vp
         L.mpk_set_destroy.argtypes = [vp]
         L.mpk_set_destroy.restype = None
-        for n in SYMBOLS[:13]:
+        for n in SYMBOLS[:14]:
             getattr(L, n).restype = C.c_int
         _lib = L
     return _lib
@@ -194,6 +197,12 @@ class Graph:
 
     def decode_step(self, token_ids_ptr: int, positions_ptr: int, logits_ptr: int, stream: int = 0):
         _check(lib().mpk_decode_step(self._h, token_ids_ptr, positions_ptr, logits_ptr, stream))
+
+    def decode_step_static(self, token_ids_ptr: int, positions_ptr: int, logits_ptr: int, stream: int = 0):
+        _check(lib().mpk_decode_step_static(self._h, token_ids_ptr, positions_ptr, logits_ptr, stream))
+
+    def static_scratch_need(self) -> int:
+        return int(lib().mpk_static_scratch_need(self._h))
 
     def decode_steps(self, n_steps: int, token_ids_ptr: int, positions_ptr: int, tokens_out_ptr: int,
                      logits_ptr: int, logits_all_ptr: int = 0, stream: int = 0):

@@ -26,7 +26,12 @@ static const KernelVariant* pick_variant(uint32_t d, uint32_t grp, uint32_t batc
   return variant_at(moe ? n - 1 : n - 2);   // the generic fallbacks come last: dense, then mixture of experts
 }
 
-// Fills n 32-bit words (NaN patterns for MPK_DEBUG_POISON).
+// Scratch memory of mpk_decode_step_static: part of the library image, one copy per GPU.  In host
+// code this name is only a handle for hipGetSymbolAddress; every use of the memory goes through the
+// device address that call returns (static_scratch_base below).
+static __device__ __align__(256) unsigned char scratch[MPK_STATIC_SCRATCH_BYTES];
+
+// Fills n 32-bit words (counters to zero before a static step; NaN patterns for MPK_DEBUG_POISON).
 // A kernel, not a memset node: a caller may be capturing the stream.
 __global__ void __launch_bounds__(256) fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
@@ -70,6 +75,13 @@ struct mpk_graph {
   uint32_t epoch = 0;
   uint64_t timeout_ticks = 0;
   uint32_t step_flags = 0;   // StepArgs::flags of every launch (trace, jitter, no pre-loading)
+  // mpk_decode_step_static: descriptors and graph record relocated into the static scratch array
+  // (null when the graph is not eligible), and where its pieces sit in the array (bytes)
+  TaskDesc* d_tasks_static = nullptr;
+  GraphConst* d_const_static = nullptr;
+  unsigned char* static_base = nullptr;
+  size_t st_counters = 0, st_hier = 0, st_grp = 0, st_arena = 0, st_need = 0;
+  const char* static_refusal = "graph was compiled host_only";
   void* launch_out[2] = {nullptr, nullptr};   // host copy of GraphConst::tokens_out / logits_all (source of the async copy)
 };
 
@@ -90,6 +102,27 @@ static void free_device(mpk_graph* g) {
   (void)hipFree(g->d_inv_freq); (void)hipFree(g->d_grp); (void)hipFree(g->d_trace); (void)hipFree(g->d_hier); (void)hipFree(g->d_const);
   (void)hipFree(g->d_evq_buf); (void)hipFree(g->d_evq_tail); (void)hipFree(g->d_sched_state); (void)hipFree(g->d_sched_nev);
   (void)hipFree(g->d_wq_buf); (void)hipFree(g->d_wq_tail); (void)hipFree(g->d_wq_head);
+  (void)hipFree(g->d_tasks_static); (void)hipFree(g->d_const_static);
+}
+
+// Device address of this GPU's copy of the static scratch array; looked up once per device, with
+// that device current.
+static mpk_status static_scratch_base(int device, unsigned char** out) {
+  static std::mutex mu;
+  static unsigned char* base[64] = {};
+  if (device < 0 || device >= 64) { set_error("device index %d out of range", device); return MPK_ERR_INVALID_ARG; }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!base[device]) {
+    int cur = -1;
+    HIP_TRY(hipGetDevice(&cur));
+    if (cur != device) { set_error("device %d is not current (current: %d)", device, cur); return MPK_ERR_INVALID_ARG; }
+    unsigned char* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(mpk::scratch)));
+    if (!p) { set_error("hipGetSymbolAddress returned a null address"); return MPK_ERR_HIP; }
+    base[device] = p;
+  }
+  *out = base[device];
+  return MPK_OK;
 }
 
 static mpk_status resolve_options(const mpk_compile_options* in, mpk_compile_options* out,
@@ -283,6 +316,39 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
     if ((st = upload(&g->d_const, cv)) != MPK_OK) return fail(st);
     g->step_flags = (g->d_trace ? kTraceBit : 0u) | ((o.debug_flags & MPK_DEBUG_JITTER) ? kJitterBit : 0u) |
                     (o.no_preload ? kNoPreloadBit : 0u);
+    // ---- the same graph over the static scratch array (mpk_decode_step_static)
+    auto up256 = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    g->st_counters = 0;
+    g->st_hier = up256(h.events.size() * sizeof(uint32_t));
+    g->st_grp = g->st_hier + up256((size_t)std::max(h.n_hier_events, 1u) * kHierWordsPerEvent * sizeof(uint32_t));
+    g->st_arena = g->st_grp + up256(std::max<size_t>(h.n_group_counters, 1) * sizeof(uint32_t));
+    g->st_need = g->st_arena + up256(arena_bytes);
+    g->static_refusal = nullptr;
+    if (g->n_sched) g->static_refusal = "graph was compiled with scheduler workgroups";
+    else if (h.opt.greedy_loop) g->static_refusal = "graph was compiled with greedy_loop";
+    else if (g->d_trace) g->static_refusal = "graph was compiled with MPK_DEBUG_TRACE";
+    else if (g->st_need > MPK_STATIC_SCRATCH_BYTES) g->static_refusal = "graph needs more scratch memory than the static array holds";
+    if (!g->static_refusal) {
+      if ((st = static_scratch_base(g->device, &g->static_base)) != MPK_OK) return fail(st);
+      float* arena_s = (float*)(g->static_base + g->st_arena);
+      std::vector<TaskDesc> ds = h.descs;
+      auto reloc_s = [&](const float* p) -> const float* { return p ? arena_s + ((uintptr_t)p / sizeof(float) - 1) : nullptr; };
+      for (auto& t : ds) {
+        t.in = reloc_s(t.in);
+        t.in2 = reloc_s(t.in2);
+        t.out = const_cast<float*>(reloc_s(t.out));
+        if (t.kind == TK_MOE_ROUTE || t.kind == TK_MOE_EXPERT || t.kind == TK_MOE_COMBINE || (t.flags & TF_SPLITK))
+          t.aux0 = (void*)reloc_s((const float*)t.aux0);
+      }
+      if ((st = upload(&g->d_tasks_static, ds)) != MPK_OK) return fail(st);
+      GraphConst cs = c;
+      cs.tasks = g->d_tasks_static;
+      cs.counters = (uint32_t*)(g->static_base + g->st_counters);
+      cs.hier = (uint32_t*)(g->static_base + g->st_hier);
+      cs.grp_counters = (uint32_t*)(g->static_base + g->st_grp);
+      std::vector<GraphConst> csv(1, cs);
+      if ((st = upload(&g->d_const_static, csv)) != MPK_OK) return fail(st);
+    }
   }
   *out = g;
   return MPK_OK;
@@ -308,7 +374,8 @@ extern "C" mpk_status mpk_compile_dag(uint32_t n_tasks, const uint32_t* pairs, s
 }
 
 static mpk_status launch_steps(mpk_graph* g, uint32_t n_steps, const int32_t* token_ids, const int32_t* positions,
-                               int32_t* tokens_out, float* logits_out, float* logits_all, void* stream) {
+                               int32_t* tokens_out, float* logits_out, float* logits_all, void* stream,
+                               bool static_scratch = false) {
   HostGraph& h = g->h;
   StepArgs a{};
   a.g = (const MPK_CONST GraphConst*)g->d_const;
@@ -318,6 +385,17 @@ static mpk_status launch_steps(mpk_graph* g, uint32_t n_steps, const int32_t* to
   hipStream_t s = (hipStream_t)stream;
   float* arena = g->d_arena;
   const size_t arena_words = std::max<size_t>(h.arena_floats, 64);
+  if (static_scratch) {
+    // the step's working memory is the static array: counters start from zero every time (the
+    // array is shared by all graphs on this GPU), so this is always "step one"
+    a.g = (const MPK_CONST GraphConst*)g->d_const_static;
+    a.tasks = g->d_tasks_static;
+    a.counters = (uint32_t*)(g->static_base + g->st_counters);
+    a.hier = (uint32_t*)(g->static_base + g->st_hier);
+    arena = (float*)(g->static_base + g->st_arena);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(256), 0, s, (uint32_t*)g->static_base, g->st_arena / sizeof(uint32_t), 0u);
+    HIP_TRY(hipGetLastError());
+  }
   if (h.opt.debug_flags & MPK_DEBUG_POISON) {
     hipLaunchKernelGGL(fill_u32_kernel, dim3(256), dim3(256), 0, s, (uint32_t*)arena, arena_words, 0x7FC00000u);
     HIP_TRY(hipGetLastError());
@@ -337,9 +415,9 @@ static mpk_status launch_steps(mpk_graph* g, uint32_t n_steps, const int32_t* to
                            hipMemcpyHostToDevice, s));
   }
   if (h.opt.launch_mode == MPK_LAUNCH_MEGA) {
-    a.epoch = g->epoch + 1;
+    a.epoch = static_scratch ? 1u : g->epoch + 1;
     a.step = 0; a.n_steps = (uint16_t)n_steps;
-    g->epoch += n_steps;
+    if (!static_scratch) g->epoch += n_steps;
     if (n_steps > 1)   // (callers have checked: no scheduler workgroups)
       hipLaunchKernelGGL(g->kv->loop, dim3(h.opt.n_workers), dim3(kThreads), h.lds_bytes, s, a);
     else
@@ -349,7 +427,7 @@ static mpk_status launch_steps(mpk_graph* g, uint32_t n_steps, const int32_t* to
   } else {
     a.n_steps = (uint16_t)n_steps;
     for (uint32_t step = 0; step < n_steps; ++step) {
-      a.epoch = ++g->epoch;
+      a.epoch = static_scratch ? 1u : ++g->epoch;
       a.step = (uint16_t)step;
       for (size_t oi = 0; oi < h.ops.size(); ++oi) {
         if (!g->op_count[oi]) continue;
@@ -369,6 +447,21 @@ extern "C" mpk_status mpk_decode_step(mpk_graph* g, const int32_t* token_ids,
   if (g->h.opt.greedy_loop) { set_error("graph was compiled with greedy_loop: it samples and advances tokens and positions itself, run it with mpk_decode_steps"); return MPK_ERR_INVALID_ARG; }
   return launch_steps(g, 1, token_ids, positions, nullptr, logits_out, nullptr, stream);
 }
+
+extern "C" mpk_status mpk_decode_step_static(mpk_graph* g, const int32_t* token_ids, const int32_t* positions,
+                                             float* logits_out, void* stream) {
+  if (!g || !token_ids || !positions || !logits_out) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
+  if (g->static_refusal) {
+    set_error("mpk_decode_step_static: %s (needs %zu bytes, the array holds %u)", g->static_refusal, g->st_need, (unsigned)MPK_STATIC_SCRATCH_BYTES);
+    return g->host_only ? MPK_ERR_INVALID_ARG : MPK_ERR_UNSUPPORTED;
+  }
+  int cur = -1;
+  HIP_TRY(hipGetDevice(&cur));
+  if (cur != g->device) { set_error("the graph lives on device %d, device %d is current", g->device, cur); return MPK_ERR_INVALID_ARG; }
+  return launch_steps(g, 1, token_ids, positions, nullptr, logits_out, nullptr, stream, true);
+}
+
+extern "C" size_t mpk_static_scratch_need(const mpk_graph* g) { return (g && !g->host_only) ? g->st_need : 0; }
 
 extern "C" mpk_status mpk_decode_steps(mpk_graph* g, uint32_t n_steps, int32_t* token_ids, int32_t* positions,
                                        int32_t* tokens_out, float* logits_out, float* logits_all, void* stream) {
