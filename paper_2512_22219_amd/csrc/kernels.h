@@ -537,6 +537,19 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
       asm volatile("; third half block requested" ::: "memory");
     }
   }
+  // the first gains of a folded RMSNorm are weights too: requested before the event, so that the
+  // staging below is one round trip (the input) instead of two
+  constexpr int kGainPre = 4;   // x 512 threads x 2: the first 4096 inputs
+  uint32_t gpre[kGainPre];
+  {
+    const uint16_t* gain0 = (const uint16_t*)t.w2;
+#pragma unroll
+    for (int u = 0; u < kGainPre; ++u) {
+      const uint32_t i = u * kThreads + threadIdx.x;
+      gpre[u] = 0;
+      if ((t.flags & TF_PRO_NORM) && i < K / 2) gpre[u] = *as_global((const uint32_t*)(gain0 + 2 * i));
+    }
+  }
   // ---- dependent event: wavefront 0 polls, the others wait at the barrier
   if (wait_ev >= 0) {
     const uint32_t w = linear_wait(a, wait_ev, s_flag, wave, lane, svc);
@@ -594,7 +607,7 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
             if (pro_norm) {
               ss = fmaf(v.x, v.x, ss);
               ss = fmaf(v.y, v.y, ss);
-              uint32_t g2 = *as_global((const uint32_t*)(gain + 2 * i));
+              uint32_t g2 = (i0 == 0 && u < kGainPre) ? gpre[u < kGainPre ? u : 0] : *as_global((const uint32_t*)(gain + 2 * i));
               v.x *= bf16_lo(g2);
               v.y *= bf16_hi(g2);
             }
@@ -724,7 +737,8 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
     // not enough: all wavefronts of a CU share its path to memory, and behind 224 freshly issued
     // 1 KB loads the few output stores of wavefront 0 were acknowledged up to 10 us late (in-kernel
     // trace), which delays the event for every consumer -- the hop is the critical path, the
-    // pre-load has slack.
+    // pre-load has slack.  (Releasing them once the stores have been issued, not acknowledged, was
+    // measured too: 0.6 % slower per step on the 8B shape.)
     lds_barrier();
     if (wave == 0) {
       if (t.trig_event >= 0 && lane == 0) notify_event(a, t.trig_event);
@@ -1518,6 +1532,18 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
     load_rows();
     asm volatile("; cache rows requested" ::: "memory");
   }
+  // the rotation angles depend on the position alone: worked out (in double precision) before the
+  // event, off the critical path from the QKV projection to the O projection.  A thread's first
+  // query element, and the two key pairs of the threads that append the new row.
+  float pre_cs = 1.f, pre_sn = 0.f, pre_c0 = 1.f, pre_s0 = 0.f, pre_c1 = 1.f, pre_s1 = 0.f;
+  if (t.flags & TF_ROPE_FUSED) {
+    if (threadIdx.x < grp * (d / 2)) rope_cs(a, pos, threadIdx.x % (d / 2), &pre_cs, &pre_sn);
+    const uint32_t ik = kThreads - 1 - threadIdx.x;
+    if (c == C - 1 && ik < d / 4) {
+      rope_cs(a, pos, 2 * ik, &pre_c0, &pre_s0);
+      rope_cs(a, pos, 2 * ik + 1, &pre_c1, &pre_s1);
+    }
+  }
   if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
   trace_mark(a, t, 1);
   if (!preload) {
@@ -1544,7 +1570,8 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
         u0 *= inv * bf16_to_f32(as_global(gq)[e]);
         u1 *= inv * bf16_to_f32(as_global(gq)[e + half]);
       }
-      rope_cs(a, pos, e, &cs, &sn);
+      if (i < kThreads) { cs = pre_cs; sn = pre_sn; }
+      else rope_cs(a, pos, e, &cs, &sn);
       qs[j * d + e] = u0 * cs - u1 * sn;
       qs[j * d + e + half] = u1 * cs + u0 * sn;
     }
@@ -1566,9 +1593,7 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
             lo.x *= inv * bf16_lo(g0); lo.y *= inv * bf16_hi(g0);
             hi.x *= inv * bf16_lo(g1); hi.y *= inv * bf16_hi(g1);
           }
-          float c0, s0, c1, s1;
-          rope_cs(a, pos, e, &c0, &s0);
-          rope_cs(a, pos, e + 1, &c1, &s1);
+          const float c0 = pre_c0, s0 = pre_s0, c1 = pre_c1, s1 = pre_s1;   // (i < half / 2 <= kThreads: the first pass)
           float r0 = lo.x * c0 - hi.x * s0, r1 = lo.y * c1 - hi.y * s1;
           float r2 = hi.x * c0 + lo.x * s0, r3 = hi.y * c1 + lo.y * s1;
           st_act_u32((uint32_t*)(krow + e), (uint32_t)f32_to_bf16(r0) | ((uint32_t)f32_to_bf16(r1) << 16));
@@ -1814,6 +1839,18 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
     load_rows();
     asm volatile("; cache rows requested" ::: "memory");
   }
+  // the rotation angles depend on the position alone: worked out (in double precision) before the
+  // event, off the critical path from the QKV projection to the O projection.  A thread's first
+  // query element, and the two key pairs of the threads that append the new row.
+  float pre_cs = 1.f, pre_sn = 0.f, pre_c0 = 1.f, pre_s0 = 0.f, pre_c1 = 1.f, pre_s1 = 0.f;
+  if (t.flags & TF_ROPE_FUSED) {
+    if (threadIdx.x < grp * (d / 2)) rope_cs(a, pos, threadIdx.x % (d / 2), &pre_cs, &pre_sn);
+    const uint32_t ik = kThreads - 1 - threadIdx.x;
+    if (c == C - 1 && ik < d / 4) {
+      rope_cs(a, pos, 2 * ik, &pre_c0, &pre_s0);
+      rope_cs(a, pos, 2 * ik + 1, &pre_c1, &pre_s1);
+    }
+  }
   if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
   trace_mark(a, t, 1);
   if (!preload) {
@@ -1840,7 +1877,8 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
         u0 *= inv * bf16_to_f32(as_global(gq)[e]);
         u1 *= inv * bf16_to_f32(as_global(gq)[e + half]);
       }
-      rope_cs(a, pos, e, &cs, &sn);
+      if (i < kThreads) { cs = pre_cs; sn = pre_sn; }
+      else rope_cs(a, pos, e, &cs, &sn);
       qs[j * d + e] = u0 * cs - u1 * sn;
       qs[j * d + e + half] = u1 * cs + u0 * sn;
     }
@@ -1862,9 +1900,7 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
             lo.x *= inv * bf16_lo(g0); lo.y *= inv * bf16_hi(g0);
             hi.x *= inv * bf16_lo(g1); hi.y *= inv * bf16_hi(g1);
           }
-          float c0, s0, c1, s1;
-          rope_cs(a, pos, e, &c0, &s0);
-          rope_cs(a, pos, e + 1, &c1, &s1);
+          const float c0 = pre_c0, s0 = pre_s0, c1 = pre_c1, s1 = pre_s1;   // (i < half / 2 <= kThreads: the first pass)
           float r0 = lo.x * c0 - hi.x * s0, r1 = lo.y * c1 - hi.y * s1;
           float r2 = hi.x * c0 + lo.x * s0, r3 = hi.y * c1 + lo.y * s1;
           st_act_u32((uint32_t*)(krow + e), (uint32_t)f32_to_bf16(r0) | ((uint32_t)f32_to_bf16(r1) << 16));
@@ -2190,39 +2226,55 @@ __device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, f
 
 // ------------------------------------------------------------------------------ runtime
 
-// Returns false when the step is being aborted (watchdog or a peer's failure).
-// Simple events: wait until counter >= epoch * required.  Hierarchical events: wait until this
-// worker group's ready flag has reached the epoch.
-__device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag) {
-  if (threadIdx.x == 0) {
-    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
-    const uint32_t* word;
-    uint32_t target;
-    if (ev.flags & EV_HIER) {
-      word = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
-      target = a.epoch * ev.n_groups;
-    } else {
-      word = a.counters + e;
-      target = a.epoch * ev.required;
+// Has event e been activated for this step?  The whole wavefront calls it; the answer is uniform.
+// Simple events: one counter, compared with epoch * required by lane 0.  Sharded events (wide,
+// all producers ahead-of-time): one counter per producer group (worker index mod 8), each on its
+// own 256-byte line; lanes 0..7 read one group's counter each -- a single load instruction -- and
+// compare it with epoch * (that group's producers).  An arrival is then ONE atomic add that nobody
+// waits for, and 256 producers spread over 8 lines.
+__device__ __forceinline__ bool event_reached(const StepArgs& a, int32_t e, int lane) {
+  const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
+  bool ok = true;
+  if (ev.flags & EV_HIER) {
+    if (lane < 8) {
+      const uint32_t need = a.epoch * ((const MPK_CONST EventDesc*)(a.events + e))->sub_required[lane];
+      const uint32_t v = ld_relaxed(a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (1 + lane) * kHierStrideWords);
+      ok = (int32_t)(v - need) >= 0;
     }
-    uint32_t ok = 1;
-    if ((int32_t)(ld_relaxed(word) - target) < 0) {
-      const uint64_t t_start = wall_clock64();
-      uint32_t it = 0;
-      while ((int32_t)(ld_relaxed(word) - target) < 0) {
-        if ((++it & 255u) == 0) {
-          if (ld_relaxed(a.g->err + 1) != 0) { ok = 0; break; }
-          if (wall_clock64() - t_start > a.g->timeout_ticks) {
+  } else if (lane == 0) {
+    ok = (int32_t)(ld_relaxed(a.counters + e) - a.epoch * ev.required) >= 0;
+  }
+  return __builtin_amdgcn_readfirstlane((int)(__ballot(ok) == ~0ull)) != 0;
+}
+
+// The first wavefront polls until event e is activated; *s_flag = 1, or 0 when the step is being
+// aborted (watchdog or a peer's failure).  Called by all 64 lanes of the wavefront.
+__device__ __forceinline__ void poll_event_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane) {
+  uint32_t ok = 1;
+  if (!event_reached(a, e, lane)) {
+    const uint64_t t_start = wall_clock64();
+    uint32_t it = 0;
+    while (!event_reached(a, e, lane)) {
+      if ((++it & 255u) == 0) {
+        uint32_t dead = 0;
+        if (lane == 0) {
+          if (ld_relaxed(a.g->err + 1) != 0) dead = 1;
+          else if (wall_clock64() - t_start > a.g->timeout_ticks) {
             report(a, DE_TIMEOUT, (uint32_t)e, blockIdx.x);
             __hip_atomic_store(as_global(a.g->err + 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            ok = 0;
-            break;
+            dead = 1;
           }
         }
+        if (__builtin_amdgcn_readfirstlane(dead)) { ok = 0; break; }
       }
     }
-    *s_flag = ok;
   }
+  if (lane == 0) *s_flag = ok;
+}
+
+// Returns false when the step is being aborted (watchdog or a peer's failure).
+__device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_t* s_flag) {
+  if (threadIdx.x < 64) poll_event_wave0(a, e, s_flag, (int)threadIdx.x);
   __syncthreads();   // later agent-scope loads cannot move above this barrier
   return __builtin_amdgcn_readfirstlane(*s_flag) != 0;
 }
@@ -2237,16 +2289,16 @@ __device__ __forceinline__ void notify_event(const StepArgs& a, int32_t e) {
   if (flags & EV_HIER) {
     uint32_t* blk = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent;
     const uint32_t grp = blockIdx.x & 7u;
-    uint32_t old = __hip_atomic_fetch_add(as_global(blk + (1 + grp) * kHierStrideWords), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (old + 1u == a.epoch * ev.sub_required[grp]) {          // last arrival of this group
-      // tell every group of pollers: its word counts the producer groups that are complete
-#pragma unroll
-      for (uint32_t k = 0; k < 8; ++k)
-        __hip_atomic_fetch_add(as_global(blk + (9 + k) * kHierStrideWords), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if ((flags & EV_JIT) && a.n_sched) {                  // a scheduler needs to know who was last
+    if ((flags & EV_JIT) && a.n_sched) {
+      // a scheduler has to be told by the arrival that completes the event: the last arrival of a
+      // producer group adds to the top counter, the last of those hands the event over
+      uint32_t old = __hip_atomic_fetch_add(as_global(blk + (1 + grp) * kHierStrideWords), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (old + 1u == a.epoch * ev.sub_required[grp]) {
         old = __hip_atomic_fetch_add(as_global(blk), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         activated = old + 1u == a.epoch * ev.n_groups;
       }
+    } else {
+      __hip_atomic_fetch_add(as_global(blk + (1 + grp) * kHierStrideWords), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   } else if ((flags & EV_JIT) && a.n_sched) {
     const uint32_t old = __hip_atomic_fetch_add(as_global(a.counters + e), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -2272,72 +2324,31 @@ __device__ __forceinline__ void signal_event(const StepArgs& a, const TaskDesc& 
   if (threadIdx.x == 0) notify_event(a, e);
 }
 
-// Wavefront 0 only: poll the dependent event of the next task; result in *s_flag (LDS).
-__device__ __forceinline__ void poll_event_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane) {
-  if (lane == 0) {
-    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
-    const uint32_t* word;
-    uint32_t target;
-    if (ev.flags & EV_HIER) {
-      word = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
-      target = a.epoch * ev.n_groups;
-    } else {
-      word = a.counters + e;
-      target = a.epoch * ev.required;
-    }
-    uint32_t ok = 1;
-    if ((int32_t)(ld_relaxed(word) - target) < 0) {
-      const uint64_t t_start = wall_clock64();
-      uint32_t it = 0;
-      while ((int32_t)(ld_relaxed(word) - target) < 0) {
-        if ((++it & 255u) == 0) {
-          if (ld_relaxed(a.g->err + 1) != 0) { ok = 0; break; }
-          if (wall_clock64() - t_start > a.g->timeout_ticks) {
-            report(a, DE_TIMEOUT, (uint32_t)e, blockIdx.x);
-            __hip_atomic_store(as_global(a.g->err + 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            ok = 0;
-            break;
-          }
-        }
-      }
-    }
-    *s_flag = ok;
-  }
-}
-
 // Wavefront 0 only: like poll_event_wave0, but also watches the worker's just-in-time queue.
 // s_flag[0] = 1 event activated, 0 abort, 2 a just-in-time task (index in s_flag[1]) is queued.
 __device__ __forceinline__ void poll_event_or_jit_wave0(const StepArgs& a, int32_t e, uint32_t* s_flag, int lane, uint32_t jit_head) {
-  if (lane == 0) {
-    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
-    const uint32_t* word;
-    uint32_t target;
-    if (ev.flags & EV_HIER) {
-      word = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
-      target = a.epoch * ev.n_groups;
-    } else {
-      word = a.counters + e;
-      target = a.epoch * ev.required;
-    }
-    const uint64_t* slot = a.g->wq_buf + (size_t)blockIdx.x * a.g->wq_cap + (jit_head & (a.g->wq_cap - 1u));
-    const uint64_t t_start = wall_clock64();
-    uint32_t ok, it = 0;
-    while (true) {
-      if ((int32_t)(ld_relaxed(word) - target) >= 0) { ok = 1; break; }
+  const uint64_t* slot = a.g->wq_buf + (size_t)blockIdx.x * a.g->wq_cap + (jit_head & (a.g->wq_cap - 1u));
+  const uint64_t t_start = wall_clock64();
+  uint32_t ok, it = 0;
+  while (true) {
+    if (event_reached(a, e, lane)) { ok = 1; break; }
+    uint32_t got = 0, dead = 0;
+    if (lane == 0) {
       const uint64_t v = ld_relaxed64(slot);
-      if ((uint32_t)(v >> 32) == jit_head + 1u) { s_flag[1] = (uint32_t)v; ok = 2; break; }
-      if ((++it & 127u) == 0) {
-        if (ld_relaxed(a.g->err + 1) != 0) { ok = 0; break; }
-        if (wall_clock64() - t_start > a.g->timeout_ticks) {
+      if ((uint32_t)(v >> 32) == jit_head + 1u) { s_flag[1] = (uint32_t)v; got = 1; }
+      else if ((++it & 127u) == 0) {
+        if (ld_relaxed(a.g->err + 1) != 0) dead = 1;
+        else if (wall_clock64() - t_start > a.g->timeout_ticks) {
           report(a, DE_TIMEOUT, (uint32_t)e, blockIdx.x);
           __hip_atomic_store(as_global(a.g->err + 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          ok = 0;
-          break;
+          dead = 1;
         }
       }
     }
-    s_flag[0] = ok;
+    if (__builtin_amdgcn_readfirstlane(got)) { ok = 2; break; }
+    if (__builtin_amdgcn_readfirstlane(dead)) { ok = 0; break; }
   }
+  if (lane == 0) s_flag[0] = ok;
 }
 
 // Wavefront 0 only, after a workgroup barrier: wait for this wavefront's own coherent stores,
@@ -2425,9 +2436,15 @@ __device__ __noinline__ bool run_other_task(StepArgs a_in, uint32_t task_index, 
 __device__ __forceinline__ bool event_active(const StepArgs& a, int32_t e) {
   const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
   if (ev.required == 0) return true;
-  if (ev.flags & EV_HIER) {
-    const uint32_t* word = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (9 + (blockIdx.x & 7u)) * kHierStrideWords;
-    return (int32_t)(ld_relaxed(word) - a.epoch * ev.n_groups) >= 0;
+  if (ev.flags & EV_HIER) {   // (one lane: the eight group counters one after the other, all in flight together)
+    const uint32_t* blk = a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent;
+    uint32_t v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = ld_relaxed(blk + (1 + k) * kHierStrideWords);
+    bool ok = true;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) ok = ok && (int32_t)(v[k] - a.epoch * ev.sub_required[k]) >= 0;
+    return ok;
   }
   return (int32_t)(ld_relaxed(a.counters + e) - a.epoch * ev.required) >= 0;
 }

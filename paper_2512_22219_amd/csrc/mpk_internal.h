@@ -78,13 +78,11 @@ struct EventDesc {   // paper Section 4.1 "tGraph linearization" / Fig. 4(f)
 };
 static_assert(sizeof(EventDesc) == 64, "EventDesc is 64 bytes");
 constexpr uint32_t EV_JIT = 1, EV_HIER = 2;
-// A hierarchical event owns 17 words, each on its own 256-byte line: a top counter (used only
-// when a scheduler has to learn which arrival was the last), 8 producer-group counters and 8
-// poller words (one per worker group).  The last arrival of a producer group adds one to every
-// poller word; a poller waits until its word has counted all producer groups.  256 same-address
-// atomics plus 256 pollers on one line cost about 4 us per hop on this GPU; arrival by group and
-// one word per 32 pollers brings that to about 2 us, and no arrival waits for more than one
-// atomic to return.
+// A sharded ("hierarchical") event owns 9 words in use, each on its own 256-byte line: 8 producer-
+// group counters (worker index mod 8) that arrivals add to and pollers read all at once (one load
+// instruction, a lane per counter), and a top counter used only when a scheduler has to learn which
+// arrival was the last.  256 same-address atomics plus 256 pollers on one line cost about 4 us per
+// hop on this GPU; sharded, an arrival is one atomic add that nobody waits for.
 constexpr uint32_t kHierStrideWords = 64, kHierWordsPerEvent = 17 * kHierStrideWords;
 constexpr uint32_t kHierMinRequired = 48;
 

@@ -23,7 +23,7 @@ static const KernelVariant* pick_variant(uint32_t d, uint32_t grp, uint32_t batc
       if (v->d == (int)d && v->grp == (int)grp && v->nb == nb && v->moe == moe) return v;
     }
   }
-  return variant_at(moe ? n - 1 : n - 2);   // the generic fallbacks come last: dense, then mixture of experts
+  return variant_at(moe ? 7 : 6);   // the generic fallbacks: dense, mixture of experts
 }
 
 // Scratch memory of mpk_decode_step_static: part of the library image, one copy per GPU.  In host
