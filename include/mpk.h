@@ -149,6 +149,18 @@ typedef struct mpk_compile_options {
                                extent of mpk_kv_ptrs' layout); 0 = cfg.batch.  Lets a graph for
                                fewer sequences run on the first cfg.batch slots of a larger
                                cache (mpk_compile_set)                                          */
+  uint32_t worker_weight_permille[8]; /* relative streaming speed of the workers with index mod 8
+                               == k (the XCD a workgroup lands on), in thousandths; all 0 = equal.
+                               When they differ, the column tiles of a linear operator are sized in
+                               proportion to the speed of the worker that runs each (Section 4.1
+                               leaves the partition to the compiler: "the partitioning strategy
+                               ... minimizes device memory loading"; an operator ends with its
+                               slowest task).  Batch <= 4, operators with one tile per row block
+                               and at least 64 weight rows per tile, all tasks ahead-of-time; the
+                               exported graph lists the boundaries                              */
+  uint32_t xcd_balance;     /* 1 = measure those speeds on this GPU at compile time (a streaming
+                               kernel over the LM-head weights, about a millisecond) when
+                               worker_weight_permille is all 0.  Not with host_only              */
 } mpk_compile_options;
 
 typedef struct mpk_graph mpk_graph;
@@ -257,7 +269,9 @@ mpk_status mpk_graph_stats(const mpk_graph *g, mpk_stats *out);
 
 /* Export the compiled graph (host memory, little-endian, see the mpk_export_* structs).
  * Layout: header | ops[n_ops] | tasks[n_tasks] (linearized order) | events[n_events] |
- * u32 aot_offsets[n_workers + 1] | u32 aot_tasks[aot_offsets[n_workers]].
+ * u32 aot_offsets[n_workers + 1] | u32 aot_tasks[aot_offsets[n_workers]] | u32 n_explicit |
+ * n_explicit x { u32 op, u32 n (= that operator's tc + 1), u32 column_begin[n] }: the operators
+ * whose column tiles are not the even split (worker_weight_permille), with their boundaries.
  * Call with buf == NULL to get the size in *need.  INVALID_ARG if cap is too small. */
 #define MPK_EXPORT_MAGIC 0x4B504D54u /* "TMPK" */
 #define MPK_NO_EVENT (-1)

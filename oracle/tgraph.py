@@ -153,10 +153,18 @@ def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: 
     return ops
 
 
-def col_bounds(op: OpSpec, tc: int):
+def col_bounds(op: OpSpec, tc: int, explicit=None):
     """Column boundaries (tc + 1 of them) of an operator's tiles.  One even split -- except for
     the QKV projection (params["head"]), whose tiles never straddle a head: the columns are cut
-    into heads first and every head evenly into the same number of tiles (DESIGN: decomposition)."""
+    into heads first and every head evenly into the same number of tiles (DESIGN: decomposition).
+    `explicit`: boundaries handed in (a partition is the compiler's choice, Section 4.1; the
+    dependency rule is what is checked): they must cut [0, cols) into tc non-empty tiles at
+    multiples of the operator's unit."""
+    if explicit is not None:
+        b = [int(x) for x in explicit]
+        assert len(b) == tc + 1 and b[0] == 0 and b[-1] == op.cols, (op.name, len(b), tc)
+        assert all(x < y for x, y in zip(b, b[1:])) and all(x % op.unit == 0 for x in b), op.name
+        return b
     nu = op.cols // op.unit
     head = op.meta.get("head")
     if head and nu % head == 0 and tc % (nu // head) == 0:
@@ -168,11 +176,11 @@ def col_bounds(op: OpSpec, tc: int):
     return [u * op.unit for u in split_even(nu, tc)]
 
 
-def owner_map(op: OpSpec, tb: int, tc: int) -> np.ndarray:
+def owner_map(op: OpSpec, tb: int, tc: int, explicit=None) -> np.ndarray:
     """owner[b, col] = tile index (ib * tc + ic) of the task that writes that output element."""
     assert op.cols % op.unit == 0
     rb = split_even(op.rows, tb)
-    cb = col_bounds(op, tc)
+    cb = col_bounds(op, tc, explicit)
     own = np.empty((op.rows, op.cols), np.int32)
     for ib in range(tb):
         for ic in range(tc):
@@ -180,17 +188,17 @@ def owner_map(op: OpSpec, tb: int, tc: int) -> np.ndarray:
     return own
 
 
-def tile_bounds(op: OpSpec, tb: int, tc: int, tile: int):
+def tile_bounds(op: OpSpec, tb: int, tc: int, tile: int, explicit=None):
     ib, ic = divmod(tile, tc)
     rb = split_even(op.rows, tb)
-    cb = col_bounds(op, tc)
+    cb = col_bounds(op, tc, explicit)
     return rb[ib], rb[ib + 1], cb[ic], cb[ic + 1]
 
 
-def read_elements(op: OpSpec, tb: int, tc: int, tile: int, shapes: dict):
+def read_elements(op: OpSpec, tb: int, tc: int, tile: int, shapes: dict, explicit=None):
     """Elements of each input tensor that task `tile` of `op` reads, from the operator's math.
     Returns {tensor: boolean mask [rows, cols]} (masks make unions and overlaps obvious)."""
-    b0, b1, c0, c1 = tile_bounds(op, tb, tc, tile)
+    b0, b1, c0, c1 = tile_bounds(op, tb, tc, tile, explicit)
     out = {}
 
     def mask(t):
@@ -272,7 +280,8 @@ def read_elements(op: OpSpec, tb: int, tc: int, tile: int, shapes: dict):
 
 
 def producer_sets(ops, degrees):
-    """degrees: list of (tb, tc) per op.  Returns psets[op][tile] = sorted list of (op', tile')."""
+    """degrees: list of (tb, tc) per op, or (tb, tc, column boundaries) where the partition is not
+    the even split.  Returns psets[op][tile] = sorted list of (op', tile')."""
     shapes, producer, owners = {}, {}, {}
     for i, op in enumerate(ops):
         shapes[op.out] = (op.rows, op.cols)
@@ -280,10 +289,11 @@ def producer_sets(ops, degrees):
         owners[op.out] = owner_map(op, *degrees[i])
     psets = []
     for i, op in enumerate(ops):
-        tb, tc = degrees[i]
+        tb, tc = degrees[i][:2]
+        explicit = degrees[i][2] if len(degrees[i]) > 2 else None
         cache, per_op = {}, []
         for tile in range(tb * tc):
-            reads = read_elements(op, tb, tc, tile, shapes)
+            reads = read_elements(op, tb, tc, tile, shapes, explicit)
             ps = set()
             for t, m in reads.items():
                 key = (t, m.tobytes())

@@ -52,7 +52,8 @@ class CompileOptions(C.Structure):
                 ("struct_size", "n_workers", "n_sched_wgs", "fusion", "transitive_reduction",
                  "attn_chunks", "tiles_linear", "tiles_lm_head", "tiles_pointwise", "launch_mode",
                  "force_aot", "no_preload", "host_only", "spin_timeout_ms", "debug_flags",
-                 "tiles_moe", "greedy_loop", "kv_batch")]
+                 "tiles_moe", "greedy_loop", "kv_batch")] + [("worker_weight_permille", C.c_uint32 * 8),
+                                                             ("xcd_balance", C.c_uint32)]
 
 
 class Stats(C.Structure):
@@ -161,7 +162,11 @@ def compile_options(**kw) -> CompileOptions:
     for k, v in kw.items():
         if not hasattr(o, k):
             raise TypeError(k)
-        setattr(o, k, int(v))
+        if k == "worker_weight_permille":
+            for i, x in enumerate(v):
+                o.worker_weight_permille[i] = int(x)
+        else:
+            setattr(o, k, int(v))
     return o
 
 
@@ -185,6 +190,14 @@ class Export:
         off += 4 * (nw + 1)
         self.aot = np.frombuffer(blob, "<u4", int(self.aot_off[-1]), off)
         off += 4 * int(self.aot_off[-1])
+        self.col_begin = {}          # operator index -> explicit column boundaries (tc + 1 of them)
+        n_explicit = int(np.frombuffer(blob, "<u4", 1, off)[0])
+        off += 4
+        for _ in range(n_explicit):
+            op, n = (int(x) for x in np.frombuffer(blob, "<u4", 2, off))
+            off += 8
+            self.col_begin[op] = np.frombuffer(blob, "<u4", n, off)
+            off += 4 * n
         assert off == len(blob)
 
 

@@ -52,17 +52,25 @@ static inline uint32_t tile_of(uint32_t n, uint32_t k, uint32_t u) {
 // segment evenly into seg_tiles tiles, so that no tile straddles a head whatever its size.
 static inline uint32_t col_tile_begin(const HostOp& op, uint32_t ic) {
   const uint32_t nu = op.cols / op.unit;
+  if (!op.col_begin.empty()) return op.col_begin[std::min<size_t>(ic, op.col_begin.size() - 1)];
   if (!op.seg_tiles) return tile_begin(nu, op.tc, ic);
   if (ic >= op.tc) return nu;
   return ic / op.seg_tiles * op.align_unit + tile_begin(op.align_unit, op.seg_tiles, ic % op.seg_tiles);
 }
 static inline uint32_t col_tile_of(const HostOp& op, uint32_t u) {
   const uint32_t nu = op.cols / op.unit;
+  if (!op.col_begin.empty())   // the tile whose [begin, next begin) holds u
+    return (uint32_t)(std::upper_bound(op.col_begin.begin(), op.col_begin.end(), u) - op.col_begin.begin()) - 1u;
   if (!op.seg_tiles) return tile_of(nu, op.tc, u);
   return u / op.align_unit * op.seg_tiles + tile_of(op.align_unit, op.seg_tiles, u % op.align_unit);
 }
 static inline uint32_t col_tile_max_units(const HostOp& op) {
   const uint32_t nu = op.cols / op.unit;
+  if (!op.col_begin.empty()) {
+    uint32_t m = 0;
+    for (size_t i = 0; i + 1 < op.col_begin.size(); ++i) m = std::max(m, op.col_begin[i + 1] - op.col_begin[i]);
+    return m;
+  }
   if (!op.seg_tiles) return (nu + op.tc - 1) / op.tc;
   return (op.align_unit + op.seg_tiles - 1) / op.seg_tiles;
 }
@@ -1053,9 +1061,70 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
   return MPK_OK;
 }
 
+// Tiles sized by the speed of the worker that runs them (option worker_weight_permille: the eight
+// XCDs of the GPU do not stream equally fast, and an operator ends with its slowest task).  Which
+// worker runs which tile is only known after linearization and pre-enqueue, but it does not depend
+// on the tile SIZES: the graph is built once with even tiles, the assignment is read off, and the
+// graph is built again with the weighted column tiles.  Eligible: linear operators of the vector
+// body (batch <= 4) with one row of tiles, no head alignment and no input split, every task
+// ahead-of-time.
+using TileWorkers = std::vector<std::vector<int32_t>>;   // [operator][tile] -> worker, empty = not eligible
+static void apply_worker_weights(const mpk_compile_options& o, const TileWorkers& tw, HostGraph& g) {
+  for (size_t oi = 0; oi < g.ops.size() && oi < tw.size(); ++oi) {
+    HostOp& op = g.ops[oi];
+    if (tw[oi].empty() || tw[oi].size() != op.tc) continue;
+    const uint32_t nu = op.cols / op.unit;
+    std::vector<double> wsum(op.tc + 1, 0.0);
+    for (uint32_t i = 0; i < op.tc; ++i) wsum[i + 1] = wsum[i] + (double)std::max(1u, o.worker_weight_permille[(uint32_t)tw[oi][i] & 7u]);
+    op.col_begin.assign(op.tc + 1, 0);
+    for (uint32_t i = 1; i < op.tc; ++i) {
+      uint32_t b = (uint32_t)std::llround((double)nu * wsum[i] / wsum[op.tc]);
+      b = std::max(b, op.col_begin[i - 1] + 1u);       // never an empty tile
+      b = std::min(b, nu - (op.tc - i));
+      op.col_begin[i] = b;
+    }
+    op.col_begin[op.tc] = nu;
+  }
+}
+
+static mpk_status build_model_graph_pass(const mpk_model_config& cfg, const mpk_weight_ptrs* w,
+                                         const mpk_kv_ptrs* kv, const mpk_compile_options& opt_in,
+                                         const TileWorkers* tile_workers, HostGraph& g);
+
 mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs* w,
                              const mpk_kv_ptrs* kv, const mpk_compile_options& opt_in,
                              HostGraph& g) {
+  mpk_status st = build_model_graph_pass(cfg, w, kv, opt_in, nullptr, g);
+  if (st != MPK_OK) return st;
+  bool weighted = false;
+  for (int k = 0; k < 8; ++k) weighted = weighted || (opt_in.worker_weight_permille[k] != 0 && opt_in.worker_weight_permille[k] != opt_in.worker_weight_permille[0]);
+  if (!weighted || cfg.batch > 4) return MPK_OK;
+  TileWorkers tw(g.ops.size());
+  for (size_t oi = 0; oi < g.ops.size(); ++oi) {
+    const HostOp& op = g.ops[oi];
+    if ((op.kind != MPK_OP_LINEAR && op.kind != MPK_OP_GATEUP) || op.seg_tiles || (op.flags & TF_SPLITK) || op.tb != 1 || op.tc < 2 || op.jit) continue;
+    // A task deals its rows to eight wavefronts in pairs: a tile of 8 pairs that grows to 9 doubles
+    // one wavefront's share (measured: the 16-row tiles of the 8B shape's O and down projections
+    // got 3 us slower).  Only tiles of at least four pairs per wavefront are resized.
+    if ((uint64_t)(op.cols / op.unit) * op.unit * ((op.flags & TF_GATEUP) ? 2u : 1u) / op.tc < 64u) continue;
+    tw[oi].assign(op.tc, -1);
+  }
+  for (const HostTask& t : g.tasks)
+    if (t.op != MPK_TASK_DUMMY_OP && !tw[t.op].empty()) tw[t.op][t.tile] = t.worker;
+  for (auto& v : tw)
+    if (std::find(v.begin(), v.end(), -1) != v.end()) v.clear();   // a task without a fixed worker: leave the operator alone
+  HostGraph g2;
+  st = build_model_graph_pass(cfg, w, kv, opt_in, &tw, g2);
+  if (st != MPK_OK) return st;
+  for (const HostTask& t : g2.tasks)   // the assignment the sizes were computed for must be the one that came out
+    if (t.op != MPK_TASK_DUMMY_OP && !tw[t.op].empty() && tw[t.op][t.tile] != t.worker) { set_error("worker assignment changed between the two compile passes"); return MPK_ERR_INTERNAL; }
+  g = std::move(g2);
+  return MPK_OK;
+}
+
+static mpk_status build_model_graph_pass(const mpk_model_config& cfg, const mpk_weight_ptrs* w,
+                                         const mpk_kv_ptrs* kv, const mpk_compile_options& opt_in,
+                                         const TileWorkers* tile_workers, HostGraph& g) {
   mpk_compile_options opt = opt_in;
   mpk_status st = validate(cfg, w, kv, opt);
   if (st != MPK_OK) return st;
@@ -1077,6 +1146,7 @@ mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs*
   st = build_ops(cfg, w, opt, C, g);
   if (st != MPK_OK) return st;
   choose_partitions(cfg, opt, g);
+  if (tile_workers) apply_worker_weights(opt, *tile_workers, g);
   g.n_group_counters_attn = cfg.n_layers * cfg.batch * cfg.n_kv_heads;
   g.n_group_counters = g.n_group_counters_attn + g.n_splitk_counters;
   g.inv_freq.resize(cfg.head_dim / 2);
@@ -1142,15 +1212,18 @@ mpk_status build_dag_graph(uint32_t n_tasks, const uint32_t* pairs, size_t n_pai
 
 // ------------------------------------------------------------------ export
 size_t export_size(const HostGraph& g) {
-  return sizeof(mpk_export_header) + g.ops.size() * sizeof(mpk_export_op) +
-         g.tasks.size() * sizeof(mpk_export_task) + g.events.size() * sizeof(mpk_export_event) +
-         (g.aot_off.size() + g.aot.size()) * sizeof(uint32_t);
+  size_t n = sizeof(mpk_export_header) + g.ops.size() * sizeof(mpk_export_op) +
+             g.tasks.size() * sizeof(mpk_export_task) + g.events.size() * sizeof(mpk_export_event) +
+             (g.aot_off.size() + g.aot.size()) * sizeof(uint32_t) + sizeof(uint32_t);
+  for (auto& op : g.ops)
+    if (!op.col_begin.empty()) n += (2 + op.col_begin.size()) * sizeof(uint32_t);
+  return n;
 }
 
 void export_graph(const HostGraph& g, void* buf) {
   char* p = (char*)buf;
   mpk_export_header h{};
-  h.magic = MPK_EXPORT_MAGIC; h.version = 1;
+  h.magic = MPK_EXPORT_MAGIC; h.version = 2;
   h.n_ops = (uint32_t)g.ops.size(); h.n_tasks = (uint32_t)g.tasks.size();
   h.n_events = (uint32_t)g.events.size(); h.n_workers = g.opt.n_workers;
   h.n_sched_wgs = g.opt.n_sched_wgs; h.start_event = g.start_event;
@@ -1169,7 +1242,19 @@ void export_graph(const HostGraph& g, void* buf) {
     memcpy(p, &e, sizeof(e)); p += sizeof(e);
   }
   memcpy(p, g.aot_off.data(), g.aot_off.size() * 4); p += g.aot_off.size() * 4;
-  memcpy(p, g.aot.data(), g.aot.size() * 4);
+  memcpy(p, g.aot.data(), g.aot.size() * 4); p += g.aot.size() * 4;
+  // operators with explicit column tiles: count, then per operator its index, the number of
+  // boundaries and the boundaries in columns
+  uint32_t n_explicit = 0;
+  for (auto& op : g.ops) n_explicit += op.col_begin.empty() ? 0u : 1u;
+  memcpy(p, &n_explicit, 4); p += 4;
+  for (size_t oi = 0; oi < g.ops.size(); ++oi) {
+    const HostOp& op = g.ops[oi];
+    if (op.col_begin.empty()) continue;
+    const uint32_t hdr[2] = {(uint32_t)oi, (uint32_t)op.col_begin.size()};
+    memcpy(p, hdr, 8); p += 8;
+    for (uint32_t b : op.col_begin) { const uint32_t c = b * op.unit; memcpy(p, &c, 4); p += 4; }
+  }
 }
 
 }  // namespace mpk

@@ -367,10 +367,14 @@ __device__ __forceinline__ LinGeom lin_geom(const TaskDesc& t, uint32_t wave) {
   g.gateup = (t.flags & TF_GATEUP) ? 1u : 0u;
   const uint32_t R = (t.c1 - t.c0) << g.gateup;
   constexpr uint32_t NW = kThreads / 64;
-  uint32_t rpw = (R + NW - 1u) / NW;
-  if (g.gateup) rpw = (rpw + 1u) & ~1u;   // a (gate, up) pair stays in one wavefront
-  g.r0 = min(wave * rpw, R);
-  g.r1 = min(g.r0 + rpw, R);
+  // rows are dealt in pairs (a half block holds two; a (gate, up) pair stays in one wavefront):
+  // every wavefront gets floor(pairs / 8) of them and the first pairs % 8 wavefronts one more, so
+  // that a tile of any size -- tiles sized by worker speed are seldom multiples of 16 rows --
+  // loads the wavefronts to within one pair of each other
+  const uint32_t P = (R + 1u) / 2u, base = P / NW, extra = P % NW;
+  const uint32_t p0 = wave * base + min(wave, extra), p1 = p0 + base + (wave < extra ? 1u : 0u);
+  g.r0 = min(2u * p0, R);
+  g.r1 = min(2u * p1, R);
   g.nseg = (t.K + kSegLen - 1u) / kSegLen;
   return g;
 }

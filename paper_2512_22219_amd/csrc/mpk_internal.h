@@ -108,6 +108,8 @@ struct HostOp {
   int data_in = -1, data_in2 = -1, data_out = -1, data_aux = -1;
   uint32_t align_unit = 0;     // linear: no tile straddles a multiple of this (head_dim) when non-zero
   uint32_t seg_tiles = 0;      // ... by a two-level split: segments of align_unit columns, this many tiles each
+  std::vector<uint32_t> col_begin;   // explicit column tiles (tc + 1 starts, in units) when not empty: tiles
+                                     // sized by the speed of the worker that runs them
   // parameters
   uint32_t K;
   uint16_t flags;

@@ -31,6 +31,25 @@ static const KernelVariant* pick_variant(uint32_t d, uint32_t grp, uint32_t batc
 // device address that call returns (static_scratch_base below).
 static __device__ __align__(256) unsigned char scratch[MPK_STATIC_SCRATCH_BYTES];
 
+// Streaming-speed calibration (option xcd_balance): every workgroup reads its own contiguous slab
+// of `slab16` 16-byte words with the access pattern of the linear bodies and records how long it
+// took (100 MHz wall clock).  The eight XCDs of the GPU do not stream equally fast.
+__global__ void __launch_bounds__(kThreads) stream_probe_kernel(const u32x4* src, size_t slab16, uint64_t* ticks, uint32_t* sink) {
+  const u32x4* p = src + (size_t)blockIdx.x * slab16;
+  const uint64_t t0 = wall_clock64();
+  u32x4 acc = {0, 0, 0, 0};
+  for (size_t i = threadIdx.x; i < slab16; i += (size_t)kThreads * 8) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = (i + (size_t)u * kThreads < slab16) ? ld_stream16(p + i + (size_t)u * kThreads) : u32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) sink[0] = acc.x;   // keeps the loads alive
+  __syncthreads();
+  if (threadIdx.x == 0) ticks[blockIdx.x] = wall_clock64() - t0;
+}
+
 // Fills n 32-bit words (counters to zero before a static step; NaN patterns for MPK_DEBUG_POISON).
 // A kernel, not a memset node: a caller may be capturing the stream.
 __global__ void __launch_bounds__(256) fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
@@ -158,6 +177,49 @@ static mpk_status resolve_options(const mpk_compile_options* in, mpk_compile_opt
   return MPK_OK;
 }
 
+// Relative streaming speed of the workers by index mod 8, in thousandths of their mean: the median
+// of five timed runs of the probe over `bytes` of weights (after one warm-up run).
+static mpk_status measure_worker_speeds(const void* weights, size_t bytes, uint32_t n_workers, uint32_t out[8]) {
+  const size_t slab16 = std::min<size_t>(bytes / n_workers, (size_t)8 << 20) / 16;
+  if (slab16 < 4096) { set_error("xcd_balance: the LM head is too small to time a streaming probe on"); return MPK_ERR_UNSUPPORTED; }
+  uint64_t* d_ticks = nullptr;
+  uint32_t* d_sink = nullptr;
+  if (hipMalloc((void**)&d_ticks, n_workers * sizeof(uint64_t)) != hipSuccess || hipMalloc((void**)&d_sink, 16) != hipSuccess) {
+    (void)hipFree(d_ticks);
+    set_error("hipMalloc failed for the streaming probe");
+    return MPK_ERR_OOM;
+  }
+  std::vector<uint64_t> t(n_workers);
+  std::vector<double> runs[8];
+  mpk_status st = MPK_OK;
+  for (int rep = 0; rep < 6 && st == MPK_OK; ++rep) {
+    hipLaunchKernelGGL(stream_probe_kernel, dim3(n_workers), dim3(kThreads), 0, 0, (const u32x4*)weights, slab16, d_ticks, d_sink);
+    if (hipDeviceSynchronize() != hipSuccess || hipMemcpy(t.data(), d_ticks, n_workers * sizeof(uint64_t), hipMemcpyDeviceToHost) != hipSuccess) {
+      set_error("streaming probe failed: %s", hipGetErrorString(hipGetLastError()));
+      st = MPK_ERR_HIP;
+      break;
+    }
+    if (rep == 0) continue;
+    double sum[8] = {0}, n[8] = {0};
+    for (uint32_t w = 0; w < n_workers; ++w) { sum[w & 7u] += (double)t[w]; n[w & 7u] += 1.0; }
+    for (int k = 0; k < 8; ++k) runs[k].push_back(n[k] > 0 ? sum[k] / n[k] : 0.0);
+  }
+  (void)hipFree(d_ticks);
+  (void)hipFree(d_sink);
+  if (st != MPK_OK) return st;
+  double speed[8], mean = 0.0;
+  int used = 0;
+  for (int k = 0; k < 8; ++k) {
+    std::sort(runs[k].begin(), runs[k].end());
+    const double med = runs[k][runs[k].size() / 2];
+    speed[k] = med > 0 ? 1.0 / med : 0.0;
+    if (speed[k] > 0) { mean += speed[k]; ++used; }
+  }
+  mean /= std::max(used, 1);
+  for (int k = 0; k < 8; ++k) out[k] = speed[k] > 0 ? (uint32_t)std::lround(1000.0 * speed[k] / mean) : 1000u;
+  return MPK_OK;
+}
+
 template <typename T>
 static mpk_status upload(T** dst, const std::vector<T>& src) {
   size_t bytes = std::max<size_t>(src.size(), 1) * sizeof(T);
@@ -193,6 +255,15 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
   if (!o.host_only && o.n_sched_wgs > 0 && !o.force_aot && o.launch_mode != MPK_LAUNCH_MEGA) {
     set_error("scheduler workgroups only exist in the persistent kernel (launch_mode MPK_LAUNCH_MEGA)");
     return MPK_ERR_INVALID_ARG;
+  }
+  if (o.xcd_balance) {
+    if (o.host_only) { set_error("xcd_balance measures on the GPU: not with host_only (set worker_weight_permille instead)"); return MPK_ERR_INVALID_ARG; }
+    bool given = false;
+    for (int k = 0; k < 8; ++k) given = given || o.worker_weight_permille[k] != 0;
+    if (!given && weights && weights->lm_head && cfg->batch <= 4) {
+      st = measure_worker_speeds(weights->lm_head, (size_t)cfg->vocab * cfg->hidden * 2, o.n_workers, o.worker_weight_permille);
+      if (st != MPK_OK) return st;
+    }
   }
   mpk_graph* g = new (std::nothrow) mpk_graph();
   if (!g) { set_error("out of host memory"); return MPK_ERR_OOM; }

@@ -83,7 +83,8 @@ def oracle_ops_and_degrees(shape, ex, fusion, attn_chunks):
     for o, eo in zip(ops, ex.ops):
         assert o.kind == eo["kind"] and o.layer == eo["layer"], (o.name, o.kind, eo["kind"])
         assert (o.rows, o.cols) == (eo["rows"], eo["cols"]), o.name
-    degrees = [(int(eo["tb"]), int(eo["tc"])) for eo in ex.ops]
+    degrees = [(int(eo["tb"]), int(eo["tc"])) + ((ex.col_begin[i].tolist(),) if i in ex.col_begin else ())
+               for i, eo in enumerate(ex.ops)]
     return ops, degrees
 
 

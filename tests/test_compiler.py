@@ -55,6 +55,10 @@ CASES = [
     # (the 8B shape with 240 tiles per linear operator)
     ("C5", dict(n_layers=1), dict(fusion=31)),
     ("C2", dict(n_layers=1), dict(fusion=31, tiles_linear=240)),
+    # column tiles sized by the speed of the worker that runs them (workers by index mod 8)
+    ("C1", dict(batch=2), dict(fusion=31, n_workers=24, worker_weight_permille=[1300, 700] * 4)),
+    ("C1", dict(batch=3), dict(fusion=0, n_workers=16, worker_weight_permille=[1300, 700, 1000, 1000] * 2)),
+    ("C2", dict(n_layers=2), dict(fusion=31, worker_weight_permille=[1047, 955] * 4)),
 ]
 
 
@@ -342,3 +346,34 @@ def test_moe_error_paths_and_graph_shape():
     gj = host_graph(G.small_variant("C1", batch=2, **moe), fusion=31, n_workers=12, n_sched_wgs=1)
     jit = {int(o["kind"]): int(o["jit"]) for o in gj.export().ops if o["layer"] == 0}
     assert jit[M.binding.OP_EXPERT] == 1 and jit[M.binding.OP_COMBINE] == 0 and jit[M.binding.OP_ROUTER] == 0
+
+
+def test_weighted_column_tiles_follow_the_worker_speeds():
+    """worker_weight_permille: a linear operator's column tiles are proportional to the speed of
+    the worker (index mod 8) that runs each of them; operators that are not eligible (the head-
+    aligned QKV projection) keep the even split; the weights [1000] * 8 change nothing."""
+    shape = G.small_variant("C2", n_layers=2)
+    even = host_graph(shape, fusion=31).export()
+    same = host_graph(shape, fusion=31, worker_weight_permille=[1000] * 8).export()
+    assert not even.col_begin and not same.col_begin
+    ex = host_graph(shape, fusion=31, worker_weight_permille=[1047, 955] * 4).export()
+    assert ex.header["version"] == 2 and ex.col_begin
+    worker_of = {(int(t["op"]), int(t["tile"])): int(t["worker"]) for t in ex.tasks if t["op"] != M.binding.TASK_DUMMY_OP}
+    seen_kinds = set()
+    for oi, op in enumerate(ex.ops):
+        if oi not in ex.col_begin:
+            continue
+        b = ex.col_begin[oi].astype(np.int64)
+        assert b[0] == 0 and b[-1] == op["cols"] and len(b) == op["tc"] + 1 and (np.diff(b) > 0).all()
+        size = np.diff(b)
+        fast = np.array([worker_of[(oi, i)] % 2 == 0 for i in range(int(op["tc"]))])
+        # sizes follow 1047 : 955 to within the rounding of a boundary (one column either way)
+        ideal = op["cols"] / op["tc"]
+        assert np.all(np.abs(size[fast] - ideal * 1.047 / 1.001) <= 1.01) and np.all(np.abs(size[~fast] - ideal * 0.955 / 1.001) <= 1.01)
+        seen_kinds.add(int(op["kind"]))
+    assert seen_kinds == {TG.K_LINEAR, TG.K_GATEUP}     # O, down, LM head; the fused gate/up projection
+    qkv = [oi for oi, op in enumerate(ex.ops) if op["kind"] == TG.K_LINEAR and op["cols"] == (shape.n_q_heads + 2 * shape.n_kv_heads) * shape.head_dim]
+    assert qkv and all(oi not in ex.col_begin for oi in qkv)
+    # batch > 4 runs the matrix-core body, whose tiles are made of 16-row blocks: left alone
+    big = host_graph(G.small_variant("C3", n_layers=1), fusion=31, worker_weight_permille=[1047, 955] * 4).export()
+    assert not big.col_begin

@@ -208,6 +208,32 @@ def test_col_bounds_hand_written_boundaries():
     assert own[1].tolist() == [6, 6, 6, 7, 7, 7, 8, 8, 9, 9, 9, 10, 10, 10, 11, 11]
 
 
+def test_explicit_column_boundaries_hand_written():
+    """A partition handed in instead of the even split (tiles sized by worker speed): the oracle
+    takes the boundaries as they are, refuses anything that is not a partition of the columns into
+    non-empty tiles, and the brute-force producer sets follow the uneven tiles.  Expected values
+    written out by hand."""
+    lin = TG.OpSpec("gate_up", TG.K_LINEAR, 0, "gu", 1, 10, 1, ["x"], {"K": 4})
+    assert TG.col_bounds(lin, 3, [0, 5, 7, 10]) == [0, 5, 7, 10]
+    assert TG.owner_map(lin, 1, 3, [0, 5, 7, 10])[0].tolist() == [0, 0, 0, 0, 0, 1, 1, 2, 2, 2]
+    assert TG.tile_bounds(lin, 1, 3, 1, [0, 5, 7, 10]) == (0, 1, 5, 7)
+    for bad in ([0, 5, 7], [1, 5, 7, 10], [0, 5, 5, 10], [0, 7, 5, 10], [0, 5, 7, 9]):
+        with pytest.raises(AssertionError):
+            TG.col_bounds(lin, 3, bad)
+    rope = TG.OpSpec("rope", TG.K_ROPE, 0, "q", 1, 12, 4, ["qkv"])
+    with pytest.raises(AssertionError):
+        TG.col_bounds(rope, 2, [0, 6, 12])            # not at a multiple of the unit
+    # a pointwise consumer cut 0..4 | 4..10 over a producer cut 0..5 | 5..7 | 7..10:
+    # its first tile overlaps producer tile 0 only, its second tile all three
+    src = TG.OpSpec("src", TG.K_EMBED, -1, "x", 1, 4, 4, [])
+    add = TG.OpSpec("add", TG.K_ADD, 0, "y", 1, 10, 1, ["gu", "gu"])
+    ps = TG.producer_sets([src, lin, add], [(1, 1), (1, 3, [0, 5, 7, 10]), (1, 2, [0, 4, 10])])
+    assert ps[2] == [[(1, 0)], [(1, 0), (1, 1), (1, 2)]]
+    # the same consumer over the even split 0..4 | 4..7 | 7..10 of the producer
+    ps = TG.producer_sets([src, lin, add], [(1, 1), (1, 3), (1, 2, [0, 4, 10])])
+    assert ps[2] == [[(1, 0)], [(1, 1), (1, 2)]]
+
+
 def test_argmax_read_set_hand_written():
     """Greedy sampling (one task per sequence) reads every logit of its own sequence and nothing
     else, so it depends on every LM-head tile that holds a column of that row (Section 4.1's
