@@ -158,6 +158,13 @@ typedef struct mpk_compile_options {
                                slowest task).  Batch <= 4, operators with one tile per row block
                                and at least 64 weight rows per tile, all tasks ahead-of-time; the
                                exported graph lists the boundaries                              */
+  uint32_t no_lds_pages;    /* 1 = no pre-load pages in LDS.  By default, at batch 1 without
+                               scheduler workgroups, a worker that has a long wait ahead (the O
+                               projection behind the attention tasks) requests the first 16 KB
+                               per wavefront of the task AFTER that one into LDS pages while it
+                               waits (Section 5.3: pre-loading into shared-memory pages across
+                               tasks); that task's tile is made correspondingly larger than the
+                               tiles of workers that could not pre-load (they ran attention)    */
   uint32_t xcd_balance;     /* 1 = measure those speeds on this GPU at compile time (a streaming
                                kernel over the LM-head weights, about a millisecond) when
                                worker_weight_permille is all 0.  Not with host_only              */

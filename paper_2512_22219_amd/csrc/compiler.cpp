@@ -1087,18 +1087,103 @@ static void apply_worker_weights(const mpk_compile_options& o, const TileWorkers
   }
 }
 
+// LDS floats a batch-1 linear task of this operator needs below the page area.
+static size_t lin_task_floats_b1(const HostGraph& g, const HostOp& op) {
+  return (size_t)((op.K + 4095u) / 4096u * 4096u) + 2 * (size_t)g.lin_rows_max + 8;
+}
+static bool page_capable(const mpk_model_config& c, const mpk_compile_options& o) {
+  return c.batch == 1 && !o.no_lds_pages && !o.no_preload && o.n_sched_wgs == 0 && o.launch_mode == MPK_LAUNCH_MEGA && true;
+}
+
+// Which tasks get their first half blocks pre-loaded into the LDS pages by the task before them in
+// their worker's list (Section 5.3, pre-loading across tasks).  A pair (T, N) of consecutive linear
+// tasks of one worker qualifies when T comes right after another linear task (so the worker is not
+// one that just ran an attention task: it has the whole attention phase to wait through), T and N
+// both leave room for the pages in LDS, and N is long enough to gain (more than two half blocks
+// per wavefront).  Returns, per task of the linearized list, 0, TF_PAGE_NEXT or TF_PAGE_READY.
+static std::vector<uint16_t> page_plan(const mpk_model_config& c, const mpk_compile_options& o, const HostGraph& g) {
+  std::vector<uint16_t> plan(g.tasks.size(), 0);
+  if (!page_capable(c, o)) return plan;
+  const size_t room = (160 * 1024) / sizeof(float) - kLdsReduceFloats - 16 - kLinPagesFloats;
+  auto lin_op = [&](uint32_t ti) -> const HostOp* {
+    const HostTask& t = g.tasks[ti];
+    if (t.op == MPK_TASK_DUMMY_OP || t.jit) return nullptr;
+    const HostOp& op = g.ops[t.op];
+    return (op.kind == MPK_OP_LINEAR || op.kind == MPK_OP_GATEUP) ? &op : nullptr;
+  };
+  for (uint32_t w = 0; w + 1 < g.aot_off.size(); ++w) {
+    for (uint32_t qi = g.aot_off[w] + 1; qi + 1 < g.aot_off[w + 1]; ++qi) {
+      const HostOp *prev = lin_op(g.aot[qi - 1]), *cur = lin_op(g.aot[qi]), *next = lin_op(g.aot[qi + 1]);
+      if (!prev || !cur || !next) continue;
+      if (prev->layer != cur->layer || cur->layer != next->layer || cur->layer < 0) continue;
+      // T is short (fits its two register buffers: nothing of its own left to stream while it waits)
+      const uint64_t cur_rows = (uint64_t)cur->cols * ((cur->flags & TF_GATEUP) ? 2u : 1u) / cur->tc;
+      const uint64_t next_rows = (uint64_t)next->cols * ((next->flags & TF_GATEUP) ? 2u : 1u) / next->tc;
+      if (cur_rows * cur->K * 2 > 256 * 1024) continue;
+      if (next->K > 4096 || next_rows < 48 || (next->flags & TF_SPLITK) || next->seg_tiles) continue;
+      if (lin_task_floats_b1(g, *cur) > room || lin_task_floats_b1(g, *next) > room) continue;
+      plan[g.aot[qi]] |= TF_PAGE_NEXT;
+      plan[g.aot[qi + 1]] |= TF_PAGE_READY;
+    }
+  }
+  return plan;
+}
+
+// Column tiles of the operators whose tasks are partly pre-loaded into LDS pages: a task with its
+// first kLinPageUnits weight rows already on the chip when its event fires gets that many more
+// rows than a task without, so that both have the same amount left to stream.
+static void apply_page_sizes(const std::vector<std::vector<uint8_t>>& ready, HostGraph& g) {
+  for (size_t oi = 0; oi < g.ops.size() && oi < ready.size(); ++oi) {
+    HostOp& op = g.ops[oi];
+    if (ready[oi].empty() || ready[oi].size() != op.tc || !op.col_begin.empty()) continue;
+    const uint32_t n_ready = (uint32_t)std::count(ready[oi].begin(), ready[oi].end(), (uint8_t)1);
+    if (n_ready == 0 || n_ready == op.tc) continue;          // all alike: the even split is right
+    const uint32_t nu = op.cols / op.unit;
+    const uint32_t bonus = kLinPageUnits / ((op.flags & TF_GATEUP) ? 2u : 1u) / std::max(1u, op.unit);
+    const uint64_t total = (uint64_t)nu + (uint64_t)bonus * (op.tc - n_ready);
+    const uint32_t x = (uint32_t)(total / op.tc);            // size of a pre-loaded tile
+    if (x <= bonus + 8) continue;
+    uint32_t rem = (uint32_t)(total % op.tc);                 // left-over units: one more for the first tiles
+    op.col_begin.assign(op.tc + 1, 0);
+    for (uint32_t i = 0; i < op.tc; ++i) {
+      uint32_t sz = ready[oi][i] ? x : x - bonus;
+      if (rem) { ++sz; --rem; }
+      op.col_begin[i + 1] = std::min(nu, op.col_begin[i] + sz);
+    }
+    op.col_begin[op.tc] = nu;
+  }
+}
+
+struct SecondPass {
+  const TileWorkers* tile_workers = nullptr;
+  const std::vector<std::vector<uint8_t>>* page_ready = nullptr;   // [operator][tile]
+};
 static mpk_status build_model_graph_pass(const mpk_model_config& cfg, const mpk_weight_ptrs* w,
                                          const mpk_kv_ptrs* kv, const mpk_compile_options& opt_in,
-                                         const TileWorkers* tile_workers, HostGraph& g);
+                                         const SecondPass& sp, HostGraph& g);
 
 mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs* w,
                              const mpk_kv_ptrs* kv, const mpk_compile_options& opt_in,
                              HostGraph& g) {
-  mpk_status st = build_model_graph_pass(cfg, w, kv, opt_in, nullptr, g);
+  mpk_status st = build_model_graph_pass(cfg, w, kv, opt_in, SecondPass{}, g);
   if (st != MPK_OK) return st;
   bool weighted = false;
   for (int k = 0; k < 8; ++k) weighted = weighted || (opt_in.worker_weight_permille[k] != 0 && opt_in.worker_weight_permille[k] != opt_in.worker_weight_permille[0]);
-  if (!weighted || cfg.batch > 4) return MPK_OK;
+  weighted = weighted && cfg.batch <= 4;
+  // tiles that will find their first rows in the LDS pages
+  std::vector<std::vector<uint8_t>> ready(g.ops.size());
+  bool paged = false;
+  {
+    const std::vector<uint16_t> plan = page_plan(cfg, g.opt, g);
+    for (size_t i = 0; i < g.tasks.size(); ++i) {
+      if (!(plan[i] & TF_PAGE_READY)) continue;
+      const HostTask& t = g.tasks[i];
+      if (ready[t.op].empty()) ready[t.op].assign(g.ops[t.op].tc, 0);
+      ready[t.op][t.tile] = 1;
+      paged = true;
+    }
+  }
+  if (!weighted && !paged) return MPK_OK;
   TileWorkers tw(g.ops.size());
   for (size_t oi = 0; oi < g.ops.size(); ++oi) {
     const HostOp& op = g.ops[oi];
@@ -1107,24 +1192,31 @@ mpk_status build_model_graph(const mpk_model_config& cfg, const mpk_weight_ptrs*
     // one wavefront's share (measured: the 16-row tiles of the 8B shape's O and down projections
     // got 3 us slower).  Only tiles of at least four pairs per wavefront are resized.
     if ((uint64_t)(op.cols / op.unit) * op.unit * ((op.flags & TF_GATEUP) ? 2u : 1u) / op.tc < 64u) continue;
-    tw[oi].assign(op.tc, -1);
+    if (weighted && ready[oi].empty()) tw[oi].assign(op.tc, -1);
   }
   for (const HostTask& t : g.tasks)
     if (t.op != MPK_TASK_DUMMY_OP && !tw[t.op].empty()) tw[t.op][t.tile] = t.worker;
   for (auto& v : tw)
     if (std::find(v.begin(), v.end(), -1) != v.end()) v.clear();   // a task without a fixed worker: leave the operator alone
   HostGraph g2;
-  st = build_model_graph_pass(cfg, w, kv, opt_in, &tw, g2);
+  SecondPass sp;
+  sp.tile_workers = &tw;
+  sp.page_ready = &ready;
+  st = build_model_graph_pass(cfg, w, kv, opt_in, sp, g2);
   if (st != MPK_OK) return st;
-  for (const HostTask& t : g2.tasks)   // the assignment the sizes were computed for must be the one that came out
-    if (t.op != MPK_TASK_DUMMY_OP && !tw[t.op].empty() && tw[t.op][t.tile] != t.worker) { set_error("worker assignment changed between the two compile passes"); return MPK_ERR_INTERNAL; }
+  if (g2.tasks.size() != g.tasks.size()) { set_error("task list changed between the two compile passes"); return MPK_ERR_INTERNAL; }
+  for (size_t i = 0; i < g.tasks.size(); ++i)   // the assignment the sizes were computed for must be the one that came out
+    if (g.tasks[i].op != g2.tasks[i].op || g.tasks[i].tile != g2.tasks[i].tile || g.tasks[i].worker != g2.tasks[i].worker) {
+      set_error("worker assignment changed between the two compile passes");
+      return MPK_ERR_INTERNAL;
+    }
   g = std::move(g2);
   return MPK_OK;
 }
 
 static mpk_status build_model_graph_pass(const mpk_model_config& cfg, const mpk_weight_ptrs* w,
                                          const mpk_kv_ptrs* kv, const mpk_compile_options& opt_in,
-                                         const TileWorkers* tile_workers, HostGraph& g) {
+                                         const SecondPass& sp, HostGraph& g) {
   mpk_compile_options opt = opt_in;
   mpk_status st = validate(cfg, w, kv, opt);
   if (st != MPK_OK) return st;
@@ -1146,7 +1238,8 @@ static mpk_status build_model_graph_pass(const mpk_model_config& cfg, const mpk_
   st = build_ops(cfg, w, opt, C, g);
   if (st != MPK_OK) return st;
   choose_partitions(cfg, opt, g);
-  if (tile_workers) apply_worker_weights(opt, *tile_workers, g);
+  if (sp.page_ready) apply_page_sizes(*sp.page_ready, g);
+  if (sp.tile_workers) apply_worker_weights(opt, *sp.tile_workers, g);
   g.n_group_counters_attn = cfg.n_layers * cfg.batch * cfg.n_kv_heads;
   g.n_group_counters = g.n_group_counters_attn + g.n_splitk_counters;
   g.inv_freq.resize(cfg.head_dim / 2);
@@ -1162,6 +1255,19 @@ static mpk_status build_model_graph_pass(const mpk_model_config& cfg, const mpk_
   g.stats.n_pair_deps += g.stats.n_pairs_removed;
   build_descs(cfg, kv, g);
   g.lds_bytes = lds_requirement(cfg, g, C);
+  if (sp.page_ready) {   // (second pass: the tile sizes already account for the pages)
+    const std::vector<uint16_t> plan = page_plan(cfg, opt, g);
+    bool any = false;
+    for (size_t i = 0; i < g.tasks.size(); ++i) {
+      g.descs[i].flags |= plan[i];
+      any = any || plan[i];
+      if ((plan[i] & TF_PAGE_READY) && !(*sp.page_ready)[g.tasks[i].op][g.tasks[i].tile]) { set_error("page plan changed between the two compile passes"); return MPK_ERR_INTERNAL; }
+    }
+    if (any) {   // the pages sit at the top of the 160 KB
+      g.lin_page_off = (uint32_t)((160 * 1024) / sizeof(float) - kLdsReduceFloats - 16 - kLinPagesFloats);
+      g.lds_bytes = 160 * 1024;
+    }
+  }
   if (cfg.batch > 4 && g.lin_rows_max > 512) { set_error("a linear task would own %u weight rows; the batch >= 5 body handles at most 512: raise tiles_linear / tiles_lm_head", g.lin_rows_max); return MPK_ERR_UNSUPPORTED; }
   if (g.lds_bytes > 160 * 1024 && !opt.host_only) { set_error("task bodies need %u bytes of LDS (> 160 KB): batch x input length too large", g.lds_bytes); return MPK_ERR_UNSUPPORTED; }
   // statistics

@@ -56,6 +56,7 @@ struct GraphConst {
   uint32_t vocab, max_seq, n_q, n_kv, head_dim, batch;
   uint32_t lin_rows_max;     // largest number of weight rows (gate/up pairs count twice) of a linear task
   uint32_t lin_res_rows_max; // largest number of columns of a linear task that adds a residual
+  uint32_t lin_page_off;     // float offset of the LDS pre-load pages in the task area (0: none)
   // just-in-time launch (Section 5.2): scheduler event queues and worker task queues.  Entries
   // are 64-bit (ticket + 1) << 32 | id with tickets that only grow, so a slot is valid exactly
   // when it carries the ticket its reader expects; tails sit on their own 256-byte lines.
@@ -447,6 +448,35 @@ __device__ __forceinline__ void lin_consume(const LinHalf& B, const HalfRing& ri
   }
 }
 
+// LDS pre-load pages (paper Section 5.3: data of a task that has not started yet is pre-loaded into
+// shared-memory pages).  One page per wavefront holds one half block in the layout of a HalfRing:
+// [row 0..1][stage 0..7][lane] x 16 bytes.  The loads go from device memory straight into LDS (no
+// registers), so a page can be filled by one task and consumed by the worker's next one.
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+__device__ __forceinline__ void lin_request_page(const LinHalf& B, u32x4* page, int lane) {
+#pragma unroll
+  for (int u = 0; u < kRingStages; ++u) {
+    const uint32_t o = min((uint32_t)u * 512u + (uint32_t)lane * 8u, B.seglen - 8u);
+#pragma unroll
+    for (int i = 0; i < kHalfRows; ++i)
+      __builtin_amdgcn_global_load_lds(as_global((const u32x4*)(B.p[i] + o)), (lds_ptr_t)(page + (i * kRingStages + u) * 64), 16, 0, 0);
+  }
+}
+template <int NB>
+__device__ __forceinline__ void lin_consume_page(const LinHalf& B, const u32x4* page, const float* xs, uint32_t Kp,
+                                                 int lane, float (&acc)[kHalfRows][NB]) {
+#pragma unroll
+  for (int u = 0; u < kRingStages; ++u) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const float4* xp = (const float4*)(xs + (size_t)b * Kp + B.seg * kSegLen + u * 512 + lane * 8);
+      const float4 x0 = xp[0], x1 = xp[1];
+#pragma unroll
+      for (int i = 0; i < kHalfRows; ++i) acc[i][b] = dot8(page[(i * kRingStages + u) * 64 + lane], x0, x1, acc[i][b]);
+    }
+  }
+}
+
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() carries a release fence, for
 // which the compiler drains the vector-memory queue (s_waitcnt vmcnt(0)): with a pre-load of
 // the next task in flight that would stall every wavefront, and the event notification behind
@@ -497,10 +527,14 @@ __device__ __forceinline__ uint32_t linear_wait(const StepArgs& a, int32_t wait_
 // the step is still alive (false: watchdog / abort).
 template <int NB, bool MEGA, class Svc = NoJit, bool DEEP = false>
 __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
-                                                uint32_t* s_flag, const Svc& svc = Svc{}) {
+                                                uint32_t* s_flag, const Svc& svc = Svc{}, uint32_t next_ti = 0) {
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: geometry stays scalar
   const uint32_t K = t.K, nb = t.b1 - t.b0, ncols = t.c1 - t.c0;
+  // pages exist only in the all-ahead-of-time persistent kernel at batch 1 (the compiler sets the flags)
+  constexpr bool kPages = MEGA && NB == 1 && !Svc::enabled;
+  u32x4* page = (u32x4*)(lds + a.g->lin_page_off) + (size_t)wave * (kLinPageFloats / 4);
+  const bool page_ready = kPages && (t.flags & TF_PAGE_READY), page_next = kPages && (t.flags & TF_PAGE_NEXT);
   const uint32_t Kp = (K + kSegLen - 1u) / kSegLen * kSegLen;
   const uint32_t rows_max = a.g->lin_rows_max;
   float* xs = lds;                                   // [NB][Kp]
@@ -512,6 +546,7 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
   ring_clear(h0);
   ring_clear(h1);
   LinCursor rq{g.r0, 0u};   // next half block to request
+  if (page_ready && lin_valid(g, rq)) lin_advance(g, rq);   // the first one is in this wavefront's page already
   // (every request site ends in an (empty) assembly statement of its own: otherwise the compiler
   // may merge the identical last loads of two sites into one whose destination is chosen at run
   // time, and a buffer addressed that way is moved from registers to scratch memory)
@@ -553,6 +588,14 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
       gpre[u] = 0;
       if ((t.flags & TF_PRO_NORM) && i < K / 2) gpre[u] = *as_global((const uint32_t*)(gain0 + 2 * i));
     }
+  }
+  if (page_next) {
+    // this task is short and has a long wait ahead: the first half block of every wavefront's
+    // share of the worker's NEXT task goes into the pages now, two tasks ahead of its use
+    const TaskDesc tn = ld_task(a, next_ti);
+    const LinGeom gn = lin_geom(tn, wave);
+    const LinCursor cn{gn.r0, 0u};
+    if (lin_valid(gn, cn)) lin_request_page(lin_half(gn, cn), page, lane);
   }
   // ---- dependent event: wavefront 0 polls, the others wait at the barrier
   if (wait_ev >= 0) {
@@ -659,6 +702,12 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
       }
     };
     LinCursor cs{g.r0, 0u};
+    if (page_ready && lin_valid(g, cs)) {   // (requested a whole task ago: long since landed)
+      const LinHalf B = lin_half(g, cs);
+      lin_consume_page<NB>(B, page, xs, Kp, lane, acc);
+      finish(B);
+      lin_advance(g, cs);
+    }
     while (lin_valid(g, cs)) {
       {
         const LinHalf B = lin_half(g, cs);
@@ -2179,12 +2228,12 @@ __device__ __forceinline__ void body_argmax(const TaskDesc& t, const StepArgs& a
 // Batch class -> body instance (NB = 0: decided at run time).
 template <int NB, bool MEGA, class Svc = NoJit>
 __device__ __forceinline__ uint32_t run_linear(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev,
-                                           uint32_t* s_flag, const Svc& svc = Svc{}) {
+                                           uint32_t* s_flag, const Svc& svc = Svc{}, uint32_t next_ti = 0) {
   if (NB == 8) return linear_task_mfma<MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);   // batch class 5..16: matrix cores
-  if (NB == 9) return linear_task<1, MEGA, Svc, true>(t, a, lds, wait_ev, s_flag, svc);   // batch 1, large tasks: three buffers
-  if (NB != 0) return linear_task<(NB ? NB : 1), MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
+  if (NB == 9) return linear_task<1, MEGA, Svc, true>(t, a, lds, wait_ev, s_flag, svc, next_ti);   // batch 1, large tasks: three buffers
+  if (NB != 0) return linear_task<(NB ? NB : 1), MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc, next_ti);
   const uint32_t nb = t.b1 - t.b0;
-  if (nb == 1) return linear_task<1, MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
+  if (nb == 1) return linear_task<1, MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc, next_ti);
   if (nb == 2) return linear_task<2, MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
   if (nb <= 4) return linear_task<4, MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
   return linear_task_mfma<MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
@@ -2595,7 +2644,9 @@ __device__ __forceinline__ bool aot_pass(const StepArgs& a, uint32_t q0, uint32_
       const int32_t wait_ev = (t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
       trace_mark(a, t, 0);
       if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + 5] = blockIdx.x;
-      if (!run_linear<NB, true>(t, a, lds, wait_ev, s_flag)) return false;
+      // (the next task of this worker: a flagged task pre-loads its first half blocks into LDS pages)
+      const uint32_t next_ti = qi + 1 < q1 ? ld_u32c(a.g->aot + qi + 1) : 0u;
+      if (!run_linear<NB, true>(t, a, lds, wait_ev, s_flag, NoJit{}, next_ti)) return false;
     } else {
       // the callee's result comes back in a vector register: make it scalar again, or the whole
       // task loop (and every descriptor load in it) turns into per-lane code

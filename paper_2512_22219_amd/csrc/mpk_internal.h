@@ -42,6 +42,10 @@ enum TaskFlags : uint16_t {
   TF_JIT = 128,       // launched just-in-time: a scheduler hands it to a worker when its event fires
   TF_QK_NORM = 512,   // rope / attention with fused rope: RMSNorm over head_dim of every q head (gain w)
                       // and k head (gain w2), eps f0, before the rotation
+  TF_PAGE_READY = 1024,  // linear (batch 1): this task's first half block per wavefront sits in the LDS page
+                         // area, requested there by the worker's previous task
+  TF_PAGE_NEXT = 2048,   // linear (batch 1): after its own requests, and before it waits for its event, the
+                         // task requests the first half blocks of the worker's NEXT task into the LDS pages
   TF_SPLITK = 256,    // linear (batch > 4): the task owns rows x ONE of `parts` input ranges; it writes
                       // partial sums, and the task of a row block that arrives last (counter p2)
                       // adds the parts in order plus the residual into the real output (aux0).
@@ -149,6 +153,7 @@ struct HostGraph {
   uint32_t n_hier_events = 0;
   uint32_t lin_rows_max = 0;       // largest weight-row count of one linear task (gate/up pairs twice)
   uint32_t lin_res_rows_max = 0;   // largest column count of a linear task with a residual epilogue
+  uint32_t lin_page_off = 0;       // float offset (in the task area of the LDS) of the pre-load pages, 0 = none
   std::vector<size_t> moe_meta_offset;   // per MoE layer: float offset of its meta-tensor in the arena
   std::vector<double> inv_freq;    // RoPE frequencies theta^(-2i/d), i < d/2
   mpk_stats stats{};
@@ -197,5 +202,9 @@ constexpr uint32_t moe_x_floats(uint32_t batch) {
 constexpr uint32_t kThreads = 512;        // worker workgroup size (8 wavefronts, two per SIMD)
 constexpr uint32_t kLdsReduceFloats = 1024;  // scratch for cross-wave reductions
 constexpr uint32_t kMinLdsBytes = 84 * 1024; // > half of 160 KB: at most one worker per CU
+// Pre-load pages in LDS (paper Section 5.3: shared-memory pages hold data pre-loaded for a task that
+// has not started): one page of 16 KB per wavefront = one half block of the vector linear body.
+constexpr uint32_t kLinPageFloats = 4096, kLinPagesFloats = 8 * kLinPageFloats;
+constexpr uint32_t kLinPageUnits = 16;   // weight rows one set of pages holds: 8 wavefronts x 2 rows
 
 }  // namespace mpk

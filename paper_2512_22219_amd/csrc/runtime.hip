@@ -378,7 +378,7 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
     c.n_workers = h.opt.n_workers;
     c.vocab = h.cfg.vocab; c.max_seq = h.cfg.max_seq; c.n_q = h.cfg.n_q_heads;
     c.n_kv = h.cfg.n_kv_heads; c.head_dim = h.cfg.head_dim; c.batch = h.cfg.batch;
-    c.lin_rows_max = h.lin_rows_max; c.lin_res_rows_max = h.lin_res_rows_max;
+    c.lin_rows_max = h.lin_rows_max; c.lin_res_rows_max = h.lin_res_rows_max; c.lin_page_off = h.lin_page_off;
     c.n_sched = g->n_sched; c.evq_cap = g->evq_cap; c.wq_cap = g->wq_cap;
     c.evq_buf = g->d_evq_buf; c.evq_tail = g->d_evq_tail; c.sched_state = g->d_sched_state;
     c.sched_nev = g->d_sched_nev; c.wq_buf = g->d_wq_buf; c.wq_tail = g->d_wq_tail; c.wq_head = g->d_wq_head;

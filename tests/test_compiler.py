@@ -377,3 +377,34 @@ def test_weighted_column_tiles_follow_the_worker_speeds():
     # batch > 4 runs the matrix-core body, whose tiles are made of 16-row blocks: left alone
     big = host_graph(G.small_variant("C3", n_layers=1), fusion=31, worker_weight_permille=[1047, 955] * 4).export()
     assert not big.col_begin
+
+
+def test_lds_page_preload_makes_the_preloaded_tiles_larger():
+    """Batch 1, all ahead-of-time: a worker that runs a QKV task and then waits through the
+    attention phase pre-loads the first 16 weight rows per compute unit of its gate/up task into
+    LDS pages; the gate/up tiles of those workers are 8 columns (16 rows) larger than the tiles of
+    the workers that ran attention, so that all have the same amount left to stream.  8B shape:
+    192 tiles of 50 columns and 64 of 42; switched off, the split is even again.  (Pages need the worker's tasks back to back, i.e. the graph
+    without fork/join dummies that transitive reduction gives; its closures are compared with the
+    oracle's, over these uneven tiles, in test_transitive_reduction_keeps_closures.)"""
+    shape = G.small_variant("C2", n_layers=2)
+    g = host_graph(shape, fusion=31, transitive_reduction=1)
+    ex = g.export()
+    gateup = [oi for oi, op in enumerate(ex.ops) if op["kind"] == TG.K_GATEUP]
+    assert gateup and all(oi in ex.col_begin for oi in gateup) and len(ex.col_begin) == len(gateup)
+    worker_of = {(int(t["op"]), int(t["tile"])): int(t["worker"]) for t in ex.tasks if t["op"] != M.binding.TASK_DUMMY_OP}
+    attn_workers = {worker_of[(oi, i)] for oi, op in enumerate(ex.ops) if op["kind"] == TG.K_ATTN_PARTIAL
+                    for i in range(int(op["n_tasks"]))}
+    assert len(attn_workers) == 64
+    for oi in gateup:
+        size = np.diff(ex.col_begin[oi].astype(np.int64))
+        ran_attention = np.array([worker_of[(oi, i)] in attn_workers for i in range(len(size))])
+        assert set(size[~ran_attention]) == {50} and set(size[ran_attention]) == {42}
+        assert size.sum() == shape.ffn
+    assert g.stats()["lds_bytes"] == 160 * 1024
+    off = host_graph(shape, fusion=31, transitive_reduction=1, no_lds_pages=1)
+    assert not off.export().col_begin and off.stats()["lds_bytes"] < 160 * 1024
+    # nothing of it with scheduler workgroups, per-operator launches, batch > 1 or pre-loading off
+    for kw in (dict(n_sched_wgs=1), dict(launch_mode=1), dict(no_preload=1)):
+        assert not host_graph(shape, fusion=31, transitive_reduction=1, **kw).export().col_begin
+    assert not host_graph(G.small_variant("C2", n_layers=2, batch=2), fusion=31, transitive_reduction=1).export().col_begin
