@@ -1003,7 +1003,7 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
       } else {
         // matrix-core body: two buffers of three bf16 planes of one input tile (reused for the
         // per-wavefront partial tiles) | residual slice | sums of squares | 1/rms per row
-        f = (size_t)mfma_x_floats(c.batch) + (size_t)res_rows * 16 + 9 * 16;
+        f = (size_t)mfma_x_floats(c.batch) + (size_t)res_rows * 16 + 10 * 16;   // ... | split-K arrival flag
       }
     }
     else if (op.kind == MPK_OP_EXPERT) {

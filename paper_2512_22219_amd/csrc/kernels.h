@@ -837,7 +837,17 @@ __device__ __forceinline__ void split_hi_mid_lo(float x, float y, uint32_t* hi, 
   *lo = pack_bf16_rne(rx - bf16_lo(m), ry - bf16_hi(m));
 }
 
-constexpr int kMfmaRound = 16;   // weight fragments (32 inputs x 16 rows, 1 KB) a wavefront requests at a time
+#ifndef MPK_MFMA_ROUND
+#define MPK_MFMA_ROUND 16
+#endif
+constexpr int kMfmaRound = MPK_MFMA_ROUND;   // weight fragments (32 inputs x 16 rows, 1 KB) a wavefront requests at a time
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
 
 // Geometry of one matrix-core job: K inputs x nb staged rows x nrt 16-row weight tiles.  Uniform
 // over the wavefront (wave comes from readfirstlane).
@@ -886,10 +896,15 @@ __device__ __forceinline__ MfmaGeom mfma_geom(uint32_t K, uint32_t nb, uint32_t 
 // LDS: x [buffers][3 planes][nb][xstride] bf16 at `lds`, reused at the end for the per-wavefront
 // partial tiles part[8][4][16][16] f32; ssq [8][16] f32 (sums of squares per wavefront and row, when
 // pro_norm).  On return (kLinDone) every thread may read part and ssq.
-template <class RowPtr, class SrcRow, class Wait>
-__device__ __forceinline__ uint32_t mfma_job(const StepArgs& a, const TaskDesc& t, float* lds, float* ssq, const MfmaGeom& G,
-                                             RowPtr row_ptr, SrcRow src_row, bool pro_norm, const uint16_t* gain,
-                                             Wait wait_fn) {
+// PACK: how many of the three planes one multiply covers.  The multiply has 16 batch columns; up
+// to 8 staged rows leave half of them free, so columns 0..7 take the hi plane and columns 8..15
+// the mid plane of the same rows (PACK 2: two multiplies per fragment, the lo plane alone in the
+// second, on accumulators of its own); up to 4 staged rows take hi | mid | lo in columns 0..3 |
+// 4..7 | 8..11 (PACK 3: one multiply).  The column groups are added up once, at the end.
+template <int PACK, class RowPtr, class SrcRow, class Wait>
+__device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const TaskDesc& t, float* lds, float* ssq, const MfmaGeom& G,
+                                                    RowPtr row_ptr, SrcRow src_row, bool pro_norm, const uint16_t* gain,
+                                                    Wait wait_fn) {
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t K = G.K, nb = G.nb, nrt = G.nrt, Kt1 = G.Kt1, Kt = G.Kt, ntile = G.ntile;
@@ -898,9 +913,9 @@ __device__ __forceinline__ uint32_t mfma_job(const StepArgs& a, const TaskDesc& 
   float* part = lds;
   const uint32_t frow = lane & 15u, fk = (uint32_t)(lane >> 4) * 8u;
   const uint32_t kclamp = K - fk - 8u;   // the last fragment start that stays inside the row
-  f32x4 acc[4];
+  f32x4 acc[4], acc_lo[4];   // (acc_lo: the lo plane's products when PACK == 2)
 #pragma unroll
-  for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int j = 0; j < 4; ++j) acc[j] = acc_lo[j] = f32x4{0.f, 0.f, 0.f, 0.f};
   u32x4 wfrag[kMfmaRound];
   const uint32_t s_lo = G.my_slice * G.slice_len;
   // a round of a long slice (nf >= 16): 16 consecutive fragments of one (input tile, row tile)
@@ -987,34 +1002,39 @@ __device__ __forceinline__ uint32_t mfma_job(const StepArgs& a, const TaskDesc& 
   trace_mark(a, t, 2);
   // four fragments of the round (positions q0 .. q0 + 3) against the three planes, inputs
   // kk .. kk + 127 of the current tile; whole groups run without per-step tests, their LDS reads
-  // ahead of the multiplies
-  auto consume4 = [&](f32x4& c, const uint16_t* bx, auto q0c, uint32_t kk, uint32_t s_hi) {
+  // ahead of the multiplies.  b0 / b1 / b2: this lane's operand address for the first, second and
+  // third multiply of a fragment (PACK 1: hi, mid, lo of its column's row; PACK 2: hi or mid by
+  // column half, then lo; PACK 3: the plane of its column group).
+  constexpr int kMul = PACK == 1 ? 3 : (PACK == 2 ? 2 : 1);
+  auto consume4 = [&](f32x4& c, f32x4& c_lo, const uint16_t* b0, const uint16_t* b1, const uint16_t* b2, auto q0c, uint32_t kk, uint32_t s_hi) {
     constexpr int q0 = decltype(q0c)::value;
+    auto mul = [&](const u32x4& w, const u32x4& x0, const u32x4& x1, const u32x4& x2) {
+      const bf16x8 av = __builtin_bit_cast(bf16x8, w);
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0), c, 0, 0, 0);
+      if (kMul == 2) c_lo = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1), c_lo, 0, 0, 0);
+      if (kMul == 3) {
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x2), c, 0, 0, 0);
+      }
+    };
     if (kk + 128u <= s_hi) {
-      u32x4 hv[4], mv[4], lv[4];
+      u32x4 x0[4], x1[4], x2[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        hv[u] = *(const u32x4*)(bx + kk + u * 32u);
-        mv[u] = *(const u32x4*)(bx + xplane + kk + u * 32u);
-        lv[u] = *(const u32x4*)(bx + 2u * xplane + kk + u * 32u);
+        x0[u] = *(const u32x4*)(b0 + kk + u * 32u);
+        if (kMul >= 2) x1[u] = *(const u32x4*)(b1 + kk + u * 32u);
+        if (kMul >= 3) x2[u] = *(const u32x4*)(b2 + kk + u * 32u);
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
-        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, hv[u]), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, mv[u]), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, lv[u]), c, 0, 0, 0);
-      }
+      for (int u = 0; u < 4; ++u) mul(wfrag[q0 + u], x0[u], x1[u], x2[u]);
     } else {
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         if (kk + u * 32u < s_hi) {
-          const u32x4 hv = *(const u32x4*)(bx + kk + u * 32u), mv = *(const u32x4*)(bx + xplane + kk + u * 32u),
-                      lv = *(const u32x4*)(bx + 2u * xplane + kk + u * 32u);
-          const bf16x8 av = __builtin_bit_cast(bf16x8, wfrag[q0 + u]);
-          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, hv), c, 0, 0, 0);
-          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, mv), c, 0, 0, 0);
-          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, lv), c, 0, 0, 0);
+          u32x4 y0 = *(const u32x4*)(b0 + kk + u * 32u), y1 = y0, y2 = y0;
+          if (kMul >= 2) y1 = *(const u32x4*)(b1 + kk + u * 32u);
+          if (kMul >= 3) y2 = *(const u32x4*)(b2 + kk + u * 32u);
+          mul(wfrag[q0 + u], y0, y1, y2);
         }
       }
     }
@@ -1023,7 +1043,12 @@ __device__ __forceinline__ uint32_t mfma_job(const StepArgs& a, const TaskDesc& 
     const uint32_t klen = min(Kt, K - tile * Kt);
     if (!G.whole && tile + 1u < ntile) stage_issue(tile + 1u);   // in flight during this tile's arithmetic
     const uint16_t* cx = G.whole ? xbase : xbase + (size_t)(tile & 1u) * G.xbuf;
-    const uint16_t* bx = cx + (size_t)(frow % nb) * xstride + fk;
+    // (frow = this lane's batch column in the multiply)
+    const uint32_t xrow = PACK == 1 ? frow % nb : (PACK == 2 ? (frow & 7u) % nb : (frow & 3u) % nb);
+    const uint32_t xpl0 = PACK == 1 ? 0u : (PACK == 2 ? (frow >> 3) : min(frow >> 2, 2u));   // plane of the first multiply
+    const uint16_t* b0 = cx + (size_t)xpl0 * xplane + (size_t)xrow * xstride + fk;
+    const uint16_t* b1 = cx + (size_t)(PACK == 1 ? 1u : 2u) * xplane + (size_t)xrow * xstride + fk;
+    const uint16_t* b2 = cx + (size_t)2u * xplane + (size_t)xrow * xstride + fk;
     const uint32_t s_hi = min(s_lo + G.slice_len, (klen + 31u) & ~31u);
     if (G.has_work && s_lo < s_hi) {
       if (G.nf >= (uint32_t)kMfmaRound) {
@@ -1034,10 +1059,10 @@ __device__ __forceinline__ uint32_t mfma_job(const StepArgs& a, const TaskDesc& 
             const uint16_t* wp = row_ptr(rt);
             for (uint32_t kk = s_lo; kk < s_hi; kk += 32u * kMfmaRound) {
               if (!(tile == 0 && j == 0 && kk == s_lo)) request_run(wp, tile * Kt + kk);
-              consume4(acc[j], bx, std::integral_constant<int, 0>{}, kk, s_hi);
-              consume4(acc[j], bx, std::integral_constant<int, 4>{}, kk + 128u, s_hi);
-              consume4(acc[j], bx, std::integral_constant<int, 8>{}, kk + 256u, s_hi);
-              consume4(acc[j], bx, std::integral_constant<int, 12>{}, kk + 384u, s_hi);
+              static_for<0, kMfmaRound / 4>([&](auto gc) {
+                constexpr int g = decltype(gc)::value;
+                consume4(acc[j], acc_lo[j], b0, b1, b2, std::integral_constant<int, 4 * g>{}, kk + 128u * g, s_hi);
+              });
             }
           }
         }
@@ -1046,16 +1071,27 @@ __device__ __forceinline__ uint32_t mfma_job(const StepArgs& a, const TaskDesc& 
         // slice sits at groups g0 .. g0 + nf / 4 - 1 of the round
         const uint32_t g0 = (tile & (G.tpr - 1u)) * (G.nf >> 2), g1 = g0 + (G.nf >> 2);
         if (g0 == 0u && tile != 0u) request_span(row_ptr(G.my_rt0), tile);
-        if (0u >= g0 && 0u < g1) consume4(acc[0], bx, std::integral_constant<int, 0>{}, s_lo + (0u - g0) * 128u, s_hi);
-        if (1u >= g0 && 1u < g1) consume4(acc[0], bx, std::integral_constant<int, 4>{}, s_lo + (1u - g0) * 128u, s_hi);
-        if (2u >= g0 && 2u < g1) consume4(acc[0], bx, std::integral_constant<int, 8>{}, s_lo + (2u - g0) * 128u, s_hi);
-        if (3u >= g0 && 3u < g1) consume4(acc[0], bx, std::integral_constant<int, 12>{}, s_lo + (3u - g0) * 128u, s_hi);
+        static_for<0, kMfmaRound / 4>([&](auto gc) {
+          constexpr uint32_t g = (uint32_t)decltype(gc)::value;
+          if (g >= g0 && g < g1) consume4(acc[0], acc_lo[0], b0, b1, b2, std::integral_constant<int, 4 * (int)g>{}, s_lo + (g - g0) * 128u, s_hi);
+        });
       }
     }
     if (!G.whole && tile + 1u < ntile) stage_write(tile + 1u);   // into the other buffer: nobody reads it now
     lds_barrier();
   }
   trace_mark(a, t, 8);
+  // ---- the column groups of a packed multiply added up: afterwards column b < nb holds the sum
+  if (PACK != 1) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float v = acc[j][i];
+        if (PACK == 2) acc[j][i] = v + __shfl(v, lane + 8, 64) + acc_lo[j][i];        // hi + mid (8 columns up) + lo
+        else acc[j][i] = v + __shfl(v, lane + 4, 64) + __shfl(v, lane + 8, 64);       // hi + mid + lo, 4 columns apart
+      }
+  }
   // ---- partial tiles -> LDS.  part[wave][j][row 0..15][col 0..15]
 #pragma unroll
   for (int j = 0; j < 4; ++j)
@@ -1072,6 +1108,15 @@ __device__ __forceinline__ uint32_t mfma_job(const StepArgs& a, const TaskDesc& 
   }
   lds_barrier();
   return kLinDone;
+}
+
+template <class RowPtr, class SrcRow, class Wait>
+__device__ __forceinline__ uint32_t mfma_job(const StepArgs& a, const TaskDesc& t, float* lds, float* ssq, const MfmaGeom& G,
+                                             RowPtr row_ptr, SrcRow src_row, bool pro_norm, const uint16_t* gain,
+                                             Wait wait_fn) {
+  if (G.nb <= 4u) return mfma_job_packed<3>(a, t, lds, ssq, G, row_ptr, src_row, pro_norm, gain, wait_fn);
+  if (G.nb <= 8u) return mfma_job_packed<2>(a, t, lds, ssq, G, row_ptr, src_row, pro_norm, gain, wait_fn);
+  return mfma_job_packed<1>(a, t, lds, ssq, G, row_ptr, src_row, pro_norm, gain, wait_fn);
 }
 
 // Dot product of weight row r (16-row tile r / 16) with batch column bb from the partial tiles a
@@ -1165,26 +1210,34 @@ __device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const St
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     lds_barrier();
   }
-  if (wave == 0) {
-    if (splitk) {
-      // arrival at the row block's counter now that the partial sums are visible; the last of the
-      // `parts` tasks adds the parts in order, and the residual, into the real output
-      uint32_t last = 0;
-      if (lane == 0) {
-        const uint32_t old = __hip_atomic_fetch_add(as_global(a.g->grp_counters + t.p2), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        last = ((old + 1u) % parts == 0u) ? 1u : 0u;   // every step adds exactly `parts` (also when a captured launch is replayed with its step number frozen)
-      }
-      last = __builtin_amdgcn_readfirstlane(last);
-      if (last) {
-        float* xout = (float*)t.aux0;
-        for (uint32_t i = lane; i < ncols * nb; i += 64) {
-          const uint32_t cc = i / nb, bb = i % nb;
-          float v = ld_act(t.in2 + (size_t)(t.b0 + bb) * Hs + row0 + cc);
-          for (uint32_t pp = 0; pp < parts; ++pp) v += ld_act(t.out + (size_t)(t.b0 + bb) * t.ld_out + pp * Hs + row0 + cc);
-          st_act(xout + (size_t)(t.b0 + bb) * Hs + row0 + cc, v);
-        }
-      }
+  if (splitk) {
+    // arrival at the row block's counter now that the partial sums are visible; the last of the
+    // `parts` tasks adds the parts in order, and the residual, into the real output -- all
+    // wavefronts, one output each, the loads of an output in flight together
+    uint32_t* last_flag = (uint32_t*)(ssq + 9 * 16);
+    if (threadIdx.x == 0) {
+      const uint32_t old = __hip_atomic_fetch_add(as_global(a.g->grp_counters + t.p2), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      *last_flag = ((old + 1u) % parts == 0u) ? 1u : 0u;   // every step adds exactly `parts` (also when a captured launch is replayed with its step number frozen)
     }
+    lds_barrier();
+    if (__builtin_amdgcn_readfirstlane(*last_flag)) {
+      float* xout = (float*)t.aux0;
+      for (uint32_t i = threadIdx.x; i < ncols * nb; i += kThreads) {
+        const uint32_t cc = i / nb, bb = i % nb;
+        float v = ld_act(t.in2 + (size_t)(t.b0 + bb) * Hs + row0 + cc);
+        float pv[8];
+#pragma unroll
+        for (uint32_t pp = 0; pp < 8; ++pp) pv[pp] = pp < parts ? ld_act(t.out + (size_t)(t.b0 + bb) * t.ld_out + pp * Hs + row0 + cc) : 0.f;
+#pragma unroll
+        for (uint32_t pp = 0; pp < 8; ++pp) v += pv[pp];   // parts in ascending order (absent ones add zero)
+        st_act(xout + (size_t)(t.b0 + bb) * Hs + row0 + cc, v);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    lds_barrier();
+  }
+  if (wave == 0) {
     if (MEGA && t.trig_event >= 0) signal_from_wave0(a, t, t.trig_event, lane);
     trace_mark(a, t, 4);
   }
@@ -2673,13 +2726,17 @@ __global__ void __launch_bounds__(kThreads) mpk_loop_kernel(StepArgs a) {
   }
 }
 
-template <int D, int GRP, int NB, bool MOE>
+// PATHS: 0 = the all-ahead-of-time walk and the hybrid launch in one kernel, chosen at run time;
+// 1 = ahead-of-time only; 2 = hybrid only.  Which is faster is a matter of register allocation and
+// code layout, measured per body: the vector linear body (batch <= 4) runs 0.8 % faster from the
+// combined kernel, the matrix-core body spills three times less in a kernel of its own.
+template <int D, int GRP, int NB, bool MOE, int PATHS = 0>
 __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
   extern __shared__ __align__(16) float dyn_lds[];
   float* lds = dyn_lds + kLdsCtrlFloats;
   uint32_t* s_flag = (uint32_t*)dyn_lds;
   const uint32_t w = blockIdx.x;
-  if (w >= a.g->n_workers) {
+  if (PATHS != 1 && w >= a.g->n_workers) {
     // scheduler workgroup: 4 scheduler wavefronts (Section 5.1, Table 2), the rest leave
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t sc = (w - a.g->n_workers) * 4u + wave;
@@ -2687,7 +2744,7 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
     return;
   }
   const uint32_t q0 = ld_u32c(a.g->aot_off + w), q1 = ld_u32c(a.g->aot_off + w + 1);
-  if (a.n_sched == 0) {
+  if (PATHS == 1 || (PATHS == 0 && a.n_sched == 0)) {
     aot_pass<D, GRP, NB, MOE>(a, q0, q1, lds, s_flag, false);
     return;
   }
@@ -2748,9 +2805,10 @@ __global__ void __launch_bounds__(kThreads) mpk_op_kernel(StepArgs a, uint32_t f
 struct KernelVariant {
   int d, grp, nb;
   bool moe;
-  void (*mega)(StepArgs);
+  void (*mega)(StepArgs);     // all tasks ahead-of-time
   void (*op)(StepArgs, uint32_t);
   void (*loop)(StepArgs);
+  void (*hybrid)(StepArgs);   // with scheduler workgroups (may be the same kernel as `mega`)
 };
 // index, head_dim, group, batch class, mixture of experts
 #define MPK_VARIANT_LIST(X)                                                                   \

@@ -282,6 +282,7 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
   hipError_t e = reserve_lds((const void*)g->kv->mega, h.lds_bytes);
   if (e == hipSuccess) e = reserve_lds((const void*)g->kv->op, h.lds_bytes);
   if (e == hipSuccess) e = reserve_lds((const void*)g->kv->loop, h.lds_bytes);
+  if (e == hipSuccess) e = reserve_lds((const void*)g->kv->hybrid, h.lds_bytes);
   if (e != hipSuccess) { set_error("cannot reserve %u bytes of LDS: %s", h.lds_bytes, hipGetErrorString(e)); return fail(MPK_ERR_RESIDENCY); }
   int per_cu = 0;
   e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)g->kv->mega, kThreads, h.lds_bytes);
@@ -491,9 +492,10 @@ static mpk_status launch_steps(mpk_graph* g, uint32_t n_steps, const int32_t* to
     if (!static_scratch) g->epoch += n_steps;
     if (n_steps > 1)   // (callers have checked: no scheduler workgroups)
       hipLaunchKernelGGL(g->kv->loop, dim3(h.opt.n_workers), dim3(kThreads), h.lds_bytes, s, a);
+    else if (g->n_sched)
+      hipLaunchKernelGGL(g->kv->hybrid, dim3(h.opt.n_workers + h.opt.n_sched_wgs), dim3(kThreads), h.lds_bytes, s, a);
     else
-      hipLaunchKernelGGL(g->kv->mega, dim3(h.opt.n_workers + (g->n_sched ? h.opt.n_sched_wgs : 0u)), dim3(kThreads),
-                         h.lds_bytes, s, a);
+      hipLaunchKernelGGL(g->kv->mega, dim3(h.opt.n_workers), dim3(kThreads), h.lds_bytes, s, a);
     HIP_TRY(hipGetLastError());
   } else {
     a.n_steps = (uint16_t)n_steps;

@@ -17,8 +17,10 @@ MPK_VARIANT_LIST(MPK_PARAMS)
 template <int I>
 static const KernelVariant* make_variant() {
   using P = VariantParams<I>;
-  static const KernelVariant v = {P::d, P::grp, P::nb, P::moe, mpk_mega_kernel<P::d, P::grp, P::nb, P::moe>,
-                                  mpk_op_kernel<P::d, P::grp, P::nb, P::moe>, mpk_loop_kernel<P::d, P::grp, P::nb, P::moe>};
+  constexpr bool split = P::nb == 8;   // matrix-core bodies: one kernel per launch path
+  static const KernelVariant v = {P::d, P::grp, P::nb, P::moe, mpk_mega_kernel<P::d, P::grp, P::nb, P::moe, split ? 1 : 0>,
+                                  mpk_op_kernel<P::d, P::grp, P::nb, P::moe>, mpk_loop_kernel<P::d, P::grp, P::nb, P::moe>,
+                                  mpk_mega_kernel<P::d, P::grp, P::nb, P::moe, split ? 2 : 0>};
   return &v;
 }
 
