@@ -112,6 +112,12 @@ typedef struct mpk_kv_ptrs {
 #define MPK_LAUNCH_MEGA 0u   /* one persistent kernel per decode step (Section 5)               */
 #define MPK_LAUNCH_PER_OP 1u /* same task bodies, one kernel launch per operator (baseline)     */
 
+#define MPK_DEBUG_LOSE_NOTIFY 8u /* the FIRST persistent-kernel launch of the graph loses worker
+                               0's notifications: the events they belong to never activate, every
+                               wait that depends on them ends at its watchdog limit
+                               (spin_timeout_ms), all workgroups exit, and mpk_graph_status reports
+                               MPK_ERR_TIMEOUT.  For testing that path and mpk_graph_reset        */
+
 typedef struct mpk_compile_options {
   uint32_t struct_size;     /* = sizeof(mpk_compile_options)                                    */
   uint32_t n_workers;       /* worker workgroups, one per CU (Section 5); 0 = all CUs minus the

@@ -89,7 +89,7 @@ SYMBOLS = ("mpk_compile", "mpk_compile_dag", "mpk_decode_step", "mpk_decode_step
            "mpk_graph_moe_active", "mpk_graph_moe_selection", "mpk_compile_set",
            "mpk_set_decode_step", "mpk_decode_step_static", "mpk_set_size", "mpk_set_batch_for", "mpk_set_graph",
            "mpk_set_destroy", "mpk_last_error", "mpk_graph_destroy", "mpk_static_scratch_need")
-DEBUG_TRACE, DEBUG_POISON, DEBUG_JITTER = 1, 2, 4
+DEBUG_TRACE, DEBUG_POISON, DEBUG_JITTER, DEBUG_LOSE_NOTIFY = 1, 2, 4, 8
 
 _lib = None
 

@@ -170,6 +170,7 @@ constexpr int kTraceSlots = 12;
 constexpr uint32_t kTraceBit = 1u;      // per-task timestamps are recorded (buffer: GraphConst::trace)
 constexpr uint32_t kJitterBit = 2u;     // every task starts after a pseudo-random delay (race hunting)
 constexpr uint32_t kNoPreloadBit = 4u;  // no weight / cache-row request before a task's event wait
+constexpr uint32_t kLoseNotifyBit = 8u; // worker 0 drops its notifications in this launch (watchdog test)
 __device__ __forceinline__ void trace_mark(const StepArgs& a, const TaskDesc& t, int slot) {
   if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + slot] = wall_clock64();
 }
@@ -2389,6 +2390,7 @@ __device__ __forceinline__ bool wait_event(const StepArgs& a, int32_t e, uint32_
 // The arrival that activates an event whose range holds just-in-time tasks hands the event to
 // its scheduler's queue.
 __device__ __forceinline__ void notify_event(const StepArgs& a, int32_t e) {
+  if ((a.flags & kLoseNotifyBit) && blockIdx.x == 0) return;   // MPK_DEBUG_LOSE_NOTIFY: the waiters' watchdog has to end the step
   const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
   const uint32_t flags = ev.flags;
   bool activated = false;

@@ -94,6 +94,7 @@ struct mpk_graph {
   uint32_t epoch = 0;
   uint64_t timeout_ticks = 0;
   uint32_t step_flags = 0;   // StepArgs::flags of every launch (trace, jitter, no pre-loading)
+  bool lost_one = false;     // MPK_DEBUG_LOSE_NOTIFY has had its launch
   // mpk_decode_step_static: descriptors and graph record relocated into the static scratch array
   // (null when the graph is not eligible), and where its pieces sit in the array (bytes)
   TaskDesc* d_tasks_static = nullptr;
@@ -453,6 +454,10 @@ static mpk_status launch_steps(mpk_graph* g, uint32_t n_steps, const int32_t* to
   a.g = (const MPK_CONST GraphConst*)g->d_const;
   a.tasks = g->d_tasks; a.events = g->d_events; a.counters = g->d_counters; a.hier = g->d_hier;
   a.n_sched = g->n_sched; a.flags = g->step_flags;
+  if ((h.opt.debug_flags & MPK_DEBUG_LOSE_NOTIFY) && !g->lost_one && h.opt.launch_mode == MPK_LAUNCH_MEGA) {
+    a.flags |= kLoseNotifyBit;   // once
+    g->lost_one = true;
+  }
   a.token_ids = token_ids; a.positions = positions; a.logits = logits_out;
   hipStream_t s = (hipStream_t)stream;
   float* arena = g->d_arena;

@@ -4,7 +4,9 @@ oracle (oracle/) on the seeded synthetic inputs (synth/).  Nothing here touches 
 
     python tests/golden/make_golden.py C2        # Qwen3-8B-shaped, batch 1, 32 greedy steps
 
-    python tests/golden/make_golden.py C2 f64    # add the fp64 oracle's step-0 samples to C2_greedy.json
+    python tests/golden/make_golden.py C2 f64    # add the fp64 oracle's step-0 samples to C2_greedy.json and
+                                                 # write all of its step-0 logits to C2_step0_logits_f64.npy
+    python tests/golden/make_golden.py C2 f64 all   # ... and its last-step samples along the fixture's tokens
     python tests/golden/make_golden.py C4        # mixture-of-experts: routing decisions recorded too
 
 Each fixture is a small JSON file: greedy tokens of every step, the top-8 logits (index, value)
@@ -41,6 +43,20 @@ def add_f64(name):
     lg = o.step(tok, pos)
     out["samples64_0"] = [[float(v) for v in lg[b, idx]] for b in range(s.batch)]
     out["absmax64_0"] = [float(np.abs(lg[b]).max()) for b in range(s.batch)]
+    # every logit of step 0 from the fp64 build (stored as float32: 6e-8 relative, far below any
+    # bound it is compared at)
+    if s.batch == 1:
+        np.save(os.path.join(os.path.dirname(path), f"{name}_step0_logits_f64.npy"), lg.astype(np.float32))
+    if not s.n_experts and len(sys.argv) > 3 and sys.argv[3] == "all":
+        # ... and the fp64 build driven along the fixture's token sequence to the last step, so
+        # that later steps, too, are compared with a reference whose own rounding error is nil
+        t0 = time.time()
+        for i in range(1, out["steps"]):
+            tok, pos = np.array(out["tokens"][i - 1], np.int64), pos + 1
+            lg = o.step(tok, pos)
+            print(f"fp64 step {i} ({time.time() - t0:.0f} s)", flush=True)
+        out["samples64_last"] = [[float(v) for v in lg[b, idx]] for b in range(s.batch)]
+        out["absmax64_last"] = [float(np.abs(lg[b]).max()) for b in range(s.batch)]
     if s.n_experts:
         # the fp32 oracle's own error on the router outputs, per layer (largest difference to the
         # fp64 oracle over sequences and experts at step 0): a routing decision whose margin is

@@ -27,6 +27,17 @@ def _load(name):
         return json.load(f)
 
 
+# Later steps read K/V rows that each side appended itself.  A row element whose unrounded value
+# sits on a bf16 rounding boundary may round the other way on the GPU (another summation order):
+# tests/test_oracle_decoder.py measures what that does to the logits (a handful of boundary
+# elements per layer and sequence rounded the other way: 1e-5 .. 1e-4 of the largest logit at 128
+# cached positions, less at the 1024 .. 4096 of these shapes).  With the reference of the last
+# step taken from the fp64 build (no rounding noise of its own) the bound on the largest-logit
+# norm is 5e-4; the small live-oracle tests hold these decisions equal on both sides instead and
+# compare every step at the element-wise bound.
+LATER_TOL = 5e-4
+
+
 def _check_against_fixture(name, opts, free_running=True):
     gold = _load(name)
     s = G.CONFIGS[name]
@@ -39,13 +50,18 @@ def _check_against_fixture(name, opts, free_running=True):
     idx = np.array(gold["sample_indices"])
     steps = gold["steps"]
     live = np.ones(s.batch, bool)   # sequences still comparable with the oracle's trajectory
+    token_flips = routing_drops = 0
+    # how many decisions of the fixture are close calls at all: a bound on what may differ
+    near_ties = sum(1 for i in range(steps) for b in range(s.batch)
+                    if gold["top8"][i][b][0][1] - gold["top8"][i][b][1][1] < 2e-3 * abs(gold["top8"][i][b][0][1]))
+    close_routes = 0
     for i in range(steps):
         lg = gpu.step(tok, pos)
         assert np.isfinite(lg).all(), i
         if s.n_experts:
             # Routing decisions of the step against the oracle's.  Top-k is discontinuous: where
             # the oracle's margin between its top_k-th and next router output is within a few
-            # times its own fp32 rounding error at that layer (fixture: fp32 against fp64 oracle),
+            # times the fp32 rounding error at that layer (fixture: fp32 against fp64 oracle),
             # fp32 arithmetic does not resolve the decision and the other set is as valid.  A
             # sequence routed differently there is "routing-ambiguous": everything downstream of
             # the swap legitimately differs, so it leaves the comparison from then on.
@@ -55,10 +71,12 @@ def _check_against_fixture(name, opts, free_running=True):
             assert np.allclose(wt.reshape(s.n_layers, s.batch, s.top_k).sum(-1), 1.0, atol=1e-5)
             differs = (ex != np.array(gold["moe_sel"][i])).any(-1)      # [layer, sequence]
             gap, noise = np.array(gold["moe_gap"][i]), np.array(gold["moe_noise"])
+            close_routes += int((gap < 4 * noise[:, None]).sum())
             for b in np.flatnonzero(differs.any(0) & live):
                 l0 = int(np.argmax(differs[:, b]))
                 assert gap[l0, b] < 4 * noise[l0], f"step {i} layer {l0} sequence {b}: margin {gap[l0, b]}"
                 live[b] = False
+                routing_drops += 1
         want_tok = np.array(gold["tokens"][i])
         for b in np.flatnonzero(live):
             got_tok = int(lg[b].argmax())
@@ -68,6 +86,7 @@ def _check_against_fixture(name, opts, free_running=True):
                 # below 2e-3 of the largest logit and the GPU's choice must be the runner-up
                 (j0, v0), (j1, v1) = gold["top8"][i][b][0], gold["top8"][i][b][1]
                 assert got_tok == j1 and (v0 - v1) < 2e-3 * abs(v0), f"step {i} sequence {b}"
+                token_flips += 1
                 free_running = False   # keep both sides on the oracle's token sequence from here on
         for b in np.flatnonzero(live):
             top = gold["top8"][i][b]
@@ -79,40 +98,41 @@ def _check_against_fixture(name, opts, free_running=True):
             got8 = set(np.argsort(-lg[b], kind="stable")[:8].tolist())
             want8 = {j for j, _ in top}
             assert len(got8 ^ want8) <= 2, (i, b)
-        if str(i) in gold["samples"]:
+        if i == 0:
+            # identical inputs on both sides: the element-wise bound of the target against the
+            # fp64 build of the oracle (the fp32 build sums every dot product sequentially in
+            # fp32; on the widest shapes its own rounding error reaches 1e-3 of the largest logit)
+            for b in range(s.batch):
+                want64 = np.array(gold["samples64_0"][b])
+                amax = gold["absmax64_0"][b]
+                d64 = np.abs(lg[b, idx] - want64)
+                err = d64 / np.maximum(np.abs(want64), 1e-3 * amax)
+                assert err.max() < TOL, (b, float(err.max()))
+                assert d64.max() / amax < 2e-5, (b, float(d64.max() / amax))   # fp32 activations throughout
+            full = os.path.join(GOLDEN, f"{name}_step0_logits_f64.npy")
+            if os.path.exists(full):        # every logit of the step, not a sample
+                want = np.load(full).astype(np.float64)
+                assert want.shape == lg.shape
+                err = np.abs(lg - want) / np.maximum(np.abs(want), 1e-3 * np.abs(want).max())
+                assert err.max() < TOL, float(err.max())
+                assert np.array_equal(lg.argmax(-1), want.argmax(-1))
+        elif i == steps - 1:
+            key = "samples64_last" if "samples64_last" in gold else "samples"
             for b in np.flatnonzero(live):
-                want = np.array(gold["samples"][str(i)][b])
-                amax = gold["absmax_%d" % i][b]
+                want = np.array(gold[key][b] if key == "samples64_last" else gold["samples"][str(i)][b])
+                amax = (gold["absmax64_last"] if key == "samples64_last" else gold["absmax_%d" % i])[b]
+                # a dense fixture without fp64 last-step samples carries the fp32 build's own noise
+                bound = LATER_TOL if (key == "samples64_last" or gold.get("precision") == "f64") else 2e-3
                 diff = np.abs(lg[b, idx] - want)
-                if i == 0:
-                    # identical inputs on both sides: the element-wise bound of the target, taken
-                    # against the fp64 build of the oracle.  (The fp32 build sums every dot
-                    # product sequentially in fp32; on the widest shapes its own rounding error,
-                    # stored in the fixture as the fp32/fp64 difference, reaches 1e-3 of the
-                    # largest logit, far more than the GPU's.)
-                    want64 = np.array(gold["samples64_0"][b])
-                    d64 = np.abs(lg[b, idx] - want64)
-                    floor = np.maximum(np.abs(want64), 1e-3 * amax)
-                    err = d64 / floor
-                    # ... plus the reference's own uncertainty: the same measure of the fp32
-                    # oracle against the fp64 one (on the 48-layer mixture-of-experts shape it
-                    # reaches 2e-2 to 5e-2 by itself on logits near the floor)
-                    want32 = np.array(gold["samples32_0"][b]) if "samples32_0" in gold else want
-                    own_el = (np.abs(want32 - want64) / floor).max()
-                    assert err.max() < TOL + own_el, (i, b, float(err.max()), float(own_el))
-                    own = np.abs(want32 - want64).max() / amax   # the fp32 oracle's own error
-                    assert d64.max() / amax < max(1e-4, own)   # fp32 activations throughout
-                    assert diff.max() / amax < own + 1e-4, (float(diff.max() / amax), float(own))
-                else:
-                    # later steps read K/V rows each side appended itself: a row element whose
-                    # fp32 value sits on a bf16 rounding boundary may round the other way (one
-                    # bf16 ulp), which moves logits by ~1e-4 of their scale after 31 steps; the
-                    # bound here is on the error relative to the largest logit
-                    assert diff.max() / amax < 2e-3, (i, b, float(diff.max() / amax))
+                assert diff.max() / amax < bound, (i, b, float(diff.max() / amax))
         own_tok = lg.argmax(-1)
         tok = np.where(live & free_running, own_tok, want_tok).astype(np.int32)
         pos = pos + 1
-    assert live.sum() * 2 >= s.batch, f"only {int(live.sum())} of {s.batch} sequences stayed comparable"
+    print(f"{name}: {steps} steps x {s.batch} sequences: {token_flips} greedy tokens resolved the other way "
+          f"(fixture has {near_ties} near-ties), {routing_drops} sequences left on a routing close call "
+          f"(fixture has {close_routes} close calls among {steps * s.n_layers * s.batch if s.n_experts else 0} decisions)")
+    assert token_flips <= near_ties and routing_drops <= close_routes
+    assert live.sum() * 4 >= 3 * s.batch, f"only {int(live.sum())} of {s.batch} sequences stayed comparable"
     gpu.close()
 
 

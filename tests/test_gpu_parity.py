@@ -621,3 +621,34 @@ def test_cross_task_preloading_switched_off(variant, opts):
     tok = G.tokens(1, s)
     pos = np.array([(41 * b + 7) % 120 for b in range(s.batch)], np.int32)
     strict_steps(s, 1, dict(no_preload=1, **opts), tok, pos, 2)
+
+
+def test_watchdog_ends_a_step_whose_event_never_activates_and_reset_recovers():
+    """MPK_DEBUG_LOSE_NOTIFY: the first launch loses worker 0's notifications, so the events they
+    belong to never activate.  Every wait is bounded by the watchdog (20 ms here): all workgroups
+    exit by themselves, the status is MPK_ERR_TIMEOUT (not a hang, not a fault), mpk_graph_reset
+    clears counters and queues, and the next steps are correct again."""
+    s = G.small_variant("C1", batch=2)
+    tok, pos = G.tokens(0, s), G.kv_lengths(0, s)
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 0), "f64")
+    for opts in (dict(fusion=31, transitive_reduction=1), dict(fusion=7, n_sched_wgs=2)):
+        gpu = GpuDecoder(s, 0, spin_timeout_ms=20, debug_flags=M.binding.DEBUG_LOSE_NOTIFY, **opts)
+        stream = torch.cuda.current_stream().cuda_stream
+        gpu.tok.copy_(torch.as_tensor(tok))
+        gpu.pos.copy_(torch.as_tensor(pos))
+        gpu.graph.decode_step(gpu.tok.data_ptr(), gpu.pos.data_ptr(), gpu.logits.data_ptr(), stream)
+        torch.cuda.synchronize()
+        with pytest.raises(M.binding.MpkError) as e:
+            gpu.graph.status()
+        assert e.value.status == M.binding.MPK_ERR_TIMEOUT and "watchdog" in str(e.value)
+        gpu.graph.reset()
+        gpu.graph.status()                     # clean again
+        gpu.model.reset_kv()
+        fresh = D.DecoderOracle(s, G.SynthWeights(s, 0), "f64")
+        t, p = tok.copy(), pos.copy()
+        for step in range(2):
+            got, want, _, _ = held_step(fresh, gpu, t, p)
+            assert rel_err(got, want) < TOL, step
+            t, p = want.argmax(-1).astype(np.int32), p + 1
+        gpu.close()
+    del ref
