@@ -1001,8 +1001,8 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
       if (c.batch <= 4) {
         f = (size_t)nb * ((op.K + 4095u) / 4096u * 4096u) + 2 * (size_t)rows_max * nb + 8 * nb;
       } else {
-        // matrix-core body: two buffers of three bf16 planes of one input tile (reused for the
-        // per-wavefront partial tiles) | residual slice | sums of squares | 1/rms per row
+        // matrix-core body: the staged fp32 input, one chunk (reused for the per-wavefront
+        // partial tiles) | residual slice | sums of squares | 1/rms per row
         f = (size_t)mfma_x_floats(c.batch) + (size_t)res_rows * 16 + 10 * 16;   // ... | split-K arrival flag
       }
     }

@@ -211,6 +211,20 @@ __device__ __forceinline__ float wave_sum(float v) {
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
   return v;
 }
+// The same sum without LDS traffic: four data-parallel-primitive steps inside each row of 16 lanes
+// (lane ^ 1, lane ^ 2, mirror of 8, mirror of 16), then the four row totals.
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+  auto dpp = [](float x, auto ctrl) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value, 0xF, 0xF, true));
+  };
+  v += dpp(v, std::integral_constant<int, 0xB1>{});    // quad_perm [1,0,3,2]
+  v += dpp(v, std::integral_constant<int, 0x4E>{});    // quad_perm [2,3,0,1]
+  v += dpp(v, std::integral_constant<int, 0x141>{});   // row_half_mirror
+  v += dpp(v, std::integral_constant<int, 0x140>{});   // row_mirror
+  const int u = __float_as_int(v);
+  return (__int_as_float(__builtin_amdgcn_readlane(u, 0)) + __int_as_float(__builtin_amdgcn_readlane(u, 16))) +
+         (__int_as_float(__builtin_amdgcn_readlane(u, 32)) + __int_as_float(__builtin_amdgcn_readlane(u, 48)));
+}
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
@@ -815,12 +829,10 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
 //     weight is exact, and the only rounding is the fp32 accumulation -- as in the vector body.
 //     (Two terms leave x to 2^-18: logits near zero then miss the element-wise bound.)
 //   D: lane l holds batch column (l % 16), tile rows 4 (l / 16) .. + 3.
-// The input is staged in LDS one K tile at a time (three planes, row stride padded by 16 bytes so
-// that the 16 lanes of a fragment read 16 different bank groups): 1024 inputs per tile up to
-// batch 8, 512 above, two buffers (99 KB) -- or, when the whole input is at most two tiles long,
-// all of it at once in the space of both.  Work is split over the 8 wavefronts by 16-row tiles; a
-// job with fewer than 8 tiles also splits K inside each input tile, and the epilogue adds the
-// slices in a fixed order.
+// The input is staged in LDS as fp32, whole when it fits (4096 inputs up to batch 8, 2048 above;
+// longer inputs in chunks of that size), row stride padded by 128 bytes so that the lanes of a
+// fragment spread evenly over the banks; the wavefronts split it into the three terms as they go,
+// so no barrier separates the staging of one part from the multiplies of another.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -838,10 +850,6 @@ __device__ __forceinline__ void split_hi_mid_lo(float x, float y, uint32_t* hi, 
   *lo = pack_bf16_rne(rx - bf16_lo(m), ry - bf16_hi(m));
 }
 
-#ifndef MPK_MFMA_ROUND
-#define MPK_MFMA_ROUND 16
-#endif
-constexpr int kMfmaRound = MPK_MFMA_ROUND;   // weight fragments (32 inputs x 16 rows, 1 KB) a wavefront requests at a time
 template <int I, int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {
   if constexpr (I < N) {
@@ -850,92 +858,155 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-// Geometry of one matrix-core job: K inputs x nb staged rows x nrt 16-row weight tiles.  Uniform
-// over the wavefront (wave comes from readfirstlane).
+// Geometry of one matrix-core job: K inputs x nb staged rows x nrt 16-row weight tiles (nrt <= 32).
+// Uniform over the wavefront (wave comes from readfirstlane).
+//
+// The input stays in LDS as fp32, a chunk of up to mfma_kchunk(nb) inputs at a time (the whole of
+// it for every operator of the benchmark shapes), so that there is one staging pass and no
+// barrier inside the multiply loop; each wavefront turns the 8 inputs x 1 row a lane needs for a
+// multiply into the three bf16 terms on the fly.
+//
+// The 8 wavefronts form rg row groups x ks K slices (rg = 1, 2, 4 or 8, the smallest with
+// 4 rg >= nrt).  Wavefront (slice s, group g) owns row tiles g, g + rg, g + 2 rg, g + 3 rg (those
+// below nrt: nrtw of them) and, in every chunk, the s-th of ks nearly equal runs of 128-input
+// "k-groups".  It works in rounds of 16 weight fragments (32 inputs x 16 rows, 1 KB each) = 4 slot
+// groups of 4 fragments; slot group q always adds into accumulator q:
+//   nrtw >= 3: one k-group per round, slot group q = row tile q of the wavefront
+//   nrtw == 2: two k-groups per round, slot group q = (k-group q / 2, row tile q % 2)
+//   nrtw == 1: four k-groups per round, slot group q = k-group q
+// so the fragments of a k-group's inputs are converted once and used by all row tiles of the
+// round.  The epilogue adds the accumulators of a row tile over slot groups and slices in a
+// fixed order (mfma_dot).
 struct MfmaGeom {
   uint32_t K, nb, nrt;
-  uint32_t Kt1;          // inputs one staging pass covers
-  uint32_t Kt, ntile;    // inputs per multiply tile (2 Kt1 when staged whole), number of tiles
-  uint32_t whole;        // the whole input sits in LDS at once (one buffer)
-  uint32_t xstride, xplane, xbuf;   // in bf16 elements: row stride, one plane, one buffer of three planes
-  uint32_t nrt2, ks;     // row tiles rounded up to a power of two (<= 8); K slices per input tile
-  uint32_t my_slice, my_rt0, slice_len;
-  uint32_t nf, lognf;    // fragments per (input tile, row tile) of this wavefront: 4, 8, 16, 32 or 64
-  uint32_t tpr;          // input tiles one round of fragments spans (nf < 16), else 1
-  bool has_work;
+  uint32_t Kc, nchunk;   // inputs per chunk, chunks
+  uint32_t xstride;      // floats between staged rows
+  uint32_t rg, ks;       // row groups x K slices = 8
+  uint32_t my_g, my_s;
+  uint32_t nrtw;         // row tiles of this wavefront: 0 .. 4
+  uint32_t kgpr;         // k-groups per round: 1, 2 or 4
 };
+__device__ __forceinline__ uint32_t mfma_group_tiles(uint32_t nrt, uint32_t rg, uint32_t g) {
+  return g < nrt ? min(4u, (nrt - g + rg - 1u) / rg) : 0u;
+}
 __device__ __forceinline__ MfmaGeom mfma_geom(uint32_t K, uint32_t nb, uint32_t nrt, uint32_t wave) {
   MfmaGeom G;
   G.K = K; G.nb = nb; G.nrt = nrt;
-  G.Kt1 = mfma_ktile(nb);
-  G.whole = (K <= 2u * G.Kt1) ? 1u : 0u;
-  G.Kt = G.whole ? 2u * G.Kt1 : G.Kt1;
-  G.ntile = (K + G.Kt - 1u) / G.Kt;
-  G.xstride = G.Kt + 8u;
-  G.xplane = nb * G.xstride;
-  G.xbuf = 3u * G.xplane;
-  uint32_t nrt2 = 1;
-  while (nrt2 < nrt && nrt2 < 8u) nrt2 <<= 1;
-  G.nrt2 = nrt2;
-  G.ks = min(8u / nrt2, G.Kt / 128u);   // at least four fragments per slice
-  G.my_slice = wave / nrt2;
-  G.my_rt0 = wave % nrt2;
-  G.slice_len = G.Kt / G.ks;
-  G.nf = G.slice_len / 32u;
-  G.lognf = 31u - (uint32_t)__builtin_clz(G.nf);
-  G.tpr = G.nf < (uint32_t)kMfmaRound ? (uint32_t)kMfmaRound / G.nf : 1u;
-  G.has_work = G.my_rt0 < nrt && G.my_slice < G.ks;
+  G.Kc = mfma_kchunk(nb);
+  G.nchunk = (K + G.Kc - 1u) / G.Kc;
+  G.xstride = G.Kc + kMfmaXPad;
+  uint32_t rg = 1;
+  while (4u * rg < nrt && rg < 8u) rg <<= 1;
+  G.rg = rg;
+  G.ks = 8u / rg;
+  G.my_g = wave % rg;
+  G.my_s = wave / rg;
+  G.nrtw = mfma_group_tiles(nrt, rg, G.my_g);
+  G.kgpr = G.nrtw >= 3u ? 1u : (G.nrtw == 2u ? 2u : 4u);
   return G;
 }
 
+// 8 consecutive fp32 inputs of one staged row -> packed bf16 terms hi, mid, lo (4 words each)
+__device__ __forceinline__ void split8(const float4& p, const float4& q, u32x4* hi, u32x4* mid, u32x4* lo) {
+  uint32_t h[4], m[4], l[4];
+  split_hi_mid_lo(p.x, p.y, &h[0], &m[0], &l[0]);
+  split_hi_mid_lo(p.z, p.w, &h[1], &m[1], &l[1]);
+  split_hi_mid_lo(q.x, q.y, &h[2], &m[2], &l[2]);
+  split_hi_mid_lo(q.z, q.w, &h[3], &m[3], &l[3]);
+  *hi = u32x4{h[0], h[1], h[2], h[3]};
+  *mid = u32x4{m[0], m[1], m[2], m[3]};
+  *lo = u32x4{l[0], l[1], l[2], l[3]};
+}
+__device__ __forceinline__ u32x4 select4(bool c, const u32x4& x, const u32x4& y) {
+  return u32x4{c ? x.x : y.x, c ? x.y : y.y, c ? x.z : y.z, c ? x.w : y.w};
+}
+
 // One job: out[r][b] partial tiles = W rows x staged input rows, left in LDS.
-//   row_ptr(rt)  : this lane's weight address for 16-row tile rt at input 0 (fragment row and
-//                  input group of the lane included); loads are clamped to kclamp inputs
+//   wbase, row_off(rt) : weight rows start at wbase (uniform) + row_off(rt) bytes, row_off = this
+//                  lane's row of 16-row tile rt (32 bits: a scalar base and one vector offset per
+//                  load, no address pairs to keep); loads are clamped to the end of the row
 //   src_row(b)   : fp32 input row b (read with coherent loads), b < nb
 //   wait_fn()    : called after the first round of weights has been requested (cross-task
-//                  pre-loading, Section 5.3); returns kLinDone to go on
-// LDS: x [buffers][3 planes][nb][xstride] bf16 at `lds`, reused at the end for the per-wavefront
-// partial tiles part[8][4][16][16] f32; ssq [8][16] f32 (sums of squares per wavefront and row, when
-// pro_norm).  On return (kLinDone) every thread may read part and ssq.
-// PACK: how many of the three planes one multiply covers.  The multiply has 16 batch columns; up
-// to 8 staged rows leave half of them free, so columns 0..7 take the hi plane and columns 8..15
-// the mid plane of the same rows (PACK 2: two multiplies per fragment, the lo plane alone in the
+//                  pre-loading, Section 5.3: 16 KB per wavefront, 32 MB over the chip); returns
+//                  kLinDone to go on
+// LDS: x [nb][xstride] f32 at `lds`, reused at the end for the per-wavefront partial tiles
+// part[8][4][16][16] f32; ssq [8][16] f32 (sums of squares per wavefront and row, when pro_norm).
+// On return (kLinDone) every thread may read part and ssq.
+// PACK: how many of the three terms one multiply covers.  The multiply has 16 batch columns; up
+// to 8 staged rows leave half of them free, so columns 0..7 take the hi term and columns 8..15
+// the mid term of the same rows (PACK 2: two multiplies per fragment, the lo term alone in the
 // second, on accumulators of its own); up to 4 staged rows take hi | mid | lo in columns 0..3 |
 // 4..7 | 8..11 (PACK 3: one multiply).  The column groups are added up once, at the end.
-template <int PACK, class RowPtr, class SrcRow, class Wait>
+template <int PACK, class RowOff, class SrcRow, class Wait>
 __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const TaskDesc& t, float* lds, float* ssq, const MfmaGeom& G,
-                                                    RowPtr row_ptr, SrcRow src_row, bool pro_norm, const uint16_t* gain,
-                                                    Wait wait_fn) {
+                                                    const uint16_t* wbase, RowOff row_off, SrcRow src_row, bool pro_norm,
+                                                    const uint16_t* gain, Wait wait_fn) {
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const uint32_t K = G.K, nb = G.nb, nrt = G.nrt, Kt1 = G.Kt1, Kt = G.Kt, ntile = G.ntile;
-  const uint32_t xstride = G.xstride, xplane = G.xplane;
-  uint16_t* xbase = (uint16_t*)lds;
+  const uint32_t K = G.K, nb = G.nb, nrt = G.nrt, Kc = G.Kc, nchunk = G.nchunk, xstride = G.xstride;
+  const uint32_t nrtw = G.nrtw, kgpr = G.kgpr, S = G.ks;
+  float* xs = lds;
   float* part = lds;
   const uint32_t frow = lane & 15u, fk = (uint32_t)(lane >> 4) * 8u;
-  const uint32_t kclamp = K - fk - 8u;   // the last fragment start that stays inside the row
-  f32x4 acc[4], acc_lo[4];   // (acc_lo: the lo plane's products when PACK == 2)
+  // slot group q of a round: k-group offset inside the round, byte offset of its row tile's row
+  const uint32_t sh = kgpr == 4u ? 0u : (kgpr == 2u ? 1u : 2u);   // q >> sh = k-group offset
+  uint32_t wq[4];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) acc[j] = acc_lo[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  u32x4 wfrag[kMfmaRound];
-  const uint32_t s_lo = G.my_slice * G.slice_len;
-  // a round of a long slice (nf >= 16): 16 consecutive fragments of one (input tile, row tile)
-  auto request_run = [&](const uint16_t* wp, uint32_t k) {
-#pragma unroll
-    for (int q = 0; q < kMfmaRound; ++q) wfrag[q] = ld_stream16(wp + min(k + (uint32_t)q * 32u, kclamp));
+  for (int q = 0; q < 4; ++q) {
+    const uint32_t j = kgpr == 4u ? 0u : (kgpr == 2u ? (uint32_t)q & 1u : (uint32_t)q);
+    wq[q] = row_off(min(G.my_g + G.rg * j, nrt - 1u));
+  }
+  // fragment at input k of the row at byte offset ro: this lane's 8 inputs start at k + fk, or
+  // are the row's last 8 when that lies past its end (their staged inputs are zeros)
+  auto ld_frag = [&](uint32_t ro, uint32_t k) {
+    const uint32_t off = ro + 2u * min(k + fk, K - 8u);
+    return __builtin_nontemporal_load((const MPK_GLOBAL u32x4*)((const MPK_GLOBAL char*)wbase + off));
   };
-  // a round of a short slice (nf = 4 or 8, one row tile): the slices of `tpr` consecutive input tiles
-  auto request_span = [&](const uint16_t* wp, uint32_t tile) {
-#pragma unroll
-    for (int q = 0; q < kMfmaRound; ++q) {
-      const uint32_t k = (tile + ((uint32_t)q >> G.lognf)) * Kt + s_lo + ((uint32_t)q & (G.nf - 1u)) * 32u;
-      wfrag[q] = ld_stream16(wp + min(k, kclamp));
-    }
+  // the wavefront's run of k-groups in chunk c; a chunk takes an even number of round slots
+  // (>= 2), so that even slots always use fragment buffer A and odd ones B
+  auto chunk_kgs = [&](uint32_t c) { return (min(Kc, K - c * Kc) + 127u) >> 7; };
+  auto run_lo = [&](uint32_t c) { return G.my_s * chunk_kgs(c) / S; };
+  auto run_hi = [&](uint32_t c) { return nrtw ? (G.my_s + 1u) * chunk_kgs(c) / S : 0u; };
+  auto slots = [&](uint32_t c) {
+    const uint32_t lo = run_lo(c), hi = run_hi(c);
+    const uint32_t n = hi > lo ? (hi - lo + kgpr - 1u) / kgpr : 0u;
+    return max(2u, (n + 1u) & ~1u);
   };
+  // requests the 16 fragments of round slot (c, i) into buf; buf[4 Q + u] = fragment u of slot
+  // group Q
+  auto request_round = [&](u32x4* buf, uint32_t c, uint32_t i) {
+    if (c >= nchunk) return;
+    const uint32_t kg0 = run_lo(c) + i * kgpr, hi = run_hi(c);
+    if (kg0 >= hi) return;
+    const uint32_t k0 = c * Kc;
+    static_for<0, 4>([&](auto Qc) {
+      constexpr uint32_t Q = (uint32_t)decltype(Qc)::value;
+      const uint32_t kg = kg0 + (Q >> sh);
+      const bool rowok = kgpr == 1u ? Q < nrtw : true;
+      if (kg < hi && rowok) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) buf[4 * Q + u] = ld_frag(wq[Q], k0 + kg * 128u + (uint32_t)u * 32u);
+      }
+    });
+  };
+  // RMSNorm gains of the pairs of this thread: column offsets j * 1024 + tcol of a chunk (weights:
+  // chunk 0's are requested before the event)
+  const uint32_t tcol = 2u * threadIdx.x;
+  uint32_t gq[4];
+  auto request_gains = [&](uint32_t c) {
+    const uint32_t k0 = c * Kc, klen = min(Kc, K - k0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (pro_norm && (uint32_t)j * 1024u < klen) gq[j] = *as_global((const uint32_t*)(gain + k0 + min((uint32_t)j * 1024u + tcol, klen - 2u)));
+  };
+  u32x4 wA[16], wB[16];
   const bool preload = !(a.flags & kNoPreloadBit);   // off: the ablation of Section 6.5, Fig. 10
-  if (preload && G.has_work) {
-    if (G.nf >= (uint32_t)kMfmaRound) request_run(row_ptr(G.my_rt0), s_lo);
-    else request_span(row_ptr(G.my_rt0), 0u);
+  // Before the event only the first round is requested: a wavefront sees its loads complete in
+  // the order it issued them, so whatever is requested now stands between the event and the
+  // staged input.  The second round follows the staging.
+  request_gains(0u);
+  if (preload) {
+    request_round(wA, 0u, 0u);
     asm volatile("; first round requested" ::: "memory");
   }
   {
@@ -943,143 +1014,129 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
     if (w != kLinDone) return w;   // aborted or pre-empted: the requested weights are dropped
   }
   trace_mark(a, t, 1);
-  if (!preload && G.has_work) {
-    if (G.nf >= (uint32_t)kMfmaRound) request_run(row_ptr(G.my_rt0), s_lo);
-    else request_span(row_ptr(G.my_rt0), 0u);
+  if (!preload) {
+    request_round(wA, 0u, 0u);
     asm volatile("; first round requested after the event" ::: "memory");
   }
-  // Staging.  A pass of Kt1 inputs x nb rows is dealt to the threads in pairs, 8 slots per thread;
-  // the row of a slot is the same for the whole wavefront (no divisions, no per-row selects):
-  // 1024-input passes: slot q = row q, pair = thread; 512-input passes: row 2 q + thread / 256,
-  // pair = thread % 256.  A pass is requested (coherent loads into registers) while the previous
-  // tile is being multiplied and converted into the other buffer afterwards.
+  // Staging: a chunk is dealt to the threads as 32 pairs of inputs each; pair slot q belongs to
+  // half-row q / 2 (a half-row is Kc / 2 inputs up to 8 staged rows, a whole row of Kc above),
+  // the same for every thread, so that the sums of squares need no indexing.
   static_assert(kThreads == 512, "the slot -> (row, pair) mapping assumes 512 threads");
-  const uint32_t half = Kt1 == 512u ? 1u : 0u;
-  const uint32_t row_lo = half ? (wave >> 2) : 0u, pair = half ? (threadIdx.x & 255u) : threadIdx.x;
-  float sqq[8];
+  const uint32_t wide = nb > 8u ? 1u : 0u;
+  float rowsum = 0.f;   // lane b: this wavefront's sum of squares of staged row b
+  auto stage = [&](uint32_t c) {
+    float sqq[16];
 #pragma unroll
-  for (int q = 0; q < 8; ++q) sqq[q] = 0.f;
-  float2 sv[8];
-  auto stage_issue = [&](uint32_t pass) {
-    const uint32_t k0 = pass * Kt1, klen = min(Kt1, K - k0);
+    for (int q = 0; q < 16; ++q) sqq[q] = 0.f;
+    const uint32_t k0 = c * Kc, klen = min(Kc, K - k0), kpad = (klen + 127u) & ~127u;
+    // Two passes of 16 pairs: all 32 at once, next to the 128 registers of requested weights,
+    // do not fit the register file.  Addresses are a uniform row base plus one per-thread offset
+    // (scalar base registers: 32 address pairs in vector registers would be moved to scratch
+    // memory); a pair past the end of the row re-reads the row's last pair and is stored as zeros.
+    if (c) request_gains(c);
+    static_for<0, 2>([&](auto Hc) {
+      constexpr int H = decltype(Hc)::value;
+      float2 sv[16];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const uint32_t b = ((uint32_t)q << half) + row_lo;
-      sv[q] = make_float2(0.f, 0.f);
-      if (b < nb && 2u * pair < klen) sv[q] = ld_act2(src_row(b) + k0 + 2u * pair);
-    }
-  };
-  auto stage_write = [&](uint32_t pass) {
-    const uint32_t k0 = pass * Kt1, klen = min(Kt1, K - k0);
-    uint16_t* d0 = G.whole ? xbase + k0 : xbase + (size_t)(pass & 1u) * G.xbuf;
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const uint32_t b = ((uint32_t)q << half) + row_lo;
-      if (b < nb) {
-        float2 w2 = sv[q];
-        if (pro_norm && 2u * pair < klen) {
-          sqq[q] = fmaf(w2.x, w2.x, fmaf(w2.y, w2.y, sqq[q]));
-          const uint32_t g2 = *as_global((const uint32_t*)(gain + k0 + 2u * pair));
-          w2.x *= bf16_lo(g2);
-          w2.y *= bf16_hi(g2);
-        }
-        uint32_t hi, mid, lo;
-        split_hi_mid_lo(w2.x, w2.y, &hi, &mid, &lo);
-        uint16_t* d = d0 + (size_t)b * xstride + 2u * pair;
-        *(uint32_t*)d = hi;
-        *(uint32_t*)(d + xplane) = mid;
-        *(uint32_t*)(d + 2u * xplane) = lo;
-      }
-    }
-  };
-  const uint32_t npass = (K + Kt1 - 1u) / Kt1;
-  stage_issue(0);
-  stage_write(0);
-  if (G.whole && npass > 1u) {
-    stage_issue(1);
-    stage_write(1);
-  }
-  lds_barrier();
-  trace_mark(a, t, 2);
-  // four fragments of the round (positions q0 .. q0 + 3) against the three planes, inputs
-  // kk .. kk + 127 of the current tile; whole groups run without per-step tests, their LDS reads
-  // ahead of the multiplies.  b0 / b1 / b2: this lane's operand address for the first, second and
-  // third multiply of a fragment (PACK 1: hi, mid, lo of its column's row; PACK 2: hi or mid by
-  // column half, then lo; PACK 3: the plane of its column group).
-  constexpr int kMul = PACK == 1 ? 3 : (PACK == 2 ? 2 : 1);
-  auto consume4 = [&](f32x4& c, f32x4& c_lo, const uint16_t* b0, const uint16_t* b1, const uint16_t* b2, auto q0c, uint32_t kk, uint32_t s_hi) {
-    constexpr int q0 = decltype(q0c)::value;
-    auto mul = [&](const u32x4& w, const u32x4& x0, const u32x4& x1, const u32x4& x2) {
-      const bf16x8 av = __builtin_bit_cast(bf16x8, w);
-      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0), c, 0, 0, 0);
-      if (kMul == 2) c_lo = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1), c_lo, 0, 0, 0);
-      if (kMul == 3) {
-        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x2), c, 0, 0, 0);
-      }
-    };
-    if (kk + 128u <= s_hi) {
-      u32x4 x0[4], x1[4], x2[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        x0[u] = *(const u32x4*)(b0 + kk + u * 32u);
-        if (kMul >= 2) x1[u] = *(const u32x4*)(b1 + kk + u * 32u);
-        if (kMul >= 3) x2[u] = *(const u32x4*)(b2 + kk + u * 32u);
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) mul(wfrag[q0 + u], x0[u], x1[u], x2[u]);
-    } else {
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (kk + u * 32u < s_hi) {
-          u32x4 y0 = *(const u32x4*)(b0 + kk + u * 32u), y1 = y0, y2 = y0;
-          if (kMul >= 2) y1 = *(const u32x4*)(b1 + kk + u * 32u);
-          if (kMul >= 3) y2 = *(const u32x4*)(b2 + kk + u * 32u);
-          mul(wfrag[q0 + u], y0, y1, y2);
+      for (int qq = 0; qq < 16; ++qq) {
+        const uint32_t q = (uint32_t)(16 * H + qq), hr = q >> 1;
+        const uint32_t b = wide ? hr : hr >> 1;
+        const uint32_t c0 = (wide ? 0u : (hr & 1u) * 2048u) + (q & 1u) * 1024u;   // uniform
+        if (b < nb && c0 < klen) {
+          const float* rb = src_row(b) + k0;
+          sv[qq] = ld_act2(rb + min(c0 + tcol, klen - 2u));
         }
       }
+#pragma unroll
+      for (int qq = 0; qq < 16; ++qq) {
+        const uint32_t q = (uint32_t)(16 * H + qq), hr = q >> 1;
+        const uint32_t b = wide ? hr : hr >> 1;
+        const uint32_t c0 = (wide ? 0u : (hr & 1u) * 2048u) + (q & 1u) * 1024u;
+        const uint32_t col = c0 + tcol;
+        if (b < nb && c0 < klen) {
+          float2 w2 = col < klen ? sv[qq] : make_float2(0.f, 0.f);
+          if (pro_norm) {
+            sqq[q >> 1] = fmaf(w2.x, w2.x, fmaf(w2.y, w2.y, sqq[q >> 1]));
+            const uint32_t g2 = wide ? gq[q & 1u] : gq[q & 3u];
+            w2.x *= bf16_lo(g2);
+            w2.y *= bf16_hi(g2);
+          }
+          if (col < kpad) *(float2*)(xs + (size_t)b * xstride + col) = w2;   // zeros between klen and the end of its k-group
+        }
+      }
+    });
+    if (pro_norm) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const float v = wave_sum_dpp(sqq[q]);
+        if ((uint32_t)lane == (wide ? (uint32_t)q : (uint32_t)q >> 1)) rowsum += v;
+      }
     }
   };
-  for (uint32_t tile = 0; tile < ntile; ++tile) {
-    const uint32_t klen = min(Kt, K - tile * Kt);
-    if (!G.whole && tile + 1u < ntile) stage_issue(tile + 1u);   // in flight during this tile's arithmetic
-    const uint16_t* cx = G.whole ? xbase : xbase + (size_t)(tile & 1u) * G.xbuf;
-    // (frow = this lane's batch column in the multiply)
-    const uint32_t xrow = PACK == 1 ? frow % nb : (PACK == 2 ? (frow & 7u) % nb : (frow & 3u) % nb);
-    const uint32_t xpl0 = PACK == 1 ? 0u : (PACK == 2 ? (frow >> 3) : min(frow >> 2, 2u));   // plane of the first multiply
-    const uint16_t* b0 = cx + (size_t)xpl0 * xplane + (size_t)xrow * xstride + fk;
-    const uint16_t* b1 = cx + (size_t)(PACK == 1 ? 1u : 2u) * xplane + (size_t)xrow * xstride + fk;
-    const uint16_t* b2 = cx + (size_t)2u * xplane + (size_t)xrow * xstride + fk;
-    const uint32_t s_hi = min(s_lo + G.slice_len, (klen + 31u) & ~31u);
-    if (G.has_work && s_lo < s_hi) {
-      if (G.nf >= (uint32_t)kMfmaRound) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const uint32_t rt = G.my_rt0 + (uint32_t)j * 8u;
-          if (rt < nrt && (G.ks == 1u || j == 0)) {
-            const uint16_t* wp = row_ptr(rt);
-            for (uint32_t kk = s_lo; kk < s_hi; kk += 32u * kMfmaRound) {
-              if (!(tile == 0 && j == 0 && kk == s_lo)) request_run(wp, tile * Kt + kk);
-              static_for<0, kMfmaRound / 4>([&](auto gc) {
-                constexpr int g = decltype(gc)::value;
-                consume4(acc[j], acc_lo[j], b0, b1, b2, std::integral_constant<int, 4 * g>{}, kk + 128u * g, s_hi);
-              });
+  // this lane's staged row and which term its column takes in the first multiply
+  const uint32_t xrow = min(PACK == 1 ? frow : (PACK == 2 ? (frow & 7u) : (frow & 3u)), nb - 1u);
+  const float* xl = xs + (size_t)xrow * xstride + fk;
+  f32x4 acc[4], acc_lo[4];   // (acc_lo: the lo term's products when PACK == 2)
+  // one round slot: multiplies what buf holds for slot (c, i) -- fragment u of every slot group
+  // against the three terms of that fragment's inputs, converted once per k-group -- and then
+  // requests slot (c2, i2), two ahead, into the same registers
+  auto step = [&](u32x4* buf, uint32_t c, uint32_t i, uint32_t c2, uint32_t i2) {
+    const uint32_t kg0 = run_lo(c) + i * kgpr, hi = run_hi(c);
+    if (kg0 < hi) {
+      static_for<0, 4>([&](auto Uc) {
+        constexpr uint32_t U = (uint32_t)decltype(Uc)::value;
+        u32x4 p0, p1, p2;   // operands of the first, second, third multiply
+        static_for<0, 4>([&](auto Qc) {
+          constexpr uint32_t Q = (uint32_t)decltype(Qc)::value;
+          const uint32_t kg = kg0 + (Q >> sh);
+          const bool rowok = kgpr == 1u ? Q < nrtw : true;
+          if (kg < hi && rowok) {
+            if (Q == 0u || (Q >> sh) != ((Q - 1u) >> sh)) {   // first slot group of its k-group
+              const float* src = xl + kg * 128u + U * 32u;
+              const float4 x0 = *(const float4*)src, x1 = *(const float4*)(src + 4);
+              u32x4 h, m, l;
+              split8(x0, x1, &h, &m, &l);
+              if (PACK == 1) { p0 = h; p1 = m; p2 = l; }
+              if (PACK == 2) { p0 = select4(frow < 8u, h, m); p1 = l; }
+              if (PACK == 3) p0 = select4(frow < 4u, h, select4(frow < 8u, m, l));
+            }
+            const bf16x8 av = __builtin_bit_cast(bf16x8, buf[4 * Q + U]);
+            acc[Q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, p0), acc[Q], 0, 0, 0);
+            if (PACK == 2) acc_lo[Q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, p1), acc_lo[Q], 0, 0, 0);
+            if (PACK == 1) {
+              acc[Q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, p1), acc[Q], 0, 0, 0);
+              acc[Q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, p2), acc[Q], 0, 0, 0);
             }
           }
-        }
-      } else {
-        // short slices: a round holds the slices of tpr consecutive input tiles; this tile's
-        // slice sits at groups g0 .. g0 + nf / 4 - 1 of the round
-        const uint32_t g0 = (tile & (G.tpr - 1u)) * (G.nf >> 2), g1 = g0 + (G.nf >> 2);
-        if (g0 == 0u && tile != 0u) request_span(row_ptr(G.my_rt0), tile);
-        static_for<0, kMfmaRound / 4>([&](auto gc) {
-          constexpr uint32_t g = (uint32_t)decltype(gc)::value;
-          if (g >= g0 && g < g1) consume4(acc[0], acc_lo[0], b0, b1, b2, std::integral_constant<int, 4 * (int)g>{}, s_lo + (g - g0) * 128u, s_hi);
         });
-      }
+      });
     }
-    if (!G.whole && tile + 1u < ntile) stage_write(tile + 1u);   // into the other buffer: nobody reads it now
+    request_round(buf, c2, i2);
+  };
+  for (uint32_t c = 0; c < nchunk; ++c) {
+    if (c) lds_barrier();   // everybody has finished with the previous chunk
+    stage(c);
+    if (c == 0) {
+      // behind the staging loads.  (The slot number goes through an empty asm so that the 16
+      // addresses are worked out here: computed next to the first round's, ahead of the staging,
+      // they would wait in scratch memory.)
+      uint32_t one = 1u;
+      asm volatile("" : "+s"(one));
+      request_round(wB, 0u, one);
+    }
     lds_barrier();
+    if (c == 0) {
+      trace_mark(a, t, 2);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] = acc_lo[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const uint32_t ns = slots(c);
+    for (uint32_t i = 0; i < ns; i += 2u) {
+      const bool wrap = i + 2u >= ns;   // the slots two ahead are the first two of the next chunk
+      const uint32_t c2 = wrap ? c + 1u : c, i2 = wrap ? 0u : i + 2u;
+      step(wA, c, i, c2, i2);
+      step(wB, c, i + 1u, c2, i2 + 1u);
+    }
   }
   trace_mark(a, t, 8);
   // ---- the column groups of a packed multiply added up: afterwards column b < nb holds the sum
@@ -1093,40 +1150,39 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
         else acc[j][i] = v + __shfl(v, lane + 4, 64) + __shfl(v, lane + 8, 64);       // hi + mid + lo, 4 columns apart
       }
   }
-  // ---- partial tiles -> LDS.  part[wave][j][row 0..15][col 0..15]
+  lds_barrier();   // nobody reads the staged input any more: its space takes the partial tiles
+  // ---- partial tiles -> LDS.  part[wave][slot group][row 0..15][col 0..15]
 #pragma unroll
   for (int j = 0; j < 4; ++j)
 #pragma unroll
     for (int i = 0; i < 4; ++i) part[((wave * 4 + j) * 16 + (lane >> 4) * 4 + i) * 16 + (lane & 15)] = acc[j][i];
-  if (pro_norm) {
-    float rowsum = 0.f;   // lane b: this wavefront's sum of squares of staged row b
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const float v = wave_sum(sqq[q]);
-      if ((uint32_t)lane == ((uint32_t)q << half) + row_lo) rowsum += v;
-    }
-    if (lane < 16) ssq[wave * 16 + lane] = rowsum;
-  }
+  if (pro_norm && lane < 16) ssq[wave * 16 + lane] = rowsum;
   lds_barrier();
   return kLinDone;
 }
 
-template <class RowPtr, class SrcRow, class Wait>
+template <class RowOff, class SrcRow, class Wait>
 __device__ __forceinline__ uint32_t mfma_job(const StepArgs& a, const TaskDesc& t, float* lds, float* ssq, const MfmaGeom& G,
-                                             RowPtr row_ptr, SrcRow src_row, bool pro_norm, const uint16_t* gain,
-                                             Wait wait_fn) {
-  if (G.nb <= 4u) return mfma_job_packed<3>(a, t, lds, ssq, G, row_ptr, src_row, pro_norm, gain, wait_fn);
-  if (G.nb <= 8u) return mfma_job_packed<2>(a, t, lds, ssq, G, row_ptr, src_row, pro_norm, gain, wait_fn);
-  return mfma_job_packed<1>(a, t, lds, ssq, G, row_ptr, src_row, pro_norm, gain, wait_fn);
+                                             const uint16_t* wbase, RowOff row_off, SrcRow src_row, bool pro_norm,
+                                             const uint16_t* gain, Wait wait_fn) {
+  if (G.nb <= 4u) return mfma_job_packed<3>(a, t, lds, ssq, G, wbase, row_off, src_row, pro_norm, gain, wait_fn);
+  if (G.nb <= 8u) return mfma_job_packed<2>(a, t, lds, ssq, G, wbase, row_off, src_row, pro_norm, gain, wait_fn);
+  return mfma_job_packed<1>(a, t, lds, ssq, G, wbase, row_off, src_row, pro_norm, gain, wait_fn);
 }
 
 // Dot product of weight row r (16-row tile r / 16) with batch column bb from the partial tiles a
-// job left in LDS: the K slices added in a fixed order.
+// job left in LDS: the row tile's slot groups of slice 0, then those of slice 1, ... added in
+// that order.
 __device__ __forceinline__ float mfma_dot(const float* part, const MfmaGeom& G, uint32_t r, uint32_t bb) {
   const uint32_t rt = r >> 4, row = r & 15u;
-  if (G.ks == 1u) return part[(((rt & 7u) * 4 + (rt >> 3)) * 16 + row) * 16 + bb];
+  const uint32_t g = rt % G.rg, j = rt / G.rg;
+  const uint32_t n = mfma_group_tiles(G.nrt, G.rg, g);   // row tiles of the wavefronts of group g
+  const uint32_t q0 = n >= 3u ? j : (n == 2u ? j : 0u), dq = n >= 3u ? 4u : (n == 2u ? 2u : 1u);
   float v = 0.f;
-  for (uint32_t sl = 0; sl < G.ks; ++sl) v += part[(((sl * G.nrt2 + rt) * 4) * 16 + row) * 16 + bb];
+  for (uint32_t s = 0; s < G.ks; ++s) {
+    const uint32_t w = s * G.rg + g;
+    for (uint32_t q = q0; q < 4u; q += dq) v += part[(((w * 4u + q) * 16u) + row) * 16u + bb];
+  }
   return v;
 }
 
@@ -1152,10 +1208,10 @@ __device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const St
   const uint32_t parts = splitk ? (t.p3 & 0xFFu) : 1u, my_part = splitk ? (t.p3 >> 8) : 0u;
   const uint32_t Hs = t.ld_out / parts;              // columns of the real output
   const uint32_t row0 = t.c0 - my_part * Hs, ldw = splitk ? t.p1 : K;
-  auto row_ptr = [&](uint32_t rt) {
+  auto row_off = [&](uint32_t rt) {
     const uint32_t r = min(rt * 16u + frow, R - 1u);   // rows past the end repeat the last one
     const uint32_t wrow = gateup ? (row0 + (r >> 1) + ((r & 1u) ? t.p0 : 0u)) : row0 + r;
-    return W + (size_t)wrow * ldw + fk;
+    return wrow * ldw * 2u;   // bytes; the host checks that a weight matrix stays below 4 GB
   };
   auto src_row = [&](uint32_t b) { return t.in + (size_t)(t.b0 + b) * t.ld_in; };
   const bool pro_norm = t.flags & TF_PRO_NORM;
@@ -1174,7 +1230,7 @@ __device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const St
     return kLinDone;
   };
   {
-    const uint32_t w = mfma_job(a, t, lds, ssq, G, row_ptr, src_row, pro_norm, (const uint16_t*)t.w2, wait_fn);
+    const uint32_t w = mfma_job(a, t, lds, ssq, G, W, row_off, src_row, pro_norm, (const uint16_t*)t.w2, wait_fn);
     if (w != kLinDone) return w;
   }
   trace_mark(a, t, 3);
@@ -1421,13 +1477,13 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
   }
   lds_barrier();
   const uint32_t frow = lane & 15u, fk = (uint32_t)(lane >> 4) * 8u;
-  auto row_ptr = [&](uint32_t rt) {
+  auto row_off = [&](uint32_t rt) {
     const uint32_t r = (tile0 + rt) * 16u + frow;   // row of the expert's gate/up-interleaved (or plain) order
     const uint32_t wrow = gateup ? ((r >> 1) + ((r & 1u) ? t.p0 : 0u)) : r;
-    return W + (size_t)wrow * K + fk;
+    return wrow * K * 2u;   // bytes from the expert's first row
   };
-  auto src_row = [&](uint32_t b) { return t.in + (size_t)rowin[b] * t.ld_in; };
-  mfma_job(a, t, lds, ssq, G, row_ptr, src_row, pro_norm, (const uint16_t*)t.w2, []() -> uint32_t { return kLinDone; });
+  auto src_row = [&](uint32_t b) { return t.in + (size_t)__builtin_amdgcn_readfirstlane(rowin[b]) * t.ld_in; };   // uniform: scalar base addresses
+  mfma_job(a, t, lds, ssq, G, W, row_off, src_row, pro_norm, (const uint16_t*)t.w2, []() -> uint32_t { return kLinDone; });
   const uint32_t ncols = (ntile * 16u) >> gateup, col0 = (tile0 * 16u) >> gateup;
   for (uint32_t i = threadIdx.x; i < ncols * ne; i += kThreads) {
     const uint32_t cc = i / ne, bb = i % ne;

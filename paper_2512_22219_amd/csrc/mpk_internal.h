@@ -179,15 +179,14 @@ mpk_status build_dag_graph(uint32_t n_tasks, const uint32_t* pairs, size_t n_pai
 inline uint32_t moe_meta_words(uint32_t E, uint32_t P) { return 2 + 3 * E + 3 * P; }
 constexpr uint32_t kMoeMaxExperts = 512, kMoeMaxPairs = 256, kMoeMaxTopK = 16;
 
-// Matrix-core jobs (batch 5..16 and expert jobs) stage the input in LDS as three bf16 planes, one K
-// tile of this many inputs at a time, two buffers; one definition for the host's LDS requirement
-// and the kernels' layout.
-constexpr uint32_t mfma_ktile(uint32_t nb) { return nb <= 8u ? 1024u : 512u; }
-// LDS floats of a job with nb staged rows: two buffers x three planes x nb rows x (tile + 8) bf16
-// (an input of at most two tiles, staged whole, fits the same space), reused for the partial tiles
-// [8 wavefronts][4][16][16] f32 at the end.
+// Matrix-core jobs (batch 5..16 and expert jobs) stage the input in LDS as fp32, a chunk of this
+// many inputs at a time; one definition for the host's LDS requirement and the kernels' layout.
+constexpr uint32_t mfma_kchunk(uint32_t nb) { return nb <= 8u ? 4096u : 2048u; }
+constexpr uint32_t kMfmaXPad = 32;   // floats between staged rows beyond the chunk (bank spread)
+// LDS floats of a job with nb staged rows: nb rows x (chunk + pad) f32, reused for the partial
+// tiles [8 wavefronts][4][16][16] f32 at the end.
 constexpr uint32_t mfma_x_floats(uint32_t nb) {
-  const uint32_t x = 3u * nb * (mfma_ktile(nb) + 8u);
+  const uint32_t x = nb * (mfma_kchunk(nb) + kMfmaXPad);
   return x > 8u * 4u * 256u ? x : 8u * 4u * 256u;
 }
 // ... of the expert jobs of a graph with this batch size: an expert holds between 1 and min(batch,
