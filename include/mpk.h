@@ -174,6 +174,14 @@ typedef struct mpk_compile_options {
   uint32_t xcd_balance;     /* 1 = measure those speeds on this GPU at compile time (a streaming
                                kernel over the LM-head weights, about a millisecond) when
                                worker_weight_permille is all 0.  Not with host_only              */
+  uint32_t no_attn_balance; /* 1 = every sequence keeps its own attn_chunks attention tasks.  By
+                               default (batch > 1, merge fused into the attention tasks) the
+                               batch x attn_chunks tasks of a KV head are dealt to the sequences
+                               in proportion to their current lengths when the step runs, one at
+                               least each: with a ragged batch an attention operator otherwise
+                               ends with the longest sequence's chunks (the run-time imbalance
+                               Section 5.2 meets with just-in-time hand-out; here the split is
+                               a pure function of the positions, so results stay reproducible)   */
 } mpk_compile_options;
 
 typedef struct mpk_graph mpk_graph;

@@ -54,7 +54,7 @@ class OpSpec:
 
 
 def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: int = 1,
-              greedy_loop: bool = False):
+              greedy_loop: bool = False, attn_balance: bool = False):
     """Operator list of one decode step for model shape `s` (synth.gen.ModelShape) under the
     given fusion flags, in execution order.
 
@@ -71,7 +71,12 @@ def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: 
     well.  Its output tensor is then the partial sums [B][parts x H] (part p of row r at column
     p H + r); a task reads only its part of the input rows.  Whoever reads residual-stream element
     (b, r) afterwards reads all `parts` partial sums of it (the task that adds them up is only
-    known at run time; it also adds the residual, so every part task statically reads that)."""
+    known at run time; it also adds the residual, so every part task statically reads that).
+
+    attn_balance (merge fused into the attention tasks, batch > 1): the batch x C chunk tasks of a
+    KV head are dealt to the sequences in proportion to their lengths when the step runs (the
+    run-time imbalance of Section 5.2), so which sequence's query and new key/value a chunk task
+    reads is a run-time fact: statically it reads those columns of every row."""
     B, H, d, nq, nkv = s.batch, s.hidden, s.head_dim, s.n_q_heads, s.n_kv_heads
     F, V, C = s.ffn, s.vocab, attn_chunks
     grp = nq // nkv
@@ -93,7 +98,8 @@ def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: 
             qsrc = p + "rk"
         ops.append(OpSpec(p + "attn_partial", K_ATTN_PARTIAL, l, p + "part", B,
                           nkv * C * grp * (d + 2), grp * (d + 2), [qsrc],
-                          {"C": C, "grp": grp, "d": d, "nq": nq, "nkv": nkv}))
+                          {"C": C, "grp": grp, "d": d, "nq": nq, "nkv": nkv,
+                           "balance": bool(attn_balance and (fusion & F_MERGE) and B > 1)}))
         if fusion & F_MERGE:
             osrc, oK = p + "part", nkv * C * grp * (d + 2)
         else:
@@ -237,6 +243,8 @@ def read_elements(op: OpSpec, tb: int, tc: int, tile: int, shapes: dict, explici
         C, grp, d, nq, nkv = M["C"], M["grp"], M["d"], M["nq"], M["nkv"]
         m = mask(op.ins[0])
         per = grp * (d + 2)
+        if M.get("balance"):
+            b0, b1 = 0, op.rows                         # any sequence may be dealt to this task
         for u in range(c0 // per, c1 // per):
             g, c = divmod(u, C)
             m[b0:b1, g * grp * d:(g + 1) * grp * d] = True         # the group's query heads

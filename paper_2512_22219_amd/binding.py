@@ -54,7 +54,8 @@ class CompileOptions(C.Structure):
                  "force_aot", "no_preload", "host_only", "spin_timeout_ms", "debug_flags",
                  "tiles_moe", "greedy_loop", "kv_batch")] + [("worker_weight_permille", C.c_uint32 * 8),
                                                              ("no_lds_pages", C.c_uint32),
-                                                             ("xcd_balance", C.c_uint32)]
+                                                             ("xcd_balance", C.c_uint32),
+                                                             ("no_attn_balance", C.c_uint32)]
 
 
 class Stats(C.Structure):

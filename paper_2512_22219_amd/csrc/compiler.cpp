@@ -517,6 +517,7 @@ static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
       at.flags |= TF_ATTN_MERGE;
       at.side_out_tensor = o_body;
       at.p2 = l * B * nkv;   // first arrival counter of this layer
+      if (B > 1 && !o.no_attn_balance) at.flags |= TF_ATTN_BALANCE;
     }
     int x1 = b.new_tensor(B, H);
     if (f & MPK_FUSE_RESID) {
@@ -793,6 +794,9 @@ static void input_rects(const mpk_model_config& c, const HostOp& op, uint32_t ti
       break;
     case MPK_OP_ATTN_PARTIAL: {
       uint32_t per = grp * (d + 2), C = op.p1;
+      // chunk tasks dealt to the sequences at run time: which sequence's query a task reads is
+      // not known statically, so it depends on all of them
+      if (op.flags & TF_ATTN_BALANCE) { b0 = 0; b1 = op.rows; }
       for (uint32_t u = c0 / per; u < c1 / per; ++u) {
         uint32_t gidx = u / C, ch = u % C;
         (void)ch;
@@ -1034,6 +1038,12 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
   } else {
     if (c.top_k || c.expert_ffn) { set_error("top_k / expert_ffn set without n_experts"); return MPK_ERR_INVALID_ARG; }
     if (!c.ffn) { set_error("ffn is zero"); return MPK_ERR_INVALID_ARG; }
+  }
+  if (c.batch > 4) {
+    // the matrix-core body addresses a weight matrix with 32-bit byte offsets from its first row
+    const uint64_t rows = std::max<uint64_t>({c.vocab, 2ull * c.ffn, (uint64_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, c.hidden});
+    const uint64_t inner = std::max<uint64_t>({c.hidden, c.ffn, (uint64_t)c.n_q_heads * c.head_dim});
+    if (rows * inner * 2ull >= (1ull << 32)) { set_error("a weight matrix of 4 GB or more is unsupported at batch sizes above 4"); return MPK_ERR_UNSUPPORTED; }
   }
   if (c.head_dim != 64 && c.head_dim != 128) { set_error("head_dim %u unsupported (64 or 128)", c.head_dim); return MPK_ERR_UNSUPPORTED; }
   if (c.n_q_heads % c.n_kv_heads) { set_error("n_q_heads must be a multiple of n_kv_heads"); return MPK_ERR_UNSUPPORTED; }

@@ -1947,6 +1947,52 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
   return true;
 }
 
+// TF_ATTN_BALANCE: the batch x C chunk tasks of a KV head, numbered v = row x C + chunk, are dealt
+// to the sequences in proportion to their lengths, every sequence at least one: sequence b gets
+// 1 + floor((batch x C - batch) x len_b / total) tasks, and what is left over (fewer than batch)
+// goes, one at a time, to the sequence whose chunks are longest at that moment (lowest index on
+// ties).  A pure function of the positions, worked out by every wavefront for itself (lane b <
+// batch holds sequence b; batch <= 16).  Returns the sequence of task v, the task's chunk number
+// there, the sequence's chunk count and its first task.
+__device__ __forceinline__ void attn_deal(const StepArgs& a, uint32_t C, uint32_t v, uint32_t* seq, uint32_t* chunk,
+                                          uint32_t* chunks, uint32_t* first) {
+  const uint32_t B = a.g->batch, li = threadIdx.x & 15u;
+  uint32_t w = 0;
+  if (li < B) {
+    const int32_t pos = a.positions[li] + (int32_t)a.step;
+    w = (pos >= 0 && (uint32_t)pos < a.g->max_seq) ? (uint32_t)pos + 1u : 1u;   // (a bad position is reported by its tasks)
+  }
+  auto row_sum = [&](uint32_t x) {   // over the 16 lanes of the row, in every lane
+#pragma unroll
+    for (uint32_t off = 1; off < 16; off <<= 1) x += (uint32_t)__shfl_xor((int)x, off, 16);
+    return x;
+  };
+  const uint32_t total = row_sum(w);
+  uint32_t cnt = li < B ? 1u + (uint32_t)((uint64_t)(B * C - B) * w / total) : 0u;
+  const uint32_t left = B * C - row_sum(cnt);   // uniform, < B
+  for (uint32_t r = 0; r < left; ++r) {
+    const float len = li < B ? (float)w / (float)cnt : -1.f;   // current chunk length of the sequence
+    float mx = len;
+#pragma unroll
+    for (uint32_t off = 1; off < 16; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 16));
+    const uint32_t who = (uint32_t)__ballot(len == mx) & 0xFFFFu;   // (the wavefront's first 16 lanes)
+    if (li == (uint32_t)__builtin_ctz(who)) ++cnt;
+  }
+  uint32_t end = cnt;   // inclusive prefix sum: first task after the sequence
+#pragma unroll
+  for (uint32_t off = 1; off < 16; off <<= 1) {
+    const uint32_t o = (uint32_t)__shfl_up((int)end, off, 16);
+    if (li >= off) end += o;
+  }
+  const uint32_t start = end - cnt;
+  const uint32_t mask = (uint32_t)__ballot(li < B && start <= v) & 0xFFFFu;
+  const uint32_t bsel = 31u - (uint32_t)__builtin_clz(mask);                  // start of sequence 0 is 0 <= v
+  *seq = bsel;
+  *first = (uint32_t)__builtin_amdgcn_readlane((int)start, bsel);
+  *chunks = (uint32_t)__builtin_amdgcn_readlane((int)cnt, bsel);
+  *chunk = v - *first;
+}
+
 // T4: split-KV decode attention for one (sequence, KV head, chunk).  Chunk c of C covers cache
 // rows [c*len/C, (c+1)*len/C) with len = position + 1, so the last chunk holds the new row.
 // Output per query head of the group: sum_t exp(s_t - m) V_t (D floats), m, l = sum_t exp(s_t - m).
@@ -1964,13 +2010,16 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
                                                   int32_t wait_ev, uint32_t* s_flag) {
   constexpr uint32_t d = D, grp = GRP, LPP = D / 8, PPW = 64 / LPP, NW = kThreads / 64;
   constexpr uint32_t stride = NW * PPW, per = grp * (d + 2);
-  const uint32_t nq = a.g->n_q, nkv = a.g->n_kv, C = t.p1;
-  const uint32_t b = t.b0, u = t.c0 / per, g = u / C, c = u % C;
+  const uint32_t nq = a.g->n_q, nkv = a.g->n_kv, Cs = t.p1;
+  const uint32_t bs = t.b0, u = t.c0 / per, g = u / Cs;   // the task's own row: where its partial result goes
+  // sequence, chunk and chunk count the task works on, first task of that sequence
+  uint32_t b = bs, c = u % Cs, C = Cs, v0 = bs * Cs;
+  if (t.flags & TF_ATTN_BALANCE) attn_deal(a, Cs, bs * Cs + c, &b, &c, &C, &v0);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   float* qs = lds;                       // [grp][d]
   float* wpart = qs + grp * d;           // [NW][grp][d + 2]: partial output, max, sum per wavefront
   uint32_t* flag = (uint32_t*)(wpart + NW * grp * (d + 2));
-  float* outp = t.out + (size_t)b * t.ld_out + t.c0;
+  float* outp = t.out + (size_t)bs * t.ld_out + t.c0;
   const int32_t pos = a.positions[b] + (int32_t)a.step;    // written by the host before the launch
   const bool bad_pos = pos < 0 || (uint32_t)pos >= a.g->max_seq;
   const uint32_t len = bad_pos ? 0u : (uint32_t)pos + 1;
@@ -2209,11 +2258,22 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
     if (threadIdx.x == 0) {
       uint32_t* cnt = a.g->grp_counters + t.p2 + b * nkv + g;
       uint32_t old = __hip_atomic_fetch_add(as_global(cnt), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      *flag = ((old + 1u) % C == 0u) ? 1u : 0u;   // every step adds exactly C
+      if (t.flags & TF_ATTN_BALANCE) {
+        // the count changes with the lengths from step to step: the last arrival puts the counter
+        // back to zero (nobody else touches it before the next step's attention tasks)
+        *flag = (old + 1u == C) ? 1u : 0u;
+        if (old + 1u == C) st_act_u32(cnt, 0u);
+      } else {
+        *flag = ((old + 1u) % C == 0u) ? 1u : 0u;   // every step adds exactly C
+      }
     }
     __syncthreads();
     if (*flag) {
-      const float* part = t.out + (size_t)b * t.ld_out + (size_t)g * C * per;
+      // chunk k of the sequence is the partial result of task v0 + k, in that task's own slot
+      auto part_of = [&](uint32_t k) {
+        const uint32_t v = v0 + k;
+        return t.out + (size_t)(v / Cs) * t.ld_out + (size_t)(g * Cs + v % Cs) * per;
+      };
       float* o = const_cast<float*>(t.in2) + (size_t)b * nq * d + (size_t)g * grp * d;
       for (uint32_t i = threadIdx.x; i < grp * d; i += kThreads) {
         uint32_t j = i / d, dim = i % d;
@@ -2223,7 +2283,7 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
 #pragma unroll
           for (int k = 0; k < 8; ++k) {
             if (c0 + k < C) {
-              const float* pp = part + ((size_t)(c0 + k) * grp + j) * (d + 2);
+              const float* pp = part_of(c0 + k) + (size_t)j * (d + 2);
               mm[k] = ld_act(pp + d);
               ll[k] = ld_act(pp + d + 1);
               oo[k] = ld_act(pp + dim);
@@ -2356,7 +2416,7 @@ __device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, f
     if (D != 0) {
       // chunks that always fit the register-resident body (wavefront-uniform: graph constants)
       constexpr uint32_t window = kAttnRounds * (kThreads / 64) * (64 / ((D ? D : 128) / 8));
-      if ((GRP ? GRP : 1) <= 4 && (a.g->max_seq + t.p1 - 1) / t.p1 <= window)
+      if ((GRP ? GRP : 1) <= 4 && !(t.flags & TF_ATTN_BALANCE) && (a.g->max_seq + t.p1 - 1) / t.p1 <= window)
         return body_attn_partial_regs<(D ? D : 128), (GRP ? GRP : 1)>(t, a, lds, wait_ev, s_flag);
       return body_attn_partial<(D ? D : 128), (GRP ? GRP : 1)>(t, a, lds, wait_ev, s_flag);
     }

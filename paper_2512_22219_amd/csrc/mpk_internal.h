@@ -50,6 +50,10 @@ enum TaskFlags : uint16_t {
                       // partial sums, and the task of a row block that arrives last (counter p2)
                       // adds the parts in order plus the residual into the real output (aux0).
                       // p1 = weight row length, p3 = parts | part << 8, K = length of the range
+  TF_ATTN_BALANCE = 4096, // attention with fused merge, batch > 1: the batch x C chunk tasks of a KV
+                      // head are dealt to the sequences in proportion to their lengths at run time
+                      // (a task may work on another sequence than its row; its partial result
+                      // still goes to its own slot)
 };
 
 struct alignas(16) TaskDesc {

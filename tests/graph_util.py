@@ -76,9 +76,13 @@ def down_parts_of(ex, shape):
     return int(last["cols"]) // shape.hidden
 
 
-def oracle_ops_and_degrees(shape, ex, fusion, attn_chunks):
+def oracle_ops_and_degrees(shape, ex, fusion, attn_chunks, attn_balance=True):
+    """attn_balance: the compile option's default (chunk tasks dealt to the sequences at run time
+    where the merge is fused and the batch has more than one sequence); False for graphs compiled
+    with no_attn_balance=1."""
     greedy = any(eo["kind"] == TG.K_ARGMAX for eo in ex.ops)
-    ops = TG.build_ops(shape, fusion, attn_chunks, moe_tasks_of(ex), down_parts_of(ex, shape), greedy)
+    ops = TG.build_ops(shape, fusion, attn_chunks, moe_tasks_of(ex), down_parts_of(ex, shape), greedy,
+                       attn_balance)
     assert len(ops) == len(ex.ops), (len(ops), len(ex.ops))
     for o, eo in zip(ops, ex.ops):
         assert o.kind == eo["kind"] and o.layer == eo["layer"], (o.name, o.kind, eo["kind"])

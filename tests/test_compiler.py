@@ -40,6 +40,8 @@ CASES = [
     ("C2", dict(n_layers=2), dict(fusion=7)),
     ("C3", dict(n_layers=1), dict(fusion=7)),
     ("C1", dict(batch=2), dict(fusion=31, n_workers=24, attn_chunks=3)),
+    ("C1", dict(batch=2), dict(fusion=31, n_workers=24, attn_chunks=3, no_attn_balance=1)),
+    ("C1", dict(batch=3), dict(fusion=15, n_workers=24, attn_chunks=2)),   # rope unfused: a dealt chunk task waits for every row's rope tasks
     ("C2", dict(n_layers=2), dict(fusion=31)),
     # mixture-of-experts blocks
     ("C1", dict(batch=2, ffn=0, n_experts=8, top_k=2, expert_ffn=64), dict(fusion=0, n_workers=12)),
@@ -69,7 +71,7 @@ def test_dependency_sets_bit_exact_and_structure(base, variant, opts):
     ex = g.export()
     GU.check_structure(ex)
     C = GU.attn_chunks_of(ex, shape)
-    ops, deg = GU.oracle_ops_and_degrees(shape, ex, opts.get("fusion", 0), C)
+    ops, deg = GU.oracle_ops_and_degrees(shape, ex, opts.get("fusion", 0), C, not opts.get("no_attn_balance", 0))
     want = TG.producer_sets(ops, deg)
     got = GU.compiled_producer_sets(ex)
     assert TG.canonical_bytes(got) == TG.canonical_bytes(want)
@@ -100,7 +102,7 @@ def test_transitive_reduction_keeps_closures(base, variant, opts):
     ex = g.export()
     GU.check_structure(ex)
     C = GU.attn_chunks_of(ex, shape)
-    ops, deg = GU.oracle_ops_and_degrees(shape, ex, opts.get("fusion", 0), C)
+    ops, deg = GU.oracle_ops_and_degrees(shape, ex, opts.get("fusion", 0), C, not opts.get("no_attn_balance", 0))
     want = TG.producer_sets(ops, deg)
     got = GU.compiled_producer_sets(ex)
     assert closure_by_op_tile(got) == closure_by_op_tile(want)
@@ -121,7 +123,7 @@ def test_simulated_execution_respects_oracle_producers():
         g = host_graph(shape, n_workers=6, attn_chunks=3, **opts)
         ex = g.export()
         C = GU.attn_chunks_of(ex, shape)
-        ops, deg = GU.oracle_ops_and_degrees(shape, ex, opts["fusion"], C)
+        ops, deg = GU.oracle_ops_and_degrees(shape, ex, opts["fusion"], C, not opts.get("no_attn_balance", 0))
         want = TG.producer_sets(ops, deg)
         lin = {(int(t["op"]), int(t["tile"])): i for i, t in enumerate(ex.tasks)
                if t["op"] != GU.DUMMY}

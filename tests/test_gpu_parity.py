@@ -117,6 +117,32 @@ def test_small_batch_and_ragged_positions(opts):
     gpu.close()
 
 
+@pytest.mark.parametrize("batch,pos,opts", [
+    # one long sequence takes most of the chunk tasks, two sequences of length 1 keep one each
+    (4, [0, 180, 0, 7], dict(attn_chunks=4)),
+    (4, [0, 180, 0, 7], dict(attn_chunks=4, no_attn_balance=1)),
+    # 16 sequences, lengths 1 .. 189, three chunks each: the deal runs its left-over loop
+    (16, [(37 * i) % 189 for i in range(16)], dict(attn_chunks=3)),
+    (8, [188, 3, 188, 3, 188, 3, 188, 3], dict(attn_chunks=2, n_sched_wgs=2)),
+    (5, [11, 150, 60, 0, 99], dict(attn_chunks=5, launch_mode=1)),
+])
+def test_attention_chunk_tasks_dealt_to_the_sequences_by_length(batch, pos, opts):
+    """Merge fused, several sequences of very different lengths: which sequence a chunk task
+    works on is decided when the step runs; three steps, so that the deal changes under way."""
+    s = G.small_variant("C1", batch=batch, n_layers=2)
+    gpu = GpuDecoder(s, 5, fusion=31, transitive_reduction=1, n_workers=29, **opts)
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 5), "f64")
+    tok = G.tokens(5, s)
+    p = np.array(pos, np.int32)
+    for _ in range(3):
+        got, want, _, _ = held_step(ref, gpu, tok, p)
+        assert rel_err(got, want) < TOL
+        assert np.array_equal(got.argmax(-1), want.argmax(-1))
+        tok = want.argmax(-1).astype(np.int32)
+        p = p + 1
+    gpu.close()
+
+
 @pytest.mark.parametrize("variant,opts", [
     # ffn 4360: the down projection's input is one full 4096-element segment plus a short one
     (dict(hidden=1000, ffn=4360, batch=1), dict(fusion=31, transitive_reduction=1, n_workers=13)),

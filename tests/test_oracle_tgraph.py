@@ -311,6 +311,41 @@ def test_producer_sets_spot_checks_unfused():
     assert set(ps[ix["L0.swiglu"]][0]) == {(ix["L0.gate_up"], t) for t in range(4)}
 
 
+def test_producer_sets_of_attention_tasks_dealt_to_the_sequences_at_run_time():
+    """With the merge fused and more than one sequence, a chunk task may be handed any sequence
+    (Section 5.2's run-time imbalance, met by a length-proportional deal): it statically needs
+    the query / new key / new value columns of its KV head from EVERY row.  Unfused rope makes the
+    difference visible (rope tasks are per row); with one sequence, or the merge as an operator
+    of its own, nothing changes."""
+    s = G.small_variant("C1", n_layers=1, batch=3)
+    fusion = TG.F_MERGE
+    C = 2
+    for balance in (False, True):
+        ops = TG.build_ops(s, fusion, attn_chunks=C, attn_balance=balance)
+        names = [o.name for o in ops]
+        ix = {n: i for i, n in enumerate(names)}
+        assert "L0.attn_merge" not in ix
+        ps = TG.producer_sets(ops, tiny_degrees(ops))
+        nslots = s.n_q_heads + 2 * s.n_kv_heads
+        grp = s.n_q_heads // s.n_kv_heads
+        for b in range(3):
+            for g in range(s.n_kv_heads):
+                for c in range(C):
+                    rows = range(3) if balance else [b]
+                    want = set()
+                    for r in rows:
+                        want |= {(ix["L0.rope"], r * nslots + g * grp + j) for j in range(grp)}
+                        want |= {(ix["L0.rope"], r * nslots + s.n_q_heads + g),
+                                 (ix["L0.rope"], r * nslots + s.n_q_heads + s.n_kv_heads + g)}
+                    assert set(ps[ix["L0.attn_partial"]][(b * s.n_kv_heads + g) * C + c]) == want
+    # no effect without the fused merge, or with a single sequence
+    a = TG.build_ops(s, 0, attn_chunks=C, attn_balance=True)
+    assert not [o for o in a if o.kind == TG.K_ATTN_PARTIAL][0].meta["balance"]
+    s1 = G.small_variant("C1", n_layers=1, batch=1)
+    a = TG.build_ops(s1, fusion, attn_chunks=C, attn_balance=True)
+    assert not [o for o in a if o.kind == TG.K_ATTN_PARTIAL][0].meta["balance"]
+
+
 def test_producer_sets_fused_residual_reads_only_its_tile():
     s = G.small_variant("C1", n_layers=2)
     fusion = TG.F_NORM | TG.F_RESID | TG.F_SWIGLU
