@@ -225,6 +225,28 @@ __device__ __forceinline__ float wave_sum_dpp(float v) {
   return (__int_as_float(__builtin_amdgcn_readlane(u, 0)) + __int_as_float(__builtin_amdgcn_readlane(u, 16))) +
          (__int_as_float(__builtin_amdgcn_readlane(u, 32)) + __int_as_float(__builtin_amdgcn_readlane(u, 48)));
 }
+// ... and the largest / smallest value of the wavefront the same way
+template <class Op>
+__device__ __forceinline__ uint32_t wave_reduce_dpp(uint32_t v, Op op) {
+  auto dpp = [](uint32_t x, auto ctrl) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, decltype(ctrl)::value, 0xF, 0xF, true);
+  };
+  v = op(v, dpp(v, std::integral_constant<int, 0xB1>{}));
+  v = op(v, dpp(v, std::integral_constant<int, 0x4E>{}));
+  v = op(v, dpp(v, std::integral_constant<int, 0x141>{}));
+  v = op(v, dpp(v, std::integral_constant<int, 0x140>{}));
+  const int u = (int)v;
+  return op(op((uint32_t)__builtin_amdgcn_readlane(u, 0), (uint32_t)__builtin_amdgcn_readlane(u, 16)),
+            op((uint32_t)__builtin_amdgcn_readlane(u, 32), (uint32_t)__builtin_amdgcn_readlane(u, 48)));
+}
+__device__ __forceinline__ float wave_max_dpp(float v) {
+  return __uint_as_float(wave_reduce_dpp(__float_as_uint(v), [](uint32_t x, uint32_t y) {
+    return __float_as_uint(fmaxf(__uint_as_float(x), __uint_as_float(y)));
+  }));
+}
+__device__ __forceinline__ uint32_t wave_min_u32_dpp(uint32_t v) {
+  return wave_reduce_dpp(v, [](uint32_t x, uint32_t y) { return min(x, y); });
+}
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
@@ -930,7 +952,7 @@ __device__ __forceinline__ u32x4 select4(bool c, const u32x4& x, const u32x4& y)
 //                  pre-loading, Section 5.3: 16 KB per wavefront, 32 MB over the chip); returns
 //                  kLinDone to go on
 // LDS: x [nb][xstride] f32 at `lds`, reused at the end for the per-wavefront partial tiles
-// part[8][4][16][16] f32; ssq [8][16] f32 (sums of squares per wavefront and row, when pro_norm).
+// part[8][4][16][16] f32, then the chunk's RMSNorm gains [Kc] bf16; ssq [8][16] f32 (sums of squares per wavefront and row, when pro_norm).
 // On return (kLinDone) every thread may read part and ssq.
 // PACK: how many of the three terms one multiply covers.  The multiply has 16 batch columns; up
 // to 8 staged rows leave half of them free, so columns 0..7 take the hi term and columns 8..15
@@ -958,8 +980,8 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
   }
   // fragment at input k of the row at byte offset ro: this lane's 8 inputs start at k + fk, or
   // are the row's last 8 when that lies past its end (their staged inputs are zeros)
-  auto ld_frag = [&](uint32_t ro, uint32_t k) {
-    const uint32_t off = ro + 2u * min(k + fk, K - 8u);
+  auto ld_frag = [&](uint32_t ro, uint32_t k, bool real) {
+    const uint32_t off = real ? ro + 2u * min(k + fk, K - 8u) : 0u;   // not real: every lane the matrix' first 16 bytes
     return __builtin_nontemporal_load((const MPK_GLOBAL u32x4*)((const MPK_GLOBAL char*)wbase + off));
   };
   // the wavefront's run of k-groups in chunk c; a chunk takes an even number of round slots
@@ -973,31 +995,31 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
     return max(2u, (n + 1u) & ~1u);
   };
   // requests the 16 fragments of round slot (c, i) into buf; buf[4 Q + u] = fragment u of slot
-  // group Q
+  // group Q.  Always 16 loads, no branch: the compiler counts the loads in flight statically, and a
+  // load that may or may not have been issued makes it wait for everything older than it could
+  // be -- in effect for the whole pipeline, every round.  For a slot group that does not exist
+  // (past the end of the run, or no row tile) all lanes read the matrix' first 16 bytes instead
+  // (one cached line; nobody uses the result).
   auto request_round = [&](u32x4* buf, uint32_t c, uint32_t i) {
-    if (c >= nchunk) return;
-    const uint32_t kg0 = run_lo(c) + i * kgpr, hi = run_hi(c);
-    if (kg0 >= hi) return;
-    const uint32_t k0 = c * Kc;
+    const uint32_t cc = min(c, nchunk - 1u);
+    const uint32_t kg0 = run_lo(cc) + i * kgpr, hi = c < nchunk ? run_hi(cc) : 0u;
+    const uint32_t k0 = cc * Kc;
     static_for<0, 4>([&](auto Qc) {
       constexpr uint32_t Q = (uint32_t)decltype(Qc)::value;
       const uint32_t kg = kg0 + (Q >> sh);
-      const bool rowok = kgpr == 1u ? Q < nrtw : true;
-      if (kg < hi && rowok) {
+      const bool ok = kg < hi && (kgpr == 1u ? Q < nrtw : true);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) buf[4 * Q + u] = ld_frag(wq[Q], k0 + kg * 128u + (uint32_t)u * 32u);
-      }
+      for (int u = 0; u < 4; ++u) buf[4 * Q + u] = ld_frag(wq[Q], k0 + kg * 128u + (uint32_t)u * 32u, ok);
     });
   };
-  // RMSNorm gains of the pairs of this thread: column offsets j * 1024 + tcol of a chunk (weights:
-  // chunk 0's are requested before the event)
-  const uint32_t tcol = 2u * threadIdx.x;
-  uint32_t gq[4];
+  // RMSNorm gains of a chunk, bf16, copied to LDS behind the staged rows (weights: chunk 0's are
+  // requested before the event).  All copies into LDS here go from device memory straight to LDS
+  // (no registers): 16 bytes per lane, a wavefront's 64 lanes land side by side.
+  uint16_t* gl = (uint16_t*)(xs + (size_t)nb * xstride);   // [Kc]
   auto request_gains = [&](uint32_t c) {
-    const uint32_t k0 = c * Kc, klen = min(Kc, K - k0);
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (pro_norm && (uint32_t)j * 1024u < klen) gq[j] = *as_global((const uint32_t*)(gain + k0 + min((uint32_t)j * 1024u + tcol, klen - 2u)));
+    const uint32_t k0 = c * Kc, klen = min(Kc, K - k0), col = 8u * threadIdx.x;
+    if (pro_norm && col < klen)
+      __builtin_amdgcn_global_load_lds(as_global((const u32x4*)(gain + k0 + col)), (lds_ptr_t)(gl + wave * 512u), 16, 0, 0);
   };
   u32x4 wA[16], wB[16];
   const bool preload = !(a.flags & kNoPreloadBit);   // off: the ablation of Section 6.5, Fig. 10
@@ -1018,59 +1040,39 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
     request_round(wA, 0u, 0u);
     asm volatile("; first round requested after the event" ::: "memory");
   }
-  // Staging: a chunk is dealt to the threads as 32 pairs of inputs each; pair slot q belongs to
-  // half-row q / 2 (a half-row is Kc / 2 inputs up to 8 staged rows, a whole row of Kc above),
-  // the same for every thread, so that the sums of squares need no indexing.
-  static_assert(kThreads == 512, "the slot -> (row, pair) mapping assumes 512 threads");
+  // Staging: the nb rows of a chunk, 256 inputs (1 KB) per instruction, the instructions dealt
+  // round-robin to the wavefronts (16 each for a full chunk), with agent-coherent loads straight
+  // into LDS.  What lies between the end of a row and the end of its last k-group is zeroed.
   const uint32_t wide = nb > 8u ? 1u : 0u;
   float rowsum = 0.f;   // lane b: this wavefront's sum of squares of staged row b
   auto stage = [&](uint32_t c) {
-    float sqq[16];
-#pragma unroll
-    for (int q = 0; q < 16; ++q) sqq[q] = 0.f;
     const uint32_t k0 = c * Kc, klen = min(Kc, K - k0), kpad = (klen + 127u) & ~127u;
-    // Two passes of 16 pairs: all 32 at once, next to the 128 registers of requested weights,
-    // do not fit the register file.  Addresses are a uniform row base plus one per-thread offset
-    // (scalar base registers: 32 address pairs in vector registers would be moved to scratch
-    // memory); a pair past the end of the row re-reads the row's last pair and is stored as zeros.
     if (c) request_gains(c);
-    static_for<0, 2>([&](auto Hc) {
-      constexpr int H = decltype(Hc)::value;
-      float2 sv[16];
 #pragma unroll
-      for (int qq = 0; qq < 16; ++qq) {
-        const uint32_t q = (uint32_t)(16 * H + qq), hr = q >> 1;
-        const uint32_t b = wide ? hr : hr >> 1;
-        const uint32_t c0 = (wide ? 0u : (hr & 1u) * 2048u) + (q & 1u) * 1024u;   // uniform
-        if (b < nb && c0 < klen) {
-          const float* rb = src_row(b) + k0;
-          sv[qq] = ld_act2(rb + min(c0 + tcol, klen - 2u));
-        }
+    for (int i = 0; i < 16; ++i) {
+      const uint32_t n = wave + 8u * (uint32_t)i;
+      const uint32_t b = wide ? n >> 3 : n >> 4, seg = wide ? n & 7u : n & 15u;   // Kc / 256 instructions per row
+      if (b < nb && seg * 256u < klen) {
+        const uint32_t col = seg * 256u + 4u * (uint32_t)lane;
+        if (col < klen)
+          __builtin_amdgcn_global_load_lds(as_global((const u32x4*)(src_row(b) + k0 + col)), (lds_ptr_t)(xs + (size_t)b * xstride + seg * 256u), 16, 0, 16);
       }
-#pragma unroll
-      for (int qq = 0; qq < 16; ++qq) {
-        const uint32_t q = (uint32_t)(16 * H + qq), hr = q >> 1;
-        const uint32_t b = wide ? hr : hr >> 1;
-        const uint32_t c0 = (wide ? 0u : (hr & 1u) * 2048u) + (q & 1u) * 1024u;
-        const uint32_t col = c0 + tcol;
-        if (b < nb && c0 < klen) {
-          float2 w2 = col < klen ? sv[qq] : make_float2(0.f, 0.f);
-          if (pro_norm) {
-            sqq[q >> 1] = fmaf(w2.x, w2.x, fmaf(w2.y, w2.y, sqq[q >> 1]));
-            const uint32_t g2 = wide ? gq[q & 1u] : gq[q & 3u];
-            w2.x *= bf16_lo(g2);
-            w2.y *= bf16_hi(g2);
-          }
-          if (col < kpad) *(float2*)(xs + (size_t)b * xstride + col) = w2;   // zeros between klen and the end of its k-group
-        }
+    }
+    if (kpad != klen)
+      for (uint32_t i = threadIdx.x; i < nb * (kpad - klen); i += kThreads) xs[(size_t)(i / (kpad - klen)) * xstride + klen + i % (kpad - klen)] = 0.f;
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's copies have landed
+  };
+  // sums of squares of the staged rows (before the gains): wavefront w takes rows w, w + 8
+  auto row_squares = [&](uint32_t c) {
+    const uint32_t klen = min(Kc, K - c * Kc);
+    for (uint32_t r = wave; r < nb; r += 8u) {
+      float sq = 0.f;
+      for (uint32_t col = 4u * (uint32_t)lane; col < klen; col += 256u) {
+        const float4 v = *(const float4*)(xs + (size_t)r * xstride + col);
+        sq = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, sq))));
       }
-    });
-    if (pro_norm) {
-#pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const float v = wave_sum_dpp(sqq[q]);
-        if ((uint32_t)lane == (wide ? (uint32_t)q : (uint32_t)q >> 1)) rowsum += v;
-      }
+      sq = wave_sum_dpp(sq);
+      if ((uint32_t)lane == r) rowsum += sq;
     }
   };
   // this lane's staged row and which term its column takes in the first multiply
@@ -1093,7 +1095,12 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
           if (kg < hi && rowok) {
             if (Q == 0u || (Q >> sh) != ((Q - 1u) >> sh)) {   // first slot group of its k-group
               const float* src = xl + kg * 128u + U * 32u;
-              const float4 x0 = *(const float4*)src, x1 = *(const float4*)(src + 4);
+              float4 x0 = *(const float4*)src, x1 = *(const float4*)(src + 4);
+              if (pro_norm) {
+                const u32x4 gg = *(const u32x4*)(gl + kg * 128u + U * 32u + fk);
+                x0.x *= bf16_lo(gg.x); x0.y *= bf16_hi(gg.x); x0.z *= bf16_lo(gg.y); x0.w *= bf16_hi(gg.y);
+                x1.x *= bf16_lo(gg.z); x1.y *= bf16_hi(gg.z); x1.z *= bf16_lo(gg.w); x1.w *= bf16_hi(gg.w);
+              }
               u32x4 h, m, l;
               split8(x0, x1, &h, &m, &l);
               if (PACK == 1) { p0 = h; p1 = m; p2 = l; }
@@ -1116,15 +1123,16 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
   for (uint32_t c = 0; c < nchunk; ++c) {
     if (c) lds_barrier();   // everybody has finished with the previous chunk
     stage(c);
+    lds_barrier();
+    if (pro_norm) row_squares(c);
     if (c == 0) {
-      // behind the staging loads.  (The slot number goes through an empty asm so that the 16
-      // addresses are worked out here: computed next to the first round's, ahead of the staging,
-      // they would wait in scratch memory.)
+      // the second round, behind the staging.  (The slot number goes through an empty asm so
+      // that the 16 addresses are worked out here: computed next to the first round's, ahead of
+      // the staging, they would wait in scratch memory.)
       uint32_t one = 1u;
       asm volatile("" : "+s"(one));
       request_round(wB, 0u, one);
     }
-    lds_barrier();
     if (c == 0) {
       trace_mark(a, t, 2);
 #pragma unroll
@@ -1344,7 +1352,7 @@ __device__ __forceinline__ void body_moe_route(const TaskDesc& t, const StepArgs
       if ((uint32_t)i < nper && e < E) pr[i] = ld_act(t.in + (size_t)tok * t.ld_in + e);
       m = fmaxf(m, pr[i]);
     }
-    m = wave_max(m);
+    m = wave_max_dpp(m);
     float l = 0.f;
 #pragma unroll
     for (int i = 0; i < kPerLane; ++i) {
@@ -1354,7 +1362,7 @@ __device__ __forceinline__ void body_moe_route(const TaskDesc& t, const StepArgs
       if ((uint32_t)i < nper && e < E) pr[i] = expf(lg - m);
       l += pr[i];
     }
-    l = wave_sum(l);
+    l = wave_sum_dpp(l);
 #pragma unroll
     for (int i = 0; i < kPerLane; ++i)
       if ((uint32_t)i < nper) pr[i] = pr[i] / l;
@@ -1367,14 +1375,14 @@ __device__ __forceinline__ void body_moe_route(const TaskDesc& t, const StepArgs
         const uint32_t e = (uint32_t)lane + 64u * i;
         if ((uint32_t)i < nper && e < E && !((taken >> i) & 1u) && pr[i] > best) { best = pr[i]; best_e = e; }   // ascending e: ties keep the lower
       }
-      const float wbest = wave_max(best);
-      const uint32_t we = wave_min_u32(best == wbest ? best_e : 0xFFFFFFFFu);
+      const float wbest = wave_max_dpp(best);
+      const uint32_t we = wave_min_u32_dpp(best == wbest ? best_e : 0xFFFFFFFFu);
       if (we != 0xFFFFFFFFu && (we & 63u) == (uint32_t)lane) taken |= 1u << (we >> 6);
     }
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < kPerLane; ++i) s += ((taken >> i) & 1u) ? pr[i] : 0.f;
-    s = wave_sum(s);
+    s = wave_sum_dpp(s);
     uint32_t before = 0;   // selected experts with a smaller index, so far
 #pragma unroll
     for (int i = 0; i < kPerLane; ++i) {

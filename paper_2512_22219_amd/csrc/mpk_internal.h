@@ -187,11 +187,11 @@ constexpr uint32_t kMoeMaxExperts = 512, kMoeMaxPairs = 256, kMoeMaxTopK = 16;
 // many inputs at a time; one definition for the host's LDS requirement and the kernels' layout.
 constexpr uint32_t mfma_kchunk(uint32_t nb) { return nb <= 8u ? 4096u : 2048u; }
 constexpr uint32_t kMfmaXPad = 32;   // floats between staged rows beyond the chunk (bank spread)
-// LDS floats of a job with nb staged rows: nb rows x (chunk + pad) f32, reused for the partial
-// tiles [8 wavefronts][4][16][16] f32 at the end.
+// LDS floats of a job with nb staged rows: nb rows x (chunk + pad) f32 (reused for the partial
+// tiles [8 wavefronts][4][16][16] f32 at the end), then the chunk's RMSNorm gains as bf16.
 constexpr uint32_t mfma_x_floats(uint32_t nb) {
   const uint32_t x = nb * (mfma_kchunk(nb) + kMfmaXPad);
-  return x > 8u * 4u * 256u ? x : 8u * 4u * 256u;
+  return (x > 8u * 4u * 256u ? x : 8u * 4u * 256u) + mfma_kchunk(nb) / 2u;
 }
 // ... of the expert jobs of a graph with this batch size: an expert holds between 1 and min(batch,
 // 16) token rows.
