@@ -1020,7 +1020,7 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
           + (size_t)(kThreads * 8 / c.head_dim) * grp * (c.head_dim + 4) + 16 + 64;   // partials per position slot (register-resident body; the other keeps one per wavefront)
     need = std::max(need, f);
   }
-  size_t bytes = (need + kLdsReduceFloats + 16) * sizeof(float);   // + 64 bytes of control words
+  size_t bytes = (need + kLdsReduceFloats + kLdsCtrlFloats) * sizeof(float);   // + the control words
   return (uint32_t)std::max<size_t>(bytes, kMinLdsBytes);
 }
 
@@ -1114,7 +1114,7 @@ static bool page_capable(const mpk_model_config& c, const mpk_compile_options& o
 static std::vector<uint16_t> page_plan(const mpk_model_config& c, const mpk_compile_options& o, const HostGraph& g) {
   std::vector<uint16_t> plan(g.tasks.size(), 0);
   if (!page_capable(c, o)) return plan;
-  const size_t room = (160 * 1024) / sizeof(float) - kLdsReduceFloats - 16 - kLinPagesFloats;
+  const size_t room = (160 * 1024) / sizeof(float) - kLdsReduceFloats - kLdsCtrlFloats - kLinPagesFloats;
   auto lin_op = [&](uint32_t ti) -> const HostOp* {
     const HostTask& t = g.tasks[ti];
     if (t.op == MPK_TASK_DUMMY_OP || t.jit) return nullptr;
@@ -1274,7 +1274,7 @@ static mpk_status build_model_graph_pass(const mpk_model_config& cfg, const mpk_
       if ((plan[i] & TF_PAGE_READY) && !(*sp.page_ready)[g.tasks[i].op][g.tasks[i].tile]) { set_error("page plan changed between the two compile passes"); return MPK_ERR_INTERNAL; }
     }
     if (any) {   // the pages sit at the top of the 160 KB
-      g.lin_page_off = (uint32_t)((160 * 1024) / sizeof(float) - kLdsReduceFloats - 16 - kLinPagesFloats);
+      g.lin_page_off = (uint32_t)((160 * 1024) / sizeof(float) - kLdsReduceFloats - kLdsCtrlFloats - kLinPagesFloats);
       g.lds_bytes = 160 * 1024;
     }
   }

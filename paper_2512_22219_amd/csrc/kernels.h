@@ -2592,9 +2592,38 @@ __device__ __forceinline__ void signal_from_wave0(const StepArgs& a, const TaskD
   if (lane == 0) notify_event(a, e);
 }
 
-// The first 64 bytes of the dynamic LDS are control words ([0] = result of the last event wait);
-// task bodies use the rest.
-constexpr uint32_t kLdsCtrlFloats = 16;
+// The first 192 bytes of the dynamic LDS are control words ([0] = result of the last event wait;
+// from word 16: the kernel's arguments); task bodies use the rest.
+// The arguments are kept there for the task functions that are real calls: a struct passed by
+// value to such a function travels through private memory -- every one of the 512 lanes stores
+// and re-loads its own 80-byte copy, 10 MB per call over the chip and a memory round trip before
+// the task can start (measured on the MoE shape: 3.9 GB written per step, most of it this).
+constexpr uint32_t kLdsArgsAt = 16;
+static_assert(kLdsArgsAt * 4 + sizeof(StepArgs) <= kLdsCtrlFloats * 4, "control words too small for the arguments");
+// Thread 0 leaves the arguments in LDS; the callers' next barrier publishes them.
+__device__ __forceinline__ void publish_args(const StepArgs& a) {
+  extern __shared__ __align__(16) float dyn_lds[];
+  if (threadIdx.x == 0) *(StepArgs*)(dyn_lds + kLdsArgsAt) = a;
+}
+__device__ __forceinline__ StepArgs published_args() {
+  extern __shared__ __align__(16) float dyn_lds[];
+  return uniform_args(*(const StepArgs*)(dyn_lds + kLdsArgsAt));
+}
+// How a real task function gets the arguments: from LDS (the batch-5..16 kernel, NB = 8, for dense models:
+// -1.5 % per step on the batch-8 shape) or by value (the batch-1 kernels, where the LDS form
+// measured 0 to +1.3 %, and the mixture-of-experts kernels, whose expert-task function grew a
+// larger stack frame with it: +8 % on the MoE shape).
+struct ArgsInLds {};
+__device__ __forceinline__ StepArgs task_args(const ArgsInLds&) { return published_args(); }
+__device__ __forceinline__ StepArgs task_args(const StepArgs& a) { return uniform_args(a); }
+template <int NB, bool MOE>
+struct TaskArgs {
+  using type = std::conditional_t<(NB == 8 && !MOE), ArgsInLds, StepArgs>;
+  static __device__ __forceinline__ type make(const StepArgs& a) {
+    if constexpr (NB == 8 && !MOE) return ArgsInLds{};
+    else return a;
+  }
+};
 
 // Mixture-of-experts tasks get a function of their own as well: the expert jobs hold many
 // registers, and a function saves every callee-saved register it uses anywhere on each call, so
@@ -2637,8 +2666,8 @@ __device__ __forceinline__ bool is_moe_kind(uint16_t kind) { return kind >= TK_M
 // force spills of registers that have loads in flight.
 // Returns false when the step is being aborted.
 template <int D, int GRP, int NB, bool MEGA, bool MOE>
-__device__ __noinline__ bool run_other_task(StepArgs a_in, uint32_t task_index, bool skip_wait) {
-  const StepArgs a = uniform_args(a_in);
+__device__ __noinline__ bool run_other_task(typename TaskArgs<NB, MOE>::type args, uint32_t task_index, bool skip_wait) {
+  const StepArgs a = task_args(args);
   task_index = uniform_u32(task_index);
   skip_wait = uniform_u32(skip_wait) != 0;
   extern __shared__ __align__(16) float dyn_lds[];
@@ -2647,7 +2676,7 @@ __device__ __noinline__ bool run_other_task(StepArgs a_in, uint32_t task_index, 
   const TaskDesc t = ld_task(a, task_index);
   // kernels for dense models are built without this call: with it the function is no leaf any
   // more and every attention task pays for that (measured: 0.1 ms per step on the 8B shape)
-  if (MOE && is_moe_kind(t.kind)) return run_moe_task<MEGA>(a_in, task_index, skip_wait);
+  if (MOE && is_moe_kind(t.kind)) return run_moe_task<MEGA>(a, task_index, skip_wait);
   int32_t wait_ev = -1;
   if (MEGA) {
     debug_jitter(a, task_index);
@@ -2829,7 +2858,7 @@ __device__ __forceinline__ bool aot_pass(const StepArgs& a, uint32_t q0, uint32_
     } else {
       // the callee's result comes back in a vector register: make it scalar again, or the whole
       // task loop (and every descriptor load in it) turns into per-lane code
-      if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(a, ti, false))) return false;
+      if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(TaskArgs<NB, MOE>::make(a), ti, false))) return false;
     }
   }
   return true;
@@ -2848,6 +2877,11 @@ __global__ void __launch_bounds__(kThreads) mpk_loop_kernel(StepArgs a) {
   const uint32_t n_steps = a.n_steps;
   for (uint32_t step = 0; step < n_steps; ++step, ++a.epoch) {
     a.step = (uint16_t)step;
+    if (NB == 8 && !MOE) {
+      __syncthreads();   // (nobody is inside a task function any more)
+      publish_args(a);
+      __syncthreads();
+    }
     if (!aot_pass<D, GRP, NB, MOE>(a, q0, q1, lds, s_flag, step > 0)) return;
   }
 }
@@ -2862,6 +2896,10 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
   float* lds = dyn_lds + kLdsCtrlFloats;
   uint32_t* s_flag = (uint32_t*)dyn_lds;
   const uint32_t w = blockIdx.x;
+  if (NB == 8 && !MOE) {
+    publish_args(a);
+    __syncthreads();
+  }
   if (PATHS != 1 && w >= a.g->n_workers) {
     // scheduler workgroup: 4 scheduler wavefronts (Section 5.1, Table 2), the rest leave
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -2899,11 +2937,11 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
         if (tjd.kind == TK_LINEAR) {
           debug_jitter(a, tj);
           if (run_linear<NB, true>(tjd, a, lds, -1, s_flag) != kLinDone) { r = kLinAbort; break; }
-        } else if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(a, tj, true))) { r = kLinAbort; break; }
+        } else if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(TaskArgs<NB, MOE>::make(a), tj, true))) { r = kLinAbort; break; }
       }
       if (r == kLinAbort) break;
     } else {
-      if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(a, ti, true))) break;
+      if (!__builtin_amdgcn_readfirstlane((int)run_other_task<D, GRP, NB, true, MOE>(TaskArgs<NB, MOE>::make(a), ti, true))) break;
     }
   }
   if (threadIdx.x == 0) __hip_atomic_store(as_global(a.g->wq_head + w), jit_head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -2915,12 +2953,16 @@ template <int D, int GRP, int NB, bool MOE>
 __global__ void __launch_bounds__(kThreads) mpk_op_kernel(StepArgs a, uint32_t first) {
   extern __shared__ __align__(16) float dyn_lds[];
   float* lds = dyn_lds + kLdsCtrlFloats;
+  if (NB == 8 && !MOE) {
+    publish_args(a);
+    __syncthreads();
+  }
   const uint32_t ti = ld_u32c(a.g->op_list + first + blockIdx.x);
   const TaskDesc t = ld_task(a, ti);
   if (t.kind == TK_LINEAR) {
     run_linear<NB, false>(t, a, lds, -1, nullptr);
   } else {
-    run_other_task<D, GRP, NB, false, MOE>(a, ti, true);
+    run_other_task<D, GRP, NB, false, MOE>(TaskArgs<NB, MOE>::make(a), ti, true);
   }
 }
 

@@ -204,6 +204,7 @@ constexpr uint32_t moe_x_floats(uint32_t batch) {
 // LDS layout constants shared with the kernels
 constexpr uint32_t kThreads = 512;        // worker workgroup size (8 wavefronts, two per SIMD)
 constexpr uint32_t kLdsReduceFloats = 1024;  // scratch for cross-wave reductions
+constexpr uint32_t kLdsCtrlFloats = 48;      // control words ahead of the task area (event-wait result, the kernel's arguments)
 constexpr uint32_t kMinLdsBytes = 84 * 1024; // > half of 160 KB: at most one worker per CU
 // Pre-load pages in LDS (paper Section 5.3: shared-memory pages hold data pre-loaded for a task that
 // has not started): one page of 16 KB per wavefront = one half block of the vector linear body.
