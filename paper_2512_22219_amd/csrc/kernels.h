@@ -2013,6 +2013,14 @@ __device__ __forceinline__ void attn_deal(const StepArgs& a, uint32_t C, uint32_
 // Cache rows of earlier steps are immutable during a step, so the task requests its first
 // kAttnPre rounds of K and V rows BEFORE it waits for its dependent event; only the query (and the
 // row appended this step) arrive later.  Later rounds are requested a batch at a time.
+// These early reads are plain non-temporal loads.  In a multi-token launch they include the row
+// another workgroup appended in the PREVIOUS step of the same launch; that is safe because (1) the
+// row was written with coherent stores that completed before its task notified, and this worker
+// has since waited for an event downstream of that notification (a step's first tasks wait for
+// the previous step's terminal event), and (2) no cache can hold an older copy of the row's
+// lines: a row fills whole 128-byte lines of its own and is never read before it is written (the
+// row at the current position is excluded from the early reads and fetched coherently).
+// The caller in turn must not change rows below a sequence's position while a launch runs.
 template <int D, int GRP>
 __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepArgs& a, float* lds,
                                                   int32_t wait_ev, uint32_t* s_flag) {
