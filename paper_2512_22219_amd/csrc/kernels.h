@@ -705,7 +705,7 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
       for (uint32_t i = threadIdx.x; i < Kp / 2; i += kThreads) dst[i] = make_float2(0.f, 0.f);
     }
     if (pro_norm) {
-      ss = wave_sum(ss);
+      ss = wave_sum_dpp(ss);
       if (lane == 0) ssq[wave * NB + b] = ss;
     }
   }
@@ -732,7 +732,7 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
         for (int i = 0; i < kHalfRows; ++i)
 #pragma unroll
           for (int b = 0; b < NB; ++b) {
-            const float v = wave_sum(acc[i][b]);
+            const float v = wave_sum_dpp(acc[i][b]);
             if (lane == 0 && (uint32_t)i < B.nrows) outbuf[(size_t)(B.row0 + i) * NB + b] = v;
             acc[i][b] = 0.f;
           }
@@ -1153,9 +1153,14 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
     for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
+        // (a lane's column is its index in its row of 16 lanes: the value 8 / 4 columns up comes
+        // by a DPP row shift; columns that get nothing are not results)
         const float v = acc[j][i];
-        if (PACK == 2) acc[j][i] = v + __shfl(v, lane + 8, 64) + acc_lo[j][i];        // hi + mid (8 columns up) + lo
-        else acc[j][i] = v + __shfl(v, lane + 4, 64) + __shfl(v, lane + 8, 64);       // hi + mid + lo, 4 columns apart
+        auto up = [](float x, auto ctrl) {
+          return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value, 0xF, 0xF, true));
+        };
+        if (PACK == 2) acc[j][i] = v + up(v, std::integral_constant<int, 0x108>{}) + acc_lo[j][i];        // hi + mid (8 columns up) + lo
+        else acc[j][i] = v + up(v, std::integral_constant<int, 0x104>{}) + up(v, std::integral_constant<int, 0x108>{});   // hi + mid + lo, 4 columns apart
       }
   }
   lds_barrier();   // nobody reads the staged input any more: its space takes the partial tiles
