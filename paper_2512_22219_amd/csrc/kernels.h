@@ -2624,8 +2624,8 @@ __device__ __forceinline__ StepArgs published_args() {
 }
 // How a real task function gets the arguments: from LDS (the batch-5..16 kernel, NB = 8, for dense models:
 // -1.5 % per step on the batch-8 shape) or by value (the batch-1 kernels, where the LDS form
-// measured 0 to +1.3 %, and the mixture-of-experts kernels, whose expert-task function grew a
-// larger stack frame with it: +8 % on the MoE shape).
+// measured 0 to +1.3 %, and the mixture-of-experts kernels: +5 % on the MoE shape, also with the
+// expert bodies inlined into the task function).
 struct ArgsInLds {};
 __device__ __forceinline__ StepArgs task_args(const ArgsInLds&) { return published_args(); }
 __device__ __forceinline__ StepArgs task_args(const StepArgs& a) { return uniform_args(a); }
@@ -2638,11 +2638,12 @@ struct TaskArgs {
   }
 };
 
-// Mixture-of-experts tasks get a function of their own as well: the expert jobs hold many
-// registers, and a function saves every callee-saved register it uses anywhere on each call, so
-// sharing run_other_task would tax every attention task with those saves.
+// Mixture-of-experts tasks: inlined into run_other_task of the MoE kernels.  (As a real function of
+// its own -- so that attention calls would not have to save the many callee-saved registers the
+// expert jobs use -- every MoE task paid two nested calls, each with its by-value argument copies
+// and register saves: measured 3 to 4 % slower per step on the MoE shape.)
 template <bool MEGA>
-__device__ __noinline__ bool run_moe_task(StepArgs a_in, uint32_t task_index, bool skip_wait) {
+__device__ __forceinline__ bool run_moe_task(StepArgs a_in, uint32_t task_index, bool skip_wait) {
   const StepArgs a = uniform_args(a_in);
   task_index = uniform_u32(task_index);
   skip_wait = uniform_u32(skip_wait) != 0;
@@ -2687,8 +2688,7 @@ __device__ __noinline__ bool run_other_task(typename TaskArgs<NB, MOE>::type arg
   float* lds = dyn_lds + kLdsCtrlFloats;
   uint32_t* s_flag = (uint32_t*)dyn_lds;
   const TaskDesc t = ld_task(a, task_index);
-  // kernels for dense models are built without this call: with it the function is no leaf any
-  // more and every attention task pays for that (measured: 0.1 ms per step on the 8B shape)
+  // (kernels for dense models are built without the mixture-of-experts bodies)
   if (MOE && is_moe_kind(t.kind)) return run_moe_task<MEGA>(a, task_index, skip_wait);
   int32_t wait_ev = -1;
   if (MEGA) {
