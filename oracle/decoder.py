@@ -206,6 +206,14 @@ class DecoderOracle:
             self.kv[l] = (np.ascontiguousarray(k).copy(), np.ascontiguousarray(v).copy())
         return self.kv[l]
 
+    def _rows_in(self, l, b, K, V, pos):
+        """The cache of sequence b in layer l as the layer function wants it: [n_kv][max_seq][d]
+        with rows 0..pos-1 valid; it writes row pos.  Here the cache is stored that way."""
+        return K[b], V[b]
+
+    def _rows_out(self, l, b, Kb, Vb, pos):
+        """Called after the layer function appended row pos to (Kb, Vb): nothing to put back."""
+
     def step(self, tokens, positions, return_hidden=False, held: "Held | None" = None):
         """tokens[B], positions[B] (= rows already cached).  Returns logits [B, vocab].
         held: decisions to hold fixed (class Held).  After the call last_k_exact / last_v_exact
@@ -238,6 +246,7 @@ class DecoderOracle:
             K, V = self._kv(l)
             for b in range(B):
                 assert 0 <= positions[b] < s.max_seq
+                Kb, Vb = self._rows_in(l, b, K, V, int(positions[b]))
                 h = _Held(None, None, None, k_exact[l, b].ctypes.data, v_exact[l, b].ctypes.data)
                 if held is not None and held.k_rows is not None:
                     h.k_rows = held.k_rows[l, b].ctypes.data
@@ -245,9 +254,10 @@ class DecoderOracle:
                     h.v_rows = held.v_rows[l, b].ctypes.data
                 if held is not None and held.experts is not None:
                     h.experts = held.experts[l, b].ctypes.data
-                L.orc_layer(ctypes.byref(cfg), ctypes.byref(w), K[b].ctypes.data,
-                            V[b].ctypes.data, int(positions[b]), _p(xs[b]), _p(work),
+                L.orc_layer(ctypes.byref(cfg), ctypes.byref(w), Kb.ctypes.data,
+                            Vb.ctypes.data, int(positions[b]), _p(xs[b]), _p(work),
                             moe_sel[l, b].ctypes.data, moe_logits[l, b].ctypes.data, ctypes.byref(h))
+                self._rows_out(l, b, Kb, Vb, int(positions[b]))
             del keep
         self.last_moe_sel = moe_sel
         self.last_moe_logits = moe_logits

@@ -27,7 +27,7 @@ F_NORM, F_RESID, F_SWIGLU, F_MERGE, F_ROPE = 1, 2, 4, 8, 16
 
 # operator kinds (same numbering as the exported op table)
 (K_EMBED, K_RMSNORM, K_LINEAR, K_ROPE, K_ATTN_PARTIAL, K_ATTN_MERGE, K_ADD, K_SWIGLU,
- K_GATEUP, K_ROUTER, K_EXPERT, K_DUMMY, K_COMBINE, K_ARGMAX) = range(14)
+ K_GATEUP, K_ROUTER, K_EXPERT, K_DUMMY, K_COMBINE, K_ARGMAX, K_SERVE) = range(15)
 
 
 def split_even(n: int, k: int):
@@ -54,7 +54,7 @@ class OpSpec:
 
 
 def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: int = 1,
-              greedy_loop: bool = False, attn_balance: bool = False):
+              greedy_loop: bool = False, attn_balance: bool = False, serving: bool = False):
     """Operator list of one decode step for model shape `s` (synth.gen.ModelShape) under the
     given fusion flags, in execution order.
 
@@ -76,12 +76,21 @@ def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: 
     attn_balance (merge fused into the attention tasks, batch > 1): the batch x C chunk tasks of a
     KV head are dealt to the sequences in proportion to their lengths when the step runs (the
     run-time imbalance of Section 5.2), so which sequence's query and new key/value a chunk task
-    reads is a run-time fact: statically it reads those columns of every row."""
+    reads is a run-time fact: statically it reads those columns of every row.
+
+    serving (Section 6.1: a decoding iteration is prepared by ONE task on the start event, which
+    retires and admits requests and updates the KV-cache metadata): that task comes first and
+    writes one metadata element per batch slot -- the slot's token, position and page table for
+    the iteration; the embedding of slot b reads element b, so everything in the iteration is
+    downstream of the task."""
     B, H, d, nq, nkv = s.batch, s.hidden, s.head_dim, s.n_q_heads, s.n_kv_heads
     F, V, C = s.ffn, s.vocab, attn_chunks
     grp = nq // nkv
     QKV = (nq + 2 * nkv) * d
-    ops = [OpSpec("embed", K_EMBED, -1, "x0", B, H, H, [])]
+    ops = []
+    if serving:
+        ops.append(OpSpec("serve", K_SERVE, -1, "slots", B, 1, 1, []))
+    ops.append(OpSpec("embed", K_EMBED, -1, "x0", B, H, H, ["slots"] if serving else []))
     x = "x0"
     x_parts = 1   # > 1: x names a tensor of partial sums
     for l in range(s.n_layers):
@@ -213,8 +222,11 @@ def read_elements(op: OpSpec, tb: int, tc: int, tile: int, shapes: dict, explici
         return out[t]
 
     k = op.kind
-    if k == K_EMBED:
-        pass                                            # token ids are external inputs
+    if k == K_SERVE:
+        pass                                            # request queue and metadata are not graph tensors
+    elif k == K_EMBED:
+        if op.ins:                                      # serving: the slot's token comes from the serve task
+            mask(op.ins[0])[b0:b1, :] = True            # (otherwise token ids are external inputs)
     elif k == K_RMSNORM:
         mask(op.ins[0])[b0:b1, :] = True                # every output needs the whole row's mean
     elif k in (K_LINEAR, K_GATEUP) and op.meta.get("parts", 1) > 1:

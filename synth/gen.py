@@ -325,3 +325,51 @@ class SynthWeights:
 
     def kv_layer(self, l: int):
         return host_kv_layer(self.seed, self.s, l)
+
+
+# ----------------------------------------------------------------------------- paged KV cache
+# Input provisioning for the paged layout: which page every (sequence, block of page_size rows)
+# lives in, and the seeded contiguous cache re-filed into pages.  No arithmetic of the method.
+BF16_NAN_BITS = 0x7FC0
+
+
+def page_table(seed: int, s: ModelShape, page_size: int, n_pages: int, rows) -> np.ndarray:
+    """int32 [B][max_seq // page_size]: sequence b gets a page of its own, drawn from a seeded
+    shuffle of all pages, for every block that holds one of its first rows[b] rows; the other
+    entries are -1."""
+    nb = s.max_seq // page_size
+    need = [-(-int(r) // page_size) for r in rows]
+    assert sum(need) <= n_pages and max(need) <= nb
+    perm = np.random.default_rng(seed).permutation(n_pages)
+    t = np.full((s.batch, nb), -1, np.int32)
+    k = 0
+    for b in range(s.batch):
+        for i in range(need[b]):
+            t[b, i] = perm[k]
+            k += 1
+    return t
+
+
+def paginate(cache: np.ndarray, table: np.ndarray, page_size: int, n_pages: int) -> np.ndarray:
+    """cache uint16 [B][n_kv][max_seq][d] -> pool uint16 [n_pages][n_kv][page_size][d]; pages no
+    table entry names hold NaN patterns."""
+    B, nkv, _, d = cache.shape
+    pool = np.full((n_pages, nkv, page_size, d), BF16_NAN_BITS, np.uint16)
+    for b in range(B):
+        for i, pg in enumerate(table[b]):
+            if pg >= 0:
+                pool[pg] = cache[b, :, i * page_size:(i + 1) * page_size, :]
+    return pool
+
+
+class PagedWeights(SynthWeights):
+    """SynthWeights whose prior cache is handed out in pages (kv_pool) under a given table."""
+
+    def __init__(self, shape, seed, table, page_size, n_pages, **kw):
+        super().__init__(shape, seed, **kw)
+        self.table, self.page_size, self.n_pages = np.asarray(table), page_size, n_pages
+
+    def kv_pool(self, l: int):
+        k, v = host_kv_layer(self.seed, self.s, l)
+        return (paginate(k, self.table, self.page_size, self.n_pages),
+                paginate(v, self.table, self.page_size, self.n_pages))

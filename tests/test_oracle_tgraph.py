@@ -256,6 +256,38 @@ def test_argmax_read_set_hand_written():
     assert ps[2] == [[(1, 0), (1, 1), (1, 2)], [(1, 3), (1, 4), (1, 5)]]
 
 
+def test_serving_task_read_sets_hand_written():
+    """Serving inside the graph (Section 6.1): ONE task on the start event prepares the iteration
+    and writes a metadata element per batch slot; the embedding task of slot b reads element b.
+    Expected sets written out by hand for 3 slots: the serving task has no producer, every
+    embedding task has exactly that task, and in the whole operator list of a small model every
+    other task is downstream of it."""
+    sv = TG.OpSpec("serve", TG.K_SERVE, -1, "slots", 3, 1, 1, [])
+    em = TG.OpSpec("embed", TG.K_EMBED, -1, "x0", 3, 4, 4, ["slots"])
+    shapes = {"slots": (3, 1), "x0": (3, 4)}
+    assert TG.read_elements(sv, 1, 1, 0, shapes) == {}
+    for b in range(3):
+        r = TG.read_elements(em, 3, 1, b, shapes)
+        assert list(r) == ["slots"]
+        assert r["slots"].tolist() == [[i == b] for i in range(3)]
+    ps = TG.producer_sets([sv, em], [(1, 1), (3, 1)])
+    assert ps == [[[]], [[(0, 0)], [(0, 0)], [(0, 0)]]]
+    s = G.small_variant("C1", batch=3, n_layers=1)
+    ops = TG.build_ops(s, 31, 2, greedy_loop=True, serving=True)
+    assert [o.kind for o in ops[:2]] == [TG.K_SERVE, TG.K_EMBED]
+    plain = TG.build_ops(s, 31, 2, greedy_loop=True)
+    assert [o.name for o in ops[2:]] == [o.name for o in plain[1:]]
+    deg = tiny_degrees(ops)
+    deg[0] = (1, 1)        # one task, whatever the number of slots
+    psets = TG.producer_sets(ops, deg)
+    reached = {(0, 0)}
+    for i, per_op in enumerate(psets):
+        for t, prod in enumerate(per_op):
+            if (i, t) != (0, 0):
+                assert prod and all(p in reached for p in prod), (ops[i].name, t)
+                reached.add((i, t))
+
+
 def tiny_degrees(ops, lin=4, rope=None, merge=2, pw=1):
     deg = []
     for op in ops:
