@@ -35,7 +35,8 @@ typedef enum {
   MPK_ERR_HIP = 5,         /* a HIP call failed; message holds the HIP error string           */
   MPK_ERR_TIMEOUT = 6,     /* the in-kernel watchdog fired (an event never activated)         */
   MPK_ERR_INTERNAL = 7,    /* compiler invariant violated                                     */
-  MPK_ERR_DEVICE = 8       /* the kernel reported an error (e.g. position >= max_seq)         */
+  MPK_ERR_DEVICE = 8       /* the kernel reported an error (e.g. position >= max_seq, a page
+                              table entry outside the pool)                                   */
 } mpk_status;
 
 /* ----------------------------------------------------------------------------------------------
@@ -182,6 +183,21 @@ typedef struct mpk_compile_options {
                                ends with the longest sequence's chunks (the run-time imbalance
                                Section 5.2 meets with just-in-time hand-out; here the split is
                                a pure function of the positions, so results stay reproducible)   */
+  uint32_t kv_page_size;    /* 0 = contiguous KV cache.  Otherwise the cache is PAGED (Section 6.1,
+                               paged attention): rows per page, a power of two >= 8 that divides
+                               max_seq.  mpk_kv_ptrs then points to pools laid out
+                               [n_layers][kv_pages][n_kv_heads][kv_page_size][head_dim], and row r
+                               of sequence b lives in page page_table[b][r / kv_page_size] (the
+                               same page number in every layer).  The table is device memory: the
+                               serving task's (serving = 1) or the caller's
+                               (mpk_graph_set_page_table).  Needs MPK_FUSE_ROPE; kv_batch must
+                               be 0                                                             */
+  uint32_t kv_pages;        /* pages per layer in the pools (with kv_page_size)                 */
+  uint32_t serving;         /* 1 = the graph starts with the serving task (Section 6.1: ONE task
+                               on the start event removes completed requests, admits arrivals and
+                               updates the KV-cache metadata in device memory).  Needs
+                               greedy_loop = 1, kv_page_size > 0, no scheduler workgroups.  Such
+                               a graph is run through its server only: mpk_serve_run             */
 } mpk_compile_options;
 
 typedef struct mpk_graph mpk_graph;
@@ -330,7 +346,8 @@ typedef struct mpk_export_event {
 enum {
   MPK_OP_EMBED = 0, MPK_OP_RMSNORM = 1, MPK_OP_LINEAR = 2, MPK_OP_ROPE = 3,
   MPK_OP_ATTN_PARTIAL = 4, MPK_OP_ATTN_MERGE = 5, MPK_OP_ADD = 6, MPK_OP_SWIGLU = 7,
-  MPK_OP_GATEUP = 8, MPK_OP_ROUTER = 9, MPK_OP_EXPERT = 10, MPK_OP_COMBINE = 12, MPK_OP_ARGMAX = 13
+  MPK_OP_GATEUP = 8, MPK_OP_ROUTER = 9, MPK_OP_EXPERT = 10, MPK_OP_COMBINE = 12, MPK_OP_ARGMAX = 13,
+  MPK_OP_SERVE = 14
 };
 
 mpk_status mpk_graph_export(const mpk_graph *g, void *buf, size_t cap, size_t *need);
@@ -385,6 +402,72 @@ uint32_t mpk_set_batch_for(const mpk_graph_set *s, uint32_t n_active);
 mpk_status mpk_set_decode_step(mpk_graph_set *s, uint32_t n_active, const int32_t *token_ids,
                                const int32_t *positions, float *logits_out, void *stream);
 void mpk_set_destroy(mpk_graph_set *s);
+
+/* ----------------------------------------------------------------------------------------------
+ * Paged KV cache and serving inside the task graph (Section 6.1, "supporting runtime dynamism").
+ * -------------------------------------------------------------------------------------------- */
+
+/* Give a graph compiled with kv_page_size (and without serving) the page table its attention
+ * tasks read: device int32 [batch][max_seq / kv_page_size], entry [b][i] = page that holds rows
+ * i * kv_page_size .. of sequence b.  Only entries for rows 0 .. positions[b] (+ the steps of a
+ * multi-token launch) are read; an entry outside [0, kv_pages) is reported by mpk_graph_status
+ * (MPK_ERR_DEVICE) and never dereferenced.  The pointer is kept, the contents may change between
+ * launches.  Synchronous (a small copy); not while a launch of the graph is in flight. */
+mpk_status mpk_graph_set_page_table(mpk_graph *g, const int32_t *page_table);
+
+/* A server: the request queue, the slot table, the page tables and the free-page stack that the
+ * graph's serving task (compile option serving = 1) works on, all in device memory.  Each decoding
+ * iteration starts with that ONE task, which (1) removes completed requests, (2) admits arrivals,
+ * (3) updates the KV-cache metadata the attention tasks then read (Section 6.1).  The paper fixes
+ * no policy; this is the contract:
+ *   - a request is a prompt and max_new_tokens; it ends with max_new_tokens produced tokens or with
+ *     eos_token (kept as its last token).  Prompts go through the decode path, one token per
+ *     iteration; the token sampled meanwhile is ignored.
+ *   - retire: slots in ascending order; pages go back on the free stack in page-table order.
+ *   - admit: idle slots in ascending order take requests in arrival order; a request enters only
+ *     when ceil((prompt_len + max_new_tokens - 1) / kv_page_size) pages are free and not promised
+ *     to running requests; the first request that does not fit ends admission for the iteration.
+ *   - a running slot pops a page when its position reaches a page boundary; an idle slot computes
+ *     on token 0 at position 0 in a page of its own (pages 0 .. batch-1 are reserved for that).
+ * Sampling is greedy (the graph's sampling operator). */
+typedef struct mpk_serve_config {
+  uint32_t struct_size;  /* = sizeof(mpk_serve_config)                                  */
+  uint32_t max_requests; /* requests the server accepts over its lifetime (1 .. 2^20)   */
+  uint32_t max_prompt;   /* longest prompt, in tokens (1 .. max_seq)                     */
+  uint32_t max_new;      /* largest max_new_tokens of a request (1 .. max_seq)           */
+  int32_t eos_token;     /* -1 = none                                                    */
+} mpk_serve_config;
+typedef struct mpk_server mpk_server;
+
+/* Allocates and initialises the server's device state and attaches it to `g` (one server per
+ * graph; destroy it before the graph).  Errors: INVALID_ARG, OOM, HIP. */
+mpk_status mpk_serve_create(mpk_graph *g, const mpk_serve_config *cfg, mpk_server **out);
+/* Queue a request: prompt = HOST int32 [prompt_len] (copied before the call returns), tokens in
+ * [0, vocab).  The request becomes visible to the serving task of launches issued on `stream`
+ * after this call.  request_id (host, may be NULL) = arrival number, from 0.  INVALID_ARG when
+ * the request could never be admitted (rows above max_seq, more pages than the pool can free). */
+mpk_status mpk_serve_submit(mpk_server *s, const int32_t *prompt, uint32_t prompt_len,
+                            uint32_t max_new_tokens, void *stream, uint32_t *request_id);
+/* Run n_iterations decoding iterations (1 .. 65535) in ONE launch of the persistent kernel
+ * (per-operator launches with MPK_LAUNCH_PER_OP): every iteration is the serving task, one decode
+ * step of all slots, greedy sampling.  Asynchronous on `stream`; launches of one server must not
+ * overlap.  Errors as mpk_decode_steps; device errors through mpk_graph_status. */
+mpk_status mpk_serve_run(mpk_server *s, uint32_t n_iterations, void *stream);
+/* After the caller synchronised the stream: state (0 queued, 1 running, 2 done) and the tokens a
+ * request has produced so far (tokens = HOST int32 [cap] or NULL; n_tokens = how many exist). */
+mpk_status mpk_serve_result(mpk_server *s, uint32_t request_id, int32_t *tokens, size_t cap,
+                            uint32_t *n_tokens, uint32_t *state);
+/* After the caller synchronised the stream: the whole serving state as int32 words into buf
+ * (HOST, cap words; *need = words required, nothing is written when cap is too small):
+ *   [0] batch B  [1] blocks per sequence M  [2] free pages  [3] promised pages  [4] requests
+ *   admitted  [5] requests submitted  [6] iterations run  [7] tokens produced, then
+ *   slot_req[B] (-1 idle), slot_pos[B], slot_held[B], token[B] (what the last iteration
+ *   sampled: the next iteration's serving task reads it there), position[B],
+ *   page table [B][M] (-1 = none), free stack [kv_pages] (the first [2] entries, top last). */
+mpk_status mpk_serve_state(mpk_server *s, int32_t *buf, size_t cap, size_t *need);
+/* Device fp32 [batch][vocab]: the logits of the last iteration run (owned by the server). */
+const float *mpk_serve_logits(const mpk_server *s);
+void mpk_serve_destroy(mpk_server *s);
 
 const char *mpk_last_error(void);
 void mpk_graph_destroy(mpk_graph *g);

@@ -6,6 +6,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+import weakref
 
 import numpy as np
 
@@ -22,6 +23,7 @@ TASK_DUMMY_OP = 0xFFFFFFFF
  OP_GATEUP, OP_ROUTER, OP_EXPERT) = range(11)
 OP_COMBINE = 12
 OP_ARGMAX = 13
+OP_SERVE = 14
 
 
 class ModelConfig(C.Structure):
@@ -55,7 +57,15 @@ class CompileOptions(C.Structure):
                  "tiles_moe", "greedy_loop", "kv_batch")] + [("worker_weight_permille", C.c_uint32 * 8),
                                                              ("no_lds_pages", C.c_uint32),
                                                              ("xcd_balance", C.c_uint32),
-                                                             ("no_attn_balance", C.c_uint32)]
+                                                             ("no_attn_balance", C.c_uint32),
+                                                             ("kv_page_size", C.c_uint32),
+                                                             ("kv_pages", C.c_uint32),
+                                                             ("serving", C.c_uint32)]
+
+
+class ServeConfig(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("max_requests", C.c_uint32), ("max_prompt", C.c_uint32),
+                ("max_new", C.c_uint32), ("eos_token", C.c_int32)]
 
 
 class Stats(C.Structure):
@@ -89,7 +99,9 @@ SYMBOLS = ("mpk_compile", "mpk_compile_dag", "mpk_decode_step", "mpk_decode_step
            "mpk_graph_reset", "mpk_graph_stats", "mpk_graph_export", "mpk_graph_trace",
            "mpk_graph_moe_active", "mpk_graph_moe_selection", "mpk_compile_set",
            "mpk_set_decode_step", "mpk_decode_step_static", "mpk_set_size", "mpk_set_batch_for", "mpk_set_graph",
-           "mpk_set_destroy", "mpk_last_error", "mpk_graph_destroy", "mpk_static_scratch_need")
+           "mpk_set_destroy", "mpk_last_error", "mpk_graph_destroy", "mpk_static_scratch_need",
+           "mpk_graph_set_page_table", "mpk_serve_create", "mpk_serve_submit", "mpk_serve_run",
+           "mpk_serve_result", "mpk_serve_state", "mpk_serve_logits", "mpk_serve_destroy")
 DEBUG_TRACE, DEBUG_POISON, DEBUG_JITTER, DEBUG_LOSE_NOTIFY = 1, 2, 4, 8
 
 _lib = None
@@ -133,7 +145,18 @@ def lib():
         L.mpk_set_graph.restype = vp
         L.mpk_set_destroy.argtypes = [vp]
         L.mpk_set_destroy.restype = None
-        for n in SYMBOLS[:14]:
+        L.mpk_graph_set_page_table.argtypes = [vp, vp]
+        L.mpk_serve_create.argtypes = [vp, C.POINTER(ServeConfig), C.POINTER(vp)]
+        L.mpk_serve_submit.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, C.POINTER(C.c_uint32)]
+        L.mpk_serve_run.argtypes = [vp, C.c_uint32, vp]
+        L.mpk_serve_result.argtypes = [vp, C.c_uint32, vp, C.c_size_t, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+        L.mpk_serve_state.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
+        L.mpk_serve_logits.argtypes = [vp]
+        L.mpk_serve_logits.restype = vp
+        L.mpk_serve_destroy.argtypes = [vp]
+        L.mpk_serve_destroy.restype = None
+        for n in SYMBOLS[:14] + ("mpk_graph_set_page_table", "mpk_serve_create", "mpk_serve_submit",
+                                 "mpk_serve_run", "mpk_serve_result", "mpk_serve_state"):
             getattr(L, n).restype = C.c_int
         _lib = L
     return _lib
@@ -224,6 +247,17 @@ class Graph:
         _check(lib().mpk_decode_steps(self._h, n_steps, token_ids_ptr, positions_ptr, tokens_out_ptr or None,
                                       logits_ptr, logits_all_ptr or None, stream))
 
+    def set_page_table(self, page_table_ptr: int):
+        _check(lib().mpk_graph_set_page_table(self._h, page_table_ptr))
+
+    def serve(self, max_requests: int, max_prompt: int, max_new: int, eos_token: int = -1) -> "Server":
+        cfg = ServeConfig(C.sizeof(ServeConfig), max_requests, max_prompt, max_new, eos_token)
+        h = C.c_void_p()
+        _check(lib().mpk_serve_create(self._h, C.byref(cfg), C.byref(h)))
+        srv = Server(h, self)
+        self._server = weakref.ref(srv)
+        return srv
+
     def status(self):
         _check(lib().mpk_graph_status(self._h))
 
@@ -267,8 +301,67 @@ class Graph:
         return ex, wt
 
     def destroy(self):
+        srv = getattr(self, "_server", None)
+        if srv is not None and srv() is not None:
+            srv().destroy()          # (the library would destroy it with the graph: drop our handle first)
         if self._h:
             lib().mpk_graph_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+class Server:
+    """Owner of one mpk_server handle (destroyed before its graph)."""
+
+    def __init__(self, handle, graph):
+        self._h = handle
+        self._graph = graph
+
+    def submit(self, prompt, max_new_tokens: int, stream: int = 0) -> int:
+        p = np.ascontiguousarray(np.asarray(prompt, dtype=np.int32).reshape(-1))
+        rid = C.c_uint32(0)
+        _check(lib().mpk_serve_submit(self._h, p.ctypes.data, len(p), max_new_tokens, stream, C.byref(rid)))
+        return rid.value
+
+    def run(self, n_iterations: int, stream: int = 0):
+        _check(lib().mpk_serve_run(self._h, n_iterations, stream))
+
+    def result(self, request_id: int):
+        """(tokens produced so far, state: 0 queued / 1 running / 2 done)."""
+        n, st = C.c_uint32(0), C.c_uint32(0)
+        _check(lib().mpk_serve_result(self._h, request_id, None, 0, C.byref(n), C.byref(st)))
+        buf = np.zeros(max(n.value, 1), np.int32)
+        _check(lib().mpk_serve_result(self._h, request_id, buf.ctypes.data, len(buf), C.byref(n), C.byref(st)))
+        return buf[:n.value].tolist(), st.value
+
+    def state(self) -> dict:
+        need = C.c_size_t(0)
+        _check(lib().mpk_serve_state(self._h, None, 0, C.byref(need)))
+        w = np.zeros(need.value, np.int32)
+        _check(lib().mpk_serve_state(self._h, w.ctypes.data, need.value, C.byref(need)))
+        B, M, n_free = int(w[0]), int(w[1]), int(w[2])
+        o = 8
+        out = {"n_free": n_free, "promised": int(w[3]), "q_head": int(w[4]), "q_tail": int(w[5]),
+               "iterations": int(w[6]), "tokens_produced": int(w[7])}
+        for name in ("slot_req", "slot_pos", "slot_held", "tokens", "positions"):
+            out[name] = w[o:o + B].tolist()
+            o += B
+        out["table"] = w[o:o + B * M].reshape(B, M).tolist()
+        o += B * M
+        out["free"] = w[o:o + n_free].tolist()
+        return out
+
+    def logits_ptr(self) -> int:
+        return int(lib().mpk_serve_logits(self._h) or 0)
+
+    def destroy(self):
+        if self._h:
+            lib().mpk_serve_destroy(self._h)
             self._h = None
 
     def __del__(self):

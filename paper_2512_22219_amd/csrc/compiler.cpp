@@ -465,8 +465,16 @@ static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
     if (second) { op.in2_tensor = x_dep; op.body_in2_tensor = x; op.in2_kparts = x_parts; }
     else { op.in_tensor = x_dep; op.body_in_tensor = x; op.in_kparts = x_parts; }
   };
+  // Serving (Section 6.1): ONE task on the start event prepares the iteration -- it retires and
+  // admits requests and updates the paged-cache metadata -- and writes one metadata element per
+  // batch slot; slot b's embedding reads element b, so the whole iteration is downstream of it.
+  int slots = -1;
+  if (o.serving) {
+    slots = b.new_tensor(B, 1);
+    b.add(MPK_OP_SERVE, -1, "serve", slots, 1, -1);
+  }
   {
-    HostOp& op = b.add(MPK_OP_EMBED, -1, "embed", x, H, -1);
+    HostOp& op = b.add(MPK_OP_EMBED, -1, "embed", x, H, slots);
     op.w = w ? w->embed : nullptr;
     op.K = H;
   }
@@ -497,6 +505,7 @@ static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
     {
       HostOp& op = b.add(MPK_OP_ATTN_PARTIAL, l, "attn_partial", part, grp * (d + 2), qsrc);
       op.p0 = l; op.p1 = C; op.f1 = c.rope_theta;
+      if (o.kv_page_size) op.flags |= TF_KV_PAGED;
       if (f & MPK_FUSE_ROPE) {
         op.flags |= TF_ROPE_FUSED;
         if (c.flags & MPK_MODEL_QK_NORM) { op.flags |= TF_QK_NORM; op.w = lw.q_norm; op.w2 = lw.k_norm; op.f0 = c.rms_eps; }
@@ -731,6 +740,7 @@ static void choose_partitions(const mpk_model_config& c, const mpk_compile_optio
         op.tc = 1;
         break;
       case MPK_OP_ROUTER:   // one task: the per-expert token lists need every token's choice
+      case MPK_OP_SERVE:    // one task: admission and the page stack are sequential decisions
         op.tb = 1;
         op.tc = 1;
         break;
@@ -764,7 +774,10 @@ static void input_rects(const mpk_model_config& c, const HostOp& op, uint32_t ti
   const uint32_t d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, grp = nq / nkv;
   out.clear();
   switch (op.kind) {
-    case MPK_OP_EMBED:
+    case MPK_OP_SERVE:   // request queue and metadata are not graph tensors
+      break;
+    case MPK_OP_EMBED:   // (serving graphs: the slot's token comes from the serving task)
+      if (op.in_tensor >= 0) out.push_back({op.in_tensor, b0, b1, 0, 1});
       break;
     case MPK_OP_RMSNORM:
       out.push_back({op.in_tensor, b0, b1, 0, op.K});
@@ -914,7 +927,10 @@ static const float* act_ref(const HostGraph& g, int tensor) {
 
 static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGraph& g) {
   g.descs.assign(g.tasks.size(), TaskDesc{});
-  const size_t kv_layer = (size_t)(g.opt.kv_batch ? g.opt.kv_batch : c.batch) * c.n_kv_heads * c.max_seq * c.head_dim;   // elements
+  // elements of one layer's K (or V) cache: [batch][n_kv][max_seq][d], or the pool [pages][n_kv][page][d]
+  const size_t kv_layer = g.opt.kv_page_size
+                              ? (size_t)g.opt.kv_pages * c.n_kv_heads * g.opt.kv_page_size * c.head_dim
+                              : (size_t)(g.opt.kv_batch ? g.opt.kv_batch : c.batch) * c.n_kv_heads * c.max_seq * c.head_dim;
   for (size_t i = 0; i < g.tasks.size(); ++i) {
     const HostTask& ht = g.tasks[i];
     TaskDesc& t = g.descs[i];
@@ -951,6 +967,7 @@ static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGr
       case MPK_OP_EXPERT: t.kind = TK_MOE_EXPERT; break;
       case MPK_OP_COMBINE: t.kind = TK_MOE_COMBINE; break;
       case MPK_OP_ARGMAX: t.kind = TK_ARGMAX; break;
+      case MPK_OP_SERVE: t.kind = TK_SERVE; break;
     }
     if (op.flags & TF_SPLITK) {
       const uint32_t Hh = op.p1, parts = op.p0, part = t.c0 / Hh, klen = op.K / parts;
@@ -1056,6 +1073,19 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
   if (o.greedy_loop > 1) { set_error("greedy_loop must be 0 or 1"); return MPK_ERR_INVALID_ARG; }
   if (o.debug_flags & ~(MPK_DEBUG_TRACE | MPK_DEBUG_POISON | MPK_DEBUG_JITTER | MPK_DEBUG_LOSE_NOTIFY)) { set_error("unknown debug_flags bits"); return MPK_ERR_INVALID_ARG; }
   if (o.kv_batch != 0 && o.kv_batch < c.batch) { set_error("kv_batch %u is below batch %u", o.kv_batch, c.batch); return MPK_ERR_INVALID_ARG; }
+  if (o.kv_page_size) {
+    const uint32_t ps = o.kv_page_size;
+    if (ps < 8 || (ps & (ps - 1)) || c.max_seq % ps) { set_error("kv_page_size %u must be a power of two >= 8 that divides max_seq %u", ps, c.max_seq); return MPK_ERR_INVALID_ARG; }
+    if (!(o.fusion & MPK_FUSE_ROPE)) { set_error("a paged KV cache needs MPK_FUSE_ROPE (the attention tasks append the new rows)"); return MPK_ERR_UNSUPPORTED; }
+    if (o.kv_batch) { set_error("kv_batch does not apply to a paged KV cache"); return MPK_ERR_INVALID_ARG; }
+    if (o.kv_pages < c.batch + 1u) { set_error("kv_pages %u: a paged cache needs more pages than batch slots (%u)", o.kv_pages, c.batch); return MPK_ERR_INVALID_ARG; }
+    if ((uint64_t)o.kv_pages * c.n_kv_heads * ps * c.head_dim >= (1ull << 40)) { set_error("kv_pages %u: pool too large", o.kv_pages); return MPK_ERR_UNSUPPORTED; }
+  } else if (o.kv_pages) { set_error("kv_pages without kv_page_size"); return MPK_ERR_INVALID_ARG; }
+  if (o.serving > 1) { set_error("serving must be 0 or 1"); return MPK_ERR_INVALID_ARG; }
+  if (o.serving) {
+    if (!o.greedy_loop || !o.kv_page_size) { set_error("serving needs greedy_loop = 1 and a paged KV cache (kv_page_size)"); return MPK_ERR_INVALID_ARG; }
+    if (o.n_sched_wgs && !o.force_aot) { set_error("serving is only supported without scheduler workgroups"); return MPK_ERR_UNSUPPORTED; }
+  }
   if (o.fusion & ~(MPK_FUSE_NORM | MPK_FUSE_RESID | MPK_FUSE_SWIGLU | MPK_FUSE_MERGE | MPK_FUSE_ROPE)) { set_error("unknown fusion bits"); return MPK_ERR_INVALID_ARG; }
   if (!o.host_only) {
     if (!w || !kv || !w->layers) { set_error("weights / kv pointers are NULL"); return MPK_ERR_INVALID_ARG; }

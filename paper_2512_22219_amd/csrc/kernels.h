@@ -73,6 +73,13 @@ struct GraphConst {
   // multi-token launch: written by mpk_decode_steps before the launch (stream-ordered copy)
   int32_t* tokens_out;   // [n_steps][batch] or null
   float* logits_all;     // [n_steps][batch][vocab] or null
+  // paged KV cache (Section 6.1): row r of sequence b lives in page page_table[b][r >> page_shift]
+  // of the layer's pool [kv_pages][n_kv][1 << page_shift][head_dim]; the table is device memory
+  // that the serving task (or the caller, between launches) writes
+  const int32_t* page_table;   // [batch][max_seq >> page_shift], or null
+  const ServeDev* serve;       // serving state, or null
+  uint32_t page_shift, kv_pages;
+  int32_t serve_event;         // event the serving task triggers, -1 = none
 };
 
 // Per-step kernel arguments, passed by value.  Every device function taking it is force-inlined:
@@ -171,6 +178,8 @@ constexpr uint32_t kTraceBit = 1u;      // per-task timestamps are recorded (buf
 constexpr uint32_t kJitterBit = 2u;     // every task starts after a pseudo-random delay (race hunting)
 constexpr uint32_t kNoPreloadBit = 4u;  // no weight / cache-row request before a task's event wait
 constexpr uint32_t kLoseNotifyBit = 8u; // worker 0 drops its notifications in this launch (watchdog test)
+constexpr uint32_t kServeBit = 16u;     // serving launch: positions[] and token_ids[] are rewritten by the serving
+                                        // task at the start of every step (absolute positions, read coherently)
 __device__ __forceinline__ void trace_mark(const StepArgs& a, const TaskDesc& t, int slot) {
   if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + slot] = wall_clock64();
 }
@@ -191,7 +200,7 @@ __device__ __forceinline__ void debug_jitter(const StepArgs& a, uint32_t task_in
   __syncthreads();
 }
 
-enum DevErr : uint32_t { DE_NONE = 0, DE_TIMEOUT = 1, DE_BAD_POSITION = 2, DE_BAD_TOKEN = 3, DE_BAD_META = 4 };
+enum DevErr : uint32_t { DE_NONE = 0, DE_TIMEOUT = 1, DE_BAD_POSITION = 2, DE_BAD_TOKEN = 3, DE_BAD_META = 4, DE_BAD_PAGE = 5 };
 
 // ------------------------------------------------------------------------------ device helpers
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
@@ -1967,12 +1976,23 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
 // ties).  A pure function of the positions, worked out by every wavefront for itself (lane b <
 // batch holds sequence b; batch <= 16).  Returns the sequence of task v, the task's chunk number
 // there, the sequence's chunk count and its first task.
+// Position of sequence b in this step.  positions[] is the host's and stays as written for the
+// whole launch (tasks add the step number) -- except in a serving launch, where the serving task
+// rewrites it at the start of every step: then it holds the step's own positions and is read with
+// coherent loads, after the serving task's event.
+template <bool PAGED>
+__device__ __forceinline__ int32_t step_position(const StepArgs& a, uint32_t b) {
+  if (PAGED && (a.flags & kServeBit)) return (int32_t)ld_relaxed((const uint32_t*)a.positions + b);
+  return a.positions[b] + (int32_t)a.step;
+}
+
+template <bool PAGED>
 __device__ __forceinline__ void attn_deal(const StepArgs& a, uint32_t C, uint32_t v, uint32_t* seq, uint32_t* chunk,
                                           uint32_t* chunks, uint32_t* first) {
   const uint32_t B = a.g->batch, li = threadIdx.x & 15u;
   uint32_t w = 0;
   if (li < B) {
-    const int32_t pos = a.positions[li] + (int32_t)a.step;
+    const int32_t pos = step_position<PAGED>(a, li);
     w = (pos >= 0 && (uint32_t)pos < a.g->max_seq) ? (uint32_t)pos + 1u : 1u;   // (a bad position is reported by its tasks)
   }
   auto row_sum = [&](uint32_t x) {   // over the 16 lanes of the row, in every lane
@@ -2026,28 +2046,52 @@ __device__ __forceinline__ void attn_deal(const StepArgs& a, uint32_t C, uint32_
 // lines: a row fills whole 128-byte lines of its own and is never read before it is written (the
 // row at the current position is excluded from the early reads and fetched coherently).
 // The caller in turn must not change rows below a sequence's position while a launch runs.
-template <int D, int GRP>
+// PAGED (TF_KV_PAGED; paper Section 6.1, paged attention): the cache is a pool of pages
+// [kv_pages][n_kv][page][D] per layer and row r of sequence b is row r % page of page
+// page_table[b][r / page].  The table (and, in a serving launch, positions[]) belong to THIS step
+// only once the serving task has run, so the task first waits for that task's event -- activated
+// at the very start of the step, long before the task's own event -- and only then deals the chunk
+// tasks, looks up its pages and requests its rows.  Table entries are read with coherent loads
+// (one per row and lane group; the lookups of a batch of rounds travel together).  An entry
+// outside the pool is reported and replaced by page 0: no address ever leaves the pool.
+template <int D, int GRP, bool PAGED = false>
 __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepArgs& a, float* lds,
                                                   int32_t wait_ev, uint32_t* s_flag) {
   constexpr uint32_t d = D, grp = GRP, LPP = D / 8, PPW = 64 / LPP, NW = kThreads / 64;
   constexpr uint32_t stride = NW * PPW, per = grp * (d + 2);
   const uint32_t nq = a.g->n_q, nkv = a.g->n_kv, Cs = t.p1;
   const uint32_t bs = t.b0, u = t.c0 / per, g = u / Cs;   // the task's own row: where its partial result goes
+  if (PAGED && wait_ev >= 0 && a.g->serve_event >= 0 && !wait_event(a, a.g->serve_event, s_flag)) return false;
   // sequence, chunk and chunk count the task works on, first task of that sequence
   uint32_t b = bs, c = u % Cs, C = Cs, v0 = bs * Cs;
-  if (t.flags & TF_ATTN_BALANCE) attn_deal(a, Cs, bs * Cs + c, &b, &c, &C, &v0);
+  if (t.flags & TF_ATTN_BALANCE) attn_deal<PAGED>(a, Cs, bs * Cs + c, &b, &c, &C, &v0);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   float* qs = lds;                       // [grp][d]
   float* wpart = qs + grp * d;           // [NW][grp][d + 2]: partial output, max, sum per wavefront
   uint32_t* flag = (uint32_t*)(wpart + NW * grp * (d + 2));
   float* outp = t.out + (size_t)bs * t.ld_out + t.c0;
-  const int32_t pos = a.positions[b] + (int32_t)a.step;    // written by the host before the launch
+  const int32_t pos = step_position<PAGED>(a, b);    // written by the host before the launch (or by the serving task)
   const bool bad_pos = pos < 0 || (uint32_t)pos >= a.g->max_seq;
   const uint32_t len = bad_pos ? 0u : (uint32_t)pos + 1;
   const uint32_t t0 = (uint32_t)((uint64_t)c * len / C), t1 = (uint32_t)((uint64_t)(c + 1) * len / C);
   const uint32_t n = t1 - t0;
-  const uint16_t* Kb = (const uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.g->max_seq + t0) * d;
-  const uint16_t* Vb = (const uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.g->max_seq + t0) * d;
+  // contiguous cache: the chunk's first row; paged: the layer's pools
+  const uint16_t* Kb = (const uint16_t*)t.aux0 + (PAGED ? (size_t)0 : (((size_t)b * nkv + g) * a.g->max_seq + t0) * d);
+  const uint16_t* Vb = (const uint16_t*)t.aux1 + (PAGED ? (size_t)0 : (((size_t)b * nkv + g) * a.g->max_seq + t0) * d);
+  const uint32_t pshift = PAGED ? a.g->page_shift : 0u;
+  const uint32_t* ptab = PAGED ? (const uint32_t*)a.g->page_table + (size_t)b * (a.g->max_seq >> pshift) : nullptr;
+  bool bad_page = false;
+  // element offset of row i of the chunk (row t0 + i of the sequence) from Kb / Vb
+  auto row_off = [&](uint32_t i) -> size_t {
+    if constexpr (PAGED) {
+      const uint32_t r = t0 + i;
+      uint32_t pg = ld_relaxed(ptab + (r >> pshift));
+      if (pg >= a.g->kv_pages) { bad_page = true; pg = 0; }
+      return ((((size_t)pg * nkv + g) << pshift) + (r & ((1u << pshift) - 1u))) * d;
+    } else {
+      return (size_t)i * d;
+    }
+  };
   const uint32_t sub = lane % LPP, slot = lane / LPP;
   const uint32_t i_first = wave * PPW + slot;
   const uint32_t n_rounds = (n + stride - 1) / stride;
@@ -2062,8 +2106,9 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
       kreg[r] = u32x4{0, 0, 0, 0};
       vreg[r] = u32x4{0, 0, 0, 0};
       if (i < n && t0 + i != (uint32_t)pos) {
-        kreg[r] = ld_stream16(Kb + (size_t)i * d + sub * 8);
-        vreg[r] = ld_stream16(Vb + (size_t)i * d + sub * 8);
+        const size_t off = row_off(i);
+        kreg[r] = ld_stream16(Kb + off + sub * 8);
+        vreg[r] = ld_stream16(Vb + off + sub * 8);
       }
     }
   };
@@ -2118,8 +2163,15 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
     if (c == C - 1) {
       const float* ksrc = t.in + (size_t)b * t.ld_in + (size_t)(nq + g) * d;
       const float* vsrc = t.in + (size_t)b * t.ld_in + (size_t)(nq + nkv + g) * d;
-      uint16_t* krow = (uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
-      uint16_t* vrow = (uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
+      uint16_t *krow, *vrow;
+      if constexpr (PAGED) {
+        const size_t off = row_off((uint32_t)pos - t0);
+        krow = const_cast<uint16_t*>(Kb) + off;
+        vrow = const_cast<uint16_t*>(Vb) + off;
+      } else {
+        krow = (uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
+        vrow = (uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
+      }
       // threads from the top of the workgroup, so that they do not also rotate query pairs
       for (uint32_t i = kThreads - 1 - threadIdx.x; i < half / 2 + half; i += kThreads) {
         if (i < half / 2) {   // two adjacent rotation pairs of the key
@@ -2179,8 +2231,9 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
       for (int r = lo; r < hi; ++r) {
         const uint32_t i = i_first + (r0 + kAttnPre + r) * stride;
         if (i < n && i != i_new) {
-          kreg[r] = ld_stream16(Kb + (size_t)i * d + sub * 8);
-          vreg[r] = ld_stream16(Vb + (size_t)i * d + sub * 8);
+          const size_t off = row_off(i);
+          kreg[r] = ld_stream16(Kb + off + sub * 8);
+          vreg[r] = ld_stream16(Vb + off + sub * 8);
         }
       }
     }
@@ -2192,8 +2245,9 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
       const uint32_t i = i_first + (r0 + r) * stride;
       if (i == i_new) {
         // written after the pre-load, by this or another workgroup: coherent loads
-        kreg[r] = ld_row16_coherent(Kb + (size_t)i * d + sub * 8);
-        vreg[r] = ld_row16_coherent(Vb + (size_t)i * d + sub * 8);
+        const size_t off = row_off(i);
+        kreg[r] = ld_row16_coherent(Kb + off + sub * 8);
+        vreg[r] = ld_row16_coherent(Vb + off + sub * 8);
       }
       const bool valid = i < n;
       const u32x4 kv = kreg[r], vv = vreg[r];
@@ -2224,6 +2278,7 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
     }
     request_next(r0, std::false_type{});
   }
+  if (PAGED && bad_page) report(a, DE_BAD_PAGE, b, t0);   // (the rows came from page 0 instead: wrong, but in bounds)
   // ---- combine the lane groups of the wavefront, then the wavefronts
 #pragma unroll
   for (int j = 0; j < GRP; ++j) {
@@ -2406,10 +2461,150 @@ __device__ __forceinline__ void body_argmax(const TaskDesc& t, const StepArgs& a
       if (mi >= V) mi = 0;   // logits that are not numbers: keep the token in range
       st_act_u32((uint32_t*)const_cast<int32_t*>(a.token_ids) + b, mi);
       if (tokens_out) st_act_u32((uint32_t*)tokens_out + (size_t)a.step * B + b, mi);
-      if ((uint32_t)a.step + 1u == a.n_steps)
+      if ((uint32_t)a.step + 1u == a.n_steps && !(a.flags & kServeBit))   // (a serving launch: the serving task keeps the positions)
         st_act_u32((uint32_t*)const_cast<int32_t*>(a.positions) + b, (uint32_t)(a.positions[b] + (int32_t)a.n_steps));
     }
     lds_barrier();
+  }
+}
+
+// The task on the start event of a serving graph (paper Section 6.1: the scheduler prepares a new
+// decoding iteration by (1) removing completed requests, (2) admitting newly arrived requests and
+// (3) updating the per-request KV-cache metadata; "this logic executes as a single task").  The
+// paper fixes no policy; this one is the library's contract (mpk_serve_* in the public header):
+//   (1) a slot whose request still has prompt tokens is fed the next one (the sampled token is
+//       ignored: prompts go through the decode path a token per iteration); otherwise the sampled
+//       token is the request's next output, and the request is finished on the end-of-sequence
+//       token or with max_new tokens.  Finished slots, in ascending order, push their pages onto
+//       the free stack in page-table order.
+//   (2) idle slots, in ascending order, take the queued requests in arrival order, each only if
+//       the pages it can ever need, ceil((prompt + max_new - 1) / page), are free and not promised
+//       to running requests; the first request that does not fit ends admission (no overtaking).
+//   (3) a running slot whose position is at a page boundary pops a page (ascending slot order);
+//       an idle slot computes on token 0 at position 0 in its own page (page number = slot).
+// One wavefront, lane b = slot b (batch <= 16): every slot's state is loaded and stored once, the
+// sequential decisions (stack positions, admission) are prefix counts over lanes, so the task is
+// a handful of memory round trips however many slots change.  All state is read and written with
+// agent-scope accesses: attention tasks on other compute units read the tables in the same step.
+__device__ __forceinline__ void body_serve(const StepArgs& a) {
+  const ServeDev* Sp = a.g->serve;
+  if (threadIdx.x >= 64 || Sp == nullptr) return;
+  const ServeDev sv = *Sp;
+  const uint32_t lane = threadIdx.x, B = a.g->batch, n_pages = a.g->kv_pages;
+  const uint32_t shift = sv.page_shift, ps_mask = (1u << shift) - 1u;
+  const bool mine = lane < B;
+  const uint64_t below = (1ull << lane) - 1ull;
+  uint32_t* tok_io = (uint32_t*)const_cast<int32_t*>(a.token_ids);
+  uint32_t* pos_io = (uint32_t*)const_cast<int32_t*>(a.positions);
+  int32_t req = mine ? (int32_t)ld_relaxed((const uint32_t*)sv.slot_req + lane) : -1;
+  uint32_t pos = mine ? ld_relaxed((const uint32_t*)sv.slot_pos + lane) : 0u;
+  uint32_t held = mine ? ld_relaxed((const uint32_t*)sv.slot_held + lane) : 0u;
+  const uint32_t sampled = mine ? ld_relaxed(tok_io + lane) : 0u;
+  uint32_t n_free = __builtin_amdgcn_readfirstlane(ld_relaxed(sv.scalars + kServeNFree));
+  uint32_t promised = __builtin_amdgcn_readfirstlane(ld_relaxed(sv.scalars + kServePromised));
+  uint32_t q_head = __builtin_amdgcn_readfirstlane(ld_relaxed(sv.scalars + kServeQHead));
+  const uint32_t q_tail = __builtin_amdgcn_readfirstlane(ld_relaxed(sv.scalars + kServeQTail));
+  auto pages_of = [&](uint32_t plen, uint32_t max_new) { return (plen + max_new - 1u + ps_mask) >> shift; };
+  // ---- (1) completed requests leave
+  uint32_t nxt = 0, need = 0;
+  bool done = false, produced = false;
+  if (req >= 0) {
+    const uint32_t plen = ld_relaxed(sv.req_len + 2 * (size_t)req), max_new = ld_relaxed(sv.req_len + 2 * (size_t)req + 1);
+    need = pages_of(plen, max_new);
+    const uint32_t cached = pos + 1u;
+    if (cached < plen) {
+      nxt = ld_relaxed((const uint32_t*)sv.req_prompt + (size_t)req * sv.max_prompt + cached);
+    } else {
+      uint32_t n_out = ld_relaxed(sv.req_state + 2 * (size_t)req + 1);
+      if (n_out < sv.max_new) st_act_u32((uint32_t*)sv.req_out + (size_t)req * sv.max_new + n_out, sampled);
+      ++n_out;
+      st_act_u32(sv.req_state + 2 * (size_t)req + 1, n_out);
+      nxt = sampled;
+      produced = true;
+      done = (int32_t)sampled == sv.eos || n_out >= max_new;
+    }
+    pos = cached;
+  }
+  const uint32_t n_produced = (uint32_t)__builtin_popcountll(__ballot(produced));
+  for (uint64_t retiring = __ballot(done); retiring; retiring &= retiring - 1ull) {
+    const uint32_t b = (uint32_t)__builtin_ctzll(retiring);
+    const uint32_t hb = (uint32_t)__builtin_amdgcn_readlane((int)held, (int)b);
+    const uint32_t nb = (uint32_t)__builtin_amdgcn_readlane((int)need, (int)b);
+    uint32_t* row = (uint32_t*)sv.table + (size_t)b * sv.max_blocks;
+    for (uint32_t i = lane; i < hb && i < sv.max_blocks; i += 64u) {
+      const uint32_t pg = ld_relaxed(row + i);
+      if (n_free + i < n_pages) st_act_u32((uint32_t*)sv.free_stack + n_free + i, pg);
+      st_act_u32(row + i, i == 0u ? b : 0xFFFFFFFFu);   // the idle slot's own page; the rest: none
+    }
+    n_free += hb;
+    promised -= nb - hb;
+  }
+  if (done) {
+    st_act_u32(sv.req_state + 2 * (size_t)req, 2u);
+    req = -1;
+    held = 0;
+    pos = 0;
+  }
+  // the pages pushed above may be popped below, by other lanes: the stores must have completed
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  // ---- (2) arrivals enter, in order, while their pages are there
+  const bool idle = mine && req < 0;
+  const uint64_t idle_mask = __ballot(idle);
+  const uint32_t n_idle = (uint32_t)__builtin_popcountll(idle_mask);
+  uint32_t c_plen = 0, c_new = 0;   // lane i < 16: the request that is i-th in the queue
+  if (lane < 16u && q_head + lane < q_tail && q_head + lane < sv.max_requests) {
+    c_plen = ld_relaxed(sv.req_len + 2 * (size_t)(q_head + lane));
+    c_new = ld_relaxed(sv.req_len + 2 * (size_t)(q_head + lane) + 1);
+  }
+  const uint32_t c_need = pages_of(c_plen, c_new);
+  uint32_t n_admit = 0;
+  for (uint32_t k = 0; k < n_idle; ++k) {
+    if (q_head + k >= q_tail || q_head + k >= sv.max_requests) break;
+    const uint32_t nd = (uint32_t)__builtin_amdgcn_readlane((int)c_need, (int)k);
+    if (n_free - promised < nd) break;
+    promised += nd;
+    ++n_admit;
+  }
+  const uint32_t my_rank = (uint32_t)__builtin_popcountll(idle_mask & below) & 15u;
+  const uint32_t got_need = (uint32_t)__shfl((int)c_need, (int)my_rank, 64);   // (all lanes take part)
+  if (idle && my_rank < n_admit) {
+    req = (int32_t)(q_head + my_rank);
+    pos = 0;
+    held = 0;
+    need = got_need;
+    nxt = ld_relaxed((const uint32_t*)sv.req_prompt + (size_t)req * sv.max_prompt);
+    st_act_u32(sv.req_state + 2 * (size_t)req, 1u);
+  }
+  q_head += n_admit;
+  // ---- (3) the iteration's metadata
+  const bool act = mine && req >= 0;
+  const bool wants = act && (pos & ps_mask) == 0u;
+  const uint64_t want_mask = __ballot(wants);
+  if (wants) {
+    const uint32_t idx = n_free - 1u - (uint32_t)__builtin_popcountll(want_mask & below);
+    uint32_t pg = lane;   // (never taken: the admission rule keeps promised <= n_free)
+    if (idx < n_pages) pg = ld_relaxed((const uint32_t*)sv.free_stack + idx);
+    else report(a, DE_BAD_META, 0xFFFFFFFFu, idx);
+    const uint32_t blk = pos >> shift;
+    if (blk < sv.max_blocks) st_act_u32((uint32_t*)sv.table + (size_t)lane * sv.max_blocks + blk, pg);
+    ++held;
+  }
+  const uint32_t n_popped = (uint32_t)__builtin_popcountll(want_mask);
+  n_free -= n_popped;
+  promised -= n_popped;
+  if (mine) {
+    st_act_u32((uint32_t*)sv.slot_req + lane, (uint32_t)req);
+    st_act_u32((uint32_t*)sv.slot_pos + lane, act ? pos : 0u);
+    st_act_u32((uint32_t*)sv.slot_held + lane, held);
+    st_act_u32(tok_io + lane, act ? nxt : 0u);
+    st_act_u32(pos_io + lane, act ? pos : 0u);
+  }
+  if (lane == 0) {
+    st_act_u32(sv.scalars + kServeNFree, n_free);
+    st_act_u32(sv.scalars + kServePromised, promised);
+    st_act_u32(sv.scalars + kServeQHead, q_head);
+    st_act_u32(sv.scalars + kServeIterations, ld_relaxed(sv.scalars + kServeIterations) + 1u);
+    st_act_u32(sv.scalars + kServeTokens, ld_relaxed(sv.scalars + kServeTokens) + n_produced);
   }
 }
 
@@ -2434,6 +2629,20 @@ template <int D, int GRP, int NB>
 __device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, float* lds,
                                          int32_t wait_ev, uint32_t* s_flag) {
   if (t.kind == TK_ATTN_PARTIAL) {
+    if (t.flags & TF_KV_PAGED) {   // paged cache: one body for every chunk length
+      if (D != 0) return body_attn_partial<(D ? D : 128), (GRP ? GRP : 1), true>(t, a, lds, wait_ev, s_flag);
+      const uint32_t grp = a.g->n_q / a.g->n_kv;
+      if (a.g->head_dim == 128) {
+        if (grp == 8) return body_attn_partial<128, 8, true>(t, a, lds, wait_ev, s_flag);
+        if (grp == 4) return body_attn_partial<128, 4, true>(t, a, lds, wait_ev, s_flag);
+        if (grp == 2) return body_attn_partial<128, 2, true>(t, a, lds, wait_ev, s_flag);
+        return body_attn_partial<128, 1, true>(t, a, lds, wait_ev, s_flag);
+      }
+      if (grp == 8) return body_attn_partial<64, 8, true>(t, a, lds, wait_ev, s_flag);
+      if (grp == 4) return body_attn_partial<64, 4, true>(t, a, lds, wait_ev, s_flag);
+      if (grp == 2) return body_attn_partial<64, 2, true>(t, a, lds, wait_ev, s_flag);
+      return body_attn_partial<64, 1, true>(t, a, lds, wait_ev, s_flag);
+    }
     if (D != 0) {
       // chunks that always fit the register-resident body (wavefront-uniform: graph constants)
       constexpr uint32_t window = kAttnRounds * (kThreads / 64) * (64 / ((D ? D : 128) / 8));
@@ -2463,6 +2672,7 @@ __device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, f
     case TK_ADD: body_add(t); break;
     case TK_SWIGLU: body_swiglu(t); break;
     case TK_ARGMAX: body_argmax(t, a, lds); break;
+    case TK_SERVE: body_serve(a); break;
     default: break;   // TK_DUMMY: no computation (normalization, Section 4.1)
   }
   return true;

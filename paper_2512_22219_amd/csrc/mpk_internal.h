@@ -28,6 +28,8 @@ enum TaskKind : uint16_t {
   TK_MOE_EXPERT,    // a share of one expert stage (gate/up or down), sized from the meta-tensor
   TK_MOE_COMBINE,   // weighted sum of a token's expert outputs + residual
   TK_ARGMAX,        // greedy sampling: arg max of one sequence's logits -> next token
+  TK_SERVE,         // the task on the start event of a serving graph (paper Section 6.1): retires
+                    // finished requests, admits arrivals, updates the paged KV-cache metadata
 };
 
 enum TaskFlags : uint16_t {
@@ -50,6 +52,7 @@ enum TaskFlags : uint16_t {
                       // partial sums, and the task of a row block that arrives last (counter p2)
                       // adds the parts in order plus the residual into the real output (aux0).
                       // p1 = weight row length, p3 = parts | part << 8, K = length of the range
+  TF_KV_PAGED = 8192, // attention: cache rows are reached through the page table (GraphConst::page_table)
   TF_ATTN_BALANCE = 4096, // attention with fused merge, batch > 1: the batch x C chunk tasks of a KV
                       // head are dealt to the sequences in proportion to their lengths at run time
                       // (a task may work on another sequence than its row; its partial result
@@ -93,6 +96,28 @@ constexpr uint32_t EV_JIT = 1, EV_HIER = 2;
 // hop on this GPU; sharded, an arrival is one atomic add that nobody waits for.
 constexpr uint32_t kHierStrideWords = 64, kHierWordsPerEvent = 17 * kHierStrideWords;
 constexpr uint32_t kHierMinRequired = 48;
+
+// ---------------------------------------------------------------- serving state (device)
+// What the start-event task of a serving graph keeps in device memory (paper Section 6.1: "the
+// KV-cache metadata is stored in device memory for direct access by attention tasks").  One
+// record per server; the graph record points to it.  Slots are the batch rows of the graph.
+struct ServeDev {
+  int32_t* slot_req;         // [batch] request in the slot, -1 = idle
+  int32_t* slot_pos;         // [batch] rows cached = position of the token fed this iteration
+  int32_t* slot_held;        // [batch] pages the slot's request holds
+  int32_t* table;            // [batch][max_blocks] page of (slot, row / page_size); idle slot b: page b
+  int32_t* free_stack;       // [kv_pages] free pages, the top is popped first
+  uint32_t* scalars;         // kServe* below
+  const int32_t* req_prompt; // [max_requests][max_prompt]
+  const uint32_t* req_len;   // [max_requests][2]: prompt length, max_new_tokens
+  int32_t* req_out;          // [max_requests][max_new]
+  uint32_t* req_state;       // [max_requests][2]: 0 pending / 1 running / 2 done, tokens produced
+  uint32_t max_blocks, max_prompt, max_new, max_requests;
+  int32_t eos;
+  uint32_t page_shift;
+};
+enum : uint32_t { kServeNFree = 0, kServePromised = 1, kServeQHead = 2, kServeQTail = 3, kServeIterations = 4,
+                  kServeTokens = 5, kServeScalars = 8 };
 
 // ---------------------------------------------------------------- host-side graph
 struct HostOp {

@@ -103,6 +103,8 @@ struct mpk_graph {
   size_t st_counters = 0, st_hier = 0, st_grp = 0, st_arena = 0, st_need = 0;
   const char* static_refusal = "graph was compiled host_only";
   void* launch_out[2] = {nullptr, nullptr};   // host copy of GraphConst::tokens_out / logits_all (source of the async copy)
+  const int32_t* page_table = nullptr;        // paged cache: the table the attention tasks read (device)
+  struct mpk_server* server = nullptr;        // serving graph: the server attached to it
 };
 
 #define HIP_TRY(expr)                                                              \
@@ -385,6 +387,11 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
     c.evq_buf = g->d_evq_buf; c.evq_tail = g->d_evq_tail; c.sched_state = g->d_sched_state;
     c.sched_nev = g->d_sched_nev; c.wq_buf = g->d_wq_buf; c.wq_tail = g->d_wq_tail; c.wq_head = g->d_wq_head;
     c.start_event = h.start_event; c.terminal_event = h.terminal_event;
+    c.page_table = nullptr; c.serve = nullptr; c.serve_event = -1;
+    c.kv_pages = h.opt.kv_pages;
+    for (c.page_shift = 0; h.opt.kv_page_size && (1u << c.page_shift) < h.opt.kv_page_size; ++c.page_shift) {}
+    for (const TaskDesc& t : h.descs)
+      if (t.kind == TK_SERVE) c.serve_event = t.trig_event;
     std::vector<GraphConst> cv(1, c);
     if ((st = upload(&g->d_const, cv)) != MPK_OK) return fail(st);
     g->step_flags = (g->d_trace ? kTraceBit : 0u) | ((o.debug_flags & MPK_DEBUG_JITTER) ? kJitterBit : 0u) |
@@ -400,6 +407,7 @@ extern "C" mpk_status mpk_compile(const mpk_model_config* cfg, const mpk_weight_
     if (g->n_sched) g->static_refusal = "graph was compiled with scheduler workgroups";
     else if (h.opt.greedy_loop) g->static_refusal = "graph was compiled with greedy_loop";
     else if (g->d_trace) g->static_refusal = "graph was compiled with MPK_DEBUG_TRACE";
+    else if (h.opt.kv_page_size) g->static_refusal = "graph was compiled for a paged KV cache";
     else if (g->st_need > MPK_STATIC_SCRATCH_BYTES) g->static_refusal = "graph needs more scratch memory than the static array holds";
     if (!g->static_refusal) {
       if ((st = static_scratch_base(g->device, &g->static_base)) != MPK_OK) return fail(st);
@@ -523,6 +531,7 @@ extern "C" mpk_status mpk_decode_step(mpk_graph* g, const int32_t* token_ids,
   if (!g || !token_ids || !positions || !logits_out) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
   if (g->host_only) { set_error("graph was compiled host_only"); return MPK_ERR_INVALID_ARG; }
   if (g->h.opt.greedy_loop) { set_error("graph was compiled with greedy_loop: it samples and advances tokens and positions itself, run it with mpk_decode_steps"); return MPK_ERR_INVALID_ARG; }
+  if (g->h.opt.kv_page_size && !g->page_table) { set_error("the graph reads a paged KV cache: give it a page table first (mpk_graph_set_page_table)"); return MPK_ERR_INVALID_ARG; }
   return launch_steps(g, 1, token_ids, positions, nullptr, logits_out, nullptr, stream);
 }
 
@@ -548,6 +557,8 @@ extern "C" mpk_status mpk_decode_steps(mpk_graph* g, uint32_t n_steps, int32_t* 
   if (!g->h.opt.greedy_loop) { set_error("mpk_decode_steps needs a graph compiled with greedy_loop = 1"); return MPK_ERR_INVALID_ARG; }
   if (n_steps == 0 || n_steps > g->h.cfg.max_seq || n_steps > 65535u) { set_error("n_steps %u out of range (1..min(max_seq, 65535))", n_steps); return MPK_ERR_INVALID_ARG; }
   if (g->n_sched && n_steps > 1) { set_error("several steps per launch are only supported without scheduler workgroups"); return MPK_ERR_UNSUPPORTED; }
+  if (g->h.opt.serving) { set_error("a serving graph is run through its server (mpk_serve_run)"); return MPK_ERR_INVALID_ARG; }
+  if (g->h.opt.kv_page_size && !g->page_table) { set_error("the graph reads a paged KV cache: give it a page table first (mpk_graph_set_page_table)"); return MPK_ERR_INVALID_ARG; }
   return launch_steps(g, n_steps, token_ids, positions, tokens_out, logits_out, logits_all, stream);
 }
 
@@ -566,6 +577,9 @@ extern "C" mpk_status mpk_graph_status(mpk_graph* g) {
       return MPK_ERR_DEVICE;
     case DE_BAD_TOKEN:
       set_error("sequence %u has token %d outside [0, vocab)", err[2], (int)err[3]);
+      return MPK_ERR_DEVICE;
+    case DE_BAD_PAGE:
+      set_error("sequence %u: a page-table entry for rows from %u on is outside the pool", err[2], err[3]);
       return MPK_ERR_DEVICE;
     case DE_BAD_META:
       set_error("an expert task found an inconsistent meta-tensor (expert %u, %u tokens)", err[2], err[3]);
@@ -683,7 +697,8 @@ extern "C" mpk_status mpk_compile_set(const mpk_model_config* cfg, const mpk_wei
     o.struct_size = sizeof(o);
   }
   if (o.kv_batch != 0) { set_error("kv_batch is set by mpk_compile_set itself"); return MPK_ERR_INVALID_ARG; }
-  o.kv_batch = cfg->batch;
+  if (o.serving) { set_error("a serving graph is compiled for the maximum batch alone (idle slots cost next to nothing)"); return MPK_ERR_UNSUPPORTED; }
+  if (!o.kv_page_size) o.kv_batch = cfg->batch;   // (a paged pool has no batch extent: every graph reads it through its table)
   mpk_graph_set* s = new (std::nothrow) mpk_graph_set();
   if (!s) { set_error("out of host memory"); return MPK_ERR_OOM; }
   std::vector<uint32_t> sizes;
@@ -724,10 +739,189 @@ extern "C" mpk_status mpk_set_decode_step(mpk_graph_set* s, uint32_t n_active, c
   return MPK_ERR_INVALID_ARG;
 }
 
+// ------------------------------------------------------------------ paged cache and serving
+extern "C" mpk_status mpk_graph_set_page_table(mpk_graph* g, const int32_t* page_table) {
+  if (!g || !page_table) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
+  if (g->host_only) { set_error("graph was compiled host_only"); return MPK_ERR_INVALID_ARG; }
+  if (!g->h.opt.kv_page_size) { set_error("the graph was compiled for a contiguous KV cache"); return MPK_ERR_INVALID_ARG; }
+  if (g->h.opt.serving) { set_error("a serving graph's page table belongs to its server"); return MPK_ERR_INVALID_ARG; }
+  HIP_TRY(hipMemcpy((char*)g->d_const + offsetof(GraphConst, page_table), &page_table, sizeof(page_table), hipMemcpyHostToDevice));
+  g->page_table = page_table;
+  return MPK_OK;
+}
+
+struct mpk_server {
+  mpk_graph* g = nullptr;
+  mpk_serve_config cfg{};
+  uint32_t batch = 0, max_blocks = 0, n_submitted = 0;
+  // device state (ServeDev points into these)
+  int32_t *d_slot = nullptr, *d_table = nullptr, *d_free = nullptr, *d_prompt = nullptr, *d_out = nullptr;
+  int32_t *d_tokens = nullptr, *d_positions = nullptr;
+  uint32_t *d_scalars = nullptr, *d_len = nullptr, *d_state = nullptr;
+  float* d_logits = nullptr;
+  ServeDev* d_rec = nullptr;
+  // host staging that outlives the asynchronous copies of mpk_serve_submit
+  std::vector<std::vector<int32_t>> prompts;
+  std::vector<uint32_t> lens, tails;
+};
+
+static void server_free(mpk_server* s) {
+  (void)hipFree(s->d_slot); (void)hipFree(s->d_table); (void)hipFree(s->d_free); (void)hipFree(s->d_prompt);
+  (void)hipFree(s->d_out); (void)hipFree(s->d_tokens); (void)hipFree(s->d_positions); (void)hipFree(s->d_scalars);
+  (void)hipFree(s->d_len); (void)hipFree(s->d_state); (void)hipFree(s->d_logits); (void)hipFree(s->d_rec);
+}
+
+extern "C" mpk_status mpk_serve_create(mpk_graph* g, const mpk_serve_config* cfg, mpk_server** out) {
+  if (out) *out = nullptr;
+  if (!g || !cfg || !out) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
+  if (cfg->struct_size != sizeof(mpk_serve_config)) { set_error("mpk_serve_config.struct_size is %u, expected %zu", cfg->struct_size, sizeof(mpk_serve_config)); return MPK_ERR_INVALID_ARG; }
+  if (g->host_only || !g->h.opt.serving) { set_error("the graph was not compiled with serving = 1 (or is host_only)"); return MPK_ERR_INVALID_ARG; }
+  if (g->server) { set_error("the graph already has a server"); return MPK_ERR_INVALID_ARG; }
+  const mpk_model_config& c = g->h.cfg;
+  const uint32_t ps = g->h.opt.kv_page_size, n_pages = g->h.opt.kv_pages, B = c.batch;
+  if (!cfg->max_requests || !cfg->max_prompt || !cfg->max_new || cfg->max_prompt > c.max_seq || cfg->max_new > c.max_seq ||
+      cfg->max_requests > (1u << 20)) {
+    set_error("mpk_serve_config: max_requests (1..2^20), max_prompt and max_new (1..max_seq) out of range");
+    return MPK_ERR_INVALID_ARG;
+  }
+  int cur = -1;
+  HIP_TRY(hipGetDevice(&cur));
+  if (cur != g->device) { set_error("the graph lives on device %d, device %d is current", g->device, cur); return MPK_ERR_INVALID_ARG; }
+  mpk_server* s = new (std::nothrow) mpk_server();
+  if (!s) { set_error("out of host memory"); return MPK_ERR_OOM; }
+  s->g = g; s->cfg = *cfg; s->batch = B; s->max_blocks = c.max_seq / ps;
+  auto fail = [&](mpk_status st) { server_free(s); delete s; return st; };
+  // initial state: every slot idle in its own page, every other page free (lowest number on top)
+  std::vector<int32_t> slot(3 * (size_t)B, 0), table((size_t)B * s->max_blocks, -1), free_stack(n_pages, -1), zb(B, 0);
+  for (uint32_t b = 0; b < B; ++b) { slot[b] = -1; table[(size_t)b * s->max_blocks] = (int32_t)b; }
+  for (uint32_t i = 0; i + B < n_pages; ++i) free_stack[i] = (int32_t)(n_pages - 1 - i);
+  std::vector<uint32_t> scalars(kServeScalars, 0);
+  scalars[kServeNFree] = n_pages - B;
+  std::vector<int32_t> prompt0((size_t)cfg->max_requests * cfg->max_prompt, 0), out0((size_t)cfg->max_requests * cfg->max_new, -1);
+  std::vector<uint32_t> len0(2 * (size_t)cfg->max_requests, 0);
+  std::vector<float> lg((size_t)B * c.vocab, 0.f);
+  mpk_status st;
+  if ((st = upload(&s->d_slot, slot)) != MPK_OK || (st = upload(&s->d_table, table)) != MPK_OK ||
+      (st = upload(&s->d_free, free_stack)) != MPK_OK || (st = upload(&s->d_scalars, scalars)) != MPK_OK ||
+      (st = upload(&s->d_prompt, prompt0)) != MPK_OK || (st = upload(&s->d_out, out0)) != MPK_OK ||
+      (st = upload(&s->d_len, len0)) != MPK_OK || (st = upload(&s->d_state, len0)) != MPK_OK ||
+      (st = upload(&s->d_tokens, zb)) != MPK_OK || (st = upload(&s->d_positions, zb)) != MPK_OK ||
+      (st = upload(&s->d_logits, lg)) != MPK_OK)
+    return fail(st);
+  ServeDev rec{};
+  rec.slot_req = s->d_slot; rec.slot_pos = s->d_slot + B; rec.slot_held = s->d_slot + 2 * B;
+  rec.table = s->d_table; rec.free_stack = s->d_free; rec.scalars = s->d_scalars;
+  rec.req_prompt = s->d_prompt; rec.req_len = s->d_len; rec.req_out = s->d_out; rec.req_state = s->d_state;
+  rec.max_blocks = s->max_blocks; rec.max_prompt = cfg->max_prompt; rec.max_new = cfg->max_new;
+  rec.max_requests = cfg->max_requests; rec.eos = cfg->eos_token;
+  for (rec.page_shift = 0; (1u << rec.page_shift) < ps; ++rec.page_shift) {}
+  std::vector<ServeDev> rv(1, rec);
+  if ((st = upload(&s->d_rec, rv)) != MPK_OK) return fail(st);
+  const void* ptrs[2] = {s->d_table, s->d_rec};
+  static_assert(offsetof(GraphConst, serve) == offsetof(GraphConst, page_table) + sizeof(void*), "page_table and serve are adjacent");
+  if (hipMemcpy((char*)g->d_const + offsetof(GraphConst, page_table), ptrs, sizeof(ptrs), hipMemcpyHostToDevice) != hipSuccess) {
+    set_error("hipMemcpy of the serving record failed");
+    return fail(MPK_ERR_HIP);
+  }
+  s->lens.reserve(2 * (size_t)cfg->max_requests);
+  s->tails.reserve(cfg->max_requests);
+  g->page_table = s->d_table;
+  g->server = s;
+  *out = s;
+  return MPK_OK;
+}
+
+extern "C" mpk_status mpk_serve_submit(mpk_server* s, const int32_t* prompt, uint32_t prompt_len, uint32_t max_new_tokens,
+                                       void* stream, uint32_t* request_id) {
+  if (!s || !prompt) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
+  const mpk_model_config& c = s->g->h.cfg;
+  const uint32_t ps = s->g->h.opt.kv_page_size;
+  if (s->n_submitted >= s->cfg.max_requests) { set_error("the server has taken its max_requests = %u requests", s->cfg.max_requests); return MPK_ERR_UNSUPPORTED; }
+  if (prompt_len == 0 || prompt_len > s->cfg.max_prompt || max_new_tokens == 0 || max_new_tokens > s->cfg.max_new) {
+    set_error("prompt_len %u (1..%u) or max_new_tokens %u (1..%u) out of range", prompt_len, s->cfg.max_prompt, max_new_tokens, s->cfg.max_new);
+    return MPK_ERR_INVALID_ARG;
+  }
+  const uint64_t rows = (uint64_t)prompt_len + max_new_tokens - 1;
+  if (rows > c.max_seq) { set_error("the request would cache %llu rows, max_seq is %u", (unsigned long long)rows, c.max_seq); return MPK_ERR_INVALID_ARG; }
+  if ((rows + ps - 1) / ps > s->g->h.opt.kv_pages - c.batch) { set_error("the request needs more pages than the pool can ever free"); return MPK_ERR_INVALID_ARG; }
+  for (uint32_t i = 0; i < prompt_len; ++i)
+    if (prompt[i] < 0 || (uint32_t)prompt[i] >= c.vocab) { set_error("prompt token %u is %d, outside [0, vocab)", i, prompt[i]); return MPK_ERR_INVALID_ARG; }
+  const uint32_t r = s->n_submitted;
+  s->prompts.emplace_back(prompt, prompt + prompt_len);
+  s->lens.push_back(prompt_len); s->lens.push_back(max_new_tokens);
+  s->tails.push_back(r + 1);
+  hipStream_t st = (hipStream_t)stream;
+  HIP_TRY(hipMemcpyAsync(s->d_prompt + (size_t)r * s->cfg.max_prompt, s->prompts.back().data(), prompt_len * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  HIP_TRY(hipMemcpyAsync(s->d_len + 2 * (size_t)r, &s->lens[2 * (size_t)r], 2 * sizeof(uint32_t), hipMemcpyHostToDevice, st));
+  // the queue's tail last: a request is visible to the serving task only with its prompt in place
+  HIP_TRY(hipMemcpyAsync(s->d_scalars + kServeQTail, &s->tails[r], sizeof(uint32_t), hipMemcpyHostToDevice, st));
+  s->n_submitted = r + 1;
+  if (request_id) *request_id = r;
+  return MPK_OK;
+}
+
+extern "C" mpk_status mpk_serve_run(mpk_server* s, uint32_t n_iterations, void* stream) {
+  if (!s) { set_error("NULL server"); return MPK_ERR_INVALID_ARG; }
+  if (n_iterations == 0 || n_iterations > 65535u) { set_error("n_iterations %u out of range (1..65535)", n_iterations); return MPK_ERR_INVALID_ARG; }
+  mpk_graph* g = s->g;
+  const uint32_t keep = g->step_flags;
+  g->step_flags |= kServeBit;
+  const mpk_status st = launch_steps(g, n_iterations, s->d_tokens, s->d_positions, nullptr, s->d_logits, nullptr, stream);
+  g->step_flags = keep;
+  return st;
+}
+
+extern "C" mpk_status mpk_serve_result(mpk_server* s, uint32_t request_id, int32_t* tokens, size_t cap, uint32_t* n_tokens,
+                                       uint32_t* state) {
+  if (!s || !n_tokens || !state) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
+  if (request_id >= s->n_submitted) { set_error("request %u was never submitted", request_id); return MPK_ERR_INVALID_ARG; }
+  uint32_t st[2] = {0, 0};
+  HIP_TRY(hipMemcpy(st, s->d_state + 2 * (size_t)request_id, sizeof(st), hipMemcpyDeviceToHost));
+  *state = st[0];
+  *n_tokens = st[1];
+  const size_t n = std::min<size_t>(st[1], cap);
+  if (n && tokens) HIP_TRY(hipMemcpy(tokens, s->d_out + (size_t)request_id * s->cfg.max_new, n * sizeof(int32_t), hipMemcpyDeviceToHost));
+  return MPK_OK;
+}
+
+extern "C" mpk_status mpk_serve_state(mpk_server* s, int32_t* buf, size_t cap, size_t* need) {
+  if (!s || !need) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
+  const uint32_t B = s->batch, mb = s->max_blocks, n_pages = s->g->h.opt.kv_pages;
+  const size_t n = 8 + 5 * (size_t)B + (size_t)B * mb + n_pages;
+  *need = n;
+  if (!buf || cap < n) return MPK_OK;
+  uint32_t sc[kServeScalars];
+  HIP_TRY(hipMemcpy(sc, s->d_scalars, sizeof(sc), hipMemcpyDeviceToHost));
+  buf[0] = (int32_t)B; buf[1] = (int32_t)mb; buf[2] = (int32_t)sc[kServeNFree]; buf[3] = (int32_t)sc[kServePromised];
+  buf[4] = (int32_t)sc[kServeQHead]; buf[5] = (int32_t)sc[kServeQTail]; buf[6] = (int32_t)sc[kServeIterations]; buf[7] = (int32_t)sc[kServeTokens];
+  int32_t* p = buf + 8;
+  HIP_TRY(hipMemcpy(p, s->d_slot, 3 * (size_t)B * sizeof(int32_t), hipMemcpyDeviceToHost)); p += 3 * (size_t)B;
+  HIP_TRY(hipMemcpy(p, s->d_tokens, B * sizeof(int32_t), hipMemcpyDeviceToHost)); p += B;
+  HIP_TRY(hipMemcpy(p, s->d_positions, B * sizeof(int32_t), hipMemcpyDeviceToHost)); p += B;
+  HIP_TRY(hipMemcpy(p, s->d_table, (size_t)B * mb * sizeof(int32_t), hipMemcpyDeviceToHost)); p += (size_t)B * mb;
+  HIP_TRY(hipMemcpy(p, s->d_free, (size_t)n_pages * sizeof(int32_t), hipMemcpyDeviceToHost));
+  return MPK_OK;
+}
+
+extern "C" const float* mpk_serve_logits(const mpk_server* s) { return s ? s->d_logits : nullptr; }
+
+extern "C" void mpk_serve_destroy(mpk_server* s) {
+  if (!s) return;
+  (void)hipSetDevice(s->g->device);
+  (void)hipDeviceSynchronize();
+  const void* none[2] = {nullptr, nullptr};
+  (void)hipMemcpy((char*)s->g->d_const + offsetof(GraphConst, page_table), none, sizeof(none), hipMemcpyHostToDevice);
+  s->g->page_table = nullptr;
+  s->g->server = nullptr;
+  server_free(s);
+  delete s;
+}
+
 extern "C" const char* mpk_last_error(void) { return mpk::last_error(); }
 
 extern "C" void mpk_graph_destroy(mpk_graph* g) {
   if (!g) return;
+  if (g->server) mpk_serve_destroy(g->server);
   if (!g->host_only) {
     (void)hipSetDevice(g->device);
     (void)hipDeviceSynchronize();

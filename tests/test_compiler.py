@@ -53,6 +53,9 @@ CASES = [
     # greedy sampling as an operator of the graph (multi-token launch)
     ("C1", dict(batch=3), dict(fusion=31, n_workers=24, greedy_loop=1)),
     ("C1", {}, dict(fusion=0, greedy_loop=1)),
+    # serving graphs (Section 6.1): the serving task first, every embedding task behind it
+    ("C1", dict(batch=3), dict(fusion=31, greedy_loop=1, kv_page_size=16, kv_pages=40, serving=1)),
+    ("C1", dict(batch=8), dict(fusion=31, greedy_loop=1, kv_page_size=32, kv_pages=64, serving=1, n_workers=40)),
     # QKV heads cut unevenly, 3 tiles of 43, 43, 42 rows per head: 80 heads (the 70B shape) and 48 heads
     # (the 8B shape with 240 tiles per linear operator)
     ("C5", dict(n_layers=1), dict(fusion=31)),
@@ -95,7 +98,7 @@ def closure_by_op_tile(psets):
     return {(o, t): go((o, t)) for o in range(len(psets)) for t in range(len(psets[o]))}
 
 
-@pytest.mark.parametrize("base,variant,opts", CASES[:5] + CASES[8:12])
+@pytest.mark.parametrize("base,variant,opts", CASES[:5] + CASES[8:12] + [c for c in CASES if c[2].get("serving")])
 def test_transitive_reduction_keeps_closures(base, variant, opts):
     shape = G.small_variant(base, **variant)
     g = host_graph(shape, transitive_reduction=1, **opts)
