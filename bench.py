@@ -83,6 +83,11 @@ def main():
                          "--steps must be a multiple of N")
     ap.add_argument("--opt", action="append", default=[], metavar="NAME=INT",
                     help="extra mpk_compile_options field, e.g. --opt attn_chunks=32")
+    ap.add_argument("--serving", type=int, default=0, metavar="PAGE_SIZE",
+                    help="also time the same workload served from inside the kernel (paged KV cache of this "
+                         "page size, serving task on the start event, --steps iterations in one launch) and "
+                         "attach it as the 'serving' sub-record; prompts are fed through the decode path "
+                         "first, off the clock, until every slot stands at the workload's KV length")
     ap.add_argument("--no-batch8", action="store_true",
                     help="default run (C2, batch 1) only: skip the batch-8 half of the metric (C3)")
     args = ap.parse_args()
@@ -91,6 +96,8 @@ def main():
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     out = measure(args, args.config, baselines=not args.no_baselines, cpu=not args.no_cpu)
+    if args.serving:
+        out["serving"] = measure_serving(args, args.config, args.serving)
     if args.config == "C2" and not args.no_batch8 and args.tokens_per_launch == 1:
         # the metric is ms/token at batch 1 AND 8: the batch-8 shape (C3) timed the same way, as a
         # sub-record of the same line
@@ -102,6 +109,84 @@ def main():
             if k in b8:
                 out["batch8"][k] = b8[k]
     print(json.dumps(out))
+
+
+def measure_serving(args, config, page_size):
+    """The workload of `config` served from inside the persistent kernel (paper Section 6.1):
+    one request per batch slot, its prompt as long as the slot's KV length in the workload, fed
+    through the decode path off the clock (requests are submitted longest first, so that all
+    slots reach their lengths in the same iteration); then args.steps iterations -- serving
+    task, decode step through the page tables, greedy sampling -- timed as ONE launch."""
+    import numpy as np
+    import torch
+    import paper_2512_22219_amd as M
+    from synth import gen as G
+    from synth.device import DeviceModel
+
+    shape = G.CONFIGS[config]
+    seed = 0
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    model = DeviceModel(shape, seed, dev)
+    model.k = model.v = None          # the contiguous cache is not used here
+    torch.cuda.empty_cache()
+    n_pages = shape.batch + shape.batch * (shape.max_seq // page_size)
+    pools = []
+    for which in (G.L_KCACHE, G.L_VCACHE):
+        pool = torch.empty((shape.n_layers, n_pages, shape.n_kv_heads, page_size, shape.head_dim),
+                           dtype=torch.bfloat16, device=dev)
+        for l in range(shape.n_layers):
+            G.fill_device(pool[l], seed, G.layer_tid(l, which), 0, "kv")
+        pools.append(pool)
+    common = dict(fusion=args.fusion, transitive_reduction=1)
+    common.update({k: int(v) for k, v in (o.split("=", 1) for o in args.opt)})
+    graph = M.compile_graph(shape, model.weight_ptrs(), (pools[0].data_ptr(), pools[1].data_ptr()), launch_mode=0,
+                            greedy_loop=1, serving=1, kv_page_size=page_size, kv_pages=n_pages, **common)
+    stats = graph.stats()
+    lens = sorted((int(x) for x in G.kv_lengths(seed, shape)), reverse=True)
+    max_new = args.steps + args.warmup + 1          # nobody finishes on the clock
+    assert lens[0] + max_new - 1 <= shape.max_seq
+    srv = graph.serve(shape.batch, lens[0], max_new, -1)
+    stream = torch.cuda.current_stream().cuda_stream
+    rng = np.random.default_rng(seed)
+
+    def run(n):
+        while n > 0:
+            k = min(n, 4096)
+            srv.run(k, stream)
+            n -= k
+
+    for i, L in enumerate(lens):
+        srv.submit(rng.integers(0, shape.vocab, L), max_new, stream)
+        run((L - lens[i + 1]) if i + 1 < len(lens) else L + args.warmup)
+    torch.cuda.synchronize()
+    graph.status()
+    st = srv.state()
+    assert sorted(st["positions"], reverse=True) == [L + args.warmup - 1 for L in lens], st["positions"]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    srv.run(args.steps, stream)
+    e1.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    graph.status()
+    st = srv.state()
+    assert all(r >= 0 for r in st["slot_req"]) and st["iterations"] == lens[0] + args.warmup + args.steps
+    ms = dt * 1e3 / args.steps
+    pos_avg = float(sum(lens)) + shape.batch * (args.warmup + (args.steps - 1) / 2 + 1)
+    bytes_step = stats["weight_bytes"] + stats["kv_row_bytes"] * pos_avg
+    kern_ms = e0.elapsed_time(e1) / args.steps
+    out = {"ms_per_iteration": ms, "tokens_per_s": shape.batch * 1e3 / ms, "kernel_ms_per_iteration": kern_ms,
+           "iterations_per_launch": args.steps, "page_size": page_size, "kv_pages": n_pages,
+           "achieved_hbm_GBps": bytes_step / (kern_ms * 1e-3) / 1e9,
+           "prompt_iterations_off_the_clock": lens[0] + args.warmup,
+           "tokens_produced": st["tokens_produced"]}
+    srv.destroy()
+    graph.destroy()
+    del model, pools
+    torch.cuda.empty_cache()
+    return out
 
 
 def measure(args, config, baselines=True, cpu=True):

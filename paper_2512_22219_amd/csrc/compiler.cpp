@@ -1035,6 +1035,8 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
     else if (op.kind == MPK_OP_ATTN_PARTIAL)
       f = (size_t)grp * c.head_dim                                        // q
           + (size_t)(kThreads * 8 / c.head_dim) * grp * (c.head_dim + 4) + 16 + 64;   // partials per position slot (register-resident body; the other keeps one per wavefront)
+    if (op.kind == MPK_OP_ATTN_PARTIAL && g.opt.kv_page_size)   // paged cache: + the chunk's page numbers
+      f += c.max_seq / g.opt.kv_page_size;
     need = std::max(need, f);
   }
   size_t bytes = (need + kLdsReduceFloats + kLdsCtrlFloats) * sizeof(float);   // + the control words

@@ -1661,6 +1661,16 @@ __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
+// Position of sequence b in this step.  positions[] is the host's and stays as written for the
+// whole launch (tasks add the step number) -- except in a serving launch, where the serving task
+// rewrites it at the start of every step: then it holds the step's own positions and is read with
+// coherent loads, after the serving task's event.
+template <bool PAGED>
+__device__ __forceinline__ int32_t step_position(const StepArgs& a, uint32_t b) {
+  if (PAGED && (a.flags & kServeBit)) return (int32_t)ld_relaxed((const uint32_t*)a.positions + b);
+  return a.positions[b] + (int32_t)a.step;
+}
+
 // T4, short chunks: the same task when a chunk never exceeds kAttnRounds rounds (8 x 32 = 256 cache
 // positions at head_dim 128): all of its K and V rows are requested before the event wait and
 // stay in registers, scores are formed once, one chunk-wide maximum, one exp per score.  Fewer
@@ -1675,7 +1685,7 @@ __device__ __forceinline__ float group_sum(float v) {
 // arrive later.  Scores, probabilities and the running sums stay in registers.
 constexpr int kAttnRounds = 8;
 
-template <int D, int GRP>
+template <int D, int GRP, bool PAGED = false>
 __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const StepArgs& a, float* lds,
                                                   int32_t wait_ev, uint32_t* s_flag) {
   constexpr uint32_t d = D, grp = GRP, LPP = D / 8, PPW = 64 / LPP, NW = kThreads / 64;
@@ -1683,18 +1693,45 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
   constexpr uint32_t WS = d + 4;   // row of one partial in LDS: output, max, sum; 16-byte aligned rows
   const uint32_t nq = a.g->n_q, nkv = a.g->n_kv, C = t.p1;
   const uint32_t b = t.b0, u = t.c0 / per, g = u / C, c = u % C;
+  // (paged cache: positions and page table are this step's once the serving task has run -- see
+  // the running-softmax body below)
+  if (PAGED && wait_ev >= 0 && a.g->serve_event >= 0 && !wait_event(a, a.g->serve_event, s_flag)) return false;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   float* qs = lds;                       // [grp][d]
   float* wpart = qs + grp * d;           // [NW * PPW][grp][WS]: partial output and sum per position slot
   uint32_t* flag = (uint32_t*)(wpart + stride * grp * WS);    // then [16..) the maxima exchange
   float* outp = t.out + (size_t)b * t.ld_out + t.c0;
-  const int32_t pos = a.positions[b] + (int32_t)a.step;    // written by the host before the launch
+  const int32_t pos = step_position<PAGED>(a, b);    // written by the host before the launch (or by the serving task)
   const bool bad_pos = pos < 0 || (uint32_t)pos >= a.g->max_seq;
   const uint32_t len = bad_pos ? 0u : (uint32_t)pos + 1;
   const uint32_t t0 = (uint32_t)((uint64_t)c * len / C), t1 = (uint32_t)((uint64_t)(c + 1) * len / C);
   const uint32_t n = t1 - t0;
-  const uint16_t* Kb = (const uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.g->max_seq + t0) * d;
-  const uint16_t* Vb = (const uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.g->max_seq + t0) * d;
+  const uint16_t* Kb = (const uint16_t*)t.aux0 + (PAGED ? (size_t)0 : (((size_t)b * nkv + g) * a.g->max_seq + t0) * d);
+  const uint16_t* Vb = (const uint16_t*)t.aux1 + (PAGED ? (size_t)0 : (((size_t)b * nkv + g) * a.g->max_seq + t0) * d);
+  // paged: the chunk's page numbers, staged in LDS (behind the maxima exchange)
+  const uint32_t pshift = PAGED ? a.g->page_shift : 0u;
+  const uint32_t pg0 = t0 >> pshift;
+  uint32_t* pgs = flag + 48;
+  bool bad_page = false;
+  if constexpr (PAGED) {
+    const uint32_t* ptab = (const uint32_t*)a.g->page_table + (size_t)b * (a.g->max_seq >> pshift);
+    const uint32_t npg = n ? ((t1 - 1u) >> pshift) - pg0 + 1u : 0u;
+    for (uint32_t i = threadIdx.x; i < npg; i += kThreads) {
+      uint32_t pg = ld_relaxed(ptab + pg0 + i);
+      if (pg >= a.g->kv_pages) { bad_page = true; pg = 0; }
+      pgs[i] = pg;
+    }
+    __syncthreads();
+    if (bad_page) report(a, DE_BAD_PAGE, b, t0);   // (its rows come from page 0 instead: wrong, but in bounds)
+  }
+  auto row_off = [&](uint32_t i) -> size_t {   // element offset of row i of the chunk from Kb / Vb
+    if constexpr (PAGED) {
+      const uint32_t r = t0 + i;
+      return ((((size_t)pgs[(r >> pshift) - pg0] * nkv + g) << pshift) + (r & ((1u << pshift) - 1u))) * d;
+    } else {
+      return (size_t)i * d;
+    }
+  };
   const uint32_t sub = lane % LPP, slot = lane / LPP;
   const uint32_t i_first = wave * PPW + slot;
   const uint32_t n_rounds = (n + stride - 1) / stride;
@@ -1707,8 +1744,9 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
       kreg[r] = u32x4{0, 0, 0, 0};
       vreg[r] = u32x4{0, 0, 0, 0};
       if (i < n && t0 + i != (uint32_t)pos) {
-        kreg[r] = ld_stream16(Kb + (size_t)i * d + sub * 8);
-        vreg[r] = ld_stream16(Vb + (size_t)i * d + sub * 8);
+        const size_t off = row_off(i);
+        kreg[r] = ld_stream16(Kb + off + sub * 8);
+        vreg[r] = ld_stream16(Vb + off + sub * 8);
       }
     }
   };
@@ -1763,8 +1801,15 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
     if (c == C - 1) {
       const float* ksrc = t.in + (size_t)b * t.ld_in + (size_t)(nq + g) * d;
       const float* vsrc = t.in + (size_t)b * t.ld_in + (size_t)(nq + nkv + g) * d;
-      uint16_t* krow = (uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
-      uint16_t* vrow = (uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
+      uint16_t *krow, *vrow;
+      if constexpr (PAGED) {
+        const size_t off = row_off((uint32_t)pos - t0);
+        krow = const_cast<uint16_t*>(Kb) + off;
+        vrow = const_cast<uint16_t*>(Vb) + off;
+      } else {
+        krow = (uint16_t*)t.aux0 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
+        vrow = (uint16_t*)t.aux1 + (((size_t)b * nkv + g) * a.g->max_seq + (uint32_t)pos) * d;
+      }
       // threads from the top of the workgroup, so that they do not also rotate query pairs
       for (uint32_t i = kThreads - 1 - threadIdx.x; i < half / 2 + half; i += kThreads) {
         if (i < half / 2) {   // two adjacent rotation pairs of the key
@@ -1804,8 +1849,9 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
 #pragma unroll
     for (int r = 0; r < kAttnRounds; ++r) {
       if (i_first + r * stride == i_new) {
-        kreg[r] = ld_row16_coherent(Kb + (size_t)i_new * d + sub * 8);
-        vreg[r] = ld_row16_coherent(Vb + (size_t)i_new * d + sub * 8);
+        const size_t off = row_off(i_new);
+        kreg[r] = ld_row16_coherent(Kb + off + sub * 8);
+        vreg[r] = ld_row16_coherent(Vb + off + sub * 8);
       }
     }
   }
@@ -1976,16 +2022,6 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
 // ties).  A pure function of the positions, worked out by every wavefront for itself (lane b <
 // batch holds sequence b; batch <= 16).  Returns the sequence of task v, the task's chunk number
 // there, the sequence's chunk count and its first task.
-// Position of sequence b in this step.  positions[] is the host's and stays as written for the
-// whole launch (tasks add the step number) -- except in a serving launch, where the serving task
-// rewrites it at the start of every step: then it holds the step's own positions and is read with
-// coherent loads, after the serving task's event.
-template <bool PAGED>
-__device__ __forceinline__ int32_t step_position(const StepArgs& a, uint32_t b) {
-  if (PAGED && (a.flags & kServeBit)) return (int32_t)ld_relaxed((const uint32_t*)a.positions + b);
-  return a.positions[b] + (int32_t)a.step;
-}
-
 template <bool PAGED>
 __device__ __forceinline__ void attn_deal(const StepArgs& a, uint32_t C, uint32_t v, uint32_t* seq, uint32_t* chunk,
                                           uint32_t* chunks, uint32_t* first) {
@@ -2078,16 +2114,27 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
   // contiguous cache: the chunk's first row; paged: the layer's pools
   const uint16_t* Kb = (const uint16_t*)t.aux0 + (PAGED ? (size_t)0 : (((size_t)b * nkv + g) * a.g->max_seq + t0) * d);
   const uint16_t* Vb = (const uint16_t*)t.aux1 + (PAGED ? (size_t)0 : (((size_t)b * nkv + g) * a.g->max_seq + t0) * d);
+  // paged: the page numbers of the chunk's rows go to LDS first (one coherent load per page, all in
+  // flight together), so that a row's address costs an LDS read, not a trip to memory
   const uint32_t pshift = PAGED ? a.g->page_shift : 0u;
-  const uint32_t* ptab = PAGED ? (const uint32_t*)a.g->page_table + (size_t)b * (a.g->max_seq >> pshift) : nullptr;
+  const uint32_t pg0 = t0 >> pshift;
+  uint32_t* pgs = flag + 16;
   bool bad_page = false;
+  if constexpr (PAGED) {
+    const uint32_t* ptab = (const uint32_t*)a.g->page_table + (size_t)b * (a.g->max_seq >> pshift);
+    const uint32_t npg = n ? ((t1 - 1u) >> pshift) - pg0 + 1u : 0u;
+    for (uint32_t i = threadIdx.x; i < npg; i += kThreads) {
+      uint32_t pg = ld_relaxed(ptab + pg0 + i);
+      if (pg >= a.g->kv_pages) { bad_page = true; pg = 0; }
+      pgs[i] = pg;
+    }
+    __syncthreads();
+  }
   // element offset of row i of the chunk (row t0 + i of the sequence) from Kb / Vb
   auto row_off = [&](uint32_t i) -> size_t {
     if constexpr (PAGED) {
       const uint32_t r = t0 + i;
-      uint32_t pg = ld_relaxed(ptab + (r >> pshift));
-      if (pg >= a.g->kv_pages) { bad_page = true; pg = 0; }
-      return ((((size_t)pg * nkv + g) << pshift) + (r & ((1u << pshift) - 1u))) * d;
+      return ((((size_t)pgs[(r >> pshift) - pg0] * nkv + g) << pshift) + (r & ((1u << pshift) - 1u))) * d;
     } else {
       return (size_t)i * d;
     }
@@ -2629,8 +2676,13 @@ template <int D, int GRP, int NB>
 __device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, float* lds,
                                          int32_t wait_ev, uint32_t* s_flag) {
   if (t.kind == TK_ATTN_PARTIAL) {
-    if (t.flags & TF_KV_PAGED) {   // paged cache: one body for every chunk length
-      if (D != 0) return body_attn_partial<(D ? D : 128), (GRP ? GRP : 1), true>(t, a, lds, wait_ev, s_flag);
+    if (t.flags & TF_KV_PAGED) {   // paged cache: the same two bodies, rows reached through the page table
+      if (D != 0) {
+        constexpr uint32_t window = kAttnRounds * (kThreads / 64) * (64 / ((D ? D : 128) / 8));
+        if ((GRP ? GRP : 1) <= 4 && !(t.flags & TF_ATTN_BALANCE) && (a.g->max_seq + t.p1 - 1) / t.p1 <= window)
+          return body_attn_partial_regs<(D ? D : 128), (GRP ? GRP : 1), true>(t, a, lds, wait_ev, s_flag);
+        return body_attn_partial<(D ? D : 128), (GRP ? GRP : 1), true>(t, a, lds, wait_ev, s_flag);
+      }
       const uint32_t grp = a.g->n_q / a.g->n_kv;
       if (a.g->head_dim == 128) {
         if (grp == 8) return body_attn_partial<128, 8, true>(t, a, lds, wait_ev, s_flag);

@@ -234,12 +234,16 @@ def _server_logits(srv, s, dev):
     return t.clone().cpu().numpy().reshape(s.batch, s.vocab)
 
 
-@pytest.mark.parametrize("variant,ps,n_pages,n_iter", [
-    (dict(batch=3, n_layers=2), 8, 3 + 12, 7),
-    (dict(batch=8, n_layers=2, head_dim=128, n_q_heads=4, n_kv_heads=2), 16, 8 + 14, 25),
-    (dict(batch=4, ffn=0, n_experts=8, top_k=2, expert_ffn=64), 8, 4 + 10, 11),
+@pytest.mark.parametrize("variant,ps,n_pages,n_iter,extra", [
+    (dict(batch=3, n_layers=2), 8, 3 + 12, 7, {}),
+    (dict(batch=8, n_layers=2, head_dim=128, n_q_heads=4, n_kv_heads=2), 16, 8 + 14, 25, {}),
+    (dict(batch=4, ffn=0, n_experts=8, top_k=2, expert_ffn=64), 8, 4 + 10, 11, {}),
+    # every task starts after a pseudo-random delay, buffers that cross tasks are poisoned before
+    # each launch: a task that read metadata or activations too early would show
+    (dict(batch=3, n_layers=2), 8, 3 + 12, 5, dict(debug_flags=M.binding.DEBUG_POISON | M.binding.DEBUG_JITTER)),
+    (dict(batch=1, n_layers=2), 16, 1 + 3, 9, {}),
 ])
-def test_many_iterations_per_launch_serve_every_request_as_if_alone(variant, ps, n_pages, n_iter):
+def test_many_iterations_per_launch_serve_every_request_as_if_alone(variant, ps, n_pages, n_iter, extra):
     """The kernel keeps running through n_iter iterations per launch (no host round trip between
     tokens, none for retiring or admitting): every request ends with the tokens the whole-iteration
     oracle produces -- which are the tokens of the request decoded alone -- the final state equals
@@ -256,7 +260,7 @@ def test_many_iterations_per_launch_serve_every_request_as_if_alone(variant, ps,
         ora.iteration()
     eos = ora.state.requests[0].out[min(1, len(ora.state.requests[0].out) - 1)]
     ora = S.ServingOracle(s, G.PagedWeights(s, 4, table0, ps, n_pages), ps, n_pages, eos, "f32")
-    gpu = PagedGpu(s, 4, None, ps, n_pages, greedy_loop=1, serving=1, **FUSED)
+    gpu = PagedGpu(s, 4, None, ps, n_pages, greedy_loop=1, serving=1, **FUSED, **extra)
     stream = torch.cuda.current_stream().cuda_stream
     srv = gpu.graph.serve(64, 8, 8, eos)
     half = len(reqs) // 2
