@@ -1661,6 +1661,17 @@ __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
+// 16 bytes of a cache row of an earlier step.  Contiguous cache: a plain streaming load (the row's
+// lines were never read in this launch before they were written, see the attention body).  Paged
+// cache: a page that one request gave back may be handed to another within the same launch, so a
+// compute unit may still hold lines of the page's previous life -- every row is read with
+// agent-scope loads, which do not hit such lines.
+template <bool PAGED>
+__device__ __forceinline__ u32x4 ld_cache_row(const uint16_t* p) {
+  if constexpr (PAGED) return ld_row16_coherent(p);
+  else return ld_stream16(p);
+}
+
 // Position of sequence b in this step.  positions[] is the host's and stays as written for the
 // whole launch (tasks add the step number) -- except in a serving launch, where the serving task
 // rewrites it at the start of every step: then it holds the step's own positions and is read with
@@ -1745,8 +1756,8 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
       vreg[r] = u32x4{0, 0, 0, 0};
       if (i < n && t0 + i != (uint32_t)pos) {
         const size_t off = row_off(i);
-        kreg[r] = ld_stream16(Kb + off + sub * 8);
-        vreg[r] = ld_stream16(Vb + off + sub * 8);
+        kreg[r] = ld_cache_row<PAGED>(Kb + off + sub * 8);
+        vreg[r] = ld_cache_row<PAGED>(Vb + off + sub * 8);
       }
     }
   };
@@ -2154,8 +2165,8 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
       vreg[r] = u32x4{0, 0, 0, 0};
       if (i < n && t0 + i != (uint32_t)pos) {
         const size_t off = row_off(i);
-        kreg[r] = ld_stream16(Kb + off + sub * 8);
-        vreg[r] = ld_stream16(Vb + off + sub * 8);
+        kreg[r] = ld_cache_row<PAGED>(Kb + off + sub * 8);
+        vreg[r] = ld_cache_row<PAGED>(Vb + off + sub * 8);
       }
     }
   };
@@ -2279,8 +2290,8 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
         const uint32_t i = i_first + (r0 + kAttnPre + r) * stride;
         if (i < n && i != i_new) {
           const size_t off = row_off(i);
-          kreg[r] = ld_stream16(Kb + off + sub * 8);
-          vreg[r] = ld_stream16(Vb + off + sub * 8);
+          kreg[r] = ld_cache_row<PAGED>(Kb + off + sub * 8);
+          vreg[r] = ld_cache_row<PAGED>(Vb + off + sub * 8);
         }
       }
     }
