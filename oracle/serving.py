@@ -24,6 +24,10 @@ ServeState           the start-event task as a state machine over slots (one slo
                          kernel here.
                        * retire: slots in ascending order; a finished request gives its pages
                          back in page-table order (pushed onto the free stack).
+                       * compact: the requests still running move, in order, to the lowest slots
+                         (a slot is only metadata -- the rows stay in their pages), so the
+                         running requests always occupy slots 0 .. n-1 and a task graph compiled
+                         for fewer slots can serve them.
                        * admit: free slots in ascending order take requests in arrival order; a
                          request is admitted only if the pages it can ever need,
                          ceil((prompt_len + max_new - 1) / page_size), are free and not promised
@@ -152,6 +156,17 @@ class ServeState:
                     q.state = DONE
                     continue
             self.slot_pos[b], self.slot_next[b] = cached, nxt
+        # (1b) the running requests close ranks
+        running = [b for b in range(B) if self.slot_req[b] >= 0]
+        for dst, src in enumerate(running):
+            if dst == src:
+                continue
+            held = self.slot_held[src]
+            self.slot_req[dst], self.slot_pos[dst] = self.slot_req[src], self.slot_pos[src]
+            self.slot_next[dst], self.slot_held[dst] = self.slot_next[src], held
+            self.table[dst] = self.table[src][:held] + [-1] * (self.max_blocks - held)
+            self.slot_req[src], self.slot_held[src] = -1, 0
+            self.table[src] = [src] + [-1] * (self.max_blocks - 1)
         # (2) arrivals enter, in order, while their pages are there
         for b in range(B):
             if self.slot_req[b] >= 0:

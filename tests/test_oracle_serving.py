@@ -112,7 +112,8 @@ def test_start_event_task_reproduces_the_hand_worked_iterations(sc):
 @pytest.mark.parametrize("seed", range(6))
 def test_start_event_task_invariants_under_random_arrivals(seed):
     """Whatever arrives and whatever is sampled: no page has two owners, no page is lost, a pop
-    never finds the stack empty, requests start in arrival order, every request is fed its prompt
+    never finds the stack empty, requests start in arrival order, the running requests fill the
+    lowest slots in arrival order, every request is fed its prompt
     and then its own outputs at positions 0, 1, 2, ..., and ends on the end-of-sequence token or
     with max_new tokens."""
     rng = np.random.default_rng(seed)
@@ -129,8 +130,10 @@ def test_start_event_task_invariants_under_random_arrivals(seed):
                 plen = int(rng.integers(1, 12))
                 st.submit(rng.integers(4, 50, plen).tolist(), int(rng.integers(1, max_seq - plen + 2)))
                 n_req += 1
-        before = list(st.slot_req)
         tokens, positions = st.begin_iteration(sampled)
+        n_run = st.n_running()
+        assert all(r >= 0 for r in st.slot_req[:n_run]) and all(r < 0 for r in st.slot_req[n_run:])
+        assert st.slot_req[:n_run] == sorted(st.slot_req[:n_run])      # ranks closed, order kept
         owned = [pg for b in range(B) if st.slot_req[b] >= 0 for pg in st.table[b][:st.slot_held[b]]]
         assert len(set(owned)) == len(owned)
         assert sorted(owned + st.free) == list(range(B, n_pages))
@@ -140,7 +143,7 @@ def test_start_event_task_invariants_under_random_arrivals(seed):
             if r < 0:
                 assert (tokens[b], positions[b], st.table[b][0]) == (0, 0, b)
                 continue
-            if r != before[b]:
+            if r not in fed:
                 started.append(r)
             assert st.slot_held[b] == positions[b] // ps + 1
             assert all(pg >= B for pg in st.table[b][:st.slot_held[b]])
