@@ -424,6 +424,8 @@ mpk_status mpk_graph_set_page_table(mpk_graph *g, const int32_t *page_table);
  *     eos_token (kept as its last token).  Prompts go through the decode path, one token per
  *     iteration; the token sampled meanwhile is ignored.
  *   - retire: slots in ascending order; pages go back on the free stack in page-table order.
+ *   - close ranks: the requests still running move, in order, to the lowest slots (a slot is
+ *     metadata only; the rows stay in their pages), so running requests always fill slots 0..n-1.
  *   - admit: idle slots in ascending order take requests in arrival order; a request enters only
  *     when ceil((prompt_len + max_new_tokens - 1) / kv_page_size) pages are free and not promised
  *     to running requests; the first request that does not fit ends admission for the iteration.
@@ -442,6 +444,17 @@ typedef struct mpk_server mpk_server;
 /* Allocates and initialises the server's device state and attaches it to `g` (one server per
  * graph; destroy it before the graph).  Errors: INVALID_ARG, OOM, HIP. */
 mpk_status mpk_serve_create(mpk_graph *g, const mpk_serve_config *cfg, mpk_server **out);
+/* The same over a graph set compiled with serving = 1 (mpk_compile_set: a graph per power-of-two
+ * batch size, Section 6.1): one server state shared by all graphs, sized for the largest batch.
+ * Every mpk_serve_run then launches the graph of the smallest batch size that holds the requests
+ * that can be in flight, min(largest batch, submitted - finished), where "finished" is what the
+ * host has read back so far through mpk_serve_result or mpk_serve_state (a caller that never
+ * reads back always runs the largest graph once enough requests were submitted). */
+mpk_status mpk_serve_create_set(mpk_graph_set *set, const mpk_serve_config *cfg, mpk_server **out);
+/* Batch size of the graph the last mpk_serve_run launched (0 before the first). */
+uint32_t mpk_serve_last_batch(const mpk_server *s);
+/* mpk_graph_status over every graph of the server (after the caller synchronised the stream). */
+mpk_status mpk_serve_status(mpk_server *s);
 /* Queue a request: prompt = HOST int32 [prompt_len] (copied before the call returns), tokens in
  * [0, vocab).  The request becomes visible to the serving task of launches issued on `stream`
  * after this call.  request_id (host, may be NULL) = arrival number, from 0.  INVALID_ARG when

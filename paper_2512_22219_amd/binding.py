@@ -101,7 +101,8 @@ SYMBOLS = ("mpk_compile", "mpk_compile_dag", "mpk_decode_step", "mpk_decode_step
            "mpk_set_decode_step", "mpk_decode_step_static", "mpk_set_size", "mpk_set_batch_for", "mpk_set_graph",
            "mpk_set_destroy", "mpk_last_error", "mpk_graph_destroy", "mpk_static_scratch_need",
            "mpk_graph_set_page_table", "mpk_serve_create", "mpk_serve_submit", "mpk_serve_run",
-           "mpk_serve_result", "mpk_serve_state", "mpk_serve_logits", "mpk_serve_destroy")
+           "mpk_serve_result", "mpk_serve_state", "mpk_serve_logits", "mpk_serve_destroy",
+           "mpk_serve_create_set", "mpk_serve_last_batch", "mpk_serve_status")
 DEBUG_TRACE, DEBUG_POISON, DEBUG_JITTER, DEBUG_LOSE_NOTIFY = 1, 2, 4, 8
 
 _lib = None
@@ -155,6 +156,12 @@ def lib():
         L.mpk_serve_logits.restype = vp
         L.mpk_serve_destroy.argtypes = [vp]
         L.mpk_serve_destroy.restype = None
+        L.mpk_serve_create_set.argtypes = [vp, C.POINTER(ServeConfig), C.POINTER(vp)]
+        L.mpk_serve_create_set.restype = C.c_int
+        L.mpk_serve_last_batch.argtypes = [vp]
+        L.mpk_serve_last_batch.restype = C.c_uint32
+        L.mpk_serve_status.argtypes = [vp]
+        L.mpk_serve_status.restype = C.c_int
         for n in SYMBOLS[:14] + ("mpk_graph_set_page_table", "mpk_serve_create", "mpk_serve_submit",
                                  "mpk_serve_run", "mpk_serve_result", "mpk_serve_state"):
             getattr(L, n).restype = C.c_int
@@ -359,6 +366,12 @@ class Server:
     def logits_ptr(self) -> int:
         return int(lib().mpk_serve_logits(self._h) or 0)
 
+    def last_batch(self) -> int:
+        return int(lib().mpk_serve_last_batch(self._h))
+
+    def status(self):
+        _check(lib().mpk_serve_status(self._h))
+
     def destroy(self):
         if self._h:
             lib().mpk_serve_destroy(self._h)
@@ -394,10 +407,21 @@ class GraphSet:
         g.destroy = lambda: None
         return g
 
+    def serve(self, max_requests: int, max_prompt: int, max_new: int, eos_token: int = -1) -> "Server":
+        cfg = ServeConfig(C.sizeof(ServeConfig), max_requests, max_prompt, max_new, eos_token)
+        h = C.c_void_p()
+        _check(lib().mpk_serve_create_set(self._h, C.byref(cfg), C.byref(h)))
+        srv = Server(h, self)
+        self._server = weakref.ref(srv)
+        return srv
+
     def decode_step(self, n_active: int, token_ids_ptr: int, positions_ptr: int, logits_ptr: int, stream: int = 0):
         _check(lib().mpk_set_decode_step(self._h, n_active, token_ids_ptr, positions_ptr, logits_ptr, stream))
 
     def destroy(self):
+        srv = getattr(self, "_server", None)
+        if srv is not None and srv() is not None:
+            srv().destroy()
         if self._h:
             lib().mpk_set_destroy(self._h)
             self._h = None

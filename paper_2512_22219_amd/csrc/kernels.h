@@ -2584,6 +2584,7 @@ __device__ __forceinline__ void body_serve(const StepArgs& a) {
     pos = cached;
   }
   const uint32_t n_produced = (uint32_t)__builtin_popcountll(__ballot(produced));
+  const uint32_t n_done = (uint32_t)__builtin_popcountll(__ballot(done));
   for (uint64_t retiring = __ballot(done); retiring; retiring &= retiring - 1ull) {
     const uint32_t b = (uint32_t)__builtin_ctzll(retiring);
     const uint32_t hb = (uint32_t)__builtin_amdgcn_readlane((int)held, (int)b);
@@ -2602,6 +2603,39 @@ __device__ __forceinline__ void body_serve(const StepArgs& a) {
     req = -1;
     held = 0;
     pos = 0;
+  }
+  // ---- (1b) the running requests close ranks: in order, to the lowest slots (a slot is metadata
+  // only, the rows stay in their pages), so that the graph of a smaller batch size can serve them
+  {
+    const uint64_t run_mask = __ballot(mine && req >= 0);
+    const uint32_t n_run = (uint32_t)__builtin_popcountll(run_mask);
+    if (run_mask != (1ull << n_run) - 1ull) {   // (uniform) there are gaps
+      uint32_t my_src = lane, k = 0;
+      for (uint64_t m = run_mask; m; m &= m - 1ull, ++k) {
+        const uint32_t src = (uint32_t)__builtin_ctzll(m);
+        if (lane == k) my_src = src;
+        if (src == k) continue;
+        // page-table row src -> row k (k < src; rows below k are final, rows above src untouched so far)
+        const uint32_t hb = (uint32_t)__builtin_amdgcn_readlane((int)held, (int)src);
+        uint32_t* from = (uint32_t*)sv.table + (size_t)src * sv.max_blocks;
+        uint32_t* to = (uint32_t*)sv.table + (size_t)k * sv.max_blocks;
+        for (uint32_t i = lane; i < sv.max_blocks; i += 64u) {
+          const uint32_t v = i < hb ? ld_relaxed(from + i) : 0xFFFFFFFFu;
+          st_act_u32(to + i, v);
+          st_act_u32(from + i, i == 0u ? src : 0xFFFFFFFFu);   // vacated (a later move may fill it again)
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the next move may read what this one wrote
+      }
+      const int src_lane = (int)my_src;
+      const int32_t req_m = __shfl(req, src_lane, 64);
+      const uint32_t pos_m = (uint32_t)__shfl((int)pos, src_lane, 64), held_m = (uint32_t)__shfl((int)held, src_lane, 64);
+      const uint32_t nxt_m = (uint32_t)__shfl((int)nxt, src_lane, 64);
+      const bool keep = lane < n_run;
+      req = keep ? req_m : -1;
+      pos = keep ? pos_m : 0u;
+      held = keep ? held_m : 0u;
+      nxt = keep ? nxt_m : 0u;
+    }
   }
   // the pages pushed above may be popped below, by other lanes: the stores must have completed
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -2663,6 +2697,7 @@ __device__ __forceinline__ void body_serve(const StepArgs& a) {
     st_act_u32(sv.scalars + kServeQHead, q_head);
     st_act_u32(sv.scalars + kServeIterations, ld_relaxed(sv.scalars + kServeIterations) + 1u);
     st_act_u32(sv.scalars + kServeTokens, ld_relaxed(sv.scalars + kServeTokens) + n_produced);
+    st_act_u32(sv.scalars + kServeDone, ld_relaxed(sv.scalars + kServeDone) + n_done);
   }
 }
 

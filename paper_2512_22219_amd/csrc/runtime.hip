@@ -697,7 +697,6 @@ extern "C" mpk_status mpk_compile_set(const mpk_model_config* cfg, const mpk_wei
     o.struct_size = sizeof(o);
   }
   if (o.kv_batch != 0) { set_error("kv_batch is set by mpk_compile_set itself"); return MPK_ERR_INVALID_ARG; }
-  if (o.serving) { set_error("a serving graph is compiled for the maximum batch alone (idle slots cost next to nothing)"); return MPK_ERR_UNSUPPORTED; }
   if (!o.kv_page_size) o.kv_batch = cfg->batch;   // (a paged pool has no batch extent: every graph reads it through its table)
   mpk_graph_set* s = new (std::nothrow) mpk_graph_set();
   if (!s) { set_error("out of host memory"); return MPK_ERR_OOM; }
@@ -751,9 +750,12 @@ extern "C" mpk_status mpk_graph_set_page_table(mpk_graph* g, const int32_t* page
 }
 
 struct mpk_server {
-  mpk_graph* g = nullptr;
+  mpk_graph* g = nullptr;              // the graph of the largest batch size
+  std::vector<mpk_graph*> graphs;      // ascending batch size (one entry unless created over a graph set)
   mpk_serve_config cfg{};
   uint32_t batch = 0, max_blocks = 0, n_submitted = 0;
+  uint32_t known_done = 0;             // requests known to have finished (read back by mpk_serve_state / _result)
+  uint32_t last_batch = 0;             // batch size of the graph the last launch ran on
   // device state (ServeDev points into these)
   int32_t *d_slot = nullptr, *d_table = nullptr, *d_free = nullptr, *d_prompt = nullptr, *d_out = nullptr;
   int32_t *d_tokens = nullptr, *d_positions = nullptr;
@@ -771,13 +773,22 @@ static void server_free(mpk_server* s) {
   (void)hipFree(s->d_len); (void)hipFree(s->d_state); (void)hipFree(s->d_logits); (void)hipFree(s->d_rec);
 }
 
-extern "C" mpk_status mpk_serve_create(mpk_graph* g, const mpk_serve_config* cfg, mpk_server** out) {
+static mpk_status serve_create(const std::vector<mpk_graph*>& graphs, const mpk_serve_config* cfg, mpk_server** out) {
   if (out) *out = nullptr;
-  if (!g || !cfg || !out) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
+  if (graphs.empty() || !graphs.back() || !cfg || !out) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
   if (cfg->struct_size != sizeof(mpk_serve_config)) { set_error("mpk_serve_config.struct_size is %u, expected %zu", cfg->struct_size, sizeof(mpk_serve_config)); return MPK_ERR_INVALID_ARG; }
-  if (g->host_only || !g->h.opt.serving) { set_error("the graph was not compiled with serving = 1 (or is host_only)"); return MPK_ERR_INVALID_ARG; }
-  if (g->server) { set_error("the graph already has a server"); return MPK_ERR_INVALID_ARG; }
+  mpk_graph* g = graphs.back();
+  for (mpk_graph* x : graphs) {
+    if (x->host_only || !x->h.opt.serving) { set_error("the graph was not compiled with serving = 1 (or is host_only)"); return MPK_ERR_INVALID_ARG; }
+    if (x->server) { set_error("the graph already has a server"); return MPK_ERR_INVALID_ARG; }
+    if (x->h.opt.kv_page_size != g->h.opt.kv_page_size || x->h.opt.kv_pages != g->h.opt.kv_pages || x->device != g->device ||
+        x->h.cfg.max_seq != g->h.cfg.max_seq || x->h.cfg.vocab != g->h.cfg.vocab || x->h.cfg.batch > g->h.cfg.batch) {
+      set_error("the graphs of a served set must share the paged cache, max_seq and vocab");
+      return MPK_ERR_INVALID_ARG;
+    }
+  }
   const mpk_model_config& c = g->h.cfg;
+  if (g->h.opt.kv_pages <= c.batch) { set_error("kv_pages %u: the pool needs more pages than the %u batch slots", g->h.opt.kv_pages, c.batch); return MPK_ERR_INVALID_ARG; }
   const uint32_t ps = g->h.opt.kv_page_size, n_pages = g->h.opt.kv_pages, B = c.batch;
   if (!cfg->max_requests || !cfg->max_prompt || !cfg->max_new || cfg->max_prompt > c.max_seq || cfg->max_new > c.max_seq ||
       cfg->max_requests > (1u << 20)) {
@@ -789,7 +800,7 @@ extern "C" mpk_status mpk_serve_create(mpk_graph* g, const mpk_serve_config* cfg
   if (cur != g->device) { set_error("the graph lives on device %d, device %d is current", g->device, cur); return MPK_ERR_INVALID_ARG; }
   mpk_server* s = new (std::nothrow) mpk_server();
   if (!s) { set_error("out of host memory"); return MPK_ERR_OOM; }
-  s->g = g; s->cfg = *cfg; s->batch = B; s->max_blocks = c.max_seq / ps;
+  s->g = g; s->graphs = graphs; s->cfg = *cfg; s->batch = B; s->max_blocks = c.max_seq / ps;
   auto fail = [&](mpk_status st) { server_free(s); delete s; return st; };
   // initial state: every slot idle in its own page, every other page free (lowest number on top)
   std::vector<int32_t> slot(3 * (size_t)B, 0), table((size_t)B * s->max_blocks, -1), free_stack(n_pages, -1), zb(B, 0);
@@ -819,15 +830,41 @@ extern "C" mpk_status mpk_serve_create(mpk_graph* g, const mpk_serve_config* cfg
   if ((st = upload(&s->d_rec, rv)) != MPK_OK) return fail(st);
   const void* ptrs[2] = {s->d_table, s->d_rec};
   static_assert(offsetof(GraphConst, serve) == offsetof(GraphConst, page_table) + sizeof(void*), "page_table and serve are adjacent");
-  if (hipMemcpy((char*)g->d_const + offsetof(GraphConst, page_table), ptrs, sizeof(ptrs), hipMemcpyHostToDevice) != hipSuccess) {
-    set_error("hipMemcpy of the serving record failed");
-    return fail(MPK_ERR_HIP);
-  }
+  for (mpk_graph* x : graphs)
+    if (hipMemcpy((char*)x->d_const + offsetof(GraphConst, page_table), ptrs, sizeof(ptrs), hipMemcpyHostToDevice) != hipSuccess) {
+      set_error("hipMemcpy of the serving record failed");
+      return fail(MPK_ERR_HIP);
+    }
   s->lens.reserve(2 * (size_t)cfg->max_requests);
   s->tails.reserve(cfg->max_requests);
-  g->page_table = s->d_table;
-  g->server = s;
+  for (mpk_graph* x : graphs) {
+    x->page_table = s->d_table;
+    x->server = s;
+  }
   *out = s;
+  return MPK_OK;
+}
+
+extern "C" mpk_status mpk_serve_create(mpk_graph* g, const mpk_serve_config* cfg, mpk_server** out) {
+  if (out) *out = nullptr;
+  if (!g) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
+  return serve_create(std::vector<mpk_graph*>(1, g), cfg, out);
+}
+
+extern "C" mpk_status mpk_serve_create_set(mpk_graph_set* set, const mpk_serve_config* cfg, mpk_server** out) {
+  if (out) *out = nullptr;
+  if (!set || set->graphs.empty()) { set_error("NULL argument"); return MPK_ERR_INVALID_ARG; }
+  return serve_create(set->graphs, cfg, out);
+}
+
+extern "C" uint32_t mpk_serve_last_batch(const mpk_server* s) { return s ? s->last_batch : 0u; }
+
+extern "C" mpk_status mpk_serve_status(mpk_server* s) {
+  if (!s) { set_error("NULL server"); return MPK_ERR_INVALID_ARG; }
+  for (mpk_graph* x : s->graphs) {
+    const mpk_status st = mpk_graph_status(x);
+    if (st != MPK_OK) return st;
+  }
   return MPK_OK;
 }
 
@@ -863,7 +900,15 @@ extern "C" mpk_status mpk_serve_submit(mpk_server* s, const int32_t* prompt, uin
 extern "C" mpk_status mpk_serve_run(mpk_server* s, uint32_t n_iterations, void* stream) {
   if (!s) { set_error("NULL server"); return MPK_ERR_INVALID_ARG; }
   if (n_iterations == 0 || n_iterations > 65535u) { set_error("n_iterations %u out of range (1..65535)", n_iterations); return MPK_ERR_INVALID_ARG; }
+  // Section 6.1: the task graph specialised for the smallest batch size that holds the current
+  // batch.  The running requests always fill the lowest slots (the serving task closes ranks), and
+  // there are at most (submitted - finished) of them plus arrivals; "finished" is what the host has
+  // read back so far, so the bound errs on the large side.
+  const uint32_t open = std::max(1u, std::min(s->batch, s->n_submitted - std::min(s->known_done, s->n_submitted)));
   mpk_graph* g = s->g;
+  for (mpk_graph* x : s->graphs)
+    if (x->h.cfg.batch >= open) { g = x; break; }
+  s->last_batch = g->h.cfg.batch;
   const uint32_t keep = g->step_flags;
   g->step_flags |= kServeBit;
   const mpk_status st = launch_steps(g, n_iterations, s->d_tokens, s->d_positions, nullptr, s->d_logits, nullptr, stream);
@@ -879,6 +924,7 @@ extern "C" mpk_status mpk_serve_result(mpk_server* s, uint32_t request_id, int32
   HIP_TRY(hipMemcpy(st, s->d_state + 2 * (size_t)request_id, sizeof(st), hipMemcpyDeviceToHost));
   *state = st[0];
   *n_tokens = st[1];
+  HIP_TRY(hipMemcpy(&s->known_done, s->d_scalars + kServeDone, sizeof(uint32_t), hipMemcpyDeviceToHost));
   const size_t n = std::min<size_t>(st[1], cap);
   if (n && tokens) HIP_TRY(hipMemcpy(tokens, s->d_out + (size_t)request_id * s->cfg.max_new, n * sizeof(int32_t), hipMemcpyDeviceToHost));
   return MPK_OK;
@@ -894,6 +940,7 @@ extern "C" mpk_status mpk_serve_state(mpk_server* s, int32_t* buf, size_t cap, s
   HIP_TRY(hipMemcpy(sc, s->d_scalars, sizeof(sc), hipMemcpyDeviceToHost));
   buf[0] = (int32_t)B; buf[1] = (int32_t)mb; buf[2] = (int32_t)sc[kServeNFree]; buf[3] = (int32_t)sc[kServePromised];
   buf[4] = (int32_t)sc[kServeQHead]; buf[5] = (int32_t)sc[kServeQTail]; buf[6] = (int32_t)sc[kServeIterations]; buf[7] = (int32_t)sc[kServeTokens];
+  s->known_done = sc[kServeDone];
   int32_t* p = buf + 8;
   HIP_TRY(hipMemcpy(p, s->d_slot, 3 * (size_t)B * sizeof(int32_t), hipMemcpyDeviceToHost)); p += 3 * (size_t)B;
   HIP_TRY(hipMemcpy(p, s->d_tokens, B * sizeof(int32_t), hipMemcpyDeviceToHost)); p += B;
@@ -910,9 +957,11 @@ extern "C" void mpk_serve_destroy(mpk_server* s) {
   (void)hipSetDevice(s->g->device);
   (void)hipDeviceSynchronize();
   const void* none[2] = {nullptr, nullptr};
-  (void)hipMemcpy((char*)s->g->d_const + offsetof(GraphConst, page_table), none, sizeof(none), hipMemcpyHostToDevice);
-  s->g->page_table = nullptr;
-  s->g->server = nullptr;
+  for (mpk_graph* x : s->graphs) {
+    (void)hipMemcpy((char*)x->d_const + offsetof(GraphConst, page_table), none, sizeof(none), hipMemcpyHostToDevice);
+    x->page_table = nullptr;
+    x->server = nullptr;
+  }
   server_free(s);
   delete s;
 }

@@ -322,3 +322,45 @@ def test_serving_entry_points_refuse_what_they_cannot_run():
     assert [srv.result(r)[1] for r in range(4)] == [S.DONE] * 4
     srv.destroy()
     gpu.close()
+
+
+def test_a_served_graph_set_runs_the_smallest_graph_that_holds_the_open_requests():
+    """A graph per power-of-two batch size over ONE server state (Section 6.1: the graph that fits
+    the current batch is selected at run time; here by the host, per launch).  The running
+    requests always fill the lowest slots, so whichever graph runs sees all of them: the outputs of
+    every request and the final state equal the full-batch oracle's, and the batch size of the
+    graph launched follows the number of open requests."""
+    s = G.small_variant("C1", max_seq=48, batch=8, n_layers=2)
+    ps, n_pages = 8, 8 + 16
+    model = DeviceModel(s, 4)
+    dev = model.device
+    pool_k, pool_v = _nan_pool(s, n_pages, ps, dev), _nan_pool(s, n_pages, ps, dev)
+    gset = M.compile_set(s, model.weight_ptrs(), (pool_k.data_ptr(), pool_v.data_ptr()), greedy_loop=1, serving=1,
+                         kv_page_size=ps, kv_pages=n_pages, **FUSED)
+    assert len(gset) == 4
+    stream = torch.cuda.current_stream().cuda_stream
+    rng = np.random.default_rng(17)
+    reqs = _requests(rng, s.vocab, 12, 4, 6)
+    table0 = np.full((s.batch, s.max_seq // ps), -1)
+    ora = S.ServingOracle(s, G.PagedWeights(s, 4, table0, ps, n_pages), ps, n_pages, -1, "f32")
+    srv = gset.serve(32, 8, 8, -1)
+    # (requests submitted before the launch, iterations, batch size of the graph that must run)
+    plan = [(1, 3, 1), (1, 2, 2), (5, 4, 8), (0, 30, 2), (2, 3, 2), (0, 20, 2), (3, 2, 4), (0, 25, 2)]
+    nxt = 0
+    for n_new, n_iter, want_batch in plan:
+        for r in reqs[nxt:nxt + n_new]:
+            assert srv.submit(r[0], r[1], stream) == ora.submit(*r)
+        nxt += n_new
+        srv.run(n_iter, stream)
+        for _ in range(n_iter):
+            ora.iteration()
+        torch.cuda.synchronize()
+        srv.status()
+        assert srv.last_batch() == want_batch, (nxt, srv.last_batch(), want_batch)
+        _same_state(srv.state(), ora.state, nxt)          # (also tells the host how many have finished)
+    assert nxt == len(reqs)
+    for r in range(len(reqs)):
+        assert srv.result(r) == ora.outputs(r), r
+        assert srv.result(r)[1] == S.DONE
+    srv.destroy()
+    gset.destroy()
