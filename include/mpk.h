@@ -198,6 +198,10 @@ typedef struct mpk_compile_options {
                                updates the KV-cache metadata in device memory).  Needs
                                greedy_loop = 1, kv_page_size > 0, no scheduler workgroups.  Such
                                a graph is run through its server only: mpk_serve_run             */
+  uint32_t tiles_sampling;  /* tasks per sequence of the sampling operator (greedy_loop): each scans
+                               a share of the logits as soon as the LM-head tasks that produce it
+                               are done, the one to finish last picks the token.  0 = one per 8192
+                               logits (at most 32)                                              */
 } mpk_compile_options;
 
 typedef struct mpk_graph mpk_graph;

@@ -54,7 +54,8 @@ class OpSpec:
 
 
 def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: int = 1,
-              greedy_loop: bool = False, attn_balance: bool = False, serving: bool = False):
+              greedy_loop: bool = False, attn_balance: bool = False, serving: bool = False,
+              sampling_tiles: int = 1):
     """Operator list of one decode step for model shape `s` (synth.gen.ModelShape) under the
     given fusion flags, in execution order.
 
@@ -163,8 +164,12 @@ def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: 
     else:
         ops.append(OpSpec("final_norm", K_RMSNORM, -1, "xnf", B, H, H, [x]))
         ops.append(OpSpec("lm_head", K_LINEAR, -1, "logits", B, V, 1, ["xnf"], {"K": H}))
-    if greedy_loop:   # greedy sampling as an operator: next token of each sequence
-        ops.append(OpSpec("argmax", K_ARGMAX, -1, "ntok", B, 1, 1, ["logits"]))
+    if greedy_loop:
+        # greedy sampling as an operator, `sampling_tiles` tasks per sequence: task j finds the
+        # largest of its even share of the sequence's logits and leaves (value, index) in output
+        # columns 2j, 2j+1; which of them picks the token is a run-time matter
+        ops.append(OpSpec("argmax", K_ARGMAX, -1, "ntok", B, 2 * sampling_tiles, 2, ["logits"],
+                          {"T": sampling_tiles, "V": V}))
     return ops
 
 
@@ -282,7 +287,13 @@ def read_elements(op: OpSpec, tb: int, tc: int, tile: int, shapes: dict, explici
         m[b0:b1, c0:c1] = True
         m[b0:b1, F + c0:F + c1] = True
     elif k == K_ARGMAX:
-        mask(op.ins[0])[b0:b1, :] = True                # the largest of all logits of the sequence
+        T = op.meta.get("T", 1)
+        if T == 1:
+            mask(op.ins[0])[b0:b1, :] = True            # the largest of all logits of the sequence
+        else:
+            share = split_even(op.meta["V"], T)
+            for j in range(c0 // 2, c1 // 2):           # pair j: the largest of share j
+                mask(op.ins[0])[b0:b1, share[j]:share[j + 1]] = True
     elif k == K_ROUTER:
         mask(op.ins[0])[:, :] = True                    # top-k of every token, lists per expert
     elif k == K_EXPERT:

@@ -60,7 +60,8 @@ class CompileOptions(C.Structure):
                                                              ("no_attn_balance", C.c_uint32),
                                                              ("kv_page_size", C.c_uint32),
                                                              ("kv_pages", C.c_uint32),
-                                                             ("serving", C.c_uint32)]
+                                                             ("serving", C.c_uint32),
+                                                             ("tiles_sampling", C.c_uint32)]
 
 
 class ServeConfig(C.Structure):

@@ -660,9 +660,14 @@ static mpk_status build_ops(const mpk_model_config& c, const mpk_weight_ptrs* w,
   if (o.greedy_loop) {
     // greedy sampling inside the graph: the tokens of the next step (one task per sequence);
     // with it the kernel can go round again without the host (multi-token launch)
-    int ntok = b.new_tensor(B, 1);
-    HostOp& op = b.add(MPK_OP_ARGMAX, -1, "argmax", ntok, 1, logits);
+    // T tasks per sequence: task (b, j) scans logits [V j / T, V (j+1) / T) of row b and leaves
+    // (largest value, its index) in element (b, 2j .. 2j+1) of the output; the task of a row that
+    // arrives last (counter p2 + b) picks the token from the T pairs
+    const uint32_t T = o.tiles_sampling ? std::min(o.tiles_sampling, V) : std::max(1u, std::min(32u, V / 8192u));
+    int ntok = b.new_tensor(B, 2 * T);
+    HostOp& op = b.add(MPK_OP_ARGMAX, -1, "argmax", ntok, 2, logits);
     op.K = V;
+    op.p1 = T;
   }
   return MPK_OK;
 }
@@ -737,7 +742,7 @@ static void choose_partitions(const mpk_model_config& c, const mpk_compile_optio
         break;
       case MPK_OP_ARGMAX:
         op.tb = op.rows;
-        op.tc = 1;
+        op.tc = nu;
         break;
       case MPK_OP_ROUTER:   // one task: the per-expert token lists need every token's choice
       case MPK_OP_SERVE:    // one task: admission and the page stack are sequential decisions
@@ -844,9 +849,11 @@ static void input_rects(const mpk_model_config& c, const HostOp& op, uint32_t ti
     case MPK_OP_ROUTER:   // every token's router output
       out.push_back({op.in_tensor, 0, UINT32_MAX, 0, UINT32_MAX});
       break;
-    case MPK_OP_ARGMAX:   // all logits of its sequences
-      out.push_back({op.in_tensor, b0, b1, 0, UINT32_MAX});
+    case MPK_OP_ARGMAX: {   // its share of the logits of its sequences
+      const uint32_t T = op.p1, j0 = c0 / 2, j1 = c1 / 2;
+      out.push_back({op.in_tensor, b0, b1, tile_begin(op.K, T, j0), tile_begin(op.K, T, j1)});
       break;
+    }
     case MPK_OP_EXPERT:   // the meta-tensor + whatever routing sends here: statically everything
       out.push_back({op.in_tensor, 0, UINT32_MAX, 0, UINT32_MAX});
       out.push_back({op.in2_tensor, 0, UINT32_MAX, 0, UINT32_MAX});
@@ -980,6 +987,7 @@ static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGr
       t.in2 = act_ref(g, op.in2_tensor);             // residual [B][H]
       t.aux0 = (void*)act_ref(g, op.side_out_tensor);   // the real output [B][H]; relocated by the runtime
     }
+    if (op.kind == MPK_OP_ARGMAX) t.p2 = g.n_group_counters_attn + g.n_splitk_counters;   // first sampling counter (+ sequence)
     if (op.kind == MPK_OP_ROUTER || op.kind == MPK_OP_EXPERT || op.kind == MPK_OP_COMBINE) {
       t.in = act_ref(g, op.data_in);
       t.in2 = act_ref(g, op.data_in2);
@@ -1283,7 +1291,7 @@ static mpk_status build_model_graph_pass(const mpk_model_config& cfg, const mpk_
   if (sp.page_ready) apply_page_sizes(*sp.page_ready, g);
   if (sp.tile_workers) apply_worker_weights(opt, *sp.tile_workers, g);
   g.n_group_counters_attn = cfg.n_layers * cfg.batch * cfg.n_kv_heads;
-  g.n_group_counters = g.n_group_counters_attn + g.n_splitk_counters;
+  g.n_group_counters = g.n_group_counters_attn + g.n_splitk_counters + (opt.greedy_loop ? cfg.batch : 0u);   // + one per sequence for the sampling tasks
   g.inv_freq.resize(cfg.head_dim / 2);
   for (uint32_t i = 0; i < cfg.head_dim / 2; ++i)
     g.inv_freq[i] = std::pow((double)cfg.rope_theta, -2.0 * (double)i / (double)cfg.head_dim);

@@ -2484,15 +2484,19 @@ __device__ __forceinline__ void body_swiglu(const TaskDesc& t) {
     }
 }
 
-// Runs one task.  wait_ev >= 0: the task must first wait for that event (persistent kernel);
-// linear and attention tasks do so after requesting their first weight / cache block.
-// Greedy sampling (one task per sequence): the index of the largest logit, lowest index on ties;
-// the token goes to token_ids[b] for the next step's embedding task (and to tokens_out); the
-// last step of a launch also advances positions[b].  Optionally keeps a copy of the logits.
+// Greedy sampling: the index of the largest logit of a sequence, lowest index on ties.  T tasks
+// per sequence (t.p1): task j scans logits [V j / T, V (j+1) / T) -- it depends only on the LM-head
+// tasks that produce them -- and leaves (largest value, its index) in its pair of the output row;
+// the task of a sequence that arrives last (arrival counter t.p2 + sequence, T arrivals per step)
+// picks the token from the T pairs.  The token goes to token_ids[b] for the next step's embedding
+// task (and to tokens_out); the last step of a launch also advances positions[b].  Optionally
+// keeps a copy of the logits.
 __device__ __forceinline__ void body_argmax(const TaskDesc& t, const StepArgs& a, float* lds) {
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const uint32_t V = t.K, B = a.g->batch;
+  const uint32_t V = t.K, B = a.g->batch, T = t.p1, j = t.c0 / 2u;
+  const uint32_t q = V / T, r = V % T;
+  const uint32_t v0 = j * q + min(j, r), v1 = (j + 1u) * q + min(j + 1u, r);   // the even split of V into T shares
   float* vmax = lds;                          // [8]
   uint32_t* imax = (uint32_t*)(lds + 8);      // [8]
   for (uint32_t b = t.b0; b < t.b1; ++b) {
@@ -2502,10 +2506,25 @@ __device__ __forceinline__ void body_argmax(const TaskDesc& t, const StepArgs& a
     float* copy = logits_all ? logits_all + ((size_t)a.step * B + b) * V : nullptr;
     float best = -INFINITY;
     uint32_t best_i = 0xFFFFFFFFu;
-    for (uint32_t i = threadIdx.x; i < V; i += kThreads) {   // ascending per thread: keeps the first maximum
-      const float v = ld_act(row + i);
-      if (copy) as_global(copy)[i] = v;
-      if (v > best || best_i == 0xFFFFFFFFu) { best = v; best_i = i; }
+    // One workgroup reads its share with coherent loads: what counts is how many of them are in
+    // flight (one at a time, the row of a 152k vocabulary took about 150 us -- 5 % of a batch-1
+    // step of the 8B shape).  32 per thread are requested before the first is looked at.
+    constexpr int kInFlight = 32;
+    for (uint32_t i0 = v0 + threadIdx.x; i0 < v1; i0 += kThreads * kInFlight) {   // ascending per thread: keeps the first maximum
+      float v[kInFlight];
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {
+        const uint32_t i = i0 + (uint32_t)u * kThreads;
+        v[u] = i < v1 ? ld_act(row + i) : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {
+        const uint32_t i = i0 + (uint32_t)u * kThreads;
+        if (i < v1) {
+          if (copy) as_global(copy)[i] = v[u];
+          if (v[u] > best || best_i == 0xFFFFFFFFu) { best = v[u]; best_i = i; }
+        }
+      }
     }
     const float wbest = wave_max(best);
     const uint32_t wi = wave_min_u32(best == wbest ? best_i : 0xFFFFFFFFu);
@@ -2516,11 +2535,36 @@ __device__ __forceinline__ void body_argmax(const TaskDesc& t, const StepArgs& a
       uint32_t mi = imax[0];
       for (uint32_t w = 1; w < kThreads / 64; ++w)
         if (vmax[w] > m || (vmax[w] == m && imax[w] < mi)) { m = vmax[w]; mi = imax[w]; }
-      if (mi >= V) mi = 0;   // logits that are not numbers: keep the token in range
-      st_act_u32((uint32_t*)const_cast<int32_t*>(a.token_ids) + b, mi);
-      if (tokens_out) st_act_u32((uint32_t*)tokens_out + (size_t)a.step * B + b, mi);
-      if ((uint32_t)a.step + 1u == a.n_steps && !(a.flags & kServeBit))   // (a serving launch: the serving task keeps the positions)
-        st_act_u32((uint32_t*)const_cast<int32_t*>(a.positions) + b, (uint32_t)(a.positions[b] + (int32_t)a.n_steps));
+      bool pick = true;
+      if (T > 1u) {
+        float* pairs = t.out + (size_t)b * t.ld_out;
+        st_act(pairs + 2u * j, m);
+        st_act_u32((uint32_t*)pairs + 2u * j + 1u, mi);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the pair is in place before the arrival counts
+        uint32_t* cnt = a.g->grp_counters + t.p2 + b;
+        const uint32_t old = __hip_atomic_fetch_add(as_global(cnt), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        pick = (old + 1u) % T == 0u;   // every step adds exactly T
+        if (pick) {
+          float pm[32];
+          uint32_t pi[32];
+#pragma unroll
+          for (uint32_t k = 0; k < 32u; ++k) {
+            if (k < T) { pm[k] = ld_act(pairs + 2u * k); pi[k] = ld_relaxed((const uint32_t*)pairs + 2u * k + 1u); }
+          }
+          m = pm[0];
+          mi = pi[0];
+#pragma unroll
+          for (uint32_t k = 1; k < 32u; ++k)
+            if (k < T && pm[k] > m) { m = pm[k]; mi = pi[k]; }   // shares ascend with k: the first maximum stays
+        }
+      }
+      if (pick) {
+        if (mi >= V) mi = 0;   // logits that are not numbers: keep the token in range
+        st_act_u32((uint32_t*)const_cast<int32_t*>(a.token_ids) + b, mi);
+        if (tokens_out) st_act_u32((uint32_t*)tokens_out + (size_t)a.step * B + b, mi);
+        if ((uint32_t)a.step + 1u == a.n_steps && !(a.flags & kServeBit))   // (a serving launch: the serving task keeps the positions)
+          st_act_u32((uint32_t*)const_cast<int32_t*>(a.positions) + b, (uint32_t)(a.positions[b] + (int32_t)a.n_steps));
+      }
     }
     lds_barrier();
   }
@@ -2718,6 +2762,8 @@ __device__ __forceinline__ uint32_t run_linear(const TaskDesc& t, const StepArgs
   return linear_task_mfma<MEGA, Svc>(t, a, lds, wait_ev, s_flag, svc);
 }
 
+// Runs one task that is not a linear task.  wait_ev >= 0: the task must first wait for that event
+// (persistent kernel); attention tasks do so after requesting their first cache rows.
 template <int D, int GRP, int NB>
 __device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, float* lds,
                                          int32_t wait_ev, uint32_t* s_flag) {

@@ -82,8 +82,9 @@ def oracle_ops_and_degrees(shape, ex, fusion, attn_chunks, attn_balance=True):
     with no_attn_balance=1."""
     greedy = any(eo["kind"] == TG.K_ARGMAX for eo in ex.ops)
     serving = any(eo["kind"] == TG.K_SERVE for eo in ex.ops)
+    sampling_tiles = max([int(eo["cols"]) // 2 for eo in ex.ops if eo["kind"] == TG.K_ARGMAX] or [1])
     ops = TG.build_ops(shape, fusion, attn_chunks, moe_tasks_of(ex), down_parts_of(ex, shape), greedy,
-                       attn_balance, serving)
+                       attn_balance, serving, sampling_tiles)
     assert len(ops) == len(ex.ops), (len(ops), len(ex.ops))
     for o, eo in zip(ops, ex.ops):
         assert o.kind == eo["kind"] and o.layer == eo["layer"], (o.name, o.kind, eo["kind"])

@@ -53,6 +53,7 @@ CASES = [
     # greedy sampling as an operator of the graph (multi-token launch)
     ("C1", dict(batch=3), dict(fusion=31, n_workers=24, greedy_loop=1)),
     ("C1", {}, dict(fusion=0, greedy_loop=1)),
+    ("C1", dict(batch=2), dict(fusion=31, greedy_loop=1, tiles_sampling=5, tiles_lm_head=7)),   # sampling tasks that share a row
     # serving graphs (Section 6.1): the serving task first, every embedding task behind it
     ("C1", dict(batch=3), dict(fusion=31, greedy_loop=1, kv_page_size=16, kv_pages=40, serving=1)),
     ("C1", dict(batch=8), dict(fusion=31, greedy_loop=1, kv_page_size=32, kv_pages=64, serving=1, n_workers=40)),

@@ -459,6 +459,10 @@ def test_moe_routing_ties_take_the_lower_expert_index(batch):
     (dict(batch=8, n_layers=2), dict(fusion=31, transitive_reduction=1), 6),
     (dict(batch=2), dict(fusion=31, transitive_reduction=1, launch_mode=1), 5),
     (dict(batch=4, ffn=0, n_experts=16, top_k=4, expert_ffn=96), dict(fusion=31, transitive_reduction=1), 6),
+    # several sampling tasks per sequence: each scans a share of the logits, the last to arrive picks
+    (dict(batch=3, n_layers=2), dict(fusion=31, transitive_reduction=1, tiles_sampling=5), 8),
+    (dict(batch=2), dict(fusion=31, transitive_reduction=1, launch_mode=1, tiles_sampling=32), 5),
+    (dict(), dict(fusion=0, tiles_sampling=3, debug_flags=6), 6),
 ])
 def test_greedy_loop_decodes_several_tokens_in_one_launch(variant, opts, n_steps):
     """Graph with the sampling operator: n_steps tokens from ONE launch of the persistent kernel

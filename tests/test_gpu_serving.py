@@ -242,6 +242,7 @@ def _server_logits(srv, s, dev):
     # each launch: a task that read metadata or activations too early would show
     (dict(batch=3, n_layers=2), 8, 3 + 12, 5, dict(debug_flags=M.binding.DEBUG_POISON | M.binding.DEBUG_JITTER)),
     (dict(batch=1, n_layers=2), 16, 1 + 3, 9, {}),
+    (dict(batch=3, n_layers=2), 8, 3 + 12, 6, dict(tiles_sampling=4)),
 ])
 def test_many_iterations_per_launch_serve_every_request_as_if_alone(variant, ps, n_pages, n_iter, extra):
     """The kernel keeps running through n_iter iterations per launch (no host round trip between

@@ -256,6 +256,21 @@ def test_argmax_read_set_hand_written():
     assert ps[2] == [[(1, 0), (1, 1), (1, 2)], [(1, 3), (1, 4), (1, 5)]]
 
 
+def test_sampling_tasks_that_share_a_row_read_their_share_only():
+    """The sampling operator cut into T tasks per sequence: task j reads the j-th even share of the
+    sequence's logits, so it depends on the LM-head tiles that overlap that share and no others.
+    Written out by hand for 2 sequences x 10 logits, T = 2 (shares [0, 5) and [5, 10)), LM head in
+    3 column tiles [0, 4), [4, 7), [7, 10)."""
+    lm = TG.OpSpec("lm_head", TG.K_LINEAR, -1, "logits", 2, 10, 1, ["x"], {"K": 4})
+    am = TG.OpSpec("argmax", TG.K_ARGMAX, -1, "ntok", 2, 4, 2, ["logits"], {"T": 2, "V": 10})
+    src = TG.OpSpec("src", TG.K_EMBED, -1, "x", 2, 4, 4, [])
+    shapes = {"logits": (2, 10), "x": (2, 4)}
+    r = TG.read_elements(am, 2, 2, 3, shapes)        # sequence 1, share 1
+    assert r["logits"].tolist() == [[False] * 10, [False] * 5 + [True] * 5]
+    ps = TG.producer_sets([src, lm, am], [(2, 1), (1, 3), (2, 2)])
+    assert ps[2] == [[(1, 0), (1, 1)], [(1, 1), (1, 2)], [(1, 0), (1, 1)], [(1, 1), (1, 2)]]
+
+
 def test_serving_task_read_sets_hand_written():
     """Serving inside the graph (Section 6.1): ONE task on the start event prepares the iteration
     and writes a metadata element per batch slot; the embedding task of slot b reads element b.
