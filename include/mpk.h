@@ -148,7 +148,7 @@ typedef struct mpk_compile_options {
                                (Section 6.4: expert tasks are fixed at compile time and split
                                the active experts' rows evenly at run time); 0 = n_workers      */
   uint32_t greedy_loop;     /* 1 = append a greedy-sampling operator (arg max of the logits,
-                               lowest index on ties, one task per sequence) so that several
+                               lowest index on ties; tiles_sampling tasks per sequence) so that several
                                tokens can be decoded in ONE launch (mpk_decode_steps): the
                                kernel runs until its workload is done (Section 5).  Such a
                                graph is run with mpk_decode_steps only                          */
