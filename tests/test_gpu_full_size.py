@@ -191,3 +191,57 @@ def test_c2_full_size_32_tokens_from_one_launch():
             assert abs(lg[0, j] - v) <= TOL * max(abs(v), 1e-3 * abs(gold["top8"][steps - 1][0][0][1]))
         assert pos.cpu().numpy().tolist() == [p + steps for p in gold["start_positions"]]
     gpu.close()
+
+
+@pytest.mark.parametrize("name,page_size,n_steps", [("C2", 64, 12), ("C3", 64, 10), ("C4", 32, 6)])
+def test_full_size_serving_reproduces_the_plain_greedy_decode(name, page_size, n_steps):
+    """At the benchmark's sizes the oracle cannot follow a serving run step by step; what holds at
+    any size: serving changes where rows live and who feeds the tokens, not one arithmetic
+    operation.  One request per slot with a one-token prompt, all admitted in the first
+    iteration, must reproduce -- bit for bit, tokens and final logits -- the greedy decode of the
+    same tokens from position 0 on the contiguous cache (whose parity with the oracle the tests
+    above establish), through another attention instance, page tables and the serving task."""
+    import paper_2512_22219_amd as M
+    from synth.device import DeviceModel
+    s = G.CONFIGS[name]
+    need = s.n_layers * sum(r * c * 2 for _, r, c, _ in G.layer_tensor_shapes(s)) * 1.2
+    if torch.cuda.mem_get_info()[0] < need:
+        pytest.skip("not enough free device memory for this configuration")
+    model = DeviceModel(s, 0)
+    dev = model.device
+    stream = torch.cuda.current_stream().cuda_stream
+    tok0 = G.tokens(0, s).astype(np.int32)
+    # the plain path: greedy_loop graph on the contiguous cache, positions 0
+    plain = M.compile_graph(s, model.weight_ptrs(), model.kv_ptrs(), greedy_loop=1, **BENCH_OPTS)
+    tok = torch.as_tensor(tok0, device=dev)
+    pos = torch.zeros(s.batch, dtype=torch.int32, device=dev)
+    toks = torch.full((n_steps, s.batch), -1, dtype=torch.int32, device=dev)
+    logits = torch.empty((s.batch, s.vocab), dtype=torch.float32, device=dev)
+    plain.decode_steps(n_steps, tok.data_ptr(), pos.data_ptr(), toks.data_ptr(), logits.data_ptr(), 0, stream)
+    torch.cuda.synchronize()
+    plain.status()
+    want_tokens, want_logits = toks.cpu().numpy(), logits.cpu().numpy()
+    plain.destroy()
+    # served: pages of the pool handed out by the serving task
+    n_pages = s.batch + s.batch * (256 // page_size)
+    pools = [torch.full((s.n_layers, n_pages, s.n_kv_heads, page_size, s.head_dim), G.BF16_NAN_BITS,
+                        dtype=torch.int16, device=dev).view(torch.bfloat16) for _ in range(2)]
+    graph = M.compile_graph(s, model.weight_ptrs(), (pools[0].data_ptr(), pools[1].data_ptr()), greedy_loop=1, serving=1,
+                            kv_page_size=page_size, kv_pages=n_pages, **BENCH_OPTS)
+    srv = graph.serve(s.batch, 4, n_steps + 1, -1)
+    for b in range(s.batch):
+        assert srv.submit([int(tok0[b])], n_steps + 1, stream) == b
+    srv.run(n_steps, stream)
+    torch.cuda.synchronize()
+    graph.status()
+    st = srv.state()
+    assert st["slot_req"] == list(range(s.batch)) and st["positions"] == [n_steps - 1] * s.batch
+    # iteration i samples token i; the serving task of iteration i + 1 records it: n_steps - 1 so far
+    for b in range(s.batch):
+        got, state = srv.result(b)
+        assert state == 1 and got == want_tokens[:n_steps - 1, b].tolist(), b
+    assert st["tokens"] == want_tokens[n_steps - 1].tolist()
+    from tests.test_gpu_serving import _server_logits
+    assert np.array_equal(_server_logits(srv, s, dev), want_logits)
+    srv.destroy()
+    graph.destroy()
