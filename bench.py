@@ -5,6 +5,9 @@ shaped mixture of experts, batch 16; --config C5: 70B-shaped).
 
 A "step" is one decode step through the persistent mega-kernel (mpk_decode_step) followed by the
 greedy token feedback (arg max on the device, no host sync).  Prints ONE JSON line.
+The default run also attaches `batch8` (the batch-8 shape timed the same way) and `serving` (the
+batch-1 workload served from inside the kernel: paged KV cache, serving task, 32 iterations per
+launch).
 Also measured and attached: the same task bodies launched one kernel per operator (eager and as
 a replayed HIP graph), and the CPU oracle timed on a bounded sample of the same workload.
 """
@@ -88,6 +91,8 @@ def main():
                          "page size, serving task on the start event, --steps iterations in one launch) and "
                          "attach it as the 'serving' sub-record; prompts are fed through the decode path "
                          "first, off the clock, until every slot stands at the workload's KV length")
+    ap.add_argument("--no-serving", action="store_true",
+                    help="default run (C2) only: skip the serving sub-record")
     ap.add_argument("--no-batch8", action="store_true",
                     help="default run (C2, batch 1) only: skip the batch-8 half of the metric (C3)")
     args = ap.parse_args()
@@ -95,13 +100,28 @@ def main():
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
-    out = measure(args, args.config, baselines=not args.no_baselines, cpu=not args.no_cpu)
-    if args.serving:
-        out["serving"] = measure_serving(args, args.config, args.serving)
+    b8 = None
     if args.config == "C2" and not args.no_batch8 and args.tokens_per_launch == 1:
         # the metric is ms/token at batch 1 AND 8: the batch-8 shape (C3) timed the same way, as a
-        # sub-record of the same line
-        b8 = measure(args, "C3", baselines=not args.no_baselines, cpu=False)
+        # sub-record of the same line.  In a process of its own, started before this one touches
+        # the GPU: measured after the batch-1 workload in one process the batch-8 step came out
+        # 3 to 4 % slower (5.53-5.57 against 5.37 ms, three runs each) -- where the allocator
+        # places 20 GB after 16 GB were freed is not part of either workload.
+        import subprocess
+        cmd = [sys.executable, os.path.abspath(__file__), "--config", "C3", "--no-cpu", "--steps", str(args.steps),
+               "--warmup", str(args.warmup), "--fusion", str(args.fusion)] + (["--no-baselines"] if args.no_baselines else [])
+        for o in args.opt:
+            cmd += ["--opt", o]
+        child = subprocess.run(cmd, capture_output=True, text=True)
+        if child.returncode != 0:
+            sys.stderr.write(child.stderr)
+            sys.exit(child.returncode)
+        b8 = json.loads(child.stdout.strip().splitlines()[-1])
+    out = measure(args, args.config, baselines=not args.no_baselines, cpu=not args.no_cpu)
+    if args.serving or (args.config == "C2" and not args.no_serving and args.tokens_per_launch == 1):
+        # (the default run: the batch-1 workload also served from inside the kernel, pages of 64 rows)
+        out["serving"] = measure_serving(args, args.config, args.serving or 64)
+    if b8 is not None:
         out["batch8"] = {k: b8[k] for k in ("metric", "value", "unit", "ms_per_step", "tokens_per_s", "steps", "warmup",
                                             "achieved_hbm_GBps", "bytes_per_step", "roofline", "config", "final_tokens")
                          if k in b8}
