@@ -365,3 +365,40 @@ def test_a_served_graph_set_runs_the_smallest_graph_that_holds_the_open_requests
         assert srv.result(r)[1] == S.DONE
     srv.destroy()
     gset.destroy()
+
+
+def test_a_graph_set_over_a_paged_cache_needs_no_batch_extent():
+    """mpk_compile_set over a paged pool (no serving): every graph reads the same pool through
+    the table it was given, so the graph for 2 sequences runs the first two rows of a table laid
+    out for 4."""
+    s = G.small_variant("C1", max_seq=64, batch=4)
+    ps, n_pages = 16, 4 * 4 + 3
+    pos = np.array([20, 33, 5, 47])
+    table = G.page_table(9, s, ps, n_pages, pos + 1)
+    model = DeviceModel(s, 4)
+    dev = model.device
+    pool_k, pool_v = _nan_pool(s, n_pages, ps, dev), _nan_pool(s, n_pages, ps, dev)
+    for b in range(s.batch):
+        for i, pg in enumerate(table[b]):
+            if pg >= 0:
+                pool_k[:, pg] = model.k[:, b, :, i * ps:(i + 1) * ps, :]
+                pool_v[:, pg] = model.v[:, b, :, i * ps:(i + 1) * ps, :]
+    gset = M.compile_set(s, model.weight_ptrs(), (pool_k.data_ptr(), pool_v.data_ptr()), kv_page_size=ps, kv_pages=n_pages, **FUSED)
+    d_table = torch.as_tensor(table, dtype=torch.int32, device=dev).contiguous()
+    for i in range(len(gset)):
+        gset.graph(i).set_page_table(d_table.data_ptr())
+    ref = S.PagedDecoderOracle(s, G.PagedWeights(s, 4, table, ps, n_pages), ps, "f32")
+    ref.page_table = table
+    tok = np.array([7, 8, 9, 10])
+    d_tok = torch.as_tensor(tok.astype(np.int32), device=dev)
+    d_pos = torch.as_tensor(pos.astype(np.int32), device=dev)
+    logits = torch.full((s.batch, s.vocab), float("nan"), dtype=torch.float32, device=dev)
+    gset.decode_step(2, d_tok.data_ptr(), d_pos.data_ptr(), logits.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    gset.graph(1).status()
+    got = logits.cpu().numpy()
+    k_rows, v_rows = _rows(pool_k, table, pos, ps), _rows(pool_v, table, pos, ps)
+    want = ref.step(tok, pos)     # (all four on the oracle; the first two are compared)
+    assert rel_err(got[:2], want[:2]) < TOL
+    assert np.isnan(got[2:]).all()
+    gset.destroy()
