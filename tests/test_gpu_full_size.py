@@ -193,14 +193,19 @@ def test_c2_full_size_32_tokens_from_one_launch():
     gpu.close()
 
 
-@pytest.mark.parametrize("name,page_size,n_steps", [("C2", 64, 12), ("C3", 64, 10), ("C4", 32, 6)])
-def test_full_size_serving_reproduces_the_plain_greedy_decode(name, page_size, n_steps):
+@pytest.mark.parametrize("name,page_size,n_steps,debug", [("C2", 64, 12, 0), ("C3", 64, 10, 0), ("C4", 32, 6, 0),
+                                                          ("C3", 16, 6, 4), ("C2", 8, 6, 4)])
+def test_full_size_serving_reproduces_the_plain_greedy_decode(name, page_size, n_steps, debug):
     """At the benchmark's sizes the oracle cannot follow a serving run step by step; what holds at
     any size: serving changes where rows live and who feeds the tokens, not one arithmetic
     operation.  One request per slot with a one-token prompt, all admitted in the first
     iteration, must reproduce -- bit for bit, tokens and final logits -- the greedy decode of the
     same tokens from position 0 on the contiguous cache (whose parity with the oracle the tests
-    above establish), through another attention instance, page tables and the serving task."""
+    above establish), through another attention instance, page tables and the serving task.
+    debug = 4 (MPK_DEBUG_JITTER on the served graph): every task starts after a pseudo-random
+    delay, so producers and consumers meet in another order in every iteration; results must not
+    move by a bit (every order-dependent decision -- who merges, who picks the token -- only
+    chooses WHO adds up, never in which order)."""
     import paper_2512_22219_amd as M
     from synth.device import DeviceModel
     s = G.CONFIGS[name]
@@ -227,7 +232,7 @@ def test_full_size_serving_reproduces_the_plain_greedy_decode(name, page_size, n
     pools = [torch.full((s.n_layers, n_pages, s.n_kv_heads, page_size, s.head_dim), G.BF16_NAN_BITS,
                         dtype=torch.int16, device=dev).view(torch.bfloat16) for _ in range(2)]
     graph = M.compile_graph(s, model.weight_ptrs(), (pools[0].data_ptr(), pools[1].data_ptr()), greedy_loop=1, serving=1,
-                            kv_page_size=page_size, kv_pages=n_pages, **BENCH_OPTS)
+                            kv_page_size=page_size, kv_pages=n_pages, debug_flags=debug, **BENCH_OPTS)
     srv = graph.serve(s.batch, 4, n_steps + 1, -1)
     for b in range(s.batch):
         assert srv.submit([int(tok0[b])], n_steps + 1, stream) == b
