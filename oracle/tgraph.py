@@ -176,7 +176,7 @@ def build_ops(s, fusion: int, attn_chunks: int, moe_tasks: int = 0, down_parts: 
 def col_bounds(op: OpSpec, tc: int, explicit=None):
     """Column boundaries (tc + 1 of them) of an operator's tiles.  One even split -- except for
     the QKV projection (params["head"]), whose tiles never straddle a head: the columns are cut
-    into heads first and every head evenly into the same number of tiles (DESIGN: decomposition).
+    into heads first and every head evenly into the same number of tiles.
     `explicit`: boundaries handed in (a partition is the compiler's choice, Section 4.1; the
     dependency rule is what is checked): they must cut [0, cols) into tc non-empty tiles at
     multiples of the operator's unit."""
