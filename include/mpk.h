@@ -465,10 +465,13 @@ mpk_status mpk_serve_status(mpk_server *s);
  * the request could never be admitted (rows above max_seq, more pages than the pool can free). */
 mpk_status mpk_serve_submit(mpk_server *s, const int32_t *prompt, uint32_t prompt_len,
                             uint32_t max_new_tokens, void *stream, uint32_t *request_id);
-/* Run n_iterations decoding iterations (1 .. 65535) in ONE launch of the persistent kernel
+/* Run up to n_iterations decoding iterations (1 .. 65535) in ONE launch of the persistent kernel
  * (per-operator launches with MPK_LAUNCH_PER_OP): every iteration is the serving task, one decode
- * step of all slots, greedy sampling.  Asynchronous on `stream`; launches of one server must not
- * overlap.  Errors as mpk_decode_steps; device errors through mpk_graph_status. */
+ * step of all slots, greedy sampling.  The kernel runs until its workload is done (Section 5): the
+ * iteration whose serving task finds nothing running and nothing queued is the launch's last
+ * (mpk_serve_state tells how many iterations have run; with MPK_LAUNCH_PER_OP the host has issued
+ * all of them beforehand, so all of them run).  Asynchronous on `stream`; launches of one server
+ * must not overlap.  Errors as mpk_decode_steps; device errors through mpk_graph_status. */
 mpk_status mpk_serve_run(mpk_server *s, uint32_t n_iterations, void *stream);
 /* After the caller synchronised the stream: state (0 queued, 1 running, 2 done) and the tokens a
  * request has produced so far (tokens = HOST int32 [cap] or NULL; n_tokens = how many exist). */

@@ -196,6 +196,10 @@ class ServeState:
     def n_running(self):
         return sum(r >= 0 for r in self.slot_req)
 
+    def drained(self):
+        """Nothing running and nothing queued (after an iteration's start-event task)."""
+        return self.n_running() == 0 and self.q_head == len(self.requests)
+
     def snapshot(self):
         """The state as plain integers (what a device-side implementation must reproduce)."""
         return {"slot_req": list(self.slot_req),
@@ -225,6 +229,16 @@ class ServingOracle:
         self.sampled = [self.dec.ops.argmax(lg[b]) for b in range(len(tokens))]
         self.last_logits = lg
         return tokens, positions
+
+    def launch(self, n):
+        """One launch of up to n iterations: the kernel runs until its workload is done (paper
+        Section 5), i.e. the iteration whose start-event task finds nothing running and nothing
+        queued is the launch's last.  Returns the number of iterations run."""
+        for i in range(n):
+            self.iteration()
+            if self.state.drained():
+                return i + 1
+        return n
 
     def outputs(self, r):
         q = self.state.requests[r]

@@ -2714,6 +2714,7 @@ __device__ __forceinline__ void body_serve(const StepArgs& a) {
   q_head += n_admit;
   // ---- (3) the iteration's metadata
   const bool act = mine && req >= 0;
+  const bool drained = __ballot(act) == 0ull && q_head >= q_tail;   // nothing running, nothing queued
   const bool wants = act && (pos & ps_mask) == 0u;
   const uint64_t want_mask = __ballot(wants);
   if (wants) {
@@ -2742,6 +2743,9 @@ __device__ __forceinline__ void body_serve(const StepArgs& a) {
     st_act_u32(sv.scalars + kServeIterations, ld_relaxed(sv.scalars + kServeIterations) + 1u);
     st_act_u32(sv.scalars + kServeTokens, ld_relaxed(sv.scalars + kServeTokens) + n_produced);
     st_act_u32(sv.scalars + kServeDone, ld_relaxed(sv.scalars + kServeDone) + n_done);
+    // nothing running and nothing queued: this iteration is the launch's last (the step number
+    // names the decision, so that no stale one is ever taken for it)
+    if (drained) st_act_u32(sv.scalars + kServeStop, a.epoch);
   }
 }
 
@@ -3244,6 +3248,32 @@ __global__ void __launch_bounds__(kThreads) mpk_loop_kernel(StepArgs a) {
   const uint32_t n_steps = a.n_steps;
   for (uint32_t step = 0; step < n_steps; ++step, ++a.epoch) {
     a.step = (uint16_t)step;
+    if (step > 0 && (a.flags & kServeBit)) {
+      // A serving launch ends when its server has drained (Section 5: the kernel runs until the
+      // workload is done).  The serving task of the previous step recorded that step's number if
+      // it found nothing running and nothing queued; every worker has since run a task downstream
+      // of it, so all of them read the same decision here.  The steps that are not run must still
+      // count for the events -- the host has advanced the step number by n_steps -- so every
+      // worker adds the notifications of its own tasks for all of them at once; only after the
+      // previous step has ended altogether (its terminal event), or a counter would pass the
+      // target that one of that step's tasks is still waiting for.
+      const uint32_t stop = __builtin_amdgcn_readfirstlane(ld_relaxed(a.g->serve->scalars + kServeStop));
+      if (stop == a.epoch - 1u) {
+        StepArgs prev = a;
+        prev.epoch = a.epoch - 1u;
+        if (!wait_event(prev, (int32_t)a.g->terminal_event, s_flag)) return;
+        const uint32_t left = n_steps - step;
+        for (uint32_t qi = q0 + threadIdx.x; qi < q1; qi += kThreads) {
+          const int32_t e = ((const MPK_CONST TaskDesc*)(a.tasks + ld_u32c(a.g->aot + qi)))->trig_event;
+          if (e < 0) continue;
+          const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
+          uint32_t* cnt = (ev.flags & EV_HIER) ? a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (1u + (blockIdx.x & 7u)) * kHierStrideWords
+                                               : a.counters + e;
+          __hip_atomic_fetch_add(as_global(cnt), left, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        return;
+      }
+    }
     if (NB == 8 && !MOE) {
       __syncthreads();   // (nobody is inside a task function any more)
       publish_args(a);

@@ -117,7 +117,7 @@ struct ServeDev {
   uint32_t page_shift;
 };
 enum : uint32_t { kServeNFree = 0, kServePromised = 1, kServeQHead = 2, kServeQTail = 3, kServeIterations = 4,
-                  kServeTokens = 5, kServeDone = 6, kServeScalars = 8 };
+                  kServeTokens = 5, kServeDone = 6, kServeStop = 7, kServeScalars = 8 };
 
 // ---------------------------------------------------------------- host-side graph
 struct HostOp {

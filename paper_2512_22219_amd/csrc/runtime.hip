@@ -588,6 +588,8 @@ extern "C" mpk_status mpk_graph_status(mpk_graph* g) {
   }
 }
 
+static hipError_t server_forget_drained(mpk_server* s);
+
 extern "C" mpk_status mpk_graph_reset(mpk_graph* g) {
   if (!g) { set_error("NULL graph"); return MPK_ERR_INVALID_ARG; }
   if (g->host_only) return MPK_OK;
@@ -596,6 +598,7 @@ extern "C" mpk_status mpk_graph_reset(mpk_graph* g) {
   HIP_TRY(hipMemset(g->d_err, 0, 8 * sizeof(uint32_t)));
   HIP_TRY(hipMemset(g->d_hier, 0, (size_t)std::max(g->h.n_hier_events, 1u) * kHierWordsPerEvent * sizeof(uint32_t)));
   HIP_TRY(hipMemset(g->d_grp, 0, std::max<size_t>(g->h.n_group_counters, 1) * sizeof(uint32_t)));
+  if (g->server) HIP_TRY(server_forget_drained(g->server));   // (step numbers start over)
   {
     const size_t ns = std::max(g->n_sched, 1u), nw = g->h.opt.n_workers;
     HIP_TRY(hipMemset(g->d_evq_buf, 0, ns * g->evq_cap * sizeof(uint64_t)));
@@ -767,6 +770,8 @@ struct mpk_server {
   std::vector<uint32_t> lens, tails;
 };
 
+static hipError_t server_forget_drained(mpk_server* s) { return hipMemset(s->d_scalars + kServeStop, 0, sizeof(uint32_t)); }
+
 static void server_free(mpk_server* s) {
   (void)hipFree(s->d_slot); (void)hipFree(s->d_table); (void)hipFree(s->d_free); (void)hipFree(s->d_prompt);
   (void)hipFree(s->d_out); (void)hipFree(s->d_tokens); (void)hipFree(s->d_positions); (void)hipFree(s->d_scalars);
@@ -909,6 +914,10 @@ extern "C" mpk_status mpk_serve_run(mpk_server* s, uint32_t n_iterations, void* 
   for (mpk_graph* x : s->graphs)
     if (x->h.cfg.batch >= open) { g = x; break; }
   s->last_batch = g->h.cfg.batch;
+  // the "drained" marker is a step number of the graph that ran: each graph of a set counts its
+  // own steps, so the marker starts every launch at zero (no step has that number)
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, s->d_scalars + kServeStop, (size_t)1, 0u);
+  HIP_TRY(hipGetLastError());
   const uint32_t keep = g->step_flags;
   g->step_flags |= kServeBit;
   const mpk_status st = launch_steps(g, n_iterations, s->d_tokens, s->d_positions, nullptr, s->d_logits, nullptr, stream);

@@ -267,21 +267,35 @@ def test_many_iterations_per_launch_serve_every_request_as_if_alone(variant, ps,
     half = len(reqs) // 2
     for r in reqs[:half]:
         assert srv.submit(r[0], r[1], stream) == ora.submit(*r)
-    launches = 0
+    launches = ran = 0
     while launches < 40:
         if launches == 1:
             for r in reqs[half:]:
                 assert srv.submit(r[0], r[1], stream) == ora.submit(*r)
         srv.run(n_iter, stream)
-        for _ in range(n_iter):
-            ora.iteration()
+        ran += ora.launch(n_iter)
         launches += 1
         torch.cuda.synchronize()
         gpu.graph.status()
         gs = srv.state()
+        assert gs["iterations"] == ran, launches      # (a launch ends with the iteration that finds the server drained)
         if launches > 1 and gs["q_head"] == len(reqs) and all(r < 0 for r in gs["slot_req"]):
             break
-    assert gs["iterations"] == launches * n_iter
+    # a launch with nothing to do is over after one iteration, and the events are where a launch
+    # that ran all its steps would have left them: the next launch serves a new request
+    srv.run(9, stream)
+    assert ora.launch(9) == 1
+    torch.cuda.synchronize()
+    gpu.graph.status()
+    assert srv.state()["iterations"] == ran + 1
+    assert srv.submit(reqs[0][0], reqs[0][1], stream) == ora.submit(*reqs[0])
+    srv.run(40, stream)
+    more = ora.launch(40)
+    torch.cuda.synchronize()
+    gpu.graph.status()
+    gs = srv.state()
+    assert gs["iterations"] == ran + 1 + more and more < 40
+    assert srv.result(len(reqs)) == ora.outputs(len(reqs))
     _same_state(gs, ora.state, launches)
     assert sorted(gs["free"]) == list(range(s.batch, n_pages)) and gs["promised"] == 0
     for r in range(len(reqs)):
@@ -353,8 +367,7 @@ def test_a_served_graph_set_runs_the_smallest_graph_that_holds_the_open_requests
             assert srv.submit(r[0], r[1], stream) == ora.submit(*r)
         nxt += n_new
         srv.run(n_iter, stream)
-        for _ in range(n_iter):
-            ora.iteration()
+        ora.launch(n_iter)
         torch.cuda.synchronize()
         srv.status()
         assert srv.last_batch() == want_batch, (nxt, srv.last_batch(), want_batch)
