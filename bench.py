@@ -91,6 +91,10 @@ def main():
                          "page size, serving task on the start event, --steps iterations in one launch) and "
                          "attach it as the 'serving' sub-record; prompts are fed through the decode path "
                          "first, off the clock, until every slot stands at the workload's KV length")
+    ap.add_argument("--offline", type=int, default=0, metavar="N_REQUESTS",
+                    help="also run the paper's end-to-end workload on this config (offline batched inference: N "
+                         "requests of a 64-token prompt and 1024 generated tokens, served from inside the kernel "
+                         "until the queue has drained) and attach it as the 'offline' sub-record")
     ap.add_argument("--no-serving", action="store_true",
                     help="default run (C2) only: skip the serving sub-record")
     ap.add_argument("--no-batch8", action="store_true",
@@ -121,6 +125,8 @@ def main():
     if args.serving or (args.config == "C2" and not args.no_serving and args.tokens_per_launch == 1):
         # (the default run: the batch-1 workload also served from inside the kernel, pages of 64 rows)
         out["serving"] = measure_serving(args, args.config, args.serving or 64)
+    if args.offline:
+        out["offline"] = measure_offline(args, args.config, args.offline)
     if b8 is not None:
         out["batch8"] = {k: b8[k] for k in ("metric", "value", "unit", "ms_per_step", "tokens_per_s", "steps", "warmup",
                                             "achieved_hbm_GBps", "bytes_per_step", "roofline", "config", "final_tokens")
@@ -202,6 +208,67 @@ def measure_serving(args, config, page_size):
            "achieved_hbm_GBps": bytes_step / (kern_ms * 1e-3) / 1e9,
            "prompt_iterations_off_the_clock": lens[0] + args.warmup,
            "tokens_produced": st["tokens_produced"]}
+    srv.destroy()
+    graph.destroy()
+    del model, pools
+    torch.cuda.empty_cache()
+    return out
+
+
+def measure_offline(args, config, n_requests, prompt_len=64, new_tokens=1024, page_size=64):
+    """The paper's end-to-end workload (Section 6.2: offline batched inference, every request a
+    64-token prompt and 1024 generated tokens, paged attention and continuous batching on, the
+    maximum batch size = the config's batch): n_requests seeded requests are queued up front and
+    served from inside the persistent kernel until the server has drained -- launches of up to 4096
+    iterations, each ending by itself when nothing is left.  Prompts go through the decode path."""
+    import numpy as np
+    import torch
+    import paper_2512_22219_amd as M
+    from synth import gen as G
+    from synth.device import DeviceModel
+
+    shape = G.CONFIGS[config]
+    seed = 0
+    assert prompt_len + new_tokens - 1 <= shape.max_seq
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    model = DeviceModel(shape, seed, dev)
+    model.k = model.v = None
+    torch.cuda.empty_cache()
+    per_req = -(-(prompt_len + new_tokens - 1) // page_size)
+    n_pages = shape.batch + shape.batch * per_req
+    pools = [torch.zeros((shape.n_layers, n_pages, shape.n_kv_heads, page_size, shape.head_dim),
+                         dtype=torch.bfloat16, device=dev) for _ in range(2)]
+    common = dict(fusion=args.fusion, transitive_reduction=1)
+    common.update({k: int(v) for k, v in (o.split("=", 1) for o in args.opt)})
+    graph = M.compile_graph(shape, model.weight_ptrs(), (pools[0].data_ptr(), pools[1].data_ptr()), launch_mode=0,
+                            greedy_loop=1, serving=1, kv_page_size=page_size, kv_pages=n_pages, **common)
+    srv = graph.serve(n_requests, prompt_len, new_tokens, -1)
+    stream = torch.cuda.current_stream().cuda_stream
+    rng = np.random.default_rng(seed)
+    for _ in range(n_requests):
+        srv.submit(rng.integers(0, shape.vocab, prompt_len), new_tokens, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    launches = 0
+    while True:
+        srv.run(4096, stream)
+        launches += 1
+        torch.cuda.synchronize()
+        st = srv.state()
+        if st["q_head"] == n_requests and all(r < 0 for r in st["slot_req"]):
+            break
+        assert launches < 64
+    dt = time.perf_counter() - t0
+    graph.status()
+    assert st["tokens_produced"] == n_requests * new_tokens
+    assert all(srv.result(r)[1] == 2 for r in range(n_requests))
+    out = {"workload": f"{n_requests} requests, prompt {prompt_len}, {new_tokens} generated tokens each, max batch {shape.batch}, "
+                       f"pages of {page_size} rows",
+           "seconds": dt, "iterations": st["iterations"], "launches": launches,
+           "ms_per_iteration": dt * 1e3 / st["iterations"],
+           "generated_tokens_per_s": n_requests * new_tokens / dt,
+           "ms_per_generated_token_per_request": dt * 1e3 * min(shape.batch, n_requests) / (n_requests * new_tokens)}
     srv.destroy()
     graph.destroy()
     del model, pools
