@@ -7,7 +7,8 @@ A "step" is one decode step through the persistent mega-kernel (mpk_decode_step)
 greedy token feedback (arg max on the device, no host sync).  Prints ONE JSON line.
 The default run also attaches `batch8` (the batch-8 shape timed the same way) and `serving` (the
 batch-1 workload served from inside the kernel: paged KV cache, serving task, 32 iterations per
-launch).
+launch) and `offline` (one request of the paper's end-to-end workload -- 64-token prompt, 1024
+generated tokens -- served in one launch until the queue has drained).
 Also measured and attached: the same task bodies launched one kernel per operator (eager and as
 a replayed HIP graph), and the CPU oracle timed on a bounded sample of the same workload.
 """
@@ -96,7 +97,7 @@ def main():
                          "requests of a 64-token prompt and 1024 generated tokens, served from inside the kernel "
                          "until the queue has drained) and attach it as the 'offline' sub-record")
     ap.add_argument("--no-serving", action="store_true",
-                    help="default run (C2) only: skip the serving sub-record")
+                    help="default run (C2) only: skip the serving and offline sub-records")
     ap.add_argument("--no-batch8", action="store_true",
                     help="default run (C2, batch 1) only: skip the batch-8 half of the metric (C3)")
     args = ap.parse_args()
@@ -125,8 +126,9 @@ def main():
     if args.serving or (args.config == "C2" and not args.no_serving and args.tokens_per_launch == 1):
         # (the default run: the batch-1 workload also served from inside the kernel, pages of 64 rows)
         out["serving"] = measure_serving(args, args.config, args.serving or 64)
-    if args.offline:
-        out["offline"] = measure_offline(args, args.config, args.offline)
+    if args.offline or (args.config == "C2" and not args.no_serving and args.tokens_per_launch == 1):
+        # (the default run: one request of the paper's offline workload on the batch-1 shape)
+        out["offline"] = measure_offline(args, args.config, args.offline or 1)
     if b8 is not None:
         out["batch8"] = {k: b8[k] for k in ("metric", "value", "unit", "ms_per_step", "tokens_per_s", "steps", "warmup",
                                             "achieved_hbm_GBps", "bytes_per_step", "roofline", "config", "final_tokens")
