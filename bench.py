@@ -7,8 +7,8 @@ A "step" is one decode step through the persistent mega-kernel (mpk_decode_step)
 greedy token feedback (arg max on the device, no host sync).  Prints ONE JSON line.
 The default run also attaches `batch8` (the batch-8 shape timed the same way) and `serving` (the
 batch-1 workload served from inside the kernel: paged KV cache, serving task, 32 iterations per
-launch) and `offline` (one request of the paper's end-to-end workload -- 64-token prompt, 1024
-generated tokens -- served in one launch until the queue has drained).
+call) and `offline` (one request of the paper's end-to-end workload -- 64-token prompt, 1024
+generated tokens -- served in one call until the queue has drained).
 Also measured and attached: the same task bodies launched one kernel per operator (eager and as
 a replayed HIP graph), and the CPU oracle timed on a bounded sample of the same workload.
 """
@@ -144,7 +144,9 @@ def measure_serving(args, config, page_size):
     one request per batch slot, its prompt as long as the slot's KV length in the workload, fed
     through the decode path off the clock (requests are submitted longest first, so that all
     slots reach their lengths in the same iteration); then args.steps iterations -- serving
-    task, decode step through the page tables, greedy sampling -- timed as ONE launch."""
+    task, decode step through the page tables, greedy sampling -- timed as ONE mpk_serve_run call
+    (one launch of the persistent kernel at batch > 4, a launch per iteration back to back with
+    no host synchronisation at batch <= 4: the library's choice)."""
     import numpy as np
     import torch
     import paper_2512_22219_amd as M
@@ -206,7 +208,7 @@ def measure_serving(args, config, page_size):
     bytes_step = stats["weight_bytes"] + stats["kv_row_bytes"] * pos_avg
     kern_ms = e0.elapsed_time(e1) / args.steps
     out = {"ms_per_iteration": ms, "tokens_per_s": shape.batch * 1e3 / ms, "kernel_ms_per_iteration": kern_ms,
-           "iterations_per_launch": args.steps, "page_size": page_size, "kv_pages": n_pages,
+           "iterations_per_call": args.steps, "page_size": page_size, "kv_pages": n_pages,
            "achieved_hbm_GBps": bytes_step / (kern_ms * 1e-3) / 1e9,
            "prompt_iterations_off_the_clock": lens[0] + args.warmup,
            "tokens_produced": st["tokens_produced"]}
@@ -221,8 +223,9 @@ def measure_offline(args, config, n_requests, prompt_len=64, new_tokens=1024, pa
     """The paper's end-to-end workload (Section 6.2: offline batched inference, every request a
     64-token prompt and 1024 generated tokens, paged attention and continuous batching on, the
     maximum batch size = the config's batch): n_requests seeded requests are queued up front and
-    served from inside the persistent kernel until the server has drained -- launches of up to 4096
-    iterations, each ending by itself when nothing is left.  Prompts go through the decode path."""
+    served from inside the persistent kernel until the server has drained -- mpk_serve_run calls of
+    up to 4096 iterations, each ending by itself when nothing is left.  Prompts go through the
+    decode path."""
     import numpy as np
     import torch
     import paper_2512_22219_amd as M
@@ -267,7 +270,7 @@ def measure_offline(args, config, n_requests, prompt_len=64, new_tokens=1024, pa
     assert all(srv.result(r)[1] == 2 for r in range(n_requests))
     out = {"workload": f"{n_requests} requests, prompt {prompt_len}, {new_tokens} generated tokens each, max batch {shape.batch}, "
                        f"pages of {page_size} rows",
-           "seconds": dt, "iterations": st["iterations"], "launches": launches,
+           "seconds": dt, "iterations": st["iterations"], "calls": launches,
            "ms_per_iteration": dt * 1e3 / st["iterations"],
            "generated_tokens_per_s": n_requests * new_tokens / dt,
            "ms_per_generated_token_per_request": dt * 1e3 * min(shape.batch, n_requests) / (n_requests * new_tokens)}
@@ -385,7 +388,7 @@ def measure(args, config, baselines=True, cpu=True):
                                f"vocab {shape.vocab}, batch {shape.batch}, KV "
                                f"{shape.kv_len_lo}" + (f"..{shape.kv_len_hi}" if shape.kv_len_hi != shape.kv_len_lo else "")
                                + " prior positions, greedy decode",
-                   "launch": "persistent mega-kernel" + (f", {tpl} tokens per launch" if tpl > 1 else ""),
+                   "launch": "persistent mega-kernel" + (f", {tpl} tokens per mpk_decode_steps call" if tpl > 1 else ""),
                    "fusion": args.fusion,
                    "n_workers": stats["n_workers"], "tasks": stats["n_tasks"],
                    "events": stats["n_events"],

@@ -151,7 +151,12 @@ typedef struct mpk_compile_options {
                                lowest index on ties; tiles_sampling tasks per sequence) so that several
                                tokens can be decoded in ONE launch (mpk_decode_steps): the
                                kernel runs until its workload is done (Section 5).  Such a
-                               graph is run with mpk_decode_steps only                          */
+                               graph is run with mpk_decode_steps only.  How n steps are
+                               issued is the library's choice: one launch of the persistent
+                               kernel, or -- for batch sizes up to 4, whose linear bodies run
+                               about 3.5 % slower inside the step loop -- n launches of the
+                               single-step kernel back to back, with no host synchronisation
+                               between them; 2 = always the one launch                          */
   uint32_t kv_batch;        /* number of sequences the KV cache is laid out for (the `batch`
                                extent of mpk_kv_ptrs' layout); 0 = cfg.batch.  Lets a graph for
                                fewer sequences run on the first cfg.batch slots of a larger
@@ -465,12 +470,14 @@ mpk_status mpk_serve_status(mpk_server *s);
  * the request could never be admitted (rows above max_seq, more pages than the pool can free). */
 mpk_status mpk_serve_submit(mpk_server *s, const int32_t *prompt, uint32_t prompt_len,
                             uint32_t max_new_tokens, void *stream, uint32_t *request_id);
-/* Run up to n_iterations decoding iterations (1 .. 65535) in ONE launch of the persistent kernel
- * (per-operator launches with MPK_LAUNCH_PER_OP): every iteration is the serving task, one decode
- * step of all slots, greedy sampling.  The kernel runs until its workload is done (Section 5): the
- * iteration whose serving task finds nothing running and nothing queued is the launch's last
- * (mpk_serve_state tells how many iterations have run; with MPK_LAUNCH_PER_OP the host has issued
- * all of them beforehand, so all of them run).  Asynchronous on `stream`; launches of one server
+/* Run up to n_iterations decoding iterations (1 .. 65535) with no host round trip between them:
+ * ONE launch of the persistent kernel -- or, at batch sizes up to 4 unless the graph was compiled
+ * with greedy_loop = 2, a launch of the single-step kernel per iteration, issued back to back (see
+ * greedy_loop) -- or per-operator launches with MPK_LAUNCH_PER_OP.  Every iteration is the serving
+ * task, one decode step of all slots, greedy sampling.  The kernel runs until its workload is done
+ * (Section 5): the iteration whose serving task finds nothing running and nothing queued is the
+ * call's last; launches queued behind it only settle the event counters and leave
+ * (mpk_serve_state tells how many iterations have run; with MPK_LAUNCH_PER_OP all of them run).  Asynchronous on `stream`; launches of one server
  * must not overlap.  Errors as mpk_decode_steps; device errors through mpk_graph_status. */
 mpk_status mpk_serve_run(mpk_server *s, uint32_t n_iterations, void *stream);
 /* After the caller synchronised the stream: state (0 queued, 1 running, 2 done) and the tokens a

@@ -1080,7 +1080,7 @@ static mpk_status validate(const mpk_model_config& c, const mpk_weight_ptrs* w,
   }
   if (c.hidden % 8 || (!moe && c.ffn % 8) || (c.n_q_heads * c.head_dim) % 8) { set_error("hidden, ffn and n_q*head_dim must be multiples of 8"); return MPK_ERR_UNSUPPORTED; }
   if (c.batch > 16) { set_error("batch %u unsupported by the dense linear bodies (max 16)", c.batch); return MPK_ERR_UNSUPPORTED; }
-  if (o.greedy_loop > 1) { set_error("greedy_loop must be 0 or 1"); return MPK_ERR_INVALID_ARG; }
+  if (o.greedy_loop > 2) { set_error("greedy_loop must be 0, 1 or 2"); return MPK_ERR_INVALID_ARG; }
   if (o.debug_flags & ~(MPK_DEBUG_TRACE | MPK_DEBUG_POISON | MPK_DEBUG_JITTER | MPK_DEBUG_LOSE_NOTIFY)) { set_error("unknown debug_flags bits"); return MPK_ERR_INVALID_ARG; }
   if (o.kv_batch != 0 && o.kv_batch < c.batch) { set_error("kv_batch %u is below batch %u", o.kv_batch, c.batch); return MPK_ERR_INVALID_ARG; }
   if (o.kv_page_size) {

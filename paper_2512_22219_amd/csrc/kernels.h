@@ -3235,6 +3235,39 @@ __device__ __forceinline__ bool aot_pass(const StepArgs& a, uint32_t q0, uint32_
   return true;
 }
 
+// Serving launches end when the server has drained (Section 5: the kernel runs until the workload
+// is done).  The serving task that finds nothing running and nothing queued records its step
+// number; steps after that one are not run, but they must still count for the events -- the host
+// has advanced the step number for all of them, and events compare counters with step x producers
+// -- so every worker adds the notifications of its own tasks, `steps` times each, and leaves.
+__device__ __noinline__ void serve_skip_steps(StepArgs a_in, uint32_t q0, uint32_t q1, uint32_t steps) {
+  const StepArgs a = uniform_args(a_in);
+  q0 = uniform_u32(q0); q1 = uniform_u32(q1); steps = uniform_u32(steps);
+  for (uint32_t qi = q0 + threadIdx.x; qi < q1; qi += kThreads) {
+    const int32_t e = ((const MPK_CONST TaskDesc*)(a.tasks + ld_u32c(a.g->aot + qi)))->trig_event;
+    if (e < 0) continue;
+    const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
+    uint32_t* cnt = (ev.flags & EV_HIER) ? a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (1u + (blockIdx.x & 7u)) * kHierStrideWords
+                                         : a.counters + e;
+    __hip_atomic_fetch_add(as_global(cnt), steps, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+// Did an earlier step of this run (steps a.epoch - a.step .. a.epoch - 1) find the server drained?
+__device__ __forceinline__ bool serve_drained(const StepArgs& a) {
+  const uint32_t stop = __builtin_amdgcn_readfirstlane(ld_relaxed(a.g->serve->scalars + kServeStop));
+  return stop - (a.epoch - (uint32_t)a.step) < (uint32_t)a.step;
+}
+
+// A launch that is one step of a run: true when an earlier step of the run left the server
+// drained -- this step's share of the event counters has then been settled and the kernel leaves.
+// (A real call, so that the kernel around it keeps the code it has without it.)
+__device__ __noinline__ bool serve_step_gate(StepArgs a_in, uint32_t q0, uint32_t q1) {
+  const StepArgs a = uniform_args(a_in);
+  if (!(a.flags & kServeBit) || a.step == 0 || !serve_drained(a)) return false;
+  serve_skip_steps(a, q0, q1, 1u);
+  return true;
+}
+
 // Multi-token launch (graphs with the sampling operator, no schedulers): the task list is walked
 // n_steps times, the epoch -- hence every counter target -- growing by one each time.  A kernel of
 // its own: with the step loop in mpk_mega_kernel the single-step launch measured 2 to 4 % slower.
@@ -3248,31 +3281,16 @@ __global__ void __launch_bounds__(kThreads) mpk_loop_kernel(StepArgs a) {
   const uint32_t n_steps = a.n_steps;
   for (uint32_t step = 0; step < n_steps; ++step, ++a.epoch) {
     a.step = (uint16_t)step;
-    if (step > 0 && (a.flags & kServeBit)) {
-      // A serving launch ends when its server has drained (Section 5: the kernel runs until the
-      // workload is done).  The serving task of the previous step recorded that step's number if
-      // it found nothing running and nothing queued; every worker has since run a task downstream
-      // of it, so all of them read the same decision here.  The steps that are not run must still
-      // count for the events -- the host has advanced the step number by n_steps -- so every
-      // worker adds the notifications of its own tasks for all of them at once; only after the
-      // previous step has ended altogether (its terminal event), or a counter would pass the
-      // target that one of that step's tasks is still waiting for.
-      const uint32_t stop = __builtin_amdgcn_readfirstlane(ld_relaxed(a.g->serve->scalars + kServeStop));
-      if (stop == a.epoch - 1u) {
-        StepArgs prev = a;
-        prev.epoch = a.epoch - 1u;
-        if (!wait_event(prev, (int32_t)a.g->terminal_event, s_flag)) return;
-        const uint32_t left = n_steps - step;
-        for (uint32_t qi = q0 + threadIdx.x; qi < q1; qi += kThreads) {
-          const int32_t e = ((const MPK_CONST TaskDesc*)(a.tasks + ld_u32c(a.g->aot + qi)))->trig_event;
-          if (e < 0) continue;
-          const MPK_CONST EventDesc& ev = *(const MPK_CONST EventDesc*)(a.events + e);
-          uint32_t* cnt = (ev.flags & EV_HIER) ? a.hier + (size_t)ev.hier_slot * kHierWordsPerEvent + (1u + (blockIdx.x & 7u)) * kHierStrideWords
-                                               : a.counters + e;
-          __hip_atomic_fetch_add(as_global(cnt), left, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        return;
-      }
+    if (step > 0 && (a.flags & kServeBit) && serve_drained(a)) {
+      // The previous step's serving task found the server drained; every worker has since run a
+      // task downstream of it, so all of them read the same decision here.  The counters move only
+      // after that step has ended altogether (its terminal event), or one would pass the target
+      // that one of its tasks is still waiting for.
+      StepArgs prev = a;
+      prev.epoch = a.epoch - 1u;
+      if (!wait_event(prev, (int32_t)a.g->terminal_event, s_flag)) return;
+      serve_skip_steps(a, q0, q1, n_steps - step);
+      return;
     }
     if (NB == 8 && !MOE) {
       __syncthreads();   // (nobody is inside a task function any more)
@@ -3287,7 +3305,10 @@ __global__ void __launch_bounds__(kThreads) mpk_loop_kernel(StepArgs a) {
 // 1 = ahead-of-time only; 2 = hybrid only.  Which is faster is a matter of register allocation and
 // code layout, measured per body: the vector linear body (batch <= 4) runs 0.8 % faster from the
 // combined kernel, the matrix-core body spills three times less in a kernel of its own.
-template <int D, int GRP, int NB, bool MOE, int PATHS = 0>
+// RUN: the instance launched once per step for a run of several steps (vector linear bodies): it
+// can find that an earlier step of the run left the server drained.  A kernel of its own, so that
+// the single-step kernel stays exactly as it is (1.2 % slower with the check compiled in).
+template <int D, int GRP, int NB, bool MOE, int PATHS = 0, bool RUN = false>
 __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
   extern __shared__ __align__(16) float dyn_lds[];
   float* lds = dyn_lds + kLdsCtrlFloats;
@@ -3306,6 +3327,9 @@ __global__ void __launch_bounds__(kThreads) mpk_mega_kernel(StepArgs a) {
   }
   const uint32_t q0 = ld_u32c(a.g->aot_off + w), q1 = ld_u32c(a.g->aot_off + w + 1);
   if (PATHS == 1 || (PATHS == 0 && a.n_sched == 0)) {
+    // (a run of serving iterations issued as one launch per step: the launches behind the one
+    // that found the server drained only settle their share of the event counters)
+    if (RUN && __builtin_amdgcn_readfirstlane((int)serve_step_gate(a, q0, q1))) return;
     aot_pass<D, GRP, NB, MOE>(a, q0, q1, lds, s_flag, false);
     return;
   }
@@ -3374,6 +3398,7 @@ struct KernelVariant {
   void (*op)(StepArgs, uint32_t);
   void (*loop)(StepArgs);
   void (*hybrid)(StepArgs);   // with scheduler workgroups (may be the same kernel as `mega`)
+  void (*run_step)(StepArgs); // one step of a run of several, a launch per step (null: use `loop`)
 };
 // index, head_dim, group, batch class, mixture of experts
 #define MPK_VARIANT_LIST(X)                                                                   \

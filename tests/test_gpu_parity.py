@@ -463,6 +463,9 @@ def test_moe_routing_ties_take_the_lower_expert_index(batch):
     (dict(batch=3, n_layers=2), dict(fusion=31, transitive_reduction=1, tiles_sampling=5), 8),
     (dict(batch=2), dict(fusion=31, transitive_reduction=1, launch_mode=1, tiles_sampling=32), 5),
     (dict(), dict(fusion=0, tiles_sampling=3, debug_flags=6), 6),
+    # batch <= 4 issues a launch per step by default; greedy_loop = 2: the one launch of the loop kernel
+    (dict(), dict(fusion=31, transitive_reduction=1, greedy_loop=2), 16),
+    (dict(batch=3, n_layers=2), dict(fusion=31, transitive_reduction=1, greedy_loop=2, tiles_sampling=2), 7),
 ])
 def test_greedy_loop_decodes_several_tokens_in_one_launch(variant, opts, n_steps):
     """Graph with the sampling operator: n_steps tokens from ONE launch of the persistent kernel
@@ -474,7 +477,7 @@ def test_greedy_loop_decodes_several_tokens_in_one_launch(variant, opts, n_steps
     pos0 = rng.integers(20, 100, s.batch)
     ref = D.DecoderOracle(s, G.SynthWeights(s, 4), "f32")
     want_t, want_l = ref.greedy(tok0, pos0, 2 * n_steps)
-    gpu = GpuDecoder(s, 4, greedy_loop=1, **opts)
+    gpu = GpuDecoder(s, 4, **{"greedy_loop": 1, **opts})
     dev = gpu.model.device
     tok = torch.as_tensor(tok0.astype(np.int32), device=dev)
     pos = torch.as_tensor(pos0.astype(np.int32), device=dev)

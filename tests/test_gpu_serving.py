@@ -243,6 +243,9 @@ def _server_logits(srv, s, dev):
     (dict(batch=3, n_layers=2), 8, 3 + 12, 5, dict(debug_flags=M.binding.DEBUG_POISON | M.binding.DEBUG_JITTER)),
     (dict(batch=1, n_layers=2), 16, 1 + 3, 9, {}),
     (dict(batch=3, n_layers=2), 8, 3 + 12, 6, dict(tiles_sampling=4)),
+    # batch <= 4, one launch of the loop kernel for all iterations (the default is a launch per iteration)
+    (dict(batch=3, n_layers=2), 8, 3 + 12, 7, dict(greedy_loop=2)),
+    (dict(batch=1, n_layers=2), 16, 1 + 3, 9, dict(greedy_loop=2, debug_flags=M.binding.DEBUG_JITTER)),
 ])
 def test_many_iterations_per_launch_serve_every_request_as_if_alone(variant, ps, n_pages, n_iter, extra):
     """The kernel keeps running through n_iter iterations per launch (no host round trip between
@@ -261,7 +264,7 @@ def test_many_iterations_per_launch_serve_every_request_as_if_alone(variant, ps,
         ora.iteration()
     eos = ora.state.requests[0].out[min(1, len(ora.state.requests[0].out) - 1)]
     ora = S.ServingOracle(s, G.PagedWeights(s, 4, table0, ps, n_pages), ps, n_pages, eos, "f32")
-    gpu = PagedGpu(s, 4, None, ps, n_pages, greedy_loop=1, serving=1, **FUSED, **extra)
+    gpu = PagedGpu(s, 4, None, ps, n_pages, **{"greedy_loop": 1, "serving": 1, **FUSED, **extra})
     stream = torch.cuda.current_stream().cuda_stream
     srv = gpu.graph.serve(64, 8, 8, eos)
     half = len(reqs) // 2
