@@ -171,7 +171,7 @@ def measure_serving(args, config, page_size):
     common = dict(fusion=args.fusion, transitive_reduction=1)
     common.update({k: int(v) for k, v in (o.split("=", 1) for o in args.opt)})
     graph = M.compile_graph(shape, model.weight_ptrs(), (pools[0].data_ptr(), pools[1].data_ptr()), launch_mode=0,
-                            greedy_loop=1, serving=1, kv_page_size=page_size, kv_pages=n_pages, **common)
+                            **{"greedy_loop": 1, "serving": 1, "kv_page_size": page_size, "kv_pages": n_pages, **common})
     stats = graph.stats()
     lens = sorted((int(x) for x in G.kv_lengths(seed, shape)), reverse=True)
     max_new = args.steps + args.warmup + 1          # nobody finishes on the clock
@@ -247,7 +247,7 @@ def measure_offline(args, config, n_requests, prompt_len=64, new_tokens=1024, pa
     common = dict(fusion=args.fusion, transitive_reduction=1)
     common.update({k: int(v) for k, v in (o.split("=", 1) for o in args.opt)})
     graph = M.compile_graph(shape, model.weight_ptrs(), (pools[0].data_ptr(), pools[1].data_ptr()), launch_mode=0,
-                            greedy_loop=1, serving=1, kv_page_size=page_size, kv_pages=n_pages, **common)
+                            **{"greedy_loop": 1, "serving": 1, "kv_page_size": page_size, "kv_pages": n_pages, **common})
     srv = graph.serve(n_requests, prompt_len, new_tokens, -1)
     stream = torch.cuda.current_stream().cuda_stream
     rng = np.random.default_rng(seed)
@@ -348,7 +348,7 @@ def measure(args, config, baselines=True, cpu=True):
     common = dict(fusion=args.fusion, transitive_reduction=1)
     common.update({k: int(v) for k, v in (o.split("=", 1) for o in args.opt)})
     mega = M.compile_graph(shape, model.weight_ptrs(), model.kv_ptrs(), launch_mode=0,
-                           **common, **({"greedy_loop": 1} if tpl > 1 else {}))
+                           **{**({"greedy_loop": 1} if tpl > 1 else {}), **common})
     mega.multi = tpl > 1
     stats = mega.stats()
     dt, kern_ms = timed(mega)
