@@ -224,7 +224,7 @@ def measure_offline(args, config, n_requests, prompt_len=64, new_tokens=1024, pa
     64-token prompt and 1024 generated tokens, paged attention and continuous batching on, the
     maximum batch size = the config's batch): n_requests seeded requests are queued up front and
     served from inside the persistent kernel until the server has drained -- mpk_serve_run calls of
-    up to 4096 iterations, each ending by itself when nothing is left.  Prompts go through the
+    up to 512 iterations, each ending by itself when nothing is left.  Prompts go through the
     decode path."""
     import numpy as np
     import torch
@@ -257,7 +257,7 @@ def measure_offline(args, config, n_requests, prompt_len=64, new_tokens=1024, pa
     t0 = time.perf_counter()
     launches = 0
     while True:
-        srv.run(4096, stream)
+        srv.run(512, stream)      # (a call per 512 iterations: the host looks at the queue in between)
         launches += 1
         torch.cuda.synchronize()
         st = srv.state()
