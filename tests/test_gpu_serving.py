@@ -418,3 +418,41 @@ def test_a_graph_set_over_a_paged_cache_needs_no_batch_extent():
     assert rel_err(got[:2], want[:2]) < TOL
     assert np.isnan(got[2:]).all()
     gset.destroy()
+
+
+@pytest.mark.parametrize("variant,ps,n_pages,n_req,extra,seed", [
+    (dict(batch=8, n_layers=2, head_dim=128, n_q_heads=4, n_kv_heads=2), 8, 8 + 14, 60, {}, 1),
+    (dict(batch=3, n_layers=2), 8, 3 + 7, 40, dict(debug_flags=M.binding.DEBUG_JITTER), 3),
+    (dict(batch=16, n_layers=1, head_dim=128, n_q_heads=8, n_kv_heads=1), 8, 16 + 30, 80, {}, 6),
+])
+def test_random_arrivals_and_call_lengths_against_the_oracle(variant, ps, n_pages, n_req, extra, seed):
+    """A long randomized run: requests of random prompt and output lengths arrive in bursts of
+    random size between calls of random length, pages are scarce, an end-of-sequence token occurs
+    now and then.  After every call the whole serving state equals the oracle's; at the end so do
+    the outputs of every request."""
+    s = G.small_variant("C1", max_seq=64, **variant)
+    rng = np.random.default_rng(seed)
+    reqs = _requests(rng, s.vocab, n_req, 9, 20)
+    table0 = np.full((s.batch, s.max_seq // ps), -1)
+    ora = S.ServingOracle(s, G.PagedWeights(s, 4, table0, ps, n_pages), ps, n_pages, 7, "f32")
+    gpu = PagedGpu(s, 4, None, ps, n_pages, **{"greedy_loop": 1, "serving": 1, **FUSED, **extra})
+    stream = torch.cuda.current_stream().cuda_stream
+    srv = gpu.graph.serve(n_req, 16, 32, 7)
+    nxt = calls = 0
+    while not (nxt == len(reqs) and ora.state.drained()):
+        k = int(rng.integers(0, 6))
+        for r in reqs[nxt:nxt + k]:
+            assert srv.submit(r[0], r[1], stream) == ora.submit(*r)
+        nxt = min(len(reqs), nxt + k)
+        n = int(rng.integers(1, 30))
+        srv.run(n, stream)
+        ora.launch(n)
+        calls += 1
+        torch.cuda.synchronize()
+        gpu.graph.status()
+        gs = srv.state()
+        _same_state(gs, ora.state, calls)
+        assert calls < 400
+    assert [r for r in range(len(reqs)) if srv.result(r) != ora.outputs(r)] == []
+    srv.destroy()
+    gpu.close()
