@@ -25,6 +25,16 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), name
 
 
+def test_public_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 on its own."""
+    import subprocess
+    src = tmp_path / "t.c"
+    src.write_text('#include "mpk.h"\nint main(void) { mpk_compile_options o = {0}; mpk_serve_config c = {0}; '
+                   '(void)o; (void)c; return (int)MPK_OK; }\n')
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                           "-fsyntax-only", str(src)])
+
+
 def host_graph(shape, **kw):
     kw.setdefault("host_only", 1)
     return M.compile_graph(shape, None, None, **kw)
