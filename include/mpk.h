@@ -245,9 +245,10 @@ mpk_status mpk_compile_dag(uint32_t n_tasks, const uint32_t *pairs, size_t n_pai
 mpk_status mpk_decode_step(mpk_graph *g, const int32_t *token_ids, const int32_t *positions,
                            float *logits_out, void *stream);
 
-/* Decode n_steps tokens greedily in one launch of the persistent kernel (Section 5: the kernel
- * keeps running until the workload completes; no host round trip between tokens).  Only for graphs
- * compiled with greedy_loop = 1 and without scheduler workgroups; with MPK_LAUNCH_PER_OP the host
+/* Decode n_steps tokens greedily in one call, with no host round trip between tokens (Section 5:
+ * the kernel keeps running until the workload completes): one launch of the persistent kernel, or
+ * a launch per step at batch sizes up to 4 (see greedy_loop).  Only for graphs compiled with
+ * greedy_loop and without scheduler workgroups; with MPK_LAUNCH_PER_OP the host
  * issues the operator kernels of every step instead.
  *   token_ids  : device int32 [batch], IN: the tokens to feed first; OUT: the last tokens sampled
  *   positions  : device int32 [batch], IN: rows already cached; OUT: advanced by n_steps
