@@ -180,6 +180,8 @@ constexpr uint32_t kNoPreloadBit = 4u;  // no weight / cache-row request before 
 constexpr uint32_t kLoseNotifyBit = 8u; // worker 0 drops its notifications in this launch (watchdog test)
 constexpr uint32_t kServeBit = 16u;     // serving launch: positions[] and token_ids[] are rewritten by the serving
                                         // task at the start of every step (absolute positions, read coherently)
+constexpr uint32_t kOneStepBit = 32u;   // the launch runs ONE step (single-step entry points, a launch per step of a run):
+                                        // nothing that earlier steps wrote can be stale in a cache
 __device__ __forceinline__ void trace_mark(const StepArgs& a, const TaskDesc& t, int slot) {
   if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)t.pad * kTraceSlots + slot] = wall_clock64();
 }
@@ -1664,12 +1666,18 @@ __device__ __forceinline__ float group_sum(float v) {
 // 16 bytes of a cache row of an earlier step.  Contiguous cache: a plain streaming load (the row's
 // lines were never read in this launch before they were written, see the attention body).  Paged
 // cache: a page that one request gave back may be handed to another within the same launch, so a
-// compute unit may still hold lines of the page's previous life -- every row is read with
-// agent-scope loads, which do not hit such lines.
+// compute unit may still hold lines of the page's previous life -- in a launch that runs several
+// steps every row is read with agent-scope loads, which do not hit such lines; a launch of one
+// step cannot see a page change owners (the serving task runs before any row is read), so there
+// the streaming load is as good as on the contiguous cache.
 template <bool PAGED>
-__device__ __forceinline__ u32x4 ld_cache_row(const uint16_t* p) {
-  if constexpr (PAGED) return ld_row16_coherent(p);
-  else return ld_stream16(p);
+__device__ __forceinline__ u32x4 ld_cache_row(const StepArgs& a, const uint16_t* p) {
+  if constexpr (PAGED) {
+    if (a.flags & kOneStepBit) return ld_stream16(p);
+    return ld_row16_coherent(p);
+  } else {
+    return ld_stream16(p);
+  }
 }
 
 // Position of sequence b in this step.  positions[] is the host's and stays as written for the
@@ -1756,8 +1764,8 @@ __device__ __forceinline__ bool body_attn_partial_regs(const TaskDesc& t, const 
       vreg[r] = u32x4{0, 0, 0, 0};
       if (i < n && t0 + i != (uint32_t)pos) {
         const size_t off = row_off(i);
-        kreg[r] = ld_cache_row<PAGED>(Kb + off + sub * 8);
-        vreg[r] = ld_cache_row<PAGED>(Vb + off + sub * 8);
+        kreg[r] = ld_cache_row<PAGED>(a, Kb + off + sub * 8);
+        vreg[r] = ld_cache_row<PAGED>(a, Vb + off + sub * 8);
       }
     }
   };
@@ -2165,8 +2173,8 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
       vreg[r] = u32x4{0, 0, 0, 0};
       if (i < n && t0 + i != (uint32_t)pos) {
         const size_t off = row_off(i);
-        kreg[r] = ld_cache_row<PAGED>(Kb + off + sub * 8);
-        vreg[r] = ld_cache_row<PAGED>(Vb + off + sub * 8);
+        kreg[r] = ld_cache_row<PAGED>(a, Kb + off + sub * 8);
+        vreg[r] = ld_cache_row<PAGED>(a, Vb + off + sub * 8);
       }
     }
   };
@@ -2290,8 +2298,8 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
         const uint32_t i = i_first + (r0 + kAttnPre + r) * stride;
         if (i < n && i != i_new) {
           const size_t off = row_off(i);
-          kreg[r] = ld_cache_row<PAGED>(Kb + off + sub * 8);
-          vreg[r] = ld_cache_row<PAGED>(Vb + off + sub * 8);
+          kreg[r] = ld_cache_row<PAGED>(a, Kb + off + sub * 8);
+          vreg[r] = ld_cache_row<PAGED>(a, Vb + off + sub * 8);
         }
       }
     }

@@ -510,6 +510,7 @@ static mpk_status launch_steps(mpk_graph* g, uint32_t n_steps, const int32_t* to
     // 3.01 ms per token), and the GPU front end overlaps back-to-back launches almost completely.
     // greedy_loop = 2 asks for the single launch regardless.
     const bool by_step = n_steps > 1 && h.opt.greedy_loop != 2 && !g->n_sched && g->kv->run_step != nullptr;
+    if (by_step || n_steps == 1) a.flags |= kOneStepBit;
     if (by_step) {
       for (uint32_t i = 0; i < n_steps; ++i) {
         a.step = (uint16_t)i;
