@@ -154,9 +154,11 @@ typedef struct mpk_compile_options {
                                graph is run with mpk_decode_steps only.  How n steps are
                                issued is the library's choice: one launch of the persistent
                                kernel, or -- for batch sizes up to 4, whose linear bodies run
-                               about 3.5 % slower inside the step loop -- n launches of the
-                               single-step kernel back to back, with no host synchronisation
-                               between them; 2 = always the one launch                          */
+                               about 3.5 % slower inside the step loop, and for serving calls,
+                               whose paged attention needs slower loads inside a launch of
+                               several steps -- n launches of the single-step kernel back to
+                               back, with no host synchronisation between them; 2 = always the
+                               one launch                                                       */
   uint32_t kv_batch;        /* number of sequences the KV cache is laid out for (the `batch`
                                extent of mpk_kv_ptrs' layout); 0 = cfg.batch.  Lets a graph for
                                fewer sequences run on the first cfg.batch slots of a larger
@@ -472,9 +474,10 @@ mpk_status mpk_serve_status(mpk_server *s);
 mpk_status mpk_serve_submit(mpk_server *s, const int32_t *prompt, uint32_t prompt_len,
                             uint32_t max_new_tokens, void *stream, uint32_t *request_id);
 /* Run up to n_iterations decoding iterations (1 .. 65535) with no host round trip between them:
- * ONE launch of the persistent kernel -- or, at batch sizes up to 4 unless the graph was compiled
- * with greedy_loop = 2, a launch of the single-step kernel per iteration, issued back to back (see
- * greedy_loop) -- or per-operator launches with MPK_LAUNCH_PER_OP.  Every iteration is the serving
+ * a launch of the single-step kernel per iteration, issued back to back (measured faster than the
+ * alternative at every batch size: see greedy_loop) -- or ONE launch of the persistent kernel for
+ * all of them when the graph was compiled with greedy_loop = 2 (and for graphs that fall back to
+ * the generic kernels) -- or per-operator launches with MPK_LAUNCH_PER_OP.  Every iteration is the serving
  * task, one decode step of all slots, greedy sampling.  The kernel runs until its workload is done
  * (Section 5): the iteration whose serving task finds nothing running and nothing queued is the
  * call's last; launches queued behind it only settle the event counters and leave

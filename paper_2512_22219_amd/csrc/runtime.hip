@@ -509,7 +509,8 @@ static mpk_status launch_steps(mpk_graph* g, uint32_t n_steps, const int32_t* to
     // the step loop those bodies come out about 3.5 % slower (8B shape, batch 1: 3.12 against
     // 3.01 ms per token), and the GPU front end overlaps back-to-back launches almost completely.
     // greedy_loop = 2 asks for the single launch regardless.
-    const bool by_step = n_steps > 1 && h.opt.greedy_loop != 2 && !g->n_sched && g->kv->run_step != nullptr;
+    const bool by_step = n_steps > 1 && h.opt.greedy_loop != 2 && !g->n_sched && g->kv->run_step != nullptr &&
+                         (g->kv->nb != 8 || (g->step_flags & kServeBit));
     if (by_step || n_steps == 1) a.flags |= kOneStepBit;
     if (by_step) {
       for (uint32_t i = 0; i < n_steps; ++i) {

@@ -246,6 +246,11 @@ def _server_logits(srv, s, dev):
     # batch <= 4, one launch of the loop kernel for all iterations (the default is a launch per iteration)
     (dict(batch=3, n_layers=2), 8, 3 + 12, 7, dict(greedy_loop=2)),
     (dict(batch=1, n_layers=2), 16, 1 + 3, 9, dict(greedy_loop=2, debug_flags=M.binding.DEBUG_JITTER)),
+    # batch 8: serving calls are a launch per iteration by default as well; the one launch of the loop kernel
+    (dict(batch=8, n_layers=2, head_dim=128, n_q_heads=4, n_kv_heads=2), 16, 8 + 14, 25, dict(greedy_loop=2)),
+    (dict(batch=8, n_layers=1, head_dim=128, n_q_heads=8, n_kv_heads=1, ffn=0, n_experts=8, top_k=2, expert_ffn=64), 8, 8 + 20, 9, {}),
+    (dict(batch=8, n_layers=1, head_dim=128, n_q_heads=8, n_kv_heads=1, ffn=0, n_experts=8, top_k=2, expert_ffn=64), 8, 8 + 20, 9,
+     dict(greedy_loop=2, debug_flags=M.binding.DEBUG_JITTER)),
 ])
 def test_many_iterations_per_launch_serve_every_request_as_if_alone(variant, ps, n_pages, n_iter, extra):
     """The kernel keeps running through n_iter iterations per launch (no host round trip between
@@ -424,6 +429,7 @@ def test_a_graph_set_over_a_paged_cache_needs_no_batch_extent():
     (dict(batch=8, n_layers=2, head_dim=128, n_q_heads=4, n_kv_heads=2), 8, 8 + 14, 60, {}, 1),
     (dict(batch=3, n_layers=2), 8, 3 + 7, 40, dict(debug_flags=M.binding.DEBUG_JITTER), 3),
     (dict(batch=16, n_layers=1, head_dim=128, n_q_heads=8, n_kv_heads=1), 8, 16 + 30, 80, {}, 6),
+    (dict(batch=8, n_layers=2, head_dim=128, n_q_heads=4, n_kv_heads=2), 8, 8 + 14, 40, dict(greedy_loop=2), 7),
 ])
 def test_random_arrivals_and_call_lengths_against_the_oracle(variant, ps, n_pages, n_req, extra, seed):
     """A long randomized run: requests of random prompt and output lengths arrive in bursts of
