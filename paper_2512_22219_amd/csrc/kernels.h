@@ -1663,6 +1663,23 @@ __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
+// Rounds of cache rows the running-softmax attention body keeps in registers (requested ahead of
+// their use), by the kernel's batch class nb (0: the generic kernels) and query heads per KV head.
+// Batch 1: chunks are a few rounds long and the task is a chain of latencies -- as many rounds as
+// the running state of the heads leaves registers for, so that a whole chunk is requested before
+// the event.  Matrix-core batch classes: chunks are tens of rounds long and all 256 workers stream
+// at once; three rounds in flight per wavefront measured fastest (8B shape at batch 8: 5.29 ms per
+// step against 5.30 / 5.36 / 5.36 / 5.52 with 2 / 4 / 6 / 8; the mixture-of-experts shape at batch
+// 16: 15.0 against 15.5 / 15.4 with 2 / 4) -- what is in flight beyond that only lengthens the
+// queue in front of everybody's next request.
+constexpr int attn_depth(int nb, int grp) { return nb >= 5 ? 3 : (grp <= 4 ? 8 : 4); }
+constexpr bool attn_streams(int nb) { return nb >= 5; }
+
+__device__ __forceinline__ void unpack8(const u32x4& w, float (&f)[8]) {   // 8 bf16 -> fp32
+  f[0] = bf16_lo(w.x); f[1] = bf16_hi(w.x); f[2] = bf16_lo(w.y); f[3] = bf16_hi(w.y);
+  f[4] = bf16_lo(w.z); f[5] = bf16_hi(w.z); f[6] = bf16_lo(w.w); f[7] = bf16_hi(w.w);
+}
+
 // 16 bytes of a cache row of an earlier step.  Contiguous cache: a plain streaming load (the row's
 // lines were never read in this launch before they were written, see the attention body).  Paged
 // cache: a page that one request gave back may be handed to another within the same launch, so a
@@ -2109,7 +2126,7 @@ __device__ __forceinline__ void attn_deal(const StepArgs& a, uint32_t C, uint32_
 // tasks, looks up its pages and requests its rows.  Table entries are read with coherent loads
 // (one per row and lane group; the lookups of a batch of rounds travel together).  An entry
 // outside the pool is reported and replaced by page 0: no address ever leaves the pool.
-template <int D, int GRP, bool PAGED = false>
+template <int D, int GRP, bool PAGED = false, int NB = 0>
 __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepArgs& a, float* lds,
                                                   int32_t wait_ev, uint32_t* s_flag) {
   constexpr uint32_t d = D, grp = GRP, LPP = D / 8, PPW = 64 / LPP, NW = kThreads / 64;
@@ -2161,20 +2178,54 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
   const uint32_t sub = lane % LPP, slot = lane / LPP;
   const uint32_t i_first = wave * PPW + slot;
   const uint32_t n_rounds = (n + stride - 1) / stride;
-  // rounds held in registers at a time: bounded by what the running state of GRP heads leaves
-  constexpr int kAttnPre = GRP <= 4 ? 8 : 4;
-  // ---- pre-load: the first rounds of K and V rows (never the row appended this step)
+  constexpr int kAttnPre = attn_depth(NB, GRP);   // rounds held in registers at a time
+  constexpr bool STREAM = attn_streams(NB);         // which of the two request schedules below
+  // the row appended this step, if in this chunk: it is written after the early reads (by this or
+  // another workgroup), so it is never among them and is fetched with coherent loads when its turn
+  // comes (STREAM: after all the rounds)
+  const uint32_t i_new = (!bad_pos && c == C - 1) ? n - 1 : 0xFFFFFFFFu;
+  // ---- STREAM: K and V rows of round `rnd` into register pair r.  Always two loads, no branch around
+  // them: the compiler counts the loads in flight statically, and a load that may or may not have
+  // been issued makes every later wait a wait for everything.  A position the chunk does not have
+  // (or the appended row) reads the chunk's last row of an earlier step again -- this compute
+  // unit's own line, already on its way or cached -- and nobody uses the result; a chunk with no
+  // such row reads 16 bytes of the task array (immutable).
   u32x4 kreg[kAttnPre], vreg[kAttnPre];
+  const uint16_t* nothing = (const uint16_t*)a.tasks;
+  const uint32_t n_old = n - (i_new != 0xFFFFFFFFu ? 1u : 0u);   // rows of earlier steps in the chunk
+  // (`coherent`: which kind of load a paged cache needs in this launch, see ld_cache_row -- a
+  // compile-time choice here, made once per task by the callers: a branch around the load would
+  // spoil the count just the same)
+  auto request_round = [&](auto coherent, int r, uint32_t rnd) {
+    const uint32_t i = min(i_first + rnd * stride, n_old - 1u);
+    const bool ok = n_old != 0u;
+    const size_t off = ok ? row_off(i) + sub * 8 : (size_t)0;
+    const uint16_t *kp = ok ? Kb + off : nothing, *vp = ok ? Vb + off : nothing;
+    kreg[r] = decltype(coherent)::value ? ld_row16_coherent(kp) : ld_stream16(kp);
+    vreg[r] = decltype(coherent)::value ? ld_row16_coherent(vp) : ld_stream16(vp);
+  };
+  const bool coherent_rows = PAGED && !(a.flags & kOneStepBit);
+  // ---- pre-load: the first rounds (never the row appended this step)
   auto load_rows = [&]() {
+    if constexpr (STREAM) {
+      if (coherent_rows) {
 #pragma unroll
-    for (int r = 0; r < kAttnPre; ++r) {
-      const uint32_t i = i_first + r * stride;
-      kreg[r] = u32x4{0, 0, 0, 0};
-      vreg[r] = u32x4{0, 0, 0, 0};
-      if (i < n && t0 + i != (uint32_t)pos) {
-        const size_t off = row_off(i);
-        kreg[r] = ld_cache_row<PAGED>(a, Kb + off + sub * 8);
-        vreg[r] = ld_cache_row<PAGED>(a, Vb + off + sub * 8);
+        for (int r = 0; r < kAttnPre; ++r) request_round(std::true_type{}, r, (uint32_t)r);
+      } else {
+#pragma unroll
+        for (int r = 0; r < kAttnPre; ++r) request_round(std::false_type{}, r, (uint32_t)r);
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < kAttnPre; ++r) {
+        const uint32_t i = i_first + r * stride;
+        kreg[r] = u32x4{0, 0, 0, 0};
+        vreg[r] = u32x4{0, 0, 0, 0};
+        if (i < n && i != i_new) {
+          const size_t off = row_off(i);
+          kreg[r] = ld_cache_row<PAGED>(a, Kb + off + sub * 8);
+          vreg[r] = ld_cache_row<PAGED>(a, Vb + off + sub * 8);
+        }
       }
     }
   };
@@ -2286,63 +2337,93 @@ __device__ __forceinline__ bool body_attn_partial(const TaskDesc& t, const StepA
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[j][e] = 0.f;
   }
-  const uint32_t i_new = (c == C - 1) ? n - 1 : 0xFFFFFFFFu;   // the row appended this step, if in this chunk
-  // A batch of rounds lives in registers; its first half is requested again (for the next batch)
-  // as soon as it has been used, so that those loads travel while the second half is multiplied.
-  constexpr int kHalf = kAttnPre / 2;
-  auto request_next = [&](uint32_t r0, auto first_half) {
-    constexpr int lo = decltype(first_half)::value ? 0 : kHalf, hi = decltype(first_half)::value ? kHalf : kAttnPre;
-    if (r0 + kAttnPre < n_rounds) {
+  // one position per lane group: score, running maximum, probability, P.V
+  auto consume = [&](const float (&k8)[8], const float (&v8)[8], bool valid) {
 #pragma unroll
-      for (int r = lo; r < hi; ++r) {
-        const uint32_t i = i_first + (r0 + kAttnPre + r) * stride;
-        if (i < n && i != i_new) {
-          const size_t off = row_off(i);
-          kreg[r] = ld_cache_row<PAGED>(a, Kb + off + sub * 8);
-          vreg[r] = ld_cache_row<PAGED>(a, Vb + off + sub * 8);
+    for (int j = 0; j < GRP; ++j) {
+      float sv = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sv = fmaf(k8[e], q[j][e], sv);
+      sv = group_sum<LPP>(sv);
+      if (valid) {
+        if (sv > m[j]) {   // a new maximum (rare after the first positions): rescale the running state
+          const float sc = __builtin_amdgcn_exp2f(m[j] - sv);   // 2^(-inf) = 0 on the first position
+          l[j] *= sc;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[j][e] *= sc;
+          m[j] = sv;
         }
+        const float p = __builtin_amdgcn_exp2f(sv - m[j]);
+        l[j] += p;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p, v8[e], acc[j][e]);
       }
     }
   };
-  for (uint32_t r0 = 0; r0 < n_rounds; r0 += kAttnPre) {
+  if constexpr (STREAM) {
+    // Long chunks, every worker streaming: kAttnPre rounds live in registers; a pair is requested
+    // again, kAttnPre rounds ahead, as soon as it has been used, so that all but one of them are
+    // in flight while one is multiplied.
+    auto rounds = [&](auto coherent) {
+      for (uint32_t r0 = 0; r0 < n_rounds; r0 += kAttnPre) {
 #pragma unroll
-    for (int r = 0; r < kAttnPre; ++r) {
-      if (r == kHalf) request_next(r0, std::true_type{});
-      const uint32_t i = i_first + (r0 + r) * stride;
-      if (i == i_new) {
-        // written after the pre-load, by this or another workgroup: coherent loads
-        const size_t off = row_off(i);
-        kreg[r] = ld_row16_coherent(Kb + off + sub * 8);
-        vreg[r] = ld_row16_coherent(Vb + off + sub * 8);
-      }
-      const bool valid = i < n;
-      const u32x4 kv = kreg[r], vv = vreg[r];
-      const float k8[8] = {bf16_lo(kv.x), bf16_hi(kv.x), bf16_lo(kv.y), bf16_hi(kv.y),
-                           bf16_lo(kv.z), bf16_hi(kv.z), bf16_lo(kv.w), bf16_hi(kv.w)};
-      const float v8[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
-                           bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
-#pragma unroll
-      for (int j = 0; j < GRP; ++j) {
-        float sv = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) sv = fmaf(k8[e], q[j][e], sv);
-        sv = group_sum<LPP>(sv);
-        if (valid) {
-          if (sv > m[j]) {   // a new maximum (rare after the first positions): rescale the running state
-            const float sc = __builtin_amdgcn_exp2f(m[j] - sv);   // 2^(-inf) = 0 on the first position
-            l[j] *= sc;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[j][e] *= sc;
-            m[j] = sv;
-          }
-          const float p = __builtin_amdgcn_exp2f(sv - m[j]);
-          l[j] += p;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p, v8[e], acc[j][e]);
+        for (int r = 0; r < kAttnPre; ++r) {
+          const uint32_t i = i_first + (r0 + r) * stride;
+          float k8[8], v8[8];
+          unpack8(kreg[r], k8);
+          unpack8(vreg[r], v8);
+          request_round(coherent, r, r0 + r + kAttnPre);   // (behind the unpacking: the pair's registers are free)
+          consume(k8, v8, i < n && i != i_new);
         }
       }
+    };
+    if (coherent_rows) rounds(std::true_type{});
+    else rounds(std::false_type{});
+    if (i_new != 0xFFFFFFFFu) {   // (uniform) the appended row: the lane group its position falls to
+      const size_t off = row_off(i_new) + sub * 8;
+      float k8[8], v8[8];
+      unpack8(ld_row16_coherent(Kb + off), k8);
+      unpack8(ld_row16_coherent(Vb + off), v8);
+      consume(k8, v8, i_new % stride == i_first);
     }
-    request_next(r0, std::false_type{});
+  } else {
+    // Short chunks (a few rounds, most often all of them requested before the event): a batch of
+    // rounds lives in registers; its first half is requested again (for the next batch) as soon
+    // as it has been used, the second half at the end of the batch, and only when the chunk goes
+    // on -- a chunk that fits the registers issues no further request at all.
+    constexpr int kHalf = kAttnPre / 2;
+    auto request_next = [&](uint32_t r0, auto first_half) {
+      constexpr int lo = decltype(first_half)::value ? 0 : kHalf, hi = decltype(first_half)::value ? kHalf : kAttnPre;
+      if (r0 + kAttnPre < n_rounds) {
+#pragma unroll
+        for (int r = lo; r < hi; ++r) {
+          const uint32_t i = i_first + (r0 + kAttnPre + r) * stride;
+          if (i < n && i != i_new) {
+            const size_t off = row_off(i);
+            kreg[r] = ld_cache_row<PAGED>(a, Kb + off + sub * 8);
+            vreg[r] = ld_cache_row<PAGED>(a, Vb + off + sub * 8);
+          }
+        }
+      }
+    };
+    for (uint32_t r0 = 0; r0 < n_rounds; r0 += kAttnPre) {
+#pragma unroll
+      for (int r = 0; r < kAttnPre; ++r) {
+        if (r == kHalf) request_next(r0, std::true_type{});
+        const uint32_t i = i_first + (r0 + r) * stride;
+        if (i == i_new) {
+          // written after the pre-load, by this or another workgroup: coherent loads
+          const size_t off = row_off(i);
+          kreg[r] = ld_row16_coherent(Kb + off + sub * 8);
+          vreg[r] = ld_row16_coherent(Vb + off + sub * 8);
+        }
+        float k8[8], v8[8];
+        unpack8(kreg[r], k8);
+        unpack8(vreg[r], v8);
+        consume(k8, v8, i < n);
+      }
+      request_next(r0, std::false_type{});
+    }
   }
   if (PAGED && bad_page) report(a, DE_BAD_PAGE, b, t0);   // (the rows came from page 0 instead: wrong, but in bounds)
   // ---- combine the lane groups of the wavefront, then the wavefronts
@@ -2785,7 +2866,7 @@ __device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, f
         constexpr uint32_t window = kAttnRounds * (kThreads / 64) * (64 / ((D ? D : 128) / 8));
         if ((GRP ? GRP : 1) <= 4 && !(t.flags & TF_ATTN_BALANCE) && (a.g->max_seq + t.p1 - 1) / t.p1 <= window)
           return body_attn_partial_regs<(D ? D : 128), (GRP ? GRP : 1), true>(t, a, lds, wait_ev, s_flag);
-        return body_attn_partial<(D ? D : 128), (GRP ? GRP : 1), true>(t, a, lds, wait_ev, s_flag);
+        return body_attn_partial<(D ? D : 128), (GRP ? GRP : 1), true, NB>(t, a, lds, wait_ev, s_flag);
       }
       const uint32_t grp = a.g->n_q / a.g->n_kv;
       if (a.g->head_dim == 128) {
@@ -2804,7 +2885,7 @@ __device__ __forceinline__ bool run_task(const TaskDesc& t, const StepArgs& a, f
       constexpr uint32_t window = kAttnRounds * (kThreads / 64) * (64 / ((D ? D : 128) / 8));
       if ((GRP ? GRP : 1) <= 4 && !(t.flags & TF_ATTN_BALANCE) && (a.g->max_seq + t.p1 - 1) / t.p1 <= window)
         return body_attn_partial_regs<(D ? D : 128), (GRP ? GRP : 1)>(t, a, lds, wait_ev, s_flag);
-      return body_attn_partial<(D ? D : 128), (GRP ? GRP : 1)>(t, a, lds, wait_ev, s_flag);
+      return body_attn_partial<(D ? D : 128), (GRP ? GRP : 1), false, NB>(t, a, lds, wait_ev, s_flag);
     }
     const uint32_t grp = a.g->n_q / a.g->n_kv;
     if (a.g->head_dim == 128) {
