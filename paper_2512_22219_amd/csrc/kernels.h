@@ -901,15 +901,20 @@ __device__ __forceinline__ void static_for(F&& f) {
 //
 // The 8 wavefronts form rg row groups x ks K slices (rg = 1, 2, 4 or 8, the smallest with
 // 4 rg >= nrt).  Wavefront (slice s, group g) owns row tiles g, g + rg, g + 2 rg, g + 3 rg (those
-// below nrt: nrtw of them) and, in every chunk, the s-th of ks nearly equal runs of 128-input
-// "k-groups".  It works in rounds of 16 weight fragments (32 inputs x 16 rows, 1 KB each) = 4 slot
-// groups of 4 fragments; slot group q always adds into accumulator q:
+// below nrt: nrtw of them) and, in every chunk, the s-th of ks nearly equal runs of 64-input
+// "k-groups".  It works in rounds of 8 weight fragments (32 inputs x 16 rows, 1 KB each) = 4 slot
+// groups of kMfmaFrags = 2 fragments, two rounds in flight (16 KB per wavefront, 32 MB over the
+// chip: rounds of twice the size keep 64 MB in flight, which HBM does not need and which stands in
+// the way of every store acknowledgement, counter update and poll of the hops between operators
+// -- 8B shape at batch 8: 5.27 -> 5.10 ms per step; rounds of half the size starve: 5.93);
+// slot group q always adds into accumulator q:
 //   nrtw >= 3: one k-group per round, slot group q = row tile q of the wavefront
 //   nrtw == 2: two k-groups per round, slot group q = (k-group q / 2, row tile q % 2)
 //   nrtw == 1: four k-groups per round, slot group q = k-group q
 // so the fragments of a k-group's inputs are converted once and used by all row tiles of the
 // round.  The epilogue adds the accumulators of a row tile over slot groups and slices in a
 // fixed order (mfma_dot).
+constexpr uint32_t kMfmaFrags = 2;
 struct MfmaGeom {
   uint32_t K, nb, nrt;
   uint32_t Kc, nchunk;   // inputs per chunk, chunks
@@ -959,7 +964,7 @@ __device__ __forceinline__ u32x4 select4(bool c, const u32x4& x, const u32x4& y)
 //                  lane's row of 16-row tile rt (32 bits: a scalar base and one vector offset per
 //                  load, no address pairs to keep); loads are clamped to the end of the row
 //   src_row(b)   : fp32 input row b (read with coherent loads), b < nb
-//   wait_fn()    : called after the first round of weights has been requested (cross-task
+//   wait_fn()    : called after the first two rounds of weights have been requested (cross-task
 //                  pre-loading, Section 5.3: 16 KB per wavefront, 32 MB over the chip); returns
 //                  kLinDone to go on
 // LDS: x [nb][xstride] f32 at `lds`, reused at the end for the per-wavefront partial tiles
@@ -981,6 +986,7 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
   float* xs = lds;
   float* part = lds;
   const uint32_t frow = lane & 15u, fk = (uint32_t)(lane >> 4) * 8u;
+  constexpr uint32_t FR = kMfmaFrags, KG = 32u * FR;   // fragments per slot group, inputs per k-group
   // slot group q of a round: k-group offset inside the round, byte offset of its row tile's row
   const uint32_t sh = kgpr == 4u ? 0u : (kgpr == 2u ? 1u : 2u);   // q >> sh = k-group offset
   uint32_t wq[4];
@@ -997,7 +1003,7 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
   };
   // the wavefront's run of k-groups in chunk c; a chunk takes an even number of round slots
   // (>= 2), so that even slots always use fragment buffer A and odd ones B
-  auto chunk_kgs = [&](uint32_t c) { return (min(Kc, K - c * Kc) + 127u) >> 7; };
+  auto chunk_kgs = [&](uint32_t c) { return (min(Kc, K - c * Kc) + KG - 1u) / KG; };
   auto run_lo = [&](uint32_t c) { return G.my_s * chunk_kgs(c) / S; };
   auto run_hi = [&](uint32_t c) { return nrtw ? (G.my_s + 1u) * chunk_kgs(c) / S : 0u; };
   auto slots = [&](uint32_t c) {
@@ -1005,8 +1011,8 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
     const uint32_t n = hi > lo ? (hi - lo + kgpr - 1u) / kgpr : 0u;
     return max(2u, (n + 1u) & ~1u);
   };
-  // requests the 16 fragments of round slot (c, i) into buf; buf[4 Q + u] = fragment u of slot
-  // group Q.  Always 16 loads, no branch: the compiler counts the loads in flight statically, and a
+  // requests the 4 FR fragments of round slot (c, i) into buf; buf[FR Q + u] = fragment u of slot
+  // group Q.  Always that many loads, no branch: the compiler counts the loads in flight statically, and a
   // load that may or may not have been issued makes it wait for everything older than it could
   // be -- in effect for the whole pipeline, every round.  For a slot group that does not exist
   // (past the end of the run, or no row tile) all lanes read the matrix' first 16 bytes instead
@@ -1020,7 +1026,7 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
       const uint32_t kg = kg0 + (Q >> sh);
       const bool ok = kg < hi && (kgpr == 1u ? Q < nrtw : true);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) buf[4 * Q + u] = ld_frag(wq[Q], k0 + kg * 128u + (uint32_t)u * 32u, ok);
+      for (int u = 0; u < (int)FR; ++u) buf[FR * Q + u] = ld_frag(wq[Q], k0 + kg * KG + (uint32_t)u * 32u, ok);
     });
   };
   // RMSNorm gains of a chunk, bf16, copied to LDS behind the staged rows (weights: chunk 0's are
@@ -1032,15 +1038,17 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
     if (pro_norm && col < klen)
       __builtin_amdgcn_global_load_lds(as_global((const u32x4*)(gain + k0 + col)), (lds_ptr_t)(gl + wave * 512u), 16, 0, 0);
   };
-  u32x4 wA[16], wB[16];
+  u32x4 wA[4 * FR], wB[4 * FR];
   const bool preload = !(a.flags & kNoPreloadBit);   // off: the ablation of Section 6.5, Fig. 10
-  // Before the event only the first round is requested: a wavefront sees its loads complete in
-  // the order it issued them, so whatever is requested now stands between the event and the
-  // staged input.  The second round follows the staging.
+  // Both rounds (16 KB per wavefront) are requested before the event.  A wavefront sees its loads
+  // complete in the order it issued them, so whatever is requested now stands between the event
+  // and the staged input: more than this measured slower.
   request_gains(0u);
   if (preload) {
     request_round(wA, 0u, 0u);
     asm volatile("; first round requested" ::: "memory");
+    request_round(wB, 0u, 1u);
+    asm volatile("; second round requested" ::: "memory");
   }
   {
     const uint32_t w = wait_fn();
@@ -1096,7 +1104,7 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
   auto step = [&](u32x4* buf, uint32_t c, uint32_t i, uint32_t c2, uint32_t i2) {
     const uint32_t kg0 = run_lo(c) + i * kgpr, hi = run_hi(c);
     if (kg0 < hi) {
-      static_for<0, 4>([&](auto Uc) {
+      static_for<0, (int)FR>([&](auto Uc) {
         constexpr uint32_t U = (uint32_t)decltype(Uc)::value;
         u32x4 p0, p1, p2;   // operands of the first, second, third multiply
         static_for<0, 4>([&](auto Qc) {
@@ -1105,10 +1113,10 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
           const bool rowok = kgpr == 1u ? Q < nrtw : true;
           if (kg < hi && rowok) {
             if (Q == 0u || (Q >> sh) != ((Q - 1u) >> sh)) {   // first slot group of its k-group
-              const float* src = xl + kg * 128u + U * 32u;
+              const float* src = xl + kg * KG + U * 32u;
               float4 x0 = *(const float4*)src, x1 = *(const float4*)(src + 4);
               if (pro_norm) {
-                const u32x4 gg = *(const u32x4*)(gl + kg * 128u + U * 32u + fk);
+                const u32x4 gg = *(const u32x4*)(gl + kg * KG + U * 32u + fk);
                 x0.x *= bf16_lo(gg.x); x0.y *= bf16_hi(gg.x); x0.z *= bf16_lo(gg.y); x0.w *= bf16_hi(gg.y);
                 x1.x *= bf16_lo(gg.z); x1.y *= bf16_hi(gg.z); x1.z *= bf16_lo(gg.w); x1.w *= bf16_hi(gg.w);
               }
@@ -1118,7 +1126,7 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
               if (PACK == 2) { p0 = select4(frow < 8u, h, m); p1 = l; }
               if (PACK == 3) p0 = select4(frow < 4u, h, select4(frow < 8u, m, l));
             }
-            const bf16x8 av = __builtin_bit_cast(bf16x8, buf[4 * Q + U]);
+            const bf16x8 av = __builtin_bit_cast(bf16x8, buf[FR * Q + U]);
             acc[Q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, p0), acc[Q], 0, 0, 0);
             if (PACK == 2) acc_lo[Q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, p1), acc_lo[Q], 0, 0, 0);
             if (PACK == 1) {
@@ -1136,14 +1144,7 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
     stage(c);
     lds_barrier();
     if (pro_norm) row_squares(c);
-    if (c == 0) {
-      // the second round, behind the staging.  (The slot number goes through an empty asm so
-      // that the 16 addresses are worked out here: computed next to the first round's, ahead of
-      // the staging, they would wait in scratch memory.)
-      uint32_t one = 1u;
-      asm volatile("" : "+s"(one));
-      request_round(wB, 0u, one);
-    }
+    if (c == 0 && !preload) request_round(wB, 0u, 1u);
     if (c == 0) {
       trace_mark(a, t, 2);
 #pragma unroll
