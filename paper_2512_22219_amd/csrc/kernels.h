@@ -1081,10 +1081,13 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
       for (uint32_t i = threadIdx.x; i < nb * (kpad - klen); i += kThreads) xs[(size_t)(i / (kpad - klen)) * xstride + klen + i % (kpad - klen)] = 0.f;
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's copies have landed
   };
-  // sums of squares of the staged rows (before the gains): wavefront w takes rows w, w + 8
+  // sums of squares of the staged rows (before the gains), needed only by the epilogue: taken
+  // behind the chunk's multiplies by wavefronts 0..3 (rows w, w + 4, ...), which are through their
+  // share well before the upper four are (they win the arbitration on their SIMDs), so the pass is
+  // off the path from the event to the first multiply and costs nothing at the end either
   auto row_squares = [&](uint32_t c) {
     const uint32_t klen = min(Kc, K - c * Kc);
-    for (uint32_t r = wave; r < nb; r += 8u) {
+    for (uint32_t r = wave; r < nb && wave < 4u; r += 4u) {
       float sq = 0.f;
       for (uint32_t col = 4u * (uint32_t)lane; col < klen; col += 256u) {
         const float4 v = *(const float4*)(xs + (size_t)r * xstride + col);
@@ -1143,7 +1146,6 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
     if (c) lds_barrier();   // everybody has finished with the previous chunk
     stage(c);
     lds_barrier();
-    if (pro_norm) row_squares(c);
     if (c == 0 && !preload) request_round(wB, 0u, 1u);
     if (c == 0) {
       trace_mark(a, t, 2);
@@ -1157,6 +1159,7 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
       step(wA, c, i, c2, i2);
       step(wB, c, i + 1u, c2, i2 + 1u);
     }
+    if (pro_norm) row_squares(c);   // (the chunk is still staged: the next barrier is ahead)
   }
   trace_mark(a, t, 8);
   // ---- the column groups of a packed multiply added up: afterwards column b < nb holds the sum
