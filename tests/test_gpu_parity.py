@@ -164,6 +164,42 @@ def test_linear_stream_odd_shapes(variant, opts):
     strict_steps(s, 2, opts, tok, pos, 2)
 
 
+@pytest.mark.parametrize("shape,pos,opts", [
+    # 4 query heads per KV head, batch 8: lengths 1 and 2 leave chunks empty, chunks that hold
+    # only the row appended this step, and chunks with a single row of an earlier step
+    (dict(batch=8, n_q_heads=8, n_kv_heads=2), [0, 1, 2, 3, 40, 95, 150, 0], dict(attn_chunks=4)),
+    (dict(batch=8, n_q_heads=8, n_kv_heads=2), [0, 1, 2, 3, 40, 95, 150, 0], dict(attn_chunks=4, no_attn_balance=1)),
+    (dict(batch=8, n_q_heads=8, n_kv_heads=2), [150, 149, 33, 32, 31, 64, 65, 97], dict(attn_chunks=1)),
+    (dict(batch=16, n_q_heads=4, n_kv_heads=1), [(37 * i) % 150 for i in range(16)], dict(attn_chunks=3)),
+    (dict(batch=5, n_q_heads=4, n_kv_heads=1), [0, 150, 0, 7, 99], dict(attn_chunks=2, launch_mode=1)),
+    # 8 query heads per KV head, mixture of experts, batch 16
+    (dict(batch=16, n_q_heads=8, n_kv_heads=1, ffn=0, n_experts=16, top_k=4, expert_ffn=96),
+     [(53 * i) % 150 for i in range(16)], dict(attn_chunks=2)),
+    (dict(batch=8, n_q_heads=8, n_kv_heads=1, ffn=0, n_experts=16, top_k=4, expert_ffn=96),
+     [0, 1, 2, 3, 150, 95, 31, 32], dict(attn_chunks=4)),
+])
+def test_kernels_specialised_for_batch_5_to_16_on_short_and_ragged_chunks(shape, pos, opts):
+    """Head dimension 128 with 4 (dense) or 8 (mixture of experts) query heads per KV head selects
+    the kernels compiled for those shapes, whose attention body requests cache rows a fixed number
+    of rounds ahead with no branch around a request: chunks shorter than that, empty chunks,
+    chunks that are nothing but the appended row, and the deal changing from step to step."""
+    s = G.small_variant("C1", n_layers=2, hidden=512, head_dim=128, max_seq=192, **shape)
+    ref = D.DecoderOracle(s, G.SynthWeights(s, 4), "f64")
+    gpu = GpuDecoder(s, 4, fusion=31, transitive_reduction=1, **opts)
+    tok = G.tokens(4, s)
+    p = np.array(pos, np.int32)
+    for step in range(3):
+        # (the oracle holds the GPU's appended bf16 rows and expert sets, each checked to be a
+        # valid outcome: at positions 0..3 one rounding decision is most of the attention output)
+        got, want, _, _ = held_step(ref, gpu, tok, p)
+        assert np.isfinite(got).all()
+        assert rel_err(got, want) < TOL, step
+        assert np.array_equal(got.argmax(-1), want.argmax(-1))
+        tok = want.argmax(-1).astype(np.int32)
+        p = p + 1
+    gpu.close()
+
+
 @pytest.mark.parametrize("batch,opts", [
     (8, dict(fusion=31, transitive_reduction=1)),
     (8, dict(fusion=0)),

@@ -64,6 +64,7 @@ class PagedGpu:
     (dict(batch=3, n_layers=2), 16, FUSED),
     (dict(batch=1, n_layers=2), 64, FUSED),
     (dict(batch=8, n_layers=2, head_dim=128, n_q_heads=4, n_kv_heads=2), 32, FUSED),
+    (dict(batch=8, n_layers=2, head_dim=128, n_q_heads=8, n_kv_heads=2), 32, FUSED),      # the kernels compiled for 4 heads per KV head
     (dict(batch=2, n_q_heads=8, n_kv_heads=1), 16, dict(fusion=23)),                      # merge operator of its own
     (dict(batch=4, ffn=0, n_experts=8, top_k=2, expert_ffn=64), 16, FUSED),
     (dict(batch=3, n_layers=2), 8, dict(fusion=31, launch_mode=1)),                       # kernel per operator
@@ -248,6 +249,9 @@ def _server_logits(srv, s, dev):
     (dict(batch=1, n_layers=2), 16, 1 + 3, 9, dict(greedy_loop=2, debug_flags=M.binding.DEBUG_JITTER)),
     # batch 8: serving calls are a launch per iteration by default as well; the one launch of the loop kernel
     (dict(batch=8, n_layers=2, head_dim=128, n_q_heads=4, n_kv_heads=2), 16, 8 + 14, 25, dict(greedy_loop=2)),
+    # the kernels compiled for head dimension 128 and 4 query heads per KV head (dense, batch 5..16): both launch forms
+    (dict(batch=8, n_layers=2, head_dim=128, n_q_heads=8, n_kv_heads=2), 16, 8 + 14, 25, {}),
+    (dict(batch=8, n_layers=2, head_dim=128, n_q_heads=8, n_kv_heads=2), 16, 8 + 14, 25, dict(greedy_loop=2)),
     (dict(batch=8, n_layers=1, head_dim=128, n_q_heads=8, n_kv_heads=1, ffn=0, n_experts=8, top_k=2, expert_ffn=64), 8, 8 + 20, 9, {}),
     (dict(batch=8, n_layers=1, head_dim=128, n_q_heads=8, n_kv_heads=1, ffn=0, n_experts=8, top_k=2, expert_ffn=64), 8, 8 + 20, 9,
      dict(greedy_loop=2, debug_flags=M.binding.DEBUG_JITTER)),
