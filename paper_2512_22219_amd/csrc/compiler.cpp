@@ -1036,7 +1036,8 @@ static uint32_t lds_requirement(const mpk_model_config& c, HostGraph& g, uint32_
       }
     }
     else if (op.kind == MPK_OP_EXPERT) {
-      f = (size_t)moe_x_floats(c.batch) + 8 * 16 + 32;   // input tiles | sums of squares | staged row lists
+      f = (size_t)moe_x_floats(c.batch) + 8 * 16 + 32   // input tiles | sums of squares | staged row lists
+          + 2 + 3 * (size_t)c.n_experts + (size_t)c.batch * c.top_k;   // | the task's copy of the meta-tensor
     }
     else if (op.kind == MPK_OP_ROUTER)
       f = (size_t)c.batch * c.top_k * 2 + (size_t)c.n_experts * (3 + 16) + 64;   // pairs | per-expert counts, offsets, masks, pair table

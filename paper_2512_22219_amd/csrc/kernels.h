@@ -1499,7 +1499,7 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
   uint32_t* rowidx = (uint32_t*)(ssq + 8 * 16);  // [16] pair of each staged row (= output row)
   uint32_t* rowin = rowidx + 16;                 // [16] input row: gate/up reads the token's row, down the pair's
   if (threadIdx.x < ne) {
-    const uint32_t pair = ld_relaxed(plist + threadIdx.x);
+    const uint32_t pair = plist[threadIdx.x];   // (the task's copy of the meta-tensor in LDS)
     rowidx[threadIdx.x] = pair;
     rowin[threadIdx.x] = gateup ? pair / TK : pair;
   }
@@ -1541,22 +1541,30 @@ __device__ __forceinline__ void body_moe_expert(const TaskDesc& t, const StepArg
   const uint32_t* meta = (const uint32_t*)t.in2;
   const uint32_t E = t.p3 & 0xFFFFu, TK = t.p3 >> 16, NT = t.p1, rows_per_expert = t.p2;
   const uint32_t tiles_per_expert = rows_per_expert / 16u;
-  const uint32_t n_active = __builtin_amdgcn_readfirstlane(ld_relaxed(meta));
+  // The part of the meta-tensor an expert task reads -- header, active list, per-expert counts and
+  // offsets, pair lists -- comes to LDS in one round trip; looked up in device memory, every job
+  // cost three dependent trips (expert, its count and offset, its pairs) before its first weight
+  // request could go out.
+  const uint32_t P = a.g->batch * TK, MW = 2u + 3u * E + P;
+  uint32_t* mlds = (uint32_t*)(lds + moe_x_floats(a.g->batch) + 8 * 16 + 32);   // behind the staged row lists
+  for (uint32_t i = threadIdx.x; i < MW; i += kThreads) mlds[i] = ld_relaxed(meta + i);
+  lds_barrier();
+  const uint32_t n_active = min(__builtin_amdgcn_readfirstlane(mlds[0]), E);
   const uint32_t total = n_active * tiles_per_expert;
   uint32_t u0 = (uint32_t)((uint64_t)total * t.c0 / NT);
   const uint32_t u1 = (uint32_t)((uint64_t)total * (t.c0 + 1u) / NT);
   while (u0 < u1) {
     const uint32_t ai = u0 / tiles_per_expert, tile0 = u0 % tiles_per_expert;
     const uint32_t ntile = min(min(u1 - u0, tiles_per_expert - tile0), 32u);
-    const uint32_t e = __builtin_amdgcn_readfirstlane(ld_relaxed(meta + 2 + ai));
-    const uint32_t ne = __builtin_amdgcn_readfirstlane(ld_relaxed(meta + 2 + E + e));
-    const uint32_t po = __builtin_amdgcn_readfirstlane(ld_relaxed(meta + 2 + 2 * E + e));
-    if (e >= E || ne == 0 || ne > 16u || po + ne > a.g->batch * TK) {   // never index with a damaged meta-tensor
+    const uint32_t e = min(__builtin_amdgcn_readfirstlane(mlds[2 + ai]), E);   // (E: rejected below; the two reads stay inside the copy)
+    const uint32_t ne = __builtin_amdgcn_readfirstlane(mlds[2 + E + min(e, E - 1u)]);
+    const uint32_t po = __builtin_amdgcn_readfirstlane(mlds[2 + 2 * E + min(e, E - 1u)]);
+    if (e >= E || ne == 0 || ne > 16u || po + ne > P) {   // never index with a damaged meta-tensor
       if (threadIdx.x == 0) report(a, DE_BAD_META, e, ne);
       return;
     }
     const uint16_t* W = (const uint16_t*)t.w + (size_t)e * rows_per_expert * t.K;
-    moe_expert_job(t, a, lds, W, tile0, ntile, ne, meta + 2 + 3 * E + po, TK);
+    moe_expert_job(t, a, lds, W, tile0, ntile, ne, mlds + 2 + 3 * E + po, TK);
     u0 += ntile;
   }
 }
