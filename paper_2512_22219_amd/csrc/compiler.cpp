@@ -938,6 +938,9 @@ static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGr
   const size_t kv_layer = g.opt.kv_page_size
                               ? (size_t)g.opt.kv_pages * c.n_kv_heads * g.opt.kv_page_size * c.head_dim
                               : (size_t)(g.opt.kv_batch ? g.opt.kv_batch : c.batch) * c.n_kv_heads * c.max_seq * c.head_dim;
+  std::map<int, int32_t> route_event;   // layer -> the event its routing task triggers
+  for (const HostTask& rt : g.tasks)
+    if (rt.op != MPK_TASK_DUMMY_OP && g.ops[rt.op].kind == MPK_OP_ROUTER && rt.trig_event >= 0) route_event[g.ops[rt.op].layer] = rt.trig_event;
   for (size_t i = 0; i < g.tasks.size(); ++i) {
     const HostTask& ht = g.tasks[i];
     TaskDesc& t = g.descs[i];
@@ -995,6 +998,12 @@ static void build_descs(const mpk_model_config& c, const mpk_kv_ptrs* kv, HostGr
       t.aux0 = (void*)act_ref(g, op.data_aux);   // relocated by the runtime like in / in2 / out
       t.ld_in = g.tensors[op.data_in].cols;
       t.ld_out = g.tensors[op.data_out].cols;
+      // second-stage expert task: the event the layer's routing task triggers (+ 1), behind which
+      // the meta-tensor may be read -- the task requests its first weights before its own event
+      if (op.kind == MPK_OP_EXPERT && !(op.flags & TF_GATEUP)) {
+        auto it = route_event.find(op.layer);
+        if (it != route_event.end()) t.aux1 = (void*)(uintptr_t)(it->second + 1);
+      }
     }
     if (op.kind == MPK_OP_ROPE || op.kind == MPK_OP_ATTN_PARTIAL) {
       if (kv && kv->k && kv->v) {

@@ -1485,9 +1485,12 @@ __device__ __forceinline__ void body_moe_route(const TaskDesc& t, const StepArgs
 // token rows routed to that expert: a matrix-core job (mfma_job) whose input rows are gathered
 // through the expert's pair list while they are staged.  All wavefronts take part; ntile <= 32,
 // ne <= 16.
-__device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs& a, float* lds, const uint16_t* W,
+// wait_ev >= 0: the job's inputs exist only once that event is activated (the first job of a
+// second-stage expert task, see run_moe_task): it is waited for behind the job's first weight
+// requests.  Returns false when the step is being aborted.
+__device__ __forceinline__ bool moe_expert_job(const TaskDesc& t, const StepArgs& a, float* lds, const uint16_t* W,
                                                uint32_t tile0, uint32_t ntile, uint32_t ne, const uint32_t* plist,
-                                               uint32_t TK) {
+                                               uint32_t TK, int32_t wait_ev, uint32_t* s_flag) {
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t K = t.K;
@@ -1511,7 +1514,13 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
     return wrow * K * 2u;   // bytes from the expert's first row
   };
   auto src_row = [&](uint32_t b) { return t.in + (size_t)__builtin_amdgcn_readfirstlane(rowin[b]) * t.ld_in; };   // uniform: scalar base addresses
-  mfma_job(a, t, lds, ssq, G, W, row_off, src_row, pro_norm, (const uint16_t*)t.w2, []() -> uint32_t { return kLinDone; });
+  auto wait_fn = [&]() -> uint32_t {
+    if (wait_ev < 0) return kLinDone;
+    const uint32_t w = linear_wait(a, wait_ev, s_flag, wave, lane, NoJit{});
+    trace_mark(a, t, 1);
+    return w;
+  };
+  if (mfma_job(a, t, lds, ssq, G, W, row_off, src_row, pro_norm, (const uint16_t*)t.w2, wait_fn) != kLinDone) return false;
   const uint32_t ncols = (ntile * 16u) >> gateup, col0 = (tile0 * 16u) >> gateup;
   for (uint32_t i = threadIdx.x; i < ncols * ne; i += kThreads) {
     const uint32_t cc = i / ne, bb = i % ne;
@@ -1532,12 +1541,16 @@ __device__ __forceinline__ void moe_expert_job(const TaskDesc& t, const StepArgs
     st_act(t.out + (size_t)rowidx[bb] * t.ld_out + col0 + cc, v);
   }
   lds_barrier();   // the next job reuses the buffers
+  return true;
 }
 
 // Expert task `c0` of `p1`: the active experts' 16-row weight tiles, laid end to end in ascending
 // expert order, are dealt evenly to the expert tasks (the run-time refinement of Section 6.4);
 // a task's share is worked off in jobs of at most 32 tiles that stay inside one expert.
-__device__ __forceinline__ void body_moe_expert(const TaskDesc& t, const StepArgs& a, float* lds) {
+// wait_ev >= 0: the caller has NOT waited for the task's event yet (only for the routing task's,
+// so the meta-tensor is this step's); the first job does, behind its first weight requests.
+__device__ __forceinline__ bool body_moe_expert(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev = -1,
+                                                uint32_t* s_flag = nullptr) {
   const uint32_t* meta = (const uint32_t*)t.in2;
   const uint32_t E = t.p3 & 0xFFFFu, TK = t.p3 >> 16, NT = t.p1, rows_per_expert = t.p2;
   const uint32_t tiles_per_expert = rows_per_expert / 16u;
@@ -1561,12 +1574,16 @@ __device__ __forceinline__ void body_moe_expert(const TaskDesc& t, const StepArg
     const uint32_t po = __builtin_amdgcn_readfirstlane(mlds[2 + 2 * E + min(e, E - 1u)]);
     if (e >= E || ne == 0 || ne > 16u || po + ne > P) {   // never index with a damaged meta-tensor
       if (threadIdx.x == 0) report(a, DE_BAD_META, e, ne);
-      return;
+      break;
     }
     const uint16_t* W = (const uint16_t*)t.w + (size_t)e * rows_per_expert * t.K;
-    moe_expert_job(t, a, lds, W, tile0, ntile, ne, mlds + 2 + 3 * E + po, TK);
+    if (!moe_expert_job(t, a, lds, W, tile0, ntile, ne, mlds + 2 + 3 * E + po, TK, wait_ev, s_flag)) return false;
+    wait_ev = -1;
     u0 += ntile;
   }
+  // (no job ran: the task still ends after its event, like every task)
+  if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
+  return true;
 }
 
 // out[b][c] = resid[b][c] + sum over the token's experts, in ascending expert index, of
@@ -3115,6 +3132,21 @@ __device__ __forceinline__ bool run_moe_task(StepArgs a_in, uint32_t task_index,
     const int32_t wait_ev = (!skip_wait && t.dep_event >= 0 && ((const MPK_CONST EventDesc*)(a.events + t.dep_event))->required != 0) ? t.dep_event : -1;
     trace_mark(a, t, 0);
     if ((a.flags & kTraceBit) && threadIdx.x == 0) as_global(a.g->trace)[(size_t)task_index * kTraceSlots + 5] = blockIdx.x;
+    // Cross-task pre-loading (Section 5.3) for the experts' second stage: which experts are active
+    // is known since the routing task, long before the first stage has produced this task's
+    // inputs.  Such a task (the compiler leaves the routing task's event number + 1 in aux1)
+    // waits for that event -- activated before the first stage could start, so this returns at
+    // once and only orders the reads of the meta-tensor -- finds its first job and requests that
+    // job's first weights, and only then waits for its own event.
+    if (wait_ev >= 0 && t.kind == TK_MOE_EXPERT && t.aux1 != nullptr && !(a.flags & kNoPreloadBit)) {
+      if (!wait_event(a, (int32_t)(uintptr_t)t.aux1 - 1, s_flag)) return false;
+      if (!body_moe_expert(t, a, lds, wait_ev, s_flag)) return false;
+      trace_mark(a, t, 3);
+      if (t.trig_event >= 0) signal_event(a, t, t.trig_event);
+      else __syncthreads();
+      trace_mark(a, t, 4);
+      return true;
+    }
     if (wait_ev >= 0 && !wait_event(a, wait_ev, s_flag)) return false;
     trace_mark(a, t, 1);
   }
