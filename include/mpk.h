@@ -100,10 +100,12 @@ typedef struct mpk_kv_ptrs {
 #define MPK_DEBUG_TRACE 1u  /* record per-task timestamps inside the persistent kernel          */
 #define MPK_DEBUG_POISON 2u /* before every launch, fill every buffer the graph owns for data that
                                crosses tasks (activations, split-KV partials, partial sums,
-                               meta-tensors) with NaN: a task that reads what this step has not
-                               produced yet, or what an earlier step left behind, shows in the
-                               logits (the paper's runtime has no such mode; Section 5 only
-                               states that events order producers before consumers)              */
+                               meta-tensors) with NaN, and leave NaN patterns in the compute
+                               units' local data share: a task that reads what this step has not
+                               produced yet, what an earlier step left behind, or a word of its
+                               staging area that it has not written, shows in the logits (the
+                               paper's runtime has no such mode; Section 5 only states that
+                               events order producers before consumers)                          */
 #define MPK_DEBUG_JITTER 4u /* every task of the persistent kernel starts after a pseudo-random
                                delay of 0 .. 20 us (a hash of task and step): the relative timing
                                of producers and consumers differs in every step, so a missing

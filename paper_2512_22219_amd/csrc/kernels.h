@@ -1037,6 +1037,11 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
     const uint32_t k0 = c * Kc, klen = min(Kc, K - k0), col = 8u * threadIdx.x;
     if (pro_norm && col < klen)
       __builtin_amdgcn_global_load_lds(as_global((const u32x4*)(gain + k0 + col)), (lds_ptr_t)(gl + wave * 512u), 16, 0, 0);
+    // between the end of the row and the end of its last k-group the staged inputs are zeros, and
+    // so must the gains be: whatever an earlier workgroup left there may read as NaN, and
+    // 0 x NaN is NaN
+    if (pro_norm)
+      for (uint32_t i = klen + threadIdx.x; i < ((klen + 127u) & ~127u); i += kThreads) gl[i] = 0;
   };
   u32x4 wA[4 * FR], wB[4 * FR];
   const bool preload = !(a.flags & kNoPreloadBit);   // off: the ablation of Section 6.5, Fig. 10

@@ -56,6 +56,18 @@ __global__ void __launch_bounds__(256) fill_u32_kernel(uint32_t* p, size_t n, ui
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
 
+// MPK_DEBUG_POISON: the local data share keeps what the last workgroup on the compute unit left in
+// it.  A task that reads a word of it that the task has not written (the tail of a staged row, a
+// gain past the end of the input) normally finds an old activation there and gets away with it;
+// this kernel, launched with the decode kernels' own LDS size on 512 workgroups (two per compute unit of the
+// GPU), leaves NaN patterns (as fp32 and as the upper bf16 of a pair) instead.
+__global__ void __launch_bounds__(kThreads) lds_poison_kernel(uint32_t words) {
+  extern __shared__ __align__(16) uint32_t poison_lds[];
+  volatile uint32_t* p = poison_lds;
+  for (uint32_t i = threadIdx.x; i < words; i += kThreads) p[i] = 0x7FC00000u;
+  __syncthreads();
+}
+
 }  // namespace mpk
 
 
@@ -484,6 +496,9 @@ static mpk_status launch_steps(mpk_graph* g, uint32_t n_steps, const int32_t* to
   }
   if (h.opt.debug_flags & MPK_DEBUG_POISON) {
     hipLaunchKernelGGL(fill_u32_kernel, dim3(256), dim3(256), 0, s, (uint32_t*)arena, arena_words, 0x7FC00000u);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(reserve_lds((const void*)lds_poison_kernel, h.lds_bytes));
+    hipLaunchKernelGGL(lds_poison_kernel, dim3(512), dim3(kThreads), h.lds_bytes, s, h.lds_bytes / 4u);
     HIP_TRY(hipGetLastError());
   }
   if (h.opt.launch_mode == MPK_LAUNCH_MEGA) {

@@ -659,6 +659,9 @@ POISON, JITTER = M.binding.DEBUG_POISON, M.binding.DEBUG_JITTER
     (("C1", dict(batch=8, max_seq=192)), dict(fusion=31, transitive_reduction=1)),
     (("C1", dict(batch=4, ffn=0, n_experts=16, top_k=4, expert_ffn=96)), dict(fusion=31, transitive_reduction=1)),
     (("C2", dict(n_layers=2)), dict(fusion=31, transitive_reduction=1)),
+    # inputs that end inside a k-group of the matrix-core body (2056 = 32 x 64 + 8): what lies
+    # between the end of a staged row, or of the gains, and the end of the k-group is multiplied too
+    (("C1", dict(n_layers=2, hidden=2056, ffn=3000, batch=5, max_seq=192)), dict(fusion=31, transitive_reduction=1, n_workers=24)),
 ])
 @pytest.mark.parametrize("debug", [POISON, JITTER, POISON | JITTER])
 def test_poisoned_buffers_and_jittered_task_starts_change_nothing(variant, opts, debug):
