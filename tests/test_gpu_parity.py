@@ -662,6 +662,11 @@ POISON, JITTER = M.binding.DEBUG_POISON, M.binding.DEBUG_JITTER
     # inputs that end inside a k-group of the matrix-core body (2056 = 32 x 64 + 8): what lies
     # between the end of a staged row, or of the gains, and the end of the k-group is multiplied too
     (("C1", dict(n_layers=2, hidden=2056, ffn=3000, batch=5, max_seq=192)), dict(fusion=31, transitive_reduction=1, n_workers=24)),
+    # the kernels compiled for head dimension 128 at batch 5..16, dense (1000 inputs: under one staging tile) and experts
+    (("C1", dict(n_layers=2, hidden=1000, ffn=520, batch=16, vocab=520, head_dim=128, n_q_heads=8, n_kv_heads=2, max_seq=192)),
+     dict(fusion=31, transitive_reduction=1, n_workers=24)),
+    (("C1", dict(n_layers=2, hidden=528, batch=16, head_dim=128, n_q_heads=8, n_kv_heads=1, ffn=0, n_experts=16, top_k=4, expert_ffn=104, max_seq=192)),
+     dict(fusion=31, transitive_reduction=1)),
 ])
 @pytest.mark.parametrize("debug", [POISON, JITTER, POISON | JITTER])
 def test_poisoned_buffers_and_jittered_task_starts_change_nothing(variant, opts, debug):
