@@ -853,8 +853,9 @@ __device__ __forceinline__ uint32_t linear_task(const TaskDesc& t, const StepArg
 // The same operator for 5 to 16 batch rows, on the matrix cores.  At batch 8 the vector ALUs
 // would need about as many cycles for the multiply-adds as HBM needs to deliver the weights; one
 // v_mfma_f32_16x16x32_bf16 does 16 weight rows x 32 inputs x 16 batch columns at once.
-//   A operand = weights: lane l holds row (l % 16) of a 16-row tile, inputs 8 (l / 16) .. + 7 of
-//     the current 32-input step: 16 bytes straight from HBM, no conversion.
+//   A operand = weights: lane l holds row (l % 16) of a 16-row tile and 8 of the 32 inputs of the
+//     multiply: 16 bytes straight from HBM, no conversion (loaded as 8 rows x 128 bytes per
+//     instruction and put in place by one DPP move per register: see mfma_job_packed).
 //   B operand = activations: lane l holds batch column (l % 16), the same 8 inputs, as bf16.
 //     Activations are fp32: x is split into THREE bf16 terms, hi = bf16(x), mid = bf16(x - hi),
 //     lo = bf16(x - hi - mid).  Each conversion rounds to nearest and each remainder is exact in
@@ -989,17 +990,45 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
   constexpr uint32_t FR = kMfmaFrags, KG = 32u * FR;   // fragments per slot group, inputs per k-group
   // slot group q of a round: k-group offset inside the round, byte offset of its row tile's row
   const uint32_t sh = kgpr == 4u ? 0u : (kgpr == 2u ? 1u : 2u);   // q >> sh = k-group offset
-  uint32_t wq[4];
+  // How the weights are loaded.  A multiply wants lane (i = l % 16, j = l / 16) to hold 8 inputs of
+  // tile row i, the same 8 for all i.  Loaded that way an instruction touches 16 rows x 64 bytes --
+  // half lines, which streams 12 % slower than whole lines (5.9 against 6.7 TB/s in isolation).
+  // So the two fragments of a k-group (64 inputs = 128 bytes of a row) are loaded as two
+  // instructions of 8 rows x 128 bytes: load h (h = 0, 1), lane l: row 8 h + l % 8, inputs
+  // 8 (l / 8) .. + 7 of the k-group.  Lane (i, j) then holds, of load 0: row i % 8, input block 2 j
+  // (i < 8) or 2 j + 1 (i >= 8); of load 1: row 8 + i % 8, the same blocks.  One DPP move per
+  // register (rotate the row of 16 lanes by 8, written to half of its lanes) turns the pair into
+  //   first operand : row i, block 2 j      = load 0 (i < 8) | load 1 rotated (i >= 8)
+  //   second operand: row i, block 2 j + 1  = load 0 rotated (i < 8) | load 1 (i >= 8)
+  // and the activations follow: the multiplies of a k-group take input blocks (0, 2, 4, 6) and
+  // (1, 3, 5, 7) instead of (0 .. 3) and (4 .. 7) -- any split of the 64 inputs will do as long as
+  // both operands use the same one.
+  static_assert(kMfmaFrags == 2, "the load pattern pairs the two fragments of a k-group");
+  const uint32_t lrow = lane & 7u, lk = (uint32_t)(lane >> 3) * 8u;   // a load's row (+ 8 h) and first input
+  uint32_t wq[4][2];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const uint32_t j = kgpr == 4u ? 0u : (kgpr == 2u ? (uint32_t)q & 1u : (uint32_t)q);
-    wq[q] = row_off(min(G.my_g + G.rg * j, nrt - 1u));
+    const uint32_t rt = min(G.my_g + G.rg * j, nrt - 1u);
+    wq[q][0] = row_off(rt, lrow);
+    wq[q][1] = row_off(rt, 8u + lrow);
   }
-  // fragment at input k of the row at byte offset ro: this lane's 8 inputs start at k + fk, or
-  // are the row's last 8 when that lies past its end (their staged inputs are zeros)
+  // load h of the k-group at input k of the rows at byte offsets ro: this lane's 8 inputs start at
+  // k + lk, or are the row's last 8 when that lies past its end (their staged inputs are zeros)
   auto ld_frag = [&](uint32_t ro, uint32_t k, bool real) {
-    const uint32_t off = real ? ro + 2u * min(k + fk, K - 8u) : 0u;   // not real: every lane the matrix' first 16 bytes
+    const uint32_t off = real ? ro + 2u * min(k + lk, K - 8u) : 0u;   // not real: every lane the matrix' first 16 bytes
     return __builtin_nontemporal_load((const MPK_GLOBAL u32x4*)((const MPK_GLOBAL char*)wbase + off));
+  };
+  // the pair as loaded -> the two operands (in place)
+  auto to_operands = [&](u32x4& l0, u32x4& l1) {
+    auto ror8 = [](uint32_t old, uint32_t src, auto bank) {   // lanes of `bank`: src of the lane 8 further in its row of 16
+      return (uint32_t)__builtin_amdgcn_update_dpp((int)old, (int)src, 0x128, 0xF, decltype(bank)::value, false);
+    };
+    const u32x4 a = l0, b = l1;
+    l0 = u32x4{ror8(a.x, b.x, std::integral_constant<int, 0xC>{}), ror8(a.y, b.y, std::integral_constant<int, 0xC>{}),
+               ror8(a.z, b.z, std::integral_constant<int, 0xC>{}), ror8(a.w, b.w, std::integral_constant<int, 0xC>{})};
+    l1 = u32x4{ror8(b.x, a.x, std::integral_constant<int, 0x3>{}), ror8(b.y, a.y, std::integral_constant<int, 0x3>{}),
+               ror8(b.z, a.z, std::integral_constant<int, 0x3>{}), ror8(b.w, a.w, std::integral_constant<int, 0x3>{})};
   };
   // the wavefront's run of k-groups in chunk c; a chunk takes an even number of round slots
   // (>= 2), so that even slots always use fragment buffer A and odd ones B
@@ -1026,7 +1055,7 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
       const uint32_t kg = kg0 + (Q >> sh);
       const bool ok = kg < hi && (kgpr == 1u ? Q < nrtw : true);
 #pragma unroll
-      for (int u = 0; u < (int)FR; ++u) buf[FR * Q + u] = ld_frag(wq[Q], k0 + kg * KG + (uint32_t)u * 32u, ok);
+      for (int u = 0; u < (int)FR; ++u) buf[FR * Q + u] = ld_frag(wq[Q][u], k0 + kg * KG, ok);
     });
   };
   // RMSNorm gains of a chunk, bf16, copied to LDS behind the staged rows (weights: chunk 0's are
@@ -1104,7 +1133,7 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
   };
   // this lane's staged row and which term its column takes in the first multiply
   const uint32_t xrow = min(PACK == 1 ? frow : (PACK == 2 ? (frow & 7u) : (frow & 3u)), nb - 1u);
-  const float* xl = xs + (size_t)xrow * xstride + fk;
+  const float* xl = xs + (size_t)xrow * xstride + 2u * fk;   // (operand U of a k-group: input block 2 j + U)
   f32x4 acc[4], acc_lo[4];   // (acc_lo: the lo term's products when PACK == 2)
   // one round slot: multiplies what buf holds for slot (c, i) -- fragment u of every slot group
   // against the three terms of that fragment's inputs, converted once per k-group -- and then
@@ -1112,6 +1141,8 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
   auto step = [&](u32x4* buf, uint32_t c, uint32_t i, uint32_t c2, uint32_t i2) {
     const uint32_t kg0 = run_lo(c) + i * kgpr, hi = run_hi(c);
     if (kg0 < hi) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) to_operands(buf[FR * q], buf[FR * q + 1]);
       static_for<0, (int)FR>([&](auto Uc) {
         constexpr uint32_t U = (uint32_t)decltype(Uc)::value;
         u32x4 p0, p1, p2;   // operands of the first, second, third multiply
@@ -1121,10 +1152,10 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
           const bool rowok = kgpr == 1u ? Q < nrtw : true;
           if (kg < hi && rowok) {
             if (Q == 0u || (Q >> sh) != ((Q - 1u) >> sh)) {   // first slot group of its k-group
-              const float* src = xl + kg * KG + U * 32u;
+              const float* src = xl + kg * KG + U * 8u;
               float4 x0 = *(const float4*)src, x1 = *(const float4*)(src + 4);
               if (pro_norm) {
-                const u32x4 gg = *(const u32x4*)(gl + kg * KG + U * 32u + fk);
+                const u32x4 gg = *(const u32x4*)(gl + kg * KG + 2u * fk + U * 8u);
                 x0.x *= bf16_lo(gg.x); x0.y *= bf16_hi(gg.x); x0.z *= bf16_lo(gg.y); x0.w *= bf16_hi(gg.y);
                 x1.x *= bf16_lo(gg.z); x1.y *= bf16_hi(gg.z); x1.z *= bf16_lo(gg.w); x1.w *= bf16_hi(gg.w);
               }
@@ -1241,8 +1272,8 @@ __device__ __forceinline__ uint32_t linear_task_mfma(const TaskDesc& t, const St
   const uint32_t parts = splitk ? (t.p3 & 0xFFu) : 1u, my_part = splitk ? (t.p3 >> 8) : 0u;
   const uint32_t Hs = t.ld_out / parts;              // columns of the real output
   const uint32_t row0 = t.c0 - my_part * Hs, ldw = splitk ? t.p1 : K;
-  auto row_off = [&](uint32_t rt) {
-    const uint32_t r = min(rt * 16u + frow, R - 1u);   // rows past the end repeat the last one
+  auto row_off = [&](uint32_t rt, uint32_t row) {       // row: this lane's row of the 16-row tile
+    const uint32_t r = min(rt * 16u + row, R - 1u);    // rows past the end repeat the last one
     const uint32_t wrow = gateup ? (row0 + (r >> 1) + ((r & 1u) ? t.p0 : 0u)) : row0 + r;
     return wrow * ldw * 2u;   // bytes; the host checks that a weight matrix stays below 4 GB
   };
@@ -1513,8 +1544,8 @@ __device__ __forceinline__ bool moe_expert_job(const TaskDesc& t, const StepArgs
   }
   lds_barrier();
   const uint32_t frow = lane & 15u, fk = (uint32_t)(lane >> 4) * 8u;
-  auto row_off = [&](uint32_t rt) {
-    const uint32_t r = (tile0 + rt) * 16u + frow;   // row of the expert's gate/up-interleaved (or plain) order
+  auto row_off = [&](uint32_t rt, uint32_t row) {   // row: this lane's row of the 16-row tile
+    const uint32_t r = (tile0 + rt) * 16u + row;    // row of the expert's gate/up-interleaved (or plain) order
     const uint32_t wrow = gateup ? ((r >> 1) + ((r & 1u) ? t.p0 : 0u)) : r;
     return wrow * K * 2u;   // bytes from the expert's first row
   };
