@@ -1040,8 +1040,9 @@ __device__ __forceinline__ uint32_t mfma_job_packed(const StepArgs& a, const Tas
     const uint32_t n = hi > lo ? (hi - lo + kgpr - 1u) / kgpr : 0u;
     return max(2u, (n + 1u) & ~1u);
   };
-  // requests the 4 FR fragments of round slot (c, i) into buf; buf[FR Q + u] = fragment u of slot
-  // group Q.  Always that many loads, no branch: the compiler counts the loads in flight statically, and a
+  // requests the 4 FR kilobytes of round slot (c, i) into buf; buf[FR Q + u] = load u of slot
+  // group Q's k-group (rows 8 u .. 8 u + 7 of the tile, see above; two fragments after the
+  // exchange in step).  Always that many loads, no branch: the compiler counts the loads in flight statically, and a
   // load that may or may not have been issued makes it wait for everything older than it could
   // be -- in effect for the whole pipeline, every round.  For a slot group that does not exist
   // (past the end of the run, or no row tile) all lanes read the matrix' first 16 bytes instead
