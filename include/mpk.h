@@ -384,6 +384,17 @@ mpk_status mpk_graph_trace(mpk_graph *g, uint64_t *buf, size_t cap, size_t *need
  * returns the element count in *need.  INVALID_ARG for a dense or host_only graph. */
 mpk_status mpk_graph_moe_active(mpk_graph *g, uint32_t *out, size_t cap, size_t *need);
 
+/* Mixture-of-experts graphs, Section 6.4 (tasks re-balanced at run time from the meta-tensor):
+ * which of the active experts' 16-row weight tiles -- laid end to end in ascending expert order,
+ * n_active x tiles_per_expert of them -- expert task `task` of `n_tasks` works on in a step that
+ * selected n_active distinct experts: tiles [*first, *last).  The shares are disjoint, in task
+ * order, cover every tile, and are equal in cost rather than in tiles: an expert boundary inside
+ * a share (a second job for the task) is charged like 8 tiles.  A pure function, the one the
+ * kernels evaluate; no GPU is touched.  INVALID_ARG: a null pointer, n_tasks == 0, task >=
+ * n_tasks or tiles_per_expert == 0. */
+mpk_status mpk_moe_task_share(uint32_t n_active, uint32_t tiles_per_expert, uint32_t n_tasks,
+                              uint32_t task, uint32_t *first, uint32_t *last);
+
 /* Mixture-of-experts graphs: the routing decision of the LAST decode step (from each layer's
  * meta-tensor).  experts: host u32 [n_layers][batch][top_k], a token's experts in ascending index;
  * weights: host fp32, same shape, the renormalised combine weights; either may be NULL.  cap is in

@@ -98,7 +98,7 @@ EXPORT_EVENT = np.dtype([("required", "<u4"), ("first", "<u4"), ("last", "<u4"),
 
 SYMBOLS = ("mpk_compile", "mpk_compile_dag", "mpk_decode_step", "mpk_decode_steps", "mpk_graph_status",
            "mpk_graph_reset", "mpk_graph_stats", "mpk_graph_export", "mpk_graph_trace",
-           "mpk_graph_moe_active", "mpk_graph_moe_selection", "mpk_compile_set",
+           "mpk_graph_moe_active", "mpk_graph_moe_selection", "mpk_moe_task_share", "mpk_compile_set",
            "mpk_set_decode_step", "mpk_decode_step_static", "mpk_set_size", "mpk_set_batch_for", "mpk_set_graph",
            "mpk_set_destroy", "mpk_last_error", "mpk_graph_destroy", "mpk_static_scratch_need",
            "mpk_graph_set_page_table", "mpk_serve_create", "mpk_serve_submit", "mpk_serve_run",
@@ -133,6 +133,7 @@ def lib():
         L.mpk_graph_export.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
         L.mpk_graph_trace.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
         L.mpk_graph_moe_active.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
+        L.mpk_moe_task_share.argtypes = [C.c_uint32] * 4 + [C.POINTER(C.c_uint32)] * 2
         L.mpk_graph_moe_selection.argtypes = [vp, vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
         L.mpk_last_error.restype = C.c_char_p
         L.mpk_graph_destroy.argtypes = [vp]
@@ -452,6 +453,13 @@ def compile_set(shape, weights: dict, kv: tuple, **opts) -> GraphSet:
     arr, wp, kp = _marshal_model(shape, weights, kv)
     _check(lib().mpk_compile_set(C.byref(cfg), C.byref(wp), C.byref(kp), C.byref(o), C.byref(h)))
     return GraphSet(h, [arr, wp, kp])
+
+
+def moe_task_share(n_active: int, tiles_per_expert: int, n_tasks: int, task: int) -> tuple:
+    """Tiles [first, last) of the active experts' tiles that expert task `task` works on."""
+    a, b = C.c_uint32(0), C.c_uint32(0)
+    _check(lib().mpk_moe_task_share(n_active, tiles_per_expert, n_tasks, task, C.byref(a), C.byref(b)))
+    return a.value, b.value
 
 
 def compile_graph(shape, weights: dict | None, kv: tuple | None, **opts) -> Graph:

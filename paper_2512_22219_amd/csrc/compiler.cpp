@@ -1424,3 +1424,13 @@ void export_graph(const HostGraph& g, void* buf) {
 }
 
 }  // namespace mpk
+
+extern "C" mpk_status mpk_moe_task_share(uint32_t n_active, uint32_t tiles_per_expert, uint32_t n_tasks, uint32_t task,
+                                         uint32_t* first, uint32_t* last) {
+  if (!first || !last || n_tasks == 0 || task >= n_tasks || tiles_per_expert == 0) {
+    mpk::set_error("mpk_moe_task_share: null pointer, no tasks, task out of range or no tiles");
+    return MPK_ERR_INVALID_ARG;
+  }
+  mpk::moe_task_share(n_active, tiles_per_expert, n_tasks, task, first, last);
+  return MPK_OK;
+}

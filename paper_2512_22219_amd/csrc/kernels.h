@@ -1584,7 +1584,6 @@ __device__ __forceinline__ bool moe_expert_job(const TaskDesc& t, const StepArgs
 // Expert task `c0` of `p1`: the active experts' 16-row weight tiles, laid end to end in ascending
 // expert order, are dealt to the expert tasks in shares of equal cost (the run-time refinement of
 // Section 6.4); a task's share is worked off in jobs of at most 32 tiles that stay inside one expert.
-constexpr uint32_t kMoeSwitchTiles = 8;   // what starting another expert's job costs, in tiles (4: +1.5 % per step, 7 and 10: the same)
 // wait_ev >= 0: the caller has NOT waited for the task's event yet (only for the routing task's,
 // so the meta-tensor is this step's); the first job does, behind its first weight requests.
 __device__ __forceinline__ bool body_moe_expert(const TaskDesc& t, const StepArgs& a, float* lds, int32_t wait_ev = -1,
@@ -1601,19 +1600,8 @@ __device__ __forceinline__ bool body_moe_expert(const TaskDesc& t, const StepArg
   for (uint32_t i = threadIdx.x; i < MW; i += kThreads) mlds[i] = ld_relaxed(meta + i);
   lds_barrier();
   const uint32_t n_active = min(__builtin_amdgcn_readfirstlane(mlds[0]), E);
-  const uint32_t total = n_active * tiles_per_expert;
-  // The deal.  A task whose share crosses from one expert into the next works it off in two jobs,
-  // and the change-over (epilogue, staging, the first weights with nothing requested ahead) costs
-  // about as much as kMoeSwitchTiles tiles -- with equal shares every third task or so finished
-  // that much later than the rest, and the operator with it.  So the shares are equal in COST:
-  // every expert boundary counts as kMoeSwitchTiles extra tiles.  Position x on the cost axis
-  // (an expert = its tiles + the gap behind it) maps back to tile min(x mod period, tiles) of
-  // expert x / period; a pure function of the number of active experts, like the equal deal.
-  const uint32_t period = tiles_per_expert + kMoeSwitchTiles;
-  auto tile_at = [&](uint64_t x) { return (uint32_t)(x / period) * tiles_per_expert + min((uint32_t)(x % period), tiles_per_expert); };
-  const uint64_t cost = (uint64_t)n_active * period;
-  uint32_t u0 = tile_at(cost * t.c0 / NT);
-  const uint32_t u1 = tile_at(cost * (t.c0 + 1u) / NT);
+  uint32_t u0, u1;   // this task's share of the tiles: equal in cost, see moe_task_share
+  moe_task_share(n_active, tiles_per_expert, NT, t.c0, &u0, &u1);
   while (u0 < u1) {
     const uint32_t ai = u0 / tiles_per_expert, tile0 = u0 % tiles_per_expert;
     const uint32_t ntile = min(min(u1 - u0, tiles_per_expert - tile0), 32u);

@@ -206,6 +206,30 @@ mpk_status build_dag_graph(uint32_t n_tasks, const uint32_t* pairs, size_t n_pai
 //   [2+3E+P .. +P)    combine weight of pair p (float)
 //   [2+3E+2P .. +P)   expert of pair p
 inline uint32_t moe_meta_words(uint32_t E, uint32_t P) { return 2 + 3 * E + 3 * P; }
+
+// Section 6.4, the run-time refinement: which of the active experts' 16-row weight tiles -- laid
+// end to end in ascending expert order, n_active x tiles_per_expert of them -- expert task `task`
+// of `n_tasks` works on: [*first, *last).  A task whose share crosses from one expert into the
+// next works it off in two jobs, and the change-over (epilogue, staging, the first weights with
+// nothing requested ahead) costs about as much as kMoeSwitchTiles tiles, so the shares are equal
+// in COST: every expert counts as its tiles plus a gap of kMoeSwitchTiles, the tasks divide that
+// axis evenly, and position x on it maps back to tile min(x mod period, tiles) of expert
+// x / period.  A pure function of its arguments (host and device compute the same split); the
+// shares are disjoint, in order, and cover every tile.
+constexpr uint32_t kMoeSwitchTiles = 8;   // (4: +1.5 % per step on the mixture-of-experts shape; 7 and 10: the same as 8)
+#if defined(__HIPCC__)
+#define MPK_HOST_DEVICE __host__ __device__
+#else
+#define MPK_HOST_DEVICE
+#endif
+MPK_HOST_DEVICE inline void moe_task_share(uint32_t n_active, uint32_t tiles_per_expert, uint32_t n_tasks, uint32_t task,
+                                           uint32_t* first, uint32_t* last) {
+  const uint64_t period = (uint64_t)tiles_per_expert + kMoeSwitchTiles, cost = (uint64_t)n_active * period;
+  const uint64_t x0 = cost * task / n_tasks, x1 = cost * ((uint64_t)task + 1u) / n_tasks;
+  const uint64_t r0 = x0 % period, r1 = x1 % period;
+  *first = (uint32_t)(x0 / period) * tiles_per_expert + (uint32_t)(r0 < tiles_per_expert ? r0 : tiles_per_expert);
+  *last = (uint32_t)(x1 / period) * tiles_per_expert + (uint32_t)(r1 < tiles_per_expert ? r1 : tiles_per_expert);
+}
 constexpr uint32_t kMoeMaxExperts = 512, kMoeMaxPairs = 256, kMoeMaxTopK = 16;
 
 // Matrix-core jobs (batch 5..16 and expert jobs) stage the input in LDS as fp32, a chunk of this

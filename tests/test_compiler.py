@@ -424,3 +424,32 @@ def test_lds_page_preload_makes_the_preloaded_tiles_larger():
     for kw in (dict(n_sched_wgs=1), dict(launch_mode=1), dict(no_preload=1)):
         assert not host_graph(shape, fusion=31, transitive_reduction=1, **kw).export().col_begin
     assert not host_graph(G.small_variant("C2", n_layers=2, batch=2), fusion=31, transitive_reduction=1).export().col_begin
+
+
+@pytest.mark.parametrize("tiles_per_expert,n_tasks", [(96, 256), (128, 256), (96, 37), (2, 9), (5, 1), (40, 512)])
+def test_expert_tasks_share_the_active_tiles_disjointly_in_order_and_completely(tiles_per_expert, n_tasks):
+    """Section 6.4, tasks re-balanced at run time: for every number of active experts the shares
+    of the expert tasks are consecutive ranges that start at tile 0, end at the last tile and
+    leave no gap; an expert boundary inside a share costs the task tiles (it is charged like 8),
+    so shares differ by no more than that charge plus rounding, and a share that crosses no
+    boundary is never smaller than one that does."""
+    from paper_2512_22219_amd.binding import moe_task_share
+    for n_active in [0, 1, 2, 3, 7, 82, 128]:
+        total = n_active * tiles_per_expert
+        at = 0
+        sizes, crossing = [], []
+        for task in range(n_tasks):
+            first, last = moe_task_share(n_active, tiles_per_expert, n_tasks, task)
+            assert first == at and last >= first, (n_active, task, first, last, at)
+            at = last
+            sizes.append(last - first)
+            # expert boundaries strictly inside the share (a tile on each side of them)
+            crossing.append(0 if last == first else (last - 1) // tiles_per_expert - first // tiles_per_expert)
+        assert at == total
+        if n_active:
+            cost = [s + 8 * c for s, c in zip(sizes, crossing)]
+            assert max(cost) - min(cost) <= 8 + 2, (n_active, max(cost), min(cost))
+    with pytest.raises(M.MpkError):
+        moe_task_share(3, tiles_per_expert, n_tasks, n_tasks)
+    with pytest.raises(M.MpkError):
+        moe_task_share(3, 0, n_tasks, 0)
