@@ -155,12 +155,12 @@ typedef struct mpk_compile_options {
                                kernel runs until its workload is done (Section 5).  Such a
                                graph is run with mpk_decode_steps only.  How n steps are
                                issued is the library's choice: one launch of the persistent
-                               kernel, or -- for batch sizes up to 4, whose linear bodies run
-                               about 3.5 % slower inside the step loop, and for serving calls,
-                               whose paged attention needs slower loads inside a launch of
-                               several steps -- n launches of the single-step kernel back to
-                               back, with no host synchronisation between them; 2 = always the
-                               one launch                                                       */
+                               kernel, or -- for the model shapes the library has specialised
+                               kernels for, whose linear bodies run 1 to 3.5 % slower inside
+                               the step loop and whose paged attention needs slower loads
+                               inside a launch of several steps -- n launches of the
+                               single-step kernel back to back, with no host synchronisation
+                               between them; 2 = always the one launch                          */
   uint32_t kv_batch;        /* number of sequences the KV cache is laid out for (the `batch`
                                extent of mpk_kv_ptrs' layout); 0 = cfg.batch.  Lets a graph for
                                fewer sequences run on the first cfg.batch slots of a larger
@@ -251,7 +251,7 @@ mpk_status mpk_decode_step(mpk_graph *g, const int32_t *token_ids, const int32_t
 
 /* Decode n_steps tokens greedily in one call, with no host round trip between tokens (Section 5:
  * the kernel keeps running until the workload completes): one launch of the persistent kernel, or
- * a launch per step at batch sizes up to 4 (see greedy_loop).  Only for graphs compiled with
+ * a launch per step issued back to back (see greedy_loop).  Only for graphs compiled with
  * greedy_loop and without scheduler workgroups; with MPK_LAUNCH_PER_OP the host
  * issues the operator kernels of every step instead.
  *   token_ids  : device int32 [batch], IN: the tokens to feed first; OUT: the last tokens sampled

@@ -519,13 +519,13 @@ static mpk_status launch_steps(mpk_graph* g, uint32_t n_steps, const int32_t* to
     a.epoch = static_scratch ? 1u : g->epoch + 1;
     a.step = 0; a.n_steps = (uint16_t)n_steps;
     if (!static_scratch) g->epoch += n_steps;
-    // Several steps: one launch of the loop kernel -- or, for the vector linear bodies (batch <= 4),
-    // a launch of the single-step kernel per step, back to back with no host synchronisation: inside
-    // the step loop those bodies come out about 3.5 % slower (8B shape, batch 1: 3.12 against
-    // 3.01 ms per token), and the GPU front end overlaps back-to-back launches almost completely.
-    // greedy_loop = 2 asks for the single launch regardless.
-    const bool by_step = n_steps > 1 && h.opt.greedy_loop != 2 && !g->n_sched && g->kv->run_step != nullptr &&
-                         (g->kv->nb != 8 || (g->step_flags & kServeBit));
+    // Several steps: one launch of the loop kernel -- or, where the kernel set has a single-step
+    // kernel for runs (every set compiled for a model shape), a launch of that kernel per step, back
+    // to back with no host synchronisation: inside the step loop the linear bodies come out slower
+    // (8B shape, batch 1: 3.12 against 3.01 ms per token; batch 8: 4.93 against 4.87), and the GPU
+    // front end overlaps back-to-back launches almost completely.  greedy_loop = 2 asks for the
+    // single launch regardless.
+    const bool by_step = n_steps > 1 && h.opt.greedy_loop != 2 && !g->n_sched && g->kv->run_step != nullptr;
     if (by_step || n_steps == 1) a.flags |= kOneStepBit;
     if (by_step) {
       for (uint32_t i = 0; i < n_steps; ++i) {

@@ -18,10 +18,10 @@ template <int I>
 static const KernelVariant* make_variant() {
   using P = VariantParams<I>;
   constexpr bool split = P::nb == 8;   // matrix-core bodies: one kernel per launch path
-  // vector linear bodies (batch <= 4): several steps are issued as a launch per step
+  // kernel sets compiled for a model shape: several steps are issued as a launch per step
   void (*run_step)(StepArgs) = nullptr;
   if constexpr (P::nb == 1 || P::nb == 9) run_step = mpk_mega_kernel<P::d, P::grp, P::nb, P::moe, 0, true>;
-  if constexpr (P::nb == 8) run_step = mpk_mega_kernel<P::d, P::grp, P::nb, P::moe, 1, true>;   // (used for serving launches only)
+  if constexpr (P::nb == 8) run_step = mpk_mega_kernel<P::d, P::grp, P::nb, P::moe, 1, true>;
   static const KernelVariant v = {P::d, P::grp, P::nb, P::moe, mpk_mega_kernel<P::d, P::grp, P::nb, P::moe, split ? 1 : 0>,
                                   mpk_op_kernel<P::d, P::grp, P::nb, P::moe>, mpk_loop_kernel<P::d, P::grp, P::nb, P::moe>,
                                   mpk_mega_kernel<P::d, P::grp, P::nb, P::moe, split ? 2 : 0>, run_step};

@@ -502,6 +502,10 @@ def test_moe_routing_ties_take_the_lower_expert_index(batch):
     # batch <= 4 issues a launch per step by default; greedy_loop = 2: the one launch of the loop kernel
     (dict(), dict(fusion=31, transitive_reduction=1, greedy_loop=2), 16),
     (dict(batch=3, n_layers=2), dict(fusion=31, transitive_reduction=1, greedy_loop=2, tiles_sampling=2), 7),
+    # the kernels compiled for head dimension 128 at batch 5..16: a launch per step, and the loop kernel
+    (dict(batch=8, n_layers=2, head_dim=128, n_q_heads=8, n_kv_heads=2), dict(fusion=31, transitive_reduction=1), 6),
+    (dict(batch=8, n_layers=2, head_dim=128, n_q_heads=8, n_kv_heads=2), dict(fusion=31, transitive_reduction=1, greedy_loop=2), 6),
+    (dict(batch=16, head_dim=128, n_q_heads=8, n_kv_heads=1, ffn=0, n_experts=16, top_k=4, expert_ffn=96), dict(fusion=31, transitive_reduction=1), 5),
 ])
 def test_greedy_loop_decodes_several_tokens_in_one_launch(variant, opts, n_steps):
     """Graph with the sampling operator: n_steps tokens from ONE launch of the persistent kernel
